@@ -1,0 +1,275 @@
+"""fp64 CPU oracle for WERSA attention (forward and backward).
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+HIP kernels are checked against.  It shares no code with the GPU path and the
+product never calls it: only tests, the smoke check and the CPU-baseline leg
+of the benchmark import it.
+
+Everything is written per (batch, head) slice with NumPy in float64, in the
+order the paper states the method (Section 3.1 steps 3-8; Appendix D,
+Algorithms 1 and 2).  Library primitives used as steps: ``@`` (matmul),
+``mean``, ``maximum``.  No blocking, fusion or reordering.
+
+Readings of the paper taken here (each one is a choice where the text is
+silent or disagrees with itself):
+
+* Normalisation follows the Section 3.1 attention equation (divide by
+  phi(Q_F) phi(K_F)^T 1 + eps), not the LayerNorm of Algorithm 1.
+* One shared random matrix Omega (Section 3.1 step 7) and the 1/sqrt(m) factor
+  of Algorithm 1's random projection lines.
+* The gate g is a single linear map per head (Algorithm 1's W_filter), applied
+  to that head's own pooled query (Section 3.1 step 4), plus a bias; the
+  per-scale weights omega are shared by all heads.
+* The same filter F (computed from Q) multiplies the coefficients of both Q
+  and K (Section 3.1 step 6).
+* Band order of F: index 0 is the finest detail band d_1, index L-1 is d_L,
+  index L is the approximation a_L (return order of Algorithm 2's DWT).
+* Haar pair convention (Appendix A, Appendix C, Algorithm 2): pair
+  (x[2k], x[2k+1]), approximation = (even+odd)/sqrt(2), detail =
+  (even-odd)/sqrt(2).
+* Zero padding to the next power of two before the transform, trim after the
+  inverse (Algorithm 2); the pooled query uses the original n rows.
+* sigma_eff = max(sigma, bw_floor) (Algorithm 1's bandwidth line); one scalar
+  for the whole call.
+* Sub-gradient of ReLU at exactly 0 is 0.
+
+Pins (tests/test_oracle_pins.py): hand-derived Haar coefficients, perfect
+reconstruction, energy preservation, block-mean closed form, explicit n x n
+kernel-matrix attention, arc-cosine kernel limit and m^-1/2 rate, convexity,
+sigma homogeneity, central finite differences for every gradient, ablation
+special cases.  Absolute output values on real data: parity unpinned (the paper
+prints no worked numeric example).
+"""
+import math
+
+import numpy as np
+
+SQRT2 = math.sqrt(2.0)
+
+
+# ----------------------------------------------------------------------------
+# Haar transform along the sequence axis (Appendix A equations; Algorithm 2)
+# ----------------------------------------------------------------------------
+def next_pow2(n):
+    return 1 << max(0, math.ceil(math.log2(n))) if n > 1 else 1
+
+
+def haar_dwt(X, L):
+    """L-level Haar analysis of X (n, d) along axis 0.
+
+    Returns ([d_1, ..., d_L, a_L], n): details finest first, then the last
+    approximation (Algorithm 2, VectorizedDWT).  X is zero-padded to the next
+    power of two first.
+    """
+    n = X.shape[0]
+    npad = next_pow2(n)
+    if npad < (1 << L):
+        npad = 1 << L
+    approx = np.zeros((npad,) + X.shape[1:], dtype=np.float64)
+    approx[:n] = X
+    details = []
+    for _ in range(L):
+        even = approx[0::2]
+        odd = approx[1::2]
+        details.append((even - odd) / SQRT2)
+        approx = (even + odd) / SQRT2
+    return details + [approx], n
+
+
+def haar_idwt(coeffs, n):
+    """Inverse of haar_dwt; trims to the original n rows (VectorizedIDWT)."""
+    approx = coeffs[-1]
+    for detail in reversed(coeffs[:-1]):
+        even = (approx + detail) / SQRT2
+        odd = (approx - detail) / SQRT2
+        nxt = np.empty((2 * approx.shape[0],) + approx.shape[1:], dtype=np.float64)
+        nxt[0::2] = even
+        nxt[1::2] = odd
+        approx = nxt
+    return approx[:n]
+
+
+def filtered_idwt(coeffs, F, n):
+    """Multiply band i by F[i], then inverse transform (FilteredIDWT)."""
+    return haar_idwt([c * F[i] for i, c in enumerate(coeffs)], n)
+
+
+def haar_filter(X, F, L):
+    """X_F = W^-1 (F (.) W X)  (Section 3.1 step 6)."""
+    coeffs, n = haar_dwt(X, L)
+    return filtered_idwt(coeffs, F, n)
+
+
+# ----------------------------------------------------------------------------
+# Gate (Section 3.1 step 4, equations for Q'_avg, F and F_i)
+# ----------------------------------------------------------------------------
+def gate(qbar, Wg_h, bg_h, omega):
+    """qbar (d,), Wg_h (L+1, d), bg_h (L+1,), omega (L+1,) -> logits, s, F."""
+    logits = Wg_h @ qbar + bg_h
+    s = 1.0 / (1.0 + np.exp(-logits))
+    return logits, s, s * omega
+
+
+# ----------------------------------------------------------------------------
+# Random feature map (Section 3.1 step 7; Algorithm 1 projection lines)
+# ----------------------------------------------------------------------------
+def feature_map(XF, Omega, sigma, bw_floor):
+    m = Omega.shape[1]
+    sigma_eff = max(float(sigma), float(bw_floor))
+    U = (XF @ Omega) / sigma_eff
+    Phi = np.maximum(U, 0.0) / math.sqrt(m)
+    return U, Phi
+
+
+# ----------------------------------------------------------------------------
+# Forward, one (b, h) slice
+# ----------------------------------------------------------------------------
+def forward_slice(Q, K, V, Omega, sigma, Wg_h, bg_h, omega, L, eps, bw_floor):
+    """Q, K, V (n, d) -> dict of every stage tensor, 'O' is the output."""
+    Q = np.asarray(Q, np.float64)
+    K = np.asarray(K, np.float64)
+    V = np.asarray(V, np.float64)
+    qbar = Q.mean(axis=0)
+    logits, s, F = gate(qbar, Wg_h, bg_h, omega)
+    QF = haar_filter(Q, F, L)
+    KF = haar_filter(K, F, L)
+    UQ, PhiQ = feature_map(QF, Omega, sigma, bw_floor)
+    UK, PhiK = feature_map(KF, Omega, sigma, bw_floor)
+    S = PhiK.T @ V                       # (m, d)  phi(K_F)^T V
+    z = PhiK.T @ np.ones(K.shape[0])     # (m,)    phi(K_F)^T 1
+    N = PhiQ @ S
+    D = PhiQ @ z + eps
+    O = N / D[:, None]
+    return dict(qbar=qbar, logits=logits, s=s, F=F, QF=QF, KF=KF, UQ=UQ, UK=UK,
+                PhiQ=PhiQ, PhiK=PhiK, S=S, z=z, N=N, D=D, O=O)
+
+
+# ----------------------------------------------------------------------------
+# Backward, one (b, h) slice: chain rule through forward_slice, step by step
+# in reverse.  The paper states no backward; this is the derivative of the
+# forward above (checked by finite differences in the pins).
+# ----------------------------------------------------------------------------
+def _haar_filter_vjp(X, F, L, dXF):
+    """Given dL/dX_F, return dL/dX and dL/dF for X_F = W^-1 (F (.) W X).
+
+    The padded Haar transform matrix W is orthonormal, so the transpose of the
+    inverse transform is the forward transform and vice versa; the transpose of
+    'trim to n rows' is 'zero-pad back', which haar_dwt does on entry.
+    """
+    cx, n = haar_dwt(X, L)           # coefficients of the input
+    cg, _ = haar_dwt(dXF, L)         # (W^-1)^T applied to the padded cotangent
+    dF = np.array([np.sum(cx[i] * cg[i]) for i in range(L + 1)])
+    dX = haar_idwt([cg[i] * F[i] for i in range(L + 1)], n)   # W^T (F (.) .)
+    return dX, dF
+
+
+def backward_slice(Q, K, V, Omega, sigma, Wg_h, bg_h, omega, L, eps, bw_floor, dO,
+                   fwd=None):
+    """Returns dict dQ, dK, dV (n, d), dWg_h (L+1, d), dbg_h, domega (L+1,),
+    dsigma (scalar, term-by-term chain rule form), plus intermediates."""
+    Q = np.asarray(Q, np.float64)
+    K = np.asarray(K, np.float64)
+    V = np.asarray(V, np.float64)
+    dO = np.asarray(dO, np.float64)
+    f = fwd if fwd is not None else forward_slice(Q, K, V, Omega, sigma, Wg_h, bg_h,
+                                                  omega, L, eps, bw_floor)
+    n, d = Q.shape
+    m = Omega.shape[1]
+    sigma_eff = max(float(sigma), float(bw_floor))
+    D, O, S, z = f["D"], f["O"], f["S"], f["z"]
+    PhiQ, PhiK, UQ, UK = f["PhiQ"], f["PhiK"], f["UQ"], f["UK"]
+
+    # O = N / D
+    dN = dO / D[:, None]
+    dD = -np.sum(dO * O, axis=1) / D
+    # N = PhiQ S ; D = PhiQ z + eps
+    dPhiQ = dN @ S.T + np.outer(dD, z)
+    dS = PhiQ.T @ dN
+    dz = PhiQ.T @ dD
+    # S = PhiK^T V ; z = PhiK^T 1
+    dPhiK = V @ dS.T + np.outer(np.ones(n), dz)
+    dV = PhiK @ dS
+    # Phi = max(U, 0)/sqrt(m)
+    dUQ = dPhiQ * (UQ > 0.0) / math.sqrt(m)
+    dUK = dPhiK * (UK > 0.0) / math.sqrt(m)
+    # U = X_F Omega / sigma_eff
+    dQF = (dUQ @ Omega.T) / sigma_eff
+    dKF = (dUK @ Omega.T) / sigma_eff
+    if float(sigma) > float(bw_floor):
+        dsigma = -(np.sum(dUQ * UQ) + np.sum(dUK * UK)) / sigma_eff
+    else:
+        dsigma = 0.0
+    # X_F = W^-1 (F (.) W X), for Q and K with the same F
+    dQ, dF_q = _haar_filter_vjp(Q, f["F"], L, dQF)
+    dK, dF_k = _haar_filter_vjp(K, f["F"], L, dKF)
+    dF = dF_q + dF_k
+    # F = s * omega ; s = sigmoid(logits) ; logits = Wg qbar + bg ; qbar = mean(Q)
+    s = f["s"]
+    domega = dF * s
+    ds = dF * omega
+    dlogits = ds * s * (1.0 - s)
+    dWg_h = np.outer(dlogits, f["qbar"])
+    dbg_h = dlogits
+    dqbar = Wg_h.T @ dlogits
+    dQ = dQ + dqbar[None, :] / n
+    return dict(dQ=dQ, dK=dK, dV=dV, dWg_h=dWg_h, dbg_h=dbg_h, domega=domega,
+                dsigma=dsigma, dS=dS, dz=dz, dD=dD, dF=dF, dQF=dQF, dKF=dKF)
+
+
+# ----------------------------------------------------------------------------
+# Whole call over (B, H, n, d)
+# ----------------------------------------------------------------------------
+def forward(Q, K, V, Omega, sigma, Wg, bg, omega, L, eps=1e-6, bw_floor=1e-6,
+            slices=None, keep=("O",)):
+    """Q, K, V (B, H, n, d); Omega (d, m); Wg (H, L+1, d); bg (H, L+1); omega (L+1,).
+
+    Returns dict of stacked stage tensors named in `keep`, each (B, H, ...).
+    `slices` optionally restricts the work to a list of (b, h) pairs; other
+    slices are left as zeros.
+    """
+    B, H = Q.shape[:2]
+    Omega = np.asarray(Omega, np.float64)
+    out = {}
+    todo = slices if slices is not None else [(b, h) for b in range(B) for h in range(H)]
+    for (b, h) in todo:
+        f = forward_slice(Q[b, h], K[b, h], V[b, h], Omega, sigma,
+                          np.asarray(Wg[h], np.float64), np.asarray(bg[h], np.float64),
+                          np.asarray(omega, np.float64), L, eps, bw_floor)
+        for name in keep:
+            if name not in out:
+                out[name] = np.zeros((B, H) + np.shape(f[name]), np.float64)
+            out[name][b, h] = f[name]
+    return out
+
+
+def backward(Q, K, V, Omega, sigma, Wg, bg, omega, L, dO, eps=1e-6, bw_floor=1e-6,
+             slices=None):
+    """Gradients of sum(O * dO) w.r.t. Q, K, V, Wg, bg, omega, sigma.
+
+    Parameter gradients are summed over every slice processed (all of them
+    unless `slices` restricts the work).
+    """
+    B, H, n, d = Q.shape
+    Omega = np.asarray(Omega, np.float64)
+    omega = np.asarray(omega, np.float64)
+    g = dict(dQ=np.zeros((B, H, n, d)), dK=np.zeros((B, H, n, d)), dV=np.zeros((B, H, n, d)),
+             dWg=np.zeros((H, L + 1, d)), dbg=np.zeros((H, L + 1)), domega=np.zeros(L + 1),
+             dsigma=0.0, O=np.zeros((B, H, n, d)), dD_sum=0.0)
+    todo = slices if slices is not None else [(b, h) for b in range(B) for h in range(H)]
+    for (b, h) in todo:
+        Wg_h = np.asarray(Wg[h], np.float64)
+        bg_h = np.asarray(bg[h], np.float64)
+        f = forward_slice(Q[b, h], K[b, h], V[b, h], Omega, sigma, Wg_h, bg_h, omega, L,
+                          eps, bw_floor)
+        r = backward_slice(Q[b, h], K[b, h], V[b, h], Omega, sigma, Wg_h, bg_h, omega, L,
+                           eps, bw_floor, dO[b, h], fwd=f)
+        g["O"][b, h] = f["O"]
+        g["dQ"][b, h] = r["dQ"]
+        g["dK"][b, h] = r["dK"]
+        g["dV"][b, h] = r["dV"]
+        g["dWg"][h] += r["dWg_h"]
+        g["dbg"][h] += r["dbg_h"]
+        g["domega"] += r["domega"]
+        g["dsigma"] += r["dsigma"]
+        g["dD_sum"] += float(np.sum(r["dD"]))
+    return g

@@ -1,0 +1,295 @@
+"""Pins for the CPU oracle: what the paper and the mathematics fix, independent of the oracle itself.
+
+Every test here runs on the CPU only.  Citations name the passage of the paper that fixes the
+property being checked.
+"""
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import wersa_oracle as wo
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rand_problem(seed, B=2, H=2, n=64, d=4, m=16, L=3, q_mean=0.7):
+    r = np.random.default_rng(seed)
+    p = dict(
+        Q=r.standard_normal((B, H, n, d)) + q_mean,
+        K=r.standard_normal((B, H, n, d)),
+        V=r.standard_normal((B, H, n, d)),
+        Omega=r.standard_normal((d, m)),
+        sigma=1.3,
+        Wg=r.standard_normal((H, L + 1, d)),
+        bg=0.1 * r.standard_normal((H, L + 1)),
+        omega=1.0 + 0.1 * r.standard_normal(L + 1),
+        L=L,
+    )
+    p["dO"] = r.standard_normal((B, H, n, d))
+    return p
+
+
+# ---------------------------------------------------------------- Haar transform
+def test_haar_hand_example():
+    """Appendix A analysis equations worked by hand on an 8-sample signal."""
+    with open(os.path.join(GOLDEN, "haar_hand_example.json")) as f:
+        g = json.load(f)
+    x = np.array(g["x"], float)[:, None]
+    coeffs, n = wo.haar_dwt(x, g["L"])
+    s2 = math.sqrt(2.0)
+    assert n == 8
+    np.testing.assert_allclose(coeffs[0][:, 0] * s2, g["d1_times_sqrt2"], atol=1e-14)
+    np.testing.assert_allclose(coeffs[1][:, 0], g["d2"], atol=1e-14)
+    np.testing.assert_allclose(coeffs[2][:, 0] * s2, g["d3_times_sqrt2"], atol=1e-14)
+    np.testing.assert_allclose(coeffs[3][:, 0] * s2, g["a3_times_sqrt2"], atol=1e-14)
+    assert abs(sum(float(np.sum(c * c)) for c in coeffs) - g["energy"]) < 1e-12
+    low = wo.haar_filter(x, np.array([0.0, 0.0, 0.0, 1.0]), 3)
+    np.testing.assert_allclose(low[:, 0], g["lowpass_only_reconstruction"], atol=1e-14)
+
+
+@pytest.mark.parametrize("n,L", [(64, 3), (256, 6), (128, 1), (48, 3), (100, 2), (8, 3)])
+def test_perfect_reconstruction_and_energy(n, L):
+    """Appendix A inverse equations undo the analysis; the transform is orthonormal."""
+    x = np.random.default_rng(n + L).standard_normal((n, 5))
+    coeffs, n0 = wo.haar_dwt(x, L)
+    assert n0 == n and len(coeffs) == L + 1
+    # band sizes: d_l has npad / 2^l rows (Algorithm 2 return order d_1..d_L, a_L)
+    npad = coeffs[0].shape[0] * 2
+    for l in range(1, L + 1):
+        assert coeffs[l - 1].shape[0] == npad >> l
+    assert coeffs[L].shape[0] == npad >> L
+    np.testing.assert_allclose(wo.haar_idwt(coeffs, n), x, atol=1e-13)
+    np.testing.assert_allclose(wo.haar_filter(x, np.ones(L + 1), L), x, atol=1e-13)
+    e_x = np.sum(x * x)
+    e_c = sum(np.sum(c * c) for c in coeffs)
+    assert abs(e_x - e_c) < 1e-10 * e_x
+
+
+def _block_mean(x, size):
+    """Replace every aligned block of `size` rows by its mean (zero padding the tail)."""
+    n = x.shape[0]
+    npad = -(-n // size) * size
+    xp = np.zeros((npad,) + x.shape[1:])
+    xp[:n] = x
+    mean = xp.reshape(npad // size, size, -1).mean(axis=1, keepdims=True)
+    return np.broadcast_to(mean, (npad // size, size, xp.shape[1])).reshape(npad, -1)[:n]
+
+
+@pytest.mark.parametrize("n,L", [(64, 3), (256, 6), (48, 3), (100, 2), (192, 5)])
+def test_block_mean_closed_form(n, L):
+    """Gated Haar filter == F_0 x + sum_l (F_l - F_{l-1}) * (mean over aligned 2^l blocks).
+
+    Follows from the Haar scaling function being an indicator (Appendix A): the level-l
+    approximation is 2^{l/2} times the block mean.  Fixes the band order of F and shows the
+    result does not depend on how far beyond a multiple of 2^L the signal is zero padded.
+    """
+    r = np.random.default_rng(7 * n + L)
+    x = r.standard_normal((n, 3))
+    F = r.uniform(0.1, 1.5, L + 1)
+    ref = F[0] * x
+    for l in range(1, L + 1):
+        ref = ref + (F[l] - F[l - 1]) * _block_mean(x, 1 << l)
+    np.testing.assert_allclose(wo.haar_filter(x, F, L), ref, atol=1e-13)
+
+
+def test_filter_special_cases_and_symmetry():
+    r = np.random.default_rng(3)
+    n, L = 128, 4
+    x, y = r.standard_normal((n, 6)), r.standard_normal((n, 6))
+    np.testing.assert_allclose(wo.haar_filter(x, np.full(L + 1, 0.37), L), 0.37 * x, atol=1e-13)
+    only_a = np.zeros(L + 1)
+    only_a[L] = 1.0
+    np.testing.assert_allclose(wo.haar_filter(x, only_a, L), _block_mean(x, 1 << L), atol=1e-13)
+    only_d1 = np.zeros(L + 1)
+    only_d1[0] = 1.0
+    np.testing.assert_allclose(wo.haar_filter(x, only_d1, L), x - _block_mean(x, 2), atol=1e-13)
+    F = r.uniform(0, 1, L + 1)
+    lhs = np.sum(wo.haar_filter(x, F, L) * y)
+    rhs = np.sum(x * wo.haar_filter(y, F, L))
+    assert abs(lhs - rhs) < 1e-10 * abs(lhs)
+
+
+# ---------------------------------------------------------------- gate
+def test_gate_formula():
+    """F_i = sigmoid(g(Q_avg)_i) * omega_i with a linear g (Section 3.1 step 4)."""
+    r = np.random.default_rng(5)
+    qbar, W, b, om = r.standard_normal(6), r.standard_normal((4, 6)), r.standard_normal(4), r.uniform(0.5, 2, 4)
+    logits, s, F = wo.gate(qbar, W, b, om)
+    for i in range(4):
+        zi = sum(W[i, j] * qbar[j] for j in range(6)) + b[i]
+        assert abs(logits[i] - zi) < 1e-14
+        assert abs(s[i] - math.exp(zi) / (1 + math.exp(zi))) < 1e-14
+        assert abs(F[i] - om[i] * s[i]) < 1e-14
+    # zero logits give sigmoid 1/2
+    _, s0, F0 = wo.gate(qbar, 0 * W, 0 * b, om)
+    np.testing.assert_allclose(s0, 0.5)
+    np.testing.assert_allclose(F0, 0.5 * om)
+
+
+# ---------------------------------------------------------------- linear attention
+@pytest.mark.parametrize("n", [32, 200])
+def test_linear_attention_equals_explicit_kernel_matrix(n):
+    """Appendix A linear attention identity and the Section 3.1 attention equation:
+    phi(Q)(phi(K)^T V) / (phi(Q) phi(K)^T 1 + eps) equals the explicit n x n product."""
+    L = 3
+    p = _rand_problem(11, B=1, H=1, n=n, d=8, m=32, L=L)
+    eps = 1e-3
+    f = wo.forward_slice(p["Q"][0, 0], p["K"][0, 0], p["V"][0, 0], p["Omega"], p["sigma"],
+                         p["Wg"][0], p["bg"][0], p["omega"], L, eps, 1e-6)
+    # independent recomputation: explicit attention matrix, entry by entry feature products
+    m = p["Omega"].shape[1]
+    QF = wo.haar_filter(p["Q"][0, 0], f["F"], L)
+    KF = wo.haar_filter(p["K"][0, 0], f["F"], L)
+    pq = np.maximum(QF @ p["Omega"] / p["sigma"], 0) / math.sqrt(m)
+    pk = np.maximum(KF @ p["Omega"] / p["sigma"], 0) / math.sqrt(m)
+    A = np.zeros((n, n))
+    for i in range(n):
+        for j in range(n):
+            A[i, j] = float(np.dot(pq[i], pk[j]))
+    O_ref = (A @ p["V"][0, 0]) / (A.sum(axis=1) + eps)[:, None]
+    np.testing.assert_allclose(f["O"], O_ref, rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(f["D"], A.sum(axis=1) + eps, rtol=1e-12)
+
+
+def test_convexity_and_unit_values():
+    """phi >= 0, so with eps = 0 each output row is a convex combination of rows of V."""
+    p = _rand_problem(13, B=1, H=1, n=96, d=8, m=64, L=2)
+    args = (p["Q"][0, 0], p["K"][0, 0])
+    tail = (p["Omega"], p["sigma"], p["Wg"][0], p["bg"][0], p["omega"], 2)
+    f = wo.forward_slice(*args, p["V"][0, 0], *tail, 0.0, 1e-6)
+    V = p["V"][0, 0]
+    assert np.all(f["O"] <= V.max(axis=0)[None, :] + 1e-12)
+    assert np.all(f["O"] >= V.min(axis=0)[None, :] - 1e-12)
+    eps = 0.05
+    f1 = wo.forward_slice(*args, np.ones_like(V), *tail, eps, 1e-6)
+    np.testing.assert_allclose(f1["O"], ((f1["D"] - eps) / f1["D"])[:, None] * np.ones_like(V), rtol=1e-12)
+
+
+# ---------------------------------------------------------------- random features
+def _arccos_kernel(q, k, sigma):
+    """E_w[relu(q.w/sigma) relu(k.w/sigma)], w ~ N(0, I): degree-1 arc-cosine kernel (textbook)."""
+    nq, nk = np.linalg.norm(q), np.linalg.norm(k)
+    th = math.acos(max(-1.0, min(1.0, float(q @ k) / (nq * nk))))
+    return nq * nk * (math.sin(th) + (math.pi - th) * math.cos(th)) / (2 * math.pi * sigma ** 2)
+
+
+def test_random_feature_kernel_converges_at_rate_inv_sqrt_m():
+    """Appendix B, random-features bullet: E|phi(q)^T phi(k) - kappa| <= C / sqrt(m).
+
+    phi(q)^T phi(k) with the 1/sqrt(m) scaling and the bandwidth is a Monte-Carlo estimate of
+    the ReLU-feature expectation; its RMS error must fall like m^-1/2.
+    """
+    r = np.random.default_rng(17)
+    d, sigma = 8, 1.7
+    q, k = r.standard_normal(d), r.standard_normal(d)
+    target = _arccos_kernel(q, k, sigma)
+    ms = [64, 256, 1024, 4096, 16384]
+    rms = []
+    for m in ms:
+        errs = []
+        for s in range(24):
+            Om = np.random.default_rng(1000 * m + s).standard_normal((d, m))
+            _, pq = wo.feature_map(q[None, :], Om, sigma, 1e-6)
+            _, pk = wo.feature_map(k[None, :], Om, sigma, 1e-6)
+            errs.append(float(pq[0] @ pk[0]) - target)
+        rms.append(math.sqrt(np.mean(np.square(errs))))
+    slope = np.polyfit(np.log(ms), np.log(rms), 1)[0]
+    assert -0.65 < slope < -0.35, (slope, rms)
+    assert rms[-1] < 0.03 * abs(target), (rms, target)
+
+
+def test_bandwidth_floor():
+    """Algorithm 1 bandwidth line: bw = max(beta, floor)."""
+    x = np.random.default_rng(2).standard_normal((5, 4))
+    Om = np.random.default_rng(3).standard_normal((4, 8))
+    U1, _ = wo.feature_map(x, Om, 1e-9, 0.5)
+    U2, _ = wo.feature_map(x, Om, 0.5, 1e-6)
+    np.testing.assert_allclose(U1, U2)
+
+
+# ---------------------------------------------------------------- homogeneity in sigma
+def test_sigma_homogeneity_and_closed_form_dsigma():
+    """ReLU is positively homogeneous: with eps = 0 the output does not depend on sigma, and
+    with eps > 0 d loss / d sigma = (2 eps / sigma) * sum_t dD_t."""
+    p = _rand_problem(19)
+    common = dict(Omega=p["Omega"], Wg=p["Wg"], bg=p["bg"], omega=p["omega"], L=p["L"])
+    o1 = wo.forward(p["Q"], p["K"], p["V"], sigma=0.8, eps=0.0, **common)["O"]
+    o2 = wo.forward(p["Q"], p["K"], p["V"], sigma=2.9, eps=0.0, **common)["O"]
+    np.testing.assert_allclose(o1, o2, rtol=1e-10, atol=1e-12)
+    eps = 1e-2
+    g = wo.backward(p["Q"], p["K"], p["V"], sigma=p["sigma"], dO=p["dO"], eps=eps, **common)
+    closed = 2.0 * eps / p["sigma"] * g["dD_sum"]
+    assert abs(g["dsigma"] - closed) < 1e-9 * max(1.0, abs(closed))
+    # a common rescaling of all F_i acts like 1/sigma: sum_i omega_i * domega_i == -sigma * dsigma
+    # holds only without the pooled path, i.e. d/d(log c) of F -> cF equals -d/d(log sigma)
+    assert abs(float(np.sum(p["omega"] * g["domega"])) + p["sigma"] * g["dsigma"]) < 1e-9
+
+
+# ---------------------------------------------------------------- finite differences
+def _loss(p, eps, **over):
+    q = dict(p)
+    q.update(over)
+    O = wo.forward(q["Q"], q["K"], q["V"], q["Omega"], q["sigma"], q["Wg"], q["bg"], q["omega"],
+                   q["L"], eps=eps)["O"]
+    return float(np.sum(O * p["dO"]))
+
+
+@pytest.mark.parametrize("n,L", [(64, 3), (40, 2)])
+def test_backward_matches_central_finite_differences(n, L):
+    """The backward is the derivative of the forward: central differences in float64 on a tiny
+    problem with a shifted Q (so the pooled-query path matters), two batches and two heads (so
+    the cross-slice sums of the parameter gradients are exercised), and n = 40 (zero padding)."""
+    eps = 1e-2
+    p = _rand_problem(23 + n, n=n, L=L)
+    g = wo.backward(p["Q"], p["K"], p["V"], p["Omega"], p["sigma"], p["Wg"], p["bg"], p["omega"],
+                    L, p["dO"], eps=eps)
+    h = 1e-6
+    r = np.random.default_rng(99)
+
+    def check(name, gname, count):
+        arr = p[name]
+        flat_idx = r.choice(arr.size, size=min(count, arr.size), replace=False)
+        for fi in flat_idx:
+            idx = np.unravel_index(fi, arr.shape)
+            ap, am = arr.copy(), arr.copy()
+            ap[idx] += h
+            am[idx] -= h
+            fd = (_loss(p, eps, **{name: ap}) - _loss(p, eps, **{name: am})) / (2 * h)
+            an = g[gname][idx]
+            assert abs(fd - an) < 2e-6 * max(1.0, abs(an)), (name, idx, fd, an)
+
+    check("Q", "dQ", 12)
+    check("K", "dK", 12)
+    check("V", "dV", 8)
+    check("Wg", "dWg", 10)
+    check("bg", "dbg", 8)
+    check("omega", "domega", L + 1)
+    fd = (_loss(p, eps, sigma=p["sigma"] + h) - _loss(p, eps, sigma=p["sigma"] - h)) / (2 * h)
+    assert abs(fd - g["dsigma"]) < 2e-6 * max(1.0, abs(fd))
+
+
+# ---------------------------------------------------------------- ablation special cases
+def test_ablation_special_cases():
+    """Appendix E switches as special cases: all filters 1 is plain ReLU-feature linear attention
+    on the unfiltered Q, K; zero gate weights make F independent of Q."""
+    p = _rand_problem(29, B=1, H=1, n=64, d=4, m=16, L=3)
+    Q, K, V = p["Q"][0, 0], p["K"][0, 0], p["V"][0, 0]
+    # F == 1: huge bias saturates the sigmoid, omega = 1
+    big = np.full(4, 50.0)
+    f = wo.forward_slice(Q, K, V, p["Omega"], 1.0, 0 * p["Wg"][0], big, np.ones(4), 3, 1e-6, 1e-6)
+    m = 16
+    pq = np.maximum(Q @ p["Omega"], 0) / math.sqrt(m)
+    pk = np.maximum(K @ p["Omega"], 0) / math.sqrt(m)
+    ref = (pq @ (pk.T @ V)) / ((pq @ pk.sum(axis=0)) + 1e-6)[:, None]
+    np.testing.assert_allclose(f["O"], ref, rtol=1e-9)
+    # Wg == 0: gradient through the pooled query vanishes, dWg is still dlogits x qbar
+    g0 = wo.backward_slice(Q, K, V, p["Omega"], 1.0, 0 * p["Wg"][0], p["bg"][0], p["omega"], 3,
+                           1e-6, 1e-6, p["dO"][0, 0])
+    QF = wo.haar_filter(Q, g0["dF"] * 0 + wo.gate(Q.mean(0), 0 * p["Wg"][0], p["bg"][0], p["omega"])[2], 3)
+    # with Wg = 0, dQ is exactly the filter applied to dQ_F (self-adjoint operator)
+    F = wo.gate(Q.mean(0), 0 * p["Wg"][0], p["bg"][0], p["omega"])[2]
+    np.testing.assert_allclose(g0["dQ"], wo.haar_filter(g0["dQF"], F, 3), atol=1e-12)
+    assert QF.shape == Q.shape
