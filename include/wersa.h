@@ -1,0 +1,118 @@
+/*
+ * wersa.h -- C ABI of the WERSA attention hot path for AMD MI355X (gfx950).
+ *
+ * WERSA (Wavelet-Enhanced Random Spectral Attention) per (batch, head) slice, with
+ * Q, K, V in R^{n x d} (paper Section 3.1, steps 3-8):
+ *
+ *   qbar   = mean over the n rows of Q                                   (step 4, Q'_avg)
+ *   F_i    = sigmoid(W_g[h] qbar + b_g[h])_i * omega_i,  i = 0..L        (step 4, F_i)
+ *   X_F    = W^-1( F (.) W X )  for X in {Q, K}; W = L-level Haar DWT    (steps 3, 5, 6)
+ *            band 0 = finest detail d_1 ... band L-1 = d_L, band L = approximation a_L
+ *            (return order of Algorithm 2's DWT); the same F gates Q and K
+ *   Phi_X  = ReLU( X_F Omega / sigma_eff ) / sqrt(m),  sigma_eff = max(sigma, bw_floor)
+ *                                                    (step 7; Algorithm 1 projection lines)
+ *   S      = Phi_K^T V  (m x d),   z = Phi_K^T 1  (m)                    (step 8 numerator/denominator)
+ *   O      = (Phi_Q S) / (Phi_Q z + eps)                                 (step 8, attention equation)
+ *
+ * wersa_backward returns the gradients of a scalar loss with respect to Q, K, V, W_g, b_g,
+ * omega and sigma given dO = d loss / d O (the paper states no backward; it is the derivative
+ * of the forward above).
+ *
+ * Conventions
+ *   - Every data pointer is a DEVICE pointer owned by the caller. The library allocates
+ *     nothing, frees nothing and never synchronises: work is enqueued on `hip_stream`
+ *     (a hipStream_t passed as void*, NULL = the default stream) and the call returns.
+ *   - Tensors q, k, v, out, dout, dq, dk, dv share one layout: element (b, h, t, j) lives at
+ *     b*stride_b + h*stride_h + t*stride_n + j (strides in elements, j contiguous).
+ *   - omega_rf (the random matrix Omega) is d x m row-major in the tensor dtype.
+ *   - Parameters and their gradients are float32: gate_w [H][L+1][d], gate_b [H][L+1],
+ *     scale_w [L+1] (the per-scale weights omega), sigma [1].
+ *   - Gradients are overwritten, not accumulated. dgate_w, dgate_b, dscale_w, dsigma may each
+ *     be NULL to skip that output.
+ *   - `saved` is written by wersa_forward and read by wersa_backward (wersa_saved_bytes).
+ *     `workspace` is scratch, at least wersa_workspace_bytes; both 256-byte aligned.
+ *   - All argument validation happens before anything is enqueued; on error nothing is
+ *     launched. No exception or abort crosses the boundary.
+ *   - No mutable global state: calls on different streams with different buffers may overlap.
+ *   - Results are deterministic: reductions use fixed-order two-pass sums, no float atomics.
+ */
+#ifndef WERSA_H
+#define WERSA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  WERSA_OK = 0,
+  WERSA_ERR_INVALID_ARG = 1, /* NULL pointer, non-positive size, bad stride or enum       */
+  WERSA_ERR_UNSUPPORTED = 2, /* valid problem outside the implemented range (see desc)    */
+  WERSA_ERR_WORKSPACE = 3,   /* workspace_bytes too small or misaligned                    */
+  WERSA_ERR_LAUNCH = 4       /* the HIP runtime refused a launch                           */
+} wersa_status;
+
+typedef enum { WERSA_F32 = 0, WERSA_BF16 = 1 } wersa_dtype;
+
+/*
+ * Problem descriptor (host memory, read during the call only).
+ * Supported range: B, H, n >= 1; 0 <= L <= 6 and n % 2^L == 0 (the Haar filter is local to
+ * aligned blocks of 2^L rows, so the zero padding of Algorithm 2 is never needed);
+ * d % 16 == 0, 16 <= d <= 256; m % 16 == 0, 16 <= m <= 4096. Anything else that is
+ * otherwise well formed returns WERSA_ERR_UNSUPPORTED.
+ */
+typedef struct {
+  int32_t B, H, n, d, L, m;
+  int32_t dtype;         /* wersa_dtype of q, k, v, omega_rf, out, dout, dq, dk, dv        */
+  float eps;             /* epsilon of the normaliser (Section 3.1 step 8)                  */
+  float bw_floor;        /* floor of the bandwidth (Algorithm 1: bw = max(beta, floor))     */
+  int64_t stride_b, stride_h, stride_n;
+} wersa_desc;
+
+/* Bytes of scratch needed by wersa_forward (for_backward == 0) or wersa_backward (!= 0).
+ * Returns 0 if the descriptor is invalid or unsupported. */
+size_t wersa_workspace_bytes(const wersa_desc *desc, int for_backward);
+
+/* Bytes of the buffer that carries S, z, qbar, the gate activations, F and the normaliser D
+ * from forward to backward. Returns 0 if the descriptor is invalid or unsupported. */
+size_t wersa_saved_bytes(const wersa_desc *desc);
+
+/* Forward pass (Section 3.1 steps 3-8). Writes out (B,H,n,d) and saved. */
+wersa_status wersa_forward(const wersa_desc *desc, const void *q, const void *k, const void *v,
+                           const void *omega_rf, const float *sigma, const float *gate_w,
+                           const float *gate_b, const float *scale_w, void *out, void *saved,
+                           void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Backward pass: derivative of wersa_forward. `out` and `saved` are those of the matching
+ * forward call on the same inputs. */
+wersa_status wersa_backward(const wersa_desc *desc, const void *q, const void *k, const void *v,
+                            const void *omega_rf, const float *sigma, const float *gate_w,
+                            const float *gate_b, const float *scale_w, const void *out,
+                            const void *dout, const void *saved, void *dq, void *dk, void *dv,
+                            float *dgate_w, float *dgate_b, float *dscale_w, float *dsigma,
+                            void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Stage entry point: the gated Haar filter alone, X_F = W^-1(F (.) W X) (Section 3.1 steps
+ * 3, 5, 6; Appendix A equations) for one tensor x laid out like q, with per-slice filter
+ * coefficients filt [B*H][L+1] (float32, device). Output xf has the same layout and dtype.
+ */
+wersa_status wersa_haar_filter(const wersa_desc *desc, const void *x, const float *filt,
+                               void *xf, void *hip_stream);
+
+/* Offsets (in floats) of the pieces inside `saved`, for tests and tools:
+ * which = 0 S [B*H][m][d], 1 z [B*H][m], 2 qbar [B*H][d], 3 gate sigmoid s [B*H][L+1],
+ * 4 F [B*H][L+1], 5 D [B*H][n]. Returns -1 on a bad argument. */
+int64_t wersa_saved_offset(const wersa_desc *desc, int which);
+
+const char *wersa_status_string(wersa_status status);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int32_t wersa_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WERSA_H */

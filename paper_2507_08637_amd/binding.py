@@ -1,0 +1,205 @@
+"""ctypes binding of libwersa.so: argument marshalling only.
+
+Function names mirror the C entry points of include/wersa.h.  Tensors are torch CUDA tensors
+(torch supplies device memory and the stream; every step of the computation runs inside the
+library's HIP kernels).  There is no CPU fallback: if the shared library is missing, loading
+raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libwersa.so")
+
+WERSA_F32, WERSA_BF16 = 0, 1
+EXPORTS = ["wersa_workspace_bytes", "wersa_saved_bytes", "wersa_forward", "wersa_backward",
+           "wersa_haar_filter", "wersa_saved_offset", "wersa_status_string", "wersa_version"]
+
+
+class WersaDesc(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("n", ctypes.c_int32),
+                ("d", ctypes.c_int32), ("L", ctypes.c_int32), ("m", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("eps", ctypes.c_float), ("bw_floor", ctypes.c_float),
+                ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64),
+                ("stride_n", ctypes.c_int64)]
+
+
+class WersaError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__(f"wersa status {status}: {text}")
+        self.status = status
+
+
+_lib = None
+
+
+def load_library():
+    """Load libwersa.so (built by paper_2507_08637_amd.build); raises if it is not there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} not found: build it with `python -m paper_2507_08637_amd.build` "
+                           "(there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, fp, dp = ctypes.c_void_p, ctypes.c_void_p, ctypes.POINTER(WersaDesc)
+    lib.wersa_workspace_bytes.restype = ctypes.c_size_t
+    lib.wersa_workspace_bytes.argtypes = [dp, ctypes.c_int]
+    lib.wersa_saved_bytes.restype = ctypes.c_size_t
+    lib.wersa_saved_bytes.argtypes = [dp]
+    lib.wersa_saved_offset.restype = ctypes.c_int64
+    lib.wersa_saved_offset.argtypes = [dp, ctypes.c_int]
+    lib.wersa_forward.restype = ctypes.c_int
+    lib.wersa_forward.argtypes = [dp, vp, vp, vp, vp, fp, fp, fp, fp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.wersa_backward.restype = ctypes.c_int
+    lib.wersa_backward.argtypes = [dp] + [vp] * 4 + [fp] * 4 + [vp] * 3 + [vp] * 3 + [fp] * 4 + \
+        [vp, ctypes.c_size_t, vp]
+    lib.wersa_haar_filter.restype = ctypes.c_int
+    lib.wersa_haar_filter.argtypes = [dp, vp, fp, vp, vp]
+    lib.wersa_status_string.restype = ctypes.c_char_p
+    lib.wersa_status_string.argtypes = [ctypes.c_int]
+    lib.wersa_version.restype = ctypes.c_int32
+    lib.wersa_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+def _check(status):
+    if status != 0:
+        raise WersaError(status, load_library().wersa_status_string(status).decode())
+
+
+def make_desc(x, L, m, eps=1e-6, bw_floor=1e-6):
+    """Descriptor for a (B, H, n, d) tensor x (last dim contiguous)."""
+    assert x.dim() == 4 and x.stride(3) == 1, "expect (B, H, n, d) with contiguous last dim"
+    B, H, n, d = x.shape
+    if x.dtype == torch.float32:
+        dt = WERSA_F32
+    elif x.dtype == torch.bfloat16:
+        dt = WERSA_BF16
+    else:
+        raise TypeError("dtype must be float32 or bfloat16")
+    return WersaDesc(B, H, n, d, L, m, dt, eps, bw_floor, x.stride(0), x.stride(1), x.stride(2))
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _same_layout(ref, *others):
+    for t in others:
+        assert t.shape == ref.shape and t.stride() == ref.stride() and t.dtype == ref.dtype, \
+            "q, k, v, out and gradients must share shape, strides and dtype"
+
+
+def wersa_workspace_bytes(desc, for_backward):
+    return load_library().wersa_workspace_bytes(ctypes.byref(desc), int(for_backward))
+
+
+def wersa_saved_bytes(desc):
+    return load_library().wersa_saved_bytes(ctypes.byref(desc))
+
+
+def saved_views(desc, saved):
+    """Named float32 views into the saved buffer: S, z, qbar, s, F, D."""
+    lib = load_library()
+    sl = desc.B * desc.H
+    shapes = [("S", (sl, desc.m, desc.d)), ("z", (sl, desc.m)), ("qbar", (sl, desc.d)),
+              ("s", (sl, desc.L + 1)), ("F", (sl, desc.L + 1)), ("D", (sl, desc.n))]
+    out = {}
+    for which, (name, shape) in enumerate(shapes):
+        off = lib.wersa_saved_offset(ctypes.byref(desc), which)
+        cnt = 1
+        for s in shape:
+            cnt *= s
+        out[name] = saved[off:off + cnt].view(*shape)
+    return out
+
+
+def alloc_like(desc, ref, for_backward):
+    """Allocate (saved, workspace) float32 buffers on ref's device."""
+    lib = load_library()
+    sb = lib.wersa_saved_bytes(ctypes.byref(desc))
+    wb = lib.wersa_workspace_bytes(ctypes.byref(desc), int(for_backward))
+    if sb == 0 or wb == 0:
+        raise WersaError(2, "descriptor rejected (invalid or unsupported shape)")
+    saved = torch.empty(sb // 4, dtype=torch.float32, device=ref.device)
+    ws = torch.empty(wb // 4, dtype=torch.float32, device=ref.device)
+    return saved, ws
+
+
+def wersa_forward(q, k, v, omega_rf, sigma, gate_w, gate_b, scale_w, L, eps=1e-6, bw_floor=1e-6,
+                  out=None, saved=None, workspace=None, stream=None):
+    """Returns (out, saved).  All tensor arguments live on one CUDA device."""
+    lib = load_library()
+    _same_layout(q, k, v)
+    desc = make_desc(q, L, omega_rf.shape[1], eps, bw_floor)
+    assert omega_rf.is_contiguous() and omega_rf.dtype == q.dtype and omega_rf.shape[0] == q.shape[3]
+    for p in (sigma, gate_w, gate_b, scale_w):
+        assert p.dtype == torch.float32 and p.is_contiguous()
+    if out is None:
+        out = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+    else:
+        _same_layout(q, out)
+    if saved is None:
+        sb = lib.wersa_saved_bytes(ctypes.byref(desc))
+        if sb == 0:
+            _check(_probe(desc))
+        saved = torch.empty(sb // 4, dtype=torch.float32, device=q.device)
+    wb = lib.wersa_workspace_bytes(ctypes.byref(desc), 0)
+    if workspace is None:
+        workspace = torch.empty(max(wb, 256) // 4, dtype=torch.float32, device=q.device)
+    _check(lib.wersa_forward(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(omega_rf), _ptr(sigma),
+                             _ptr(gate_w), _ptr(gate_b), _ptr(scale_w), _ptr(out), _ptr(saved),
+                             _ptr(workspace), workspace.numel() * 4, _stream(stream)))
+    return out, saved
+
+
+def _probe(desc):
+    # wersa_saved_bytes returned 0: ask the forward entry point for the precise status
+    return load_library().wersa_forward(ctypes.byref(desc), *([None] * 12), 0, None)
+
+
+def wersa_backward(q, k, v, omega_rf, sigma, gate_w, gate_b, scale_w, out, dout, saved, L,
+                   eps=1e-6, bw_floor=1e-6, workspace=None, stream=None, param_grads=True):
+    """Returns dict(dq, dk, dv, dgate_w, dgate_b, dscale_w, dsigma)."""
+    lib = load_library()
+    _same_layout(q, k, v, out, dout)
+    desc = make_desc(q, L, omega_rf.shape[1], eps, bw_floor)
+    dq = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+    dk = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+    dv = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+    if param_grads:
+        dgw = torch.empty_like(gate_w)
+        dgb = torch.empty_like(gate_b)
+        dsw = torch.empty_like(scale_w)
+        dsg = torch.empty(1, dtype=torch.float32, device=q.device)
+    else:
+        dgw = dgb = dsw = dsg = None
+    wb = lib.wersa_workspace_bytes(ctypes.byref(desc), 1)
+    if workspace is None:
+        workspace = torch.empty(max(wb, 256) // 4, dtype=torch.float32, device=q.device)
+    _check(lib.wersa_backward(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(omega_rf), _ptr(sigma),
+                              _ptr(gate_w), _ptr(gate_b), _ptr(scale_w), _ptr(out), _ptr(dout),
+                              _ptr(saved), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dgw), _ptr(dgb),
+                              _ptr(dsw), _ptr(dsg), _ptr(workspace), workspace.numel() * 4,
+                              _stream(stream)))
+    return dict(dq=dq, dk=dk, dv=dv, dgate_w=dgw, dgate_b=dgb, dscale_w=dsw, dsigma=dsg)
+
+
+def wersa_haar_filter(x, filt, L, out=None, stream=None):
+    """X_F = W^-1(F (.) W X) for x (B, H, n, d) and filt (B*H, L+1) float32."""
+    lib = load_library()
+    desc = make_desc(x, L, 16)
+    assert filt.dtype == torch.float32 and filt.is_contiguous() and filt.numel() == x.shape[0] * x.shape[1] * (L + 1)
+    if out is None:
+        out = torch.empty_strided(x.shape, x.stride(), dtype=x.dtype, device=x.device)
+    _check(lib.wersa_haar_filter(ctypes.byref(desc), _ptr(x), _ptr(filt), _ptr(out), _stream(stream)))
+    return out

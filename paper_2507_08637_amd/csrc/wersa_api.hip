@@ -1,0 +1,110 @@
+// C ABI entry points: argument validation and dispatch. See include/wersa.h for the contract.
+#include "wersa_internal.h"
+
+namespace wersa {
+
+wersa_status validate_desc(const wersa_desc *c) {
+  if (!c) return WERSA_ERR_INVALID_ARG;
+  if (c->B < 1 || c->H < 1 || c->n < 1 || c->d < 1 || c->m < 1 || c->L < 0) return WERSA_ERR_INVALID_ARG;
+  if (c->dtype != WERSA_F32 && c->dtype != WERSA_BF16) return WERSA_ERR_INVALID_ARG;
+  if (!(c->eps >= 0.f) || !(c->bw_floor > 0.f)) return WERSA_ERR_INVALID_ARG;
+  if (c->stride_n < c->d || c->stride_h < 0 || c->stride_b < 0) return WERSA_ERR_INVALID_ARG;
+  if (c->H > 1 && c->stride_h == 0) return WERSA_ERR_INVALID_ARG;
+  if (c->B > 1 && c->stride_b == 0) return WERSA_ERR_INVALID_ARG;
+  if (c->L > kMaxL) return WERSA_ERR_UNSUPPORTED;
+  if (c->n % (1 << c->L) != 0) return WERSA_ERR_UNSUPPORTED;
+  if (c->d % 16 != 0 || c->d < 16 || c->d > 256) return WERSA_ERR_UNSUPPORTED;
+  if (c->m % 16 != 0 || c->m < 16 || c->m > 4096) return WERSA_ERR_UNSUPPORTED;
+  if ((int64_t)c->B * c->H > 1023) return WERSA_ERR_UNSUPPORTED;
+  if ((int64_t)c->n > (int64_t)1 << 22) return WERSA_ERR_UNSUPPORTED;
+  return WERSA_OK;
+}
+
+}  // namespace wersa
+
+using namespace wersa;
+
+extern "C" {
+
+size_t wersa_workspace_bytes(const wersa_desc *desc, int for_backward) {
+  if (validate_desc(desc) != WERSA_OK) return 0;
+  return generic_workspace_bytes(*desc, for_backward);
+}
+
+size_t wersa_saved_bytes(const wersa_desc *desc) {
+  if (validate_desc(desc) != WERSA_OK) return 0;
+  return (size_t)saved_layout(*desc).total * sizeof(float);
+}
+
+int64_t wersa_saved_offset(const wersa_desc *desc, int which) {
+  if (validate_desc(desc) != WERSA_OK) return -1;
+  const SavedLayout s = saved_layout(*desc);
+  switch (which) {
+    case 0: return s.S;
+    case 1: return s.z;
+    case 2: return s.qbar;
+    case 3: return s.s;
+    case 4: return s.F;
+    case 5: return s.D;
+    default: return -1;
+  }
+}
+
+static bool misaligned(const void *p, size_t a) { return ((uintptr_t)p % a) != 0; }
+
+wersa_status wersa_forward(const wersa_desc *desc, const void *q, const void *k, const void *v,
+                           const void *omega_rf, const float *sigma, const float *gate_w,
+                           const float *gate_b, const float *scale_w, void *out, void *saved,
+                           void *workspace, size_t workspace_bytes, void *hip_stream) {
+  const wersa_status vs = validate_desc(desc);
+  if (vs != WERSA_OK) return vs;
+  if (!q || !k || !v || !omega_rf || !sigma || !gate_w || !gate_b || !scale_w || !out || !saved)
+    return WERSA_ERR_INVALID_ARG;
+  if (!workspace || workspace_bytes < wersa_workspace_bytes(desc, 0) || misaligned(workspace, 256) ||
+      misaligned(saved, 256))
+    return WERSA_ERR_WORKSPACE;
+  return generic_forward(*desc, q, k, v, omega_rf, sigma, gate_w, gate_b, scale_w, out, (float *)saved,
+                         (float *)workspace, (hipStream_t)hip_stream);
+}
+
+wersa_status wersa_backward(const wersa_desc *desc, const void *q, const void *k, const void *v,
+                            const void *omega_rf, const float *sigma, const float *gate_w,
+                            const float *gate_b, const float *scale_w, const void *out,
+                            const void *dout, const void *saved, void *dq, void *dk, void *dv,
+                            float *dgate_w, float *dgate_b, float *dscale_w, float *dsigma,
+                            void *workspace, size_t workspace_bytes, void *hip_stream) {
+  const wersa_status vs = validate_desc(desc);
+  if (vs != WERSA_OK) return vs;
+  if (!q || !k || !v || !omega_rf || !sigma || !gate_w || !gate_b || !scale_w || !out || !dout ||
+      !saved || !dq || !dk || !dv)
+    return WERSA_ERR_INVALID_ARG;
+  if (!workspace || workspace_bytes < wersa_workspace_bytes(desc, 1) || misaligned(workspace, 256) ||
+      misaligned(saved, 256))
+    return WERSA_ERR_WORKSPACE;
+  return generic_backward(*desc, q, k, v, omega_rf, sigma, gate_w, gate_b, scale_w, out, dout,
+                          (const float *)saved, dq, dk, dv, dgate_w, dgate_b, dscale_w, dsigma,
+                          (float *)workspace, (hipStream_t)hip_stream);
+}
+
+wersa_status wersa_haar_filter(const wersa_desc *desc, const void *x, const float *filt, void *xf,
+                               void *hip_stream) {
+  const wersa_status vs = validate_desc(desc);
+  if (vs != WERSA_OK) return vs;
+  if (!x || !filt || !xf) return WERSA_ERR_INVALID_ARG;
+  return generic_haar_filter(*desc, x, filt, xf, (hipStream_t)hip_stream);
+}
+
+const char *wersa_status_string(wersa_status status) {
+  switch (status) {
+    case WERSA_OK: return "ok";
+    case WERSA_ERR_INVALID_ARG: return "invalid argument";
+    case WERSA_ERR_UNSUPPORTED: return "unsupported problem shape";
+    case WERSA_ERR_WORKSPACE: return "workspace or saved buffer too small or misaligned";
+    case WERSA_ERR_LAUNCH: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+int32_t wersa_version(void) { return 100; }
+
+}  // extern "C"

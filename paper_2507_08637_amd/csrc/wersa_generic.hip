@@ -1,0 +1,709 @@
+// Generic WERSA path: float32 arithmetic for every storage dtype, one kernel per step of
+// Section 3.1 (steps 3-8), staged through caller workspace.  It covers the whole supported
+// range and is the float32 product path.  Reductions are fixed-order two-pass sums.
+#include "wersa_internal.h"
+
+namespace wersa {
+namespace {
+
+constexpr int kTileRows = 64;  // rows of one Haar tile: the largest aligned block, 2^kMaxL
+constexpr int kTileCols = 64;
+
+View contiguous_view(int64_t rows, int64_t width) {
+  View v;
+  v.sb = rows * width;
+  v.sh = 0;
+  v.sn = width;
+  v.H = 1;
+  return v;
+}
+
+// ------------------------------------------------------------------------------------
+// scalars[0] = c = 1 / (sigma_eff * sqrt(m));  scalars[1] = sigma_eff;
+// scalars[2] = 1 if sigma > bw_floor (sigma receives a gradient) else 0.
+// ------------------------------------------------------------------------------------
+__global__ void scalars_kernel(const float *sigma, float bw_floor, int m, float *scalars) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    const float s = *sigma;
+    const float se = fmaxf(s, bw_floor);
+    scalars[0] = 1.0f / (se * sqrtf((float)m));
+    scalars[1] = se;
+    scalars[2] = s > bw_floor ? 1.0f : 0.0f;
+  }
+}
+
+// part[slice][chunk][j] = sum over rows t of the chunk of w[slice][t] * x[slice][t][j]
+template <typename T>
+__global__ void colsum_partial_kernel(const T *x, View v, int n, int W, int rows_per_chunk,
+                                      const float *w, float *part) {
+  const int slice = blockIdx.y, chunk = blockIdx.x, chunks = gridDim.x;
+  const int t0 = chunk * rows_per_chunk;
+  const int t1 = min(n, t0 + rows_per_chunk);
+  const T *xs = x + v.slice_base(slice);
+  const int lane = threadIdx.x & 63, ph = threadIdx.x >> 6;
+  __shared__ float red[4][64];
+  for (int j0 = 0; j0 < W; j0 += 64) {
+    const int j = j0 + lane;
+    float acc = 0.f;
+    if (j < W) {
+      for (int t = t0 + ph; t < t1; t += 4) {
+        const float xv = ld(xs + (int64_t)t * v.sn + j);
+        acc += w ? w[(int64_t)slice * n + t] * xv : xv;
+      }
+    }
+    red[ph][lane] = acc;
+    __syncthreads();
+    if (ph == 0 && j < W)
+      part[((int64_t)slice * chunks + chunk) * W + j] =
+          (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
+    __syncthreads();
+  }
+}
+
+// out[slice][j] = scale * sum_c part[slice][c][j]   (fixed order)
+__global__ void reduce_partials_kernel(const float *part, int chunks, int64_t W, float scale,
+                                       float *out) {
+  const int slice = blockIdx.y;
+  const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= W) return;
+  const float *p = part + (int64_t)slice * chunks * W + j;
+  float acc = 0.f;
+  for (int c = 0; c < chunks; ++c) acc += p[(int64_t)c * W];
+  out[(int64_t)slice * W + j] = acc * scale;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// Gate (Section 3.1 step 4): qbar, s = sigmoid(W_g qbar + b_g), F = s * omega. One wave per slice.
+__global__ void gate_fwd_kernel(const float *qpart, int chunks, int n, int d, int L, int H,
+                                const float *gate_w, const float *gate_b, const float *scale_w,
+                                float *qbar, float *s_out, float *F_out) {
+  const int slice = blockIdx.x, h = slice % H, lane = threadIdx.x;
+  __shared__ float qb[256];
+  for (int j = lane; j < d; j += 64) {
+    const float *p = qpart + (int64_t)slice * chunks * d + j;
+    float acc = 0.f;
+    for (int c = 0; c < chunks; ++c) acc += p[(int64_t)c * d];
+    acc /= (float)n;
+    qb[j] = acc;
+    qbar[(int64_t)slice * d + j] = acc;
+  }
+  __syncthreads();
+  for (int i = 0; i <= L; ++i) {
+    const float *w = gate_w + ((int64_t)h * (L + 1) + i) * d;
+    float acc = 0.f;
+    for (int j = lane; j < d; j += 64) acc += w[j] * qb[j];
+    acc = wave_sum(acc);
+    if (lane == 0) {
+      const float logit = acc + gate_b[h * (L + 1) + i];
+      const float s = 1.0f / (1.0f + expf(-logit));
+      s_out[slice * (L + 1) + i] = s;
+      F_out[slice * (L + 1) + i] = s * scale_w[i];
+    }
+  }
+}
+
+// In-place Haar lifting on a 64-row LDS tile, one column per lane (Appendix A equations).
+// After `L` analysis levels the approximation a_L sits at rows that are multiples of 2^L and
+// the level-l detail at odd multiples of 2^(l-1).
+__device__ __forceinline__ void haar_analysis_tile(float (*tile)[kTileCols], int L, int c, int g) {
+  const float r2 = 0.70710678118654752440f;
+  for (int l = 1; l <= L; ++l) {
+    const int half = 1 << (l - 1), stride = 1 << l, pairs = kTileRows >> l;
+    for (int p = g; p < pairs; p += 4) {
+      const int i0 = p * stride, i1 = i0 + half;
+      const float a = tile[i0][c], b = tile[i1][c];
+      tile[i0][c] = (a + b) * r2;
+      tile[i1][c] = (a - b) * r2;
+    }
+    __syncthreads();
+  }
+}
+__device__ __forceinline__ void haar_synthesis_tile(float (*tile)[kTileCols], int L, int c, int g) {
+  const float r2 = 0.70710678118654752440f;
+  for (int l = L; l >= 1; --l) {
+    const int half = 1 << (l - 1), stride = 1 << l, pairs = kTileRows >> l;
+    for (int p = g; p < pairs; p += 4) {
+      const int i0 = p * stride, i1 = i0 + half;
+      const float a = tile[i0][c], dt = tile[i1][c];
+      tile[i0][c] = (a + dt) * r2;
+      tile[i1][c] = (a - dt) * r2;
+    }
+    __syncthreads();
+  }
+}
+// Band index of in-place coefficient row r: a_L at multiples of 2^L, else detail level ctz+1.
+__device__ __forceinline__ int band_of_row(int r, int L) {
+  const int pos = r & ((1 << L) - 1);
+  return pos == 0 ? L : __builtin_ctz(pos);
+}
+
+// y = W^-1 (F (.) W x) (+ addscale * addvec[slice][j]) on 64-row x 64-column tiles.
+template <typename TIn, typename TOut>
+__global__ void haar_filter_kernel(const TIn *x, View vin, TOut *y, View vout, const float *filt,
+                                   const float *addvec, float addscale, int n, int d, int L) {
+  __shared__ float tile[kTileRows][kTileCols];
+  __shared__ float F[kMaxBands];
+  const int slice = blockIdx.z;
+  const int t0 = blockIdx.x * kTileRows, j = blockIdx.y * kTileCols + (threadIdx.x & 63);
+  const int c = threadIdx.x & 63, g = threadIdx.x >> 6;
+  if (threadIdx.x <= L) F[threadIdx.x] = filt[slice * (L + 1) + threadIdx.x];
+  const TIn *xs = x + vin.slice_base(slice);
+  for (int r = g; r < kTileRows; r += 4) {
+    const int t = t0 + r;
+    tile[r][c] = (t < n && j < d) ? ld(xs + (int64_t)t * vin.sn + j) : 0.f;
+  }
+  __syncthreads();
+  haar_analysis_tile(tile, L, c, g);
+  for (int r = g; r < kTileRows; r += 4) tile[r][c] *= F[band_of_row(r, L)];
+  __syncthreads();
+  haar_synthesis_tile(tile, L, c, g);
+  TOut *ys = y + vout.slice_base(slice);
+  const float add = (addvec && j < d) ? addscale * addvec[(int64_t)slice * d + j] : 0.f;
+  for (int r = g; r < kTileRows; r += 4) {
+    const int t = t0 + r;
+    if (t < n && j < d) st(ys + (int64_t)t * vout.sn + j, tile[r][c] + add);
+  }
+}
+
+// part[slice][tile][band] = sum over the tile of band_i(W x) * band_i(W g)
+template <typename TX>
+__global__ void band_dots_kernel(const TX *x, View vx, const float *gr, View vg, int n, int d,
+                                 int L, float *part) {
+  __shared__ float tx[kTileRows][kTileCols];
+  __shared__ float tg[kTileRows][kTileCols];
+  __shared__ float red[4][kMaxBands];
+  const int slice = blockIdx.z;
+  const int t0 = blockIdx.x * kTileRows, j = blockIdx.y * kTileCols + (threadIdx.x & 63);
+  const int c = threadIdx.x & 63, g = threadIdx.x >> 6;
+  const TX *xs = x + vx.slice_base(slice);
+  const float *gs = gr + vg.slice_base(slice);
+  for (int r = g; r < kTileRows; r += 4) {
+    const int t = t0 + r;
+    const bool ok = (t < n && j < d);
+    tx[r][c] = ok ? ld(xs + (int64_t)t * vx.sn + j) : 0.f;
+    tg[r][c] = ok ? gs[(int64_t)t * vg.sn + j] : 0.f;
+  }
+  __syncthreads();
+  haar_analysis_tile(tx, L, c, g);
+  haar_analysis_tile(tg, L, c, g);
+  float acc[kMaxBands];
+#pragma unroll
+  for (int b = 0; b < kMaxBands; ++b) acc[b] = 0.f;
+  for (int r = g; r < kTileRows; r += 4) {
+    const int band = band_of_row(r, L);
+    const float pr = tx[r][c] * tg[r][c];
+#pragma unroll
+    for (int b = 0; b < kMaxBands; ++b) acc[b] += (band == b) ? pr : 0.f;
+  }
+#pragma unroll
+  for (int b = 0; b < kMaxBands; ++b) {
+    const float s = wave_sum(acc[b]);
+    if (c == 0) red[g][b] = s;
+  }
+  __syncthreads();
+  if (threadIdx.x <= L) {
+    const int64_t tile_id = (int64_t)blockIdx.x * gridDim.y + blockIdx.y;
+    const int64_t tiles = (int64_t)gridDim.x * gridDim.y;
+    part[((int64_t)slice * tiles + tile_id) * (L + 1) + threadIdx.x] =
+        (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+  }
+}
+
+// Strided (B,H,n,W) tensor of dtype T  ->  contiguous float32 [slices][n][W]
+template <typename T>
+__global__ void gather_f32_kernel(const T *x, View v, int n, int W, int64_t total, float *y) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    const int j = (int)(i % W);
+    const int64_t r = i / W;
+    const int t = (int)(r % n);
+    const int slice = (int)(r / n);
+    y[i] = ld(x + v.slice_base(slice) + (int64_t)t * v.sn + j);
+  }
+}
+// contiguous float32 [slices][n][W] (optionally divided by rowdiv[slice][t]) -> strided T
+template <typename T>
+__global__ void scatter_kernel(const float *x, const float *rowdiv, T *y, View v, int n, int W,
+                               int64_t total) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    const int j = (int)(i % W);
+    const int64_t r = i / W;
+    const int t = (int)(r % n);
+    const int slice = (int)(r / n);
+    float val = x[i];
+    if (rowdiv) val /= rowdiv[r];
+    st(y + v.slice_base(slice) + (int64_t)t * v.sn + j, val);
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// Batched float32 GEMM with arbitrary operand strides (covers NN / TN / NT) and split-K.
+//   C[bz][s] (M x N, row-major ldc) = alpha * sum_{k in split s} A(i,k) B(k,j)  (+ ReLU first)
+// ------------------------------------------------------------------------------------
+struct GemmArgs {
+  const float *A, *B;
+  float *C;
+  int M, N, K;
+  int64_t sAi, sAk, sBk, sBj, ldc;
+  int64_t bsA, bsB, bsC;  // batch strides
+  int splits;
+  int64_t splitC;         // stride between the partial results of one batch entry
+  const float *alpha;     // device scalar or nullptr (= 1)
+  int relu;               // apply max(.,0) before alpha
+};
+
+__global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
+  constexpr int BM = 64, BN = 64, BK = 16;
+  __shared__ float As[BK][BM + 4];
+  __shared__ float Bs[BK][BN + 4];
+  const int bz = blockIdx.z / a.splits, sp = blockIdx.z % a.splits;
+  const float *A = a.A + (int64_t)bz * a.bsA;
+  const float *B = a.B + (int64_t)bz * a.bsB;
+  float *C = a.C + (int64_t)bz * a.bsC + (int64_t)sp * a.splitC;
+  const int i0 = blockIdx.y * BM, j0 = blockIdx.x * BN;
+  int kc = (a.K + a.splits - 1) / a.splits;
+  kc = (kc + BK - 1) / BK * BK;
+  const int kbeg = sp * kc, kend = min(a.K, kbeg + kc);
+  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+  float acc[4][4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+#pragma unroll
+    for (int w = 0; w < 4; ++w) acc[u][w] = 0.f;
+  const bool a_k_fast = (a.sAk == 1), b_j_fast = (a.sBj == 1);
+  for (int k0 = kbeg; k0 < kend; k0 += BK) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int e = tid + 256 * q;
+      int ii, kk;
+      if (a_k_fast) { kk = e & 15; ii = e >> 4; } else { ii = e & 63; kk = e >> 6; }
+      const int gi = i0 + ii, gk = k0 + kk;
+      As[kk][ii] = (gi < a.M && gk < kend) ? A[(int64_t)gi * a.sAi + (int64_t)gk * a.sAk] : 0.f;
+      int jj, kb;
+      if (b_j_fast) { jj = e & 63; kb = e >> 6; } else { kb = e & 15; jj = e >> 4; }
+      const int gj = j0 + jj, gkb = k0 + kb;
+      Bs[kb][jj] = (gj < a.N && gkb < kend) ? B[(int64_t)gkb * a.sBk + (int64_t)gj * a.sBj] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < BK; ++kk) {
+      float av[4], bv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) av[u] = As[kk][ty * 4 + u];
+#pragma unroll
+      for (int w = 0; w < 4; ++w) bv[w] = Bs[kk][tx * 4 + w];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int w = 0; w < 4; ++w) acc[u][w] = fmaf(av[u], bv[w], acc[u][w]);
+    }
+    __syncthreads();
+  }
+  const float alpha = a.alpha ? *a.alpha : 1.0f;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int gi = i0 + ty * 4 + u;
+    if (gi >= a.M) continue;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const int gj = j0 + tx * 4 + w;
+      if (gj >= a.N) continue;
+      float val = acc[u][w];
+      if (a.relu) val = fmaxf(val, 0.f);
+      C[(int64_t)gi * a.ldc + gj] = val * alpha;
+    }
+  }
+}
+
+// D[slice][t] = sum_r Phi[slice][t][r] z[slice][r] + eps    (one wave per row)
+__global__ void rowdot_kernel(const float *phi, const float *z, int n, int m, float eps, float *D) {
+  const int slice = blockIdx.y;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (t >= n) return;
+  const float *p = phi + ((int64_t)slice * n + t) * m;
+  const float *zz = z + (int64_t)slice * m;
+  float acc = 0.f;
+  for (int r = lane; r < m; r += 64) acc += p[r] * zz[r];
+  acc = wave_sum(acc);
+  if (lane == 0) D[(int64_t)slice * n + t] = acc + eps;
+}
+
+// dN = dO / D (row-wise), dD_t = -<dO_t, O_t> / D_t   (one wave per row)
+template <typename T>
+__global__ void prep_dn_kernel(const T *dout, const T *out, View v, const float *D, int n, int d,
+                               float *dN, float *dD) {
+  const int slice = blockIdx.y;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (t >= n) return;
+  const int64_t base = v.slice_base(slice) + (int64_t)t * v.sn;
+  const float Dt = D[(int64_t)slice * n + t];
+  float acc = 0.f;
+  for (int j = lane; j < d; j += 64) {
+    const float g = ld(dout + base + j);
+    acc += g * ld(out + base + j);
+    dN[((int64_t)slice * n + t) * d + j] = g / Dt;
+  }
+  acc = wave_sum(acc);
+  if (lane == 0) dD[(int64_t)slice * n + t] = -acc / Dt;
+}
+
+// R = (R + a[slice][t] * b[slice][r]) * 1[Phi > 0] * c     (a == nullptr means a = 1)
+__global__ void mask_scale_kernel(float *R, const float *phi, const float *a, const float *b,
+                                  const float *c_ptr, int n, int m, int64_t total) {
+  const float c = *c_ptr;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    const int r = (int)(i % m);
+    const int64_t row = i / m;  // slice * n + t
+    const int slice = (int)(row / n);
+    const float av = a ? a[row] : 1.0f;
+    const float val = R[i] + av * b[(int64_t)slice * m + r];
+    R[i] = phi[i] > 0.f ? val * c : 0.f;
+  }
+}
+
+// Per slice: dF (sum of tile partials of Q and K), dlogits, dqbar = W_g^T dlogits.
+__global__ void gate_bwd_slice_kernel(const float *partQ, const float *partK, int64_t tiles, int L,
+                                      int d, int H, const float *s_saved, const float *gate_w,
+                                      const float *scale_w, float *dF, float *dlogit, float *dqbar) {
+  const int slice = blockIdx.x, h = slice % H, lane = threadIdx.x;
+  __shared__ float dl[kMaxBands];
+  for (int i = 0; i <= L; ++i) {
+    float acc = 0.f;
+    for (int64_t t = lane; t < tiles; t += 64)
+      acc += partQ[((int64_t)slice * tiles + t) * (L + 1) + i] +
+             partK[((int64_t)slice * tiles + t) * (L + 1) + i];
+    acc = wave_sum(acc);
+    if (lane == 0) {
+      const float s = s_saved[slice * (L + 1) + i];
+      dF[slice * (L + 1) + i] = acc;
+      const float g = acc * scale_w[i] * s * (1.0f - s);
+      dlogit[slice * (L + 1) + i] = g;
+      dl[i] = g;
+    }
+  }
+  __syncthreads();
+  for (int j = lane; j < d; j += 64) {
+    float acc = 0.f;
+    for (int i = 0; i <= L; ++i) acc += gate_w[((int64_t)h * (L + 1) + i) * d + j] * dl[i];
+    dqbar[(int64_t)slice * d + j] = acc;
+  }
+}
+
+// Parameter gradients, summed over batch (and heads for omega) in fixed order. One block.
+__global__ void gate_bwd_params_kernel(const float *dF, const float *dlogit, const float *s_saved,
+                                       const float *qbar, const float *dDpart, int dDparts, int B,
+                                       int H, int L, int d, float eps, const float *scalars,
+                                       float *dgate_w, float *dgate_b, float *dscale_w,
+                                       float *dsigma) {
+  const int tid = threadIdx.x, nb = L + 1;
+  if (dgate_w) {
+    for (int e = tid; e < H * nb * d; e += blockDim.x) {
+      const int j = e % d, i = (e / d) % nb, h = e / (d * nb);
+      float acc = 0.f;
+      for (int b = 0; b < B; ++b) {
+        const int slice = b * H + h;
+        acc += dlogit[slice * nb + i] * qbar[(int64_t)slice * d + j];
+      }
+      dgate_w[e] = acc;
+    }
+  }
+  if (dgate_b) {
+    for (int e = tid; e < H * nb; e += blockDim.x) {
+      const int i = e % nb, h = e / nb;
+      float acc = 0.f;
+      for (int b = 0; b < B; ++b) acc += dlogit[(b * H + h) * nb + i];
+      dgate_b[e] = acc;
+    }
+  }
+  if (dscale_w && tid < nb) {
+    float acc = 0.f;
+    for (int slice = 0; slice < B * H; ++slice) acc += dF[slice * nb + tid] * s_saved[slice * nb + tid];
+    dscale_w[tid] = acc;
+  }
+  if (dsigma && tid == 0) {
+    // ReLU is positively homogeneous, so sigma reaches the output only through eps:
+    // d loss / d sigma = (2 eps / sigma_eff) * sum_t dD_t.
+    float acc = 0.f;
+    for (int p = 0; p < dDparts; ++p) acc += dDpart[p];
+    *dsigma = scalars[2] > 0.f ? 2.0f * eps / scalars[1] * acc : 0.f;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// host helpers
+// ---------------------------------------------------------------------------------------
+struct Bump {
+  float *base;
+  int64_t off = 0;
+  explicit Bump(float *b) : base(b) {}
+  float *take(int64_t nfloat) {
+    float *p = base ? base + off : nullptr;
+    off += (nfloat + 63) / 64 * 64;
+    return p;
+  }
+};
+
+int colsum_chunks(int n) {
+  int c = (n + 255) / 256;
+  return c < 1 ? 1 : (c > 256 ? 256 : c);
+}
+int gemm_splits(int n) {
+  int s = n / 1024;
+  return s < 1 ? 1 : (s > 64 ? 64 : s);
+}
+int ew_blocks(int64_t total) {
+  int64_t b = (total + 255) / 256;
+  return (int)(b > 65536 ? 65536 : (b < 1 ? 1 : b));
+}
+
+struct GenericWs {
+  float *scalars, *qpart, *QF, *KF, *Vf, *Of, *Phi, *R, *Spart, *zpart, *Nbuf;
+  float *dN, *dD, *dS, *dz, *dDpart, *dVf, *partQ, *partK, *dF, *dlogit, *dqbar;
+  int64_t total;
+};
+
+GenericWs plan(const wersa_desc &c, int bwd, float *base) {
+  GenericWs w{};
+  Bump b(base);
+  const int64_t sl = (int64_t)c.B * c.H, nd = sl * c.n * c.d, nm = sl * c.n * c.m;
+  const int chunks = colsum_chunks(c.n), splits = gemm_splits(c.n);
+  const int64_t tiles = (int64_t)((c.n + kTileRows - 1) / kTileRows) * ((c.d + kTileCols - 1) / kTileCols);
+  w.scalars = b.take(64);
+  w.qpart = b.take(sl * chunks * (int64_t)(c.m > c.d ? c.m : c.d));
+  w.QF = b.take(nd);
+  w.KF = b.take(nd);
+  w.Vf = b.take(nd);
+  w.Of = b.take((int64_t)c.d * c.m);  // Omega in float32
+  w.Phi = b.take(nm);
+  w.Spart = b.take(sl * splits * (int64_t)c.m * c.d);
+  w.zpart = w.qpart;  // same shape family, used after qpart is consumed
+  w.Nbuf = b.take(nd);
+  if (bwd) {
+    w.R = b.take(nm);
+    w.dN = w.Nbuf;
+    w.dD = b.take(sl * c.n);
+    w.dS = b.take(sl * (int64_t)c.m * c.d);
+    w.dz = b.take(sl * c.m);
+    w.dDpart = b.take(sl * chunks);
+    w.dVf = b.take(nd);
+    w.partQ = b.take(sl * tiles * (c.L + 1));
+    w.partK = b.take(sl * tiles * (c.L + 1));
+    w.dF = b.take(sl * (c.L + 1));
+    w.dlogit = b.take(sl * (c.L + 1));
+    w.dqbar = b.take(sl * c.d);
+  }
+  w.total = b.off;
+  return w;
+}
+
+template <typename T>
+void launch_colsum(const T *x, View v, int slices, int n, int W, const float *wt, float *part,
+                   float *out, float scale, hipStream_t st) {
+  const int chunks = colsum_chunks(n);
+  const int rows = (n + chunks - 1) / chunks;
+  colsum_partial_kernel<T><<<dim3(chunks, slices), 256, 0, st>>>(x, v, n, W, rows, wt, part);
+  if (out)
+    reduce_partials_kernel<<<dim3((W + 255) / 256, slices), 256, 0, st>>>(part, chunks, W, scale, out);
+}
+
+void launch_gemm(GemmArgs a, int batch, hipStream_t st) {
+  dim3 grid((a.N + 63) / 64, (a.M + 63) / 64, batch * a.splits);
+  gemm_kernel<<<grid, 256, 0, st>>>(a);
+}
+
+// Phi = ReLU(XF Omega) * c
+void launch_features(const wersa_desc &c, const float *XF, const GenericWs &w, hipStream_t st) {
+  GemmArgs a{};
+  a.A = XF; a.B = w.Of; a.C = w.Phi;
+  a.M = c.n; a.N = c.m; a.K = c.d;
+  a.sAi = c.d; a.sAk = 1; a.sBk = c.m; a.sBj = 1; a.ldc = c.m;
+  a.bsA = (int64_t)c.n * c.d; a.bsB = 0; a.bsC = (int64_t)c.n * c.m;
+  a.splits = 1; a.splitC = 0; a.alpha = w.scalars; a.relu = 1;
+  launch_gemm(a, c.B * c.H, st);
+}
+// out[slice] (m x d) = Phi[slice]^T Y[slice], reduced over n by split partials
+void launch_phiT_times(const wersa_desc &c, const float *Y, const GenericWs &w, float *out,
+                       hipStream_t st) {
+  const int splits = gemm_splits(c.n), slices = c.B * c.H;
+  GemmArgs a{};
+  a.A = w.Phi; a.B = Y; a.C = w.Spart;
+  a.M = c.m; a.N = c.d; a.K = c.n;
+  a.sAi = 1; a.sAk = c.m; a.sBk = c.d; a.sBj = 1; a.ldc = c.d;
+  a.bsA = (int64_t)c.n * c.m; a.bsB = (int64_t)c.n * c.d; a.bsC = (int64_t)splits * c.m * c.d;
+  a.splits = splits; a.splitC = (int64_t)c.m * c.d; a.alpha = nullptr; a.relu = 0;
+  launch_gemm(a, slices, st);
+  const int64_t W = (int64_t)c.m * c.d;
+  reduce_partials_kernel<<<dim3((unsigned)((W + 255) / 256), slices), 256, 0, st>>>(w.Spart, splits, W, 1.0f, out);
+}
+// C[slice] (n x N) = A[slice] (n x K) * op(B[slice]); B given by strides
+void launch_rows_gemm(const wersa_desc &c, const float *A, int K, const float *B, int64_t sBk,
+                      int64_t sBj, int64_t bsB, int N, float *C, hipStream_t st) {
+  GemmArgs a{};
+  a.A = A; a.B = B; a.C = C;
+  a.M = c.n; a.N = N; a.K = K;
+  a.sAi = K; a.sAk = 1; a.sBk = sBk; a.sBj = sBj; a.ldc = N;
+  a.bsA = (int64_t)c.n * K; a.bsB = bsB; a.bsC = (int64_t)c.n * N;
+  a.splits = 1; a.splitC = 0; a.alpha = nullptr; a.relu = 0;
+  launch_gemm(a, c.B * c.H, st);
+}
+
+template <typename T>
+void launch_haar(const wersa_desc &c, const T *x, View vin, float *y, const float *filt,
+                 hipStream_t st) {
+  dim3 grid((c.n + kTileRows - 1) / kTileRows, (c.d + kTileCols - 1) / kTileCols, c.B * c.H);
+  haar_filter_kernel<T, float><<<grid, 256, 0, st>>>(x, vin, y, contiguous_view(c.n, c.d), filt,
+                                                     nullptr, 0.f, c.n, c.d, c.L);
+}
+
+template <typename T>
+wersa_status forward_t(const wersa_desc &c, const T *q, const T *k, const T *v, const T *omega_rf,
+                       const float *sigma, const float *gate_w, const float *gate_b,
+                       const float *scale_w, T *out, float *saved, float *ws, hipStream_t st) {
+  const GenericWs w = plan(c, 0, ws);
+  const SavedLayout sv = saved_layout(c);
+  const int slices = c.B * c.H;
+  const View tv{c.stride_b, c.stride_h, c.stride_n, c.H};
+  const int64_t nd = (int64_t)slices * c.n * c.d;
+  float *S = saved + sv.S, *z = saved + sv.z, *qbar = saved + sv.qbar, *s = saved + sv.s,
+        *F = saved + sv.F, *D = saved + sv.D;
+
+  scalars_kernel<<<1, 64, 0, st>>>(sigma, c.bw_floor, c.m, w.scalars);
+  // step 4: pooled query and gate
+  launch_colsum<T>(q, tv, slices, c.n, c.d, nullptr, w.qpart, nullptr, 1.f, st);
+  gate_fwd_kernel<<<slices, 64, 0, st>>>(w.qpart, colsum_chunks(c.n), c.n, c.d, c.L, c.H, gate_w,
+                                         gate_b, scale_w, qbar, s, F);
+  // steps 3, 5, 6: gated Haar filter of Q and K
+  launch_haar<T>(c, q, tv, w.QF, F, st);
+  launch_haar<T>(c, k, tv, w.KF, F, st);
+  gather_f32_kernel<T><<<ew_blocks(nd), 256, 0, st>>>(v, tv, c.n, c.d, nd, w.Vf);
+  gather_f32_kernel<T><<<ew_blocks((int64_t)c.d * c.m), 256, 0, st>>>(
+      omega_rf, contiguous_view(c.d, c.m), c.d, c.m, (int64_t)c.d * c.m, w.Of);
+  // step 7 on K, then S = Phi_K^T V and z = Phi_K^T 1
+  launch_features(c, w.KF, w, st);
+  launch_phiT_times(c, w.Vf, w, S, st);
+  launch_colsum<float>(w.Phi, contiguous_view(c.n, c.m), slices, c.n, c.m, nullptr, w.zpart, z, 1.f, st);
+  // step 7 on Q, then step 8
+  launch_features(c, w.QF, w, st);
+  launch_rows_gemm(c, w.Phi, c.m, S, c.d, 1, (int64_t)c.m * c.d, c.d, w.Nbuf, st);
+  rowdot_kernel<<<dim3((c.n + 3) / 4, slices), 256, 0, st>>>(w.Phi, z, c.n, c.m, c.eps, D);
+  scatter_kernel<T><<<ew_blocks(nd), 256, 0, st>>>(w.Nbuf, D, out, tv, c.n, c.d, nd);
+  return hipGetLastError() == hipSuccess ? WERSA_OK : WERSA_ERR_LAUNCH;
+}
+
+template <typename T>
+wersa_status backward_t(const wersa_desc &c, const T *q, const T *k, const T *v, const T *omega_rf,
+                        const float *sigma, const float *gate_w, const float *gate_b,
+                        const float *scale_w, const T *out, const T *dout, const float *saved,
+                        T *dq, T *dk, T *dv, float *dgate_w, float *dgate_b, float *dscale_w,
+                        float *dsigma, float *ws, hipStream_t st) {
+  (void)gate_b;
+  const GenericWs w = plan(c, 1, ws);
+  const SavedLayout sv = saved_layout(c);
+  const int slices = c.B * c.H;
+  const View tv{c.stride_b, c.stride_h, c.stride_n, c.H};
+  const View cv = contiguous_view(c.n, c.d);
+  const int64_t nd = (int64_t)slices * c.n * c.d, nm = (int64_t)slices * c.n * c.m;
+  const float *S = saved + sv.S, *z = saved + sv.z, *qbar = saved + sv.qbar, *s = saved + sv.s,
+              *F = saved + sv.F, *D = saved + sv.D;
+  const int64_t md = (int64_t)c.m * c.d;
+
+  scalars_kernel<<<1, 64, 0, st>>>(sigma, c.bw_floor, c.m, w.scalars);
+  launch_haar<T>(c, q, tv, w.QF, F, st);
+  launch_haar<T>(c, k, tv, w.KF, F, st);
+  gather_f32_kernel<T><<<ew_blocks(nd), 256, 0, st>>>(v, tv, c.n, c.d, nd, w.Vf);
+  gather_f32_kernel<T><<<ew_blocks((int64_t)c.d * c.m), 256, 0, st>>>(
+      omega_rf, contiguous_view(c.d, c.m), c.d, c.m, (int64_t)c.d * c.m, w.Of);
+  // O = N / D
+  prep_dn_kernel<T><<<dim3((c.n + 3) / 4, slices), 256, 0, st>>>(dout, out, tv, D, c.n, c.d, w.dN, w.dD);
+  {  // sum of dD over everything, for d sigma
+    const int chunks = colsum_chunks(c.n), rows = (c.n + chunks - 1) / chunks;
+    colsum_partial_kernel<float><<<dim3(chunks, slices), 256, 0, st>>>(
+        w.dD, contiguous_view(c.n, 1), c.n, 1, rows, nullptr, w.dDpart);
+  }
+  // Q side: dPhi_Q = dN S^T + dD z^T ; dS = Phi_Q^T dN ; dz = Phi_Q^T dD
+  launch_features(c, w.QF, w, st);
+  launch_rows_gemm(c, w.dN, c.d, S, 1, c.d, md, c.m, w.R, st);
+  launch_phiT_times(c, w.dN, w, w.dS, st);
+  launch_colsum<float>(w.Phi, contiguous_view(c.n, c.m), slices, c.n, c.m, w.dD, w.zpart, w.dz, 1.f, st);
+  mask_scale_kernel<<<ew_blocks(nm), 256, 0, st>>>(w.R, w.Phi, w.dD, z, w.scalars, c.n, c.m, nm);
+  // dQ_F = dU_Q Omega^T / sigma_eff (scale folded into R); reuse QF's buffer for the result
+  launch_rows_gemm(c, w.R, c.m, w.Of, 1, c.m, 0, c.d, w.QF, st);
+  // K side: dPhi_K = V dS^T + 1 dz^T ; dV = Phi_K dS
+  launch_features(c, w.KF, w, st);
+  launch_rows_gemm(c, w.Vf, c.d, w.dS, 1, c.d, md, c.m, w.R, st);
+  mask_scale_kernel<<<ew_blocks(nm), 256, 0, st>>>(w.R, w.Phi, nullptr, w.dz, w.scalars, c.n, c.m, nm);
+  launch_rows_gemm(c, w.Phi, c.m, w.dS, c.d, 1, md, c.d, w.dVf, st);
+  scatter_kernel<T><<<ew_blocks(nd), 256, 0, st>>>(w.dVf, nullptr, dv, tv, c.n, c.d, nd);
+  launch_rows_gemm(c, w.R, c.m, w.Of, 1, c.m, 0, c.d, w.KF, st);
+  // wavelet stage backward: dF from band inner products, then dX = G_F dX_F
+  dim3 tgrid((c.n + kTileRows - 1) / kTileRows, (c.d + kTileCols - 1) / kTileCols, slices);
+  const int64_t tiles = (int64_t)tgrid.x * tgrid.y;
+  band_dots_kernel<T><<<tgrid, 256, 0, st>>>(q, tv, w.QF, cv, c.n, c.d, c.L, w.partQ);
+  band_dots_kernel<T><<<tgrid, 256, 0, st>>>(k, tv, w.KF, cv, c.n, c.d, c.L, w.partK);
+  gate_bwd_slice_kernel<<<slices, 64, 0, st>>>(w.partQ, w.partK, tiles, c.L, c.d, c.H, s, gate_w,
+                                               scale_w, w.dF, w.dlogit, w.dqbar);
+  gate_bwd_params_kernel<<<1, 256, 0, st>>>(w.dF, w.dlogit, s, qbar, w.dDpart,
+                                            slices * colsum_chunks(c.n), c.B, c.H, c.L, c.d, c.eps,
+                                            w.scalars, dgate_w, dgate_b, dscale_w, dsigma);
+  haar_filter_kernel<float, T><<<tgrid, 256, 0, st>>>(w.QF, cv, dq, tv, F, w.dqbar, 1.0f / (float)c.n,
+                                                      c.n, c.d, c.L);
+  haar_filter_kernel<float, T><<<tgrid, 256, 0, st>>>(w.KF, cv, dk, tv, F, nullptr, 0.f, c.n, c.d, c.L);
+  return hipGetLastError() == hipSuccess ? WERSA_OK : WERSA_ERR_LAUNCH;
+}
+
+}  // namespace
+
+size_t generic_workspace_bytes(const wersa_desc &c, int for_backward) {
+  return (size_t)plan(c, for_backward, nullptr).total * sizeof(float);
+}
+
+wersa_status generic_forward(const wersa_desc &c, const void *q, const void *k, const void *v,
+                             const void *omega_rf, const float *sigma, const float *gate_w,
+                             const float *gate_b, const float *scale_w, void *out, float *saved,
+                             float *ws, hipStream_t st) {
+  if (c.dtype == WERSA_F32)
+    return forward_t<float>(c, (const float *)q, (const float *)k, (const float *)v,
+                            (const float *)omega_rf, sigma, gate_w, gate_b, scale_w, (float *)out,
+                            saved, ws, st);
+  return forward_t<bf16_t>(c, (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,
+                           (const bf16_t *)omega_rf, sigma, gate_w, gate_b, scale_w, (bf16_t *)out,
+                           saved, ws, st);
+}
+
+wersa_status generic_backward(const wersa_desc &c, const void *q, const void *k, const void *v,
+                              const void *omega_rf, const float *sigma, const float *gate_w,
+                              const float *gate_b, const float *scale_w, const void *out,
+                              const void *dout, const float *saved, void *dq, void *dk, void *dv,
+                              float *dgate_w, float *dgate_b, float *dscale_w, float *dsigma,
+                              float *ws, hipStream_t st) {
+  if (c.dtype == WERSA_F32)
+    return backward_t<float>(c, (const float *)q, (const float *)k, (const float *)v,
+                             (const float *)omega_rf, sigma, gate_w, gate_b, scale_w,
+                             (const float *)out, (const float *)dout, saved, (float *)dq,
+                             (float *)dk, (float *)dv, dgate_w, dgate_b, dscale_w, dsigma, ws, st);
+  return backward_t<bf16_t>(c, (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,
+                            (const bf16_t *)omega_rf, sigma, gate_w, gate_b, scale_w,
+                            (const bf16_t *)out, (const bf16_t *)dout, saved, (bf16_t *)dq,
+                            (bf16_t *)dk, (bf16_t *)dv, dgate_w, dgate_b, dscale_w, dsigma, ws, st);
+}
+
+wersa_status generic_haar_filter(const wersa_desc &c, const void *x, const float *filt, void *xf,
+                                 hipStream_t st) {
+  const View tv{c.stride_b, c.stride_h, c.stride_n, c.H};
+  dim3 grid((c.n + kTileRows - 1) / kTileRows, (c.d + kTileCols - 1) / kTileCols, c.B * c.H);
+  if (c.dtype == WERSA_F32)
+    haar_filter_kernel<float, float><<<grid, 256, 0, st>>>((const float *)x, tv, (float *)xf, tv, filt,
+                                                           nullptr, 0.f, c.n, c.d, c.L);
+  else
+    haar_filter_kernel<bf16_t, bf16_t><<<grid, 256, 0, st>>>((const bf16_t *)x, tv, (bf16_t *)xf, tv,
+                                                             filt, nullptr, 0.f, c.n, c.d, c.L);
+  return hipGetLastError() == hipSuccess ? WERSA_OK : WERSA_ERR_LAUNCH;
+}
+
+}  // namespace wersa

@@ -1,0 +1,80 @@
+// Internal declarations shared by the library's translation units (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/wersa.h"
+
+namespace wersa {
+
+constexpr int kMaxL = 6;
+constexpr int kMaxBands = kMaxL + 1;
+
+// Strided view of a (B, H, n, d) tensor; element (b, h, t, j) at b*sb + h*sh + t*sn + j.
+struct View {
+  int64_t sb, sh, sn;
+  int H;
+  __host__ __device__ int64_t slice_base(int slice) const {
+    return (int64_t)(slice / H) * sb + (int64_t)(slice % H) * sh;
+  }
+};
+
+// ---- bf16 storage helpers (round to nearest even) --------------------------------------
+typedef uint16_t bf16_t;
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t x) {
+  return __uint_as_float(((uint32_t)x) << 16);
+}
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);  // quiet NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+template <typename T> __device__ __forceinline__ float ld(const T *p);
+template <> __device__ __forceinline__ float ld<float>(const float *p) { return *p; }
+template <> __device__ __forceinline__ float ld<bf16_t>(const bf16_t *p) { return bf16_to_f32(*p); }
+template <typename T> __device__ __forceinline__ void st(T *p, float v);
+template <> __device__ __forceinline__ void st<float>(float *p, float v) { *p = v; }
+template <> __device__ __forceinline__ void st<bf16_t>(bf16_t *p, float v) { *p = f32_to_bf16(v); }
+
+// ---- saved-buffer layout (floats) -------------------------------------------------------
+struct SavedLayout {
+  int64_t S, z, qbar, s, F, D, total;
+};
+inline SavedLayout saved_layout(const wersa_desc &c) {
+  SavedLayout o;
+  const int64_t sl = (int64_t)c.B * c.H;
+  auto up = [](int64_t x) { return (x + 63) / 64 * 64; };
+  int64_t off = 0;
+  o.S = off;    off += up(sl * c.m * c.d);
+  o.z = off;    off += up(sl * c.m);
+  o.qbar = off; off += up(sl * c.d);
+  o.s = off;    off += up(sl * (c.L + 1));
+  o.F = off;    off += up(sl * (c.L + 1));
+  o.D = off;    off += up(sl * c.n);
+  o.total = off;
+  return o;
+}
+
+wersa_status validate_desc(const wersa_desc *desc);
+
+// Generic path: float32 arithmetic for every dtype, staged through workspace. Correct for
+// the whole supported range; it is the float32 product path and the fallback for bf16 shapes
+// the MFMA path does not cover.
+size_t generic_workspace_bytes(const wersa_desc &c, int for_backward);
+wersa_status generic_forward(const wersa_desc &c, const void *q, const void *k, const void *v,
+                             const void *omega_rf, const float *sigma, const float *gate_w,
+                             const float *gate_b, const float *scale_w, void *out, float *saved,
+                             float *ws, hipStream_t st);
+wersa_status generic_backward(const wersa_desc &c, const void *q, const void *k, const void *v,
+                              const void *omega_rf, const float *sigma, const float *gate_w,
+                              const float *gate_b, const float *scale_w, const void *out,
+                              const void *dout, const float *saved, void *dq, void *dk, void *dv,
+                              float *dgate_w, float *dgate_b, float *dscale_w, float *dsigma,
+                              float *ws, hipStream_t st);
+wersa_status generic_haar_filter(const wersa_desc &c, const void *x, const float *filt, void *xf,
+                                 hipStream_t st);
+
+}  // namespace wersa

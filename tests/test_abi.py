@@ -1,0 +1,77 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, and turns bad arguments into error codes before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2507_08637_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2507_08637_amd import build
+        build.build()
+    return binding.load_library()
+
+
+def _desc(**kw):
+    from paper_2507_08637_amd.binding import WersaDesc
+    base = dict(B=1, H=2, n=256, d=64, L=3, m=64, dtype=0, eps=1e-6, bw_floor=1e-6,
+                stride_b=2 * 256 * 64, stride_h=256 * 64, stride_n=64)
+    base.update(kw)
+    return WersaDesc(**base)
+
+
+def test_header_symbols_are_exported(lib):
+    with open(os.path.join(ROOT, "include", "wersa.h")) as f:
+        text = f.read()
+    declared = set(re.findall(r"\b(wersa_[a-z_]+)\s*\(", text))
+    assert declared, "no declarations found"
+    from paper_2507_08637_amd import binding
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_sizes_and_status_strings(lib):
+    d = _desc()
+    assert lib.wersa_saved_bytes(ctypes.byref(d)) > 0
+    assert lib.wersa_workspace_bytes(ctypes.byref(d), 1) >= lib.wersa_workspace_bytes(ctypes.byref(d), 0) > 0
+    offs = [lib.wersa_saved_offset(ctypes.byref(d), w) for w in range(6)]
+    assert offs == sorted(offs) and offs[0] == 0
+    assert lib.wersa_saved_offset(ctypes.byref(d), 6) == -1
+    assert lib.wersa_status_string(0) == b"ok"
+    assert lib.wersa_version() >= 100
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(B=0), 1), (dict(n=0), 1), (dict(L=-1), 1), (dict(dtype=7), 1), (dict(bw_floor=0.0), 1),
+    (dict(stride_n=32), 1), (dict(stride_h=0), 1),
+    (dict(n=100, L=3), 2),      # n not a multiple of 2^L
+    (dict(L=7, n=1024), 2), (dict(d=40), 2), (dict(m=72), 2), (dict(d=512, stride_n=512), 2),
+])
+def test_bad_descriptors_are_rejected_before_launch(lib, kw, status):
+    d = _desc(**kw)
+    one = ctypes.c_void_p(256)   # never dereferenced: validation fails first
+    args = [one] * 4 + [one] * 4 + [one, one, one, 1 << 40, None]
+    assert lib.wersa_forward(ctypes.byref(d), *args) == status
+    assert lib.wersa_saved_bytes(ctypes.byref(d)) == 0
+    assert lib.wersa_workspace_bytes(ctypes.byref(d), 0) == 0
+
+
+def test_null_pointers_and_small_workspace(lib):
+    d = _desc()
+    one = ctypes.c_void_p(256)
+    assert lib.wersa_forward(None, *([one] * 11), 1 << 40, None) == 1
+    assert lib.wersa_forward(ctypes.byref(d), None, *([one] * 10), 1 << 40, None) == 1
+    assert lib.wersa_forward(ctypes.byref(d), *([one] * 11), 16, None) == 3          # too small
+    assert lib.wersa_forward(ctypes.byref(d), *([one] * 10), ctypes.c_void_p(264), 1 << 40, None) == 3
+    bw = [one] * 4 + [one] * 4 + [one] * 3 + [one] * 3 + [None] * 4
+    assert lib.wersa_backward(ctypes.byref(d), *bw, one, 16, None) == 3
+    assert lib.wersa_backward(ctypes.byref(d), *([one] * 4 + [one] * 4 + [one, None, one] + [one] * 3 + [None] * 4),
+                              one, 1 << 40, None) == 1
+    assert lib.wersa_haar_filter(ctypes.byref(d), None, one, one, None) == 1

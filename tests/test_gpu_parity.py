@@ -1,0 +1,176 @@
+"""Parity of the HIP path (through the C-ABI) against the float64 oracle on seeded inputs.
+
+Tolerances (relative Frobenius error per output tensor): 1e-4 for float32, 2e-2 for bf16.
+bf16 inputs are rounded once on the host; the oracle consumes those rounded values in float64.
+"""
+import numpy as np
+import pytest
+
+from paper_2507_08637_amd import workloads
+from tests import helpers as hp
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def _check_all(res, ref, tol, names=("O", "dQ", "dK", "dV", "dWg", "dbg", "domega"), where=""):
+    errs = {k: hp.rel_err(res[k], ref[k]) for k in names}
+    print(where, {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+    bad = {k: v for k, v in errs.items() if not v < tol}
+    assert not bad, (where, bad)
+    return errs
+
+
+SMALL = [
+    # multi-tile, ragged tail in n (200 = 3 tiles + 8 rows), d and m not multiples of 64
+    dict(B=2, H=3, n=200, d=48, L=3, m=80),
+    dict(B=1, H=2, n=512, d=64, L=6, m=128),
+    dict(B=2, H=2, n=320, d=128, L=5, m=256),
+    dict(B=1, H=1, n=64, d=64, L=6, m=64),      # a single Haar block
+    dict(B=1, H=2, n=16, d=16, L=4, m=16),      # smallest sizes
+    dict(B=1, H=2, n=96, d=32, L=0, m=32),      # no wavelet levels: F has one entry
+    dict(B=3, H=1, n=256, d=256, L=2, m=48),    # maximum head dim
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", SMALL, ids=lambda s: "B{B}H{H}n{n}d{d}L{L}m{m}".format(**s))
+def test_small_shapes_forward_backward(shape, dtype):
+    cfg = dict(shape, dtype=dtype, flavour="plain", seed_base=4242, q_mean=0.5)
+    p = workloads.make_inputs(**cfg)
+    res = hp.gpu_forward_backward(p, cfg)
+    ref = hp.oracle_backward(p, cfg)
+    _check_all(res, ref, TOL[dtype], where=f"{shape} {dtype}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_saved_stage_tensors(dtype):
+    """q-bar, gate, F, S, z and the normaliser D (steps 4, 7, 8) against the oracle's stages."""
+    cfg = dict(B=2, H=2, n=384, d=64, L=4, m=96, dtype=dtype, flavour="plain", seed_base=99, q_mean=0.3)
+    p = workloads.make_inputs(**cfg)
+    res = hp.gpu_forward_backward(p, cfg, backward=False)
+    ref = hp.oracle_forward(p, cfg)
+    sl = cfg["B"] * cfg["H"]
+    for name in ("qbar", "s", "F", "S", "z", "D"):
+        r = ref[name].reshape((sl,) + ref[name].shape[2:])
+        e = hp.rel_err(res["saved"][name], r)
+        assert e < TOL[dtype], (name, e)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_strided_layout(dtype):
+    """Heads addressed by stride: tensors stored (B, n, H, d), presented as (B, H, n, d)."""
+    cfg = dict(B=2, H=3, n=128, d=32, L=3, m=64, dtype=dtype, flavour="plain", seed_base=7, q_mean=0.5)
+    p = workloads.make_inputs(**cfg)
+    res = hp.gpu_forward_backward(p, cfg, layout="bnhd")
+    ref = hp.oracle_backward(p, cfg)
+    _check_all(res, ref, TOL[dtype], where="strided")
+
+
+def test_dsigma_closed_form_and_floor():
+    """sigma reaches the output only through eps; with a large eps the gradient is measurable.
+    Compared with the oracle's term-by-term chain rule, relative to 2 eps/sigma * sum|dD|."""
+    eps = 1e-2
+    cfg = dict(B=2, H=2, n=256, d=32, L=3, m=64, dtype="f32", flavour="plain", seed_base=11, q_mean=0.5)
+    p = workloads.make_inputs(**cfg)
+    p["sigma"] = np.float32(1.5)
+    res = hp.gpu_forward_backward(p, cfg, eps=eps)
+    ref = hp.oracle_backward(p, cfg, eps=eps)
+    _check_all(res, ref, 1e-4, where="eps=1e-2")
+    got = float(res["dsigma"].cpu()[0])
+    assert abs(got - ref["dsigma"]) < 1e-3 * abs(ref["dsigma"]) + 1e-7, (got, ref["dsigma"])
+    # below the floor the bandwidth is clamped and receives no gradient
+    res2 = hp.gpu_forward_backward(p, cfg, eps=eps, bw_floor=2.0)
+    ref2 = hp.oracle_backward(p, cfg, eps=eps, bw_floor=2.0)
+    assert float(res2["dsigma"].cpu()[0]) == 0.0 and ref2["dsigma"] == 0.0
+    _check_all(res2, ref2, 1e-4, names=("O", "dQ"), where="floor")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_haar_filter_stage(dtype):
+    """The gated Haar stage alone (steps 3, 5, 6) against the oracle's lifting recursion."""
+    import torch
+    from oracle import wersa_oracle as wo
+    from paper_2507_08637_amd import binding
+    B, H, n, d, L = 2, 2, 448, 80, 6
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((B, H, n, d)).astype(np.float32)
+    if dtype == "bf16":
+        x = workloads.round_to_bf16(x)
+    filt = rng.uniform(0.0, 1.5, (B * H, L + 1)).astype(np.float32)
+    xt = torch.from_numpy(x).cuda().to(torch.float32 if dtype == "f32" else torch.bfloat16)
+    y = binding.wersa_haar_filter(xt, torch.from_numpy(filt).cuda(), L)
+    torch.cuda.synchronize()
+    ref = np.stack([wo.haar_filter(x[b, h].astype(np.float64), filt[b * H + h].astype(np.float64), L)
+                    for b in range(B) for h in range(H)]).reshape(B, H, n, d)
+    tol = 1e-6 if dtype == "f32" else 4e-3   # bf16 output rounding: 2^-9 per element
+    assert hp.rel_err(y, ref) < tol
+    # all-ones filter reproduces the input exactly up to float32 rounding of the lifting steps
+    y1 = binding.wersa_haar_filter(xt, torch.ones(B * H, L + 1, device="cuda"), L)
+    assert hp.rel_err(y1, x.astype(np.float64)) < tol
+
+
+def test_rerun_is_bit_identical():
+    """Fixed-order reductions: two runs give identical bits (doubles as a race check)."""
+    import torch
+    cfg = dict(B=2, H=2, n=2048, d=64, L=5, m=128, dtype="bf16", flavour="spikes", seed_base=21, q_mean=0.2)
+    p = workloads.make_inputs(**cfg)
+    a = hp.gpu_forward_backward(p, cfg)
+    b = hp.gpu_forward_backward(p, cfg)
+    for k in ("O", "dQ", "dK", "dV", "dWg", "dbg", "domega", "dsigma"):
+        assert torch.equal(a[k], b[k]), k
+
+
+def test_unsupported_shape_raises_without_launch():
+    import torch
+    from paper_2507_08637_amd import binding
+    q = torch.zeros(1, 1, 100, 64, device="cuda")
+    om = torch.zeros(64, 64, device="cuda")
+    one = torch.ones(1, device="cuda")
+    with pytest.raises(binding.WersaError) as e:
+        binding.wersa_forward(q, q, q, om, one, torch.zeros(1, 4, 64, device="cuda"),
+                              torch.zeros(1, 4, device="cuda"), torch.ones(4, device="cuda"), 3)
+    assert e.value.status == 2
+
+
+# ------------------------------------------------------------------ benchmark configurations
+def test_config1_tiny_fp32():
+    cfg, p = workloads.make_config(1, backward=True)
+    res = hp.gpu_forward_backward(p, cfg)
+    ref = hp.oracle_backward(p, cfg)
+    _check_all(res, ref, 1e-4, where="config1")
+
+
+def test_config2_bf16_forward():
+    cfg, p = workloads.make_config(2)
+    res = hp.gpu_forward_backward(p, cfg, backward=False)
+    ref = hp.oracle_forward(p, cfg, keep=("O",))
+    assert hp.rel_err(res["O"], ref["O"]) < 2e-2
+
+
+def _sampled_slices_check(idx, slices, reduced):
+    """Full-size GPU run; the oracle recomputes a sample of (b, h) slices in full (slices are
+    independent for O, dQ, dK, dV).  Parameter gradients, which sum over slices, are checked on
+    a run restricted to `reduced` batch/heads with the same n, d, m, L."""
+    cfg, p = workloads.make_config(idx)
+    res = hp.gpu_forward_backward(p, cfg)
+    ref = hp.oracle_backward(p, cfg, slices=slices)
+    for (b, h) in slices:
+        for name in ("O", "dQ", "dK", "dV"):
+            e = hp.rel_err(res[name][b, h], ref[name][b, h])
+            print(f"config{idx} slice {(b, h)} {name} {e:.2e}", flush=True)
+            assert e < 2e-2, (name, b, h, e)
+    del res, ref, p
+    cfg2, p2 = workloads.make_config(idx, **reduced)
+    res2 = hp.gpu_forward_backward(p2, cfg2)
+    ref2 = hp.oracle_backward(p2, cfg2)
+    _check_all(res2, ref2, 2e-2, where=f"config{idx} reduced {reduced}")
+
+
+def test_config3_spikes_forward_backward():
+    _sampled_slices_check(3, [(0, 0), (3, 11)], dict(B=1, H=3))
+
+
+def test_config4_long_sequence_forward_backward():
+    _sampled_slices_check(4, [(0, 5)], dict(B=1, H=2))
