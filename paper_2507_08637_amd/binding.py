@@ -164,7 +164,7 @@ def wersa_forward(q, k, v, omega_rf, sigma, gate_w, gate_b, scale_w, L, eps=1e-6
 
 def _probe(desc):
     # wersa_saved_bytes returned 0: ask the forward entry point for the precise status
-    return load_library().wersa_forward(ctypes.byref(desc), *([None] * 12), 0, None)
+    return load_library().wersa_forward(ctypes.byref(desc), *([None] * 11), 0, None)
 
 
 def wersa_backward(q, k, v, omega_rf, sigma, gate_w, gate_b, scale_w, out, dout, saved, L,
