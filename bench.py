@@ -1,0 +1,161 @@
+#!/usr/bin/env python3
+"""Benchmark: WERSA attention forward + backward tokens/s on one MI355X at n = 131072.
+
+One step = one wersa_forward + one wersa_backward (every step of the hot path) over the
+synthetic long-sequence workload (configuration 4: B=1, H=8, n=131072, d=64, L=6, m=256, bf16),
+with inputs resident in HBM.  Prints ONE JSON line with the whole-job throughput, the roofline
+figure of the dominant kernel (HIP-event timing inside the timed region) and the float64 CPU
+oracle timed on the host cores on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK = {"hbm": (8000.0, "GB/s"), "mfma_bf16": (2500.0, "TFLOP/s"), "fp32": (157.3, "TFLOP/s")}
+
+
+def kernel_models(cfg):
+    """Algorithmic work of ONE launch of each kernel: name -> (bound, peak key, work, unit scale).
+
+    Contractions: flops = 2 n d m per slice per contraction; a fused kernel counts every
+    contraction it performs.  Memory-bound kernels: the bytes the step must move (inputs read
+    once, outputs written once), never the intermediate feature matrices."""
+    sl = cfg["B"] * cfg["H"]
+    n, d, m = cfg["n"], cfg["d"], cfg["m"]
+    e = 2 if cfg["dtype"] == "bf16" else 4
+    unit = 2.0 * n * d * m * sl          # one n x d x m contraction over all slices
+    nd = float(n) * d * sl
+    models = {
+        # generic (float32 arithmetic) path
+        "gemm_features": ("alu", "fp32", unit), "gemm_phiT": ("alu", "fp32", unit),
+        "gemm_rows": ("alu", "fp32", unit),
+        "haar_filter_kernel": ("hbm", "hbm", nd * (e + 4)),
+        "colsum_partial_kernel": ("hbm", "hbm", nd * e),
+        # fused MFMA path
+        "wersa_qbar": ("hbm", "hbm", nd * e),
+        "wersa_kside_fwd": ("mfma", "mfma_bf16", 2 * unit),
+        "wersa_qside_fwd": ("mfma", "mfma_bf16", 2 * unit),
+        "wersa_qside_bwd": ("mfma", "mfma_bf16", 5 * unit),
+        "wersa_kside_bwd": ("mfma", "mfma_bf16", 4 * unit),
+    }
+    return models
+
+
+def cpu_baseline(cfg, p, budget_s=12.0):
+    """Time the oracle (as it stands) slice by slice until the budget is spent."""
+    import numpy as np
+    from oracle import wersa_oracle as wo
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count()
+    done, t0 = 0, time.perf_counter()
+    todo = [(b, h) for b in range(cfg["B"]) for h in range(cfg["H"])]
+    for (b, h) in todo:
+        wo.backward(p["Q"], p["K"], p["V"], p["Omega"], float(p["sigma"]), p["Wg"], p["bg"], p["omega"],
+                    cfg["L"], p["dO"], slices=[(b, h)])
+        done += 1
+        if time.perf_counter() - t0 > budget_s:
+            break
+    dt = time.perf_counter() - t0
+    tokens = cfg["B"] * cfg["n"] * done / len(todo)
+    return {"value": tokens / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{done} of {len(todo)} (batch, head) slices of the same workload, forward+backward, "
+                      f"float64 NumPy, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=4, help="workload configuration (1-4)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-events", action="store_true", help="do not bracket kernels with HIP events")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2507_08637_amd import binding, workloads
+    from tests.helpers import to_device
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    binding.load_library()
+    cfg, p = workloads.make_config(args.config, backward=True)
+    t = to_device(p, cfg["dtype"])
+    L = cfg["L"]
+    desc = binding.make_desc(t["Q"], L, cfg["m"])
+    saved, ws_f = binding.alloc_like(desc, t["Q"], 0)
+    _, ws_b = binding.alloc_like(desc, t["Q"], 1)
+    out = torch.empty_like(t["Q"])
+    grads = None
+
+    def step():
+        nonlocal grads
+        binding.wersa_forward(t["Q"], t["K"], t["V"], t["Omega"], t["sigma"], t["Wg"], t["bg"], t["omega"], L,
+                              out=out, saved=saved, workspace=ws_f)
+        grads = binding.wersa_backward(t["Q"], t["K"], t["V"], t["Omega"], t["sigma"], t["Wg"], t["bg"],
+                                       t["omega"], out, t["dO"], saved, L, workspace=ws_b, grads=grads)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    binding.wersa_profile_enable(not args.no_events)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = binding.wersa_profile_collect()
+    binding.wersa_profile_enable(False)
+
+    ms = (t1 - t0) * 1e3 / args.steps
+    tokens = cfg["B"] * cfg["n"]
+    path = binding.wersa_path_name(desc) if hasattr(binding, "wersa_path_name") else "generic"
+    rec = {
+        "metric": "WERSA attention fwd+bwd tokens/s on 1 GPU at n=131072; % HBM/MFMA roofline",
+        "value": tokens / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32" if path == "generic" or cfg["dtype"] == "f32" else "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"config{args.config}: B={cfg['B']} H={cfg['H']} n={cfg['n']} d={cfg['d']} "
+                               f"L={cfg['L']} m={cfg['m']} {cfg['dtype']} storage, {cfg['flavour']} inputs, "
+                               "forward+backward", "path": path},
+    }
+    roof = None
+    if prof:
+        models = kernel_models(cfg)
+        name = max(prof, key=lambda k: prof[k][0])
+        tot_ms, launches = prof[name]
+        avg_ms = tot_ms / launches
+        if name in models:
+            bound, pk, work = models[name]
+            peak, unit = PEAK[pk]
+            achieved = work / (avg_ms * 1e-3) / (1e9 if unit == "GB/s" else 1e12)
+            roof = {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
+                    "frac": achieved / peak, "traffic": None, "kernel": name,
+                    "avg_launch_ms": avg_ms, "launches_per_step": launches / args.steps}
+        rec["kernels_ms_per_step"] = {k: round(v[0] / args.steps, 4) for k, v in
+                                      sorted(prof.items(), key=lambda kv: -kv[1][0])}
+    rec["roofline"] = roof
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline(cfg, p)
+    else:
+        rec["cpu_baseline"] = None
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()

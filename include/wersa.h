@@ -33,7 +33,8 @@
  *     `workspace` is scratch, at least wersa_workspace_bytes; both 256-byte aligned.
  *   - All argument validation happens before anything is enqueued; on error nothing is
  *     launched. No exception or abort crosses the boundary.
- *   - No mutable global state: calls on different streams with different buffers may overlap.
+ *   - No mutable global state apart from the optional profiling switch below: calls on
+ *     different streams with different buffers may overlap.
  *   - Results are deterministic: reductions use fixed-order two-pass sums, no float atomics.
  */
 #ifndef WERSA_H
@@ -106,6 +107,19 @@ wersa_status wersa_haar_filter(const wersa_desc *desc, const void *x, const floa
  * which = 0 S [B*H][m][d], 1 z [B*H][m], 2 qbar [B*H][d], 3 gate sigmoid s [B*H][L+1],
  * 4 F [B*H][L+1], 5 D [B*H][n]. Returns -1 on a bad argument. */
 int64_t wersa_saved_offset(const wersa_desc *desc, int which);
+
+/*
+ * Optional per-kernel timing for benchmarks and tools (off by default; the only mutable
+ * library state, not thread-safe). While enabled, each kernel launch is bracketed by a HIP
+ * event pair on the caller's stream. wersa_profile_collect waits for the recorded events,
+ * sums the elapsed time per kernel name, clears the recording and returns the number of
+ * distinct names; wersa_profile_get copies entry `index` (0 on success, 1 on bad argument).
+ */
+void wersa_profile_enable(int on);
+void wersa_profile_reset(void);
+int32_t wersa_profile_collect(void);
+int32_t wersa_profile_get(int32_t index, char *name, int32_t name_len, double *total_ms,
+                          int32_t *launches);
 
 const char *wersa_status_string(wersa_status status);
 

@@ -15,7 +15,8 @@ LIB_PATH = os.path.join(_HERE, "libwersa.so")
 
 WERSA_F32, WERSA_BF16 = 0, 1
 EXPORTS = ["wersa_workspace_bytes", "wersa_saved_bytes", "wersa_forward", "wersa_backward",
-           "wersa_haar_filter", "wersa_saved_offset", "wersa_status_string", "wersa_version"]
+           "wersa_haar_filter", "wersa_saved_offset", "wersa_status_string", "wersa_version",
+           "wersa_profile_enable", "wersa_profile_reset", "wersa_profile_collect", "wersa_profile_get"]
 
 
 class WersaDesc(ctypes.Structure):
@@ -62,6 +63,15 @@ def load_library():
     lib.wersa_status_string.argtypes = [ctypes.c_int]
     lib.wersa_version.restype = ctypes.c_int32
     lib.wersa_version.argtypes = []
+    lib.wersa_profile_enable.restype = None
+    lib.wersa_profile_enable.argtypes = [ctypes.c_int]
+    lib.wersa_profile_reset.restype = None
+    lib.wersa_profile_reset.argtypes = []
+    lib.wersa_profile_collect.restype = ctypes.c_int32
+    lib.wersa_profile_collect.argtypes = []
+    lib.wersa_profile_get.restype = ctypes.c_int32
+    lib.wersa_profile_get.argtypes = [ctypes.c_int32, ctypes.c_char_p, ctypes.c_int32,
+                                      ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)]
     _lib = lib
     return lib
 
@@ -168,15 +178,24 @@ def _probe(desc):
 
 
 def wersa_backward(q, k, v, omega_rf, sigma, gate_w, gate_b, scale_w, out, dout, saved, L,
-                   eps=1e-6, bw_floor=1e-6, workspace=None, stream=None, param_grads=True):
-    """Returns dict(dq, dk, dv, dgate_w, dgate_b, dscale_w, dsigma)."""
+                   eps=1e-6, bw_floor=1e-6, workspace=None, stream=None, param_grads=True, grads=None):
+    """Returns dict(dq, dk, dv, dgate_w, dgate_b, dscale_w, dsigma).
+
+    `grads` may be a dict from an earlier call: its tensors are then overwritten in place."""
     lib = load_library()
     _same_layout(q, k, v, out, dout)
     desc = make_desc(q, L, omega_rf.shape[1], eps, bw_floor)
-    dq = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
-    dk = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
-    dv = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
-    if param_grads:
+    if grads is not None:
+        dq, dk, dv = grads["dq"], grads["dk"], grads["dv"]
+        _same_layout(q, dq, dk, dv)
+        dgw, dgb, dsw, dsg = grads["dgate_w"], grads["dgate_b"], grads["dscale_w"], grads["dsigma"]
+    else:
+        dq = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+        dk = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+        dv = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+    if grads is not None:
+        pass
+    elif param_grads:
         dgw = torch.empty_like(gate_w)
         dgb = torch.empty_like(gate_b)
         dsw = torch.empty_like(scale_w)
@@ -202,4 +221,23 @@ def wersa_haar_filter(x, filt, L, out=None, stream=None):
     if out is None:
         out = torch.empty_strided(x.shape, x.stride(), dtype=x.dtype, device=x.device)
     _check(lib.wersa_haar_filter(ctypes.byref(desc), _ptr(x), _ptr(filt), _ptr(out), _stream(stream)))
+    return out
+
+
+def wersa_profile_enable(on):
+    lib = load_library()
+    lib.wersa_profile_reset()
+    lib.wersa_profile_enable(int(bool(on)))
+
+
+def wersa_profile_collect():
+    """{kernel name: (total_ms, launches)} for everything recorded since the last collect."""
+    lib = load_library()
+    cnt = lib.wersa_profile_collect()
+    out = {}
+    buf = ctypes.create_string_buffer(128)
+    ms, launches = ctypes.c_double(), ctypes.c_int32()
+    for i in range(cnt):
+        if lib.wersa_profile_get(i, buf, 128, ctypes.byref(ms), ctypes.byref(launches)) == 0:
+            out[buf.value.decode()] = (ms.value, launches.value)
     return out

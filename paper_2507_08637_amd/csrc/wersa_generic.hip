@@ -507,14 +507,14 @@ void launch_colsum(const T *x, View v, int slices, int n, int W, const float *wt
                    float *out, float scale, hipStream_t st) {
   const int chunks = colsum_chunks(n);
   const int rows = (n + chunks - 1) / chunks;
-  colsum_partial_kernel<T><<<dim3(chunks, slices), 256, 0, st>>>(x, v, n, W, rows, wt, part);
+  WERSA_STAGE("colsum_partial_kernel", st, colsum_partial_kernel<T><<<dim3(chunks, slices), 256, 0, st>>>(x, v, n, W, rows, wt, part));
   if (out)
-    reduce_partials_kernel<<<dim3((W + 255) / 256, slices), 256, 0, st>>>(part, chunks, W, scale, out);
+    WERSA_STAGE("reduce_partials_kernel", st, reduce_partials_kernel<<<dim3((W + 255) / 256, slices), 256, 0, st>>>(part, chunks, W, scale, out));
 }
 
-void launch_gemm(GemmArgs a, int batch, hipStream_t st) {
+void launch_gemm(GemmArgs a, int batch, hipStream_t st, const char *name) {
   dim3 grid((a.N + 63) / 64, (a.M + 63) / 64, batch * a.splits);
-  gemm_kernel<<<grid, 256, 0, st>>>(a);
+  WERSA_STAGE(name, st, gemm_kernel<<<grid, 256, 0, st>>>(a));
 }
 
 // Phi = ReLU(XF Omega) * c
@@ -525,7 +525,7 @@ void launch_features(const wersa_desc &c, const float *XF, const GenericWs &w, h
   a.sAi = c.d; a.sAk = 1; a.sBk = c.m; a.sBj = 1; a.ldc = c.m;
   a.bsA = (int64_t)c.n * c.d; a.bsB = 0; a.bsC = (int64_t)c.n * c.m;
   a.splits = 1; a.splitC = 0; a.alpha = w.scalars; a.relu = 1;
-  launch_gemm(a, c.B * c.H, st);
+  launch_gemm(a, c.B * c.H, st, "gemm_features");
 }
 // out[slice] (m x d) = Phi[slice]^T Y[slice], reduced over n by split partials
 void launch_phiT_times(const wersa_desc &c, const float *Y, const GenericWs &w, float *out,
@@ -537,9 +537,9 @@ void launch_phiT_times(const wersa_desc &c, const float *Y, const GenericWs &w, 
   a.sAi = 1; a.sAk = c.m; a.sBk = c.d; a.sBj = 1; a.ldc = c.d;
   a.bsA = (int64_t)c.n * c.m; a.bsB = (int64_t)c.n * c.d; a.bsC = (int64_t)splits * c.m * c.d;
   a.splits = splits; a.splitC = (int64_t)c.m * c.d; a.alpha = nullptr; a.relu = 0;
-  launch_gemm(a, slices, st);
+  launch_gemm(a, slices, st, "gemm_phiT");
   const int64_t W = (int64_t)c.m * c.d;
-  reduce_partials_kernel<<<dim3((unsigned)((W + 255) / 256), slices), 256, 0, st>>>(w.Spart, splits, W, 1.0f, out);
+  WERSA_STAGE("reduce_partials_kernel", st, reduce_partials_kernel<<<dim3((unsigned)((W + 255) / 256), slices), 256, 0, st>>>(w.Spart, splits, W, 1.0f, out));
 }
 // C[slice] (n x N) = A[slice] (n x K) * op(B[slice]); B given by strides
 void launch_rows_gemm(const wersa_desc &c, const float *A, int K, const float *B, int64_t sBk,
@@ -550,15 +550,15 @@ void launch_rows_gemm(const wersa_desc &c, const float *A, int K, const float *B
   a.sAi = K; a.sAk = 1; a.sBk = sBk; a.sBj = sBj; a.ldc = N;
   a.bsA = (int64_t)c.n * K; a.bsB = bsB; a.bsC = (int64_t)c.n * N;
   a.splits = 1; a.splitC = 0; a.alpha = nullptr; a.relu = 0;
-  launch_gemm(a, c.B * c.H, st);
+  launch_gemm(a, c.B * c.H, st, "gemm_rows");
 }
 
 template <typename T>
 void launch_haar(const wersa_desc &c, const T *x, View vin, float *y, const float *filt,
                  hipStream_t st) {
   dim3 grid((c.n + kTileRows - 1) / kTileRows, (c.d + kTileCols - 1) / kTileCols, c.B * c.H);
-  haar_filter_kernel<T, float><<<grid, 256, 0, st>>>(x, vin, y, contiguous_view(c.n, c.d), filt,
-                                                     nullptr, 0.f, c.n, c.d, c.L);
+  WERSA_STAGE("haar_filter_kernel", st, haar_filter_kernel<T, float><<<grid, 256, 0, st>>>(x, vin, y, contiguous_view(c.n, c.d), filt,
+                                                     nullptr, 0.f, c.n, c.d, c.L));
 }
 
 template <typename T>
@@ -573,17 +573,17 @@ wersa_status forward_t(const wersa_desc &c, const T *q, const T *k, const T *v, 
   float *S = saved + sv.S, *z = saved + sv.z, *qbar = saved + sv.qbar, *s = saved + sv.s,
         *F = saved + sv.F, *D = saved + sv.D;
 
-  scalars_kernel<<<1, 64, 0, st>>>(sigma, c.bw_floor, c.m, w.scalars);
+  WERSA_STAGE("scalars_kernel", st, scalars_kernel<<<1, 64, 0, st>>>(sigma, c.bw_floor, c.m, w.scalars));
   // step 4: pooled query and gate
   launch_colsum<T>(q, tv, slices, c.n, c.d, nullptr, w.qpart, nullptr, 1.f, st);
-  gate_fwd_kernel<<<slices, 64, 0, st>>>(w.qpart, colsum_chunks(c.n), c.n, c.d, c.L, c.H, gate_w,
-                                         gate_b, scale_w, qbar, s, F);
+  WERSA_STAGE("gate_fwd_kernel", st, gate_fwd_kernel<<<slices, 64, 0, st>>>(w.qpart, colsum_chunks(c.n), c.n, c.d, c.L, c.H, gate_w,
+                                         gate_b, scale_w, qbar, s, F));
   // steps 3, 5, 6: gated Haar filter of Q and K
   launch_haar<T>(c, q, tv, w.QF, F, st);
   launch_haar<T>(c, k, tv, w.KF, F, st);
-  gather_f32_kernel<T><<<ew_blocks(nd), 256, 0, st>>>(v, tv, c.n, c.d, nd, w.Vf);
-  gather_f32_kernel<T><<<ew_blocks((int64_t)c.d * c.m), 256, 0, st>>>(
-      omega_rf, contiguous_view(c.d, c.m), c.d, c.m, (int64_t)c.d * c.m, w.Of);
+  WERSA_STAGE("gather_f32_kernel", st, gather_f32_kernel<T><<<ew_blocks(nd), 256, 0, st>>>(v, tv, c.n, c.d, nd, w.Vf));
+  WERSA_STAGE("gather_f32_kernel", st, gather_f32_kernel<T><<<ew_blocks((int64_t)c.d * c.m), 256, 0, st>>>(
+      omega_rf, contiguous_view(c.d, c.m), c.d, c.m, (int64_t)c.d * c.m, w.Of));
   // step 7 on K, then S = Phi_K^T V and z = Phi_K^T 1
   launch_features(c, w.KF, w, st);
   launch_phiT_times(c, w.Vf, w, S, st);
@@ -591,8 +591,8 @@ wersa_status forward_t(const wersa_desc &c, const T *q, const T *k, const T *v, 
   // step 7 on Q, then step 8
   launch_features(c, w.QF, w, st);
   launch_rows_gemm(c, w.Phi, c.m, S, c.d, 1, (int64_t)c.m * c.d, c.d, w.Nbuf, st);
-  rowdot_kernel<<<dim3((c.n + 3) / 4, slices), 256, 0, st>>>(w.Phi, z, c.n, c.m, c.eps, D);
-  scatter_kernel<T><<<ew_blocks(nd), 256, 0, st>>>(w.Nbuf, D, out, tv, c.n, c.d, nd);
+  WERSA_STAGE("rowdot_kernel", st, rowdot_kernel<<<dim3((c.n + 3) / 4, slices), 256, 0, st>>>(w.Phi, z, c.n, c.m, c.eps, D));
+  WERSA_STAGE("scatter_kernel", st, scatter_kernel<T><<<ew_blocks(nd), 256, 0, st>>>(w.Nbuf, D, out, tv, c.n, c.d, nd));
   return hipGetLastError() == hipSuccess ? WERSA_OK : WERSA_ERR_LAUNCH;
 }
 
@@ -613,47 +613,47 @@ wersa_status backward_t(const wersa_desc &c, const T *q, const T *k, const T *v,
               *F = saved + sv.F, *D = saved + sv.D;
   const int64_t md = (int64_t)c.m * c.d;
 
-  scalars_kernel<<<1, 64, 0, st>>>(sigma, c.bw_floor, c.m, w.scalars);
+  WERSA_STAGE("scalars_kernel", st, scalars_kernel<<<1, 64, 0, st>>>(sigma, c.bw_floor, c.m, w.scalars));
   launch_haar<T>(c, q, tv, w.QF, F, st);
   launch_haar<T>(c, k, tv, w.KF, F, st);
-  gather_f32_kernel<T><<<ew_blocks(nd), 256, 0, st>>>(v, tv, c.n, c.d, nd, w.Vf);
-  gather_f32_kernel<T><<<ew_blocks((int64_t)c.d * c.m), 256, 0, st>>>(
-      omega_rf, contiguous_view(c.d, c.m), c.d, c.m, (int64_t)c.d * c.m, w.Of);
+  WERSA_STAGE("gather_f32_kernel", st, gather_f32_kernel<T><<<ew_blocks(nd), 256, 0, st>>>(v, tv, c.n, c.d, nd, w.Vf));
+  WERSA_STAGE("gather_f32_kernel", st, gather_f32_kernel<T><<<ew_blocks((int64_t)c.d * c.m), 256, 0, st>>>(
+      omega_rf, contiguous_view(c.d, c.m), c.d, c.m, (int64_t)c.d * c.m, w.Of));
   // O = N / D
-  prep_dn_kernel<T><<<dim3((c.n + 3) / 4, slices), 256, 0, st>>>(dout, out, tv, D, c.n, c.d, w.dN, w.dD);
+  WERSA_STAGE("prep_dn_kernel", st, prep_dn_kernel<T><<<dim3((c.n + 3) / 4, slices), 256, 0, st>>>(dout, out, tv, D, c.n, c.d, w.dN, w.dD));
   {  // sum of dD over everything, for d sigma
     const int chunks = colsum_chunks(c.n), rows = (c.n + chunks - 1) / chunks;
-    colsum_partial_kernel<float><<<dim3(chunks, slices), 256, 0, st>>>(
-        w.dD, contiguous_view(c.n, 1), c.n, 1, rows, nullptr, w.dDpart);
+    WERSA_STAGE("colsum_partial_kernel", st, colsum_partial_kernel<float><<<dim3(chunks, slices), 256, 0, st>>>(
+        w.dD, contiguous_view(c.n, 1), c.n, 1, rows, nullptr, w.dDpart));
   }
   // Q side: dPhi_Q = dN S^T + dD z^T ; dS = Phi_Q^T dN ; dz = Phi_Q^T dD
   launch_features(c, w.QF, w, st);
   launch_rows_gemm(c, w.dN, c.d, S, 1, c.d, md, c.m, w.R, st);
   launch_phiT_times(c, w.dN, w, w.dS, st);
   launch_colsum<float>(w.Phi, contiguous_view(c.n, c.m), slices, c.n, c.m, w.dD, w.zpart, w.dz, 1.f, st);
-  mask_scale_kernel<<<ew_blocks(nm), 256, 0, st>>>(w.R, w.Phi, w.dD, z, w.scalars, c.n, c.m, nm);
+  WERSA_STAGE("mask_scale_kernel", st, mask_scale_kernel<<<ew_blocks(nm), 256, 0, st>>>(w.R, w.Phi, w.dD, z, w.scalars, c.n, c.m, nm));
   // dQ_F = dU_Q Omega^T / sigma_eff (scale folded into R); reuse QF's buffer for the result
   launch_rows_gemm(c, w.R, c.m, w.Of, 1, c.m, 0, c.d, w.QF, st);
   // K side: dPhi_K = V dS^T + 1 dz^T ; dV = Phi_K dS
   launch_features(c, w.KF, w, st);
   launch_rows_gemm(c, w.Vf, c.d, w.dS, 1, c.d, md, c.m, w.R, st);
-  mask_scale_kernel<<<ew_blocks(nm), 256, 0, st>>>(w.R, w.Phi, nullptr, w.dz, w.scalars, c.n, c.m, nm);
+  WERSA_STAGE("mask_scale_kernel", st, mask_scale_kernel<<<ew_blocks(nm), 256, 0, st>>>(w.R, w.Phi, nullptr, w.dz, w.scalars, c.n, c.m, nm));
   launch_rows_gemm(c, w.Phi, c.m, w.dS, c.d, 1, md, c.d, w.dVf, st);
-  scatter_kernel<T><<<ew_blocks(nd), 256, 0, st>>>(w.dVf, nullptr, dv, tv, c.n, c.d, nd);
+  WERSA_STAGE("scatter_kernel", st, scatter_kernel<T><<<ew_blocks(nd), 256, 0, st>>>(w.dVf, nullptr, dv, tv, c.n, c.d, nd));
   launch_rows_gemm(c, w.R, c.m, w.Of, 1, c.m, 0, c.d, w.KF, st);
   // wavelet stage backward: dF from band inner products, then dX = G_F dX_F
   dim3 tgrid((c.n + kTileRows - 1) / kTileRows, (c.d + kTileCols - 1) / kTileCols, slices);
   const int64_t tiles = (int64_t)tgrid.x * tgrid.y;
-  band_dots_kernel<T><<<tgrid, 256, 0, st>>>(q, tv, w.QF, cv, c.n, c.d, c.L, w.partQ);
-  band_dots_kernel<T><<<tgrid, 256, 0, st>>>(k, tv, w.KF, cv, c.n, c.d, c.L, w.partK);
-  gate_bwd_slice_kernel<<<slices, 64, 0, st>>>(w.partQ, w.partK, tiles, c.L, c.d, c.H, s, gate_w,
-                                               scale_w, w.dF, w.dlogit, w.dqbar);
-  gate_bwd_params_kernel<<<1, 256, 0, st>>>(w.dF, w.dlogit, s, qbar, w.dDpart,
+  WERSA_STAGE("band_dots_kernel", st, band_dots_kernel<T><<<tgrid, 256, 0, st>>>(q, tv, w.QF, cv, c.n, c.d, c.L, w.partQ));
+  WERSA_STAGE("band_dots_kernel", st, band_dots_kernel<T><<<tgrid, 256, 0, st>>>(k, tv, w.KF, cv, c.n, c.d, c.L, w.partK));
+  WERSA_STAGE("gate_bwd_slice_kernel", st, gate_bwd_slice_kernel<<<slices, 64, 0, st>>>(w.partQ, w.partK, tiles, c.L, c.d, c.H, s, gate_w,
+                                               scale_w, w.dF, w.dlogit, w.dqbar));
+  WERSA_STAGE("gate_bwd_params_kernel", st, gate_bwd_params_kernel<<<1, 256, 0, st>>>(w.dF, w.dlogit, s, qbar, w.dDpart,
                                             slices * colsum_chunks(c.n), c.B, c.H, c.L, c.d, c.eps,
-                                            w.scalars, dgate_w, dgate_b, dscale_w, dsigma);
-  haar_filter_kernel<float, T><<<tgrid, 256, 0, st>>>(w.QF, cv, dq, tv, F, w.dqbar, 1.0f / (float)c.n,
-                                                      c.n, c.d, c.L);
-  haar_filter_kernel<float, T><<<tgrid, 256, 0, st>>>(w.KF, cv, dk, tv, F, nullptr, 0.f, c.n, c.d, c.L);
+                                            w.scalars, dgate_w, dgate_b, dscale_w, dsigma));
+  WERSA_STAGE("haar_filter_kernel", st, haar_filter_kernel<float, T><<<tgrid, 256, 0, st>>>(w.QF, cv, dq, tv, F, w.dqbar, 1.0f / (float)c.n,
+                                                      c.n, c.d, c.L));
+  WERSA_STAGE("haar_filter_kernel", st, haar_filter_kernel<float, T><<<tgrid, 256, 0, st>>>(w.KF, cv, dk, tv, F, nullptr, 0.f, c.n, c.d, c.L));
   return hipGetLastError() == hipSuccess ? WERSA_OK : WERSA_ERR_LAUNCH;
 }
 
@@ -698,11 +698,11 @@ wersa_status generic_haar_filter(const wersa_desc &c, const void *x, const float
   const View tv{c.stride_b, c.stride_h, c.stride_n, c.H};
   dim3 grid((c.n + kTileRows - 1) / kTileRows, (c.d + kTileCols - 1) / kTileCols, c.B * c.H);
   if (c.dtype == WERSA_F32)
-    haar_filter_kernel<float, float><<<grid, 256, 0, st>>>((const float *)x, tv, (float *)xf, tv, filt,
-                                                           nullptr, 0.f, c.n, c.d, c.L);
+    WERSA_STAGE("haar_filter_kernel", st, haar_filter_kernel<float, float><<<grid, 256, 0, st>>>((const float *)x, tv, (float *)xf, tv, filt,
+                                                           nullptr, 0.f, c.n, c.d, c.L));
   else
-    haar_filter_kernel<bf16_t, bf16_t><<<grid, 256, 0, st>>>((const bf16_t *)x, tv, (bf16_t *)xf, tv,
-                                                             filt, nullptr, 0.f, c.n, c.d, c.L);
+    WERSA_STAGE("haar_filter_kernel", st, haar_filter_kernel<bf16_t, bf16_t><<<grid, 256, 0, st>>>((const bf16_t *)x, tv, (bf16_t *)xf, tv,
+                                                             filt, nullptr, 0.f, c.n, c.d, c.L));
   return hipGetLastError() == hipSuccess ? WERSA_OK : WERSA_ERR_LAUNCH;
 }
 

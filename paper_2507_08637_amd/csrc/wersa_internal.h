@@ -60,6 +60,18 @@ inline SavedLayout saved_layout(const wersa_desc &c) {
 
 wersa_status validate_desc(const wersa_desc *desc);
 
+// Optional event timing around kernel launches (see wersa_profile_enable in the header).
+bool profiling();
+void prof_begin(const char *name, hipStream_t st);
+void prof_end(hipStream_t st);
+// Launch `expr` (a kernel launch statement) as stage `name`.
+#define WERSA_STAGE(name, st, ...)  \
+  do {                               \
+    ::wersa::prof_begin(name, st);   \
+    __VA_ARGS__;                     \
+    ::wersa::prof_end(st);           \
+  } while (0)
+
 // Generic path: float32 arithmetic for every dtype, staged through workspace. Correct for
 // the whole supported range; it is the float32 product path and the fallback for bf16 shapes
 // the MFMA path does not cover.
