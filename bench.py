@@ -39,10 +39,13 @@ def kernel_models(cfg):
         "colsum_partial_kernel": ("hbm", "hbm", nd * e),
         # fused MFMA path
         "wersa_qbar": ("hbm", "hbm", nd * e),
-        "wersa_kside_fwd": ("mfma", "mfma_bf16", 2 * unit),
-        "wersa_qside_fwd": ("mfma", "mfma_bf16", 2 * unit),
-        "wersa_qside_bwd": ("mfma", "mfma_bf16", 5 * unit),
-        "wersa_kside_bwd": ("mfma", "mfma_bf16", 4 * unit),
+        "wersa_haar_stage": ("hbm", "hbm", nd * (e + 2)),       # one tensor in (bf16), one out (fp16)
+        "wersa_phiT_contract": ("mfma", "mfma_bf16", 2 * unit),  # projection + Phi^T Y
+        "wersa_rows_fwd": ("mfma", "mfma_bf16", 2 * unit),       # projection + Phi S
+        "wersa_rows_bwd_q": ("mfma", "mfma_bf16", 3 * unit),     # projection, dPhi, dX_F
+        "wersa_rows_bwd_k": ("mfma", "mfma_bf16", 4 * unit),     # projection, dPhi, dX_F, dV
+        "wersa_prep_bwd": ("hbm", "hbm", 2 * nd * e),
+        "wersa_add_pooled": ("hbm", "hbm", 2 * nd * e),
     }
     return models
 
@@ -123,7 +126,7 @@ def main():
 
     ms = (t1 - t0) * 1e3 / args.steps
     tokens = cfg["B"] * cfg["n"]
-    path = binding.wersa_path_name(desc) if hasattr(binding, "wersa_path_name") else "generic"
+    path = binding.wersa_path_name(desc)
     rec = {
         "metric": "WERSA attention fwd+bwd tokens/s on 1 GPU at n=131072; % HBM/MFMA roofline",
         "value": tokens / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,

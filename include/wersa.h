@@ -57,6 +57,12 @@ typedef enum {
 
 typedef enum { WERSA_F32 = 0, WERSA_BF16 = 1 } wersa_dtype;
 
+/* desc.flags bits. By default the library picks the MFMA path (bf16 storage, fp16/bf16 matrix
+ * cores, float32 accumulation) when the shape allows it: dtype bf16, d in {64, 128},
+ * n % 64 == 0, m % 128 == 0, strides multiples of 8 elements; otherwise the generic
+ * float32-arithmetic path. WERSA_FLAG_GENERIC_PATH forces the generic path. */
+#define WERSA_FLAG_GENERIC_PATH 1
+
 /*
  * Problem descriptor (host memory, read during the call only).
  * Supported range: B, H, n >= 1; 0 <= L <= 6 and n % 2^L == 0 (the Haar filter is local to
@@ -70,6 +76,7 @@ typedef struct {
   float eps;             /* epsilon of the normaliser (Section 3.1 step 8)                  */
   float bw_floor;        /* floor of the bandwidth (Algorithm 1: bw = max(beta, floor))     */
   int64_t stride_b, stride_h, stride_n;
+  int32_t flags;         /* 0 or WERSA_FLAG_* bits                                          */
 } wersa_desc;
 
 /* Bytes of scratch needed by wersa_forward (for_backward == 0) or wersa_backward (!= 0).
@@ -102,6 +109,9 @@ wersa_status wersa_backward(const wersa_desc *desc, const void *q, const void *k
  */
 wersa_status wersa_haar_filter(const wersa_desc *desc, const void *x, const float *filt,
                                void *xf, void *hip_stream);
+
+/* 1 if this descriptor runs on the MFMA path, 0 if on the generic path, -1 if rejected. */
+int32_t wersa_selected_path(const wersa_desc *desc);
 
 /* Offsets (in floats) of the pieces inside `saved`, for tests and tools:
  * which = 0 S [B*H][m][d], 1 z [B*H][m], 2 qbar [B*H][d], 3 gate sigmoid s [B*H][L+1],

@@ -14,8 +14,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libwersa.so")
 
 WERSA_F32, WERSA_BF16 = 0, 1
+WERSA_FLAG_GENERIC_PATH = 1
 EXPORTS = ["wersa_workspace_bytes", "wersa_saved_bytes", "wersa_forward", "wersa_backward",
-           "wersa_haar_filter", "wersa_saved_offset", "wersa_status_string", "wersa_version",
+           "wersa_haar_filter", "wersa_saved_offset", "wersa_selected_path", "wersa_status_string", "wersa_version",
            "wersa_profile_enable", "wersa_profile_reset", "wersa_profile_collect", "wersa_profile_get"]
 
 
@@ -24,7 +25,7 @@ class WersaDesc(ctypes.Structure):
                 ("d", ctypes.c_int32), ("L", ctypes.c_int32), ("m", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("eps", ctypes.c_float), ("bw_floor", ctypes.c_float),
                 ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64),
-                ("stride_n", ctypes.c_int64)]
+                ("stride_n", ctypes.c_int64), ("flags", ctypes.c_int32)]
 
 
 class WersaError(RuntimeError):
@@ -50,6 +51,8 @@ def load_library():
     lib.wersa_workspace_bytes.argtypes = [dp, ctypes.c_int]
     lib.wersa_saved_bytes.restype = ctypes.c_size_t
     lib.wersa_saved_bytes.argtypes = [dp]
+    lib.wersa_selected_path.restype = ctypes.c_int32
+    lib.wersa_selected_path.argtypes = [dp]
     lib.wersa_saved_offset.restype = ctypes.c_int64
     lib.wersa_saved_offset.argtypes = [dp, ctypes.c_int]
     lib.wersa_forward.restype = ctypes.c_int
@@ -81,7 +84,11 @@ def _check(status):
         raise WersaError(status, load_library().wersa_status_string(status).decode())
 
 
-def make_desc(x, L, m, eps=1e-6, bw_floor=1e-6):
+def wersa_path_name(desc):
+    return {1: "mfma", 0: "generic"}.get(load_library().wersa_selected_path(ctypes.byref(desc)), "rejected")
+
+
+def make_desc(x, L, m, eps=1e-6, bw_floor=1e-6, flags=0):
     """Descriptor for a (B, H, n, d) tensor x (last dim contiguous)."""
     assert x.dim() == 4 and x.stride(3) == 1, "expect (B, H, n, d) with contiguous last dim"
     B, H, n, d = x.shape
@@ -91,7 +98,7 @@ def make_desc(x, L, m, eps=1e-6, bw_floor=1e-6):
         dt = WERSA_BF16
     else:
         raise TypeError("dtype must be float32 or bfloat16")
-    return WersaDesc(B, H, n, d, L, m, dt, eps, bw_floor, x.stride(0), x.stride(1), x.stride(2))
+    return WersaDesc(B, H, n, d, L, m, dt, eps, bw_floor, x.stride(0), x.stride(1), x.stride(2), flags)
 
 
 def _ptr(t):
@@ -146,11 +153,11 @@ def alloc_like(desc, ref, for_backward):
 
 
 def wersa_forward(q, k, v, omega_rf, sigma, gate_w, gate_b, scale_w, L, eps=1e-6, bw_floor=1e-6,
-                  out=None, saved=None, workspace=None, stream=None):
+                  out=None, saved=None, workspace=None, stream=None, flags=0):
     """Returns (out, saved).  All tensor arguments live on one CUDA device."""
     lib = load_library()
     _same_layout(q, k, v)
-    desc = make_desc(q, L, omega_rf.shape[1], eps, bw_floor)
+    desc = make_desc(q, L, omega_rf.shape[1], eps, bw_floor, flags)
     assert omega_rf.is_contiguous() and omega_rf.dtype == q.dtype and omega_rf.shape[0] == q.shape[3]
     for p in (sigma, gate_w, gate_b, scale_w):
         assert p.dtype == torch.float32 and p.is_contiguous()
@@ -178,13 +185,14 @@ def _probe(desc):
 
 
 def wersa_backward(q, k, v, omega_rf, sigma, gate_w, gate_b, scale_w, out, dout, saved, L,
-                   eps=1e-6, bw_floor=1e-6, workspace=None, stream=None, param_grads=True, grads=None):
+                   eps=1e-6, bw_floor=1e-6, workspace=None, stream=None, param_grads=True, grads=None,
+                   flags=0):
     """Returns dict(dq, dk, dv, dgate_w, dgate_b, dscale_w, dsigma).
 
     `grads` may be a dict from an earlier call: its tensors are then overwritten in place."""
     lib = load_library()
     _same_layout(q, k, v, out, dout)
-    desc = make_desc(q, L, omega_rf.shape[1], eps, bw_floor)
+    desc = make_desc(q, L, omega_rf.shape[1], eps, bw_floor, flags)
     if grads is not None:
         dq, dk, dv = grads["dq"], grads["dk"], grads["dv"]
         _same_layout(q, dq, dk, dv)

@@ -17,6 +17,7 @@ wersa_status validate_desc(const wersa_desc *c) {
   if (c->m % 16 != 0 || c->m < 16 || c->m > 4096) return WERSA_ERR_UNSUPPORTED;
   if ((int64_t)c->B * c->H > 1023) return WERSA_ERR_UNSUPPORTED;
   if ((int64_t)c->n > (int64_t)1 << 22) return WERSA_ERR_UNSUPPORTED;
+  if (c->flags & ~WERSA_FLAG_GENERIC_PATH) return WERSA_ERR_INVALID_ARG;
   return WERSA_OK;
 }
 
@@ -28,12 +29,18 @@ extern "C" {
 
 size_t wersa_workspace_bytes(const wersa_desc *desc, int for_backward) {
   if (validate_desc(desc) != WERSA_OK) return 0;
-  return generic_workspace_bytes(*desc, for_backward);
+  return use_fast(*desc) ? fast_workspace_bytes(*desc, for_backward)
+                         : generic_workspace_bytes(*desc, for_backward);
 }
 
 size_t wersa_saved_bytes(const wersa_desc *desc) {
   if (validate_desc(desc) != WERSA_OK) return 0;
   return (size_t)saved_layout(*desc).total * sizeof(float);
+}
+
+int32_t wersa_selected_path(const wersa_desc *desc) {
+  if (validate_desc(desc) != WERSA_OK) return -1;
+  return use_fast(*desc) ? 1 : 0;
 }
 
 int64_t wersa_saved_offset(const wersa_desc *desc, int which) {
@@ -63,6 +70,9 @@ wersa_status wersa_forward(const wersa_desc *desc, const void *q, const void *k,
   if (!workspace || workspace_bytes < wersa_workspace_bytes(desc, 0) || misaligned(workspace, 256) ||
       misaligned(saved, 256))
     return WERSA_ERR_WORKSPACE;
+  if (use_fast(*desc))
+    return fast_forward(*desc, q, k, v, omega_rf, sigma, gate_w, gate_b, scale_w, out, (float *)saved,
+                        (float *)workspace, (hipStream_t)hip_stream);
   return generic_forward(*desc, q, k, v, omega_rf, sigma, gate_w, gate_b, scale_w, out, (float *)saved,
                          (float *)workspace, (hipStream_t)hip_stream);
 }
@@ -81,6 +91,10 @@ wersa_status wersa_backward(const wersa_desc *desc, const void *q, const void *k
   if (!workspace || workspace_bytes < wersa_workspace_bytes(desc, 1) || misaligned(workspace, 256) ||
       misaligned(saved, 256))
     return WERSA_ERR_WORKSPACE;
+  if (use_fast(*desc))
+    return fast_backward(*desc, q, k, v, omega_rf, sigma, gate_w, scale_w, out, dout,
+                         (const float *)saved, dq, dk, dv, dgate_w, dgate_b, dscale_w, dsigma,
+                         (float *)workspace, (hipStream_t)hip_stream);
   return generic_backward(*desc, q, k, v, omega_rf, sigma, gate_w, gate_b, scale_w, out, dout,
                           (const float *)saved, dq, dk, dv, dgate_w, dgate_b, dscale_w, dsigma,
                           (float *)workspace, (hipStream_t)hip_stream);

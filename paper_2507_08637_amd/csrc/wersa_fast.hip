@@ -1,0 +1,998 @@
+// MFMA path for bf16 tensors on gfx950 (Section 3.1 steps 3-8 and their derivatives).
+//
+// Staging (all intermediates that reach HBM are n x d sized; the n x m feature matrices live
+// only in registers):
+//   haar_stage      X (bf16) -> X_F = W^-1(F (.) W X) as fp16, LDS-staged 64-row tiles
+//                   (steps 3, 5, 6 fused; the block-mean form of the gated Haar filter)
+//   phiT_contract   sum_t ReLU(X_F Omega)[t,:]^T Y[t,:]  and  sum_t w_t ReLU(X_F Omega)[t,:]
+//                   split over n into partials (step 7 + the reductions of step 8;
+//                   reused in the backward for dS = Phi_Q^T dN, dz = Phi_Q^T dD)
+//   reduce_contract fixed-order sum of the partials, scaled; also bf16 copies as MFMA operands
+//   rows            per 64-row block: ReLU(X_F Omega) again, then either the step-8 apply +
+//                   normaliser (forward), or dPhi -> mask -> dX_F -> gated Haar filter of the
+//                   gradient + per-band inner products (backward), K side also dV
+// The projection uses fp16 MFMA operands (X_F in fp16 keeps the sign of X_F Omega right to
+// 2^-12, which the ReLU derivative needs); everything downstream of the ReLU uses bf16 MFMA.
+#include "wersa_internal.h"
+
+namespace wersa {
+namespace {
+
+#include "wersa_small_kernels.inc"
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
+
+// MFMA 32x32x16 lane layout (wave64; l32 = lane % 32, h = lane / 32):
+//   A operand: row l32, k = 8h + q (q = 0..7)      B operand: column l32, k = 8h + q
+//   C/D: acc[i] is row 8*(i/4) + 4h + (i%4), column l32.
+__device__ __forceinline__ int acc_row(int i, int h) { return 8 * (i >> 2) + 4 * h + (i & 3); }
+
+__device__ __forceinline__ f32x16 mfma_f16(f16x8 a, f16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x16 mfma_bf16(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x16 zero16() {
+  f32x16 z;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) z[i] = 0.f;
+  return z;
+}
+__device__ __forceinline__ float wave_sum64(float v) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+// Pack accumulator registers 8a .. 8a+7 into one bf16 MFMA operand. With this choice k-slot
+// (h, q) of the consuming MFMA stands for accumulator row 16a + 8*(q/4) + 4h + (q%4); the other
+// operand must be fetched in the same order (two runs of four consecutive indices).
+__device__ __forceinline__ bf16x8 pack_half(const f32x16 &v, int a) {
+  bf16x8 p;
+#pragma unroll
+  for (int q = 0; q < 8; ++q) p[q] = (__bf16)v[8 * a + q];
+  return p;
+}
+// The matching operand: indices base + 4h + {0..3} and base + 8 + 4h + {0..3} of a row in LDS.
+__device__ __forceinline__ bf16x8 lds_perm8(const bf16_t *row, int base, int h) {
+  const bf16x4 lo = *reinterpret_cast<const bf16x4 *>(row + base + 4 * h);
+  const bf16x4 hi = *reinterpret_cast<const bf16x4 *>(row + base + 8 + 4 * h);
+  bf16x8 r;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    r[q] = lo[q];
+    r[4 + q] = hi[q];
+  }
+  return r;
+}
+
+// ------------------------------------------------------------------------------------
+// Filter coefficients of the block-mean form:  X_F = sum_l coef_l * (sum over the aligned
+// 2^l block), coef_0 = F_0, coef_l = (F_l - F_{l-1}) / 2^l  (l = 1..L), 0 above L.
+// Also Omega^T in fp16 ([m][d]) for the projection's MFMA operand.
+// ------------------------------------------------------------------------------------
+__global__ void coef_kernel(const float *F, int L, int slices, float *coef) {
+  const int s = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s >= slices) return;
+  const float *f = F + s * (L + 1);
+  float *c = coef + s * 8;
+  c[0] = f[0];
+  for (int l = 1; l <= kMaxL; ++l) c[l] = l <= L ? (f[l] - f[l - 1]) / (float)(1 << l) : 0.f;
+  c[7] = 0.f;
+}
+__global__ void omega_t_kernel(const bf16_t *omega, int d, int m, _Float16 *omT) {
+  const int e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= d * m) return;
+  const int r = e / d, j = e % d;
+  omT[e] = (_Float16)bf16_to_f32(omega[(int64_t)j * m + r]);
+}
+
+// ------------------------------------------------------------------------------------
+// Column sums of Q for the pooled query: 16-byte loads, one partial per (slice, chunk).
+// ------------------------------------------------------------------------------------
+template <int DH>
+__global__ __launch_bounds__(256) void qbar_partial_kernel(const bf16_t *q, View v, int n,
+                                                          int rows_per_chunk, float *part) {
+  constexpr int CPR = DH / 8;        // 16-byte chunks per row
+  constexpr int RPI = 256 / CPR;     // rows per iteration
+  const int slice = blockIdx.y, chunk = blockIdx.x, chunks = gridDim.x;
+  const int t0 = chunk * rows_per_chunk, t1 = min(n, t0 + rows_per_chunk);
+  const int cc = threadIdx.x % CPR, rr = threadIdx.x / CPR;
+  const bf16_t *qs = q + v.slice_base(slice) + cc * 8;
+  float acc[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+  for (int t = t0 + rr; t < t1; t += RPI) {
+    const u16x8 x = *reinterpret_cast<const u16x8 *>(qs + (int64_t)t * v.sn);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] += bf16_to_f32(x[e]);
+  }
+  __shared__ float red[RPI][DH + 1];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) red[rr][cc * 8 + e] = acc[e];
+  __syncthreads();
+  if (threadIdx.x < DH) {
+    float s = 0.f;
+    for (int r = 0; r < RPI; ++r) s += red[r][threadIdx.x];
+    part[((int64_t)slice * chunks + chunk) * DH + threadIdx.x] = s;
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// Gated Haar filter in block-mean form on one column, RS consecutive rows held by a thread.
+//   bs_l = sum over the aligned 2^l block;  out = sum_l coef_l * bs_l
+// `upper` is sum_{l > log2 RS} coef_l * bs_l for the blocks that contain this segment.
+// ------------------------------------------------------------------------------------
+template <int RS>
+__device__ __forceinline__ void filter_segment(float (&v)[RS], const float *coef, float upper) {
+  constexpr int LV = RS == 32 ? 5 : 4;
+  static_assert(RS == 16 || RS == 32, "segment of 16 or 32 rows");
+  float bs[LV + 1][RS];
+#pragma unroll
+  for (int i = 0; i < RS; ++i) bs[0][i] = v[i];
+#pragma unroll
+  for (int l = 1; l <= LV; ++l)
+#pragma unroll
+    for (int k = 0; k < (RS >> l); ++k) bs[l][k] = bs[l - 1][2 * k] + bs[l - 1][2 * k + 1];
+  float T[LV + 1][RS];
+  T[LV][0] = fmaf(coef[LV], bs[LV][0], upper);
+#pragma unroll
+  for (int l = LV - 1; l >= 0; --l)
+#pragma unroll
+    for (int k = 0; k < (RS >> l); ++k) T[l][k] = fmaf(coef[l], bs[l][k], T[l + 1][k >> 1]);
+#pragma unroll
+  for (int i = 0; i < RS; ++i) v[i] = T[0][i];
+}
+template <int RS>
+__device__ __forceinline__ float segment_sum(const float (&v)[RS]) {
+  float s[RS];
+#pragma unroll
+  for (int i = 0; i < RS; ++i) s[i] = v[i];
+#pragma unroll
+  for (int w = RS / 2; w >= 1; w >>= 1)
+#pragma unroll
+    for (int k = 0; k < w; ++k) s[k] = s[2 * k] + s[2 * k + 1];
+  return s[0];
+}
+
+// X (bf16, strided) -> X_F (fp16, contiguous [slices][n][DH]); one 64-row tile per workgroup.
+// Steps: coalesced 16-byte loads into LDS; one thread per (column, row segment) computes the
+// nested block sums (in registers up to the segment, through LDS above it) and the filtered
+// values; fp16 results go back to LDS and leave with coalesced 16-byte stores.
+template <int DH>
+__global__ __launch_bounds__(256) void haar_stage_kernel(const bf16_t *x, View v, int n,
+                                                        const float *coef, _Float16 *xf) {
+  constexpr int SEGS = 256 / DH;   // row segments per column: 4 (DH=64) or 2 (DH=128)
+  constexpr int RS = 64 / SEGS;    // rows per segment: 16 or 32
+  constexpr int CPR = DH / 8;
+  __shared__ __attribute__((aligned(16))) bf16_t tile[64 * DH];
+  __shared__ float segsum[SEGS][DH];
+  __shared__ float cf[8];
+  const int slice = blockIdx.y, t0 = blockIdx.x * 64;
+  const int tid = threadIdx.x;
+  if (tid < 8) cf[tid] = coef[slice * 8 + tid];
+  const bf16_t *xs = x + v.slice_base(slice);
+  for (int e = tid; e < 64 * CPR; e += 256) {
+    const int r = e / CPR, cc = e % CPR;
+    u16x8 val;
+    if (t0 + r < n) val = *reinterpret_cast<const u16x8 *>(xs + (int64_t)(t0 + r) * v.sn + cc * 8);
+    else
+#pragma unroll
+      for (int q = 0; q < 8; ++q) val[q] = 0;
+    *reinterpret_cast<u16x8 *>(&tile[r * DH + cc * 8]) = val;
+  }
+  __syncthreads();
+  const int c = tid % DH, seg = tid / DH;
+  float vals[RS];
+#pragma unroll
+  for (int i = 0; i < RS; ++i) vals[i] = bf16_to_f32(tile[(seg * RS + i) * DH + c]);
+  segsum[seg][c] = segment_sum<RS>(vals);
+  __syncthreads();
+  float upper;
+  if (SEGS == 4) {
+    const float s5 = segsum[seg & ~1][c] + segsum[seg | 1][c];
+    const float s6 = (segsum[0][c] + segsum[1][c]) + (segsum[2][c] + segsum[3][c]);
+    upper = fmaf(cf[5], s5, cf[6] * s6);
+  } else {
+    upper = cf[6] * (segsum[0][c] + segsum[1][c]);
+  }
+  filter_segment<RS>(vals, cf, upper);
+  _Float16 *tile16 = reinterpret_cast<_Float16 *>(tile);
+#pragma unroll
+  for (int i = 0; i < RS; ++i) tile16[(seg * RS + i) * DH + c] = (_Float16)vals[i];
+  __syncthreads();
+  _Float16 *out = xf + ((int64_t)slice * n + t0) * DH;
+  for (int e = tid; e < 64 * CPR; e += 256) {
+    const int r = e / CPR, cc = e % CPR;
+    if (t0 + r < n)
+      *reinterpret_cast<u16x8 *>(out + (int64_t)r * DH + cc * 8) =
+          *reinterpret_cast<const u16x8 *>(&tile[r * DH + cc * 8]);
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// phiT_contract: for the rows of one chunk and the features [f0, f0 + 4*FW) of one slice
+//   Spart[r][c] = sum_t ReLU(X_F Omega)[t][r] * (rowscale_t * Y[t][c])
+//   zpart[r]    = sum_t w_t * ReLU(X_F Omega)[t][r]
+// Four waves split the features; each wave keeps its Omega operands in registers and chains
+// the projection's accumulators (rows t on registers) straight into the second MFMA as the
+// A operand; Y goes through LDS transposed so that t runs along the operand's k index.
+// ------------------------------------------------------------------------------------
+template <int DH, int FW>
+__global__ __launch_bounds__(256) void phiT_contract_kernel(
+    const _Float16 *xf, const bf16_t *y, View vy, const float *rowdiv, const float *w,
+    const _Float16 *omT, int n, int m, int rows_per_chunk, float *Spart, float *zpart) {
+  constexpr int KS = DH / 16;   // k-steps of the projection
+  constexpr int RT = FW / 32;   // feature tiles per wave
+  constexpr int CT = DH / 32;   // column tiles of Y
+  constexpr int CPR = DH / 8;
+  constexpr int YS = 64 + 4;    // row stride (elements) of the transposed Y tile
+  __shared__ __attribute__((aligned(16))) bf16_t yt[DH * YS];
+  __shared__ __attribute__((aligned(16))) float wl[64];
+  const int slice = blockIdx.z, chunk = blockIdx.x, chunks = gridDim.x;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
+  const int f0 = blockIdx.y * (4 * FW) + wave * FW;
+  const int t_begin = chunk * rows_per_chunk, t_end = min(n, t_begin + rows_per_chunk);
+
+  // Omega^T operands of this wave's features: B operand, column = feature, k = 8h + q.
+  f16x8 om[RT][KS];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+      om[rt][ks] = *reinterpret_cast<const f16x8 *>(omT + (int64_t)(f0 + 32 * rt + l32) * DH + 16 * ks + 8 * h);
+
+  f32x16 S[RT][CT];
+  float zacc[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    zacc[rt] = 0.f;
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) S[rt][ct] = zero16();
+  }
+  const _Float16 *xs = xf + (int64_t)slice * n * DH;
+  const bf16_t *ys = y + vy.slice_base(slice);
+  const float *rd = rowdiv ? rowdiv + (int64_t)slice * n : nullptr;
+  const float *ws = w ? w + (int64_t)slice * n : nullptr;
+
+  for (int t0 = t_begin; t0 < t_end; t0 += 64) {
+    __syncthreads();   // previous step's readers are done with yt / wl
+    // stage Y (scaled) transposed: yt[c][t]
+    for (int e = tid; e < 64 * CPR; e += 256) {
+      const int r = e / CPR, cc = e % CPR;
+      const u16x8 val = *reinterpret_cast<const u16x8 *>(ys + (int64_t)(t0 + r) * vy.sn + cc * 8);
+      if (rd) {
+        const float inv = 1.0f / rd[t0 + r];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) yt[(cc * 8 + q) * YS + r] = f32_to_bf16(bf16_to_f32(val[q]) * inv);
+      } else {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) yt[(cc * 8 + q) * YS + r] = val[q];
+      }
+    }
+    if (tid < 64) wl[tid] = ws ? ws[t0 + tid] : 1.0f;
+    __syncthreads();
+#pragma unroll
+    for (int ti = 0; ti < 2; ++ti) {
+      // projection operands: rows t0 + 32 ti + l32, k = 8h + q (+16 per k-step)
+      f16x8 xa[KS];
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        xa[ks] = *reinterpret_cast<const f16x8 *>(xs + (int64_t)(t0 + 32 * ti + l32) * DH + 16 * ks + 8 * h);
+      float wv[16];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const f32x4 w4 = *reinterpret_cast<const f32x4 *>(&wl[32 * ti + 8 * g + 4 * h]);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) wv[4 * g + q] = w4[q];
+      }
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        f32x16 R = zero16();
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) R = mfma_f16(xa[ks], om[rt][ks], R);
+        float zs = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          R[i] = fmaxf(R[i], 0.f);
+          zs = fmaf(wv[i], R[i], zs);
+        }
+        zacc[rt] += zs;
+#pragma unroll
+        for (int a = 0; a < 2; ++a) {
+          const bf16x8 pa = pack_half(R, a);
+#pragma unroll
+          for (int ct = 0; ct < CT; ++ct) {
+            const bf16x8 yb = lds_perm8(&yt[(32 * ct + l32) * YS], 32 * ti + 16 * a, h);
+            S[rt][ct] = mfma_bf16(pa, yb, S[rt][ct]);
+          }
+        }
+      }
+    }
+  }
+  float *sp = Spart + ((int64_t)slice * chunks + chunk) * (int64_t)m * DH;
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        sp[(int64_t)(f0 + 32 * rt + acc_row(i, h)) * DH + 32 * ct + l32] = S[rt][ct][i];
+    const float zt = zacc[rt] + __shfl_xor(zacc[rt], 32, 64);
+    if (h == 0) zpart[((int64_t)slice * chunks + chunk) * m + f0 + 32 * rt + l32] = zt;
+  }
+}
+
+// out[slice][e] = scale * sum_chunk part[slice][chunk][e]  (e over m*DH), plus bf16 copies
+// row-major [m][DH] and transposed [DH][m]; the vector part likewise (float only).
+template <int DH>
+__global__ void reduce_contract_kernel(const float *Spart, const float *zpart, int chunks, int m,
+                                       const float *scale_ptr, float *S, float *z, bf16_t *Sb,
+                                       bf16_t *SbT) {
+  const int slice = blockIdx.y;
+  const int64_t W = (int64_t)m * DH;
+  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const float scale = *scale_ptr;
+  if (e < W) {
+    const float *p = Spart + (int64_t)slice * chunks * W + e;
+    float acc = 0.f;
+    for (int c = 0; c < chunks; ++c) acc += p[(int64_t)c * W];
+    acc *= scale;
+    S[(int64_t)slice * W + e] = acc;
+    const int r = (int)(e / DH), cidx = (int)(e % DH);
+    const bf16_t b = f32_to_bf16(acc);
+    Sb[(int64_t)slice * W + e] = b;
+    SbT[(int64_t)slice * W + (int64_t)cidx * m + r] = b;
+  }
+  if (e < m) {
+    const float *p = zpart + (int64_t)slice * chunks * m + e;
+    float acc = 0.f;
+    for (int c = 0; c < chunks; ++c) acc += p[(int64_t)c * m];
+    z[(int64_t)slice * m + e] = acc * scale;
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// rows kernel. One wave owns 64 consecutive rows (one Haar block of the largest size); the
+// workgroup's waves share the feature-side operands in LDS.  The projection is computed
+// transposed (features on the accumulator's register index, rows on lanes) so that the ReLU
+// output chains into MFMAs that contract over the features.
+//   MODE 0 (forward, Q side):   N = relu(R) S,  D = c * relu(R) z + eps,  O = c N / D
+//   MODE 1 (backward, Q side):  G = dN S^T + dD z^T; dR = 1[R>0] G; dX_F = c dR Omega^T
+//   MODE 2 (backward, K side):  G = V dS^T + 1 dz^T; dR, dX_F as above; dV = c relu(R) dS
+// Backward epilogue: dX = gated Haar filter of dX_F (block-mean form on the accumulator
+// layout, rows on registers), per-band inner products with X for dF, bf16 stores.
+// ------------------------------------------------------------------------------------
+constexpr int kRowsWaves = 4;
+
+template <int DH>
+struct RowsSmem {
+  // element strides chosen so that the 16-byte (A operand) and 8-byte (permuted B operand)
+  // LDS reads of 32 consecutive rows fall in different banks
+  static constexpr int A_STRIDE = DH + 8;   // rows of [feature][DH] arrays
+};
+
+template <int DH, int MODE>
+__global__ __launch_bounds__(kRowsWaves * 64) void rows_kernel(
+    const _Float16 *xf,        // X_F fp16 [slices][n][DH]
+    const bf16_t *x, View vx,  // X (Q or K), for the band inner products (MODE 1, 2)
+    const bf16_t *y, View vy,  // dO (MODE 1) or V (MODE 2)
+    const float *Dsaved,       // D [slices][n]: written (MODE 0), read (MODE 1)
+    const float *arow,         // dD [slices][n] (MODE 1)
+    const _Float16 *omT,       // Omega^T fp16 [m][DH]
+    const bf16_t *omega,       // Omega bf16 [DH][m]
+    const bf16_t *Mb,          // S (MODE 1) / dS (MODE 2), bf16 [slices][m][DH]
+    const bf16_t *MbT,         // S^T (MODE 0) / dS^T (MODE 2), bf16 [slices][DH][m]
+    const float *bvec,         // z (MODE 0, 1) / dz (MODE 2), [slices][m]
+    const float *coef,         // filter coefficients [slices][8]
+    const float *scalars, float eps, int n, int m, int mc,
+    bf16_t *out0, View vo,     // O (MODE 0) / dQ or dK (MODE 1, 2)
+    bf16_t *out1,              // dV (MODE 2)
+    float *Dout,               // D (MODE 0)
+    float *partF, int L)       // [slices][gridDim.x][L+1] band partials (MODE 1, 2)
+{
+  constexpr int KS = DH / 16, CT = DH / 32;
+  constexpr int AS = DH + 8;            // stride of [feature][DH] arrays (16-byte reads)
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  const int BS = mc + 4;                // stride of [DH][feature] arrays (8-byte permuted reads)
+  // carve LDS
+  _Float16 *s_omT = reinterpret_cast<_Float16 *>(smem_raw);                 // [mc][AS]
+  unsigned char *p = smem_raw + (size_t)mc * AS * 2;
+  bf16_t *s_Mb = nullptr, *s_MbT = nullptr, *s_om = nullptr;
+  if (MODE != 0) { s_Mb = reinterpret_cast<bf16_t *>(p); p += (size_t)mc * AS * 2; }   // [mc][AS]
+  if (MODE != 1) { s_MbT = reinterpret_cast<bf16_t *>(p); p += (size_t)DH * BS * 2; }  // [DH][BS]
+  if (MODE != 0) { s_om = reinterpret_cast<bf16_t *>(p); p += (size_t)DH * BS * 2; }   // [DH][BS]
+  float *s_b = reinterpret_cast<float *>(p); p += (size_t)mc * 4;                      // [mc]
+  float *s_wave = reinterpret_cast<float *>(p);                                        // [waves][64]
+
+  const int slice = blockIdx.y;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
+  const int t0 = (blockIdx.x * kRowsWaves + wave) * 64;
+  const bool active = t0 < n;
+  const float cscale = scalars[0];
+
+  // ---- per-wave row-side operands --------------------------------------------------
+  f16x8 xb[2][KS];      // X_F rows: B operand of the transposed projection
+  bf16x8 yb[2][KS];     // dN or V rows: B operand of the dPhi MFMA (MODE 1, 2)
+  float arow_l[2];      // dD_t of this lane's row (MODE 1); 1 for MODE 2
+  if (active) {
+    const _Float16 *xs = xf + ((int64_t)slice * n + t0) * DH;
+#pragma unroll
+    for (int ti = 0; ti < 2; ++ti)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        xb[ti][ks] = *reinterpret_cast<const f16x8 *>(xs + (int64_t)(32 * ti + l32) * DH + 16 * ks + 8 * h);
+    if (MODE != 0) {
+      const bf16_t *ys = y + vy.slice_base(slice);
+#pragma unroll
+      for (int ti = 0; ti < 2; ++ti) {
+        const int t = t0 + 32 * ti + l32;
+        float inv = 1.0f;
+        if (MODE == 1) {
+          inv = 1.0f / Dsaved[(int64_t)slice * n + t];
+          arow_l[ti] = arow[(int64_t)slice * n + t];
+        } else {
+          arow_l[ti] = 1.0f;
+        }
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          const u16x8 raw = *reinterpret_cast<const u16x8 *>(ys + (int64_t)t * vy.sn + 16 * ks + 8 * h);
+          bf16x8 o;
+#pragma unroll
+          for (int q = 0; q < 8; ++q) {
+            const float f = bf16_to_f32(raw[q]);
+            o[q] = (__bf16)(MODE == 1 ? f * inv : f);
+          }
+          yb[ti][ks] = o;
+        }
+      }
+    }
+  }
+
+  f32x16 acc0[2][CT];   // N (MODE 0) or dX_F (MODE 1, 2): rows on registers, columns on lanes
+  f32x16 acc1[2][CT];   // dV (MODE 2)
+  float dacc[2] = {0.f, 0.f};   // D partial of this lane's row (MODE 0)
+#pragma unroll
+  for (int ti = 0; ti < 2; ++ti)
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+      acc0[ti][ct] = zero16();
+      if (MODE == 2) acc1[ti][ct] = zero16();
+    }
+
+  for (int m0 = 0; m0 < m; m0 += mc) {
+    __syncthreads();
+    // ---- stage the feature-side operands of features [m0, m0 + mc) -------------------
+    {
+      const int chunks_per_row = DH / 8;
+      for (int e = tid; e < mc * chunks_per_row; e += kRowsWaves * 64) {
+        const int r = e / chunks_per_row, cc = e % chunks_per_row;
+        *reinterpret_cast<u16x8 *>(&s_omT[r * AS + cc * 8]) =
+            *reinterpret_cast<const u16x8 *>(omT + (int64_t)(m0 + r) * DH + cc * 8);
+        if (MODE != 0)
+          *reinterpret_cast<u16x8 *>(&s_Mb[r * AS + cc * 8]) =
+              *reinterpret_cast<const u16x8 *>(Mb + ((int64_t)slice * m + m0 + r) * DH + cc * 8);
+      }
+      const int chunks_per_col = mc / 4;   // 8-byte pieces: the padded stride is only 8-byte aligned
+      for (int e = tid; e < DH * chunks_per_col; e += kRowsWaves * 64) {
+        const int cidx = e / chunks_per_col, cc = e % chunks_per_col;
+        if (MODE != 1)
+          *reinterpret_cast<bf16x4 *>(&s_MbT[cidx * BS + cc * 4]) =
+              *reinterpret_cast<const bf16x4 *>(MbT + ((int64_t)slice * DH + cidx) * m + m0 + cc * 4);
+        if (MODE != 0)
+          *reinterpret_cast<bf16x4 *>(&s_om[cidx * BS + cc * 4]) =
+              *reinterpret_cast<const bf16x4 *>(omega + (int64_t)cidx * m + m0 + cc * 4);
+      }
+      for (int e = tid; e < mc; e += kRowsWaves * 64) s_b[e] = bvec[(int64_t)slice * m + m0 + e];
+    }
+    __syncthreads();
+    if (!active) continue;
+
+    for (int rt = 0; rt < mc / 32; ++rt) {
+      f16x8 oa[KS];     // Omega^T rows of this feature tile: A operand of the projection
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        oa[ks] = *reinterpret_cast<const f16x8 *>(&s_omT[(32 * rt + l32) * AS + 16 * ks + 8 * h]);
+      bf16x8 ma[KS];    // S / dS rows of this feature tile: A operand of the dPhi MFMA
+      if (MODE != 0) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+          ma[ks] = *reinterpret_cast<const bf16x8 *>(&s_Mb[(32 * rt + l32) * AS + 16 * ks + 8 * h]);
+      }
+      float bv[16];     // z / dz of the features on this lane's accumulator rows
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const f32x4 b4 = *reinterpret_cast<const f32x4 *>(&s_b[32 * rt + 8 * g + 4 * h]);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) bv[4 * g + q] = b4[q];
+      }
+#pragma unroll
+      for (int ti = 0; ti < 2; ++ti) {
+        f32x16 R = zero16();
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) R = mfma_f16(oa[ks], xb[ti][ks], R);
+        if (MODE == 0) {
+          float ds = 0.f;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            R[i] = fmaxf(R[i], 0.f);
+            ds = fmaf(R[i], bv[i], ds);
+          }
+          dacc[ti] += ds;
+#pragma unroll
+          for (int a = 0; a < 2; ++a) {
+            const bf16x8 pa = pack_half(R, a);
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) {
+              const bf16x8 sb = lds_perm8(&s_MbT[(32 * ct + l32) * BS], 32 * rt + 16 * a, h);
+              acc0[ti][ct] = mfma_bf16(pa, sb, acc0[ti][ct]);
+            }
+          }
+        } else {
+          f32x16 G = zero16();
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) G = mfma_bf16(ma[ks], yb[ti][ks], G);
+#pragma unroll
+          for (int i = 0; i < 16; ++i) G[i] = R[i] > 0.f ? fmaf(arow_l[ti], bv[i], G[i]) : 0.f;
+#pragma unroll
+          for (int a = 0; a < 2; ++a) {
+            const bf16x8 pg = pack_half(G, a);
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) {
+              const bf16x8 ob = lds_perm8(&s_om[(32 * ct + l32) * BS], 32 * rt + 16 * a, h);
+              acc0[ti][ct] = mfma_bf16(pg, ob, acc0[ti][ct]);
+            }
+          }
+          if (MODE == 2) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) R[i] = fmaxf(R[i], 0.f);
+#pragma unroll
+            for (int a = 0; a < 2; ++a) {
+              const bf16x8 pa = pack_half(R, a);
+#pragma unroll
+              for (int ct = 0; ct < CT; ++ct) {
+                const bf16x8 sb = lds_perm8(&s_MbT[(32 * ct + l32) * BS], 32 * rt + 16 * a, h);
+                acc1[ti][ct] = mfma_bf16(pa, sb, acc1[ti][ct]);
+              }
+            }
+          }
+        }
+      }
+    }
+  }
+
+  // ---- epilogues -------------------------------------------------------------------
+  if (MODE == 0) {
+    if (active) {
+      float *dl = s_wave + wave * 64;
+#pragma unroll
+      for (int ti = 0; ti < 2; ++ti) {
+        const float dsum = dacc[ti] + __shfl_xor(dacc[ti], 32, 64);
+        const float Dt = fmaf(cscale, dsum, eps);
+        if (h == 0) {
+          dl[32 * ti + l32] = Dt;
+          Dout[(int64_t)slice * n + t0 + 32 * ti + l32] = Dt;
+        }
+      }
+      // dl is written and read by this wave only; LDS operations of one wave complete in order
+      bf16_t *os = out0 + vo.slice_base(slice);
+#pragma unroll
+      for (int ti = 0; ti < 2; ++ti)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int tl = 32 * ti + acc_row(i, h);
+          const float inv = cscale / dl[tl];
+#pragma unroll
+          for (int ct = 0; ct < CT; ++ct)
+            os[(int64_t)(t0 + tl) * vo.sn + 32 * ct + l32] = f32_to_bf16(acc0[ti][ct][i] * inv);
+        }
+    }
+    return;
+  }
+
+  // MODE 1, 2: gated Haar filter of dX_F on the accumulator layout and band inner products.
+  // Lane (l32, h) holds column 32 ct + l32 and rows 32 ti + 8 g + 4 h + e (g, e = 0..3):
+  //   block sums of 2 and 4 rows are in-lane, 8 rows need the other half-wave (lane ^ 32),
+  //   16 and 32 rows are in-lane again over g, 64 rows over ti.
+  float u[kMaxBands];   // u_l = sum over blocks of bs_l(g) * bs_l(x) / 2^l, this lane's share
+#pragma unroll
+  for (int l = 0; l < kMaxBands; ++l) u[l] = 0.f;
+  if (active) {
+    float cf[kMaxBands];
+#pragma unroll
+    for (int l = 0; l < kMaxBands; ++l) cf[l] = coef[slice * 8 + l];
+    const bf16_t *xs = x + vx.slice_base(slice);
+    bf16_t *os = out0 + vo.slice_base(slice);
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+      const int col = 32 * ct + l32;
+      float g0[2][16], x0[2][16];
+#pragma unroll
+      for (int ti = 0; ti < 2; ++ti)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          g0[ti][i] = acc0[ti][ct][i] * cscale;
+          x0[ti][i] = bf16_to_f32(xs[(int64_t)(t0 + 32 * ti + acc_row(i, h)) * vx.sn + col]);
+          u[0] = fmaf(g0[ti][i], x0[ti][i], u[0]);
+        }
+      float g1[2][8], x1[2][8], g2[2][4], x2[2][4], g3[2][4], x3[2][4], g4[2][2], x4[2][2], g5[2], x5[2];
+#pragma unroll
+      for (int ti = 0; ti < 2; ++ti) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          g1[ti][k] = g0[ti][2 * k] + g0[ti][2 * k + 1];
+          x1[ti][k] = x0[ti][2 * k] + x0[ti][2 * k + 1];
+          u[1] = fmaf(g1[ti][k], x1[ti][k], u[1]);
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          g2[ti][k] = g1[ti][2 * k] + g1[ti][2 * k + 1];
+          x2[ti][k] = x1[ti][2 * k] + x1[ti][2 * k + 1];
+          u[2] = fmaf(g2[ti][k], x2[ti][k], u[2]);
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {   // 8-row blocks: both half-waves hold the same sums
+          g3[ti][k] = g2[ti][k] + __shfl_xor(g2[ti][k], 32, 64);
+          x3[ti][k] = x2[ti][k] + __shfl_xor(x2[ti][k], 32, 64);
+          u[3] = fmaf(0.5f * g3[ti][k], x3[ti][k], u[3]);
+        }
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+          g4[ti][k] = g3[ti][2 * k] + g3[ti][2 * k + 1];
+          x4[ti][k] = x3[ti][2 * k] + x3[ti][2 * k + 1];
+          u[4] = fmaf(0.5f * g4[ti][k], x4[ti][k], u[4]);
+        }
+        g5[ti] = g4[ti][0] + g4[ti][1];
+        x5[ti] = x4[ti][0] + x4[ti][1];
+        u[5] = fmaf(0.5f * g5[ti], x5[ti], u[5]);
+      }
+      const float g6 = g5[0] + g5[1], x6 = x5[0] + x5[1];
+      u[6] = fmaf(0.5f * g6, x6, u[6]);
+      // filtered gradient, top-down
+      const float T6 = cf[6] * g6;
+#pragma unroll
+      for (int ti = 0; ti < 2; ++ti) {
+        const float T5 = fmaf(cf[5], g5[ti], T6);
+        float T4[2], T3[4], T2[4], T1[8];
+#pragma unroll
+        for (int k = 0; k < 2; ++k) T4[k] = fmaf(cf[4], g4[ti][k], T5);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) T3[k] = fmaf(cf[3], g3[ti][k], T4[k >> 1]);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) T2[k] = fmaf(cf[2], g2[ti][k], T3[k]);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) T1[k] = fmaf(cf[1], g1[ti][k], T2[k >> 1]);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const float val = fmaf(cf[0], g0[ti][i], T1[i >> 1]);
+          os[(int64_t)(t0 + 32 * ti + acc_row(i, h)) * vo.sn + col] = f32_to_bf16(val);
+        }
+      }
+    }
+    if (MODE == 2) {
+      bf16_t *vs = out1 + vo.slice_base(slice);
+#pragma unroll
+      for (int ti = 0; ti < 2; ++ti)
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+          for (int i = 0; i < 16; ++i)
+            vs[(int64_t)(t0 + 32 * ti + acc_row(i, h)) * vo.sn + 32 * ct + l32] =
+                f32_to_bf16(acc1[ti][ct][i] * cscale);
+    }
+  }
+  // With u_l = <dX_F, P_l X> (P_l = mean over aligned 2^l blocks) the band gradients are
+  // dF_L = u_L and dF_{l-1} = u_{l-1} - u_l (l = 1..L); one partial per workgroup.
+  __syncthreads();   // operand arrays are no longer read; reuse s_wave for the reduction
+#pragma unroll
+  for (int l = 0; l < kMaxBands; ++l) {
+    const float s = wave_sum64(u[l]) / (float)(1 << l);
+    if (lane == 0) s_wave[wave * 8 + l] = s;
+  }
+  __syncthreads();
+  if (tid <= L) {
+    float ul = 0.f, ul1 = 0.f;
+    for (int wv = 0; wv < kRowsWaves; ++wv) {
+      ul += s_wave[wv * 8 + tid];
+      if (tid < L) ul1 += s_wave[wv * 8 + tid + 1];
+    }
+    partF[((int64_t)slice * gridDim.x + blockIdx.x) * (L + 1) + tid] = tid < L ? ul - ul1 : ul;
+  }
+}
+
+// dD_t = -<dO_t, O_t> / D_t, and per-block partial sums of dD (for d sigma).
+template <int DH>
+__global__ __launch_bounds__(256) void prep_bwd_kernel(const bf16_t *dout, const bf16_t *out, View v,
+                                                      const float *D, int n, float *dD,
+                                                      float *dDpart) {
+  constexpr int CPR = DH / 8, RPB = 256 / CPR;
+  const int slice = blockIdx.y;
+  const int t = blockIdx.x * RPB + threadIdx.x / CPR, cc = threadIdx.x % CPR;
+  float acc = 0.f;
+  if (t < n) {
+    const int64_t off = v.slice_base(slice) + (int64_t)t * v.sn + cc * 8;
+    const u16x8 a = *reinterpret_cast<const u16x8 *>(dout + off);
+    const u16x8 b = *reinterpret_cast<const u16x8 *>(out + off);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) acc = fmaf(bf16_to_f32(a[q]), bf16_to_f32(b[q]), acc);
+  }
+  for (int o = CPR / 2; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+  float val = 0.f;
+  if (t < n && cc == 0) {
+    val = -acc / D[(int64_t)slice * n + t];
+    dD[(int64_t)slice * n + t] = val;
+  }
+  __shared__ float red[4];
+  const float ws = wave_sum64(val);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ws;
+  __syncthreads();
+  if (threadIdx.x == 0)
+    dDpart[(int64_t)slice * gridDim.x + blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+// dQ[t][:] += dqbar / n  (the pooled-query path), bf16 read-modify-write with 16-byte accesses.
+template <int DH>
+__global__ void add_pooled_kernel(bf16_t *dq, View v, const float *dqbar, int n, float inv_n) {
+  constexpr int CPR = DH / 8;
+  const int slice = blockIdx.y;
+  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= (int64_t)n * CPR) return;
+  const int t = (int)(e / CPR), cc = (int)(e % CPR);
+  bf16_t *p = dq + v.slice_base(slice) + (int64_t)t * v.sn + cc * 8;
+  u16x8 val = *reinterpret_cast<u16x8 *>(p);
+#pragma unroll
+  for (int q = 0; q < 8; ++q)
+    val[q] = f32_to_bf16(bf16_to_f32(val[q]) + dqbar[(int64_t)slice * DH + cc * 8 + q] * inv_n);
+  *reinterpret_cast<u16x8 *>(p) = val;
+}
+
+
+// ---------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------
+struct FastPlan {
+  int DH, FW, MB, mc;
+  int chunksQ, rowsQ;   // pooled-query partial sums
+  int chunksC, rowsC;   // split of n in phiT_contract
+  int rowGroups;        // workgroups per slice of the rows kernel
+};
+
+FastPlan fast_plan(const wersa_desc &c) {
+  FastPlan p{};
+  p.DH = c.d;
+  if (c.m % 256 == 0) { p.FW = 64; p.MB = 256; } else { p.FW = 32; p.MB = 128; }
+  p.mc = (c.d == 64 && c.m % 256 == 0) ? 256 : 128;
+  const int slices = c.B * c.H, blocks = c.n / 64;
+  int cq = (c.n + 1023) / 1024;
+  p.chunksQ = cq < 1 ? 1 : (cq > 512 ? 512 : cq);
+  p.rowsQ = (c.n + p.chunksQ - 1) / p.chunksQ;
+  p.chunksQ = (c.n + p.rowsQ - 1) / p.rowsQ;
+  int want = (768 + slices * (c.m / p.MB) - 1) / (slices * (c.m / p.MB));
+  if (want < 1) want = 1;
+  if (want > blocks) want = blocks;
+  const int bpc = (blocks + want - 1) / want;
+  p.rowsC = bpc * 64;
+  p.chunksC = (blocks + bpc - 1) / bpc;
+  p.rowGroups = (blocks + kRowsWaves - 1) / kRowsWaves;
+  return p;
+}
+
+struct FastWs {
+  float *scalars, *coef, *qpart, *Spart, *zpart, *dD, *dDpart, *dS, *dz, *partQ, *partK, *dF,
+      *dlogit, *dqbar;
+  _Float16 *omT;
+  bf16_t *Sb, *SbT, *dSb, *dSbT;
+  int64_t total;
+};
+
+FastWs fast_ws(const wersa_desc &c, const FastPlan &p, int bwd, float *base) {
+  FastWs w{};
+  Bump b(base);
+  const int64_t sl = (int64_t)c.B * c.H, md = (int64_t)c.m * c.d;
+  w.scalars = b.take(64);
+  w.coef = b.take(sl * 8);
+  w.qpart = b.take(sl * p.chunksQ * c.d);
+  w.omT = reinterpret_cast<_Float16 *>(b.take(md / 2));
+  w.Spart = b.take(sl * p.chunksC * md);
+  w.zpart = b.take(sl * p.chunksC * c.m);
+  w.Sb = reinterpret_cast<bf16_t *>(b.take(sl * md / 2));
+  w.SbT = reinterpret_cast<bf16_t *>(b.take(sl * md / 2));
+  if (bwd) {
+    w.dD = b.take(sl * c.n);
+    w.dDpart = b.take(sl * ((c.n + (256 / (c.d / 8)) - 1) / (256 / (c.d / 8))));
+    w.dS = b.take(sl * md);
+    w.dz = b.take(sl * c.m);
+    w.dSb = reinterpret_cast<bf16_t *>(b.take(sl * md / 2));
+    w.dSbT = reinterpret_cast<bf16_t *>(b.take(sl * md / 2));
+    w.partQ = b.take(sl * p.rowGroups * (c.L + 1));
+    w.partK = b.take(sl * p.rowGroups * (c.L + 1));
+    w.dF = b.take(sl * (c.L + 1));
+    w.dlogit = b.take(sl * (c.L + 1));
+    w.dqbar = b.take(sl * c.d);
+  }
+  w.total = b.off;
+  return w;
+}
+
+template <int DH, int MODE>
+size_t rows_smem_bytes(int mc) {
+  const size_t AS = DH + 8, BS = (size_t)mc + 4;
+  size_t s = (size_t)mc * AS * 2;
+  if (MODE != 0) s += (size_t)mc * AS * 2;
+  if (MODE != 1) s += (size_t)DH * BS * 2;
+  if (MODE != 0) s += (size_t)DH * BS * 2;
+  s += (size_t)mc * 4 + kRowsWaves * 64 * 4;
+  return s;
+}
+
+template <int DH, int MODE>
+hipError_t launch_rows(const wersa_desc &c, const FastPlan &p, const _Float16 *xf, const bf16_t *x,
+                       const bf16_t *y, const float *Dsaved, const float *arow, const FastWs &w,
+                       const bf16_t *omega, const bf16_t *Mb, const bf16_t *MbT, const float *bvec,
+                       bf16_t *out0, bf16_t *out1, float *Dout, float *partF, hipStream_t st) {
+  const View tv{c.stride_b, c.stride_h, c.stride_n, c.H};
+  const size_t smem = rows_smem_bytes<DH, MODE>(p.mc);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&rows_kernel<DH, MODE>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+  if (e != hipSuccess) return e;
+  const char *name = MODE == 0 ? "wersa_rows_fwd" : (MODE == 1 ? "wersa_rows_bwd_q" : "wersa_rows_bwd_k");
+  WERSA_STAGE(name, st,
+              rows_kernel<DH, MODE><<<dim3(p.rowGroups, c.B * c.H), kRowsWaves * 64, smem, st>>>(
+                  xf, x, tv, y, tv, Dsaved, arow, w.omT, omega, Mb, MbT, bvec, w.coef, w.scalars,
+                  c.eps, c.n, c.m, p.mc, out0, tv, out1, Dout, partF, c.L));
+  return hipSuccess;
+}
+
+template <int DH>
+void launch_contract(const wersa_desc &c, const FastPlan &p, const _Float16 *xf, const bf16_t *y,
+                     const float *rowdiv, const float *wt, const FastWs &w, float *S, float *z,
+                     bf16_t *Sb, bf16_t *SbT, hipStream_t st) {
+  const View tv{c.stride_b, c.stride_h, c.stride_n, c.H};
+  const int slices = c.B * c.H;
+  dim3 grid(p.chunksC, c.m / p.MB, slices);
+  if (p.FW == 64)
+    WERSA_STAGE("wersa_phiT_contract", st,
+                phiT_contract_kernel<DH, 64><<<grid, 256, 0, st>>>(xf, y, tv, rowdiv, wt, w.omT, c.n, c.m,
+                                                                    p.rowsC, w.Spart, w.zpart));
+  else
+    WERSA_STAGE("wersa_phiT_contract", st,
+                phiT_contract_kernel<DH, 32><<<grid, 256, 0, st>>>(xf, y, tv, rowdiv, wt, w.omT, c.n, c.m,
+                                                                    p.rowsC, w.Spart, w.zpart));
+  const int64_t W = (int64_t)c.m * DH;
+  WERSA_STAGE("wersa_reduce_contract", st,
+              reduce_contract_kernel<DH><<<dim3((unsigned)((W + 255) / 256), slices), 256, 0, st>>>(
+                  w.Spart, w.zpart, p.chunksC, c.m, w.scalars, S, z, Sb, SbT));
+}
+
+template <int DH>
+wersa_status fast_forward_t(const wersa_desc &c, const bf16_t *q, const bf16_t *k, const bf16_t *v,
+                            const bf16_t *omega, const float *sigma, const float *gate_w,
+                            const float *gate_b, const float *scale_w, bf16_t *out, float *saved,
+                            float *ws, hipStream_t st) {
+  const FastPlan p = fast_plan(c);
+  const FastWs w = fast_ws(c, p, 0, ws);
+  const SavedLayout sv = saved_layout(c);
+  const int slices = c.B * c.H;
+  const View tv{c.stride_b, c.stride_h, c.stride_n, c.H};
+  float *S = saved + sv.S, *z = saved + sv.z, *qbar = saved + sv.qbar, *s = saved + sv.s,
+        *F = saved + sv.F, *D = saved + sv.D;
+  _Float16 *QF = reinterpret_cast<_Float16 *>(saved + sv.QF);
+  _Float16 *KF = reinterpret_cast<_Float16 *>(saved + sv.KF);
+
+  WERSA_STAGE("scalars_kernel", st, scalars_kernel<<<1, 64, 0, st>>>(sigma, c.bw_floor, c.m, w.scalars));
+  WERSA_STAGE("omega_t_kernel", st,
+              omega_t_kernel<<<(c.d * c.m + 255) / 256, 256, 0, st>>>(omega, c.d, c.m, w.omT));
+  WERSA_STAGE("wersa_qbar", st,
+              qbar_partial_kernel<DH><<<dim3(p.chunksQ, slices), 256, 0, st>>>(q, tv, c.n, p.rowsQ, w.qpart));
+  WERSA_STAGE("gate_fwd_kernel", st,
+              gate_fwd_kernel<<<slices, 256, 0, st>>>(w.qpart, p.chunksQ, c.n, c.d, c.L, c.H, gate_w, gate_b,
+                                                     scale_w, qbar, s, F));
+  WERSA_STAGE("coef_kernel", st, coef_kernel<<<(slices + 63) / 64, 64, 0, st>>>(F, c.L, slices, w.coef));
+  WERSA_STAGE("wersa_haar_stage", st,
+              haar_stage_kernel<DH><<<dim3(c.n / 64, slices), 256, 0, st>>>(q, tv, c.n, w.coef, QF));
+  WERSA_STAGE("wersa_haar_stage", st,
+              haar_stage_kernel<DH><<<dim3(c.n / 64, slices), 256, 0, st>>>(k, tv, c.n, w.coef, KF));
+  launch_contract<DH>(c, p, KF, v, nullptr, nullptr, w, S, z, w.Sb, w.SbT, st);
+  if (launch_rows<DH, 0>(c, p, QF, nullptr, nullptr, nullptr, nullptr, w, omega, nullptr, w.SbT, z, out,
+                         nullptr, D, nullptr, st) != hipSuccess)
+    return WERSA_ERR_LAUNCH;
+  return hipGetLastError() == hipSuccess ? WERSA_OK : WERSA_ERR_LAUNCH;
+}
+
+template <int DH>
+wersa_status fast_backward_t(const wersa_desc &c, const bf16_t *q, const bf16_t *k, const bf16_t *v,
+                             const bf16_t *omega, const float *sigma, const float *gate_w,
+                             const float *scale_w, const bf16_t *out, const bf16_t *dout,
+                             const float *saved, bf16_t *dq, bf16_t *dk, bf16_t *dv, float *dgate_w,
+                             float *dgate_b, float *dscale_w, float *dsigma, float *ws,
+                             hipStream_t st) {
+  const FastPlan p = fast_plan(c);
+  const FastWs w = fast_ws(c, p, 1, ws);
+  const SavedLayout sv = saved_layout(c);
+  const int slices = c.B * c.H;
+  const View tv{c.stride_b, c.stride_h, c.stride_n, c.H};
+  const float *z = saved + sv.z, *qbar = saved + sv.qbar, *s = saved + sv.s, *F = saved + sv.F,
+              *D = saved + sv.D;
+  const _Float16 *QF = reinterpret_cast<const _Float16 *>(saved + sv.QF);
+  const _Float16 *KF = reinterpret_cast<const _Float16 *>(saved + sv.KF);
+  constexpr int RPB = 256 / (DH / 8);
+  const int prepBlocks = (c.n + RPB - 1) / RPB;
+
+  WERSA_STAGE("scalars_kernel", st, scalars_kernel<<<1, 64, 0, st>>>(sigma, c.bw_floor, c.m, w.scalars));
+  WERSA_STAGE("omega_t_kernel", st,
+              omega_t_kernel<<<(c.d * c.m + 255) / 256, 256, 0, st>>>(omega, c.d, c.m, w.omT));
+  WERSA_STAGE("coef_kernel", st, coef_kernel<<<(slices + 63) / 64, 64, 0, st>>>(F, c.L, slices, w.coef));
+  // S as bf16 MFMA operand (row-major) from the saved float32 S: a reduce over one "partial"
+  WERSA_STAGE("wersa_reduce_contract", st,
+              reduce_contract_kernel<DH><<<dim3((unsigned)(((int64_t)c.m * DH + 255) / 256), slices), 256, 0, st>>>(
+                  saved + sv.S, z, 1, c.m, w.scalars + 3, w.dS, w.dz, w.Sb, w.SbT));
+  WERSA_STAGE("wersa_prep_bwd", st,
+              prep_bwd_kernel<DH><<<dim3(prepBlocks, slices), 256, 0, st>>>(dout, out, tv, D, c.n, w.dD, w.dDpart));
+  // dX_F of the Q side needs only S, z; dS, dz need the full reduction over n first.
+  if (launch_rows<DH, 1>(c, p, QF, q, dout, D, w.dD, w, omega, w.Sb, nullptr, z, dq, nullptr, nullptr,
+                         w.partQ, st) != hipSuccess)
+    return WERSA_ERR_LAUNCH;
+  launch_contract<DH>(c, p, QF, dout, D, w.dD, w, w.dS, w.dz, w.dSb, w.dSbT, st);
+  if (launch_rows<DH, 2>(c, p, KF, k, v, nullptr, nullptr, w, omega, w.dSb, w.dSbT, w.dz, dk, dv, nullptr,
+                         w.partK, st) != hipSuccess)
+    return WERSA_ERR_LAUNCH;
+  WERSA_STAGE("gate_bwd_slice_kernel", st,
+              gate_bwd_slice_kernel<<<slices, 64, 0, st>>>(w.partQ, w.partK, p.rowGroups, c.L, c.d, c.H, s,
+                                                           gate_w, scale_w, w.dF, w.dlogit, w.dqbar));
+  WERSA_STAGE("gate_bwd_params_kernel", st,
+              gate_bwd_params_kernel<<<1, 256, 0, st>>>(w.dF, w.dlogit, s, qbar, w.dDpart, slices * prepBlocks,
+                                                        c.B, c.H, c.L, c.d, c.eps, w.scalars, dgate_w,
+                                                        dgate_b, dscale_w, dsigma));
+  const int64_t chunks = (int64_t)c.n * (DH / 8);
+  WERSA_STAGE("wersa_add_pooled", st,
+              add_pooled_kernel<DH><<<dim3((unsigned)((chunks + 255) / 256), slices), 256, 0, st>>>(
+                  dq, tv, w.dqbar, c.n, 1.0f / (float)c.n));
+  return hipGetLastError() == hipSuccess ? WERSA_OK : WERSA_ERR_LAUNCH;
+}
+
+}  // namespace
+
+bool fast_supported(const wersa_desc &c) {
+  return c.dtype == WERSA_BF16 && c.d == 64 && c.n % 64 == 0 && c.m % 128 == 0 &&
+         c.stride_n % 8 == 0 && c.stride_h % 8 == 0 && c.stride_b % 8 == 0;
+}
+
+size_t fast_workspace_bytes(const wersa_desc &c, int for_backward) {
+  return (size_t)fast_ws(c, fast_plan(c), for_backward, nullptr).total * sizeof(float);
+}
+
+wersa_status fast_forward(const wersa_desc &c, const void *q, const void *k, const void *v,
+                          const void *omega_rf, const float *sigma, const float *gate_w,
+                          const float *gate_b, const float *scale_w, void *out, float *saved,
+                          float *ws, hipStream_t st) {
+  if (c.d == 64)
+    return fast_forward_t<64>(c, (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,
+                              (const bf16_t *)omega_rf, sigma, gate_w, gate_b, scale_w, (bf16_t *)out,
+                              saved, ws, st);
+  return fast_forward_t<128>(c, (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,
+                             (const bf16_t *)omega_rf, sigma, gate_w, gate_b, scale_w, (bf16_t *)out,
+                             saved, ws, st);
+}
+
+wersa_status fast_backward(const wersa_desc &c, const void *q, const void *k, const void *v,
+                           const void *omega_rf, const float *sigma, const float *gate_w,
+                           const float *scale_w, const void *out, const void *dout,
+                           const float *saved, void *dq, void *dk, void *dv, float *dgate_w,
+                           float *dgate_b, float *dscale_w, float *dsigma, float *ws,
+                           hipStream_t st) {
+  if (c.d == 64)
+    return fast_backward_t<64>(c, (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,
+                               (const bf16_t *)omega_rf, sigma, gate_w, scale_w, (const bf16_t *)out,
+                               (const bf16_t *)dout, saved, (bf16_t *)dq, (bf16_t *)dk, (bf16_t *)dv,
+                               dgate_w, dgate_b, dscale_w, dsigma, ws, st);
+  return fast_backward_t<128>(c, (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,
+                              (const bf16_t *)omega_rf, sigma, gate_w, scale_w, (const bf16_t *)out,
+                              (const bf16_t *)dout, saved, (bf16_t *)dq, (bf16_t *)dk, (bf16_t *)dv,
+                              dgate_w, dgate_b, dscale_w, dsigma, ws, st);
+}
+
+}  // namespace wersa

@@ -6,6 +6,8 @@
 namespace wersa {
 namespace {
 
+#include "wersa_small_kernels.inc"
+
 constexpr int kTileRows = 64;  // rows of one Haar tile: the largest aligned block, 2^kMaxL
 constexpr int kTileCols = 64;
 
@@ -16,20 +18,6 @@ View contiguous_view(int64_t rows, int64_t width) {
   v.sn = width;
   v.H = 1;
   return v;
-}
-
-// ------------------------------------------------------------------------------------
-// scalars[0] = c = 1 / (sigma_eff * sqrt(m));  scalars[1] = sigma_eff;
-// scalars[2] = 1 if sigma > bw_floor (sigma receives a gradient) else 0.
-// ------------------------------------------------------------------------------------
-__global__ void scalars_kernel(const float *sigma, float bw_floor, int m, float *scalars) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) {
-    const float s = *sigma;
-    const float se = fmaxf(s, bw_floor);
-    scalars[0] = 1.0f / (se * sqrtf((float)m));
-    scalars[1] = se;
-    scalars[2] = s > bw_floor ? 1.0f : 0.0f;
-  }
 }
 
 // part[slice][chunk][j] = sum over rows t of the chunk of w[slice][t] * x[slice][t][j]
@@ -70,40 +58,6 @@ __global__ void reduce_partials_kernel(const float *part, int chunks, int64_t W,
   float acc = 0.f;
   for (int c = 0; c < chunks; ++c) acc += p[(int64_t)c * W];
   out[(int64_t)slice * W + j] = acc * scale;
-}
-
-__device__ __forceinline__ float wave_sum(float v) {
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
-}
-
-// Gate (Section 3.1 step 4): qbar, s = sigmoid(W_g qbar + b_g), F = s * omega. One wave per slice.
-__global__ void gate_fwd_kernel(const float *qpart, int chunks, int n, int d, int L, int H,
-                                const float *gate_w, const float *gate_b, const float *scale_w,
-                                float *qbar, float *s_out, float *F_out) {
-  const int slice = blockIdx.x, h = slice % H, lane = threadIdx.x;
-  __shared__ float qb[256];
-  for (int j = lane; j < d; j += 64) {
-    const float *p = qpart + (int64_t)slice * chunks * d + j;
-    float acc = 0.f;
-    for (int c = 0; c < chunks; ++c) acc += p[(int64_t)c * d];
-    acc /= (float)n;
-    qb[j] = acc;
-    qbar[(int64_t)slice * d + j] = acc;
-  }
-  __syncthreads();
-  for (int i = 0; i <= L; ++i) {
-    const float *w = gate_w + ((int64_t)h * (L + 1) + i) * d;
-    float acc = 0.f;
-    for (int j = lane; j < d; j += 64) acc += w[j] * qb[j];
-    acc = wave_sum(acc);
-    if (lane == 0) {
-      const float logit = acc + gate_b[h * (L + 1) + i];
-      const float s = 1.0f / (1.0f + expf(-logit));
-      s_out[slice * (L + 1) + i] = s;
-      F_out[slice * (L + 1) + i] = s * scale_w[i];
-    }
-  }
 }
 
 // In-place Haar lifting on a 64-row LDS tile, one column per lane (Appendix A equations).
@@ -367,88 +321,9 @@ __global__ void mask_scale_kernel(float *R, const float *phi, const float *a, co
   }
 }
 
-// Per slice: dF (sum of tile partials of Q and K), dlogits, dqbar = W_g^T dlogits.
-__global__ void gate_bwd_slice_kernel(const float *partQ, const float *partK, int64_t tiles, int L,
-                                      int d, int H, const float *s_saved, const float *gate_w,
-                                      const float *scale_w, float *dF, float *dlogit, float *dqbar) {
-  const int slice = blockIdx.x, h = slice % H, lane = threadIdx.x;
-  __shared__ float dl[kMaxBands];
-  for (int i = 0; i <= L; ++i) {
-    float acc = 0.f;
-    for (int64_t t = lane; t < tiles; t += 64)
-      acc += partQ[((int64_t)slice * tiles + t) * (L + 1) + i] +
-             partK[((int64_t)slice * tiles + t) * (L + 1) + i];
-    acc = wave_sum(acc);
-    if (lane == 0) {
-      const float s = s_saved[slice * (L + 1) + i];
-      dF[slice * (L + 1) + i] = acc;
-      const float g = acc * scale_w[i] * s * (1.0f - s);
-      dlogit[slice * (L + 1) + i] = g;
-      dl[i] = g;
-    }
-  }
-  __syncthreads();
-  for (int j = lane; j < d; j += 64) {
-    float acc = 0.f;
-    for (int i = 0; i <= L; ++i) acc += gate_w[((int64_t)h * (L + 1) + i) * d + j] * dl[i];
-    dqbar[(int64_t)slice * d + j] = acc;
-  }
-}
-
-// Parameter gradients, summed over batch (and heads for omega) in fixed order. One block.
-__global__ void gate_bwd_params_kernel(const float *dF, const float *dlogit, const float *s_saved,
-                                       const float *qbar, const float *dDpart, int dDparts, int B,
-                                       int H, int L, int d, float eps, const float *scalars,
-                                       float *dgate_w, float *dgate_b, float *dscale_w,
-                                       float *dsigma) {
-  const int tid = threadIdx.x, nb = L + 1;
-  if (dgate_w) {
-    for (int e = tid; e < H * nb * d; e += blockDim.x) {
-      const int j = e % d, i = (e / d) % nb, h = e / (d * nb);
-      float acc = 0.f;
-      for (int b = 0; b < B; ++b) {
-        const int slice = b * H + h;
-        acc += dlogit[slice * nb + i] * qbar[(int64_t)slice * d + j];
-      }
-      dgate_w[e] = acc;
-    }
-  }
-  if (dgate_b) {
-    for (int e = tid; e < H * nb; e += blockDim.x) {
-      const int i = e % nb, h = e / nb;
-      float acc = 0.f;
-      for (int b = 0; b < B; ++b) acc += dlogit[(b * H + h) * nb + i];
-      dgate_b[e] = acc;
-    }
-  }
-  if (dscale_w && tid < nb) {
-    float acc = 0.f;
-    for (int slice = 0; slice < B * H; ++slice) acc += dF[slice * nb + tid] * s_saved[slice * nb + tid];
-    dscale_w[tid] = acc;
-  }
-  if (dsigma && tid == 0) {
-    // ReLU is positively homogeneous, so sigma reaches the output only through eps:
-    // d loss / d sigma = (2 eps / sigma_eff) * sum_t dD_t.
-    float acc = 0.f;
-    for (int p = 0; p < dDparts; ++p) acc += dDpart[p];
-    *dsigma = scalars[2] > 0.f ? 2.0f * eps / scalars[1] * acc : 0.f;
-  }
-}
-
 // ---------------------------------------------------------------------------------------
 // host helpers
 // ---------------------------------------------------------------------------------------
-struct Bump {
-  float *base;
-  int64_t off = 0;
-  explicit Bump(float *b) : base(b) {}
-  float *take(int64_t nfloat) {
-    float *p = base ? base + off : nullptr;
-    off += (nfloat + 63) / 64 * 64;
-    return p;
-  }
-};
-
 int colsum_chunks(int n) {
   int c = (n + 255) / 256;
   return c < 1 ? 1 : (c > 256 ? 256 : c);
@@ -576,7 +451,7 @@ wersa_status forward_t(const wersa_desc &c, const T *q, const T *k, const T *v, 
   WERSA_STAGE("scalars_kernel", st, scalars_kernel<<<1, 64, 0, st>>>(sigma, c.bw_floor, c.m, w.scalars));
   // step 4: pooled query and gate
   launch_colsum<T>(q, tv, slices, c.n, c.d, nullptr, w.qpart, nullptr, 1.f, st);
-  WERSA_STAGE("gate_fwd_kernel", st, gate_fwd_kernel<<<slices, 64, 0, st>>>(w.qpart, colsum_chunks(c.n), c.n, c.d, c.L, c.H, gate_w,
+  WERSA_STAGE("gate_fwd_kernel", st, gate_fwd_kernel<<<slices, 256, 0, st>>>(w.qpart, colsum_chunks(c.n), c.n, c.d, c.L, c.H, gate_w,
                                          gate_b, scale_w, qbar, s, F));
   // steps 3, 5, 6: gated Haar filter of Q and K
   launch_haar<T>(c, q, tv, w.QF, F, st);

@@ -40,8 +40,14 @@ template <> __device__ __forceinline__ void st<float>(float *p, float v) { *p = 
 template <> __device__ __forceinline__ void st<bf16_t>(bf16_t *p, float v) { *p = f32_to_bf16(v); }
 
 // ---- saved-buffer layout (floats) -------------------------------------------------------
+// MFMA path (bf16 storage, d in {64, 128}, n % 64 == 0, m % 128 == 0, 16-byte aligned rows).
+bool fast_supported(const wersa_desc &c);
+inline bool use_fast(const wersa_desc &c) {
+  return !(c.flags & WERSA_FLAG_GENERIC_PATH) && fast_supported(c);
+}
+
 struct SavedLayout {
-  int64_t S, z, qbar, s, F, D, total;
+  int64_t S, z, qbar, s, F, D, QF, KF, total;
 };
 inline SavedLayout saved_layout(const wersa_desc &c) {
   SavedLayout o;
@@ -54,6 +60,11 @@ inline SavedLayout saved_layout(const wersa_desc &c) {
   o.s = off;    off += up(sl * (c.L + 1));
   o.F = off;    off += up(sl * (c.L + 1));
   o.D = off;    off += up(sl * c.n);
+  o.QF = o.KF = -1;
+  if (use_fast(c)) {  // filtered Q and K in fp16, kept for the backward
+    o.QF = off; off += up(sl * c.n * c.d / 2);
+    o.KF = off; off += up(sl * c.n * c.d / 2);
+  }
   o.total = off;
   return o;
 }
@@ -86,6 +97,17 @@ wersa_status generic_backward(const wersa_desc &c, const void *q, const void *k,
                               const void *dout, const float *saved, void *dq, void *dk, void *dv,
                               float *dgate_w, float *dgate_b, float *dscale_w, float *dsigma,
                               float *ws, hipStream_t st);
+size_t fast_workspace_bytes(const wersa_desc &c, int for_backward);
+wersa_status fast_forward(const wersa_desc &c, const void *q, const void *k, const void *v,
+                          const void *omega_rf, const float *sigma, const float *gate_w,
+                          const float *gate_b, const float *scale_w, void *out, float *saved,
+                          float *ws, hipStream_t st);
+wersa_status fast_backward(const wersa_desc &c, const void *q, const void *k, const void *v,
+                           const void *omega_rf, const float *sigma, const float *gate_w,
+                           const float *scale_w, const void *out, const void *dout,
+                           const float *saved, void *dq, void *dk, void *dv, float *dgate_w,
+                           float *dgate_b, float *dscale_w, float *dsigma, float *ws,
+                           hipStream_t st);
 wersa_status generic_haar_filter(const wersa_desc &c, const void *x, const float *filt, void *xf,
                                  hipStream_t st);
 

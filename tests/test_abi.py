@@ -21,7 +21,7 @@ def lib():
 def _desc(**kw):
     from paper_2507_08637_amd.binding import WersaDesc
     base = dict(B=1, H=2, n=256, d=64, L=3, m=64, dtype=0, eps=1e-6, bw_floor=1e-6,
-                stride_b=2 * 256 * 64, stride_h=256 * 64, stride_n=64)
+                stride_b=2 * 256 * 64, stride_h=256 * 64, stride_n=64, flags=0)
     base.update(kw)
     return WersaDesc(**base)
 
@@ -50,7 +50,7 @@ def test_sizes_and_status_strings(lib):
 
 @pytest.mark.parametrize("kw,status", [
     (dict(B=0), 1), (dict(n=0), 1), (dict(L=-1), 1), (dict(dtype=7), 1), (dict(bw_floor=0.0), 1),
-    (dict(stride_n=32), 1), (dict(stride_h=0), 1),
+    (dict(stride_n=32), 1), (dict(stride_h=0), 1), (dict(flags=2), 1),
     (dict(n=100, L=3), 2),      # n not a multiple of 2^L
     (dict(L=7, n=1024), 2), (dict(d=40), 2), (dict(m=72), 2), (dict(d=512, stride_n=512), 2),
 ])
