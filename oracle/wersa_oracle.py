@@ -33,6 +33,12 @@ silent or disagrees with itself):
   for the whole call.
 * Sub-gradient of ReLU at exactly 0 is 0.
 
+Decision precision (optional, default off): the ReLU derivative 1[U > 0] is a binary decision
+taken by floating point.  When a kernel is checked whose projection consumes X_F in a reduced
+precision, `proj_dtype` (for example numpy.float16) rounds X_F once to that type before the
+projection, so that both sides take the decision on the same numbers; everything else stays
+float64.  With proj_dtype=None the oracle is the plain float64 definition.
+
 Pins (tests/test_oracle_pins.py): hand-derived Haar coefficients, perfect
 reconstruction, energy preservation, block-mean closed form, explicit n x n
 kernel-matrix attention, arc-cosine kernel limit and m^-1/2 rate, convexity,
@@ -113,9 +119,11 @@ def gate(qbar, Wg_h, bg_h, omega):
 # ----------------------------------------------------------------------------
 # Random feature map (Section 3.1 step 7; Algorithm 1 projection lines)
 # ----------------------------------------------------------------------------
-def feature_map(XF, Omega, sigma, bw_floor):
+def feature_map(XF, Omega, sigma, bw_floor, proj_dtype=None):
     m = Omega.shape[1]
     sigma_eff = max(float(sigma), float(bw_floor))
+    if proj_dtype is not None:
+        XF = XF.astype(proj_dtype).astype(np.float64)
     U = (XF @ Omega) / sigma_eff
     Phi = np.maximum(U, 0.0) / math.sqrt(m)
     return U, Phi
@@ -124,7 +132,7 @@ def feature_map(XF, Omega, sigma, bw_floor):
 # ----------------------------------------------------------------------------
 # Forward, one (b, h) slice
 # ----------------------------------------------------------------------------
-def forward_slice(Q, K, V, Omega, sigma, Wg_h, bg_h, omega, L, eps, bw_floor):
+def forward_slice(Q, K, V, Omega, sigma, Wg_h, bg_h, omega, L, eps, bw_floor, proj_dtype=None):
     """Q, K, V (n, d) -> dict of every stage tensor, 'O' is the output."""
     Q = np.asarray(Q, np.float64)
     K = np.asarray(K, np.float64)
@@ -133,8 +141,8 @@ def forward_slice(Q, K, V, Omega, sigma, Wg_h, bg_h, omega, L, eps, bw_floor):
     logits, s, F = gate(qbar, Wg_h, bg_h, omega)
     QF = haar_filter(Q, F, L)
     KF = haar_filter(K, F, L)
-    UQ, PhiQ = feature_map(QF, Omega, sigma, bw_floor)
-    UK, PhiK = feature_map(KF, Omega, sigma, bw_floor)
+    UQ, PhiQ = feature_map(QF, Omega, sigma, bw_floor, proj_dtype)
+    UK, PhiK = feature_map(KF, Omega, sigma, bw_floor, proj_dtype)
     S = PhiK.T @ V                       # (m, d)  phi(K_F)^T V
     z = PhiK.T @ np.ones(K.shape[0])     # (m,)    phi(K_F)^T 1
     N = PhiQ @ S
@@ -164,7 +172,7 @@ def _haar_filter_vjp(X, F, L, dXF):
 
 
 def backward_slice(Q, K, V, Omega, sigma, Wg_h, bg_h, omega, L, eps, bw_floor, dO,
-                   fwd=None):
+                   fwd=None, proj_dtype=None):
     """Returns dict dQ, dK, dV (n, d), dWg_h (L+1, d), dbg_h, domega (L+1,),
     dsigma (scalar, term-by-term chain rule form), plus intermediates."""
     Q = np.asarray(Q, np.float64)
@@ -172,7 +180,7 @@ def backward_slice(Q, K, V, Omega, sigma, Wg_h, bg_h, omega, L, eps, bw_floor, d
     V = np.asarray(V, np.float64)
     dO = np.asarray(dO, np.float64)
     f = fwd if fwd is not None else forward_slice(Q, K, V, Omega, sigma, Wg_h, bg_h,
-                                                  omega, L, eps, bw_floor)
+                                                  omega, L, eps, bw_floor, proj_dtype)
     n, d = Q.shape
     m = Omega.shape[1]
     sigma_eff = max(float(sigma), float(bw_floor))
@@ -220,7 +228,7 @@ def backward_slice(Q, K, V, Omega, sigma, Wg_h, bg_h, omega, L, eps, bw_floor, d
 # Whole call over (B, H, n, d)
 # ----------------------------------------------------------------------------
 def forward(Q, K, V, Omega, sigma, Wg, bg, omega, L, eps=1e-6, bw_floor=1e-6,
-            slices=None, keep=("O",)):
+            slices=None, keep=("O",), proj_dtype=None):
     """Q, K, V (B, H, n, d); Omega (d, m); Wg (H, L+1, d); bg (H, L+1); omega (L+1,).
 
     Returns dict of stacked stage tensors named in `keep`, each (B, H, ...).
@@ -234,7 +242,7 @@ def forward(Q, K, V, Omega, sigma, Wg, bg, omega, L, eps=1e-6, bw_floor=1e-6,
     for (b, h) in todo:
         f = forward_slice(Q[b, h], K[b, h], V[b, h], Omega, sigma,
                           np.asarray(Wg[h], np.float64), np.asarray(bg[h], np.float64),
-                          np.asarray(omega, np.float64), L, eps, bw_floor)
+                          np.asarray(omega, np.float64), L, eps, bw_floor, proj_dtype)
         for name in keep:
             if name not in out:
                 out[name] = np.zeros((B, H) + np.shape(f[name]), np.float64)
@@ -243,7 +251,7 @@ def forward(Q, K, V, Omega, sigma, Wg, bg, omega, L, eps=1e-6, bw_floor=1e-6,
 
 
 def backward(Q, K, V, Omega, sigma, Wg, bg, omega, L, dO, eps=1e-6, bw_floor=1e-6,
-             slices=None):
+             slices=None, proj_dtype=None):
     """Gradients of sum(O * dO) w.r.t. Q, K, V, Wg, bg, omega, sigma.
 
     Parameter gradients are summed over every slice processed (all of them
@@ -260,7 +268,7 @@ def backward(Q, K, V, Omega, sigma, Wg, bg, omega, L, dO, eps=1e-6, bw_floor=1e-
         Wg_h = np.asarray(Wg[h], np.float64)
         bg_h = np.asarray(bg[h], np.float64)
         f = forward_slice(Q[b, h], K[b, h], V[b, h], Omega, sigma, Wg_h, bg_h, omega, L,
-                          eps, bw_floor)
+                          eps, bw_floor, proj_dtype)
         r = backward_slice(Q[b, h], K[b, h], V[b, h], Omega, sigma, Wg_h, bg_h, omega, L,
                            eps, bw_floor, dO[b, h], fwd=f)
         g["O"][b, h] = f["O"]

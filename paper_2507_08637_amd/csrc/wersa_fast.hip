@@ -215,12 +215,44 @@ __global__ __launch_bounds__(256) void haar_stage_kernel(const bf16_t *x, View v
 }
 
 // ------------------------------------------------------------------------------------
+// Small helpers for the chained MFMAs.
+// ------------------------------------------------------------------------------------
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// ReLU on a packed bf16 operand: as 16-bit integers, negative floats are negative integers.
+__device__ __forceinline__ bf16x8 relu_bf16x8(bf16x8 p) {
+  s16x8 s = __builtin_bit_cast(s16x8, p);
+  const s16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+  s = __builtin_elementwise_max(s, zero);
+  return __builtin_bit_cast(bf16x8, s);
+}
+// acc + sum_q p[q] * w[q] with bf16 pair dot products (float32 accumulate)
+__device__ __forceinline__ float dot8_bf16(bf16x8 p, bf16x8 w, float acc) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    bf16x2 a, b;
+    a[0] = p[2 * j]; a[1] = p[2 * j + 1];
+    b[0] = w[2 * j]; b[1] = w[2 * j + 1];
+    acc = __builtin_amdgcn_fdot2_f32_bf16(a, b, acc, false);
+  }
+  return acc;
+}
+__device__ __forceinline__ bf16x8 splat_bf16x8(float v) {
+  bf16x8 r;
+#pragma unroll
+  for (int q = 0; q < 8; ++q) r[q] = (__bf16)v;
+  return r;
+}
+
+// ------------------------------------------------------------------------------------
 // phiT_contract: for the rows of one chunk and the features [f0, f0 + 4*FW) of one slice
-//   Spart[r][c] = sum_t ReLU(X_F Omega)[t][r] * (rowscale_t * Y[t][c])
+//   Spart[r][c] = sum_t ReLU(X_F Omega)[t][r] * (Y[t][c] / rowdiv_t)
 //   zpart[r]    = sum_t w_t * ReLU(X_F Omega)[t][r]
 // Four waves split the features; each wave keeps its Omega operands in registers and chains
 // the projection's accumulators (rows t on registers) straight into the second MFMA as the
-// A operand; Y goes through LDS transposed so that t runs along the operand's k index.
+// A operand.  X_F and Y tiles of 64 rows go through double-buffered LDS (Y transposed so that
+// t runs along the operand's k index); the next tile is fetched while the current one is used.
 // ------------------------------------------------------------------------------------
 template <int DH, int FW>
 __global__ __launch_bounds__(256) void phiT_contract_kernel(
@@ -229,14 +261,18 @@ __global__ __launch_bounds__(256) void phiT_contract_kernel(
   constexpr int KS = DH / 16;   // k-steps of the projection
   constexpr int RT = FW / 32;   // feature tiles per wave
   constexpr int CT = DH / 32;   // column tiles of Y
-  constexpr int CPR = DH / 8;
+  constexpr int CPR = DH / 8;   // 16-byte pieces per row
+  constexpr int LPT = 64 * CPR / 256;   // pieces per thread per tile
   constexpr int YS = 64 + 4;    // row stride (elements) of the transposed Y tile
-  __shared__ __attribute__((aligned(16))) bf16_t yt[DH * YS];
-  __shared__ __attribute__((aligned(16))) float wl[64];
+  constexpr int XS = DH + 8;    // row stride (elements) of the X_F tile
+  __shared__ __attribute__((aligned(16))) bf16_t yt[2][DH * YS];
+  __shared__ __attribute__((aligned(16))) _Float16 xt[2][64 * XS];
+  __shared__ __attribute__((aligned(16))) bf16_t wl[2][64];
   const int slice = blockIdx.z, chunk = blockIdx.x, chunks = gridDim.x;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
   const int f0 = blockIdx.y * (4 * FW) + wave * FW;
   const int t_begin = chunk * rows_per_chunk, t_end = min(n, t_begin + rows_per_chunk);
+  const int steps = (t_end - t_begin) / 64;
 
   // Omega^T operands of this wave's features: B operand, column = feature, k = 8h + q.
   f16x8 om[RT][KS];
@@ -259,60 +295,74 @@ __global__ __launch_bounds__(256) void phiT_contract_kernel(
   const float *rd = rowdiv ? rowdiv + (int64_t)slice * n : nullptr;
   const float *ws = w ? w + (int64_t)slice * n : nullptr;
 
-  for (int t0 = t_begin; t0 < t_end; t0 += 64) {
-    __syncthreads();   // previous step's readers are done with yt / wl
-    // stage Y (scaled) transposed: yt[c][t]
-    for (int e = tid; e < 64 * CPR; e += 256) {
-      const int r = e / CPR, cc = e % CPR;
-      const u16x8 val = *reinterpret_cast<const u16x8 *>(ys + (int64_t)(t0 + r) * vy.sn + cc * 8);
-      if (rd) {
-        const float inv = 1.0f / rd[t0 + r];
+  u16x8 yr[LPT], xr[LPT];
+  float inv[LPT], wv = 1.0f;
+  auto fetch = [&](int t0) {
 #pragma unroll
-        for (int q = 0; q < 8; ++q) yt[(cc * 8 + q) * YS + r] = f32_to_bf16(bf16_to_f32(val[q]) * inv);
+    for (int i = 0; i < LPT; ++i) {
+      const int e = tid + 256 * i, r = e / CPR, cc = e % CPR;
+      yr[i] = *reinterpret_cast<const u16x8 *>(ys + (int64_t)(t0 + r) * vy.sn + cc * 8);
+      xr[i] = *reinterpret_cast<const u16x8 *>(xs + (int64_t)(t0 + r) * DH + cc * 8);
+      inv[i] = rd ? 1.0f / rd[t0 + r] : 1.0f;
+    }
+    if (tid < 64) wv = ws ? ws[t0 + tid] : 1.0f;
+  };
+  auto stash = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) {
+      const int e = tid + 256 * i, r = e / CPR, cc = e % CPR;
+      *reinterpret_cast<u16x8 *>(&xt[buf][r * XS + cc * 8]) = xr[i];
+      if (rd) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+          yt[buf][(cc * 8 + q) * YS + r] = f32_to_bf16(bf16_to_f32(yr[i][q]) * inv[i]);
       } else {
 #pragma unroll
-        for (int q = 0; q < 8; ++q) yt[(cc * 8 + q) * YS + r] = val[q];
+        for (int q = 0; q < 8; ++q) yt[buf][(cc * 8 + q) * YS + r] = yr[i][q];
       }
     }
-    if (tid < 64) wl[tid] = ws ? ws[t0 + tid] : 1.0f;
-    __syncthreads();
+    if (tid < 64) wl[buf][tid] = f32_to_bf16(wv);
+  };
+
+  if (steps > 0) {
+    fetch(t_begin);
+    stash(0);
+  }
+  __syncthreads();
+  for (int s = 0; s < steps; ++s) {
+    const int buf = s & 1;
+    const bool more = s + 1 < steps;
+    if (more) fetch(t_begin + 64 * (s + 1));
 #pragma unroll
     for (int ti = 0; ti < 2; ++ti) {
-      // projection operands: rows t0 + 32 ti + l32, k = 8h + q (+16 per k-step)
-      f16x8 xa[KS];
+      f16x8 xa[KS];   // projection A operand: rows 32 ti + l32, k = 8h + q (+16 per k-step)
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks)
-        xa[ks] = *reinterpret_cast<const f16x8 *>(xs + (int64_t)(t0 + 32 * ti + l32) * DH + 16 * ks + 8 * h);
-      float wv[16];
+        xa[ks] = *reinterpret_cast<const f16x8 *>(&xt[buf][(32 * ti + l32) * XS + 16 * ks + 8 * h]);
+      bf16x8 yb[2][CT], wp[2];
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const f32x4 w4 = *reinterpret_cast<const f32x4 *>(&wl[32 * ti + 8 * g + 4 * h]);
+      for (int a = 0; a < 2; ++a) {
+        wp[a] = lds_perm8(&wl[buf][0], 32 * ti + 16 * a, h);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) wv[4 * g + q] = w4[q];
+        for (int ct = 0; ct < CT; ++ct)
+          yb[a][ct] = lds_perm8(&yt[buf][(32 * ct + l32) * YS], 32 * ti + 16 * a, h);
       }
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
         f32x16 R = zero16();
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) R = mfma_f16(xa[ks], om[rt][ks], R);
-        float zs = 0.f;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          R[i] = fmaxf(R[i], 0.f);
-          zs = fmaf(wv[i], R[i], zs);
-        }
-        zacc[rt] += zs;
 #pragma unroll
         for (int a = 0; a < 2; ++a) {
-          const bf16x8 pa = pack_half(R, a);
+          const bf16x8 pa = relu_bf16x8(pack_half(R, a));
+          zacc[rt] = dot8_bf16(pa, wp[a], zacc[rt]);
 #pragma unroll
-          for (int ct = 0; ct < CT; ++ct) {
-            const bf16x8 yb = lds_perm8(&yt[(32 * ct + l32) * YS], 32 * ti + 16 * a, h);
-            S[rt][ct] = mfma_bf16(pa, yb, S[rt][ct]);
-          }
+          for (int ct = 0; ct < CT; ++ct) S[rt][ct] = mfma_bf16(pa, yb[a][ct], S[rt][ct]);
         }
       }
     }
+    if (more) stash(buf ^ 1);
+    __syncthreads();
   }
   float *sp = Spart + ((int64_t)slice * chunks + chunk) * (int64_t)m * DH;
 #pragma unroll
@@ -327,12 +377,16 @@ __global__ __launch_bounds__(256) void phiT_contract_kernel(
   }
 }
 
-// out[slice][e] = scale * sum_chunk part[slice][chunk][e]  (e over m*DH), plus bf16 copies
-// row-major [m][DH] and transposed [DH][m]; the vector part likewise (float only).
+// M[slice][e] = scale * sum_chunk part[slice][chunk][e]  (e over m*DH) and the vector part
+// b likewise; plus the bf16 MFMA operand copies:
+//   Mx  [m][DH+16]: row r = (M[r][0..DH), b[r], 0 x 15)   (A operand of dPhi = Y M^T + a b^T)
+//   MT  [DH][m]   : M transposed                           (B operand of Phi M)
+//   bb  [m]       : b in bf16
 template <int DH>
 __global__ void reduce_contract_kernel(const float *Spart, const float *zpart, int chunks, int m,
-                                       const float *scale_ptr, float *S, float *z, bf16_t *Sb,
-                                       bf16_t *SbT) {
+                                       const float *scale_ptr, float *S, float *z, bf16_t *Mx,
+                                       bf16_t *MT, bf16_t *bb) {
+  constexpr int DX = DH + 16;
   const int slice = blockIdx.y;
   const int64_t W = (int64_t)m * DH;
   const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -345,229 +399,278 @@ __global__ void reduce_contract_kernel(const float *Spart, const float *zpart, i
     S[(int64_t)slice * W + e] = acc;
     const int r = (int)(e / DH), cidx = (int)(e % DH);
     const bf16_t b = f32_to_bf16(acc);
-    Sb[(int64_t)slice * W + e] = b;
-    SbT[(int64_t)slice * W + (int64_t)cidx * m + r] = b;
+    Mx[((int64_t)slice * m + r) * DX + cidx] = b;
+    MT[(int64_t)slice * W + (int64_t)cidx * m + r] = b;
   }
   if (e < m) {
     const float *p = zpart + (int64_t)slice * chunks * m + e;
     float acc = 0.f;
     for (int c = 0; c < chunks; ++c) acc += p[(int64_t)c * m];
-    z[(int64_t)slice * m + e] = acc * scale;
+    acc *= scale;
+    z[(int64_t)slice * m + e] = acc;
+    const bf16_t b = f32_to_bf16(acc);
+    bb[(int64_t)slice * m + e] = b;
+    bf16_t *ext = Mx + ((int64_t)slice * m + e) * DX + DH;
+    ext[0] = b;
+#pragma unroll
+    for (int q = 1; q < 16; ++q) ext[q] = 0;
   }
 }
 
 // ------------------------------------------------------------------------------------
-// rows kernel. One wave owns 64 consecutive rows (one Haar block of the largest size); the
-// workgroup's waves share the feature-side operands in LDS.  The projection is computed
-// transposed (features on the accumulator's register index, rows on lanes) so that the ReLU
-// output chains into MFMAs that contract over the features.
+// rows kernel. One wave owns 64 consecutive rows at a time (one Haar block of the largest
+// size); the workgroup's waves share the feature-side operands in LDS and walk over the
+// row groups of their slice (the operands are staged once when all features fit).  The
+// projection is computed transposed (features on the accumulator's register index, rows on
+// lanes) so that the ReLU output chains into MFMAs that contract over the features.
 //   MODE 0 (forward, Q side):   N = relu(R) S,  D = c * relu(R) z + eps,  O = c N / D
 //   MODE 1 (backward, Q side):  G = dN S^T + dD z^T; dR = 1[R>0] G; dX_F = c dR Omega^T
 //   MODE 2 (backward, K side):  G = V dS^T + 1 dz^T; dR, dX_F as above; dV = c relu(R) dS
+// The rank-one term a b^T of G rides along as one extra k-step of the dPhi MFMA (operand
+// rows extended by (b_r, 0, ...) and (a_t, 0, ...)).
 // Backward epilogue: dX = gated Haar filter of dX_F (block-mean form on the accumulator
 // layout, rows on registers), per-band inner products with X for dF, bf16 stores.
 // ------------------------------------------------------------------------------------
 constexpr int kRowsWaves = 4;
 
-template <int DH>
-struct RowsSmem {
-  // element strides chosen so that the 16-byte (A operand) and 8-byte (permuted B operand)
-  // LDS reads of 32 consecutive rows fall in different banks
-  static constexpr int A_STRIDE = DH + 8;   // rows of [feature][DH] arrays
-};
-
 template <int DH, int MODE>
-__global__ __launch_bounds__(kRowsWaves * 64) void rows_kernel(
+__global__ __launch_bounds__(kRowsWaves * 64, MODE == 0 ? 2 : 1) void rows_kernel(
     const _Float16 *xf,        // X_F fp16 [slices][n][DH]
     const bf16_t *x, View vx,  // X (Q or K), for the band inner products (MODE 1, 2)
     const bf16_t *y, View vy,  // dO (MODE 1) or V (MODE 2)
-    const float *Dsaved,       // D [slices][n]: written (MODE 0), read (MODE 1)
+    const float *Dsaved,       // D [slices][n] (MODE 1)
     const float *arow,         // dD [slices][n] (MODE 1)
     const _Float16 *omT,       // Omega^T fp16 [m][DH]
     const bf16_t *omega,       // Omega bf16 [DH][m]
-    const bf16_t *Mb,          // S (MODE 1) / dS (MODE 2), bf16 [slices][m][DH]
-    const bf16_t *MbT,         // S^T (MODE 0) / dS^T (MODE 2), bf16 [slices][DH][m]
-    const float *bvec,         // z (MODE 0, 1) / dz (MODE 2), [slices][m]
+    const bf16_t *Mx,          // (S | z) (MODE 1) / (dS | dz) (MODE 2), bf16 [slices][m][DH+16]
+    const bf16_t *MT,          // S^T (MODE 0) / dS^T (MODE 2), bf16 [slices][DH][m]
+    const bf16_t *bb,          // z bf16 [slices][m] (MODE 0)
     const float *coef,         // filter coefficients [slices][8]
-    const float *scalars, float eps, int n, int m, int mc,
+    const float *scalars, float eps, int n, int m, int mc, int row_groups,
     bf16_t *out0, View vo,     // O (MODE 0) / dQ or dK (MODE 1, 2)
     bf16_t *out1,              // dV (MODE 2)
     float *Dout,               // D (MODE 0)
     float *partF, int L)       // [slices][gridDim.x][L+1] band partials (MODE 1, 2)
 {
   constexpr int KS = DH / 16, CT = DH / 32;
-  constexpr int AS = DH + 8;            // stride of [feature][DH] arrays (16-byte reads)
+  constexpr int KSX = KS + 1;           // k-steps of the dPhi MFMA incl. the rank-one extension
+  constexpr int AS = DH + 8;            // stride of the [feature][DH] fp16 array (16-byte reads)
+  constexpr int AM = DH + 16 + 8;       // stride of the [feature][DH+16] bf16 array
+  constexpr int NT = kRowsWaves * 64;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   const int BS = mc + 4;                // stride of [DH][feature] arrays (8-byte permuted reads)
-  // carve LDS
   _Float16 *s_omT = reinterpret_cast<_Float16 *>(smem_raw);                 // [mc][AS]
   unsigned char *p = smem_raw + (size_t)mc * AS * 2;
-  bf16_t *s_Mb = nullptr, *s_MbT = nullptr, *s_om = nullptr;
-  if (MODE != 0) { s_Mb = reinterpret_cast<bf16_t *>(p); p += (size_t)mc * AS * 2; }   // [mc][AS]
-  if (MODE != 1) { s_MbT = reinterpret_cast<bf16_t *>(p); p += (size_t)DH * BS * 2; }  // [DH][BS]
+  bf16_t *s_Mx = nullptr, *s_MT = nullptr, *s_om = nullptr, *s_bb = nullptr;
+  if (MODE != 0) { s_Mx = reinterpret_cast<bf16_t *>(p); p += (size_t)mc * AM * 2; }   // [mc][AM]
+  if (MODE != 1) { s_MT = reinterpret_cast<bf16_t *>(p); p += (size_t)DH * BS * 2; }   // [DH][BS]
   if (MODE != 0) { s_om = reinterpret_cast<bf16_t *>(p); p += (size_t)DH * BS * 2; }   // [DH][BS]
-  float *s_b = reinterpret_cast<float *>(p); p += (size_t)mc * 4;                      // [mc]
+  if (MODE == 0) { s_bb = reinterpret_cast<bf16_t *>(p); p += (size_t)mc * 2; }        // [mc]
   float *s_wave = reinterpret_cast<float *>(p);                                        // [waves][64]
 
   const int slice = blockIdx.y;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
-  const int t0 = (blockIdx.x * kRowsWaves + wave) * 64;
-  const bool active = t0 < n;
   const float cscale = scalars[0];
+  const int nchunks = m / mc;
 
-  // ---- per-wave row-side operands --------------------------------------------------
-  f16x8 xb[2][KS];      // X_F rows: B operand of the transposed projection
-  bf16x8 yb[2][KS];     // dN or V rows: B operand of the dPhi MFMA (MODE 1, 2)
-  float arow_l[2];      // dD_t of this lane's row (MODE 1); 1 for MODE 2
-  if (active) {
-    const _Float16 *xs = xf + ((int64_t)slice * n + t0) * DH;
+  auto stage = [&](int m0) {
+    constexpr int CPRX = DH / 8;          // 16-byte pieces per Omega^T row
+    constexpr int CPRM = (DH + 16) / 8;   // 16-byte pieces per extended M row
+    for (int e0 = 0; e0 < mc * CPRX; e0 += NT * 4) {
+      u16x8 tmp[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int e = e0 + NT * u + tid;
+        if (e < mc * CPRX)
+          tmp[u] = *reinterpret_cast<const u16x8 *>(omT + (int64_t)(m0 + e / CPRX) * DH + (e % CPRX) * 8);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int e = e0 + NT * u + tid;
+        if (e < mc * CPRX) *reinterpret_cast<u16x8 *>(&s_omT[(e / CPRX) * AS + (e % CPRX) * 8]) = tmp[u];
+      }
+    }
+    if (MODE != 0) {
+      for (int e0 = 0; e0 < mc * CPRM; e0 += NT * 4) {
+        u16x8 tmp[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int e = e0 + NT * u + tid;
+          if (e < mc * CPRM)
+            tmp[u] = *reinterpret_cast<const u16x8 *>(Mx + ((int64_t)slice * m + m0 + e / CPRM) * (DH + 16) +
+                                                      (e % CPRM) * 8);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int e = e0 + NT * u + tid;
+          if (e < mc * CPRM) *reinterpret_cast<u16x8 *>(&s_Mx[(e / CPRM) * AM + (e % CPRM) * 8]) = tmp[u];
+        }
+      }
+    }
+    const int cpc = mc / 4;   // 8-byte pieces per column row (the padded stride is 8-byte aligned)
+    for (int e0 = 0; e0 < DH * cpc; e0 += NT * 4) {
+      bf16x4 t1[4], t2[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int e = e0 + NT * u + tid;
+        if (e < DH * cpc) {
+          const int cidx = e / cpc, cc = e % cpc;
+          if (MODE != 1)
+            t1[u] = *reinterpret_cast<const bf16x4 *>(MT + ((int64_t)slice * DH + cidx) * m + m0 + cc * 4);
+          if (MODE != 0) t2[u] = *reinterpret_cast<const bf16x4 *>(omega + (int64_t)cidx * m + m0 + cc * 4);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int e = e0 + NT * u + tid;
+        if (e < DH * cpc) {
+          const int cidx = e / cpc, cc = e % cpc;
+          if (MODE != 1) *reinterpret_cast<bf16x4 *>(&s_MT[cidx * BS + cc * 4]) = t1[u];
+          if (MODE != 0) *reinterpret_cast<bf16x4 *>(&s_om[cidx * BS + cc * 4]) = t2[u];
+        }
+      }
+    }
+    if (MODE == 0)
+      for (int e = tid; e < mc; e += NT) s_bb[e] = bb[(int64_t)slice * m + m0 + e];
+  };
+
+  float u[kMaxBands];   // u_l = sum over blocks of bs_l(g) * bs_l(x), this lane's share
+#pragma unroll
+  for (int l = 0; l < kMaxBands; ++l) u[l] = 0.f;
+  float cf[kMaxBands];
+  if (MODE != 0) {
+#pragma unroll
+    for (int l = 0; l < kMaxBands; ++l) cf[l] = coef[slice * 8 + l];
+  }
+
+  if (nchunks == 1) {
+    stage(0);
+    __syncthreads();
+  }
+
+  for (int rg = blockIdx.x; rg < row_groups; rg += gridDim.x) {
+    const int t0 = (rg * kRowsWaves + wave) * 64;
+    const bool active = t0 < n;
+
+    // ---- per-wave row-side operands ------------------------------------------------
+    f16x8 xb[2][KS];      // X_F rows: B operand of the transposed projection
+    bf16x8 yb[2][KSX];    // dN or V rows (+ the a_t extension): B operand of the dPhi MFMA
+    if (active) {
+      const _Float16 *xs = xf + ((int64_t)slice * n + t0) * DH;
+#pragma unroll
+      for (int ti = 0; ti < 2; ++ti)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+          xb[ti][ks] = *reinterpret_cast<const f16x8 *>(xs + (int64_t)(32 * ti + l32) * DH + 16 * ks + 8 * h);
+      if (MODE != 0) {
+        const bf16_t *ys = y + vy.slice_base(slice);
+#pragma unroll
+        for (int ti = 0; ti < 2; ++ti) {
+          const int t = t0 + 32 * ti + l32;
+          float inv = 1.0f, at = 1.0f;
+          if (MODE == 1) {
+            inv = 1.0f / Dsaved[(int64_t)slice * n + t];
+            at = arow[(int64_t)slice * n + t];
+          }
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) {
+            const u16x8 raw = *reinterpret_cast<const u16x8 *>(ys + (int64_t)t * vy.sn + 16 * ks + 8 * h);
+            if (MODE == 1) {
+              bf16x8 o;
+#pragma unroll
+              for (int q = 0; q < 8; ++q) o[q] = (__bf16)(bf16_to_f32(raw[q]) * inv);
+              yb[ti][ks] = o;
+            } else {
+              yb[ti][ks] = __builtin_bit_cast(bf16x8, raw);
+            }
+          }
+          bf16x8 ext = splat_bf16x8(0.f);
+          if (h == 0) ext[0] = (__bf16)at;
+          yb[ti][KS] = ext;
+        }
+      }
+    }
+
+    f32x16 acc0[2][CT];   // N (MODE 0) or dX_F (MODE 1, 2): rows on registers, columns on lanes
+    f32x16 acc1[2][CT];   // dV (MODE 2)
+    float dacc[2] = {0.f, 0.f};   // D partial of this lane's row (MODE 0)
 #pragma unroll
     for (int ti = 0; ti < 2; ++ti)
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
-        xb[ti][ks] = *reinterpret_cast<const f16x8 *>(xs + (int64_t)(32 * ti + l32) * DH + 16 * ks + 8 * h);
-    if (MODE != 0) {
-      const bf16_t *ys = y + vy.slice_base(slice);
-#pragma unroll
-      for (int ti = 0; ti < 2; ++ti) {
-        const int t = t0 + 32 * ti + l32;
-        float inv = 1.0f;
-        if (MODE == 1) {
-          inv = 1.0f / Dsaved[(int64_t)slice * n + t];
-          arow_l[ti] = arow[(int64_t)slice * n + t];
-        } else {
-          arow_l[ti] = 1.0f;
-        }
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          const u16x8 raw = *reinterpret_cast<const u16x8 *>(ys + (int64_t)t * vy.sn + 16 * ks + 8 * h);
-          bf16x8 o;
-#pragma unroll
-          for (int q = 0; q < 8; ++q) {
-            const float f = bf16_to_f32(raw[q]);
-            o[q] = (__bf16)(MODE == 1 ? f * inv : f);
-          }
-          yb[ti][ks] = o;
-        }
+      for (int ct = 0; ct < CT; ++ct) {
+        acc0[ti][ct] = zero16();
+        if (MODE == 2) acc1[ti][ct] = zero16();
       }
-    }
-  }
 
-  f32x16 acc0[2][CT];   // N (MODE 0) or dX_F (MODE 1, 2): rows on registers, columns on lanes
-  f32x16 acc1[2][CT];   // dV (MODE 2)
-  float dacc[2] = {0.f, 0.f};   // D partial of this lane's row (MODE 0)
-#pragma unroll
-  for (int ti = 0; ti < 2; ++ti)
-#pragma unroll
-    for (int ct = 0; ct < CT; ++ct) {
-      acc0[ti][ct] = zero16();
-      if (MODE == 2) acc1[ti][ct] = zero16();
-    }
-
-  for (int m0 = 0; m0 < m; m0 += mc) {
-    __syncthreads();
-    // ---- stage the feature-side operands of features [m0, m0 + mc) -------------------
-    {
-      const int chunks_per_row = DH / 8;
-      for (int e = tid; e < mc * chunks_per_row; e += kRowsWaves * 64) {
-        const int r = e / chunks_per_row, cc = e % chunks_per_row;
-        *reinterpret_cast<u16x8 *>(&s_omT[r * AS + cc * 8]) =
-            *reinterpret_cast<const u16x8 *>(omT + (int64_t)(m0 + r) * DH + cc * 8);
-        if (MODE != 0)
-          *reinterpret_cast<u16x8 *>(&s_Mb[r * AS + cc * 8]) =
-              *reinterpret_cast<const u16x8 *>(Mb + ((int64_t)slice * m + m0 + r) * DH + cc * 8);
+    for (int m0 = 0; m0 < m; m0 += mc) {
+      if (nchunks > 1) {
+        __syncthreads();
+        stage(m0);
+        __syncthreads();
       }
-      const int chunks_per_col = mc / 4;   // 8-byte pieces: the padded stride is only 8-byte aligned
-      for (int e = tid; e < DH * chunks_per_col; e += kRowsWaves * 64) {
-        const int cidx = e / chunks_per_col, cc = e % chunks_per_col;
-        if (MODE != 1)
-          *reinterpret_cast<bf16x4 *>(&s_MbT[cidx * BS + cc * 4]) =
-              *reinterpret_cast<const bf16x4 *>(MbT + ((int64_t)slice * DH + cidx) * m + m0 + cc * 4);
-        if (MODE != 0)
-          *reinterpret_cast<bf16x4 *>(&s_om[cidx * BS + cc * 4]) =
-              *reinterpret_cast<const bf16x4 *>(omega + (int64_t)cidx * m + m0 + cc * 4);
-      }
-      for (int e = tid; e < mc; e += kRowsWaves * 64) s_b[e] = bvec[(int64_t)slice * m + m0 + e];
-    }
-    __syncthreads();
-    if (!active) continue;
+      if (!active) continue;
 
-    for (int rt = 0; rt < mc / 32; ++rt) {
-      f16x8 oa[KS];     // Omega^T rows of this feature tile: A operand of the projection
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
-        oa[ks] = *reinterpret_cast<const f16x8 *>(&s_omT[(32 * rt + l32) * AS + 16 * ks + 8 * h]);
-      bf16x8 ma[KS];    // S / dS rows of this feature tile: A operand of the dPhi MFMA
-      if (MODE != 0) {
+      for (int rt = 0; rt < mc / 32; ++rt) {
+        f16x8 oa[KS];     // Omega^T rows of this feature tile: A operand of the projection
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-          ma[ks] = *reinterpret_cast<const bf16x8 *>(&s_Mb[(32 * rt + l32) * AS + 16 * ks + 8 * h]);
-      }
-      float bv[16];     // z / dz of the features on this lane's accumulator rows
+          oa[ks] = *reinterpret_cast<const f16x8 *>(&s_omT[(32 * rt + l32) * AS + 16 * ks + 8 * h]);
+        bf16x8 ma[KSX];   // (M | b) rows of this feature tile: A operand of the dPhi MFMA
+        if (MODE != 0) {
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const f32x4 b4 = *reinterpret_cast<const f32x4 *>(&s_b[32 * rt + 8 * g + 4 * h]);
+          for (int ks = 0; ks < KSX; ++ks)
+            ma[ks] = *reinterpret_cast<const bf16x8 *>(&s_Mx[(32 * rt + l32) * AM + 16 * ks + 8 * h]);
+        }
 #pragma unroll
-        for (int q = 0; q < 4; ++q) bv[4 * g + q] = b4[q];
-      }
+        for (int ti = 0; ti < 2; ++ti) {
+          f32x16 R = zero16();
 #pragma unroll
-      for (int ti = 0; ti < 2; ++ti) {
-        f32x16 R = zero16();
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) R = mfma_f16(oa[ks], xb[ti][ks], R);
-        if (MODE == 0) {
-          float ds = 0.f;
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            R[i] = fmaxf(R[i], 0.f);
-            ds = fmaf(R[i], bv[i], ds);
-          }
-          dacc[ti] += ds;
-#pragma unroll
-          for (int a = 0; a < 2; ++a) {
-            const bf16x8 pa = pack_half(R, a);
-#pragma unroll
-            for (int ct = 0; ct < CT; ++ct) {
-              const bf16x8 sb = lds_perm8(&s_MbT[(32 * ct + l32) * BS], 32 * rt + 16 * a, h);
-              acc0[ti][ct] = mfma_bf16(pa, sb, acc0[ti][ct]);
-            }
-          }
-        } else {
-          f32x16 G = zero16();
-#pragma unroll
-          for (int ks = 0; ks < KS; ++ks) G = mfma_bf16(ma[ks], yb[ti][ks], G);
-#pragma unroll
-          for (int i = 0; i < 16; ++i) G[i] = R[i] > 0.f ? fmaf(arow_l[ti], bv[i], G[i]) : 0.f;
-#pragma unroll
-          for (int a = 0; a < 2; ++a) {
-            const bf16x8 pg = pack_half(G, a);
-#pragma unroll
-            for (int ct = 0; ct < CT; ++ct) {
-              const bf16x8 ob = lds_perm8(&s_om[(32 * ct + l32) * BS], 32 * rt + 16 * a, h);
-              acc0[ti][ct] = mfma_bf16(pg, ob, acc0[ti][ct]);
-            }
-          }
-          if (MODE == 2) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) R[i] = fmaxf(R[i], 0.f);
+          for (int ks = 0; ks < KS; ++ks) R = mfma_f16(oa[ks], xb[ti][ks], R);
+          if (MODE == 0) {
 #pragma unroll
             for (int a = 0; a < 2; ++a) {
-              const bf16x8 pa = pack_half(R, a);
+              const bf16x8 pa = relu_bf16x8(pack_half(R, a));
+              dacc[ti] = dot8_bf16(pa, lds_perm8(s_bb, 32 * rt + 16 * a, h), dacc[ti]);
 #pragma unroll
               for (int ct = 0; ct < CT; ++ct) {
-                const bf16x8 sb = lds_perm8(&s_MbT[(32 * ct + l32) * BS], 32 * rt + 16 * a, h);
-                acc1[ti][ct] = mfma_bf16(pa, sb, acc1[ti][ct]);
+                const bf16x8 sb = lds_perm8(&s_MT[(32 * ct + l32) * BS], 32 * rt + 16 * a, h);
+                acc0[ti][ct] = mfma_bf16(pa, sb, acc0[ti][ct]);
+              }
+            }
+          } else {
+            f32x16 G = zero16();
+#pragma unroll
+            for (int ks = 0; ks < KSX; ++ks) G = mfma_bf16(ma[ks], yb[ti][ks], G);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) G[i] = R[i] > 0.f ? G[i] : 0.f;
+#pragma unroll
+            for (int a = 0; a < 2; ++a) {
+              const bf16x8 pg = pack_half(G, a);
+#pragma unroll
+              for (int ct = 0; ct < CT; ++ct) {
+                const bf16x8 ob = lds_perm8(&s_om[(32 * ct + l32) * BS], 32 * rt + 16 * a, h);
+                acc0[ti][ct] = mfma_bf16(pg, ob, acc0[ti][ct]);
+              }
+            }
+            if (MODE == 2) {
+#pragma unroll
+              for (int a = 0; a < 2; ++a) {
+                const bf16x8 pa = relu_bf16x8(pack_half(R, a));
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct) {
+                  const bf16x8 sb = lds_perm8(&s_MT[(32 * ct + l32) * BS], 32 * rt + 16 * a, h);
+                  acc1[ti][ct] = mfma_bf16(pa, sb, acc1[ti][ct]);
+                }
               }
             }
           }
         }
       }
     }
-  }
+    if (!active) continue;
 
-  // ---- epilogues -------------------------------------------------------------------
-  if (MODE == 0) {
-    if (active) {
+    // ---- epilogues -----------------------------------------------------------------
+    if (MODE == 0) {
       float *dl = s_wave + wave * 64;
 #pragma unroll
       for (int ti = 0; ti < 2; ++ti) {
@@ -590,21 +693,24 @@ __global__ __launch_bounds__(kRowsWaves * 64) void rows_kernel(
           for (int ct = 0; ct < CT; ++ct)
             os[(int64_t)(t0 + tl) * vo.sn + 32 * ct + l32] = f32_to_bf16(acc0[ti][ct][i] * inv);
         }
+      continue;
     }
-    return;
-  }
 
-  // MODE 1, 2: gated Haar filter of dX_F on the accumulator layout and band inner products.
-  // Lane (l32, h) holds column 32 ct + l32 and rows 32 ti + 8 g + 4 h + e (g, e = 0..3):
-  //   block sums of 2 and 4 rows are in-lane, 8 rows need the other half-wave (lane ^ 32),
-  //   16 and 32 rows are in-lane again over g, 64 rows over ti.
-  float u[kMaxBands];   // u_l = sum over blocks of bs_l(g) * bs_l(x) / 2^l, this lane's share
+    // MODE 1, 2: gated Haar filter of dX_F on the accumulator layout and band inner products.
+    // Lane (l32, h) holds column 32 ct + l32 and rows 32 ti + 8 g + 4 h + e (g, e = 0..3):
+    //   block sums of 2 and 4 rows are in-lane, 8 rows need the other half-wave (lane ^ 32),
+    //   16 and 32 rows are in-lane again over g, 64 rows over ti.
+    if (MODE == 2) {
+      bf16_t *vs = out1 + vo.slice_base(slice);
 #pragma unroll
-  for (int l = 0; l < kMaxBands; ++l) u[l] = 0.f;
-  if (active) {
-    float cf[kMaxBands];
+      for (int ti = 0; ti < 2; ++ti)
 #pragma unroll
-    for (int l = 0; l < kMaxBands; ++l) cf[l] = coef[slice * 8 + l];
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+          for (int i = 0; i < 16; ++i)
+            vs[(int64_t)(t0 + 32 * ti + acc_row(i, h)) * vo.sn + 32 * ct + l32] =
+                f32_to_bf16(acc1[ti][ct][i] * cscale);
+    }
     const bf16_t *xs = x + vx.slice_base(slice);
     bf16_t *os = out0 + vo.slice_base(slice);
 #pragma unroll
@@ -673,21 +779,12 @@ __global__ __launch_bounds__(kRowsWaves * 64) void rows_kernel(
         }
       }
     }
-    if (MODE == 2) {
-      bf16_t *vs = out1 + vo.slice_base(slice);
-#pragma unroll
-      for (int ti = 0; ti < 2; ++ti)
-#pragma unroll
-        for (int ct = 0; ct < CT; ++ct)
-#pragma unroll
-          for (int i = 0; i < 16; ++i)
-            vs[(int64_t)(t0 + 32 * ti + acc_row(i, h)) * vo.sn + 32 * ct + l32] =
-                f32_to_bf16(acc1[ti][ct][i] * cscale);
-    }
   }
+  if (MODE == 0) return;
+
   // With u_l = <dX_F, P_l X> (P_l = mean over aligned 2^l blocks) the band gradients are
   // dF_L = u_L and dF_{l-1} = u_{l-1} - u_l (l = 1..L); one partial per workgroup.
-  __syncthreads();   // operand arrays are no longer read; reuse s_wave for the reduction
+  __syncthreads();   // operand arrays are no longer read; s_wave is free for the reduction
 #pragma unroll
   for (int l = 0; l < kMaxBands; ++l) {
     const float s = wave_sum64(u[l]) / (float)(1 << l);
@@ -705,29 +802,34 @@ __global__ __launch_bounds__(kRowsWaves * 64) void rows_kernel(
 }
 
 // dD_t = -<dO_t, O_t> / D_t, and per-block partial sums of dD (for d sigma).
+constexpr int kPrepIters = 16;
 template <int DH>
 __global__ __launch_bounds__(256) void prep_bwd_kernel(const bf16_t *dout, const bf16_t *out, View v,
                                                       const float *D, int n, float *dD,
                                                       float *dDpart) {
   constexpr int CPR = DH / 8, RPB = 256 / CPR;
   const int slice = blockIdx.y;
-  const int t = blockIdx.x * RPB + threadIdx.x / CPR, cc = threadIdx.x % CPR;
-  float acc = 0.f;
-  if (t < n) {
-    const int64_t off = v.slice_base(slice) + (int64_t)t * v.sn + cc * 8;
-    const u16x8 a = *reinterpret_cast<const u16x8 *>(dout + off);
-    const u16x8 b = *reinterpret_cast<const u16x8 *>(out + off);
+  const int cc = threadIdx.x % CPR;
+  float total = 0.f;
+  for (int it = 0; it < kPrepIters; ++it) {
+    const int t = (blockIdx.x * kPrepIters + it) * RPB + threadIdx.x / CPR;
+    float acc = 0.f;
+    if (t < n) {
+      const int64_t off = v.slice_base(slice) + (int64_t)t * v.sn + cc * 8;
+      const u16x8 a = *reinterpret_cast<const u16x8 *>(dout + off);
+      const u16x8 b = *reinterpret_cast<const u16x8 *>(out + off);
 #pragma unroll
-    for (int q = 0; q < 8; ++q) acc = fmaf(bf16_to_f32(a[q]), bf16_to_f32(b[q]), acc);
-  }
-  for (int o = CPR / 2; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
-  float val = 0.f;
-  if (t < n && cc == 0) {
-    val = -acc / D[(int64_t)slice * n + t];
-    dD[(int64_t)slice * n + t] = val;
+      for (int q = 0; q < 8; ++q) acc = fmaf(bf16_to_f32(a[q]), bf16_to_f32(b[q]), acc);
+    }
+    for (int o = CPR / 2; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+    if (t < n && cc == 0) {
+      const float val = -acc / D[(int64_t)slice * n + t];
+      dD[(int64_t)slice * n + t] = val;
+      total += val;
+    }
   }
   __shared__ float red[4];
-  const float ws = wave_sum64(val);
+  const float ws = wave_sum64(total);
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ws;
   __syncthreads();
   if (threadIdx.x == 0)
@@ -758,7 +860,9 @@ struct FastPlan {
   int DH, FW, MB, mc;
   int chunksQ, rowsQ;   // pooled-query partial sums
   int chunksC, rowsC;   // split of n in phiT_contract
-  int rowGroups;        // workgroups per slice of the rows kernel
+  int rowGroups;        // 256-row groups per slice in the rows kernel
+  int rowsWgs;          // workgroups per slice of the rows kernel (each walks several groups)
+  int prepBlocks;       // blocks per slice of prep_bwd
 };
 
 FastPlan fast_plan(const wersa_desc &c) {
@@ -778,6 +882,10 @@ FastPlan fast_plan(const wersa_desc &c) {
   p.rowsC = bpc * 64;
   p.chunksC = (blocks + bpc - 1) / bpc;
   p.rowGroups = (blocks + kRowsWaves - 1) / kRowsWaves;
+  int wgs = (512 + slices - 1) / slices;   // about two workgroups per compute unit in total
+  p.rowsWgs = wgs < p.rowGroups ? wgs : p.rowGroups;
+  const int rpb = (256 / (c.d / 8)) * kPrepIters;
+  p.prepBlocks = (c.n + rpb - 1) / rpb;
   return p;
 }
 
@@ -785,7 +893,7 @@ struct FastWs {
   float *scalars, *coef, *qpart, *Spart, *zpart, *dD, *dDpart, *dS, *dz, *partQ, *partK, *dF,
       *dlogit, *dqbar;
   _Float16 *omT;
-  bf16_t *Sb, *SbT, *dSb, *dSbT;
+  bf16_t *Sx, *ST, *zb, *dSx, *dST, *dzb;
   int64_t total;
 };
 
@@ -799,17 +907,20 @@ FastWs fast_ws(const wersa_desc &c, const FastPlan &p, int bwd, float *base) {
   w.omT = reinterpret_cast<_Float16 *>(b.take(md / 2));
   w.Spart = b.take(sl * p.chunksC * md);
   w.zpart = b.take(sl * p.chunksC * c.m);
-  w.Sb = reinterpret_cast<bf16_t *>(b.take(sl * md / 2));
-  w.SbT = reinterpret_cast<bf16_t *>(b.take(sl * md / 2));
+  const int64_t mx = (int64_t)c.m * (c.d + 16);
+  w.Sx = reinterpret_cast<bf16_t *>(b.take(sl * mx / 2));
+  w.ST = reinterpret_cast<bf16_t *>(b.take(sl * md / 2));
+  w.zb = reinterpret_cast<bf16_t *>(b.take(sl * c.m / 2));
   if (bwd) {
     w.dD = b.take(sl * c.n);
-    w.dDpart = b.take(sl * ((c.n + (256 / (c.d / 8)) - 1) / (256 / (c.d / 8))));
+    w.dDpart = b.take(sl * p.prepBlocks);
     w.dS = b.take(sl * md);
     w.dz = b.take(sl * c.m);
-    w.dSb = reinterpret_cast<bf16_t *>(b.take(sl * md / 2));
-    w.dSbT = reinterpret_cast<bf16_t *>(b.take(sl * md / 2));
-    w.partQ = b.take(sl * p.rowGroups * (c.L + 1));
-    w.partK = b.take(sl * p.rowGroups * (c.L + 1));
+    w.dSx = reinterpret_cast<bf16_t *>(b.take(sl * mx / 2));
+    w.dST = reinterpret_cast<bf16_t *>(b.take(sl * md / 2));
+    w.dzb = reinterpret_cast<bf16_t *>(b.take(sl * c.m / 2));
+    w.partQ = b.take(sl * p.rowsWgs * (c.L + 1));
+    w.partK = b.take(sl * p.rowsWgs * (c.L + 1));
     w.dF = b.take(sl * (c.L + 1));
     w.dlogit = b.take(sl * (c.L + 1));
     w.dqbar = b.take(sl * c.d);
@@ -820,19 +931,20 @@ FastWs fast_ws(const wersa_desc &c, const FastPlan &p, int bwd, float *base) {
 
 template <int DH, int MODE>
 size_t rows_smem_bytes(int mc) {
-  const size_t AS = DH + 8, BS = (size_t)mc + 4;
+  const size_t AS = DH + 8, AM = DH + 16 + 8, BS = (size_t)mc + 4;
   size_t s = (size_t)mc * AS * 2;
-  if (MODE != 0) s += (size_t)mc * AS * 2;
+  if (MODE != 0) s += (size_t)mc * AM * 2;
   if (MODE != 1) s += (size_t)DH * BS * 2;
   if (MODE != 0) s += (size_t)DH * BS * 2;
-  s += (size_t)mc * 4 + kRowsWaves * 64 * 4;
+  if (MODE == 0) s += (size_t)mc * 2;
+  s += kRowsWaves * 64 * 4;
   return s;
 }
 
 template <int DH, int MODE>
 hipError_t launch_rows(const wersa_desc &c, const FastPlan &p, const _Float16 *xf, const bf16_t *x,
                        const bf16_t *y, const float *Dsaved, const float *arow, const FastWs &w,
-                       const bf16_t *omega, const bf16_t *Mb, const bf16_t *MbT, const float *bvec,
+                       const bf16_t *omega, const bf16_t *Mx, const bf16_t *MT, const bf16_t *bb,
                        bf16_t *out0, bf16_t *out1, float *Dout, float *partF, hipStream_t st) {
   const View tv{c.stride_b, c.stride_h, c.stride_n, c.H};
   const size_t smem = rows_smem_bytes<DH, MODE>(p.mc);
@@ -841,16 +953,16 @@ hipError_t launch_rows(const wersa_desc &c, const FastPlan &p, const _Float16 *x
   if (e != hipSuccess) return e;
   const char *name = MODE == 0 ? "wersa_rows_fwd" : (MODE == 1 ? "wersa_rows_bwd_q" : "wersa_rows_bwd_k");
   WERSA_STAGE(name, st,
-              rows_kernel<DH, MODE><<<dim3(p.rowGroups, c.B * c.H), kRowsWaves * 64, smem, st>>>(
-                  xf, x, tv, y, tv, Dsaved, arow, w.omT, omega, Mb, MbT, bvec, w.coef, w.scalars,
-                  c.eps, c.n, c.m, p.mc, out0, tv, out1, Dout, partF, c.L));
+              rows_kernel<DH, MODE><<<dim3(p.rowsWgs, c.B * c.H), kRowsWaves * 64, smem, st>>>(
+                  xf, x, tv, y, tv, Dsaved, arow, w.omT, omega, Mx, MT, bb, w.coef, w.scalars, c.eps,
+                  c.n, c.m, p.mc, p.rowGroups, out0, tv, out1, Dout, partF, c.L));
   return hipSuccess;
 }
 
 template <int DH>
 void launch_contract(const wersa_desc &c, const FastPlan &p, const _Float16 *xf, const bf16_t *y,
                      const float *rowdiv, const float *wt, const FastWs &w, float *S, float *z,
-                     bf16_t *Sb, bf16_t *SbT, hipStream_t st) {
+                     bf16_t *Mx, bf16_t *MT, bf16_t *bb, hipStream_t st) {
   const View tv{c.stride_b, c.stride_h, c.stride_n, c.H};
   const int slices = c.B * c.H;
   dim3 grid(p.chunksC, c.m / p.MB, slices);
@@ -865,7 +977,7 @@ void launch_contract(const wersa_desc &c, const FastPlan &p, const _Float16 *xf,
   const int64_t W = (int64_t)c.m * DH;
   WERSA_STAGE("wersa_reduce_contract", st,
               reduce_contract_kernel<DH><<<dim3((unsigned)((W + 255) / 256), slices), 256, 0, st>>>(
-                  w.Spart, w.zpart, p.chunksC, c.m, w.scalars, S, z, Sb, SbT));
+                  w.Spart, w.zpart, p.chunksC, c.m, w.scalars, S, z, Mx, MT, bb));
 }
 
 template <int DH>
@@ -896,8 +1008,8 @@ wersa_status fast_forward_t(const wersa_desc &c, const bf16_t *q, const bf16_t *
               haar_stage_kernel<DH><<<dim3(c.n / 64, slices), 256, 0, st>>>(q, tv, c.n, w.coef, QF));
   WERSA_STAGE("wersa_haar_stage", st,
               haar_stage_kernel<DH><<<dim3(c.n / 64, slices), 256, 0, st>>>(k, tv, c.n, w.coef, KF));
-  launch_contract<DH>(c, p, KF, v, nullptr, nullptr, w, S, z, w.Sb, w.SbT, st);
-  if (launch_rows<DH, 0>(c, p, QF, nullptr, nullptr, nullptr, nullptr, w, omega, nullptr, w.SbT, z, out,
+  launch_contract<DH>(c, p, KF, v, nullptr, nullptr, w, S, z, w.Sx, w.ST, w.zb, st);
+  if (launch_rows<DH, 0>(c, p, QF, nullptr, nullptr, nullptr, nullptr, w, omega, nullptr, w.ST, w.zb, out,
                          nullptr, D, nullptr, st) != hipSuccess)
     return WERSA_ERR_LAUNCH;
   return hipGetLastError() == hipSuccess ? WERSA_OK : WERSA_ERR_LAUNCH;
@@ -919,8 +1031,7 @@ wersa_status fast_backward_t(const wersa_desc &c, const bf16_t *q, const bf16_t 
               *D = saved + sv.D;
   const _Float16 *QF = reinterpret_cast<const _Float16 *>(saved + sv.QF);
   const _Float16 *KF = reinterpret_cast<const _Float16 *>(saved + sv.KF);
-  constexpr int RPB = 256 / (DH / 8);
-  const int prepBlocks = (c.n + RPB - 1) / RPB;
+  const int prepBlocks = p.prepBlocks;
 
   WERSA_STAGE("scalars_kernel", st, scalars_kernel<<<1, 64, 0, st>>>(sigma, c.bw_floor, c.m, w.scalars));
   WERSA_STAGE("omega_t_kernel", st,
@@ -929,19 +1040,19 @@ wersa_status fast_backward_t(const wersa_desc &c, const bf16_t *q, const bf16_t 
   // S as bf16 MFMA operand (row-major) from the saved float32 S: a reduce over one "partial"
   WERSA_STAGE("wersa_reduce_contract", st,
               reduce_contract_kernel<DH><<<dim3((unsigned)(((int64_t)c.m * DH + 255) / 256), slices), 256, 0, st>>>(
-                  saved + sv.S, z, 1, c.m, w.scalars + 3, w.dS, w.dz, w.Sb, w.SbT));
+                  saved + sv.S, z, 1, c.m, w.scalars + 3, w.dS, w.dz, w.Sx, w.ST, w.zb));
   WERSA_STAGE("wersa_prep_bwd", st,
               prep_bwd_kernel<DH><<<dim3(prepBlocks, slices), 256, 0, st>>>(dout, out, tv, D, c.n, w.dD, w.dDpart));
   // dX_F of the Q side needs only S, z; dS, dz need the full reduction over n first.
-  if (launch_rows<DH, 1>(c, p, QF, q, dout, D, w.dD, w, omega, w.Sb, nullptr, z, dq, nullptr, nullptr,
+  if (launch_rows<DH, 1>(c, p, QF, q, dout, D, w.dD, w, omega, w.Sx, nullptr, nullptr, dq, nullptr, nullptr,
                          w.partQ, st) != hipSuccess)
     return WERSA_ERR_LAUNCH;
-  launch_contract<DH>(c, p, QF, dout, D, w.dD, w, w.dS, w.dz, w.dSb, w.dSbT, st);
-  if (launch_rows<DH, 2>(c, p, KF, k, v, nullptr, nullptr, w, omega, w.dSb, w.dSbT, w.dz, dk, dv, nullptr,
+  launch_contract<DH>(c, p, QF, dout, D, w.dD, w, w.dS, w.dz, w.dSx, w.dST, w.dzb, st);
+  if (launch_rows<DH, 2>(c, p, KF, k, v, nullptr, nullptr, w, omega, w.dSx, w.dST, nullptr, dk, dv, nullptr,
                          w.partK, st) != hipSuccess)
     return WERSA_ERR_LAUNCH;
   WERSA_STAGE("gate_bwd_slice_kernel", st,
-              gate_bwd_slice_kernel<<<slices, 64, 0, st>>>(w.partQ, w.partK, p.rowGroups, c.L, c.d, c.H, s,
+              gate_bwd_slice_kernel<<<slices, 64, 0, st>>>(w.partQ, w.partK, p.rowsWgs, c.L, c.d, c.H, s,
                                                            gate_w, scale_w, w.dF, w.dlogit, w.dqbar));
   WERSA_STAGE("gate_bwd_params_kernel", st,
               gate_bwd_params_kernel<<<1, 256, 0, st>>>(w.dF, w.dlogit, s, qbar, w.dDpart, slices * prepBlocks,

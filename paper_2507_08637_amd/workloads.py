@@ -45,6 +45,8 @@ def make_inputs(B, H, n, d, L, m, dtype="f32", flavour="plain", seed_base=0, q_m
              "spikes"   as plain, then an independent Bernoulli(0.05) mask per entry
                         multiplies the entry by 10
              "sinusoid" as plain, then K[t, :] += sin(2 pi t / 4096)
+             "smooth"   Q, K = 0.5 N(0,1) + 1.5 sin(2 pi t / 256), V = 0.3 N(0,1) + sin(2 pi t / 256):
+                        a shared low-frequency component, so that the wavelet scales carry signal
     q_mean shifts Q so that the pooled-query path carries signal.
     """
     def rng(name):
@@ -62,6 +64,10 @@ def make_inputs(B, H, n, d, L, m, dtype="f32", flavour="plain", seed_base=0, q_m
         if flavour == "sinusoid" and name == "K":
             t = np.arange(n, dtype=np.float64)
             x = x + np.sin(2.0 * np.pi * t / 4096.0).astype(np.float32)[None, None, :, None]
+        if flavour == "smooth":
+            t = np.arange(n, dtype=np.float64)
+            wave = np.sin(2.0 * np.pi * t / 256.0).astype(np.float32)[None, None, :, None]
+            x = (np.float32(0.3) * x + wave) if name == "V" else (np.float32(0.5) * x + np.float32(1.5) * wave)
         if name == "Q" and q_mean != 0.0:
             x = x + np.float32(q_mean)
         out[name] = _round(x, dtype)
