@@ -75,20 +75,39 @@ __device__ __forceinline__ bf16x8 lds_perm8(const bf16_t *row, int base, int h) 
 // 2^l block), coef_0 = F_0, coef_l = (F_l - F_{l-1}) / 2^l  (l = 1..L), 0 above L.
 // Also Omega^T in fp16 ([m][d]) for the projection's MFMA operand.
 // ------------------------------------------------------------------------------------
-__global__ void coef_kernel(const float *F, int L, int slices, float *coef) {
-  const int s = blockIdx.x * blockDim.x + threadIdx.x;
-  if (s >= slices) return;
+__device__ __forceinline__ void coef_of_slice(const float *F, int L, int s, float *coef) {
   const float *f = F + s * (L + 1);
   float *c = coef + s * 8;
   c[0] = f[0];
   for (int l = 1; l <= kMaxL; ++l) c[l] = l <= L ? (f[l] - f[l - 1]) / (float)(1 << l) : 0.f;
   c[7] = 0.f;
 }
-__global__ void omega_t_kernel(const bf16_t *omega, int d, int m, _Float16 *omT) {
+__global__ void coef_kernel(const float *F, int L, int slices, float *coef) {
+  const int s = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s < slices) coef_of_slice(F, L, s, coef);
+}
+// One launch for the per-call constants: block 0 writes the scalars (and, in the backward where
+// F is already known, the filter coefficients); every block transposes its share of Omega.
+__global__ void setup_kernel(const float *sigma, float bw_floor, const bf16_t *omega, int d, int m,
+                             const float *F, int L, int slices, float *scalars, float *coef,
+                             _Float16 *omT) {
+  if (blockIdx.x == 0) {
+    if (threadIdx.x == 0) {
+      const float s = *sigma;
+      const float se = fmaxf(s, bw_floor);
+      scalars[0] = 1.0f / (se * sqrtf((float)m));
+      scalars[1] = se;
+      scalars[2] = s > bw_floor ? 1.0f : 0.0f;
+      scalars[3] = 1.0f;
+    }
+    if (F)
+      for (int s = threadIdx.x; s < slices; s += blockDim.x) coef_of_slice(F, L, s, coef);
+  }
   const int e = blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= d * m) return;
-  const int r = e / d, j = e % d;
-  omT[e] = (_Float16)bf16_to_f32(omega[(int64_t)j * m + r]);
+  if (e < d * m) {
+    const int r = e / d, j = e % d;
+    omT[e] = (_Float16)bf16_to_f32(omega[(int64_t)j * m + r]);
+  }
 }
 
 // ------------------------------------------------------------------------------------
@@ -106,7 +125,17 @@ __global__ __launch_bounds__(256) void qbar_partial_kernel(const bf16_t *q, View
   float acc[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-  for (int t = t0 + rr; t < t1; t += RPI) {
+  int t = t0 + rr;
+  for (; t + 3 * RPI < t1; t += 4 * RPI) {   // four independent loads in flight
+    u16x8 x[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) x[u] = *reinterpret_cast<const u16x8 *>(qs + (int64_t)(t + u * RPI) * v.sn);
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] += bf16_to_f32(x[u][e]);
+  }
+  for (; t < t1; t += RPI) {
     const u16x8 x = *reinterpret_cast<const u16x8 *>(qs + (int64_t)t * v.sn);
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] += bf16_to_f32(x[e]);
@@ -394,7 +423,15 @@ __global__ void reduce_contract_kernel(const float *Spart, const float *zpart, i
   if (e < W) {
     const float *p = Spart + (int64_t)slice * chunks * W + e;
     float acc = 0.f;
-    for (int c = 0; c < chunks; ++c) acc += p[(int64_t)c * W];
+    int c = 0;
+    for (; c + 8 <= chunks; c += 8) {   // eight independent loads in flight, fixed summation order
+      float v8[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v8[u] = p[(int64_t)(c + u) * W];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) acc += v8[u];
+    }
+    for (; c < chunks; ++c) acc += p[(int64_t)c * W];
     acc *= scale;
     S[(int64_t)slice * W + e] = acc;
     const int r = (int)(e / DH), cidx = (int)(e % DH);
@@ -836,22 +873,36 @@ __global__ __launch_bounds__(256) void prep_bwd_kernel(const bf16_t *dout, const
     dDpart[(int64_t)slice * gridDim.x + blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
-// dQ[t][:] += dqbar / n  (the pooled-query path), bf16 read-modify-write with 16-byte accesses.
+// dQ[t][:] += dqbar / n  (the pooled-query path), bf16 read-modify-write with 16-byte accesses,
+// four independent pieces per thread.
 template <int DH>
-__global__ void add_pooled_kernel(bf16_t *dq, View v, const float *dqbar, int n, float inv_n) {
+__global__ __launch_bounds__(256) void add_pooled_kernel(bf16_t *dq, View v, const float *dqbar, int n,
+                                                        float inv_n) {
   constexpr int CPR = DH / 8;
   const int slice = blockIdx.y;
-  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= (int64_t)n * CPR) return;
-  const int t = (int)(e / CPR), cc = (int)(e % CPR);
-  bf16_t *p = dq + v.slice_base(slice) + (int64_t)t * v.sn + cc * 8;
-  u16x8 val = *reinterpret_cast<u16x8 *>(p);
+  const int64_t total = (int64_t)n * CPR;
+  const int64_t e0 = (int64_t)blockIdx.x * 1024 + threadIdx.x;
+  const int cc = threadIdx.x % CPR;   // 256 and 1024 are multiples of CPR: same columns for all four
+  float add[8];
 #pragma unroll
-  for (int q = 0; q < 8; ++q)
-    val[q] = f32_to_bf16(bf16_to_f32(val[q]) + dqbar[(int64_t)slice * DH + cc * 8 + q] * inv_n);
-  *reinterpret_cast<u16x8 *>(p) = val;
+  for (int q = 0; q < 8; ++q) add[q] = dqbar[(int64_t)slice * DH + cc * 8 + q] * inv_n;
+  bf16_t *base = dq + v.slice_base(slice) + cc * 8;
+  u16x8 val[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int64_t e = e0 + 256 * u;
+    if (e < total) val[u] = *reinterpret_cast<u16x8 *>(base + (e / CPR) * v.sn);
+  }
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int64_t e = e0 + 256 * u;
+    if (e < total) {
+#pragma unroll
+      for (int q = 0; q < 8; ++q) val[u][q] = f32_to_bf16(bf16_to_f32(val[u][q]) + add[q]);
+      *reinterpret_cast<u16x8 *>(base + (e / CPR) * v.sn) = val[u];
+    }
+  }
 }
-
 
 // ---------------------------------------------------------------------------------------
 // host side
@@ -995,9 +1046,9 @@ wersa_status fast_forward_t(const wersa_desc &c, const bf16_t *q, const bf16_t *
   _Float16 *QF = reinterpret_cast<_Float16 *>(saved + sv.QF);
   _Float16 *KF = reinterpret_cast<_Float16 *>(saved + sv.KF);
 
-  WERSA_STAGE("scalars_kernel", st, scalars_kernel<<<1, 64, 0, st>>>(sigma, c.bw_floor, c.m, w.scalars));
-  WERSA_STAGE("omega_t_kernel", st,
-              omega_t_kernel<<<(c.d * c.m + 255) / 256, 256, 0, st>>>(omega, c.d, c.m, w.omT));
+  WERSA_STAGE("wersa_setup", st,
+              setup_kernel<<<(c.d * c.m + 255) / 256, 256, 0, st>>>(sigma, c.bw_floor, omega, c.d, c.m, nullptr,
+                                                                    c.L, slices, w.scalars, w.coef, w.omT));
   WERSA_STAGE("wersa_qbar", st,
               qbar_partial_kernel<DH><<<dim3(p.chunksQ, slices), 256, 0, st>>>(q, tv, c.n, p.rowsQ, w.qpart));
   WERSA_STAGE("gate_fwd_kernel", st,
@@ -1033,10 +1084,9 @@ wersa_status fast_backward_t(const wersa_desc &c, const bf16_t *q, const bf16_t 
   const _Float16 *KF = reinterpret_cast<const _Float16 *>(saved + sv.KF);
   const int prepBlocks = p.prepBlocks;
 
-  WERSA_STAGE("scalars_kernel", st, scalars_kernel<<<1, 64, 0, st>>>(sigma, c.bw_floor, c.m, w.scalars));
-  WERSA_STAGE("omega_t_kernel", st,
-              omega_t_kernel<<<(c.d * c.m + 255) / 256, 256, 0, st>>>(omega, c.d, c.m, w.omT));
-  WERSA_STAGE("coef_kernel", st, coef_kernel<<<(slices + 63) / 64, 64, 0, st>>>(F, c.L, slices, w.coef));
+  WERSA_STAGE("wersa_setup", st,
+              setup_kernel<<<(c.d * c.m + 255) / 256, 256, 0, st>>>(sigma, c.bw_floor, omega, c.d, c.m, F, c.L,
+                                                                    slices, w.scalars, w.coef, w.omT));
   // S as bf16 MFMA operand (row-major) from the saved float32 S: a reduce over one "partial"
   WERSA_STAGE("wersa_reduce_contract", st,
               reduce_contract_kernel<DH><<<dim3((unsigned)(((int64_t)c.m * DH + 255) / 256), slices), 256, 0, st>>>(
@@ -1060,7 +1110,7 @@ wersa_status fast_backward_t(const wersa_desc &c, const bf16_t *q, const bf16_t 
                                                         dgate_b, dscale_w, dsigma));
   const int64_t chunks = (int64_t)c.n * (DH / 8);
   WERSA_STAGE("wersa_add_pooled", st,
-              add_pooled_kernel<DH><<<dim3((unsigned)((chunks + 255) / 256), slices), 256, 0, st>>>(
+              add_pooled_kernel<DH><<<dim3((unsigned)((chunks + 1023) / 1024), slices), 256, 0, st>>>(
                   dq, tv, w.dqbar, c.n, 1.0f / (float)c.n));
   return hipGetLastError() == hipSuccess ? WERSA_OK : WERSA_ERR_LAUNCH;
 }
