@@ -267,6 +267,10 @@ __device__ __forceinline__ float dot8_bf16(bf16x8 p, bf16x8 w, float acc) {
   }
   return acc;
 }
+// float32 -> bf16 storage with the hardware conversion (round to nearest even)
+__device__ __forceinline__ bf16_t cvt_bf16(float f) {
+  return __builtin_bit_cast(bf16_t, (__bf16)f);
+}
 __device__ __forceinline__ bf16x8 splat_bf16x8(float v) {
   bf16x8 r;
 #pragma unroll
@@ -284,7 +288,7 @@ __device__ __forceinline__ bf16x8 splat_bf16x8(float v) {
 // t runs along the operand's k index); the next tile is fetched while the current one is used.
 // ------------------------------------------------------------------------------------
 template <int DH, int FW>
-__global__ __launch_bounds__(256) void phiT_contract_kernel(
+__global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
     const _Float16 *xf, const bf16_t *y, View vy, const float *rowdiv, const float *w,
     const _Float16 *omT, int n, int m, int rows_per_chunk, float *Spart, float *zpart) {
   constexpr int KS = DH / 16;   // k-steps of the projection
@@ -324,16 +328,19 @@ __global__ __launch_bounds__(256) void phiT_contract_kernel(
   const float *rd = rowdiv ? rowdiv + (int64_t)slice * n : nullptr;
   const float *ws = w ? w + (int64_t)slice * n : nullptr;
 
+  // X_F pieces are taken row-major (coalesced); Y pieces one row per lane (piece index from the
+  // wave), so that the transposing LDS writes of a wave hit 64 consecutive 2-byte slots.
   u16x8 yr[LPT], xr[LPT];
-  float inv[LPT], wv = 1.0f;
+  float inv = 1.0f, wv = 1.0f;
+  const int yrow = tid & 63, ypiece0 = tid >> 6;
   auto fetch = [&](int t0) {
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
       const int e = tid + 256 * i, r = e / CPR, cc = e % CPR;
-      yr[i] = *reinterpret_cast<const u16x8 *>(ys + (int64_t)(t0 + r) * vy.sn + cc * 8);
       xr[i] = *reinterpret_cast<const u16x8 *>(xs + (int64_t)(t0 + r) * DH + cc * 8);
-      inv[i] = rd ? 1.0f / rd[t0 + r] : 1.0f;
+      yr[i] = *reinterpret_cast<const u16x8 *>(ys + (int64_t)(t0 + yrow) * vy.sn + (ypiece0 + 4 * i) * 8);
     }
+    inv = rd ? 1.0f / rd[t0 + yrow] : 1.0f;
     if (tid < 64) wv = ws ? ws[t0 + tid] : 1.0f;
   };
   auto stash = [&](int buf) {
@@ -341,16 +348,17 @@ __global__ __launch_bounds__(256) void phiT_contract_kernel(
     for (int i = 0; i < LPT; ++i) {
       const int e = tid + 256 * i, r = e / CPR, cc = e % CPR;
       *reinterpret_cast<u16x8 *>(&xt[buf][r * XS + cc * 8]) = xr[i];
+      const int c0 = (ypiece0 + 4 * i) * 8;
       if (rd) {
 #pragma unroll
         for (int q = 0; q < 8; ++q)
-          yt[buf][(cc * 8 + q) * YS + r] = f32_to_bf16(bf16_to_f32(yr[i][q]) * inv[i]);
+          yt[buf][(c0 + q) * YS + yrow] = cvt_bf16(bf16_to_f32(yr[i][q]) * inv);
       } else {
 #pragma unroll
-        for (int q = 0; q < 8; ++q) yt[buf][(cc * 8 + q) * YS + r] = yr[i][q];
+        for (int q = 0; q < 8; ++q) yt[buf][(c0 + q) * YS + yrow] = yr[i][q];
       }
     }
-    if (tid < 64) wl[buf][tid] = f32_to_bf16(wv);
+    if (tid < 64) wl[buf][tid] = cvt_bf16(wv);
   };
 
   if (steps > 0) {
@@ -468,10 +476,9 @@ __global__ void reduce_contract_kernel(const float *Spart, const float *zpart, i
 // Backward epilogue: dX = gated Haar filter of dX_F (block-mean form on the accumulator
 // layout, rows on registers), per-band inner products with X for dF, bf16 stores.
 // ------------------------------------------------------------------------------------
-constexpr int kRowsWaves = 4;
 
-template <int DH, int MODE>
-__global__ __launch_bounds__(kRowsWaves * 64, MODE == 0 ? 2 : 1) void rows_kernel(
+template <int DH, int MODE, int NW>
+__global__ __launch_bounds__(NW * 64, 2) void rows_kernel(
     const _Float16 *xf,        // X_F fp16 [slices][n][DH]
     const bf16_t *x, View vx,  // X (Q or K), for the band inner products (MODE 1, 2)
     const bf16_t *y, View vy,  // dO (MODE 1) or V (MODE 2)
@@ -480,12 +487,11 @@ __global__ __launch_bounds__(kRowsWaves * 64, MODE == 0 ? 2 : 1) void rows_kerne
     const _Float16 *omT,       // Omega^T fp16 [m][DH]
     const bf16_t *omega,       // Omega bf16 [DH][m]
     const bf16_t *Mx,          // (S | z) (MODE 1) / (dS | dz) (MODE 2), bf16 [slices][m][DH+16]
-    const bf16_t *MT,          // S^T (MODE 0) / dS^T (MODE 2), bf16 [slices][DH][m]
+    const bf16_t *MT,          // S^T (MODE 0) / dS^T (MODE 3), bf16 [slices][DH][m]
     const bf16_t *bb,          // z bf16 [slices][m] (MODE 0)
     const float *coef,         // filter coefficients [slices][8]
     const float *scalars, float eps, int n, int m, int mc, int row_groups,
-    bf16_t *out0, View vo,     // O (MODE 0) / dQ or dK (MODE 1, 2)
-    bf16_t *out1,              // dV (MODE 2)
+    bf16_t *out0, View vo,     // O (MODE 0) / dQ or dK (MODE 1, 2) / dV (MODE 3)
     float *Dout,               // D (MODE 0)
     float *partF, int L)       // [slices][gridDim.x][L+1] band partials (MODE 1, 2)
 {
@@ -493,17 +499,21 @@ __global__ __launch_bounds__(kRowsWaves * 64, MODE == 0 ? 2 : 1) void rows_kerne
   constexpr int KSX = KS + 1;           // k-steps of the dPhi MFMA incl. the rank-one extension
   constexpr int AS = DH + 8;            // stride of the [feature][DH] fp16 array (16-byte reads)
   constexpr int AM = DH + 16 + 8;       // stride of the [feature][DH+16] bf16 array
-  constexpr int NT = kRowsWaves * 64;
+  constexpr int NT = NW * 64;
+  constexpr bool IS_GRAD = (MODE == 1 || MODE == 2);
+  constexpr bool IS_APPLY = (MODE == 0 || MODE == 3);
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   const int BS = mc + 4;                // stride of [DH][feature] arrays (8-byte permuted reads)
   _Float16 *s_omT = reinterpret_cast<_Float16 *>(smem_raw);                 // [mc][AS]
   unsigned char *p = smem_raw + (size_t)mc * AS * 2;
   bf16_t *s_Mx = nullptr, *s_MT = nullptr, *s_om = nullptr, *s_bb = nullptr;
-  if (MODE != 0) { s_Mx = reinterpret_cast<bf16_t *>(p); p += (size_t)mc * AM * 2; }   // [mc][AM]
-  if (MODE != 1) { s_MT = reinterpret_cast<bf16_t *>(p); p += (size_t)DH * BS * 2; }   // [DH][BS]
-  if (MODE != 0) { s_om = reinterpret_cast<bf16_t *>(p); p += (size_t)DH * BS * 2; }   // [DH][BS]
+  if (IS_GRAD) { s_Mx = reinterpret_cast<bf16_t *>(p); p += (size_t)mc * AM * 2; }   // [mc][AM]
+  if (IS_APPLY) { s_MT = reinterpret_cast<bf16_t *>(p); p += (size_t)DH * BS * 2; }   // [DH][BS]
+  if (IS_GRAD) { s_om = reinterpret_cast<bf16_t *>(p); p += (size_t)DH * BS * 2; }   // [DH][BS]
   if (MODE == 0) { s_bb = reinterpret_cast<bf16_t *>(p); p += (size_t)mc * 2; }        // [mc]
-  float *s_wave = reinterpret_cast<float *>(p);                                        // [waves][64]
+  float *s_wave = reinterpret_cast<float *>(p); p += (size_t)NW * 64 * 4;              // [waves][64]
+  constexpr int TS = 36;                // row stride (elements) of the per-wave 64 x 32 epilogue tile
+  bf16_t *s_tile = reinterpret_cast<bf16_t *>(p);                                      // [waves][64][TS] (grad)
 
   const int slice = blockIdx.y;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
@@ -527,7 +537,7 @@ __global__ __launch_bounds__(kRowsWaves * 64, MODE == 0 ? 2 : 1) void rows_kerne
         if (e < mc * CPRX) *reinterpret_cast<u16x8 *>(&s_omT[(e / CPRX) * AS + (e % CPRX) * 8]) = tmp[u];
       }
     }
-    if (MODE != 0) {
+    if (IS_GRAD) {
       for (int e0 = 0; e0 < mc * CPRM; e0 += NT * 4) {
         u16x8 tmp[4];
 #pragma unroll
@@ -552,9 +562,9 @@ __global__ __launch_bounds__(kRowsWaves * 64, MODE == 0 ? 2 : 1) void rows_kerne
         const int e = e0 + NT * u + tid;
         if (e < DH * cpc) {
           const int cidx = e / cpc, cc = e % cpc;
-          if (MODE != 1)
+          if (IS_APPLY)
             t1[u] = *reinterpret_cast<const bf16x4 *>(MT + ((int64_t)slice * DH + cidx) * m + m0 + cc * 4);
-          if (MODE != 0) t2[u] = *reinterpret_cast<const bf16x4 *>(omega + (int64_t)cidx * m + m0 + cc * 4);
+          if (IS_GRAD) t2[u] = *reinterpret_cast<const bf16x4 *>(omega + (int64_t)cidx * m + m0 + cc * 4);
         }
       }
 #pragma unroll
@@ -562,8 +572,8 @@ __global__ __launch_bounds__(kRowsWaves * 64, MODE == 0 ? 2 : 1) void rows_kerne
         const int e = e0 + NT * u + tid;
         if (e < DH * cpc) {
           const int cidx = e / cpc, cc = e % cpc;
-          if (MODE != 1) *reinterpret_cast<bf16x4 *>(&s_MT[cidx * BS + cc * 4]) = t1[u];
-          if (MODE != 0) *reinterpret_cast<bf16x4 *>(&s_om[cidx * BS + cc * 4]) = t2[u];
+          if (IS_APPLY) *reinterpret_cast<bf16x4 *>(&s_MT[cidx * BS + cc * 4]) = t1[u];
+          if (IS_GRAD) *reinterpret_cast<bf16x4 *>(&s_om[cidx * BS + cc * 4]) = t2[u];
         }
       }
     }
@@ -575,7 +585,7 @@ __global__ __launch_bounds__(kRowsWaves * 64, MODE == 0 ? 2 : 1) void rows_kerne
 #pragma unroll
   for (int l = 0; l < kMaxBands; ++l) u[l] = 0.f;
   float cf[kMaxBands];
-  if (MODE != 0) {
+  if (IS_GRAD) {
 #pragma unroll
     for (int l = 0; l < kMaxBands; ++l) cf[l] = coef[slice * 8 + l];
   }
@@ -586,7 +596,7 @@ __global__ __launch_bounds__(kRowsWaves * 64, MODE == 0 ? 2 : 1) void rows_kerne
   }
 
   for (int rg = blockIdx.x; rg < row_groups; rg += gridDim.x) {
-    const int t0 = (rg * kRowsWaves + wave) * 64;
+    const int t0 = (rg * NW + wave) * 64;
     const bool active = t0 < n;
 
     // ---- per-wave row-side operands ------------------------------------------------
@@ -599,7 +609,7 @@ __global__ __launch_bounds__(kRowsWaves * 64, MODE == 0 ? 2 : 1) void rows_kerne
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
           xb[ti][ks] = *reinterpret_cast<const f16x8 *>(xs + (int64_t)(32 * ti + l32) * DH + 16 * ks + 8 * h);
-      if (MODE != 0) {
+      if (IS_GRAD) {
         const bf16_t *ys = y + vy.slice_base(slice);
 #pragma unroll
         for (int ti = 0; ti < 2; ++ti) {
@@ -628,16 +638,12 @@ __global__ __launch_bounds__(kRowsWaves * 64, MODE == 0 ? 2 : 1) void rows_kerne
       }
     }
 
-    f32x16 acc0[2][CT];   // N (MODE 0) or dX_F (MODE 1, 2): rows on registers, columns on lanes
-    f32x16 acc1[2][CT];   // dV (MODE 2)
+    f32x16 acc0[2][CT];   // N, dV (MODE 0, 3) or dX_F (MODE 1, 2): rows on registers, columns on lanes
     float dacc[2] = {0.f, 0.f};   // D partial of this lane's row (MODE 0)
 #pragma unroll
     for (int ti = 0; ti < 2; ++ti)
 #pragma unroll
-      for (int ct = 0; ct < CT; ++ct) {
-        acc0[ti][ct] = zero16();
-        if (MODE == 2) acc1[ti][ct] = zero16();
-      }
+      for (int ct = 0; ct < CT; ++ct) acc0[ti][ct] = zero16();
 
     for (int m0 = 0; m0 < m; m0 += mc) {
       if (nchunks > 1) {
@@ -653,7 +659,7 @@ __global__ __launch_bounds__(kRowsWaves * 64, MODE == 0 ? 2 : 1) void rows_kerne
         for (int ks = 0; ks < KS; ++ks)
           oa[ks] = *reinterpret_cast<const f16x8 *>(&s_omT[(32 * rt + l32) * AS + 16 * ks + 8 * h]);
         bf16x8 ma[KSX];   // (M | b) rows of this feature tile: A operand of the dPhi MFMA
-        if (MODE != 0) {
+        if (IS_GRAD) {
 #pragma unroll
           for (int ks = 0; ks < KSX; ++ks)
             ma[ks] = *reinterpret_cast<const bf16x8 *>(&s_Mx[(32 * rt + l32) * AM + 16 * ks + 8 * h]);
@@ -663,11 +669,11 @@ __global__ __launch_bounds__(kRowsWaves * 64, MODE == 0 ? 2 : 1) void rows_kerne
           f32x16 R = zero16();
 #pragma unroll
           for (int ks = 0; ks < KS; ++ks) R = mfma_f16(oa[ks], xb[ti][ks], R);
-          if (MODE == 0) {
+          if (IS_APPLY) {
 #pragma unroll
             for (int a = 0; a < 2; ++a) {
               const bf16x8 pa = relu_bf16x8(pack_half(R, a));
-              dacc[ti] = dot8_bf16(pa, lds_perm8(s_bb, 32 * rt + 16 * a, h), dacc[ti]);
+              if (MODE == 0) dacc[ti] = dot8_bf16(pa, lds_perm8(s_bb, 32 * rt + 16 * a, h), dacc[ti]);
 #pragma unroll
               for (int ct = 0; ct < CT; ++ct) {
                 const bf16x8 sb = lds_perm8(&s_MT[(32 * ct + l32) * BS], 32 * rt + 16 * a, h);
@@ -689,17 +695,6 @@ __global__ __launch_bounds__(kRowsWaves * 64, MODE == 0 ? 2 : 1) void rows_kerne
                 acc0[ti][ct] = mfma_bf16(pg, ob, acc0[ti][ct]);
               }
             }
-            if (MODE == 2) {
-#pragma unroll
-              for (int a = 0; a < 2; ++a) {
-                const bf16x8 pa = relu_bf16x8(pack_half(R, a));
-#pragma unroll
-                for (int ct = 0; ct < CT; ++ct) {
-                  const bf16x8 sb = lds_perm8(&s_MT[(32 * ct + l32) * BS], 32 * rt + 16 * a, h);
-                  acc1[ti][ct] = mfma_bf16(pa, sb, acc1[ti][ct]);
-                }
-              }
-            }
           }
         }
       }
@@ -707,6 +702,18 @@ __global__ __launch_bounds__(kRowsWaves * 64, MODE == 0 ? 2 : 1) void rows_kerne
     if (!active) continue;
 
     // ---- epilogues -----------------------------------------------------------------
+    if (MODE == 3) {   // dV = c * relu(R) dS
+      bf16_t *os = out0 + vo.slice_base(slice);
+#pragma unroll
+      for (int ti = 0; ti < 2; ++ti)
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+          for (int i = 0; i < 16; ++i)
+            os[(int64_t)(t0 + 32 * ti + acc_row(i, h)) * vo.sn + 32 * ct + l32] =
+                cvt_bf16(acc0[ti][ct][i] * cscale);
+      continue;
+    }
     if (MODE == 0) {
       float *dl = s_wave + wave * 64;
 #pragma unroll
@@ -728,7 +735,7 @@ __global__ __launch_bounds__(kRowsWaves * 64, MODE == 0 ? 2 : 1) void rows_kerne
           const float inv = cscale / dl[tl];
 #pragma unroll
           for (int ct = 0; ct < CT; ++ct)
-            os[(int64_t)(t0 + tl) * vo.sn + 32 * ct + l32] = f32_to_bf16(acc0[ti][ct][i] * inv);
+            os[(int64_t)(t0 + tl) * vo.sn + 32 * ct + l32] = cvt_bf16(acc0[ti][ct][i] * inv);
         }
       continue;
     }
@@ -737,87 +744,108 @@ __global__ __launch_bounds__(kRowsWaves * 64, MODE == 0 ? 2 : 1) void rows_kerne
     // Lane (l32, h) holds column 32 ct + l32 and rows 32 ti + 8 g + 4 h + e (g, e = 0..3):
     //   block sums of 2 and 4 rows are in-lane, 8 rows need the other half-wave (lane ^ 32),
     //   16 and 32 rows are in-lane again over g, 64 rows over ti.
-    if (MODE == 2) {
-      bf16_t *vs = out1 + vo.slice_base(slice);
-#pragma unroll
-      for (int ti = 0; ti < 2; ++ti)
-#pragma unroll
-        for (int ct = 0; ct < CT; ++ct)
-#pragma unroll
-          for (int i = 0; i < 16; ++i)
-            vs[(int64_t)(t0 + 32 * ti + acc_row(i, h)) * vo.sn + 32 * ct + l32] =
-                f32_to_bf16(acc1[ti][ct][i] * cscale);
-    }
-    const bf16_t *xs = x + vx.slice_base(slice);
-    bf16_t *os = out0 + vo.slice_base(slice);
+    // X comes in and dX goes out through a wave-private LDS tile of 64 rows x 32 columns, so
+    // that global memory sees 8-byte row-major accesses and the column accesses stay in LDS.
+    const bf16_t *xs = x + vx.slice_base(slice) + (int64_t)t0 * vx.sn;
+    bf16_t *os = out0 + vo.slice_base(slice) + (int64_t)t0 * vo.sn;
+    bf16_t *tl = s_tile + wave * (64 * TS);
+    const int prow = lane >> 3, pcol = (lane & 7) * 4;   // this lane's 8-byte piece: rows prow + 8 j
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {
-      const int col = 32 * ct + l32;
-      float g0[2][16], x0[2][16];
+      // ---- X tile -> LDS
+      __builtin_amdgcn_wave_barrier();
+      {
+        bf16x4 piece[8];
 #pragma unroll
-      for (int ti = 0; ti < 2; ++ti)
+        for (int j = 0; j < 8; ++j)
+          piece[j] = *reinterpret_cast<const bf16x4 *>(xs + (int64_t)(prow + 8 * j) * vx.sn + 32 * ct + pcol);
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          g0[ti][i] = acc0[ti][ct][i] * cscale;
-          x0[ti][i] = bf16_to_f32(xs[(int64_t)(t0 + 32 * ti + acc_row(i, h)) * vx.sn + col]);
-          u[0] = fmaf(g0[ti][i], x0[ti][i], u[0]);
-        }
-      float g1[2][8], x1[2][8], g2[2][4], x2[2][4], g3[2][4], x3[2][4], g4[2][2], x4[2][2], g5[2], x5[2];
+        for (int j = 0; j < 8; ++j)
+          *reinterpret_cast<bf16x4 *>(&tl[(prow + 8 * j) * TS + pcol]) = piece[j];
+      }
+      __builtin_amdgcn_wave_barrier();
+      // ---- pass 1: block sums of g and x, band inner products, keep the 32-row sums
+      float g5[2], x5[2];
 #pragma unroll
       for (int ti = 0; ti < 2; ++ti) {
+        float g1[8], x1[8];
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
-          g1[ti][k] = g0[ti][2 * k] + g0[ti][2 * k + 1];
-          x1[ti][k] = x0[ti][2 * k] + x0[ti][2 * k + 1];
-          u[1] = fmaf(g1[ti][k], x1[ti][k], u[1]);
+          const float ga = acc0[ti][ct][2 * k] * cscale, gb = acc0[ti][ct][2 * k + 1] * cscale;
+          const float xa = bf16_to_f32(tl[(32 * ti + acc_row(2 * k, h)) * TS + l32]);
+          const float xb2 = bf16_to_f32(tl[(32 * ti + acc_row(2 * k + 1, h)) * TS + l32]);
+          u[0] = fmaf(ga, xa, fmaf(gb, xb2, u[0]));
+          g1[k] = ga + gb;
+          x1[k] = xa + xb2;
+          u[1] = fmaf(g1[k], x1[k], u[1]);
         }
+        float g3[4], x3[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-          g2[ti][k] = g1[ti][2 * k] + g1[ti][2 * k + 1];
-          x2[ti][k] = x1[ti][2 * k] + x1[ti][2 * k + 1];
-          u[2] = fmaf(g2[ti][k], x2[ti][k], u[2]);
+          const float g2 = g1[2 * k] + g1[2 * k + 1], x2 = x1[2 * k] + x1[2 * k + 1];
+          u[2] = fmaf(g2, x2, u[2]);
+          g3[k] = g2 + __shfl_xor(g2, 32, 64);   // 8-row blocks: both half-waves hold the same sums
+          x3[k] = x2 + __shfl_xor(x2, 32, 64);
+          u[3] = fmaf(0.5f * g3[k], x3[k], u[3]);
         }
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {   // 8-row blocks: both half-waves hold the same sums
-          g3[ti][k] = g2[ti][k] + __shfl_xor(g2[ti][k], 32, 64);
-          x3[ti][k] = x2[ti][k] + __shfl_xor(x2[ti][k], 32, 64);
-          u[3] = fmaf(0.5f * g3[ti][k], x3[ti][k], u[3]);
-        }
-#pragma unroll
-        for (int k = 0; k < 2; ++k) {
-          g4[ti][k] = g3[ti][2 * k] + g3[ti][2 * k + 1];
-          x4[ti][k] = x3[ti][2 * k] + x3[ti][2 * k + 1];
-          u[4] = fmaf(0.5f * g4[ti][k], x4[ti][k], u[4]);
-        }
-        g5[ti] = g4[ti][0] + g4[ti][1];
-        x5[ti] = x4[ti][0] + x4[ti][1];
+        const float g4a = g3[0] + g3[1], g4b = g3[2] + g3[3];
+        const float x4a = x3[0] + x3[1], x4b = x3[2] + x3[3];
+        u[4] = fmaf(0.5f * g4a, x4a, fmaf(0.5f * g4b, x4b, u[4]));
+        g5[ti] = g4a + g4b;
+        x5[ti] = x4a + x4b;
         u[5] = fmaf(0.5f * g5[ti], x5[ti], u[5]);
       }
       const float g6 = g5[0] + g5[1], x6 = x5[0] + x5[1];
       u[6] = fmaf(0.5f * g6, x6, u[6]);
-      // filtered gradient, top-down
       const float T6 = cf[6] * g6;
+      __builtin_amdgcn_wave_barrier();
+      // ---- pass 2: filtered gradient, top-down (block sums of g rebuilt), bf16 into the tile
 #pragma unroll
       for (int ti = 0; ti < 2; ++ti) {
         const float T5 = fmaf(cf[5], g5[ti], T6);
-        float T4[2], T3[4], T2[4], T1[8];
+        float g1[8], g2[4], g3[4];
 #pragma unroll
-        for (int k = 0; k < 2; ++k) T4[k] = fmaf(cf[4], g4[ti][k], T5);
+        for (int k = 0; k < 8; ++k) g1[k] = (acc0[ti][ct][2 * k] + acc0[ti][ct][2 * k + 1]) * cscale;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) T3[k] = fmaf(cf[3], g3[ti][k], T4[k >> 1]);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) T2[k] = fmaf(cf[2], g2[ti][k], T3[k]);
-#pragma unroll
-        for (int k = 0; k < 8; ++k) T1[k] = fmaf(cf[1], g1[ti][k], T2[k >> 1]);
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float val = fmaf(cf[0], g0[ti][i], T1[i >> 1]);
-          os[(int64_t)(t0 + 32 * ti + acc_row(i, h)) * vo.sn + col] = f32_to_bf16(val);
+        for (int k = 0; k < 4; ++k) {
+          g2[k] = g1[2 * k] + g1[2 * k + 1];
+          g3[k] = g2[k] + __shfl_xor(g2[k], 32, 64);
         }
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2) {
+          const float T4 = fmaf(cf[4], g3[2 * k2] + g3[2 * k2 + 1], T5);
+#pragma unroll
+          for (int k1 = 0; k1 < 2; ++k1) {
+            const int k = 2 * k2 + k1;   // 8-row block (and this lane's 4-row part of it)
+            const float T2 = fmaf(cf[2], g2[k], fmaf(cf[3], g3[k], T4));
+#pragma unroll
+            for (int k0 = 0; k0 < 2; ++k0) {
+              const int kk = 2 * k + k0;   // row pair
+              const float T1 = fmaf(cf[1], g1[kk], T2);
+#pragma unroll
+              for (int e = 0; e < 2; ++e) {
+                const int i = 2 * kk + e;
+                const float val = fmaf(cf[0] * cscale, acc0[ti][ct][i], T1);
+                tl[(32 * ti + acc_row(i, h)) * TS + l32] = cvt_bf16(val);
+              }
+            }
+          }
+        }
+      }
+      __builtin_amdgcn_wave_barrier();
+      // ---- LDS -> dX
+      {
+        bf16x4 piece[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          piece[j] = *reinterpret_cast<const bf16x4 *>(&tl[(prow + 8 * j) * TS + pcol]);
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          *reinterpret_cast<bf16x4 *>(os + (int64_t)(prow + 8 * j) * vo.sn + 32 * ct + pcol) = piece[j];
       }
     }
   }
-  if (MODE == 0) return;
+  if (IS_APPLY) return;
 
   // With u_l = <dX_F, P_l X> (P_l = mean over aligned 2^l blocks) the band gradients are
   // dF_L = u_L and dF_{l-1} = u_{l-1} - u_l (l = 1..L); one partial per workgroup.
@@ -830,7 +858,7 @@ __global__ __launch_bounds__(kRowsWaves * 64, MODE == 0 ? 2 : 1) void rows_kerne
   __syncthreads();
   if (tid <= L) {
     float ul = 0.f, ul1 = 0.f;
-    for (int wv = 0; wv < kRowsWaves; ++wv) {
+    for (int wv = 0; wv < NW; ++wv) {
       ul += s_wave[wv * 8 + tid];
       if (tid < L) ul1 += s_wave[wv * 8 + tid + 1];
     }
@@ -907,12 +935,14 @@ __global__ __launch_bounds__(256) void add_pooled_kernel(bf16_t *dq, View v, con
 // ---------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------
+constexpr int kWavesApply = 4, kWavesGrad = 8;
+
 struct FastPlan {
   int DH, FW, MB, mc;
   int chunksQ, rowsQ;   // pooled-query partial sums
   int chunksC, rowsC;   // split of n in phiT_contract
-  int rowGroups;        // 256-row groups per slice in the rows kernel
-  int rowsWgs;          // workgroups per slice of the rows kernel (each walks several groups)
+  int rowGroupsA, rowsWgsA;   // apply-type rows kernel (4 waves): row groups / workgroups per slice
+  int rowGroupsG, rowsWgsG;   // gradient-type rows kernel (8 waves)
   int prepBlocks;       // blocks per slice of prep_bwd
 };
 
@@ -932,9 +962,12 @@ FastPlan fast_plan(const wersa_desc &c) {
   const int bpc = (blocks + want - 1) / want;
   p.rowsC = bpc * 64;
   p.chunksC = (blocks + bpc - 1) / bpc;
-  p.rowGroups = (blocks + kRowsWaves - 1) / kRowsWaves;
-  int wgs = (512 + slices - 1) / slices;   // about two workgroups per compute unit in total
-  p.rowsWgs = wgs < p.rowGroups ? wgs : p.rowGroups;
+  p.rowGroupsA = (blocks + kWavesApply - 1) / kWavesApply;
+  int wgs = (512 + slices - 1) / slices;   // two 4-wave workgroups per compute unit in total
+  p.rowsWgsA = wgs < p.rowGroupsA ? wgs : p.rowGroupsA;
+  p.rowGroupsG = (blocks + kWavesGrad - 1) / kWavesGrad;
+  wgs = (256 + slices - 1) / slices;       // one 8-wave workgroup per compute unit in total
+  p.rowsWgsG = wgs < p.rowGroupsG ? wgs : p.rowGroupsG;
   const int rpb = (256 / (c.d / 8)) * kPrepIters;
   p.prepBlocks = (c.n + rpb - 1) / rpb;
   return p;
@@ -970,8 +1003,8 @@ FastWs fast_ws(const wersa_desc &c, const FastPlan &p, int bwd, float *base) {
     w.dSx = reinterpret_cast<bf16_t *>(b.take(sl * mx / 2));
     w.dST = reinterpret_cast<bf16_t *>(b.take(sl * md / 2));
     w.dzb = reinterpret_cast<bf16_t *>(b.take(sl * c.m / 2));
-    w.partQ = b.take(sl * p.rowsWgs * (c.L + 1));
-    w.partK = b.take(sl * p.rowsWgs * (c.L + 1));
+    w.partQ = b.take(sl * p.rowsWgsG * (c.L + 1));
+    w.partK = b.take(sl * p.rowsWgsG * (c.L + 1));
     w.dF = b.take(sl * (c.L + 1));
     w.dlogit = b.take(sl * (c.L + 1));
     w.dqbar = b.take(sl * c.d);
@@ -980,15 +1013,16 @@ FastWs fast_ws(const wersa_desc &c, const FastPlan &p, int bwd, float *base) {
   return w;
 }
 
-template <int DH, int MODE>
+template <int DH, int MODE, int NW>
 size_t rows_smem_bytes(int mc) {
+  constexpr bool IS_GRAD = (MODE == 1 || MODE == 2);
   const size_t AS = DH + 8, AM = DH + 16 + 8, BS = (size_t)mc + 4;
   size_t s = (size_t)mc * AS * 2;
-  if (MODE != 0) s += (size_t)mc * AM * 2;
-  if (MODE != 1) s += (size_t)DH * BS * 2;
-  if (MODE != 0) s += (size_t)DH * BS * 2;
+  if (IS_GRAD) s += (size_t)mc * AM * 2 + (size_t)DH * BS * 2;
+  else s += (size_t)DH * BS * 2;
   if (MODE == 0) s += (size_t)mc * 2;
-  s += kRowsWaves * 64 * 4;
+  s += NW * 64 * 4;
+  if (IS_GRAD) s += (size_t)NW * 64 * 36 * 2;
   return s;
 }
 
@@ -996,17 +1030,21 @@ template <int DH, int MODE>
 hipError_t launch_rows(const wersa_desc &c, const FastPlan &p, const _Float16 *xf, const bf16_t *x,
                        const bf16_t *y, const float *Dsaved, const float *arow, const FastWs &w,
                        const bf16_t *omega, const bf16_t *Mx, const bf16_t *MT, const bf16_t *bb,
-                       bf16_t *out0, bf16_t *out1, float *Dout, float *partF, hipStream_t st) {
+                       bf16_t *out0, float *Dout, float *partF, hipStream_t st) {
+  constexpr bool IS_GRAD = (MODE == 1 || MODE == 2);
+  constexpr int NW = IS_GRAD ? kWavesGrad : kWavesApply;
   const View tv{c.stride_b, c.stride_h, c.stride_n, c.H};
-  const size_t smem = rows_smem_bytes<DH, MODE>(p.mc);
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&rows_kernel<DH, MODE>),
+  const size_t smem = rows_smem_bytes<DH, MODE, NW>(p.mc);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&rows_kernel<DH, MODE, NW>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
   if (e != hipSuccess) return e;
-  const char *name = MODE == 0 ? "wersa_rows_fwd" : (MODE == 1 ? "wersa_rows_bwd_q" : "wersa_rows_bwd_k");
+  const char *name = MODE == 0 ? "wersa_rows_fwd"
+                               : (MODE == 1 ? "wersa_rows_bwd_q" : (MODE == 2 ? "wersa_rows_bwd_k" : "wersa_rows_bwd_v"));
+  const int wgs = IS_GRAD ? p.rowsWgsG : p.rowsWgsA, groups = IS_GRAD ? p.rowGroupsG : p.rowGroupsA;
   WERSA_STAGE(name, st,
-              rows_kernel<DH, MODE><<<dim3(p.rowsWgs, c.B * c.H), kRowsWaves * 64, smem, st>>>(
+              rows_kernel<DH, MODE, NW><<<dim3(wgs, c.B * c.H), NW * 64, smem, st>>>(
                   xf, x, tv, y, tv, Dsaved, arow, w.omT, omega, Mx, MT, bb, w.coef, w.scalars, c.eps,
-                  c.n, c.m, p.mc, p.rowGroups, out0, tv, out1, Dout, partF, c.L));
+                  c.n, c.m, p.mc, groups, out0, tv, Dout, partF, c.L));
   return hipSuccess;
 }
 
@@ -1060,8 +1098,8 @@ wersa_status fast_forward_t(const wersa_desc &c, const bf16_t *q, const bf16_t *
   WERSA_STAGE("wersa_haar_stage", st,
               haar_stage_kernel<DH><<<dim3(c.n / 64, slices), 256, 0, st>>>(k, tv, c.n, w.coef, KF));
   launch_contract<DH>(c, p, KF, v, nullptr, nullptr, w, S, z, w.Sx, w.ST, w.zb, st);
-  if (launch_rows<DH, 0>(c, p, QF, nullptr, nullptr, nullptr, nullptr, w, omega, nullptr, w.ST, w.zb, out,
-                         nullptr, D, nullptr, st) != hipSuccess)
+  if (launch_rows<DH, 0>(c, p, QF, nullptr, nullptr, nullptr, nullptr, w, omega, nullptr, w.ST, w.zb, out, D,
+                         nullptr, st) != hipSuccess)
     return WERSA_ERR_LAUNCH;
   return hipGetLastError() == hipSuccess ? WERSA_OK : WERSA_ERR_LAUNCH;
 }
@@ -1094,15 +1132,18 @@ wersa_status fast_backward_t(const wersa_desc &c, const bf16_t *q, const bf16_t 
   WERSA_STAGE("wersa_prep_bwd", st,
               prep_bwd_kernel<DH><<<dim3(prepBlocks, slices), 256, 0, st>>>(dout, out, tv, D, c.n, w.dD, w.dDpart));
   // dX_F of the Q side needs only S, z; dS, dz need the full reduction over n first.
-  if (launch_rows<DH, 1>(c, p, QF, q, dout, D, w.dD, w, omega, w.Sx, nullptr, nullptr, dq, nullptr, nullptr,
-                         w.partQ, st) != hipSuccess)
+  if (launch_rows<DH, 1>(c, p, QF, q, dout, D, w.dD, w, omega, w.Sx, nullptr, nullptr, dq, nullptr, w.partQ,
+                         st) != hipSuccess)
     return WERSA_ERR_LAUNCH;
   launch_contract<DH>(c, p, QF, dout, D, w.dD, w, w.dS, w.dz, w.dSx, w.dST, w.dzb, st);
-  if (launch_rows<DH, 2>(c, p, KF, k, v, nullptr, nullptr, w, omega, w.dSx, w.dST, nullptr, dk, dv, nullptr,
+  if (launch_rows<DH, 2>(c, p, KF, k, v, nullptr, nullptr, w, omega, w.dSx, nullptr, nullptr, dk, nullptr,
                          w.partK, st) != hipSuccess)
     return WERSA_ERR_LAUNCH;
+  if (launch_rows<DH, 3>(c, p, KF, nullptr, nullptr, nullptr, nullptr, w, omega, nullptr, w.dST, nullptr, dv,
+                         nullptr, nullptr, st) != hipSuccess)
+    return WERSA_ERR_LAUNCH;
   WERSA_STAGE("gate_bwd_slice_kernel", st,
-              gate_bwd_slice_kernel<<<slices, 64, 0, st>>>(w.partQ, w.partK, p.rowsWgs, c.L, c.d, c.H, s,
+              gate_bwd_slice_kernel<<<slices, 64, 0, st>>>(w.partQ, w.partK, p.rowsWgsG, c.L, c.d, c.H, s,
                                                            gate_w, scale_w, w.dF, w.dlogit, w.dqbar));
   WERSA_STAGE("gate_bwd_params_kernel", st,
               gate_bwd_params_kernel<<<1, 256, 0, st>>>(w.dF, w.dlogit, s, qbar, w.dDpart, slices * prepBlocks,
