@@ -513,7 +513,7 @@ __global__ __launch_bounds__(NW * 64, 2) void rows_kernel(
   if (MODE == 0) { s_bb = reinterpret_cast<bf16_t *>(p); p += (size_t)mc * 2; }        // [mc]
   float *s_wave = reinterpret_cast<float *>(p); p += (size_t)NW * 64 * 4;              // [waves][64]
   constexpr int TS = 36;                // row stride (elements) of the per-wave 64 x 32 epilogue tile
-  bf16_t *s_tile = reinterpret_cast<bf16_t *>(p);                                      // [waves][64][TS] (grad)
+  bf16_t *s_tile = reinterpret_cast<bf16_t *>(p);                                      // [waves][64][TS]
 
   const int slice = blockIdx.y;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
@@ -610,27 +610,21 @@ __global__ __launch_bounds__(NW * 64, 2) void rows_kernel(
         for (int ks = 0; ks < KS; ++ks)
           xb[ti][ks] = *reinterpret_cast<const f16x8 *>(xs + (int64_t)(32 * ti + l32) * DH + 16 * ks + 8 * h);
       if (IS_GRAD) {
+        // MODE 1 works with the raw dO rows: G' = D_t * G (the extension carries dD_t * D_t), and
+        // row t of dX_F is scaled by c / D_t at the end; MODE 2 scales by c.
         const bf16_t *ys = y + vy.slice_base(slice);
 #pragma unroll
         for (int ti = 0; ti < 2; ++ti) {
           const int t = t0 + 32 * ti + l32;
-          float inv = 1.0f, at = 1.0f;
+          float at = 1.0f;
           if (MODE == 1) {
-            inv = 1.0f / Dsaved[(int64_t)slice * n + t];
-            at = arow[(int64_t)slice * n + t];
+            const float Dt = Dsaved[(int64_t)slice * n + t];
+            at = arow[(int64_t)slice * n + t] * Dt;
+            if (h == 0) s_wave[wave * 64 + 32 * ti + l32] = cscale / Dt;
           }
 #pragma unroll
-          for (int ks = 0; ks < KS; ++ks) {
-            const u16x8 raw = *reinterpret_cast<const u16x8 *>(ys + (int64_t)t * vy.sn + 16 * ks + 8 * h);
-            if (MODE == 1) {
-              bf16x8 o;
-#pragma unroll
-              for (int q = 0; q < 8; ++q) o[q] = (__bf16)(bf16_to_f32(raw[q]) * inv);
-              yb[ti][ks] = o;
-            } else {
-              yb[ti][ks] = __builtin_bit_cast(bf16x8, raw);
-            }
-          }
+          for (int ks = 0; ks < KS; ++ks)
+            yb[ti][ks] = *reinterpret_cast<const bf16x8 *>(ys + (int64_t)t * vy.sn + 16 * ks + 8 * h);
           bf16x8 ext = splat_bf16x8(0.f);
           if (h == 0) ext[0] = (__bf16)at;
           yb[ti][KS] = ext;
@@ -702,41 +696,64 @@ __global__ __launch_bounds__(NW * 64, 2) void rows_kernel(
     if (!active) continue;
 
     // ---- epilogues -----------------------------------------------------------------
-    if (MODE == 3) {   // dV = c * relu(R) dS
-      bf16_t *os = out0 + vo.slice_base(slice);
-#pragma unroll
-      for (int ti = 0; ti < 2; ++ti)
-#pragma unroll
-        for (int ct = 0; ct < CT; ++ct)
-#pragma unroll
-          for (int i = 0; i < 16; ++i)
-            os[(int64_t)(t0 + 32 * ti + acc_row(i, h)) * vo.sn + 32 * ct + l32] =
-                cvt_bf16(acc0[ti][ct][i] * cscale);
-      continue;
-    }
-    if (MODE == 0) {
+    bf16_t *tl = s_tile + wave * (64 * TS);
+    const int prow = lane >> 3, pcol = (lane & 7) * 4;   // this lane's 8-byte piece: rows prow + 8 j
+    bf16_t *os = out0 + vo.slice_base(slice) + (int64_t)t0 * vo.sn;
+
+    if (MODE == 0) {   // normaliser D_t = c * sum_r relu(R) z + eps, row scale c / D_t
       float *dl = s_wave + wave * 64;
 #pragma unroll
       for (int ti = 0; ti < 2; ++ti) {
         const float dsum = dacc[ti] + __shfl_xor(dacc[ti], 32, 64);
         const float Dt = fmaf(cscale, dsum, eps);
         if (h == 0) {
-          dl[32 * ti + l32] = Dt;
+          dl[32 * ti + l32] = cscale / Dt;
           Dout[(int64_t)slice * n + t0 + 32 * ti + l32] = Dt;
         }
       }
-      // dl is written and read by this wave only; LDS operations of one wave complete in order
-      bf16_t *os = out0 + vo.slice_base(slice);
+    }
+    // Row scale of the accumulators (rows on registers): c / D_t from the per-wave LDS array
+    // (written above or in the prologue by this wave; LDS operations of one wave stay in order),
+    // or the uniform c.
+    __builtin_amdgcn_wave_barrier();
 #pragma unroll
-      for (int ti = 0; ti < 2; ++ti)
+    for (int ti = 0; ti < 2; ++ti) {
+      float sc[16];
+      if (MODE == 0 || MODE == 1) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int tl = 32 * ti + acc_row(i, h);
-          const float inv = cscale / dl[tl];
+        for (int g = 0; g < 4; ++g) {
+          const f32x4 s4 = *reinterpret_cast<const f32x4 *>(&s_wave[wave * 64 + 32 * ti + 8 * g + 4 * h]);
 #pragma unroll
-          for (int ct = 0; ct < CT; ++ct)
-            os[(int64_t)(t0 + tl) * vo.sn + 32 * ct + l32] = cvt_bf16(acc0[ti][ct][i] * inv);
+          for (int q = 0; q < 4; ++q) sc[4 * g + q] = s4[q];
         }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sc[i] = cscale;
+      }
+#pragma unroll
+      for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc0[ti][ct][i] *= sc[i];
+    }
+
+    if (IS_APPLY) {   // O (MODE 0) or dV (MODE 3): bf16 through the wave's LDS tile, 8-byte row-major stores
+#pragma unroll
+      for (int ct = 0; ct < CT; ++ct) {
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int ti = 0; ti < 2; ++ti)
+#pragma unroll
+          for (int i = 0; i < 16; ++i)
+            tl[(32 * ti + acc_row(i, h)) * TS + l32] = cvt_bf16(acc0[ti][ct][i]);
+        __builtin_amdgcn_wave_barrier();
+        bf16x4 piece[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          piece[j] = *reinterpret_cast<const bf16x4 *>(&tl[(prow + 8 * j) * TS + pcol]);
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          *reinterpret_cast<bf16x4 *>(os + (int64_t)(prow + 8 * j) * vo.sn + 32 * ct + pcol) = piece[j];
+      }
       continue;
     }
 
@@ -747,9 +764,6 @@ __global__ __launch_bounds__(NW * 64, 2) void rows_kernel(
     // X comes in and dX goes out through a wave-private LDS tile of 64 rows x 32 columns, so
     // that global memory sees 8-byte row-major accesses and the column accesses stay in LDS.
     const bf16_t *xs = x + vx.slice_base(slice) + (int64_t)t0 * vx.sn;
-    bf16_t *os = out0 + vo.slice_base(slice) + (int64_t)t0 * vo.sn;
-    bf16_t *tl = s_tile + wave * (64 * TS);
-    const int prow = lane >> 3, pcol = (lane & 7) * 4;   // this lane's 8-byte piece: rows prow + 8 j
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {
       // ---- X tile -> LDS
@@ -771,7 +785,7 @@ __global__ __launch_bounds__(NW * 64, 2) void rows_kernel(
         float g1[8], x1[8];
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
-          const float ga = acc0[ti][ct][2 * k] * cscale, gb = acc0[ti][ct][2 * k + 1] * cscale;
+          const float ga = acc0[ti][ct][2 * k], gb = acc0[ti][ct][2 * k + 1];
           const float xa = bf16_to_f32(tl[(32 * ti + acc_row(2 * k, h)) * TS + l32]);
           const float xb2 = bf16_to_f32(tl[(32 * ti + acc_row(2 * k + 1, h)) * TS + l32]);
           u[0] = fmaf(ga, xa, fmaf(gb, xb2, u[0]));
@@ -805,7 +819,7 @@ __global__ __launch_bounds__(NW * 64, 2) void rows_kernel(
         const float T5 = fmaf(cf[5], g5[ti], T6);
         float g1[8], g2[4], g3[4];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) g1[k] = (acc0[ti][ct][2 * k] + acc0[ti][ct][2 * k + 1]) * cscale;
+        for (int k = 0; k < 8; ++k) g1[k] = acc0[ti][ct][2 * k] + acc0[ti][ct][2 * k + 1];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
           g2[k] = g1[2 * k] + g1[2 * k + 1];
@@ -825,8 +839,7 @@ __global__ __launch_bounds__(NW * 64, 2) void rows_kernel(
 #pragma unroll
               for (int e = 0; e < 2; ++e) {
                 const int i = 2 * kk + e;
-                const float val = fmaf(cf[0] * cscale, acc0[ti][ct][i], T1);
-                tl[(32 * ti + acc_row(i, h)) * TS + l32] = cvt_bf16(val);
+                tl[(32 * ti + acc_row(i, h)) * TS + l32] = cvt_bf16(fmaf(cf[0], acc0[ti][ct][i], T1));
               }
             }
           }
@@ -935,7 +948,7 @@ __global__ __launch_bounds__(256) void add_pooled_kernel(bf16_t *dq, View v, con
 // ---------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------
-constexpr int kWavesApply = 4, kWavesGrad = 8;
+constexpr int kWavesApply = 8, kWavesGrad = 8;
 
 struct FastPlan {
   int DH, FW, MB, mc;
@@ -963,7 +976,7 @@ FastPlan fast_plan(const wersa_desc &c) {
   p.rowsC = bpc * 64;
   p.chunksC = (blocks + bpc - 1) / bpc;
   p.rowGroupsA = (blocks + kWavesApply - 1) / kWavesApply;
-  int wgs = (512 + slices - 1) / slices;   // two 4-wave workgroups per compute unit in total
+  int wgs = (256 + slices - 1) / slices;   // one 8-wave workgroup per compute unit in total
   p.rowsWgsA = wgs < p.rowGroupsA ? wgs : p.rowGroupsA;
   p.rowGroupsG = (blocks + kWavesGrad - 1) / kWavesGrad;
   wgs = (256 + slices - 1) / slices;       // one 8-wave workgroup per compute unit in total
@@ -1022,7 +1035,7 @@ size_t rows_smem_bytes(int mc) {
   else s += (size_t)DH * BS * 2;
   if (MODE == 0) s += (size_t)mc * 2;
   s += NW * 64 * 4;
-  if (IS_GRAD) s += (size_t)NW * 64 * 36 * 2;
+  s += (size_t)NW * 64 * 36 * 2;
   return s;
 }
 
