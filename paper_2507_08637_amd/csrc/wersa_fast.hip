@@ -51,10 +51,19 @@ __device__ __forceinline__ float wave_sum64(float v) {
 // Pack accumulator registers 8a .. 8a+7 into one bf16 MFMA operand. With this choice k-slot
 // (h, q) of the consuming MFMA stands for accumulator row 16a + 8*(q/4) + 4h + (q%4); the other
 // operand must be fetched in the same order (two runs of four consecutive indices).
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ bf16x8 pack_half(const f32x16 &v, int a) {
   bf16x8 p;
 #pragma unroll
-  for (int q = 0; q < 8; ++q) p[q] = (__bf16)v[8 * a + q];
+  for (int j = 0; j < 4; ++j) {   // one packed conversion per pair
+    f32x2 f;
+    f[0] = v[8 * a + 2 * j];
+    f[1] = v[8 * a + 2 * j + 1];
+    const bf16x2_t c = __builtin_convertvector(f, bf16x2_t);
+    p[2 * j] = c[0];
+    p[2 * j + 1] = c[1];
+  }
   return p;
 }
 // The matching operand: indices base + 4h + {0..3} and base + 8 + 4h + {0..3} of a row in LDS.
@@ -478,7 +487,7 @@ __global__ void reduce_contract_kernel(const float *Spart, const float *zpart, i
 // ------------------------------------------------------------------------------------
 
 template <int DH, int MODE, int NW>
-__global__ __launch_bounds__(NW * 64, 2) void rows_kernel(
+__global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
     const _Float16 *xf,        // X_F fp16 [slices][n][DH]
     const bf16_t *x, View vx,  // X (Q or K), for the band inner products (MODE 1, 2)
     const bf16_t *y, View vy,  // dO (MODE 1) or V (MODE 2)
@@ -595,43 +604,67 @@ __global__ __launch_bounds__(NW * 64, 2) void rows_kernel(
     __syncthreads();
   }
 
+  // ---- per-wave row-side operands; the next row group's are fetched right after the feature
+  // loop of the current one (their registers are free by then), so that the latency of these
+  // loads hides behind the epilogue.
+  f16x8 xb[2][KS];      // X_F rows: B operand of the transposed projection
+  bf16x8 yb[2][KSX];    // dO or V rows (+ the a_t extension): B operand of the dPhi MFMA
+  auto load_rows = [&](int t0) {
+    const _Float16 *xs = xf + ((int64_t)slice * n + t0) * DH;
+#pragma unroll
+    for (int ti = 0; ti < 2; ++ti)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        xb[ti][ks] = *reinterpret_cast<const f16x8 *>(xs + (int64_t)(32 * ti + l32) * DH + 16 * ks + 8 * h);
+    if (IS_GRAD) {
+      // MODE 1 works with the raw dO rows: G' = D_t * G (the extension carries dD_t * D_t), and
+      // row t of dX_F is scaled by c / D_t at the end; MODE 2 scales by c.
+      const bf16_t *ys = y + vy.slice_base(slice);
+#pragma unroll
+      for (int ti = 0; ti < 2; ++ti) {
+        const int t = t0 + 32 * ti + l32;
+        float at = 1.0f;
+        if (MODE == 1) at = arow[(int64_t)slice * n + t] * Dsaved[(int64_t)slice * n + t];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+          yb[ti][ks] = *reinterpret_cast<const bf16x8 *>(ys + (int64_t)t * vy.sn + 16 * ks + 8 * h);
+        bf16x8 ext = splat_bf16x8(0.f);
+        if (h == 0) ext[0] = (__bf16)at;
+        yb[ti][KSX - 1] = ext;
+      }
+    }
+  };
+  {
+    const int t_first = (blockIdx.x * NW + wave) * 64;
+    if (blockIdx.x < row_groups && t_first < n) load_rows(t_first);
+  }
+  // With two waves per SIMD, start the second one about an epilogue later, so that one wave's
+  // epilogue (no matrix work) runs under the other's feature loop instead of both idling the pipe.
+  if (NW == 8 && wave >= 4) {
+    __builtin_amdgcn_s_sleep(100);
+  }
+
   for (int rg = blockIdx.x; rg < row_groups; rg += gridDim.x) {
     const int t0 = (rg * NW + wave) * 64;
     const bool active = t0 < n;
 
-    // ---- per-wave row-side operands ------------------------------------------------
-    f16x8 xb[2][KS];      // X_F rows: B operand of the transposed projection
-    bf16x8 yb[2][KSX];    // dN or V rows (+ the a_t extension): B operand of the dPhi MFMA
-    if (active) {
-      const _Float16 *xs = xf + ((int64_t)slice * n + t0) * DH;
+    bf16x4 xpiece[CT][8];   // X tiles of the band inner products (MODE 1, 2), 8-byte row-major pieces
+    f32x4 drow[2][4];       // D of this lane's accumulator rows (MODE 1)
+    if (IS_GRAD && active) {   // issued before the feature loop: their latency hides behind it
+      const bf16_t *xsrc = x + vx.slice_base(slice) + (int64_t)t0 * vx.sn;
 #pragma unroll
-      for (int ti = 0; ti < 2; ++ti)
+      for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-          xb[ti][ks] = *reinterpret_cast<const f16x8 *>(xs + (int64_t)(32 * ti + l32) * DH + 16 * ks + 8 * h);
-      if (IS_GRAD) {
-        // MODE 1 works with the raw dO rows: G' = D_t * G (the extension carries dD_t * D_t), and
-        // row t of dX_F is scaled by c / D_t at the end; MODE 2 scales by c.
-        const bf16_t *ys = y + vy.slice_base(slice);
+        for (int j = 0; j < 8; ++j)
+          xpiece[ct][j] = *reinterpret_cast<const bf16x4 *>(xsrc + (int64_t)((lane >> 3) + 8 * j) * vx.sn + 32 * ct + (lane & 7) * 4);
+      if (MODE == 1) {
 #pragma unroll
-        for (int ti = 0; ti < 2; ++ti) {
-          const int t = t0 + 32 * ti + l32;
-          float at = 1.0f;
-          if (MODE == 1) {
-            const float Dt = Dsaved[(int64_t)slice * n + t];
-            at = arow[(int64_t)slice * n + t] * Dt;
-            if (h == 0) s_wave[wave * 64 + 32 * ti + l32] = cscale / Dt;
-          }
+        for (int ti = 0; ti < 2; ++ti)
 #pragma unroll
-          for (int ks = 0; ks < KS; ++ks)
-            yb[ti][ks] = *reinterpret_cast<const bf16x8 *>(ys + (int64_t)t * vy.sn + 16 * ks + 8 * h);
-          bf16x8 ext = splat_bf16x8(0.f);
-          if (h == 0) ext[0] = (__bf16)at;
-          yb[ti][KS] = ext;
-        }
+          for (int g = 0; g < 4; ++g)
+            drow[ti][g] = *reinterpret_cast<const f32x4 *>(Dsaved + (int64_t)slice * n + t0 + 32 * ti + 8 * g + 4 * h);
       }
     }
-
     f32x16 acc0[2][CT];   // N, dV (MODE 0, 3) or dX_F (MODE 1, 2): rows on registers, columns on lanes
     float dacc[2] = {0.f, 0.f};   // D partial of this lane's row (MODE 0)
 #pragma unroll
@@ -678,8 +711,11 @@ __global__ __launch_bounds__(NW * 64, 2) void rows_kernel(
             f32x16 G = zero16();
 #pragma unroll
             for (int ks = 0; ks < KSX; ++ks) G = mfma_bf16(ma[ks], yb[ti][ks], G);
+            // 1[R > 0] as a multiplier without going through the condition register:
+            // clamp(R * 2^100, 0, 1) is 1 for every R > 2^-100 and 0 for R <= 0.
 #pragma unroll
-            for (int i = 0; i < 16; ++i) G[i] = R[i] > 0.f ? G[i] : 0.f;
+            for (int i = 0; i < 16; ++i)
+              G[i] *= __builtin_amdgcn_fmed3f(R[i] * 0x1p+100f, 0.f, 1.f);
 #pragma unroll
             for (int a = 0; a < 2; ++a) {
               const bf16x8 pg = pack_half(G, a);
@@ -696,6 +732,10 @@ __global__ __launch_bounds__(NW * 64, 2) void rows_kernel(
     if (!active) continue;
 
     // ---- epilogues -----------------------------------------------------------------
+    {
+      const int t_next = ((rg + gridDim.x) * NW + wave) * 64;
+      if (rg + gridDim.x < row_groups && t_next < n) load_rows(t_next);
+    }
     bf16_t *tl = s_tile + wave * (64 * TS);
     const int prow = lane >> 3, pcol = (lane & 7) * 4;   // this lane's 8-byte piece: rows prow + 8 j
     bf16_t *os = out0 + vo.slice_base(slice) + (int64_t)t0 * vo.sn;
@@ -712,20 +752,24 @@ __global__ __launch_bounds__(NW * 64, 2) void rows_kernel(
         }
       }
     }
-    // Row scale of the accumulators (rows on registers): c / D_t from the per-wave LDS array
-    // (written above or in the prologue by this wave; LDS operations of one wave stay in order),
-    // or the uniform c.
+    // Row scale of the accumulators (rows on registers): c / D_t (MODE 0 from the per-wave LDS
+    // array written just above; LDS operations of one wave stay in order; MODE 1 from D), or c.
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int ti = 0; ti < 2; ++ti) {
       float sc[16];
-      if (MODE == 0 || MODE == 1) {
+      if (MODE == 0) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const f32x4 s4 = *reinterpret_cast<const f32x4 *>(&s_wave[wave * 64 + 32 * ti + 8 * g + 4 * h]);
 #pragma unroll
           for (int q = 0; q < 4; ++q) sc[4 * g + q] = s4[q];
         }
+      } else if (MODE == 1) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) sc[4 * g + q] = cscale * __builtin_amdgcn_rcpf(drow[ti][g][q]);
       } else {
 #pragma unroll
         for (int i = 0; i < 16; ++i) sc[i] = cscale;
@@ -763,20 +807,13 @@ __global__ __launch_bounds__(NW * 64, 2) void rows_kernel(
     //   16 and 32 rows are in-lane again over g, 64 rows over ti.
     // X comes in and dX goes out through a wave-private LDS tile of 64 rows x 32 columns, so
     // that global memory sees 8-byte row-major accesses and the column accesses stay in LDS.
-    const bf16_t *xs = x + vx.slice_base(slice) + (int64_t)t0 * vx.sn;
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {
       // ---- X tile -> LDS
       __builtin_amdgcn_wave_barrier();
-      {
-        bf16x4 piece[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-          piece[j] = *reinterpret_cast<const bf16x4 *>(xs + (int64_t)(prow + 8 * j) * vx.sn + 32 * ct + pcol);
-#pragma unroll
-        for (int j = 0; j < 8; ++j)
-          *reinterpret_cast<bf16x4 *>(&tl[(prow + 8 * j) * TS + pcol]) = piece[j];
-      }
+      for (int j = 0; j < 8; ++j)
+        *reinterpret_cast<bf16x4 *>(&tl[(prow + 8 * j) * TS + pcol]) = xpiece[ct][j];
       __builtin_amdgcn_wave_barrier();
       // ---- pass 1: block sums of g and x, band inner products, keep the 32-row sums
       float g5[2], x5[2];
@@ -948,7 +985,7 @@ __global__ __launch_bounds__(256) void add_pooled_kernel(bf16_t *dq, View v, con
 // ---------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------
-constexpr int kWavesApply = 8, kWavesGrad = 8;
+constexpr int kWavesApply = 8, kWavesGrad = 4;
 
 struct FastPlan {
   int DH, FW, MB, mc;
