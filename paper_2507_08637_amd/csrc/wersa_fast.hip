@@ -486,7 +486,7 @@ __global__ void reduce_contract_kernel(const float *Spart, const float *zpart, i
 // layout, rows on registers), per-band inner products with X for dF, bf16 stores.
 // ------------------------------------------------------------------------------------
 
-template <int DH, int MODE, int NW>
+template <int DH, int MODE, int NW, int MC>
 __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
     const _Float16 *xf,        // X_F fp16 [slices][n][DH]
     const bf16_t *x, View vx,  // X (Q or K), for the band inner products (MODE 1, 2)
@@ -499,7 +499,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
     const bf16_t *MT,          // S^T (MODE 0) / dS^T (MODE 3), bf16 [slices][DH][m]
     const bf16_t *bb,          // z bf16 [slices][m] (MODE 0)
     const float *coef,         // filter coefficients [slices][8]
-    const float *scalars, float eps, int n, int m, int mc, int row_groups,
+    const float *scalars, float eps, int n, int m, int row_groups,
     bf16_t *out0, View vo,     // O (MODE 0) / dQ or dK (MODE 1, 2) / dV (MODE 3)
     float *Dout,               // D (MODE 0)
     float *partF, int L)       // [slices][gridDim.x][L+1] band partials (MODE 1, 2)
@@ -512,7 +512,8 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
   constexpr bool IS_GRAD = (MODE == 1 || MODE == 2);
   constexpr bool IS_APPLY = (MODE == 0 || MODE == 3);
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  const int BS = mc + 4;                // stride of [DH][feature] arrays (8-byte permuted reads)
+  constexpr int mc = MC;
+  constexpr int BS = MC + 4;            // stride of [DH][feature] arrays (8-byte permuted reads)
   _Float16 *s_omT = reinterpret_cast<_Float16 *>(smem_raw);                 // [mc][AS]
   unsigned char *p = smem_raw + (size_t)mc * AS * 2;
   bf16_t *s_Mx = nullptr, *s_MT = nullptr, *s_om = nullptr, *s_bb = nullptr;
@@ -529,65 +530,67 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
   const float cscale = scalars[0];
   const int nchunks = m / mc;
 
+  // Feature-side operands of features [m0, m0 + MC) into LDS: every piece count is a compile-time
+  // constant, loads go out in batches of eight before the first LDS write.
   auto stage = [&](int m0) {
     constexpr int CPRX = DH / 8;          // 16-byte pieces per Omega^T row
     constexpr int CPRM = (DH + 16) / 8;   // 16-byte pieces per extended M row
-    for (int e0 = 0; e0 < mc * CPRX; e0 += NT * 4) {
-      u16x8 tmp[4];
+    constexpr int CPC = MC / 4;           // 8-byte pieces per column row (padded stride is 8-byte aligned)
+    constexpr int B = 8;
+    for (int e0 = 0; e0 < MC * CPRX; e0 += NT * B) {
+      u16x8 tmp[B];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < B; ++u) {
         const int e = e0 + NT * u + tid;
-        if (e < mc * CPRX)
+        if (e < MC * CPRX)
           tmp[u] = *reinterpret_cast<const u16x8 *>(omT + (int64_t)(m0 + e / CPRX) * DH + (e % CPRX) * 8);
       }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < B; ++u) {
         const int e = e0 + NT * u + tid;
-        if (e < mc * CPRX) *reinterpret_cast<u16x8 *>(&s_omT[(e / CPRX) * AS + (e % CPRX) * 8]) = tmp[u];
+        if (e < MC * CPRX) *reinterpret_cast<u16x8 *>(&s_omT[(e / CPRX) * AS + (e % CPRX) * 8]) = tmp[u];
       }
     }
     if (IS_GRAD) {
-      for (int e0 = 0; e0 < mc * CPRM; e0 += NT * 4) {
-        u16x8 tmp[4];
+      for (int e0 = 0; e0 < MC * CPRM; e0 += NT * B) {
+        u16x8 tmp[B];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < B; ++u) {
           const int e = e0 + NT * u + tid;
-          if (e < mc * CPRM)
+          if (e < MC * CPRM)
             tmp[u] = *reinterpret_cast<const u16x8 *>(Mx + ((int64_t)slice * m + m0 + e / CPRM) * (DH + 16) +
                                                       (e % CPRM) * 8);
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < B; ++u) {
           const int e = e0 + NT * u + tid;
-          if (e < mc * CPRM) *reinterpret_cast<u16x8 *>(&s_Mx[(e / CPRM) * AM + (e % CPRM) * 8]) = tmp[u];
+          if (e < MC * CPRM) *reinterpret_cast<u16x8 *>(&s_Mx[(e / CPRM) * AM + (e % CPRM) * 8]) = tmp[u];
         }
       }
     }
-    const int cpc = mc / 4;   // 8-byte pieces per column row (the padded stride is 8-byte aligned)
-    for (int e0 = 0; e0 < DH * cpc; e0 += NT * 4) {
-      bf16x4 t1[4], t2[4];
+    for (int e0 = 0; e0 < DH * CPC; e0 += NT * B) {
+      bf16x4 t1[B];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < B; ++u) {
         const int e = e0 + NT * u + tid;
-        if (e < DH * cpc) {
-          const int cidx = e / cpc, cc = e % cpc;
-          if (IS_APPLY)
-            t1[u] = *reinterpret_cast<const bf16x4 *>(MT + ((int64_t)slice * DH + cidx) * m + m0 + cc * 4);
-          if (IS_GRAD) t2[u] = *reinterpret_cast<const bf16x4 *>(omega + (int64_t)cidx * m + m0 + cc * 4);
+        if (e < DH * CPC) {
+          const int cidx = e / CPC, cc = e % CPC;
+          t1[u] = IS_APPLY ? *reinterpret_cast<const bf16x4 *>(MT + ((int64_t)slice * DH + cidx) * m + m0 + cc * 4)
+                           : *reinterpret_cast<const bf16x4 *>(omega + (int64_t)cidx * m + m0 + cc * 4);
         }
       }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < B; ++u) {
         const int e = e0 + NT * u + tid;
-        if (e < DH * cpc) {
-          const int cidx = e / cpc, cc = e % cpc;
+        if (e < DH * CPC) {
+          const int cidx = e / CPC, cc = e % CPC;
           if (IS_APPLY) *reinterpret_cast<bf16x4 *>(&s_MT[cidx * BS + cc * 4]) = t1[u];
-          if (IS_GRAD) *reinterpret_cast<bf16x4 *>(&s_om[cidx * BS + cc * 4]) = t2[u];
+          else *reinterpret_cast<bf16x4 *>(&s_om[cidx * BS + cc * 4]) = t1[u];
         }
       }
     }
     if (MODE == 0)
-      for (int e = tid; e < mc; e += NT) s_bb[e] = bb[(int64_t)slice * m + m0 + e];
+      for (int e = tid; e < MC; e += NT) s_bb[e] = bb[(int64_t)slice * m + m0 + e];
   };
 
   float u[kMaxBands];   // u_l = sum over blocks of bs_l(g) * bs_l(x), this lane's share
@@ -1085,17 +1088,21 @@ hipError_t launch_rows(const wersa_desc &c, const FastPlan &p, const _Float16 *x
   constexpr int NW = IS_GRAD ? kWavesGrad : kWavesApply;
   const View tv{c.stride_b, c.stride_h, c.stride_n, c.H};
   const size_t smem = rows_smem_bytes<DH, MODE, NW>(p.mc);
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&rows_kernel<DH, MODE, NW>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-  if (e != hipSuccess) return e;
   const char *name = MODE == 0 ? "wersa_rows_fwd"
                                : (MODE == 1 ? "wersa_rows_bwd_q" : (MODE == 2 ? "wersa_rows_bwd_k" : "wersa_rows_bwd_v"));
   const int wgs = IS_GRAD ? p.rowsWgsG : p.rowsWgsA, groups = IS_GRAD ? p.rowGroupsG : p.rowGroupsA;
-  WERSA_STAGE(name, st,
-              rows_kernel<DH, MODE, NW><<<dim3(wgs, c.B * c.H), NW * 64, smem, st>>>(
-                  xf, x, tv, y, tv, Dsaved, arow, w.omT, omega, Mx, MT, bb, w.coef, w.scalars, c.eps,
-                  c.n, c.m, p.mc, groups, out0, tv, Dout, partF, c.L));
-  return hipSuccess;
+  auto go = [&](auto kern) -> hipError_t {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    WERSA_STAGE(name, st,
+                kern<<<dim3(wgs, c.B * c.H), NW * 64, smem, st>>>(
+                    xf, x, tv, y, tv, Dsaved, arow, w.omT, omega, Mx, MT, bb, w.coef, w.scalars, c.eps, c.n, c.m,
+                    groups, out0, tv, Dout, partF, c.L));
+    return hipSuccess;
+  };
+  if (p.mc == 256) return go(&rows_kernel<DH, MODE, NW, 256>);
+  return go(&rows_kernel<DH, MODE, NW, 128>);
 }
 
 template <int DH>
