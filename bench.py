@@ -20,6 +20,18 @@ if ROOT not in sys.path:
 PEAK = {"hbm": (8000.0, "GB/s"), "mfma_bf16": (2500.0, "TFLOP/s"), "fp32": (157.3, "TFLOP/s")}
 
 
+# HBM bytes per launch (read + written) on configuration 4, from the rocprofv3 FETCH_SIZE / WRITE_SIZE
+# runs summarised in profiles/mfma_path_config4_hbm_traffic.md (FETCH_SIZE scaled by the factor 2.0 that
+# a plain 1 GiB copy shows for this counter, WRITE_SIZE by 1.0).
+MIB = 1024.0 * 1024.0
+MEASURED_TRAFFIC_CONFIG4 = {
+    "wersa_rows_fwd": (130.4 + 132.7) * MIB, "wersa_rows_bwd_q": (484.2 + 147.9) * MIB,
+    "wersa_rows_bwd_k": (387.3 + 140.0) * MIB, "wersa_rows_bwd_v": (130.4 + 132.8) * MIB,
+    "wersa_phiT_contract": (260.6 + 47.7) * MIB, "wersa_haar_stage": (128.0 + 128.0) * MIB,
+    "wersa_qbar": 128.2 * MIB, "wersa_prep_bwd": (260.0 + 4.1) * MIB, "wersa_add_pooled": 256.1 * MIB,
+}
+
+
 def kernel_models(cfg):
     """Algorithmic work of ONE launch of each kernel: name -> (bound, peak key, work, unit scale).
 
@@ -43,7 +55,8 @@ def kernel_models(cfg):
         "wersa_phiT_contract": ("mfma", "mfma_bf16", 2 * unit),  # projection + Phi^T Y
         "wersa_rows_fwd": ("mfma", "mfma_bf16", 2 * unit),       # projection + Phi S
         "wersa_rows_bwd_q": ("mfma", "mfma_bf16", 3 * unit),     # projection, dPhi, dX_F
-        "wersa_rows_bwd_k": ("mfma", "mfma_bf16", 4 * unit),     # projection, dPhi, dX_F, dV
+        "wersa_rows_bwd_k": ("mfma", "mfma_bf16", 3 * unit),     # projection, dPhi, dX_F
+        "wersa_rows_bwd_v": ("mfma", "mfma_bf16", 2 * unit),     # projection, Phi dS
         "wersa_prep_bwd": ("hbm", "hbm", 2 * nd * e),
         "wersa_add_pooled": ("hbm", "hbm", 2 * nd * e),
     }
@@ -82,6 +95,9 @@ def main():
     ap.add_argument("--config", type=int, default=4, help="workload configuration (1-4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not bracket kernels with HIP events")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy (reference point for the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a profiler run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -111,6 +127,13 @@ def main():
         grads = binding.wersa_backward(t["Q"], t["K"], t["V"], t["Omega"], t["sigma"], t["Wg"], t["bg"],
                                        t["omega"], out, t["dO"], saved, L, workspace=ws_b, grads=grads)
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)   # 1 GiB
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)          # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -147,8 +170,9 @@ def main():
             bound, pk, work = models[name]
             peak, unit = PEAK[pk]
             achieved = work / (avg_ms * 1e-3) / (1e9 if unit == "GB/s" else 1e12)
+            traffic = MEASURED_TRAFFIC_CONFIG4.get(name) if args.config == 4 else None
             roof = {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
-                    "frac": achieved / peak, "traffic": None, "kernel": name,
+                    "frac": achieved / peak, "traffic": traffic, "kernel": name,
                     "avg_launch_ms": avg_ms, "launches_per_step": launches / args.steps}
         rec["kernels_ms_per_step"] = {k: round(v[0] / args.steps, 4) for k, v in
                                       sorted(prof.items(), key=lambda kv: -kv[1][0])}
