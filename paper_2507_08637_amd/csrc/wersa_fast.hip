@@ -349,10 +349,11 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
       xr[i] = *reinterpret_cast<const u16x8 *>(xs + (int64_t)(t0 + r) * DH + cc * 8);
       yr[i] = *reinterpret_cast<const u16x8 *>(ys + (int64_t)(t0 + yrow) * vy.sn + (ypiece0 + 4 * i) * 8);
     }
-    inv = rd ? 1.0f / rd[t0 + yrow] : 1.0f;
+    inv = rd ? rd[t0 + yrow] : 1.0f;   // divided at the stash, when the load has landed
     if (tid < 64) wv = ws ? ws[t0 + tid] : 1.0f;
   };
   auto stash = [&](int buf) {
+    const float rinv = 1.0f / inv;
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
       const int e = tid + 256 * i, r = e / CPR, cc = e % CPR;
@@ -361,7 +362,7 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
       if (rd) {
 #pragma unroll
         for (int q = 0; q < 8; ++q)
-          yt[buf][(c0 + q) * YS + yrow] = cvt_bf16(bf16_to_f32(yr[i][q]) * inv);
+          yt[buf][(c0 + q) * YS + yrow] = cvt_bf16(bf16_to_f32(yr[i][q]) * rinv);
       } else {
 #pragma unroll
         for (int q = 0; q < 8; ++q) yt[buf][(c0 + q) * YS + yrow] = yr[i][q];
@@ -1009,7 +1010,7 @@ FastPlan fast_plan(const wersa_desc &c) {
   p.chunksQ = cq < 1 ? 1 : (cq > 512 ? 512 : cq);
   p.rowsQ = (c.n + p.chunksQ - 1) / p.chunksQ;
   p.chunksQ = (c.n + p.rowsQ - 1) / p.rowsQ;
-  int want = (768 + slices * (c.m / p.MB) - 1) / (slices * (c.m / p.MB));
+  int want = 512 / (slices * (c.m / p.MB));   // two resident workgroups per compute unit, one round
   if (want < 1) want = 1;
   if (want > blocks) want = blocks;
   const int bpc = (blocks + want - 1) / want;
