@@ -512,6 +512,15 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
   constexpr int NT = NW * 64;
   constexpr bool IS_GRAD = (MODE == 1 || MODE == 2);
   constexpr bool IS_APPLY = (MODE == 0 || MODE == 3);
+  // The X tiles and D rows of the gradient epilogue are requested before the feature loop when
+  // the register file has room for them (head dimension 64), at the epilogue otherwise.
+  constexpr bool EARLY = (DH == 64);
+  // Head dimension 128, gradient modes: two waves share a row group and each owns one half of
+  // the output columns (the projection and dPhi are computed by both), which keeps the
+  // accumulators and operands of a wave within the register file.
+  constexpr int CS = (IS_GRAD && DH == 128) ? 2 : 1;
+  constexpr int NWR = NW / CS;          // row groups of 64 rows per workgroup step
+  constexpr int CTW = CT / CS;          // column tiles of this wave
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   constexpr int mc = MC;
   constexpr int BS = MC + 4;            // stride of [DH][feature] arrays (8-byte permuted reads)
@@ -528,6 +537,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
 
   const int slice = blockIdx.y;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
+  const int rwave = wave / CS, cbase = (wave % CS) * CTW;
   const float cscale = scalars[0];
   const int nchunks = m / mc;
 
@@ -613,6 +623,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
   // loads hides behind the epilogue.
   f16x8 xb[2][KS];      // X_F rows: B operand of the transposed projection
   bf16x8 yb[2][KSX];    // dO or V rows (+ the a_t extension): B operand of the dPhi MFMA
+  float dval[2] = {1.f, 1.f};   // D of rows 32 ti + l32 (MODE 1)
   auto load_rows = [&](int t0) {
     const _Float16 *xs = xf + ((int64_t)slice * n + t0) * DH;
 #pragma unroll
@@ -628,7 +639,10 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
       for (int ti = 0; ti < 2; ++ti) {
         const int t = t0 + 32 * ti + l32;
         float at = 1.0f;
-        if (MODE == 1) at = arow[(int64_t)slice * n + t] * Dsaved[(int64_t)slice * n + t];
+        if (MODE == 1) {
+          dval[ti] = Dsaved[(int64_t)slice * n + t];
+          at = arow[(int64_t)slice * n + t] * dval[ti];
+        }
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
           yb[ti][ks] = *reinterpret_cast<const bf16x8 *>(ys + (int64_t)t * vy.sn + 16 * ks + 8 * h);
@@ -639,7 +653,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
     }
   };
   {
-    const int t_first = (blockIdx.x * NW + wave) * 64;
+    const int t_first = (blockIdx.x * NWR + rwave) * 64;
     if (blockIdx.x < row_groups && t_first < n) load_rows(t_first);
   }
   // With two waves per SIMD, start the second one about an epilogue later, so that one wave's
@@ -649,32 +663,31 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
   }
 
   for (int rg = blockIdx.x; rg < row_groups; rg += gridDim.x) {
-    const int t0 = (rg * NW + wave) * 64;
+    const int t0 = (rg * NWR + rwave) * 64;
     const bool active = t0 < n;
 
-    bf16x4 xpiece[CT][8];   // X tiles of the band inner products (MODE 1, 2), 8-byte row-major pieces
-    f32x4 drow[2][4];       // D of this lane's accumulator rows (MODE 1)
-    if (IS_GRAD && active) {   // issued before the feature loop: their latency hides behind it
+    bf16x4 xpiece[EARLY ? CTW : 1][8];   // X tiles of the band inner products (MODE 1, 2), 8-byte row-major pieces
+    auto load_xpiece = [&](int ct, bf16x4 *dst) {
       const bf16_t *xsrc = x + vx.slice_base(slice) + (int64_t)t0 * vx.sn;
 #pragma unroll
-      for (int ct = 0; ct < CT; ++ct)
+      for (int j = 0; j < 8; ++j)
+        dst[j] = *reinterpret_cast<const bf16x4 *>(xsrc + (int64_t)((lane >> 3) + 8 * j) * vx.sn + 32 * (cbase + ct) + (lane & 7) * 4);
+    };
+    if (IS_GRAD && EARLY && active) {   // issued before the feature loop: their latency hides behind it
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-          xpiece[ct][j] = *reinterpret_cast<const bf16x4 *>(xsrc + (int64_t)((lane >> 3) + 8 * j) * vx.sn + 32 * ct + (lane & 7) * 4);
-      if (MODE == 1) {
-#pragma unroll
-        for (int ti = 0; ti < 2; ++ti)
-#pragma unroll
-          for (int g = 0; g < 4; ++g)
-            drow[ti][g] = *reinterpret_cast<const f32x4 *>(Dsaved + (int64_t)slice * n + t0 + 32 * ti + 8 * g + 4 * h);
-      }
+      for (int ct = 0; ct < CTW; ++ct) load_xpiece(ct, xpiece[ct]);
     }
-    f32x16 acc0[2][CT];   // N, dV (MODE 0, 3) or dX_F (MODE 1, 2): rows on registers, columns on lanes
+    if (MODE == 1 && active) {   // row scales c / D_t for the epilogue, before the next rows' D replace them
+#pragma unroll
+      for (int ti = 0; ti < 2; ++ti)
+        if (h == 0) s_wave[wave * 64 + 32 * ti + l32] = cscale * __builtin_amdgcn_rcpf(dval[ti]);
+    }
+    f32x16 acc0[2][CTW];   // N, dV (MODE 0, 3) or dX_F (MODE 1, 2): rows on registers, columns on lanes
     float dacc[2] = {0.f, 0.f};   // D partial of this lane's row (MODE 0)
 #pragma unroll
     for (int ti = 0; ti < 2; ++ti)
 #pragma unroll
-      for (int ct = 0; ct < CT; ++ct) acc0[ti][ct] = zero16();
+      for (int ct = 0; ct < CTW; ++ct) acc0[ti][ct] = zero16();
 
     for (int m0 = 0; m0 < m; m0 += mc) {
       if (nchunks > 1) {
@@ -724,8 +737,8 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
             for (int a = 0; a < 2; ++a) {
               const bf16x8 pg = pack_half(G, a);
 #pragma unroll
-              for (int ct = 0; ct < CT; ++ct) {
-                const bf16x8 ob = lds_perm8(&s_om[(32 * ct + l32) * BS], 32 * rt + 16 * a, h);
+              for (int ct = 0; ct < CTW; ++ct) {
+                const bf16x8 ob = lds_perm8(&s_om[(32 * (cbase + ct) + l32) * BS], 32 * rt + 16 * a, h);
                 acc0[ti][ct] = mfma_bf16(pg, ob, acc0[ti][ct]);
               }
             }
@@ -737,7 +750,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
 
     // ---- epilogues -----------------------------------------------------------------
     {
-      const int t_next = ((rg + gridDim.x) * NW + wave) * 64;
+      const int t_next = ((rg + gridDim.x) * NWR + rwave) * 64;
       if (rg + gridDim.x < row_groups && t_next < n) load_rows(t_next);
     }
     bf16_t *tl = s_tile + wave * (64 * TS);
@@ -762,24 +775,19 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
 #pragma unroll
     for (int ti = 0; ti < 2; ++ti) {
       float sc[16];
-      if (MODE == 0) {
+      if (MODE == 0 || MODE == 1) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const f32x4 s4 = *reinterpret_cast<const f32x4 *>(&s_wave[wave * 64 + 32 * ti + 8 * g + 4 * h]);
 #pragma unroll
           for (int q = 0; q < 4; ++q) sc[4 * g + q] = s4[q];
         }
-      } else if (MODE == 1) {
-#pragma unroll
-        for (int g = 0; g < 4; ++g)
-#pragma unroll
-          for (int q = 0; q < 4; ++q) sc[4 * g + q] = cscale * __builtin_amdgcn_rcpf(drow[ti][g][q]);
       } else {
 #pragma unroll
         for (int i = 0; i < 16; ++i) sc[i] = cscale;
       }
 #pragma unroll
-      for (int ct = 0; ct < CT; ++ct)
+      for (int ct = 0; ct < CTW; ++ct)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc0[ti][ct][i] *= sc[i];
     }
@@ -812,12 +820,13 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
     // X comes in and dX goes out through a wave-private LDS tile of 64 rows x 32 columns, so
     // that global memory sees 8-byte row-major accesses and the column accesses stay in LDS.
 #pragma unroll
-    for (int ct = 0; ct < CT; ++ct) {
+    for (int ct = 0; ct < CTW; ++ct) {
       // ---- X tile -> LDS
+      if (!EARLY) load_xpiece(ct, xpiece[0]);
       __builtin_amdgcn_wave_barrier();
 #pragma unroll
       for (int j = 0; j < 8; ++j)
-        *reinterpret_cast<bf16x4 *>(&tl[(prow + 8 * j) * TS + pcol]) = xpiece[ct][j];
+        *reinterpret_cast<bf16x4 *>(&tl[(prow + 8 * j) * TS + pcol]) = xpiece[EARLY ? ct : 0][j];
       __builtin_amdgcn_wave_barrier();
       // ---- pass 1: block sums of g and x, band inner products, keep the 32-row sums
       float g5[2], x5[2];
@@ -895,7 +904,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
           piece[j] = *reinterpret_cast<const bf16x4 *>(&tl[(prow + 8 * j) * TS + pcol]);
 #pragma unroll
         for (int j = 0; j < 8; ++j)
-          *reinterpret_cast<bf16x4 *>(os + (int64_t)(prow + 8 * j) * vo.sn + 32 * ct + pcol) = piece[j];
+          *reinterpret_cast<bf16x4 *>(os + (int64_t)(prow + 8 * j) * vo.sn + 32 * (cbase + ct) + pcol) = piece[j];
       }
     }
   }
@@ -989,7 +998,8 @@ __global__ __launch_bounds__(256) void add_pooled_kernel(bf16_t *dq, View v, con
 // ---------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------
-constexpr int kWavesApply = 8, kWavesGrad = 4;
+constexpr int kWavesGrad = 4;
+constexpr int waves_apply(int d) { return d == 64 ? 8 : 4; }   // head dimension 128: 512 registers per lane
 
 struct FastPlan {
   int DH, FW, MB, mc;
@@ -1003,7 +1013,7 @@ struct FastPlan {
 FastPlan fast_plan(const wersa_desc &c) {
   FastPlan p{};
   p.DH = c.d;
-  if (c.m % 256 == 0) { p.FW = 64; p.MB = 256; } else { p.FW = 32; p.MB = 128; }
+  if (c.m % 256 == 0 && c.d == 64) { p.FW = 64; p.MB = 256; } else { p.FW = 32; p.MB = 128; }
   p.mc = (c.d == 64 && c.m % 256 == 0) ? 256 : 128;
   const int slices = c.B * c.H, blocks = c.n / 64;
   int cq = (c.n + 1023) / 1024;
@@ -1016,10 +1026,11 @@ FastPlan fast_plan(const wersa_desc &c) {
   const int bpc = (blocks + want - 1) / want;
   p.rowsC = bpc * 64;
   p.chunksC = (blocks + bpc - 1) / bpc;
-  p.rowGroupsA = (blocks + kWavesApply - 1) / kWavesApply;
+  p.rowGroupsA = (blocks + waves_apply(c.d) - 1) / waves_apply(c.d);
   int wgs = (256 + slices - 1) / slices;   // one 8-wave workgroup per compute unit in total
   p.rowsWgsA = wgs < p.rowGroupsA ? wgs : p.rowGroupsA;
-  p.rowGroupsG = (blocks + kWavesGrad - 1) / kWavesGrad;
+  const int nwr = kWavesGrad / (c.d == 128 ? 2 : 1);   // row groups per gradient workgroup step
+  p.rowGroupsG = (blocks + nwr - 1) / nwr;
   wgs = (256 + slices - 1) / slices;       // one 8-wave workgroup per compute unit in total
   p.rowsWgsG = wgs < p.rowGroupsG ? wgs : p.rowGroupsG;
   const int rpb = (256 / (c.d / 8)) * kPrepIters;
@@ -1086,7 +1097,7 @@ hipError_t launch_rows(const wersa_desc &c, const FastPlan &p, const _Float16 *x
                        const bf16_t *omega, const bf16_t *Mx, const bf16_t *MT, const bf16_t *bb,
                        bf16_t *out0, float *Dout, float *partF, hipStream_t st) {
   constexpr bool IS_GRAD = (MODE == 1 || MODE == 2);
-  constexpr int NW = IS_GRAD ? kWavesGrad : kWavesApply;
+  constexpr int NW = IS_GRAD ? kWavesGrad : waves_apply(DH);
   const View tv{c.stride_b, c.stride_h, c.stride_n, c.H};
   const size_t smem = rows_smem_bytes<DH, MODE, NW>(p.mc);
   const char *name = MODE == 0 ? "wersa_rows_fwd"
@@ -1217,7 +1228,7 @@ wersa_status fast_backward_t(const wersa_desc &c, const bf16_t *q, const bf16_t 
 }  // namespace
 
 bool fast_supported(const wersa_desc &c) {
-  return c.dtype == WERSA_BF16 && c.d == 64 && c.n % 64 == 0 && c.m % 128 == 0 &&
+  return c.dtype == WERSA_BF16 && (c.d == 64 || c.d == 128) && c.n % 64 == 0 && c.m % 128 == 0 &&
          c.stride_n % 8 == 0 && c.stride_h % 8 == 0 && c.stride_b % 8 == 0;
 }
 

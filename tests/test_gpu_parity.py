@@ -83,6 +83,9 @@ MFMA_SHAPES = [
     dict(B=1, H=2, n=704, d=64, L=0, m=128),      # no wavelet levels
     dict(B=2, H=1, n=4096, d=64, L=5, m=512),     # two operand chunks in the rows kernel
     dict(B=1, H=2, n=2560, d=64, L=1, m=256),
+    dict(B=1, H=1, n=64, d=128, L=6, m=128),      # head dimension 128: column halves split over waves
+    dict(B=2, H=2, n=832, d=128, L=6, m=512),     # 13 blocks, four operand chunks
+    dict(B=1, H=2, n=1536, d=128, L=4, m=256),
 ]
 
 
