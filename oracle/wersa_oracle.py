@@ -43,7 +43,9 @@ Pins (tests/test_oracle_pins.py): hand-derived Haar coefficients, perfect
 reconstruction, energy preservation, block-mean closed form, explicit n x n
 kernel-matrix attention, arc-cosine kernel limit and m^-1/2 rate, convexity,
 sigma homogeneity, central finite differences for every gradient, ablation
-special cases.  Absolute output values on real data: parity unpinned (the paper
+special cases; for the attention block: identity projections reduce it to the
+pinned core per head, column permutation of W^out, linearity in W^V and W^out,
+central finite differences for every block gradient.  Absolute output values on real data: parity unpinned (the paper
 prints no worked numeric example).
 """
 import math
@@ -281,3 +283,66 @@ def backward(Q, K, V, Omega, sigma, Wg, bg, omega, L, dO, eps=1e-6, bw_floor=1e-
         g["dsigma"] += r["dsigma"]
         g["dD_sum"] += float(np.sum(r["dD"]))
     return g
+
+
+# ----------------------------------------------------------------------------
+# Attention block: input/output projections around the core (Section 3.1 steps 1-2 and the
+# closing lines of Algorithm 1: linear projections, head splitting, merged heads times W_out)
+# ----------------------------------------------------------------------------
+def split_heads(T, H):
+    """(B, n, H*d) -> (B, H, n, d): head h owns columns [h*d, (h+1)*d) (Section 3.1 step 2)."""
+    B, n, hidden = T.shape
+    return T.reshape(B, n, H, hidden // H).transpose(0, 2, 1, 3)
+
+
+def merge_heads(T):
+    """(B, H, n, d) -> (B, n, H*d), the inverse of split_heads (Algorithm 1, merge line)."""
+    B, H, n, d = T.shape
+    return T.transpose(0, 2, 1, 3).reshape(B, n, H * d)
+
+
+def block_forward(X, WQ, WK, WV, WO, H, Omega, sigma, Wg, bg, omega, L, eps=1e-6, bw_floor=1e-6,
+                  proj_dtype=None, store=None):
+    """Self-attention block on X (B, n, hidden): Q' = X W^Q, K' = X W^K, V' = X W^V, heads split,
+    WERSA core per head, heads merged, Y = A W^out.  Weights are (hidden_in, hidden_out).
+
+    `store`, when given, is applied to Q', K', V' and A right after each is formed (a test uses
+    it to round the intermediates to the storage type of the kernel under test); None keeps
+    everything in float64.
+    """
+    X = np.asarray(X, np.float64)
+    keepf = (lambda a: a) if store is None else store
+    Qp = keepf(X @ np.asarray(WQ, np.float64))
+    Kp = keepf(X @ np.asarray(WK, np.float64))
+    Vp = keepf(X @ np.asarray(WV, np.float64))
+    core = forward(split_heads(Qp, H), split_heads(Kp, H), split_heads(Vp, H), Omega, sigma, Wg, bg,
+                   omega, L, eps, bw_floor, proj_dtype=proj_dtype)
+    A = keepf(merge_heads(core["O"]))
+    Y = A @ np.asarray(WO, np.float64)
+    return dict(Y=Y, A=A, Qp=Qp, Kp=Kp, Vp=Vp)
+
+
+def block_backward(X, WQ, WK, WV, WO, H, Omega, sigma, Wg, bg, omega, L, dY, eps=1e-6,
+                   bw_floor=1e-6, proj_dtype=None, store=None):
+    """Gradients of sum(Y * dY) w.r.t. X, the four weight matrices and the core's parameters
+    (chain rule through block_forward; the core's part is `backward`)."""
+    X = np.asarray(X, np.float64)
+    dY = np.asarray(dY, np.float64)
+    WQ, WK, WV, WO = (np.asarray(w, np.float64) for w in (WQ, WK, WV, WO))
+    keepf = (lambda a: a) if store is None else store
+    f = block_forward(X, WQ, WK, WV, WO, H, Omega, sigma, Wg, bg, omega, L, eps, bw_floor,
+                      proj_dtype=proj_dtype, store=store)
+    B, n, hidden = X.shape
+    X2, dY2, A2 = X.reshape(B * n, hidden), dY.reshape(B * n, hidden), f["A"].reshape(B * n, hidden)
+    dWO = A2.T @ dY2
+    dA = keepf(dY @ WO.T)
+    g = backward(split_heads(f["Qp"], H), split_heads(f["Kp"], H), split_heads(f["Vp"], H), Omega,
+                 sigma, Wg, bg, omega, L, split_heads(dA, H), eps, bw_floor, proj_dtype=proj_dtype)
+    dQp, dKp, dVp = (keepf(merge_heads(g[k])) for k in ("dQ", "dK", "dV"))
+    dX = dQp @ WQ.T + dKp @ WK.T + dVp @ WV.T
+    dWQ = X2.T @ dQp.reshape(B * n, hidden)
+    dWK = X2.T @ dKp.reshape(B * n, hidden)
+    dWV = X2.T @ dVp.reshape(B * n, hidden)
+    return dict(Y=f["Y"], A=f["A"], Qp=f["Qp"], Kp=f["Kp"], Vp=f["Vp"], dA=dA, dQp=dQp, dKp=dKp,
+                dVp=dVp, dX=dX, dWQ=dWQ, dWK=dWK, dWV=dWV, dWO=dWO, dWg=g["dWg"], dbg=g["dbg"],
+                domega=g["domega"], dsigma=g["dsigma"])

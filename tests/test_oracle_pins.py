@@ -293,3 +293,83 @@ def test_ablation_special_cases():
     F = wo.gate(Q.mean(0), 0 * p["Wg"][0], p["bg"][0], p["omega"])[2]
     np.testing.assert_allclose(g0["dQ"], wo.haar_filter(g0["dQF"], F, 3), atol=1e-12)
     assert QF.shape == Q.shape
+
+
+# ---------------------------------------------------------------- attention block
+def _rand_block(seed, B=2, H=2, n=16, d=3, m=8, L=2):
+    r = np.random.default_rng(seed)
+    hidden = H * d
+    p = _rand_problem(seed + 1, B=B, H=H, n=n, d=d, m=m, L=L)
+    p.update(X=r.standard_normal((B, n, hidden)) + 0.3,
+             WQ=r.standard_normal((hidden, hidden)) / math.sqrt(hidden),
+             WK=r.standard_normal((hidden, hidden)) / math.sqrt(hidden),
+             WV=r.standard_normal((hidden, hidden)) / math.sqrt(hidden),
+             WO=r.standard_normal((hidden, hidden)) / math.sqrt(hidden),
+             dY=r.standard_normal((B, n, hidden)), H=H)
+    return p
+
+
+def _block_args(p, **over):
+    q = dict(p, **over)
+    return (q["X"], q["WQ"], q["WK"], q["WV"], q["WO"], q["H"], q["Omega"], q["sigma"], q["Wg"],
+            q["bg"], q["omega"], q["L"])
+
+
+def test_block_head_layout_and_identity_weights():
+    """Section 3.1 step 2: head h owns columns [h d, (h+1) d).  With identity projections the
+    block is the core applied to the head-split input, so it is pinned to the pinned core; a
+    column permutation folded into W^out must permute the output columns the same way."""
+    p = _rand_block(41)
+    hidden = p["X"].shape[2]
+    eye = np.eye(hidden)
+    H, d = p["H"], hidden // p["H"]
+    f = wo.block_forward(*_block_args(p, WQ=eye, WK=eye, WV=eye, WO=eye), eps=1e-3)
+    for b in range(p["X"].shape[0]):
+        for h in range(H):
+            xs = p["X"][b][:, h * d:(h + 1) * d]
+            s = wo.forward_slice(xs, xs, xs, p["Omega"], p["sigma"], p["Wg"][h], p["bg"][h],
+                                 p["omega"], p["L"], 1e-3, 1e-6)
+            np.testing.assert_allclose(f["Y"][b][:, h * d:(h + 1) * d], s["O"], rtol=1e-12, atol=1e-14)
+    perm = np.random.default_rng(5).permutation(hidden)
+    fp = wo.block_forward(*_block_args(p, WQ=eye, WK=eye, WV=eye, WO=eye[:, perm]), eps=1e-3)
+    np.testing.assert_allclose(fp["Y"], f["Y"][:, :, perm], rtol=1e-12, atol=1e-14)
+    # split and merge are inverse to each other
+    T = np.random.default_rng(6).standard_normal((2, 5, hidden))
+    np.testing.assert_array_equal(wo.merge_heads(wo.split_heads(T, H)), T)
+
+
+def test_block_is_linear_in_value_and_output_weights():
+    """Y is linear in W^V and in W^out (the normaliser does not depend on V)."""
+    p = _rand_block(43)
+    y1 = wo.block_forward(*_block_args(p), eps=1e-3)["Y"]
+    y2 = wo.block_forward(*_block_args(p, WV=2.5 * p["WV"]), eps=1e-3)["Y"]
+    y3 = wo.block_forward(*_block_args(p, WO=-0.5 * p["WO"]), eps=1e-3)["Y"]
+    np.testing.assert_allclose(y2, 2.5 * y1, rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(y3, -0.5 * y1, rtol=1e-11, atol=1e-13)
+
+
+def test_block_backward_matches_central_finite_differences():
+    """Every gradient of the block against central differences of its forward (float64)."""
+    eps = 1e-2
+    p = _rand_block(47)
+    g = wo.block_backward(*_block_args(p), p["dY"], eps=eps)
+    h = 1e-6
+    r = np.random.default_rng(3)
+
+    def loss(**over):
+        return float(np.sum(wo.block_forward(*_block_args(p, **over), eps=eps)["Y"] * p["dY"]))
+
+    for name, gname, count in (("X", "dX", 12), ("WQ", "dWQ", 8), ("WK", "dWK", 8), ("WV", "dWV", 8),
+                               ("WO", "dWO", 8), ("Wg", "dWg", 6), ("bg", "dbg", 4),
+                               ("omega", "domega", 3)):
+        arr = p[name]
+        for fi in r.choice(arr.size, size=min(count, arr.size), replace=False):
+            idx = np.unravel_index(fi, arr.shape)
+            ap, am = arr.copy(), arr.copy()
+            ap[idx] += h
+            am[idx] -= h
+            fd = (loss(**{name: ap}) - loss(**{name: am})) / (2 * h)
+            an = g[gname][idx]
+            assert abs(fd - an) < 3e-6 * max(1.0, abs(an)), (name, idx, fd, an)
+    fd = (loss(sigma=p["sigma"] + h) - loss(sigma=p["sigma"] - h)) / (2 * h)
+    assert abs(fd - g["dsigma"]) < 3e-6 * max(1.0, abs(fd))
