@@ -110,6 +110,47 @@ wersa_status wersa_backward(const wersa_desc *desc, const void *q, const void *k
 wersa_status wersa_haar_filter(const wersa_desc *desc, const void *x, const float *filt,
                                void *xf, void *hip_stream);
 
+/*
+ * Attention block around the core (Section 3.1 steps 1-2: Q' = X W^Q, K' = X W^K, V' = X W^V,
+ * split into H heads of width d; Algorithm 1's last line: merged heads times W_out):
+ *   Y = merge_heads( WERSA( split(X W^Q), split(X W^K), split(X W^V) ) ) W^out
+ * x, y, dy, dx are dense (B, n, hidden) with hidden = H*d in bf16; head h owns columns
+ * [h*d, (h+1)*d) and is addressed by stride (nothing is transposed); the four weights are
+ * hidden x hidden row-major [in][out] in bf16; their gradients are float32 [in][out],
+ * overwritten. The stride fields of desc are ignored. Supported: dtype bf16, hidden % 256 == 0,
+ * (B*n) % 256 == 0, and the core's own limits; otherwise WERSA_ERR_UNSUPPORTED.
+ * `saved` (wersa_block_saved_bytes) carries Q', K', V', the merged head outputs A and the
+ * core's saved buffer from forward to backward; `workspace` (wersa_block_workspace_bytes) is
+ * scratch. The other conventions are those of wersa_forward / wersa_backward; the core
+ * parameter gradients may be NULL, the weight gradients may not.
+ */
+size_t wersa_block_workspace_bytes(const wersa_desc *desc, int for_backward);
+size_t wersa_block_saved_bytes(const wersa_desc *desc);
+
+wersa_status wersa_block_forward(const wersa_desc *desc, const void *x, const void *wq,
+                                 const void *wk, const void *wv, const void *wo,
+                                 const void *omega_rf, const float *sigma, const float *gate_w,
+                                 const float *gate_b, const float *scale_w, void *y, void *saved,
+                                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
+wersa_status wersa_block_backward(const wersa_desc *desc, const void *x, const void *wq,
+                                  const void *wk, const void *wv, const void *wo,
+                                  const void *omega_rf, const float *sigma, const float *gate_w,
+                                  const float *gate_b, const float *scale_w, const void *dy,
+                                  const void *saved, void *dx, float *dwq, float *dwk, float *dwv,
+                                  float *dwo, float *dgate_w, float *dgate_b, float *dscale_w,
+                                  float *dsigma, void *workspace, size_t workspace_bytes,
+                                  void *hip_stream);
+
+/* Byte offsets of the pieces inside the block's `saved`, for tests and tools: which = 0 Q',
+ * 1 K', 2 V', 3 A (each bf16 (B, n, hidden)), 4 the core's saved buffer. -1 on a bad argument. */
+int64_t wersa_block_saved_offset(const wersa_desc *desc, int which);
+
+/* Byte offsets inside the backward `workspace` of the intermediate gradients left there by
+ * wersa_block_backward, for tests and tools: which = 0 dA, 1 dQ', 2 dK', 3 dV' (each bf16
+ * (B, n, hidden)). -1 on a bad argument. */
+int64_t wersa_block_workspace_offset(const wersa_desc *desc, int which);
+
 /* 1 if this descriptor runs on the MFMA path, 0 if on the generic path, -1 if rejected. */
 int32_t wersa_selected_path(const wersa_desc *desc);
 

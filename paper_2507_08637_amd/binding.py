@@ -17,7 +17,10 @@ WERSA_F32, WERSA_BF16 = 0, 1
 WERSA_FLAG_GENERIC_PATH = 1
 EXPORTS = ["wersa_workspace_bytes", "wersa_saved_bytes", "wersa_forward", "wersa_backward",
            "wersa_haar_filter", "wersa_saved_offset", "wersa_selected_path", "wersa_status_string", "wersa_version",
-           "wersa_profile_enable", "wersa_profile_reset", "wersa_profile_collect", "wersa_profile_get"]
+           "wersa_profile_enable", "wersa_profile_reset", "wersa_profile_collect", "wersa_profile_get",
+           "wersa_block_workspace_bytes", "wersa_block_saved_bytes", "wersa_block_saved_offset",
+           "wersa_block_workspace_offset",
+           "wersa_block_forward", "wersa_block_backward"]
 
 
 class WersaDesc(ctypes.Structure):
@@ -62,6 +65,19 @@ def load_library():
         [vp, ctypes.c_size_t, vp]
     lib.wersa_haar_filter.restype = ctypes.c_int
     lib.wersa_haar_filter.argtypes = [dp, vp, fp, vp, vp]
+    lib.wersa_block_workspace_bytes.restype = ctypes.c_size_t
+    lib.wersa_block_workspace_bytes.argtypes = [dp, ctypes.c_int]
+    lib.wersa_block_saved_bytes.restype = ctypes.c_size_t
+    lib.wersa_block_saved_bytes.argtypes = [dp]
+    lib.wersa_block_saved_offset.restype = ctypes.c_int64
+    lib.wersa_block_saved_offset.argtypes = [dp, ctypes.c_int]
+    lib.wersa_block_workspace_offset.restype = ctypes.c_int64
+    lib.wersa_block_workspace_offset.argtypes = [dp, ctypes.c_int]
+    lib.wersa_block_forward.restype = ctypes.c_int
+    lib.wersa_block_forward.argtypes = [dp] + [vp] * 6 + [fp] * 4 + [vp, vp, vp, ctypes.c_size_t, vp]
+    lib.wersa_block_backward.restype = ctypes.c_int
+    lib.wersa_block_backward.argtypes = [dp] + [vp] * 6 + [fp] * 4 + [vp, vp, vp] + [fp] * 8 + \
+        [vp, ctypes.c_size_t, vp]
     lib.wersa_status_string.restype = ctypes.c_char_p
     lib.wersa_status_string.argtypes = [ctypes.c_int]
     lib.wersa_version.restype = ctypes.c_int32
@@ -230,6 +246,101 @@ def wersa_haar_filter(x, filt, L, out=None, stream=None):
         out = torch.empty_strided(x.shape, x.stride(), dtype=x.dtype, device=x.device)
     _check(lib.wersa_haar_filter(ctypes.byref(desc), _ptr(x), _ptr(filt), _ptr(out), _stream(stream)))
     return out
+
+
+def make_block_desc(x, H, L, m, eps=1e-6, bw_floor=1e-6, flags=0):
+    """Descriptor for the attention block on x (B, n, hidden), hidden = H * d, dense bf16."""
+    assert x.dim() == 3 and x.is_contiguous() and x.shape[2] % H == 0
+    if x.dtype != torch.bfloat16:
+        raise TypeError("the attention block takes bfloat16 tensors")
+    B, n, hidden = x.shape
+    d = hidden // H
+    return WersaDesc(B, H, n, d, L, m, WERSA_BF16, eps, bw_floor, n * hidden, d, hidden, flags)
+
+
+def block_saved_views(desc, saved):
+    """bf16 views (B, n, hidden) of Q', K', V', A inside the block's saved byte buffer, and the
+    core's saved buffer as float32."""
+    lib = load_library()
+    B, n, hidden = desc.B, desc.n, desc.H * desc.d
+    out = {}
+    for which, name in enumerate(("Qp", "Kp", "Vp", "A")):
+        off = lib.wersa_block_saved_offset(ctypes.byref(desc), which)
+        out[name] = saved[off:off + B * n * hidden * 2].view(torch.bfloat16).view(B, n, hidden)
+    off = lib.wersa_block_saved_offset(ctypes.byref(desc), 4)
+    out["core"] = saved[off:].view(torch.float32)
+    return out
+
+
+def block_workspace_views(desc, workspace):
+    """bf16 views (B, n, hidden) of dA, dQ', dK', dV' left in the backward workspace."""
+    lib = load_library()
+    B, n, hidden = desc.B, desc.n, desc.H * desc.d
+    out = {}
+    for which, name in enumerate(("dA", "dQp", "dKp", "dVp")):
+        off = lib.wersa_block_workspace_offset(ctypes.byref(desc), which)
+        out[name] = workspace[off:off + B * n * hidden * 2].view(torch.bfloat16).view(B, n, hidden)
+    return out
+
+
+def _block_check_args(x, weights, omega_rf, params):
+    hidden = x.shape[2]
+    for w in weights:
+        assert w.shape == (hidden, hidden) and w.is_contiguous() and w.dtype == x.dtype
+    assert omega_rf.is_contiguous() and omega_rf.dtype == x.dtype
+    for p in params:
+        assert p.dtype == torch.float32 and p.is_contiguous()
+
+
+def wersa_block_forward(x, wq, wk, wv, wo, H, omega_rf, sigma, gate_w, gate_b, scale_w, L, eps=1e-6,
+                        bw_floor=1e-6, y=None, saved=None, workspace=None, stream=None, flags=0):
+    """Returns (y, saved): y (B, n, hidden) bf16, saved a uint8 buffer for wersa_block_backward."""
+    lib = load_library()
+    desc = make_block_desc(x, H, L, omega_rf.shape[1], eps, bw_floor, flags)
+    _block_check_args(x, (wq, wk, wv, wo), omega_rf, (sigma, gate_w, gate_b, scale_w))
+    sb = lib.wersa_block_saved_bytes(ctypes.byref(desc))
+    wb = lib.wersa_block_workspace_bytes(ctypes.byref(desc), 0)
+    if sb == 0 or wb == 0:
+        _check(lib.wersa_block_forward(ctypes.byref(desc), *([None] * 13), 0, None) or 2)
+    if y is None:
+        y = torch.empty_like(x)
+    if saved is None:
+        saved = torch.empty(sb, dtype=torch.uint8, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(wb, dtype=torch.uint8, device=x.device)
+    _check(lib.wersa_block_forward(ctypes.byref(desc), _ptr(x), _ptr(wq), _ptr(wk), _ptr(wv), _ptr(wo),
+                                   _ptr(omega_rf), _ptr(sigma), _ptr(gate_w), _ptr(gate_b), _ptr(scale_w),
+                                   _ptr(y), _ptr(saved), _ptr(workspace), workspace.numel(), _stream(stream)))
+    return y, saved
+
+
+def wersa_block_backward(x, wq, wk, wv, wo, H, omega_rf, sigma, gate_w, gate_b, scale_w, dy, saved, L,
+                         eps=1e-6, bw_floor=1e-6, workspace=None, stream=None, grads=None, flags=0):
+    """Returns dict(dx, dwq, dwk, dwv, dwo, dgate_w, dgate_b, dscale_w, dsigma); weight gradients are
+    float32.  `grads` may be a dict from an earlier call: its tensors are then overwritten."""
+    lib = load_library()
+    desc = make_block_desc(x, H, L, omega_rf.shape[1], eps, bw_floor, flags)
+    _block_check_args(x, (wq, wk, wv, wo), omega_rf, (sigma, gate_w, gate_b, scale_w))
+    assert dy.shape == x.shape and dy.is_contiguous() and dy.dtype == x.dtype
+    wb = lib.wersa_block_workspace_bytes(ctypes.byref(desc), 1)
+    if wb == 0:
+        _check(lib.wersa_block_backward(ctypes.byref(desc), *([None] * 21), 0, None) or 2)
+    if grads is None:
+        f32 = dict(dtype=torch.float32, device=x.device)
+        grads = dict(dx=torch.empty_like(x), dwq=torch.empty(wq.shape, **f32), dwk=torch.empty(wq.shape, **f32),
+                     dwv=torch.empty(wq.shape, **f32), dwo=torch.empty(wq.shape, **f32),
+                     dgate_w=torch.empty_like(gate_w), dgate_b=torch.empty_like(gate_b),
+                     dscale_w=torch.empty_like(scale_w), dsigma=torch.empty(1, **f32))
+    if workspace is None:
+        workspace = torch.empty(wb, dtype=torch.uint8, device=x.device)
+    g = grads
+    _check(lib.wersa_block_backward(ctypes.byref(desc), _ptr(x), _ptr(wq), _ptr(wk), _ptr(wv), _ptr(wo),
+                                    _ptr(omega_rf), _ptr(sigma), _ptr(gate_w), _ptr(gate_b), _ptr(scale_w),
+                                    _ptr(dy), _ptr(saved), _ptr(g["dx"]), _ptr(g["dwq"]), _ptr(g["dwk"]),
+                                    _ptr(g["dwv"]), _ptr(g["dwo"]), _ptr(g["dgate_w"]), _ptr(g["dgate_b"]),
+                                    _ptr(g["dscale_w"]), _ptr(g["dsigma"]), _ptr(workspace),
+                                    workspace.numel(), _stream(stream)))
+    return grads
 
 
 def wersa_profile_enable(on):

@@ -5,7 +5,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libwersa.so")
-SOURCES = ["wersa_api.hip", "wersa_generic.hip", "wersa_profile.hip", "wersa_fast.hip"]
+SOURCES = ["wersa_api.hip", "wersa_generic.hip", "wersa_profile.hip", "wersa_fast.hip",
+           "wersa_block.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

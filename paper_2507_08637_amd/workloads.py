@@ -87,6 +87,33 @@ def make_inputs(B, H, n, d, L, m, dtype="f32", flavour="plain", seed_base=0, q_m
     return out
 
 
+BLOCK_TENSOR_INDEX = dict(X=0, WQ=10, WK=11, WV=12, WO=13, dY=7)
+
+
+def make_block_inputs(B, H, n, d, L, m, seed_base=0, x_mean=0.0, backward=True, **_unused):
+    """Inputs of the attention block (bf16 storage): X (B, n, H*d) ~ N(0,1) + x_mean, the four
+    hidden x hidden weights ~ N(0, 1/hidden), dY ~ N(0,1); the core's parameters as in make_inputs."""
+    hidden = H * d
+
+    def rng(name):
+        return np.random.default_rng(seed_base + BLOCK_TENSOR_INDEX[name])
+
+    out = {}
+    x = rng("X").standard_normal((B, n, hidden), dtype=np.float32)
+    if x_mean != 0.0:
+        x += np.float32(x_mean)
+    out["X"] = round_to_bf16(x)
+    for name in ("WQ", "WK", "WV", "WO"):
+        w = rng(name).standard_normal((hidden, hidden), dtype=np.float32) / np.float32(np.sqrt(hidden))
+        out[name] = round_to_bf16(w)
+    core = make_inputs(1, H, 1, d, L, m, dtype="bf16", seed_base=seed_base, backward=False)
+    for name in ("Omega", "Wg", "bg", "omega", "sigma"):
+        out[name] = core[name]
+    if backward:
+        out["dY"] = round_to_bf16(rng("dY").standard_normal((B, n, hidden), dtype=np.float32))
+    return out
+
+
 def make_config(idx, **override):
     """Inputs for benchmark configuration idx (1..5); seed = 1000 * idx + tensor index."""
     cfg = dict(CONFIGS[idx])
