@@ -60,6 +60,12 @@ def kernel_models(cfg):
         "wersa_prep_bwd": ("hbm", "hbm", 2 * nd * e),
         "wersa_add_pooled": ("hbm", "hbm", 2 * nd * e),
     }
+    # attention block (configuration 5): hidden x hidden projections over all tokens.  Average
+    # launch: forward and backward hold 6 NT launches worth 8 products (dX sums three), 4 TN launches.
+    hidden, tokens = cfg["H"] * d, cfg["B"] * n
+    gemm = 2.0 * tokens * hidden * hidden
+    models["wersa_gemm_nt"] = ("mfma", "mfma_bf16", gemm * 8.0 / 6.0)
+    models["wersa_gemm_tn"] = ("mfma", "mfma_bf16", gemm)
     return models
 
 
@@ -87,12 +93,82 @@ def cpu_baseline(cfg, p, budget_s=12.0):
                       f"float64 NumPy, {dt:.1f} s"}
 
 
+def cpu_baseline_block(cfg, p, budget_s=15.0):
+    """Configuration 5: the oracle on the per-head part of the block (that head's three input
+    projections, then the core forward and backward), slice by slice until the budget is spent.
+    The output projection and the weight gradients are not in the sample."""
+    import numpy as np
+    from oracle import wersa_oracle as wo
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count()
+    d, H = cfg["d"], cfg["H"]
+    done, t0 = 0, time.perf_counter()
+    todo = [(b, h) for b in range(cfg["B"]) for h in range(H)]
+    for (b, h) in todo:
+        cols = slice(h * d, (h + 1) * d)
+        Xb = np.asarray(p["X"][b], np.float64)
+        Q, K, V = (Xb @ np.asarray(p[w][:, cols], np.float64) for w in ("WQ", "WK", "WV"))
+        dA = np.asarray(p["dY"][b], np.float64) @ np.asarray(p["WO"][cols, :], np.float64).T
+        wo.backward_slice(Q, K, V, np.asarray(p["Omega"], np.float64), float(p["sigma"]),
+                          np.asarray(p["Wg"][h], np.float64), np.asarray(p["bg"][h], np.float64),
+                          np.asarray(p["omega"], np.float64), cfg["L"], 1e-6, 1e-6, dA)
+        done += 1
+        if time.perf_counter() - t0 > budget_s:
+            break
+    dt = time.perf_counter() - t0
+    tokens = cfg["B"] * cfg["n"] * done / len(todo)
+    return {"value": tokens / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{done} of {len(todo)} (batch, head) slices: that head's Q', K', V' and dA projections and "
+                      f"the core forward+backward in float64 NumPy, {dt:.1f} s; output projection and weight "
+                      "gradients not included"}
+
+
+def run_block(args):
+    """Configuration 5: the attention block (projections around the core), forward + backward."""
+    import numpy as np
+    import torch
+    from paper_2507_08637_amd import binding, workloads
+
+    cfg = dict(workloads.CONFIGS[5])
+    B, H, n, d, L, m = (cfg[k] for k in ("B", "H", "n", "d", "L", "m"))
+    p = workloads.make_block_inputs(B, H, n, d, L, m, seed_base=5000)
+    dev = "cuda:0"
+    bf = lambda a: torch.from_numpy(a).to(dev).to(torch.bfloat16)
+    t = {k: bf(p[k]) for k in ("X", "WQ", "WK", "WV", "WO", "Omega", "dY")}
+    t.update({k: torch.from_numpy(np.ascontiguousarray(p[k], dtype=np.float32)).to(dev) for k in ("Wg", "bg", "omega")})
+    t["sigma"] = torch.tensor([float(p["sigma"])], dtype=torch.float32, device=dev)
+    desc = binding.make_block_desc(t["X"], H, L, m)
+    lib = binding.load_library()
+    import ctypes
+    saved = torch.empty(lib.wersa_block_saved_bytes(ctypes.byref(desc)), dtype=torch.uint8, device=dev)
+    ws_f = torch.empty(lib.wersa_block_workspace_bytes(ctypes.byref(desc), 0), dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(lib.wersa_block_workspace_bytes(ctypes.byref(desc), 1), dtype=torch.uint8, device=dev)
+    y = torch.empty_like(t["X"])
+    grads = None
+    weights = (t["WQ"], t["WK"], t["WV"], t["WO"])
+    params = (t["Omega"], t["sigma"], t["Wg"], t["bg"], t["omega"])
+
+    def step():
+        nonlocal grads
+        binding.wersa_block_forward(t["X"], *weights, H, *params, L, y=y, saved=saved, workspace=ws_f)
+        grads = binding.wersa_block_backward(t["X"], *weights, H, *params, t["dY"], saved, L, workspace=ws_b,
+                                             grads=grads)
+
+    core_desc = binding.WersaDesc(B, H, n, d, L, m, 1, 1e-6, 1e-6, n * H * d, d, H * d, 0)
+    workload = (f"config5: attention block B={B} n={n} hidden={H * d} (H={H} d={d}) L={L} m={m} bf16 storage, "
+                "N(0,1) inputs, forward+backward")
+    return cfg, p, step, binding.wersa_path_name(core_desc), workload
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=4, help="workload configuration (1-4)")
+    ap.add_argument("--config", type=int, default=4, help="workload configuration (1-4: the core; 5: the attention block)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not bracket kernels with HIP events")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -111,21 +187,28 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     binding.load_library()
-    cfg, p = workloads.make_config(args.config, backward=True)
-    t = to_device(p, cfg["dtype"])
-    L = cfg["L"]
-    desc = binding.make_desc(t["Q"], L, cfg["m"])
-    saved, ws_f = binding.alloc_like(desc, t["Q"], 0)
-    _, ws_b = binding.alloc_like(desc, t["Q"], 1)
-    out = torch.empty_like(t["Q"])
-    grads = None
+    if args.config == 5:
+        cfg, p, step, path, workload = run_block(args)
+    else:
+        cfg, p = workloads.make_config(args.config, backward=True)
+        t = to_device(p, cfg["dtype"])
+        L = cfg["L"]
+        desc = binding.make_desc(t["Q"], L, cfg["m"])
+        saved, ws_f = binding.alloc_like(desc, t["Q"], 0)
+        _, ws_b = binding.alloc_like(desc, t["Q"], 1)
+        out = torch.empty_like(t["Q"])
+        grads = None
+        path = binding.wersa_path_name(desc)
+        workload = (f"config{args.config}: B={cfg['B']} H={cfg['H']} n={cfg['n']} d={cfg['d']} "
+                    f"L={cfg['L']} m={cfg['m']} {cfg['dtype']} storage, {cfg['flavour']} inputs, "
+                    "forward+backward")
 
-    def step():
-        nonlocal grads
-        binding.wersa_forward(t["Q"], t["K"], t["V"], t["Omega"], t["sigma"], t["Wg"], t["bg"], t["omega"], L,
-                              out=out, saved=saved, workspace=ws_f)
-        grads = binding.wersa_backward(t["Q"], t["K"], t["V"], t["Omega"], t["sigma"], t["Wg"], t["bg"],
-                                       t["omega"], out, t["dO"], saved, L, workspace=ws_b, grads=grads)
+        def step():
+            nonlocal grads
+            binding.wersa_forward(t["Q"], t["K"], t["V"], t["Omega"], t["sigma"], t["Wg"], t["bg"], t["omega"], L,
+                                  out=out, saved=saved, workspace=ws_f)
+            grads = binding.wersa_backward(t["Q"], t["K"], t["V"], t["Omega"], t["sigma"], t["Wg"], t["bg"],
+                                           t["omega"], out, t["dO"], saved, L, workspace=ws_b, grads=grads)
 
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)   # 1 GiB
@@ -149,16 +232,15 @@ def main():
 
     ms = (t1 - t0) * 1e3 / args.steps
     tokens = cfg["B"] * cfg["n"]
-    path = binding.wersa_path_name(desc)
     rec = {
-        "metric": "WERSA attention fwd+bwd tokens/s on 1 GPU at n=131072; % HBM/MFMA roofline",
+        "metric": "WERSA attention fwd+bwd tokens/s on 1 GPU at n=131072; % HBM/MFMA roofline"
+                  if args.config != 5 else
+                  "WERSA attention block fwd+bwd tokens/s on 1 GPU at n=65536 (hidden 2048); % MFMA roofline",
         "value": tokens / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32" if path == "generic" or cfg["dtype"] == "f32" else "bf16",
         "data": "synthetic",
-        "config": {"workload": f"config{args.config}: B={cfg['B']} H={cfg['H']} n={cfg['n']} d={cfg['d']} "
-                               f"L={cfg['L']} m={cfg['m']} {cfg['dtype']} storage, {cfg['flavour']} inputs, "
-                               "forward+backward", "path": path},
+        "config": {"workload": workload, "path": path},
     }
     roof = None
     if prof:
@@ -178,7 +260,7 @@ def main():
                                       sorted(prof.items(), key=lambda kv: -kv[1][0])}
     rec["roofline"] = roof
     if not args.no_cpu_baseline:
-        rec["cpu_baseline"] = cpu_baseline(cfg, p)
+        rec["cpu_baseline"] = cpu_baseline_block(cfg, p) if args.config == 5 else cpu_baseline(cfg, p)
     else:
         rec["cpu_baseline"] = None
     print(json.dumps(rec))
