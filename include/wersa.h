@@ -165,8 +165,11 @@ int64_t wersa_saved_offset(const wersa_desc *desc, int which);
  * event pair on the caller's stream. wersa_profile_collect waits for the recorded events,
  * sums the elapsed time per kernel name, clears the recording and returns the number of
  * distinct names; wersa_profile_get copies entry `index` (0 on success, 1 on bad argument).
+ * wersa_profile_only restricts the bracketing to launches of one kernel name (NULL or "" =
+ * every launch), so that timing one kernel does not put event records between all the others.
  */
 void wersa_profile_enable(int on);
+void wersa_profile_only(const char *name);
 void wersa_profile_reset(void);
 int32_t wersa_profile_collect(void);
 int32_t wersa_profile_get(int32_t index, char *name, int32_t name_len, double *total_ms,

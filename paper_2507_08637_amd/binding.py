@@ -17,7 +17,7 @@ WERSA_F32, WERSA_BF16 = 0, 1
 WERSA_FLAG_GENERIC_PATH = 1
 EXPORTS = ["wersa_workspace_bytes", "wersa_saved_bytes", "wersa_forward", "wersa_backward",
            "wersa_haar_filter", "wersa_saved_offset", "wersa_selected_path", "wersa_status_string", "wersa_version",
-           "wersa_profile_enable", "wersa_profile_reset", "wersa_profile_collect", "wersa_profile_get",
+           "wersa_profile_enable", "wersa_profile_only", "wersa_profile_reset", "wersa_profile_collect", "wersa_profile_get",
            "wersa_block_workspace_bytes", "wersa_block_saved_bytes", "wersa_block_saved_offset",
            "wersa_block_workspace_offset",
            "wersa_block_forward", "wersa_block_backward"]
@@ -84,6 +84,8 @@ def load_library():
     lib.wersa_version.argtypes = []
     lib.wersa_profile_enable.restype = None
     lib.wersa_profile_enable.argtypes = [ctypes.c_int]
+    lib.wersa_profile_only.restype = None
+    lib.wersa_profile_only.argtypes = [ctypes.c_char_p]
     lib.wersa_profile_reset.restype = None
     lib.wersa_profile_reset.argtypes = []
     lib.wersa_profile_collect.restype = ctypes.c_int32
@@ -343,9 +345,11 @@ def wersa_block_backward(x, wq, wk, wv, wo, H, omega_rf, sigma, gate_w, gate_b, 
     return grads
 
 
-def wersa_profile_enable(on):
+def wersa_profile_enable(on, only=None):
+    """Switch the event bracketing on or off; `only` restricts it to one kernel name."""
     lib = load_library()
     lib.wersa_profile_reset()
+    lib.wersa_profile_only(only.encode() if only else None)
     lib.wersa_profile_enable(int(bool(on)))
 
 

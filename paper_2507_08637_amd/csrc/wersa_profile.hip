@@ -14,6 +14,8 @@ struct Rec {
   hipEvent_t a, b;
 };
 bool g_on = false;
+bool g_open = false;        // the last prof_begin recorded an event pair
+std::string g_only;         // when not empty: bracket only launches of this name
 std::vector<Rec> g_recs;
 std::vector<hipEvent_t> g_pool;
 size_t g_pool_used = 0;
@@ -39,15 +41,19 @@ std::vector<Agg> g_agg;
 bool profiling() { return g_on; }
 
 void prof_begin(const char *name, hipStream_t st) {
+  g_open = false;
   if (!g_on) return;
+  if (!g_only.empty() && g_only != name) return;
   hipEvent_t a = take_event(), b = take_event();
   if (!a || !b) return;
   g_recs.push_back(Rec{name, a, b});
   (void)hipEventRecord(a, st);
+  g_open = true;
 }
 void prof_end(hipStream_t st) {
-  if (!g_on || g_recs.empty()) return;
+  if (!g_on || !g_open || g_recs.empty()) return;
   (void)hipEventRecord(g_recs.back().b, st);
+  g_open = false;
 }
 }  // namespace wersa
 
@@ -57,6 +63,10 @@ extern "C" {
 
 void wersa_profile_enable(int on) {
   g_on = on != 0;
+}
+
+void wersa_profile_only(const char *name) {
+  g_only = name ? name : "";
 }
 
 void wersa_profile_reset(void) {
