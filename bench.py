@@ -24,6 +24,7 @@ PEAK = {"hbm": (8000.0, "GB/s"), "mfma_bf16": (2500.0, "TFLOP/s"), "fp32": (157.
 # runs summarised in profiles/mfma_path_config4_hbm_traffic.md (FETCH_SIZE scaled by the factor 2.0 that
 # a plain 1 GiB copy shows for this counter, WRITE_SIZE by 1.0).
 MIB = 1024.0 * 1024.0
+SURVEY_STEPS = 5   # untimed steps with every launch bracketed, to rank the kernels
 MEASURED_TRAFFIC_CONFIG4 = {
     "wersa_rows_fwd": (130.4 + 132.7) * MIB, "wersa_rows_bwd_q": (484.2 + 147.9) * MIB,
     "wersa_rows_bwd_k": (387.3 + 140.0) * MIB, "wersa_rows_bwd_v": (130.4 + 132.8) * MIB,
@@ -220,13 +221,13 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    # Untimed survey: two steps with every launch bracketed, to rank the kernels.  The timed
+    # Untimed survey: a few steps with every launch bracketed, to rank the kernels.  The timed
     # region then brackets only the dominant one, so that the event records do not sit between
     # all the other launches of the step being timed.
     survey, dominant = {}, None
     if not args.no_events:
         binding.wersa_profile_enable(True)
-        for _ in range(2):
+        for _ in range(SURVEY_STEPS):
             step()
         torch.cuda.synchronize()
         survey = binding.wersa_profile_collect()
@@ -269,7 +270,7 @@ def main():
                     "frac": achieved / peak, "traffic": traffic, "kernel": name,
                     "avg_launch_ms": avg_ms, "launches_per_step": launches / args.steps}
         # every kernel, from the untimed survey steps (all launches bracketed)
-        rec["kernels_ms_per_step"] = {k: round(v[0] / 2, 4) for k, v in
+        rec["kernels_ms_per_step"] = {k: round(v[0] / SURVEY_STEPS, 4) for k, v in
                                       sorted(survey.items(), key=lambda kv: -kv[1][0])}
     rec["roofline"] = roof
     if not args.no_cpu_baseline:

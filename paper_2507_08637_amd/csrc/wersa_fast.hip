@@ -80,37 +80,19 @@ __device__ __forceinline__ bf16x8 lds_perm8(const bf16_t *row, int base, int h) 
 }
 
 // ------------------------------------------------------------------------------------
-// Filter coefficients of the block-mean form:  X_F = sum_l coef_l * (sum over the aligned
-// 2^l block), coef_0 = F_0, coef_l = (F_l - F_{l-1}) / 2^l  (l = 1..L), 0 above L.
-// Also Omega^T in fp16 ([m][d]) for the projection's MFMA operand.
+// Per-call constants: block 0 writes the scalars; every block transposes its share of Omega
+// into Omega^T in fp16 ([m][d]), the projection's MFMA operand.  (The filter coefficients of
+// the block-mean form come from the gate kernel.)
 // ------------------------------------------------------------------------------------
-__device__ __forceinline__ void coef_of_slice(const float *F, int L, int s, float *coef) {
-  const float *f = F + s * (L + 1);
-  float *c = coef + s * 8;
-  c[0] = f[0];
-  for (int l = 1; l <= kMaxL; ++l) c[l] = l <= L ? (f[l] - f[l - 1]) / (float)(1 << l) : 0.f;
-  c[7] = 0.f;
-}
-__global__ void coef_kernel(const float *F, int L, int slices, float *coef) {
-  const int s = blockIdx.x * blockDim.x + threadIdx.x;
-  if (s < slices) coef_of_slice(F, L, s, coef);
-}
-// One launch for the per-call constants: block 0 writes the scalars (and, in the backward where
-// F is already known, the filter coefficients); every block transposes its share of Omega.
 __global__ void setup_kernel(const float *sigma, float bw_floor, const bf16_t *omega, int d, int m,
-                             const float *F, int L, int slices, float *scalars, float *coef,
-                             _Float16 *omT) {
-  if (blockIdx.x == 0) {
-    if (threadIdx.x == 0) {
-      const float s = *sigma;
-      const float se = fmaxf(s, bw_floor);
-      scalars[0] = 1.0f / (se * sqrtf((float)m));
-      scalars[1] = se;
-      scalars[2] = s > bw_floor ? 1.0f : 0.0f;
-      scalars[3] = 1.0f;
-    }
-    if (F)
-      for (int s = threadIdx.x; s < slices; s += blockDim.x) coef_of_slice(F, L, s, coef);
+                             float *scalars, _Float16 *omT) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    const float s = *sigma;
+    const float se = fmaxf(s, bw_floor);
+    scalars[0] = 1.0f / (se * sqrtf((float)m));
+    scalars[1] = se;
+    scalars[2] = s > bw_floor ? 1.0f : 0.0f;
+    scalars[3] = 1.0f;
   }
   const int e = blockIdx.x * blockDim.x + threadIdx.x;
   if (e < d * m) {
@@ -296,9 +278,14 @@ __device__ __forceinline__ bf16x8 splat_bf16x8(float v) {
 // A operand.  X_F and Y tiles of 64 rows go through double-buffered LDS (Y transposed so that
 // t runs along the operand's k index); the next tile is fetched while the current one is used.
 // ------------------------------------------------------------------------------------
-template <int DH, int FW>
+// PREP (backward, Q side): Y = dO, rowdiv = D, and the weights are computed here instead of
+// read: w_t = dD_t = -<dO_t, O_t> / D_t from the rows of O (`orows`, laid out like Y).  The
+// feature block 0 also writes dD [slices][n] for the gradient rows kernel and one partial sum
+// of dD per (slice, chunk) for d sigma.
+template <int DH, int FW, bool PREP>
 __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
     const _Float16 *xf, const bf16_t *y, View vy, const float *rowdiv, const float *w,
+    const bf16_t *orows, float *dDout, float *dDpart,
     const _Float16 *omT, int n, int m, int rows_per_chunk, float *Spart, float *zpart) {
   constexpr int KS = DH / 16;   // k-steps of the projection
   constexpr int RT = FW / 32;   // feature tiles per wave
@@ -342,7 +329,23 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
   u16x8 yr[LPT], xr[LPT];
   float inv = 1.0f, wv = 1.0f;
   const int yrow = tid & 63, ypiece0 = tid >> 6;
+  // PREP: the wave owns rows 16 wave .. 16 wave + 15 of the tile for the row dot products; lane
+  // (r, quarter) takes a quarter of row r, the four quarters meet by two lane exchanges.
+  constexpr int QP = CPR / 4;   // 16-byte pieces per quarter row
+  bf16x8 po[PREP ? QP : 1], pd[PREP ? QP : 1];
+  float pdiv = 1.0f, dsum = 0.f;
+  const int prow = 16 * wave + (lane & 15), pquart = lane >> 4;
+  const bf16_t *os = PREP ? orows + vy.slice_base(slice) : nullptr;
   auto fetch = [&](int t0) {
+    if (PREP) {
+#pragma unroll
+      for (int j = 0; j < QP; ++j) {
+        const int64_t off = (int64_t)(t0 + prow) * vy.sn + (pquart * QP + j) * 8;
+        po[j] = *reinterpret_cast<const bf16x8 *>(os + off);
+        pd[j] = *reinterpret_cast<const bf16x8 *>(ys + off);
+      }
+      pdiv = rd[t0 + prow];
+    }
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
       const int e = tid + 256 * i, r = e / CPR, cc = e % CPR;
@@ -350,8 +353,9 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
       yr[i] = *reinterpret_cast<const u16x8 *>(ys + (int64_t)(t0 + yrow) * vy.sn + (ypiece0 + 4 * i) * 8);
     }
     inv = rd ? rd[t0 + yrow] : 1.0f;   // divided at the stash, when the load has landed
-    if (tid < 64) wv = ws ? ws[t0 + tid] : 1.0f;
+    if (!PREP && tid < 64) wv = ws ? ws[t0 + tid] : 1.0f;
   };
+  int t_stash = t_begin;   // first row of the tile the registers hold
   auto stash = [&](int buf) {
     const float rinv = 1.0f / inv;
 #pragma unroll
@@ -368,7 +372,21 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
         for (int q = 0; q < 8; ++q) yt[buf][(c0 + q) * YS + yrow] = yr[i][q];
       }
     }
-    if (tid < 64) wl[buf][tid] = cvt_bf16(wv);
+    if (PREP) {
+      float dot = 0.f;
+#pragma unroll
+      for (int j = 0; j < QP; ++j) dot = dot8_bf16(po[j], pd[j], dot);
+      dot += __shfl_xor(dot, 16, 64);
+      dot += __shfl_xor(dot, 32, 64);
+      const float dDt = -dot / pdiv;
+      if (lane < 16) {
+        wl[buf][prow] = cvt_bf16(dDt);
+        dsum += dDt;
+        if (blockIdx.y == 0) dDout[(int64_t)slice * n + t_stash + prow] = dDt;
+      }
+    } else if (tid < 64) {
+      wl[buf][tid] = cvt_bf16(wv);
+    }
   };
 
   if (steps > 0) {
@@ -379,7 +397,10 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
   for (int s = 0; s < steps; ++s) {
     const int buf = s & 1;
     const bool more = s + 1 < steps;
-    if (more) fetch(t_begin + 64 * (s + 1));
+    if (more) {
+      t_stash = t_begin + 64 * (s + 1);
+      fetch(t_stash);
+    }
 #pragma unroll
     for (int ti = 0; ti < 2; ++ti) {
       f16x8 xa[KS];   // projection A operand: rows 32 ti + l32, k = 8h + q (+16 per k-step)
@@ -421,6 +442,13 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
         sp[(int64_t)(f0 + 32 * rt + acc_row(i, h)) * DH + 32 * ct + l32] = S[rt][ct][i];
     const float zt = zacc[rt] + __shfl_xor(zacc[rt], 32, 64);
     if (h == 0) zpart[((int64_t)slice * chunks + chunk) * m + f0 + 32 * rt + l32] = zt;
+  }
+  if (PREP && blockIdx.y == 0) {   // sum of dD over this chunk's rows, fixed order
+    __shared__ float red[4];
+    const float wsum = wave_sum64(dsum);
+    if (lane == 0) red[wave] = wsum;
+    __syncthreads();
+    if (tid == 0) dDpart[(int64_t)slice * chunks + chunk] = (red[0] + red[1]) + (red[2] + red[3]);
   }
 }
 
@@ -929,41 +957,6 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
   }
 }
 
-// dD_t = -<dO_t, O_t> / D_t, and per-block partial sums of dD (for d sigma).
-constexpr int kPrepIters = 16;
-template <int DH>
-__global__ __launch_bounds__(256) void prep_bwd_kernel(const bf16_t *dout, const bf16_t *out, View v,
-                                                      const float *D, int n, float *dD,
-                                                      float *dDpart) {
-  constexpr int CPR = DH / 8, RPB = 256 / CPR;
-  const int slice = blockIdx.y;
-  const int cc = threadIdx.x % CPR;
-  float total = 0.f;
-  for (int it = 0; it < kPrepIters; ++it) {
-    const int t = (blockIdx.x * kPrepIters + it) * RPB + threadIdx.x / CPR;
-    float acc = 0.f;
-    if (t < n) {
-      const int64_t off = v.slice_base(slice) + (int64_t)t * v.sn + cc * 8;
-      const u16x8 a = *reinterpret_cast<const u16x8 *>(dout + off);
-      const u16x8 b = *reinterpret_cast<const u16x8 *>(out + off);
-#pragma unroll
-      for (int q = 0; q < 8; ++q) acc = fmaf(bf16_to_f32(a[q]), bf16_to_f32(b[q]), acc);
-    }
-    for (int o = CPR / 2; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
-    if (t < n && cc == 0) {
-      const float val = -acc / D[(int64_t)slice * n + t];
-      dD[(int64_t)slice * n + t] = val;
-      total += val;
-    }
-  }
-  __shared__ float red[4];
-  const float ws = wave_sum64(total);
-  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ws;
-  __syncthreads();
-  if (threadIdx.x == 0)
-    dDpart[(int64_t)slice * gridDim.x + blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
-}
-
 // dQ[t][:] += dqbar / n  (the pooled-query path), bf16 read-modify-write with 16-byte accesses,
 // four independent pieces per thread.
 template <int DH>
@@ -1007,7 +1000,6 @@ struct FastPlan {
   int chunksC, rowsC;   // split of n in phiT_contract
   int rowGroupsA, rowsWgsA;   // apply-type rows kernel (4 waves): row groups / workgroups per slice
   int rowGroupsG, rowsWgsG;   // gradient-type rows kernel (8 waves)
-  int prepBlocks;       // blocks per slice of prep_bwd
 };
 
 FastPlan fast_plan(const wersa_desc &c) {
@@ -1033,8 +1025,6 @@ FastPlan fast_plan(const wersa_desc &c) {
   p.rowGroupsG = (blocks + nwr - 1) / nwr;
   wgs = (256 + slices - 1) / slices;       // one 8-wave workgroup per compute unit in total
   p.rowsWgsG = wgs < p.rowGroupsG ? wgs : p.rowGroupsG;
-  const int rpb = (256 / (c.d / 8)) * kPrepIters;
-  p.prepBlocks = (c.n + rpb - 1) / rpb;
   return p;
 }
 
@@ -1046,23 +1036,28 @@ struct FastWs {
   int64_t total;
 };
 
-FastWs fast_ws(const wersa_desc &c, const FastPlan &p, int bwd, float *base) {
+// Workspace pieces; the per-call constants and the forward's bf16 operand copies live in the
+// saved buffer (the backward reads them back instead of rebuilding them).
+FastWs fast_ws(const wersa_desc &c, const FastPlan &p, int bwd, float *base, float *saved) {
   FastWs w{};
   Bump b(base);
   const int64_t sl = (int64_t)c.B * c.H, md = (int64_t)c.m * c.d;
-  w.scalars = b.take(64);
-  w.coef = b.take(sl * 8);
+  const SavedLayout sv = saved_layout(c);
+  if (saved) {
+    w.scalars = saved + sv.scalars;
+    w.coef = saved + sv.coef;
+    w.omT = reinterpret_cast<_Float16 *>(saved + sv.omT);
+    w.Sx = reinterpret_cast<bf16_t *>(saved + sv.Sx);
+    w.ST = reinterpret_cast<bf16_t *>(saved + sv.ST);
+    w.zb = reinterpret_cast<bf16_t *>(saved + sv.zb);
+  }
   w.qpart = b.take(sl * p.chunksQ * c.d);
-  w.omT = reinterpret_cast<_Float16 *>(b.take(md / 2));
   w.Spart = b.take(sl * p.chunksC * md);
   w.zpart = b.take(sl * p.chunksC * c.m);
   const int64_t mx = (int64_t)c.m * (c.d + 16);
-  w.Sx = reinterpret_cast<bf16_t *>(b.take(sl * mx / 2));
-  w.ST = reinterpret_cast<bf16_t *>(b.take(sl * md / 2));
-  w.zb = reinterpret_cast<bf16_t *>(b.take(sl * c.m / 2));
   if (bwd) {
     w.dD = b.take(sl * c.n);
-    w.dDpart = b.take(sl * p.prepBlocks);
+    w.dDpart = b.take(sl * p.chunksC);
     w.dS = b.take(sl * md);
     w.dz = b.take(sl * c.m);
     w.dSx = reinterpret_cast<bf16_t *>(b.take(sl * mx / 2));
@@ -1117,21 +1112,26 @@ hipError_t launch_rows(const wersa_desc &c, const FastPlan &p, const _Float16 *x
   return go(&rows_kernel<DH, MODE, NW, 128>);
 }
 
+// orows != nullptr selects the backward form that derives dD from the rows of O itself.
 template <int DH>
 void launch_contract(const wersa_desc &c, const FastPlan &p, const _Float16 *xf, const bf16_t *y,
-                     const float *rowdiv, const float *wt, const FastWs &w, float *S, float *z,
+                     const float *rowdiv, const bf16_t *orows, const FastWs &w, float *S, float *z,
                      bf16_t *Mx, bf16_t *MT, bf16_t *bb, hipStream_t st) {
   const View tv{c.stride_b, c.stride_h, c.stride_n, c.H};
   const int slices = c.B * c.H;
   dim3 grid(p.chunksC, c.m / p.MB, slices);
-  if (p.FW == 64)
+  auto go = [&](auto kern) {
     WERSA_STAGE("wersa_phiT_contract", st,
-                phiT_contract_kernel<DH, 64><<<grid, 256, 0, st>>>(xf, y, tv, rowdiv, wt, w.omT, c.n, c.m,
-                                                                    p.rowsC, w.Spart, w.zpart));
-  else
-    WERSA_STAGE("wersa_phiT_contract", st,
-                phiT_contract_kernel<DH, 32><<<grid, 256, 0, st>>>(xf, y, tv, rowdiv, wt, w.omT, c.n, c.m,
-                                                                    p.rowsC, w.Spart, w.zpart));
+                kern<<<grid, 256, 0, st>>>(xf, y, tv, rowdiv, nullptr, orows, w.dD, w.dDpart, w.omT, c.n, c.m,
+                                           p.rowsC, w.Spart, w.zpart));
+  };
+  if (p.FW == 64) {
+    if (orows) go(&phiT_contract_kernel<DH, 64, true>);
+    else go(&phiT_contract_kernel<DH, 64, false>);
+  } else {
+    if (orows) go(&phiT_contract_kernel<DH, 32, true>);
+    else go(&phiT_contract_kernel<DH, 32, false>);
+  }
   const int64_t W = (int64_t)c.m * DH;
   WERSA_STAGE("wersa_reduce_contract", st,
               reduce_contract_kernel<DH><<<dim3((unsigned)((W + 255) / 256), slices), 256, 0, st>>>(
@@ -1144,7 +1144,7 @@ wersa_status fast_forward_t(const wersa_desc &c, const bf16_t *q, const bf16_t *
                             const float *gate_b, const float *scale_w, bf16_t *out, float *saved,
                             float *ws, hipStream_t st) {
   const FastPlan p = fast_plan(c);
-  const FastWs w = fast_ws(c, p, 0, ws);
+  const FastWs w = fast_ws(c, p, 0, ws, saved);
   const SavedLayout sv = saved_layout(c);
   const int slices = c.B * c.H;
   const View tv{c.stride_b, c.stride_h, c.stride_n, c.H};
@@ -1154,14 +1154,13 @@ wersa_status fast_forward_t(const wersa_desc &c, const bf16_t *q, const bf16_t *
   _Float16 *KF = reinterpret_cast<_Float16 *>(saved + sv.KF);
 
   WERSA_STAGE("wersa_setup", st,
-              setup_kernel<<<(c.d * c.m + 255) / 256, 256, 0, st>>>(sigma, c.bw_floor, omega, c.d, c.m, nullptr,
-                                                                    c.L, slices, w.scalars, w.coef, w.omT));
+              setup_kernel<<<(c.d * c.m + 255) / 256, 256, 0, st>>>(sigma, c.bw_floor, omega, c.d, c.m, w.scalars,
+                                                                    w.omT));
   WERSA_STAGE("wersa_qbar", st,
               qbar_partial_kernel<DH><<<dim3(p.chunksQ, slices), 256, 0, st>>>(q, tv, c.n, p.rowsQ, w.qpart));
   WERSA_STAGE("gate_fwd_kernel", st,
               gate_fwd_kernel<<<slices, 256, 0, st>>>(w.qpart, p.chunksQ, c.n, c.d, c.L, c.H, gate_w, gate_b,
-                                                     scale_w, qbar, s, F));
-  WERSA_STAGE("coef_kernel", st, coef_kernel<<<(slices + 63) / 64, 64, 0, st>>>(F, c.L, slices, w.coef));
+                                                     scale_w, qbar, s, F, w.coef));
   WERSA_STAGE("wersa_haar_stage", st,
               haar_stage_kernel<DH><<<dim3(c.n / 64, slices), 256, 0, st>>>(q, tv, c.n, w.coef, QF));
   WERSA_STAGE("wersa_haar_stage", st,
@@ -1181,7 +1180,7 @@ wersa_status fast_backward_t(const wersa_desc &c, const bf16_t *q, const bf16_t 
                              float *dgate_b, float *dscale_w, float *dsigma, float *ws,
                              hipStream_t st) {
   const FastPlan p = fast_plan(c);
-  const FastWs w = fast_ws(c, p, 1, ws);
+  const FastWs w = fast_ws(c, p, 1, ws, const_cast<float *>(saved));   // operand copies are only read
   const SavedLayout sv = saved_layout(c);
   const int slices = c.B * c.H;
   const View tv{c.stride_b, c.stride_h, c.stride_n, c.H};
@@ -1189,22 +1188,13 @@ wersa_status fast_backward_t(const wersa_desc &c, const bf16_t *q, const bf16_t 
               *D = saved + sv.D;
   const _Float16 *QF = reinterpret_cast<const _Float16 *>(saved + sv.QF);
   const _Float16 *KF = reinterpret_cast<const _Float16 *>(saved + sv.KF);
-  const int prepBlocks = p.prepBlocks;
 
-  WERSA_STAGE("wersa_setup", st,
-              setup_kernel<<<(c.d * c.m + 255) / 256, 256, 0, st>>>(sigma, c.bw_floor, omega, c.d, c.m, F, c.L,
-                                                                    slices, w.scalars, w.coef, w.omT));
-  // S as bf16 MFMA operand (row-major) from the saved float32 S: a reduce over one "partial"
-  WERSA_STAGE("wersa_reduce_contract", st,
-              reduce_contract_kernel<DH><<<dim3((unsigned)(((int64_t)c.m * DH + 255) / 256), slices), 256, 0, st>>>(
-                  saved + sv.S, z, 1, c.m, w.scalars + 3, w.dS, w.dz, w.Sx, w.ST, w.zb));
-  WERSA_STAGE("wersa_prep_bwd", st,
-              prep_bwd_kernel<DH><<<dim3(prepBlocks, slices), 256, 0, st>>>(dout, out, tv, D, c.n, w.dD, w.dDpart));
-  // dX_F of the Q side needs only S, z; dS, dz need the full reduction over n first.
+  // dS = Phi_Q^T dN, dz = Phi_Q^T dD; the same pass derives dD_t = -<dO_t, O_t> / D_t from the
+  // rows of O and leaves it in the workspace for the Q-side gradient kernel.
+  launch_contract<DH>(c, p, QF, dout, D, out, w, w.dS, w.dz, w.dSx, w.dST, w.dzb, st);
   if (launch_rows<DH, 1>(c, p, QF, q, dout, D, w.dD, w, omega, w.Sx, nullptr, nullptr, dq, nullptr, w.partQ,
                          st) != hipSuccess)
     return WERSA_ERR_LAUNCH;
-  launch_contract<DH>(c, p, QF, dout, D, w.dD, w, w.dS, w.dz, w.dSx, w.dST, w.dzb, st);
   if (launch_rows<DH, 2>(c, p, KF, k, v, nullptr, nullptr, w, omega, w.dSx, nullptr, nullptr, dk, nullptr,
                          w.partK, st) != hipSuccess)
     return WERSA_ERR_LAUNCH;
@@ -1215,7 +1205,7 @@ wersa_status fast_backward_t(const wersa_desc &c, const bf16_t *q, const bf16_t 
               gate_bwd_slice_kernel<<<slices, 64, 0, st>>>(w.partQ, w.partK, p.rowsWgsG, c.L, c.d, c.H, s,
                                                            gate_w, scale_w, w.dF, w.dlogit, w.dqbar));
   WERSA_STAGE("gate_bwd_params_kernel", st,
-              gate_bwd_params_kernel<<<1, 256, 0, st>>>(w.dF, w.dlogit, s, qbar, w.dDpart, slices * prepBlocks,
+              gate_bwd_params_kernel<<<1, 256, 0, st>>>(w.dF, w.dlogit, s, qbar, w.dDpart, slices * p.chunksC,
                                                         c.B, c.H, c.L, c.d, c.eps, w.scalars, dgate_w,
                                                         dgate_b, dscale_w, dsigma));
   const int64_t chunks = (int64_t)c.n * (DH / 8);
@@ -1233,7 +1223,7 @@ bool fast_supported(const wersa_desc &c) {
 }
 
 size_t fast_workspace_bytes(const wersa_desc &c, int for_backward) {
-  return (size_t)fast_ws(c, fast_plan(c), for_backward, nullptr).total * sizeof(float);
+  return (size_t)fast_ws(c, fast_plan(c), for_backward, nullptr, nullptr).total * sizeof(float);
 }
 
 wersa_status fast_forward(const wersa_desc &c, const void *q, const void *k, const void *v,

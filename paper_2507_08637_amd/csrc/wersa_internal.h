@@ -48,6 +48,9 @@ inline bool use_fast(const wersa_desc &c) {
 
 struct SavedLayout {
   int64_t S, z, qbar, s, F, D, QF, KF, total;
+  // MFMA path only: per-call constants and bf16 operand copies written by the forward and
+  // read again by the backward (scalars, filter coefficients, Omega^T fp16, (S|z), S^T, z).
+  int64_t scalars, coef, omT, Sx, ST, zb;
 };
 inline SavedLayout saved_layout(const wersa_desc &c) {
   SavedLayout o;
@@ -60,10 +63,17 @@ inline SavedLayout saved_layout(const wersa_desc &c) {
   o.s = off;    off += up(sl * (c.L + 1));
   o.F = off;    off += up(sl * (c.L + 1));
   o.D = off;    off += up(sl * c.n);
-  o.QF = o.KF = -1;
+  o.QF = o.KF = o.scalars = o.coef = o.omT = o.Sx = o.ST = o.zb = -1;
   if (use_fast(c)) {  // filtered Q and K in fp16, kept for the backward
     o.QF = off; off += up(sl * c.n * c.d / 2);
     o.KF = off; off += up(sl * c.n * c.d / 2);
+    const int64_t md = (int64_t)c.m * c.d, mx = (int64_t)c.m * (c.d + 16);
+    o.scalars = off; off += 64;
+    o.coef = off;    off += up(sl * 8);
+    o.omT = off;     off += up(md / 2);
+    o.Sx = off;      off += up(sl * mx / 2);
+    o.ST = off;      off += up(sl * md / 2);
+    o.zb = off;      off += up(sl * c.m / 2);
   }
   o.total = off;
   return o;
