@@ -15,11 +15,36 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int BM = 256, BN = 256, BK = 64;   // workgroup tile; four waves of 128 x 128
-constexpr int LS = BK + 8;                   // LDS row stride (elements): 16-byte reads, no bank pile-up
+constexpr int BM = 256, BN = 256, BK = 64;   // workgroup tile
+constexpr int LS = BK + 8;                   // NT form: LDS tiles [row][k], row stride (elements)
+constexpr int LT = BM + 32;                  // TN form: LDS tiles [k][row]; 576-byte rows put four
+                                             // consecutive k rows into different bank quarters
 constexpr int kMaxSrc = 3;
 constexpr int kMaxSplit = 32;
+
+// MFMA operand (row or column l32 = lane % 32, k = 8 h + q) out of a tile stored [k][row] in LDS,
+// through the transposing LDS read of gfx950 (ds_read_b64_tr_b16): within each group of 16
+// lanes, lane i passes the address of four consecutive 16-bit values, taken as row i / 4,
+// columns 4 (i % 4) .. + 3 of a 4 x 16 block, and receives column i of that block.  (Lane
+// mapping checked on the GPU with an index-valued LDS array.)  `tile` points at (k row 0, first
+// row of the 32-row operand tile); krow is this lane's first k.
+__device__ __forceinline__ bf16x8 lds_operand_tr(const bf16_t *tile, int krow, int lane) {
+  const int i16 = lane & 15, grp = (lane >> 4) & 1;
+  const bf16_t *p0 = tile + (krow + (i16 >> 2)) * LT + 16 * grp + 4 * (i16 & 3);
+  typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)p0);
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p0 + 4 * LT));
+  s16x8 r;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    r[q] = lo[q];
+    r[4 + q] = hi[q];
+  }
+  return __builtin_bit_cast(bf16x8, r);
+}
 
 struct GemmSrc {
   const bf16_t *a[kMaxSrc];
@@ -32,12 +57,17 @@ __device__ __forceinline__ bf16_t to_bf16(float f) { return __builtin_bit_cast(b
 // TRANS = false: NT form, A [M][K] (lda), B [N][K] (ldb).  TRANS = true: TN form, A [K][M] (lda),
 // B [K][N] (ldb).  OUT_F32: float32 output at C + split * M * ldc (split = this workgroup's K
 // range), else bf16 output.  M % 256 == 0, N % 256 == 0, every K range a multiple of 64.
+// NW waves: 4 (2 x 2 waves of 128 x 128) or 8 (2 x 4 waves of 128 x 64, two waves per SIMD).
 // Logical tile ids are dealt to the eight XCDs in contiguous runs (workgroup w runs on XCD
 // w % 8), n fastest within a run, so that the workgroups sharing an A panel share an L2.
-template <bool TRANS, bool OUT_F32>
-__global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(GemmSrc src, int lda, int ldb, void *Cout,
-                                                           int ldc, int M, int N, int K, int k_chunk,
-                                                           int splits) {
+template <bool TRANS, bool OUT_F32, int NW>
+__global__ __launch_bounds__(64 * NW, 1) void gemm_bf16_kernel(GemmSrc src, int lda, int ldb, void *Cout,
+                                                              int ldc, int M, int N, int K, int k_chunk,
+                                                              int splits) {
+  constexpr int NT = 64 * NW;
+  constexpr int WN = NW / 2;            // waves along n
+  constexpr int TN = 8 / WN;            // 32-column tiles per wave: 4 or 2
+  constexpr int PPT = 2048 / NT;        // 16-byte pieces per thread and operand per k-step
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16_t *At = reinterpret_cast<bf16_t *>(smem_raw);          // [2][BM][LS]
   bf16_t *Bt = At + 2 * BM * LS;                              // [2][BN][LS]
@@ -50,54 +80,51 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(GemmSrc src, int lda,
   const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
   const int k_begin = split * k_chunk, k_end = min(K, k_begin + k_chunk);
   const int steps_per_src = (k_end - k_begin) / BK, steps = steps_per_src * src.count;
-  const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
+  const int wm = (wave / WN) * 128, wn = (wave % WN) * (32 * TN);
 
-  f32x16 acc[4][4];
+  f32x16 acc[4][TN];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  u16x8 ra[8], rb[8];
+  u16x8 ra[PPT], rb[PPT];
   auto fetch = [&](int s) {
     const int which = s / steps_per_src, k0 = k_begin + (s % steps_per_src) * BK;
     const bf16_t *A = src.a[which], *B = src.b[which];
     if (!TRANS) {   // 256 rows x 8 pieces of 16 bytes along K, row-major
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int e = tid + 256 * i, r = e >> 3, cc = e & 7;
+      for (int i = 0; i < PPT; ++i) {
+        const int e = tid + NT * i, r = e >> 3, cc = e & 7;
         ra[i] = *reinterpret_cast<const u16x8 *>(A + (int64_t)(m0 + r) * lda + k0 + cc * 8);
         rb[i] = *reinterpret_cast<const u16x8 *>(B + (int64_t)(n0 + r) * ldb + k0 + cc * 8);
       }
-    } else {        // one k per lane, 8 consecutive rows per piece
+    } else {        // 64 k rows x 32 pieces of 16 bytes along the output rows, as stored
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int p = wave + 4 * i;
-        ra[i] = *reinterpret_cast<const u16x8 *>(A + (int64_t)(k0 + lane) * lda + m0 + 8 * p);
-        rb[i] = *reinterpret_cast<const u16x8 *>(B + (int64_t)(k0 + lane) * ldb + n0 + 8 * p);
+      for (int i = 0; i < PPT; ++i) {
+        const int e = tid + NT * i, r = e >> 5, cc = e & 31;
+        ra[i] = *reinterpret_cast<const u16x8 *>(A + (int64_t)(k0 + r) * lda + m0 + cc * 8);
+        rb[i] = *reinterpret_cast<const u16x8 *>(B + (int64_t)(k0 + r) * ldb + n0 + cc * 8);
       }
     }
   };
   auto stash = [&](int buf) {
-    bf16_t *as = At + buf * BM * LS, *bs = Bt + buf * BN * LS;
+    bf16_t *as = At + buf * BM * LS, *bs = Bt + buf * BN * LS;   // BM * LS == BK * LT
     if (!TRANS) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int e = tid + 256 * i, r = e >> 3, cc = e & 7;
+      for (int i = 0; i < PPT; ++i) {
+        const int e = tid + NT * i, r = e >> 3, cc = e & 7;
         *reinterpret_cast<u16x8 *>(&as[r * LS + cc * 8]) = ra[i];
         *reinterpret_cast<u16x8 *>(&bs[r * LS + cc * 8]) = rb[i];
       }
-    } else {        // transposing writes: for each q the wave covers 64 consecutive 2-byte slots
+    } else {        // [k][row] tiles: the transposition happens at the operand reads
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int p = wave + 4 * i;
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-          as[(8 * p + q) * LS + lane] = ra[i][q];
-          bs[(8 * p + q) * LS + lane] = rb[i][q];
-        }
+      for (int i = 0; i < PPT; ++i) {
+        const int e = tid + NT * i, r = e >> 5, cc = e & 31;
+        *reinterpret_cast<u16x8 *>(&as[r * LT + cc * 8]) = ra[i];
+        *reinterpret_cast<u16x8 *>(&bs[r * LT + cc * 8]) = rb[i];
       }
     }
   };
@@ -111,19 +138,23 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(GemmSrc src, int lda,
     const int buf = s & 1;
     const bool more = s + 1 < steps;
     if (more) fetch(s + 1);
-    const bf16_t *as = At + buf * BM * LS + wm * LS, *bs = Bt + buf * BN * LS + wn * LS;
+    const bf16_t *as = At + buf * BM * LS + (TRANS ? wm : wm * LS);
+    const bf16_t *bs = Bt + buf * BN * LS + (TRANS ? wn : wn * LS);
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 a[4], b[4];
+      bf16x8 a[4], b[TN];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        a[i] = *reinterpret_cast<const bf16x8 *>(&as[(32 * i + l32) * LS + 16 * ks + 8 * h]);
-        b[i] = *reinterpret_cast<const bf16x8 *>(&bs[(32 * i + l32) * LS + 16 * ks + 8 * h]);
-      }
+      for (int i = 0; i < 4; ++i)
+        a[i] = TRANS ? lds_operand_tr(as + 32 * i, 16 * ks + 8 * h, lane)
+                     : *reinterpret_cast<const bf16x8 *>(&as[(32 * i + l32) * LS + 16 * ks + 8 * h]);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        b[j] = TRANS ? lds_operand_tr(bs + 32 * j, 16 * ks + 8 * h, lane)
+                     : *reinterpret_cast<const bf16x8 *>(&bs[(32 * j + l32) * LS + 16 * ks + 8 * h]);
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
     if (more) stash(buf ^ 1);
@@ -136,30 +167,30 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(GemmSrc src, int lda,
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int row = m0 + wm + 32 * i + 8 * (r >> 2) + 4 * h + (r & 3);
           C[(int64_t)row * ldc + n0 + wn + 32 * j + l32] = acc[i][j][r];
         }
   } else {
-    // bf16 through a wave-private LDS tile of 32 rows x 128 columns: 16-byte row-major stores.
-    // (All waves are past the last barrier of the loop: the operand tiles are free.)
-    constexpr int ES = 128 + 8;
+    // bf16 through a wave-private LDS tile of 32 rows x (32 TN) columns: 16-byte row-major
+    // stores.  (All waves are past the last barrier of the loop: the operand tiles are free.)
+    constexpr int ES = 32 * TN + 8, PPR = 4 * TN;   // tile row stride; 16-byte pieces per row
     bf16_t *C = reinterpret_cast<bf16_t *>(Cout);
     bf16_t *tl = reinterpret_cast<bf16_t *>(smem_raw) + wave * (32 * ES);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       __builtin_amdgcn_wave_barrier();
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int r = 0; r < 16; ++r)
           tl[(8 * (r >> 2) + 4 * h + (r & 3)) * ES + 32 * j + l32] = to_bf16(acc[i][j][r]);
       __builtin_amdgcn_wave_barrier();
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int e = lane + 64 * u, r = e >> 4, cc = e & 15;
+      for (int u = 0; u < 32 * PPR / 64; ++u) {
+        const int e = lane + 64 * u, r = e / PPR, cc = e % PPR;
         const u16x8 piece = *reinterpret_cast<const u16x8 *>(&tl[r * ES + cc * 8]);
         *reinterpret_cast<u16x8 *>(C + (int64_t)(m0 + wm + 32 * i + r) * ldc + n0 + wn + cc * 8) = piece;
       }
@@ -195,18 +226,20 @@ __global__ void transpose_bf16_kernel(const bf16_t *src, int R, int C, bf16_t *d
 }
 
 constexpr size_t kGemmSmem = (size_t)2 * (BM + BN) * LS * sizeof(bf16_t);
+static_assert(BM * LS == BK * LT && BN == BM, "both tile forms share one LDS budget");
 
 template <bool TRANS, bool OUT_F32>
 hipError_t launch_gemm(const char *name, const GemmSrc &src, int lda, int ldb, void *C, int ldc, int M, int N,
                        int K, int k_chunk, int splits, hipStream_t st) {
-  auto kern = &gemm_bf16_kernel<TRANS, OUT_F32>;
+  constexpr int kGemmWaves = 8;   // two waves per SIMD
+  auto kern = &gemm_bf16_kernel<TRANS, OUT_F32, kGemmWaves>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmSmem);
   if (e != hipSuccess) return e;
   const int total = (M / BM) * (N / BN) * splits;
   const int grid = ((total + 7) / 8) * 8;
   WERSA_STAGE(name, st,
-              kern<<<grid, 256, kGemmSmem, st>>>(src, lda, ldb, C, ldc, M, N, K, k_chunk, splits));
+              kern<<<grid, 64 * kGemmWaves, kGemmSmem, st>>>(src, lda, ldb, C, ldc, M, N, K, k_chunk, splits));
   return hipSuccess;
 }
 
