@@ -240,6 +240,16 @@ __global__ __launch_bounds__(256) void haar_stage_kernel(const bf16_t *x, View v
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
+// Transposing LDS read of gfx950 (ds_read_b64_tr_b16): within each group of 16 lanes, lane i
+// passes the address of four consecutive 16-bit values, taken as row i / 4, columns
+// 4 (i % 4) .. + 3 of a 4 x 16 block, and receives column i of that block.  (Lane mapping
+// checked on the GPU with an index-valued LDS array.)
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ bf16x4 lds_read_tr4(const bf16_t *p) {
+  typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
+  return __builtin_bit_cast(bf16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)p));
+}
+
 // ReLU on a packed bf16 operand: as 16-bit integers, negative floats are negative integers.
 __device__ __forceinline__ bf16x8 relu_bf16x8(bf16x8 p) {
   s16x8 s = __builtin_bit_cast(s16x8, p);
@@ -561,6 +571,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
   if (MODE == 0) { s_bb = reinterpret_cast<bf16_t *>(p); p += (size_t)mc * 2; }        // [mc]
   float *s_wave = reinterpret_cast<float *>(p); p += (size_t)NW * 64 * 4;              // [waves][64]
   constexpr int TS = 36;                // row stride (elements) of the per-wave 64 x 32 epilogue tile
+  constexpr int TT = 68;                // column stride (elements) of the same tile held transposed [32][64]
   bf16_t *s_tile = reinterpret_cast<bf16_t *>(p);                                      // [waves][64][TS]
 
   const int slice = blockIdx.y;
@@ -782,6 +793,29 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
       if (rg + gridDim.x < row_groups && t_next < n) load_rows(t_next);
     }
     bf16_t *tl = s_tile + wave * (64 * TS);
+    // Gradient modes: output tiles leave through the wave's LDS tile held transposed ([column][row]): a lane
+    // stores its four consecutive accumulator rows as one 8-byte write, and transposing reads
+    // hand back 8-byte row-major pieces (read u: rows 16 (u % 4) + lane % 16, columns
+    // 16 (u / 4) + 4 (lane / 16) .. + 3) for the global stores.
+    const int i16 = lane & 15, g16 = lane >> 4;
+    auto tile_put = [&](int ti, const float *v16) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        bf16x4 pk;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pk[e] = (__bf16)v16[4 * g + e];
+        *reinterpret_cast<bf16x4 *>(&tl[l32 * TT + 32 * ti + 8 * g + 4 * h]) = pk;
+      }
+    };
+    auto tile_store = [&](bf16_t *dst, int64_t sn, int col0) {
+      bf16x4 piece[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        piece[u] = lds_read_tr4(&tl[(16 * (u >> 2) + 4 * g16 + (i16 >> 2)) * TT + 16 * (u & 3) + 4 * (i16 & 3)]);
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        *reinterpret_cast<bf16x4 *>(dst + (int64_t)(16 * (u & 3) + i16) * sn + col0 + 16 * (u >> 2) + 4 * g16) = piece[u];
+    };
     const int prow = lane >> 3, pcol = (lane & 7) * 4;   // this lane's 8-byte piece: rows prow + 8 j
     bf16_t *os = out0 + vo.slice_base(slice) + (int64_t)t0 * vo.sn;
 
@@ -861,11 +895,15 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
 #pragma unroll
       for (int ti = 0; ti < 2; ++ti) {
         float g1[8], x1[8];
+        bf16x4 xq[4];   // X at this lane's accumulator positions: rows 8 g + 4 h + e of column l32
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          xq[g] = lds_read_tr4(&tl[(32 * ti + 8 * g + 4 * h + (i16 >> 2)) * TS + 16 * (g16 & 1) + 4 * (i16 & 3)]);
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
           const float ga = acc0[ti][ct][2 * k], gb = acc0[ti][ct][2 * k + 1];
-          const float xa = bf16_to_f32(tl[(32 * ti + acc_row(2 * k, h)) * TS + l32]);
-          const float xb2 = bf16_to_f32(tl[(32 * ti + acc_row(2 * k + 1, h)) * TS + l32]);
+          const float xa = (float)xq[k >> 1][2 * (k & 1)];
+          const float xb2 = (float)xq[k >> 1][2 * (k & 1) + 1];
           u[0] = fmaf(ga, xa, fmaf(gb, xb2, u[0]));
           g1[k] = ga + gb;
           x1[k] = xa + xb2;
@@ -895,7 +933,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
 #pragma unroll
       for (int ti = 0; ti < 2; ++ti) {
         const float T5 = fmaf(cf[5], g5[ti], T6);
-        float g1[8], g2[4], g3[4];
+        float g1[8], g2[4], g3[4], o16[16];
 #pragma unroll
         for (int k = 0; k < 8; ++k) g1[k] = acc0[ti][ct][2 * k] + acc0[ti][ct][2 * k + 1];
 #pragma unroll
@@ -917,23 +955,16 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
 #pragma unroll
               for (int e = 0; e < 2; ++e) {
                 const int i = 2 * kk + e;
-                tl[(32 * ti + acc_row(i, h)) * TS + l32] = cvt_bf16(fmaf(cf[0], acc0[ti][ct][i], T1));
+                o16[i] = fmaf(cf[0], acc0[ti][ct][i], T1);
               }
             }
           }
         }
+        tile_put(ti, o16);
       }
       __builtin_amdgcn_wave_barrier();
       // ---- LDS -> dX
-      {
-        bf16x4 piece[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j)
-          piece[j] = *reinterpret_cast<const bf16x4 *>(&tl[(prow + 8 * j) * TS + pcol]);
-#pragma unroll
-        for (int j = 0; j < 8; ++j)
-          *reinterpret_cast<bf16x4 *>(os + (int64_t)(prow + 8 * j) * vo.sn + 32 * (cbase + ct) + pcol) = piece[j];
-      }
+      tile_store(os, vo.sn, 32 * (cbase + ct));
     }
   }
   if (IS_APPLY) return;
