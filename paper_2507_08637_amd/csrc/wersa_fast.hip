@@ -240,16 +240,6 @@ __global__ __launch_bounds__(256) void haar_stage_kernel(const bf16_t *x, View v
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
-// Transposing LDS read of gfx950 (ds_read_b64_tr_b16): within each group of 16 lanes, lane i
-// passes the address of four consecutive 16-bit values, taken as row i / 4, columns
-// 4 (i % 4) .. + 3 of a 4 x 16 block, and receives column i of that block.  (Lane mapping
-// checked on the GPU with an index-valued LDS array.)
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ bf16x4 lds_read_tr4(const bf16_t *p) {
-  typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
-  return __builtin_bit_cast(bf16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)p));
-}
-
 // ReLU on a packed bf16 operand: as 16-bit integers, negative floats are negative integers.
 __device__ __forceinline__ bf16x8 relu_bf16x8(bf16x8 p) {
   s16x8 s = __builtin_bit_cast(s16x8, p);
@@ -279,6 +269,16 @@ __device__ __forceinline__ bf16x8 splat_bf16x8(float v) {
   return r;
 }
 
+// Transposing LDS read of gfx950 (ds_read_b64_tr_b16): within each group of 16 lanes, lane i
+// passes the address of four consecutive 16-bit values, taken as row i / 4, columns
+// 4 (i % 4) .. + 3 of a 4 x 16 block, and receives column i of that block.  (Lane mapping
+// checked on the GPU with an index-valued LDS array.)
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ bf16x4 lds_read_tr4(const bf16_t *p) {
+  typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
+  return __builtin_bit_cast(bf16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)p));
+}
+
 // ------------------------------------------------------------------------------------
 // phiT_contract: for the rows of one chunk and the features [f0, f0 + 4*FW) of one slice
 //   Spart[r][c] = sum_t ReLU(X_F Omega)[t][r] * (Y[t][c] / rowdiv_t)
@@ -302,9 +302,10 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
   constexpr int CT = DH / 32;   // column tiles of Y
   constexpr int CPR = DH / 8;   // 16-byte pieces per row
   constexpr int LPT = 64 * CPR / 256;   // pieces per thread per tile
-  constexpr int YS = 64 + 4;    // row stride (elements) of the transposed Y tile
+  constexpr int YS = DH + 32;   // row stride (elements) of the Y tile [t][column]: 64 bytes past a multiple
+                                // of 256, so the four rows of a transposing read fall into different bank quarters
   constexpr int XS = DH + 8;    // row stride (elements) of the X_F tile
-  __shared__ __attribute__((aligned(16))) bf16_t yt[2][DH * YS];
+  __shared__ __attribute__((aligned(16))) bf16_t yt[2][64 * YS];
   __shared__ __attribute__((aligned(16))) _Float16 xt[2][64 * XS];
   __shared__ __attribute__((aligned(16))) bf16_t wl[2][64];
   const int slice = blockIdx.z, chunk = blockIdx.x, chunks = gridDim.x;
@@ -334,11 +335,10 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
   const float *rd = rowdiv ? rowdiv + (int64_t)slice * n : nullptr;
   const float *ws = w ? w + (int64_t)slice * n : nullptr;
 
-  // X_F pieces are taken row-major (coalesced); Y pieces one row per lane (piece index from the
-  // wave), so that the transposing LDS writes of a wave hit 64 consecutive 2-byte slots.
+  // X_F and Y pieces are taken row-major (coalesced) and stored as they are; the Y operand
+  // (t along k) comes out of its tile through transposing LDS reads.
   u16x8 yr[LPT], xr[LPT];
-  float inv = 1.0f, wv = 1.0f;
-  const int yrow = tid & 63, ypiece0 = tid >> 6;
+  float inv[LPT], wv = 1.0f;
   // PREP: the wave owns rows 16 wave .. 16 wave + 15 of the tile for the row dot products; lane
   // (r, quarter) takes a quarter of row r, the four quarters meet by two lane exchanges.
   constexpr int QP = CPR / 4;   // 16-byte pieces per quarter row
@@ -360,26 +360,25 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
     for (int i = 0; i < LPT; ++i) {
       const int e = tid + 256 * i, r = e / CPR, cc = e % CPR;
       xr[i] = *reinterpret_cast<const u16x8 *>(xs + (int64_t)(t0 + r) * DH + cc * 8);
-      yr[i] = *reinterpret_cast<const u16x8 *>(ys + (int64_t)(t0 + yrow) * vy.sn + (ypiece0 + 4 * i) * 8);
+      yr[i] = *reinterpret_cast<const u16x8 *>(ys + (int64_t)(t0 + r) * vy.sn + cc * 8);
+      inv[i] = rd ? rd[t0 + r] : 1.0f;   // divided at the stash, when the load has landed
     }
-    inv = rd ? rd[t0 + yrow] : 1.0f;   // divided at the stash, when the load has landed
     if (!PREP && tid < 64) wv = ws ? ws[t0 + tid] : 1.0f;
   };
   int t_stash = t_begin;   // first row of the tile the registers hold
   auto stash = [&](int buf) {
-    const float rinv = 1.0f / inv;
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
       const int e = tid + 256 * i, r = e / CPR, cc = e % CPR;
       *reinterpret_cast<u16x8 *>(&xt[buf][r * XS + cc * 8]) = xr[i];
-      const int c0 = (ypiece0 + 4 * i) * 8;
       if (rd) {
+        const float rinv = 1.0f / inv[i];
+        u16x8 sc;
 #pragma unroll
-        for (int q = 0; q < 8; ++q)
-          yt[buf][(c0 + q) * YS + yrow] = cvt_bf16(bf16_to_f32(yr[i][q]) * rinv);
+        for (int q = 0; q < 8; ++q) sc[q] = cvt_bf16(bf16_to_f32(yr[i][q]) * rinv);
+        *reinterpret_cast<u16x8 *>(&yt[buf][r * YS + cc * 8]) = sc;
       } else {
-#pragma unroll
-        for (int q = 0; q < 8; ++q) yt[buf][(c0 + q) * YS + yrow] = yr[i][q];
+        *reinterpret_cast<u16x8 *>(&yt[buf][r * YS + cc * 8]) = yr[i];
       }
     }
     if (PREP) {
@@ -421,9 +420,20 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
 #pragma unroll
       for (int a = 0; a < 2; ++a) {
         wp[a] = lds_perm8(&wl[buf][0], 32 * ti + 16 * a, h);
+        // k-slot (h, q) of the chained MFMA stands for row 16 a + 8 (q / 4) + 4 h + (q % 4): two
+        // transposing reads of four consecutive rows each, at column 32 ct + l32.
+        const int i16 = lane & 15, c16 = 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
+        const int trow = 32 * ti + 16 * a + 4 * h + (i16 >> 2);
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct)
-          yb[a][ct] = lds_perm8(&yt[buf][(32 * ct + l32) * YS], 32 * ti + 16 * a, h);
+        for (int ct = 0; ct < CT; ++ct) {
+          const bf16x4 lo = lds_read_tr4(&yt[buf][trow * YS + 32 * ct + c16]);
+          const bf16x4 hi = lds_read_tr4(&yt[buf][(trow + 8) * YS + 32 * ct + c16]);
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            yb[a][ct][q] = lo[q];
+            yb[a][ct][4 + q] = hi[q];
+          }
+        }
       }
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
