@@ -117,12 +117,12 @@ __global__ __launch_bounds__(256) void qbar_partial_kernel(const bf16_t *q, View
 #pragma unroll
   for (int e = 0; e < 8; ++e) acc[e] = 0.f;
   int t = t0 + rr;
-  for (; t + 3 * RPI < t1; t += 4 * RPI) {   // four independent loads in flight
-    u16x8 x[4];
+  for (; t + 7 * RPI < t1; t += 8 * RPI) {   // eight independent loads in flight
+    u16x8 x[8];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) x[u] = *reinterpret_cast<const u16x8 *>(qs + (int64_t)(t + u * RPI) * v.sn);
+    for (int u = 0; u < 8; ++u) x[u] = *reinterpret_cast<const u16x8 *>(qs + (int64_t)(t + u * RPI) * v.sn);
 #pragma unroll
-    for (int u = 0; u < 4; ++u)
+    for (int u = 0; u < 8; ++u)
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc[e] += bf16_to_f32(x[u][e]);
   }
@@ -477,41 +477,45 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
 //   Mx  [m][DH+16]: row r = (M[r][0..DH), b[r], 0 x 15)   (A operand of dPhi = Y M^T + a b^T)
 //   MT  [DH][m]   : M transposed                           (B operand of Phi M)
 //   bb  [m]       : b in bf16
+// One workgroup = 64 consecutive outputs x 4 waves; wave g sums the chunks g, g+4, ... with up
+// to 16 loads in flight, the four partial sums meet in LDS in a fixed order.  Workgroups
+// [0, m*DH/64) handle M, the next m/64 handle b.
 template <int DH>
-__global__ void reduce_contract_kernel(const float *Spart, const float *zpart, int chunks, int m,
-                                       const float *scale_ptr, float *S, float *z, bf16_t *Mx,
-                                       bf16_t *MT, bf16_t *bb) {
+__global__ __launch_bounds__(256) void reduce_contract_kernel(const float *Spart, const float *zpart,
+                                                             int chunks, int m, const float *scale_ptr,
+                                                             float *S, float *z, bf16_t *Mx, bf16_t *MT,
+                                                             bf16_t *bb) {
   constexpr int DX = DH + 16;
-  const int slice = blockIdx.y;
+  const int slice = blockIdx.y, lane = threadIdx.x & 63, grp = threadIdx.x >> 6;
   const int64_t W = (int64_t)m * DH;
-  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const float scale = *scale_ptr;
-  if (e < W) {
-    const float *p = Spart + (int64_t)slice * chunks * W + e;
-    float acc = 0.f;
-    int c = 0;
-    for (; c + 8 <= chunks; c += 8) {   // eight independent loads in flight, fixed summation order
-      float v8[8];
+  const int wblocks = (int)(W / 64);
+  const bool is_z = (int)blockIdx.x >= wblocks;
+  const int64_t count = is_z ? m : W;
+  const int64_t e = (is_z ? (int64_t)(blockIdx.x - wblocks) : (int64_t)blockIdx.x) * 64 + lane;
+  const float *p = (is_z ? zpart : Spart) + (int64_t)slice * chunks * count + e;
+  float acc = 0.f;
+  int c = grp;
+  for (; c + 60 < chunks; c += 64) {
+    float v16[16];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) v8[u] = p[(int64_t)(c + u) * W];
+    for (int u = 0; u < 16; ++u) v16[u] = p[(int64_t)(c + 4 * u) * count];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) acc += v8[u];
-    }
-    for (; c < chunks; ++c) acc += p[(int64_t)c * W];
-    acc *= scale;
+    for (int u = 0; u < 16; ++u) acc += v16[u];
+  }
+  for (; c < chunks; c += 4) acc += p[(int64_t)c * count];
+  __shared__ float part[4][64];
+  part[grp][lane] = acc;
+  __syncthreads();
+  if (grp != 0) return;
+  acc = ((part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane])) * (*scale_ptr);
+  const bf16_t b = f32_to_bf16(acc);
+  if (!is_z) {
     S[(int64_t)slice * W + e] = acc;
     const int r = (int)(e / DH), cidx = (int)(e % DH);
-    const bf16_t b = f32_to_bf16(acc);
     Mx[((int64_t)slice * m + r) * DX + cidx] = b;
     MT[(int64_t)slice * W + (int64_t)cidx * m + r] = b;
-  }
-  if (e < m) {
-    const float *p = zpart + (int64_t)slice * chunks * m + e;
-    float acc = 0.f;
-    for (int c = 0; c < chunks; ++c) acc += p[(int64_t)c * m];
-    acc *= scale;
+  } else {
     z[(int64_t)slice * m + e] = acc;
-    const bf16_t b = f32_to_bf16(acc);
     bb[(int64_t)slice * m + e] = b;
     bf16_t *ext = Mx + ((int64_t)slice * m + e) * DX + DH;
     ext[0] = b;
@@ -1175,7 +1179,7 @@ void launch_contract(const wersa_desc &c, const FastPlan &p, const _Float16 *xf,
   }
   const int64_t W = (int64_t)c.m * DH;
   WERSA_STAGE("wersa_reduce_contract", st,
-              reduce_contract_kernel<DH><<<dim3((unsigned)((W + 255) / 256), slices), 256, 0, st>>>(
+              reduce_contract_kernel<DH><<<dim3((unsigned)(W / 64 + c.m / 64), slices), 256, 0, st>>>(
                   w.Spart, w.zpart, p.chunksC, c.m, w.scalars, S, z, Mx, MT, bb));
 }
 
