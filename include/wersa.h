@@ -65,10 +65,12 @@ typedef enum { WERSA_F32 = 0, WERSA_BF16 = 1 } wersa_dtype;
 
 /*
  * Problem descriptor (host memory, read during the call only).
- * Supported range: B, H, n >= 1; 0 <= L <= 6 and n % 2^L == 0 (the Haar filter is local to
- * aligned blocks of 2^L rows, so the zero padding of Algorithm 2 is never needed);
- * d % 16 == 0, 16 <= d <= 256; m % 16 == 0, 16 <= m <= 4096. Anything else that is
- * otherwise well formed returns WERSA_ERR_UNSUPPORTED.
+ * Supported range: B, H, n >= 1; 0 <= L <= 6; d % 16 == 0, 16 <= d <= 256; m % 16 == 0,
+ * 16 <= m <= 4096. Anything else that is otherwise well formed returns WERSA_ERR_UNSUPPORTED.
+ * Any n is accepted: the Haar filter is local to aligned blocks of 2^L rows, so Algorithm 2's
+ * zero padding to the next power of two and the trim after the inverse are the same as reading
+ * the rows past n of the last block as zeros and not writing them (done in-kernel; the pooled
+ * query averages the n real rows).
  */
 typedef struct {
   int32_t B, H, n, d, L, m;

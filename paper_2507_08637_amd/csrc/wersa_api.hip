@@ -12,7 +12,6 @@ wersa_status validate_desc(const wersa_desc *c) {
   if (c->H > 1 && c->stride_h == 0) return WERSA_ERR_INVALID_ARG;
   if (c->B > 1 && c->stride_b == 0) return WERSA_ERR_INVALID_ARG;
   if (c->L > kMaxL) return WERSA_ERR_UNSUPPORTED;
-  if (c->n % (1 << c->L) != 0) return WERSA_ERR_UNSUPPORTED;
   if (c->d % 16 != 0 || c->d < 16 || c->d > 256) return WERSA_ERR_UNSUPPORTED;
   if (c->m % 16 != 0 || c->m < 16 || c->m > 4096) return WERSA_ERR_UNSUPPORTED;
   if ((int64_t)c->B * c->H > 1023) return WERSA_ERR_UNSUPPORTED;

@@ -55,6 +55,9 @@ SMALL = [
     dict(B=1, H=2, n=16, d=16, L=4, m=16),      # smallest sizes
     dict(B=1, H=2, n=96, d=32, L=0, m=32),      # no wavelet levels: F has one entry
     dict(B=3, H=1, n=256, d=256, L=2, m=48),    # maximum head dim
+    dict(B=2, H=2, n=203, d=32, L=3, m=48),     # n not a multiple of 2^L: zero padding of Algorithm 2 in-kernel
+    dict(B=1, H=2, n=100, d=64, L=6, m=64),     # n between 2^L and 2^(L+1)
+    dict(B=1, H=1, n=5, d=16, L=2, m=16),       # n barely above one block
 ]
 
 
