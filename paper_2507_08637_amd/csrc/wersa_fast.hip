@@ -9,8 +9,9 @@
 //                   reused in the backward for dS = Phi_Q^T dN, dz = Phi_Q^T dD)
 //   reduce_contract fixed-order sum of the partials, scaled; also bf16 copies as MFMA operands
 //   rows            per 64-row block: ReLU(X_F Omega) again, then either the step-8 apply +
-//                   normaliser (forward), or dPhi -> mask -> dX_F -> gated Haar filter of the
-//                   gradient + per-band inner products (backward), K side also dV
+//                   normaliser (forward; the same apply form gives dV = Phi_K dS), or
+//                   dPhi -> mask -> dX_F -> gated Haar filter of the gradient + per-band
+//                   inner products (backward, Q side and K side)
 // The projection uses fp16 MFMA operands (X_F in fp16 keeps the sign of X_F Omega right to
 // 2^-12, which the ReLU derivative needs); everything downstream of the ReLU uses bf16 MFMA.
 #include "wersa_internal.h"
@@ -532,7 +533,8 @@ __global__ __launch_bounds__(256) void reduce_contract_kernel(const float *Spart
 // lanes) so that the ReLU output chains into MFMAs that contract over the features.
 //   MODE 0 (forward, Q side):   N = relu(R) S,  D = c * relu(R) z + eps,  O = c N / D
 //   MODE 1 (backward, Q side):  G = dN S^T + dD z^T; dR = 1[R>0] G; dX_F = c dR Omega^T
-//   MODE 2 (backward, K side):  G = V dS^T + 1 dz^T; dR, dX_F as above; dV = c relu(R) dS
+//   MODE 2 (backward, K side):  G = V dS^T + 1 dz^T; dR, dX_F as above
+//   MODE 3 (backward, K side):  dV = c relu(R) dS  (apply form, like MODE 0 without the normaliser)
 // The rank-one term a b^T of G rides along as one extra k-step of the dPhi MFMA (operand
 // rows extended by (b_r, 0, ...) and (a_t, 0, ...)).
 // Backward epilogue: dX = gated Haar filter of dX_F (block-mean form on the accumulator
