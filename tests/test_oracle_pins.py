@@ -373,3 +373,87 @@ def test_block_backward_matches_central_finite_differences():
             assert abs(fd - an) < 3e-6 * max(1.0, abs(an)), (name, idx, fd, an)
     fd = (loss(sigma=p["sigma"] + h) - loss(sigma=p["sigma"] - h)) / (2 * h)
     assert abs(fd - g["dsigma"]) < 3e-6 * max(1.0, abs(fd))
+
+
+# ---------------------------------------------------------------- the pins bite
+def test_planted_mistakes_are_caught(monkeypatch):
+    """Each plausible mistake, planted in the oracle (on the CPU), must fail at least one pin:
+    a swapped Haar pair sign, a dropped 1/sqrt(2), a transposed operand in S, a dropped epsilon,
+    a missing 1/sqrt(m), a wrong band order of the filter."""
+    import oracle.wersa_oracle as mod
+
+    def expect_failure(pins):
+        failed = 0
+        for pin in pins:
+            try:
+                pin()
+            except AssertionError:
+                failed += 1
+        assert failed >= 1, "no pin noticed the planted mistake"
+
+    haar_pins = [test_haar_hand_example, lambda: test_perfect_reconstruction_and_energy(64, 3),
+                 lambda: test_block_mean_closed_form(64, 3)]
+    attn_pins = [lambda: test_linear_attention_equals_explicit_kernel_matrix(16),
+                 test_random_feature_kernel_converges_at_rate_inv_sqrt_m, test_convexity_and_unit_values]
+
+    # 1. detail = (odd - even)/sqrt(2) instead of (even - odd)/sqrt(2)
+    real_dwt = mod.haar_dwt
+
+    def dwt_wrong_sign(X, L):
+        coeffs, n = real_dwt(X, L)
+        return [-c for c in coeffs[:-1]] + [coeffs[-1]], n
+    monkeypatch.setattr(mod, "haar_dwt", dwt_wrong_sign)
+    expect_failure(haar_pins)
+    monkeypatch.setattr(mod, "haar_dwt", real_dwt)
+
+    # 2. analysis without the 1/sqrt(2) normalisation
+    def dwt_unnormalised(X, L):
+        coeffs, n = real_dwt(X, L)
+        return [c * mod.SQRT2 for c in coeffs], n
+    monkeypatch.setattr(mod, "haar_dwt", dwt_unnormalised)
+    expect_failure(haar_pins)
+    monkeypatch.setattr(mod, "haar_dwt", real_dwt)
+
+    # 3. filter applied with the band order reversed
+    real_fidwt = mod.filtered_idwt
+    monkeypatch.setattr(mod, "filtered_idwt", lambda coeffs, F, n: real_fidwt(coeffs, F[::-1], n))
+    expect_failure([lambda: test_block_mean_closed_form(64, 3), test_filter_special_cases_and_symmetry])
+    monkeypatch.setattr(mod, "filtered_idwt", real_fidwt)
+
+    # 4. feature map without the 1/sqrt(m) factor, and with the bandwidth multiplied instead of divided
+    real_fm = mod.feature_map
+
+    def fm_no_sqrt_m(XF, Omega, sigma, bw_floor, proj_dtype=None):
+        U, Phi = real_fm(XF, Omega, sigma, bw_floor, proj_dtype)
+        return U, Phi * math.sqrt(Omega.shape[1])
+    monkeypatch.setattr(mod, "feature_map", fm_no_sqrt_m)
+    expect_failure(attn_pins)
+
+    def fm_bandwidth_inverted(XF, Omega, sigma, bw_floor, proj_dtype=None):
+        return real_fm(XF, Omega, 1.0 / max(sigma, bw_floor), bw_floor, proj_dtype)
+    monkeypatch.setattr(mod, "feature_map", fm_bandwidth_inverted)
+    expect_failure([test_bandwidth_floor, test_sigma_homogeneity_and_closed_form_dsigma] + attn_pins)
+    monkeypatch.setattr(mod, "feature_map", real_fm)
+
+    # 5. a backward with one term dropped (the pooled-query path) fails the finite differences
+    real_bwd = mod.backward_slice
+
+    def bwd_no_pooled_path(*args, **kw):
+        r = real_bwd(*args, **kw)
+        Q, L = args[0], args[8]
+        r = dict(r)
+        r["dQ"] = mod.haar_filter(r["dQF"], mod.gate(Q.mean(0), args[5], args[6], args[7])[2], L)
+        return r
+    monkeypatch.setattr(mod, "backward_slice", bwd_no_pooled_path)
+    expect_failure([lambda: test_backward_matches_central_finite_differences(64, 3)])
+    monkeypatch.setattr(mod, "backward_slice", real_bwd)
+
+    # 6. head split that interleaves heads instead of giving each a contiguous column block
+    real_split = mod.split_heads
+
+    def split_interleaved(T, H):
+        B, n, hidden = T.shape
+        return T.reshape(B, n, hidden // H, H).transpose(0, 3, 1, 2)
+    monkeypatch.setattr(mod, "split_heads", split_interleaved)
+    expect_failure([test_block_head_layout_and_identity_weights])
+    monkeypatch.setattr(mod, "split_heads", real_split)
