@@ -172,6 +172,9 @@ def main():
     ap.add_argument("--config", type=int, default=4, help="workload configuration (1-4: the core; 5: the attention block)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not bracket kernels with HIP events")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step into a HIP graph and time K replays (no event bracketing in the "
+                         "timed region: the roofline then comes from the untimed survey steps)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (reference point for the "
                          "FETCH_SIZE / WRITE_SIZE counters of a profiler run)")
@@ -233,15 +236,29 @@ def main():
         survey = binding.wersa_profile_collect()
         binding.wersa_profile_enable(False)
         dominant = max(survey, key=lambda k: survey[k][0])
-    binding.wersa_profile_enable(dominant is not None, only=dominant)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    prof = binding.wersa_profile_collect()
-    binding.wersa_profile_enable(False)
+    if args.graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        prof = {dominant: (survey[dominant][0] * args.steps / SURVEY_STEPS,
+                           survey[dominant][1] * args.steps // SURVEY_STEPS)} if dominant else {}
+    else:
+        binding.wersa_profile_enable(dominant is not None, only=dominant)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        prof = binding.wersa_profile_collect()
+        binding.wersa_profile_enable(False)
 
     ms = (t1 - t0) * 1e3 / args.steps
     tokens = cfg["B"] * cfg["n"]
@@ -253,7 +270,7 @@ def main():
         "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32" if path == "generic" or cfg["dtype"] == "f32" else "bf16",
         "data": "synthetic",
-        "config": {"workload": workload, "path": path},
+        "config": {"workload": workload, "path": path, "launch": "hip graph replay" if args.graph else "eager"},
     }
     roof = None
     if prof:
