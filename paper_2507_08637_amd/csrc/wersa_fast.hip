@@ -1066,11 +1066,12 @@ FastPlan fast_plan(const wersa_desc &c) {
   p.rowsC = bpc * 64;
   p.chunksC = (blocks + bpc - 1) / bpc;
   p.rowGroupsA = (blocks + waves_apply(c.d) - 1) / waves_apply(c.d);
-  int wgs = (256 + slices - 1) / slices;   // one 8-wave workgroup per compute unit in total
+  // One resident workgroup per compute unit (the operand arrays fill most of the LDS): at most
+  // 256 workgroups in total, so that no second, mostly empty round follows the first.
+  int wgs = 256 / slices < 1 ? 1 : 256 / slices;
   p.rowsWgsA = wgs < p.rowGroupsA ? wgs : p.rowGroupsA;
   const int nwr = kWavesGrad / (c.d == 128 ? 2 : 1);   // row groups per gradient workgroup step
   p.rowGroupsG = (blocks + nwr - 1) / nwr;
-  wgs = (256 + slices - 1) / slices;       // one 8-wave workgroup per compute unit in total
   p.rowsWgsG = wgs < p.rowGroupsG ? wgs : p.rowGroupsG;
   return p;
 }
@@ -1252,7 +1253,7 @@ wersa_status fast_backward_t(const wersa_desc &c, const bf16_t *q, const bf16_t 
               gate_bwd_slice_kernel<<<slices, 64, 0, st>>>(w.partQ, w.partK, p.rowsWgsG, c.L, c.d, c.H, s,
                                                            gate_w, scale_w, w.dF, w.dlogit, w.dqbar));
   WERSA_STAGE("gate_bwd_params_kernel", st,
-              gate_bwd_params_kernel<<<1, 256, 0, st>>>(w.dF, w.dlogit, s, qbar, w.dDpart, slices * p.chunksC,
+              gate_bwd_params_kernel<<<gate_bwd_params_blocks(c.H, c.L, c.d), 256, 0, st>>>(w.dF, w.dlogit, s, qbar, w.dDpart, slices * p.chunksC,
                                                         c.B, c.H, c.L, c.d, c.eps, w.scalars, dgate_w,
                                                         dgate_b, dscale_w, dsigma));
   const int64_t chunks = (int64_t)c.n * (DH / 8);

@@ -523,7 +523,7 @@ wersa_status backward_t(const wersa_desc &c, const T *q, const T *k, const T *v,
   WERSA_STAGE("band_dots_kernel", st, band_dots_kernel<T><<<tgrid, 256, 0, st>>>(k, tv, w.KF, cv, c.n, c.d, c.L, w.partK));
   WERSA_STAGE("gate_bwd_slice_kernel", st, gate_bwd_slice_kernel<<<slices, 64, 0, st>>>(w.partQ, w.partK, tiles, c.L, c.d, c.H, s, gate_w,
                                                scale_w, w.dF, w.dlogit, w.dqbar));
-  WERSA_STAGE("gate_bwd_params_kernel", st, gate_bwd_params_kernel<<<1, 256, 0, st>>>(w.dF, w.dlogit, s, qbar, w.dDpart,
+  WERSA_STAGE("gate_bwd_params_kernel", st, gate_bwd_params_kernel<<<gate_bwd_params_blocks(c.H, c.L, c.d), 256, 0, st>>>(w.dF, w.dlogit, s, qbar, w.dDpart,
                                             slices * colsum_chunks(c.n), c.B, c.H, c.L, c.d, c.eps,
                                             w.scalars, dgate_w, dgate_b, dscale_w, dsigma));
   WERSA_STAGE("haar_filter_kernel", st, haar_filter_kernel<float, T><<<tgrid, 256, 0, st>>>(w.QF, cv, dq, tv, F, w.dqbar, 1.0f / (float)c.n,

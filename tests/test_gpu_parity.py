@@ -231,11 +231,11 @@ def test_rerun_is_bit_identical():
 def test_unsupported_shape_raises_without_launch():
     import torch
     from paper_2507_08637_amd import binding
-    q = torch.zeros(1, 1, 100, 64, device="cuda")
-    om = torch.zeros(64, 64, device="cuda")
+    q = torch.zeros(1, 1, 128, 40, device="cuda")   # head dimension 40: not a multiple of 16
+    om = torch.zeros(40, 64, device="cuda")
     one = torch.ones(1, device="cuda")
     with pytest.raises(binding.WersaError) as e:
-        binding.wersa_forward(q, q, q, om, one, torch.zeros(1, 4, 64, device="cuda"),
+        binding.wersa_forward(q, q, q, om, one, torch.zeros(1, 4, 40, device="cuda"),
                               torch.zeros(1, 4, device="cuda"), torch.ones(4, device="cuda"), 3)
     assert e.value.status == 2
 
