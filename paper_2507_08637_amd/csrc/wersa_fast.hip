@@ -39,6 +39,49 @@ __device__ __forceinline__ f32x16 mfma_f16(f16x8 a, f16x8 b, f32x16 c) {
 __device__ __forceinline__ f32x16 mfma_bf16(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
+// Projection and dPhi chains with their accumulators forced into architectural VGPRs.  In a
+// kernel that is given the 512-register budget the compiler keeps every MFMA result in
+// accumulation registers, and VALU work on a result then costs one v_accvgpr_read per element;
+// the projection (R) and dPhi (G) tiles of the gradient kernel are consumed by VALU at once, so
+// they are better off in VGPRs.  The compiler does not see through an asm statement, so each
+// statement is hazard-safe on its own: dependent MFMAs are never adjacent (the two chains
+// alternate), and the statement ends with the wait states an 8-pass MFMA needs before anything
+// (VALU, a copy, a spill) may read its result.
+//   chain_first: G = sum_{k<5} ma_k yb_k, R = sum_{k<4} oa_k xb_k;  chain_more: four more steps of each.
+__device__ __forceinline__ void chain_first(f32x16 &R, f32x16 &G, const f16x8 *oa, const f16x8 *xb,
+                                            const bf16x8 *ma, const bf16x8 *yb) {
+  asm volatile(
+      "v_mfma_f32_32x32x16_bf16 %1, %10, %15, 0\n\t"
+      "v_mfma_f32_32x32x16_f16 %0, %2, %6, 0\n\t"
+      "v_mfma_f32_32x32x16_bf16 %1, %11, %16, %1\n\t"
+      "v_mfma_f32_32x32x16_f16 %0, %3, %7, %0\n\t"
+      "v_mfma_f32_32x32x16_bf16 %1, %12, %17, %1\n\t"
+      "v_mfma_f32_32x32x16_f16 %0, %4, %8, %0\n\t"
+      "v_mfma_f32_32x32x16_bf16 %1, %13, %18, %1\n\t"
+      "v_mfma_f32_32x32x16_f16 %0, %5, %9, %0\n\t"
+      "v_mfma_f32_32x32x16_bf16 %1, %14, %19, %1\n\t"
+      "s_nop 11"
+      : "=&v"(R), "=&v"(G)
+      : "v"(oa[0]), "v"(oa[1]), "v"(oa[2]), "v"(oa[3]), "v"(xb[0]), "v"(xb[1]), "v"(xb[2]), "v"(xb[3]),
+        "v"(ma[0]), "v"(ma[1]), "v"(ma[2]), "v"(ma[3]), "v"(ma[4]), "v"(yb[0]), "v"(yb[1]), "v"(yb[2]),
+        "v"(yb[3]), "v"(yb[4]));
+}
+__device__ __forceinline__ void chain_more(f32x16 &R, f32x16 &G, const f16x8 *oa, const f16x8 *xb,
+                                           const bf16x8 *ma, const bf16x8 *yb) {
+  asm volatile(
+      "v_mfma_f32_32x32x16_bf16 %1, %10, %14, %1\n\t"
+      "v_mfma_f32_32x32x16_f16 %0, %2, %6, %0\n\t"
+      "v_mfma_f32_32x32x16_bf16 %1, %11, %15, %1\n\t"
+      "v_mfma_f32_32x32x16_f16 %0, %3, %7, %0\n\t"
+      "v_mfma_f32_32x32x16_bf16 %1, %12, %16, %1\n\t"
+      "v_mfma_f32_32x32x16_f16 %0, %4, %8, %0\n\t"
+      "v_mfma_f32_32x32x16_bf16 %1, %13, %17, %1\n\t"
+      "v_mfma_f32_32x32x16_f16 %0, %5, %9, %0\n\t"
+      "s_nop 11"
+      : "+v"(R), "+v"(G)
+      : "v"(oa[0]), "v"(oa[1]), "v"(oa[2]), "v"(oa[3]), "v"(xb[0]), "v"(xb[1]), "v"(xb[2]), "v"(xb[3]),
+        "v"(ma[0]), "v"(ma[1]), "v"(ma[2]), "v"(ma[3]), "v"(yb[0]), "v"(yb[1]), "v"(yb[2]), "v"(yb[3]));
+}
 __device__ __forceinline__ f32x16 zero16() {
   f32x16 z;
 #pragma unroll
@@ -569,6 +612,10 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
   // The X tiles and D rows of the gradient epilogue are requested before the feature loop when
   // the register file has room for them (head dimension 64), at the epilogue otherwise.
   constexpr bool EARLY = (DH == 64);
+  // Gradient modes run with the 512-register budget: projection and dPhi results go to VGPRs
+  // where the register file has room for all their operands in VGPRs as well (head dimension 64
+  // with the whole feature range staged; the other shapes keep the compiler's own allocation).
+  constexpr bool VGPR_RG = IS_GRAD && NW == 4 && DH == 64 && MC == 256;
   // Head dimension 128, gradient modes: two waves share a row group and each owns one half of
   // the output columns (the projection and dPhi are computed by both), which keeps the
   // accumulators and operands of a wave within the register file.
@@ -763,6 +810,38 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
           for (int ks = 0; ks < KSX; ++ks)
             ma[ks] = *reinterpret_cast<const bf16x8 *>(&s_Mx[(32 * rt + l32) * AM + 16 * ks + 8 * h]);
         }
+        if (VGPR_RG) {
+          // Both row tiles' projection and dPhi chains are issued first (interleaved G R G R ...,
+          // results in VGPRs), so that the mask/pack VALU work of tile 0 runs while the matrix
+          // pipe works through tile 1's chain, and tile 1's VALU work behind tile 0's dX_F MFMAs.
+          // (Head dimension 128 has no registers to spare for that: one tile at a time.)
+          constexpr bool JOINT = (DH == 64);
+          f32x16 Rv[2], Gv[2];
+          if (JOINT) {
+            chain_first(Rv[0], Gv[0], oa, xb[0], ma, yb[0]);
+            chain_first(Rv[1], Gv[1], oa, xb[1], ma, yb[1]);
+          }
+#pragma unroll
+          for (int ti = 0; ti < 2; ++ti) {
+            if (!JOINT) {
+              chain_first(Rv[ti], Gv[ti], oa, xb[ti], ma, yb[ti]);
+              if (DH == 128) chain_more(Rv[ti], Gv[ti], oa + 4, xb[ti] + 4, ma + 5, yb[ti] + 5);
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+              Gv[ti][i] *= __builtin_amdgcn_fmed3f(Rv[ti][i] * 0x1p+100f, 0.f, 1.f);
+#pragma unroll
+            for (int a = 0; a < 2; ++a) {
+              const bf16x8 pg = pack_half(Gv[ti], a);
+#pragma unroll
+              for (int ct = 0; ct < CTW; ++ct) {
+                const bf16x8 ob = lds_perm8(&s_om[(32 * (cbase + ct) + l32) * BS], 32 * rt + 16 * a, h);
+                acc0[ti][ct] = mfma_bf16(pg, ob, acc0[ti][ct]);
+              }
+            }
+          }
+          continue;
+        }
 #pragma unroll
         for (int ti = 0; ti < 2; ++ti) {
           f32x16 R = zero16();
@@ -805,8 +884,11 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
 
     // ---- epilogues -----------------------------------------------------------------
     {
+      // Unconditional (the last round re-requests its own rows): a branch around these loads
+      // would leave two paths with different numbers of outstanding memory operations, and the
+      // waits the compiler then places further down would cover the loads just issued.
       const int t_next = ((rg + gridDim.x) * NWR + rwave) * 64;
-      if (rg + gridDim.x < row_groups && t_next < n) load_rows(t_next);
+      load_rows((rg + gridDim.x < row_groups && t_next < n) ? t_next : t0);
     }
     bf16_t *tl = s_tile + wave * (64 * TS);
     // Gradient modes: output tiles leave through the wave's LDS tile held transposed ([column][row]): a lane
@@ -841,10 +923,9 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
       for (int ti = 0; ti < 2; ++ti) {
         const float dsum = dacc[ti] + __shfl_xor(dacc[ti], 32, 64);
         const float Dt = fmaf(cscale, dsum, eps);
-        if (h == 0) {
-          dl[32 * ti + l32] = cscale / Dt;
-          Dout[(int64_t)slice * n + t0 + 32 * ti + l32] = Dt;
-        }
+        // both half-waves hold the same sum and write the same values: no branch around the store
+        dl[32 * ti + l32] = cscale * __builtin_amdgcn_rcpf(Dt);
+        Dout[(int64_t)slice * n + t0 + 32 * ti + l32] = Dt;
       }
     }
     // Row scale of the accumulators (rows on registers): c / D_t (MODE 0 from the per-wave LDS
