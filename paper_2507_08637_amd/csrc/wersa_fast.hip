@@ -726,6 +726,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
   f16x8 xb[2][KS];      // X_F rows: B operand of the transposed projection
   bf16x8 yb[2][KSX];    // dO or V rows (+ the a_t extension): B operand of the dPhi MFMA
   float dval[2] = {1.f, 1.f};   // D of rows 32 ti + l32 (MODE 1)
+  float aval[2] = {1.f, 1.f};   // dD of the same rows (MODE 1)
   auto load_rows = [&](int t0) {
     const _Float16 *xs = xf + ((int64_t)slice * n + t0) * DH;
 #pragma unroll
@@ -740,16 +741,23 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
 #pragma unroll
       for (int ti = 0; ti < 2; ++ti) {
         const int t = t0 + 32 * ti + l32;
-        float at = 1.0f;
-        if (MODE == 1) {
+        if (MODE == 1) {   // only requested here: used at the top of the next round (finish_rows)
           dval[ti] = Dsaved[(int64_t)slice * n + t];
-          at = arow[(int64_t)slice * n + t] * dval[ti];
+          aval[ti] = arow[(int64_t)slice * n + t];
         }
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
           yb[ti][ks] = *reinterpret_cast<const bf16x8 *>(ys + (int64_t)t * vy.sn + 16 * ks + 8 * h);
+      }
+    }
+  };
+  // The rank-one extension (a_t, 0, ...) of the dPhi operand, built when the values have landed.
+  auto finish_rows = [&]() {
+    if (IS_GRAD) {
+#pragma unroll
+      for (int ti = 0; ti < 2; ++ti) {
         bf16x8 ext = splat_bf16x8(0.f);
-        if (h == 0) ext[0] = (__bf16)at;
+        if (h == 0) ext[0] = (__bf16)(MODE == 1 ? aval[ti] * dval[ti] : 1.0f);
         yb[ti][KSX - 1] = ext;
       }
     }
@@ -779,6 +787,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
 #pragma unroll
       for (int ct = 0; ct < CTW; ++ct) load_xpiece(ct, xpiece[ct]);
     }
+    if (active) finish_rows();
     if (MODE == 1 && active) {   // row scales c / D_t for the epilogue, before the next rows' D replace them
 #pragma unroll
       for (int ti = 0; ti < 2; ++ti)
