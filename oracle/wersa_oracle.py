@@ -16,7 +16,8 @@ silent or disagrees with itself):
 * Normalisation follows the Section 3.1 attention equation (divide by
   phi(Q_F) phi(K_F)^T 1 + eps), not the LayerNorm of Algorithm 1.
 * One shared random matrix Omega (Section 3.1 step 7) and the 1/sqrt(m) factor
-  of Algorithm 1's random projection lines.
+  of Algorithm 1's random projection lines.  Algorithm 1's separate matrices for
+  Q and K are available as an option (Omega_K).
 * The gate g is a single linear map per head (Algorithm 1's W_filter), applied
   to that head's own pooled query (Section 3.1 step 4), plus a bias; the
   per-scale weights omega are shared by all heads.
@@ -134,8 +135,13 @@ def feature_map(XF, Omega, sigma, bw_floor, proj_dtype=None):
 # ----------------------------------------------------------------------------
 # Forward, one (b, h) slice
 # ----------------------------------------------------------------------------
-def forward_slice(Q, K, V, Omega, sigma, Wg_h, bg_h, omega, L, eps, bw_floor, proj_dtype=None):
-    """Q, K, V (n, d) -> dict of every stage tensor, 'O' is the output."""
+def forward_slice(Q, K, V, Omega, sigma, Wg_h, bg_h, omega, L, eps, bw_floor, proj_dtype=None,
+                  Omega_K=None):
+    """Q, K, V (n, d) -> dict of every stage tensor, 'O' is the output.
+
+    Omega_K: a second random matrix for the key side (Algorithm 1 draws separate projection
+    matrices for Q and K); None = the one shared matrix of Section 3.1 step 7."""
+    OmK = Omega if Omega_K is None else np.asarray(Omega_K, np.float64)
     Q = np.asarray(Q, np.float64)
     K = np.asarray(K, np.float64)
     V = np.asarray(V, np.float64)
@@ -144,7 +150,7 @@ def forward_slice(Q, K, V, Omega, sigma, Wg_h, bg_h, omega, L, eps, bw_floor, pr
     QF = haar_filter(Q, F, L)
     KF = haar_filter(K, F, L)
     UQ, PhiQ = feature_map(QF, Omega, sigma, bw_floor, proj_dtype)
-    UK, PhiK = feature_map(KF, Omega, sigma, bw_floor, proj_dtype)
+    UK, PhiK = feature_map(KF, OmK, sigma, bw_floor, proj_dtype)
     S = PhiK.T @ V                       # (m, d)  phi(K_F)^T V
     z = PhiK.T @ np.ones(K.shape[0])     # (m,)    phi(K_F)^T 1
     N = PhiQ @ S
@@ -174,7 +180,7 @@ def _haar_filter_vjp(X, F, L, dXF):
 
 
 def backward_slice(Q, K, V, Omega, sigma, Wg_h, bg_h, omega, L, eps, bw_floor, dO,
-                   fwd=None, proj_dtype=None):
+                   fwd=None, proj_dtype=None, Omega_K=None):
     """Returns dict dQ, dK, dV (n, d), dWg_h (L+1, d), dbg_h, domega (L+1,),
     dsigma (scalar, term-by-term chain rule form), plus intermediates."""
     Q = np.asarray(Q, np.float64)
@@ -182,7 +188,8 @@ def backward_slice(Q, K, V, Omega, sigma, Wg_h, bg_h, omega, L, eps, bw_floor, d
     V = np.asarray(V, np.float64)
     dO = np.asarray(dO, np.float64)
     f = fwd if fwd is not None else forward_slice(Q, K, V, Omega, sigma, Wg_h, bg_h,
-                                                  omega, L, eps, bw_floor, proj_dtype)
+                                                  omega, L, eps, bw_floor, proj_dtype, Omega_K)
+    OmK = Omega if Omega_K is None else np.asarray(Omega_K, np.float64)
     n, d = Q.shape
     m = Omega.shape[1]
     sigma_eff = max(float(sigma), float(bw_floor))
@@ -204,7 +211,7 @@ def backward_slice(Q, K, V, Omega, sigma, Wg_h, bg_h, omega, L, eps, bw_floor, d
     dUK = dPhiK * (UK > 0.0) / math.sqrt(m)
     # U = X_F Omega / sigma_eff
     dQF = (dUQ @ Omega.T) / sigma_eff
-    dKF = (dUK @ Omega.T) / sigma_eff
+    dKF = (dUK @ OmK.T) / sigma_eff
     if float(sigma) > float(bw_floor):
         dsigma = -(np.sum(dUQ * UQ) + np.sum(dUK * UK)) / sigma_eff
     else:
@@ -230,7 +237,7 @@ def backward_slice(Q, K, V, Omega, sigma, Wg_h, bg_h, omega, L, eps, bw_floor, d
 # Whole call over (B, H, n, d)
 # ----------------------------------------------------------------------------
 def forward(Q, K, V, Omega, sigma, Wg, bg, omega, L, eps=1e-6, bw_floor=1e-6,
-            slices=None, keep=("O",), proj_dtype=None):
+            slices=None, keep=("O",), proj_dtype=None, Omega_K=None):
     """Q, K, V (B, H, n, d); Omega (d, m); Wg (H, L+1, d); bg (H, L+1); omega (L+1,).
 
     Returns dict of stacked stage tensors named in `keep`, each (B, H, ...).
@@ -244,7 +251,7 @@ def forward(Q, K, V, Omega, sigma, Wg, bg, omega, L, eps=1e-6, bw_floor=1e-6,
     for (b, h) in todo:
         f = forward_slice(Q[b, h], K[b, h], V[b, h], Omega, sigma,
                           np.asarray(Wg[h], np.float64), np.asarray(bg[h], np.float64),
-                          np.asarray(omega, np.float64), L, eps, bw_floor, proj_dtype)
+                          np.asarray(omega, np.float64), L, eps, bw_floor, proj_dtype, Omega_K)
         for name in keep:
             if name not in out:
                 out[name] = np.zeros((B, H) + np.shape(f[name]), np.float64)
@@ -253,7 +260,7 @@ def forward(Q, K, V, Omega, sigma, Wg, bg, omega, L, eps=1e-6, bw_floor=1e-6,
 
 
 def backward(Q, K, V, Omega, sigma, Wg, bg, omega, L, dO, eps=1e-6, bw_floor=1e-6,
-             slices=None, proj_dtype=None):
+             slices=None, proj_dtype=None, Omega_K=None):
     """Gradients of sum(O * dO) w.r.t. Q, K, V, Wg, bg, omega, sigma.
 
     Parameter gradients are summed over every slice processed (all of them
@@ -270,9 +277,9 @@ def backward(Q, K, V, Omega, sigma, Wg, bg, omega, L, dO, eps=1e-6, bw_floor=1e-
         Wg_h = np.asarray(Wg[h], np.float64)
         bg_h = np.asarray(bg[h], np.float64)
         f = forward_slice(Q[b, h], K[b, h], V[b, h], Omega, sigma, Wg_h, bg_h, omega, L,
-                          eps, bw_floor, proj_dtype)
+                          eps, bw_floor, proj_dtype, Omega_K)
         r = backward_slice(Q[b, h], K[b, h], V[b, h], Omega, sigma, Wg_h, bg_h, omega, L,
-                           eps, bw_floor, dO[b, h], fwd=f)
+                           eps, bw_floor, dO[b, h], fwd=f, Omega_K=Omega_K)
         g["O"][b, h] = f["O"]
         g["dQ"][b, h] = r["dQ"]
         g["dK"][b, h] = r["dK"]

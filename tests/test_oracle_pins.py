@@ -457,3 +457,46 @@ def test_planted_mistakes_are_caught(monkeypatch):
     monkeypatch.setattr(mod, "split_heads", split_interleaved)
     expect_failure([test_block_head_layout_and_identity_weights])
     monkeypatch.setattr(mod, "split_heads", real_split)
+
+
+# ---------------------------------------------------------------- Algorithm 1 variant: separate random matrices
+def test_separate_key_matrix_explicit_kernel_and_gradients():
+    """Algorithm 1 draws separate projection matrices for Q and K.  Pins: passing the shared
+    matrix as Omega_K changes nothing; with a different Omega_K the output equals the explicit
+    n x n attention built from phi_Q = ReLU(Q_F Omega_Q), phi_K = ReLU(K_F Omega_K); all
+    gradients match central differences."""
+    L, n, eps = 2, 48, 1e-2
+    p = _rand_problem(61, B=1, H=1, n=n, d=4, m=16, L=L)
+    OmK = np.random.default_rng(62).standard_normal(p["Omega"].shape)
+    args = (p["Q"][0, 0], p["K"][0, 0], p["V"][0, 0], p["Omega"], p["sigma"], p["Wg"][0], p["bg"][0],
+            p["omega"], L, eps, 1e-6)
+    f_shared = wo.forward_slice(*args)
+    f_same = wo.forward_slice(*args, Omega_K=p["Omega"])
+    np.testing.assert_array_equal(f_shared["O"], f_same["O"])
+    f = wo.forward_slice(*args, Omega_K=OmK)
+    m = OmK.shape[1]
+    pq = np.maximum(f["QF"] @ p["Omega"] / p["sigma"], 0) / math.sqrt(m)
+    pk = np.maximum(f["KF"] @ OmK / p["sigma"], 0) / math.sqrt(m)
+    A = pq @ pk.T
+    np.testing.assert_allclose(f["O"], (A @ p["V"][0, 0]) / (A.sum(axis=1) + eps)[:, None], rtol=1e-11)
+    assert np.abs(f["O"] - f_shared["O"]).max() > 1e-3   # the second matrix is really used
+    g = wo.backward(p["Q"], p["K"], p["V"], p["Omega"], p["sigma"], p["Wg"], p["bg"], p["omega"], L, p["dO"],
+                    eps=eps, Omega_K=OmK)
+    h = 1e-6
+    r = np.random.default_rng(5)
+
+    def loss(**over):
+        q = dict(p, **over)
+        O = wo.forward(q["Q"], q["K"], q["V"], q["Omega"], q["sigma"], q["Wg"], q["bg"], q["omega"], L, eps=eps,
+                       Omega_K=OmK)["O"]
+        return float(np.sum(O * p["dO"]))
+
+    for name, gname in (("Q", "dQ"), ("K", "dK"), ("V", "dV"), ("Wg", "dWg"), ("omega", "domega")):
+        arr = p[name]
+        for fi in r.choice(arr.size, size=min(6, arr.size), replace=False):
+            idx = np.unravel_index(fi, arr.shape)
+            ap, am = arr.copy(), arr.copy()
+            ap[idx] += h
+            am[idx] -= h
+            fd = (loss(**{name: ap}) - loss(**{name: am})) / (2 * h)
+            assert abs(fd - g[gname][idx]) < 3e-6 * max(1.0, abs(fd)), (name, idx, fd, g[gname][idx])
