@@ -62,6 +62,10 @@ typedef enum { WERSA_F32 = 0, WERSA_BF16 = 1 } wersa_dtype;
  * n % 64 == 0, m % 128 == 0, strides multiples of 8 elements; otherwise the generic
  * float32-arithmetic path. WERSA_FLAG_GENERIC_PATH forces the generic path. */
 #define WERSA_FLAG_GENERIC_PATH 1
+/* Separate random matrices for the query and the key side (Algorithm 1 draws W_Q^rand and
+ * W_K^rand independently; Section 3.1 step 7 uses one): omega_rf then holds two d x m row-major
+ * matrices back to back, the query-side one first. */
+#define WERSA_FLAG_SEPARATE_OMEGA 2
 
 /*
  * Problem descriptor (host memory, read during the call only).

@@ -134,6 +134,20 @@ def _same_layout(ref, *others):
             "q, k, v, out and gradients must share shape, strides and dtype"
 
 
+FLAG_GENERIC_PATH = 1
+FLAG_SEPARATE_OMEGA = 2
+
+
+def _check_omega(omega_rf, q, flags):
+    """(d, m), or (2, d, m) with FLAG_SEPARATE_OMEGA: the query-side matrix, then the key-side one."""
+    d = q.shape[3]
+    assert omega_rf.is_contiguous() and omega_rf.dtype == q.dtype
+    if flags & FLAG_SEPARATE_OMEGA:
+        assert omega_rf.dim() == 3 and omega_rf.shape[0] == 2 and omega_rf.shape[1] == d
+    else:
+        assert omega_rf.dim() == 2 and omega_rf.shape[0] == d
+
+
 def wersa_workspace_bytes(desc, for_backward):
     return load_library().wersa_workspace_bytes(ctypes.byref(desc), int(for_backward))
 
@@ -175,8 +189,8 @@ def wersa_forward(q, k, v, omega_rf, sigma, gate_w, gate_b, scale_w, L, eps=1e-6
     """Returns (out, saved).  All tensor arguments live on one CUDA device."""
     lib = load_library()
     _same_layout(q, k, v)
-    desc = make_desc(q, L, omega_rf.shape[1], eps, bw_floor, flags)
-    assert omega_rf.is_contiguous() and omega_rf.dtype == q.dtype and omega_rf.shape[0] == q.shape[3]
+    desc = make_desc(q, L, omega_rf.shape[-1], eps, bw_floor, flags)
+    _check_omega(omega_rf, q, flags)
     for p in (sigma, gate_w, gate_b, scale_w):
         assert p.dtype == torch.float32 and p.is_contiguous()
     if out is None:
@@ -210,7 +224,8 @@ def wersa_backward(q, k, v, omega_rf, sigma, gate_w, gate_b, scale_w, out, dout,
     `grads` may be a dict from an earlier call: its tensors are then overwritten in place."""
     lib = load_library()
     _same_layout(q, k, v, out, dout)
-    desc = make_desc(q, L, omega_rf.shape[1], eps, bw_floor, flags)
+    desc = make_desc(q, L, omega_rf.shape[-1], eps, bw_floor, flags)
+    _check_omega(omega_rf, q, flags)
     if grads is not None:
         dq, dk, dv = grads["dq"], grads["dk"], grads["dv"]
         _same_layout(q, dq, dk, dv)

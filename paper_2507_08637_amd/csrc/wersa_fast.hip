@@ -129,7 +129,7 @@ __device__ __forceinline__ bf16x8 lds_perm8(const bf16_t *row, int base, int h) 
 // the block-mean form come from the gate kernel.)
 // ------------------------------------------------------------------------------------
 __global__ void setup_kernel(const float *sigma, float bw_floor, const bf16_t *omega, int d, int m,
-                             float *scalars, _Float16 *omT) {
+                             int matrices, float *scalars, _Float16 *omT) {
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     const float s = *sigma;
     const float se = fmaxf(s, bw_floor);
@@ -139,9 +139,10 @@ __global__ void setup_kernel(const float *sigma, float bw_floor, const bf16_t *o
     scalars[3] = 1.0f;
   }
   const int e = blockIdx.x * blockDim.x + threadIdx.x;
-  if (e < d * m) {
-    const int r = e / d, j = e % d;
-    omT[e] = (_Float16)bf16_to_f32(omega[(int64_t)j * m + r]);
+  if (e < matrices * d * m) {   // one or two d x m matrices, each transposed on its own
+    const int mat = e / (d * m), w = e % (d * m);
+    const int r = w / d, j = w % d;
+    omT[e] = (_Float16)bf16_to_f32(omega[(int64_t)mat * d * m + (int64_t)j * m + r]);
   }
 }
 
@@ -1231,6 +1232,10 @@ hipError_t launch_rows(const wersa_desc &c, const FastPlan &p, const _Float16 *x
                        bf16_t *out0, float *Dout, float *partF, hipStream_t st) {
   constexpr bool IS_GRAD = (MODE == 1 || MODE == 2);
   constexpr int NW = IS_GRAD ? kWavesGrad : waves_apply(DH);
+  // key-side modes take the second random matrix when the descriptor has two
+  const int64_t side = ((c.flags & WERSA_FLAG_SEPARATE_OMEGA) && MODE >= 2) ? (int64_t)c.d * c.m : 0;
+  const _Float16 *omT = w.omT + side;
+  omega += side;
   const View tv{c.stride_b, c.stride_h, c.stride_n, c.H};
   const size_t smem = rows_smem_bytes<DH, MODE, NW>(p.mc);
   const char *name = MODE == 0 ? "wersa_rows_fwd"
@@ -1242,7 +1247,7 @@ hipError_t launch_rows(const wersa_desc &c, const FastPlan &p, const _Float16 *x
     if (e != hipSuccess) return e;
     WERSA_STAGE(name, st,
                 kern<<<dim3(wgs, c.B * c.H), NW * 64, smem, st>>>(
-                    xf, x, tv, y, tv, Dsaved, arow, w.omT, omega, Mx, MT, bb, w.coef, w.scalars, c.eps, c.n, c.m,
+                    xf, x, tv, y, tv, Dsaved, arow, omT, omega, Mx, MT, bb, w.coef, w.scalars, c.eps, c.n, c.m,
                     groups, out0, tv, Dout, partF, c.L));
     return hipSuccess;
   };
@@ -1258,9 +1263,11 @@ void launch_contract(const wersa_desc &c, const FastPlan &p, const _Float16 *xf,
   const View tv{c.stride_b, c.stride_h, c.stride_n, c.H};
   const int slices = c.B * c.H;
   dim3 grid(p.chunksC, c.m / p.MB, slices);
+  // the forward launch contracts over the key side, the backward one (orows given) over the query side
+  const _Float16 *omT = w.omT + (((c.flags & WERSA_FLAG_SEPARATE_OMEGA) && !orows) ? (int64_t)c.d * c.m : 0);
   auto go = [&](auto kern) {
     WERSA_STAGE("wersa_phiT_contract", st,
-                kern<<<grid, 256, 0, st>>>(xf, y, tv, rowdiv, nullptr, orows, w.dD, w.dDpart, w.omT, c.n, c.m,
+                kern<<<grid, 256, 0, st>>>(xf, y, tv, rowdiv, nullptr, orows, w.dD, w.dDpart, omT, c.n, c.m,
                                            p.rowsC, w.Spart, w.zpart));
   };
   if (p.FW == 64) {
@@ -1291,9 +1298,10 @@ wersa_status fast_forward_t(const wersa_desc &c, const bf16_t *q, const bf16_t *
   _Float16 *QF = reinterpret_cast<_Float16 *>(saved + sv.QF);
   _Float16 *KF = reinterpret_cast<_Float16 *>(saved + sv.KF);
 
+  const int nmat = (c.flags & WERSA_FLAG_SEPARATE_OMEGA) ? 2 : 1;
   WERSA_STAGE("wersa_setup", st,
-              setup_kernel<<<(c.d * c.m + 255) / 256, 256, 0, st>>>(sigma, c.bw_floor, omega, c.d, c.m, w.scalars,
-                                                                    w.omT));
+              setup_kernel<<<(nmat * c.d * c.m + 255) / 256, 256, 0, st>>>(sigma, c.bw_floor, omega, c.d, c.m, nmat,
+                                                                           w.scalars, w.omT));
   WERSA_STAGE("wersa_qbar", st,
               qbar_partial_kernel<DH><<<dim3(p.chunksQ, slices), 256, 0, st>>>(q, tv, c.n, p.rowsQ, w.qpart));
   WERSA_STAGE("gate_fwd_kernel", st,

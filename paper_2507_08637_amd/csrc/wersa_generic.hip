@@ -354,7 +354,7 @@ GenericWs plan(const wersa_desc &c, int bwd, float *base) {
   w.QF = b.take(nd);
   w.KF = b.take(nd);
   w.Vf = b.take(nd);
-  w.Of = b.take((int64_t)c.d * c.m);  // Omega in float32
+  w.Of = b.take((int64_t)2 * c.d * c.m);  // Omega in float32: the query-side matrix, then the key-side one
   w.Phi = b.take(nm);
   w.Spart = b.take(sl * splits * (int64_t)c.m * c.d);
   w.zpart = w.qpart;  // same shape family, used after qpart is consumed
@@ -392,10 +392,16 @@ void launch_gemm(GemmArgs a, int batch, hipStream_t st, const char *name) {
   WERSA_STAGE(name, st, gemm_kernel<<<grid, 256, 0, st>>>(a));
 }
 
+// Omega of the query side (side 0) or the key side (side 1) in float32; the same matrix unless the
+// descriptor asks for separate ones.
+const float *omega_of(const wersa_desc &c, const GenericWs &w, int side) {
+  return w.Of + ((c.flags & WERSA_FLAG_SEPARATE_OMEGA) && side ? (int64_t)c.d * c.m : 0);
+}
+
 // Phi = ReLU(XF Omega) * c
-void launch_features(const wersa_desc &c, const float *XF, const GenericWs &w, hipStream_t st) {
+void launch_features(const wersa_desc &c, const float *XF, int side, const GenericWs &w, hipStream_t st) {
   GemmArgs a{};
-  a.A = XF; a.B = w.Of; a.C = w.Phi;
+  a.A = XF; a.B = omega_of(c, w, side); a.C = w.Phi;
   a.M = c.n; a.N = c.m; a.K = c.d;
   a.sAi = c.d; a.sAk = 1; a.sBk = c.m; a.sBj = 1; a.ldc = c.m;
   a.bsA = (int64_t)c.n * c.d; a.bsB = 0; a.bsC = (int64_t)c.n * c.m;
@@ -457,14 +463,17 @@ wersa_status forward_t(const wersa_desc &c, const T *q, const T *k, const T *v, 
   launch_haar<T>(c, q, tv, w.QF, F, st);
   launch_haar<T>(c, k, tv, w.KF, F, st);
   WERSA_STAGE("gather_f32_kernel", st, gather_f32_kernel<T><<<ew_blocks(nd), 256, 0, st>>>(v, tv, c.n, c.d, nd, w.Vf));
-  WERSA_STAGE("gather_f32_kernel", st, gather_f32_kernel<T><<<ew_blocks((int64_t)c.d * c.m), 256, 0, st>>>(
-      omega_rf, contiguous_view(c.d, c.m), c.d, c.m, (int64_t)c.d * c.m, w.Of));
+  {
+    const int64_t om = (int64_t)c.d * c.m * ((c.flags & WERSA_FLAG_SEPARATE_OMEGA) ? 2 : 1);
+    WERSA_STAGE("gather_f32_kernel", st, gather_f32_kernel<T><<<ew_blocks(om), 256, 0, st>>>(
+        omega_rf, contiguous_view(c.d, c.m), c.d, c.m, om, w.Of));
+  }
   // step 7 on K, then S = Phi_K^T V and z = Phi_K^T 1
-  launch_features(c, w.KF, w, st);
+  launch_features(c, w.KF, 1, w, st);
   launch_phiT_times(c, w.Vf, w, S, st);
   launch_colsum<float>(w.Phi, contiguous_view(c.n, c.m), slices, c.n, c.m, nullptr, w.zpart, z, 1.f, st);
   // step 7 on Q, then step 8
-  launch_features(c, w.QF, w, st);
+  launch_features(c, w.QF, 0, w, st);
   launch_rows_gemm(c, w.Phi, c.m, S, c.d, 1, (int64_t)c.m * c.d, c.d, w.Nbuf, st);
   WERSA_STAGE("rowdot_kernel", st, rowdot_kernel<<<dim3((c.n + 3) / 4, slices), 256, 0, st>>>(w.Phi, z, c.n, c.m, c.eps, D));
   WERSA_STAGE("scatter_kernel", st, scatter_kernel<T><<<ew_blocks(nd), 256, 0, st>>>(w.Nbuf, D, out, tv, c.n, c.d, nd));
@@ -492,8 +501,11 @@ wersa_status backward_t(const wersa_desc &c, const T *q, const T *k, const T *v,
   launch_haar<T>(c, q, tv, w.QF, F, st);
   launch_haar<T>(c, k, tv, w.KF, F, st);
   WERSA_STAGE("gather_f32_kernel", st, gather_f32_kernel<T><<<ew_blocks(nd), 256, 0, st>>>(v, tv, c.n, c.d, nd, w.Vf));
-  WERSA_STAGE("gather_f32_kernel", st, gather_f32_kernel<T><<<ew_blocks((int64_t)c.d * c.m), 256, 0, st>>>(
-      omega_rf, contiguous_view(c.d, c.m), c.d, c.m, (int64_t)c.d * c.m, w.Of));
+  {
+    const int64_t om = (int64_t)c.d * c.m * ((c.flags & WERSA_FLAG_SEPARATE_OMEGA) ? 2 : 1);
+    WERSA_STAGE("gather_f32_kernel", st, gather_f32_kernel<T><<<ew_blocks(om), 256, 0, st>>>(
+        omega_rf, contiguous_view(c.d, c.m), c.d, c.m, om, w.Of));
+  }
   // O = N / D
   WERSA_STAGE("prep_dn_kernel", st, prep_dn_kernel<T><<<dim3((c.n + 3) / 4, slices), 256, 0, st>>>(dout, out, tv, D, c.n, c.d, w.dN, w.dD));
   {  // sum of dD over everything, for d sigma
@@ -502,20 +514,20 @@ wersa_status backward_t(const wersa_desc &c, const T *q, const T *k, const T *v,
         w.dD, contiguous_view(c.n, 1), c.n, 1, rows, nullptr, w.dDpart));
   }
   // Q side: dPhi_Q = dN S^T + dD z^T ; dS = Phi_Q^T dN ; dz = Phi_Q^T dD
-  launch_features(c, w.QF, w, st);
+  launch_features(c, w.QF, 0, w, st);
   launch_rows_gemm(c, w.dN, c.d, S, 1, c.d, md, c.m, w.R, st);
   launch_phiT_times(c, w.dN, w, w.dS, st);
   launch_colsum<float>(w.Phi, contiguous_view(c.n, c.m), slices, c.n, c.m, w.dD, w.zpart, w.dz, 1.f, st);
   WERSA_STAGE("mask_scale_kernel", st, mask_scale_kernel<<<ew_blocks(nm), 256, 0, st>>>(w.R, w.Phi, w.dD, z, w.scalars, c.n, c.m, nm));
   // dQ_F = dU_Q Omega^T / sigma_eff (scale folded into R); reuse QF's buffer for the result
-  launch_rows_gemm(c, w.R, c.m, w.Of, 1, c.m, 0, c.d, w.QF, st);
+  launch_rows_gemm(c, w.R, c.m, omega_of(c, w, 0), 1, c.m, 0, c.d, w.QF, st);
   // K side: dPhi_K = V dS^T + 1 dz^T ; dV = Phi_K dS
-  launch_features(c, w.KF, w, st);
+  launch_features(c, w.KF, 1, w, st);
   launch_rows_gemm(c, w.Vf, c.d, w.dS, 1, c.d, md, c.m, w.R, st);
   WERSA_STAGE("mask_scale_kernel", st, mask_scale_kernel<<<ew_blocks(nm), 256, 0, st>>>(w.R, w.Phi, nullptr, w.dz, w.scalars, c.n, c.m, nm));
   launch_rows_gemm(c, w.Phi, c.m, w.dS, c.d, 1, md, c.d, w.dVf, st);
   WERSA_STAGE("scatter_kernel", st, scatter_kernel<T><<<ew_blocks(nd), 256, 0, st>>>(w.dVf, nullptr, dv, tv, c.n, c.d, nd));
-  launch_rows_gemm(c, w.R, c.m, w.Of, 1, c.m, 0, c.d, w.KF, st);
+  launch_rows_gemm(c, w.R, c.m, omega_of(c, w, 1), 1, c.m, 0, c.d, w.KF, st);
   // wavelet stage backward: dF from band inner products, then dX = G_F dX_F
   dim3 tgrid((c.n + kTileRows - 1) / kTileRows, (c.d + kTileCols - 1) / kTileCols, slices);
   const int64_t tiles = (int64_t)tgrid.x * tgrid.y;

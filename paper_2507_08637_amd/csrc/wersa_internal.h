@@ -70,7 +70,7 @@ inline SavedLayout saved_layout(const wersa_desc &c) {
     const int64_t md = (int64_t)c.m * c.d, mx = (int64_t)c.m * (c.d + 16);
     o.scalars = off; off += 64;
     o.coef = off;    off += up(sl * 8);
-    o.omT = off;     off += up(md / 2);
+    o.omT = off;     off += up(md / 2 * ((c.flags & WERSA_FLAG_SEPARATE_OMEGA) ? 2 : 1));
     o.Sx = off;      off += up(sl * mx / 2);
     o.ST = off;      off += up(sl * md / 2);
     o.zb = off;      off += up(sl * c.m / 2);

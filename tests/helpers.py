@@ -14,7 +14,8 @@ def to_device(p, dtype, device="cuda:0", layout="bhnd"):
             if layout == "bnhd":   # physically (B, n, H, d), presented as (B, H, n, d)
                 x = x.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
             t[k] = x
-    t["Omega"] = torch.from_numpy(p["Omega"]).to(device).to(tdt)
+    om = p["Omega"] if "OmegaK" not in p else np.stack([p["Omega"], p["OmegaK"]])
+    t["Omega"] = torch.from_numpy(np.ascontiguousarray(om)).to(device).to(tdt)
     for k in ("Wg", "bg", "omega"):
         t[k] = torch.from_numpy(np.ascontiguousarray(p[k], dtype=np.float32)).to(device)
     t["sigma"] = torch.tensor([float(p["sigma"])], dtype=torch.float32, device=device)
@@ -44,7 +45,7 @@ def oracle_backward(p, cfg, eps=1e-6, bw_floor=1e-6, slices=None, proj_dtype=Non
     from oracle import wersa_oracle as wo
     return wo.backward(p["Q"], p["K"], p["V"], p["Omega"], float(p["sigma"]), p["Wg"], p["bg"],
                        p["omega"], cfg["L"], p["dO"], eps=eps, bw_floor=bw_floor, slices=slices,
-                       proj_dtype=proj_dtype)
+                       proj_dtype=proj_dtype, Omega_K=p.get("OmegaK"))
 
 
 def oracle_forward(p, cfg, eps=1e-6, bw_floor=1e-6, slices=None,
@@ -84,8 +85,8 @@ def gate_grad_scales(p, cfg, eps=1e-6, bw_floor=1e-6):
                     np.asarray(p["V"][b, h], np.float64), Om, float(p["sigma"]),
                     np.asarray(p["Wg"][h], np.float64), np.asarray(p["bg"][h], np.float64), omega, L,
                     eps, bw_floor)
-            r = wo.backward_slice(*args, np.asarray(p["dO"][b, h], np.float64))
-            f = wo.forward_slice(*args)
+            r = wo.backward_slice(*args, np.asarray(p["dO"][b, h], np.float64), Omega_K=p.get("OmegaK"))
+            f = wo.forward_slice(*args, Omega_K=p.get("OmegaK"))
             s_all[b, h], qbar[b, h] = f["s"], f["qbar"]
             for X, G in ((args[0], r["dQF"]), (args[1], r["dKF"])):
                 cx, _ = wo.haar_dwt(X, L)

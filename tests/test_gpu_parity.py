@@ -240,6 +240,26 @@ def test_unsupported_shape_raises_without_launch():
     assert e.value.status == 2
 
 
+@pytest.mark.parametrize("path", ["generic_f32", "generic_bf16", "mfma"])
+def test_separate_query_and_key_random_matrices(path):
+    """WERSA_FLAG_SEPARATE_OMEGA (Algorithm 1's independent W_Q^rand, W_K^rand): omega_rf carries
+    two matrices; both paths against the oracle given the same pair."""
+    dtype = "f32" if path == "generic_f32" else "bf16"
+    cfg = dict(B=2, H=2, n=256, d=64, L=4, m=128, dtype=dtype, flavour="plain", seed_base=3100, q_mean=0.4)
+    p = workloads.make_inputs(**cfg)
+    omk = np.random.default_rng(3199).standard_normal(p["Omega"].shape, dtype=np.float32)
+    p["OmegaK"] = workloads.round_to_bf16(omk) if dtype == "bf16" else omk
+    flags = 2 | (0 if path == "mfma" else 1)
+    res = hp.gpu_forward_backward(p, cfg, flags=flags)
+    ref = hp.oracle_backward(p, cfg)
+    shared = hp.oracle_backward({k: v for k, v in p.items() if k != "OmegaK"}, cfg)
+    assert hp.rel_err(res["O"], shared["O"]) > 0.1   # the key-side matrix is really the second one
+    if path == "mfma":
+        _check_mfma(res, ref, p, cfg, where="separate omega mfma")
+    else:
+        _check_all(res, ref, TOL[dtype], where=f"separate omega {path}")
+
+
 # ------------------------------------------------------------------ benchmark configurations
 def test_config1_tiny_fp32():
     cfg, p = workloads.make_config(1, backward=True)
