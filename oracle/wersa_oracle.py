@@ -20,7 +20,9 @@ silent or disagrees with itself):
   Q and K are available as an option (Omega_K).
 * The gate g is a single linear map per head (Algorithm 1's W_filter), applied
   to that head's own pooled query (Section 3.1 step 4), plus a bias; the
-  per-scale weights omega are shared by all heads.
+  per-scale weights omega are shared by all heads.  Algorithm 1's form (one
+  map on the pooled queries of all heads, one filter per batch element) is
+  available as an option (pooled).
 * The same filter F (computed from Q) multiplies the coefficients of both Q
   and K (Section 3.1 step 6).
 * Band order of F: index 0 is the finest detail band d_1, index L-1 is d_L,
@@ -136,17 +138,18 @@ def feature_map(XF, Omega, sigma, bw_floor, proj_dtype=None):
 # Forward, one (b, h) slice
 # ----------------------------------------------------------------------------
 def forward_slice(Q, K, V, Omega, sigma, Wg_h, bg_h, omega, L, eps, bw_floor, proj_dtype=None,
-                  Omega_K=None):
+                  Omega_K=None, gate_given=None):
     """Q, K, V (n, d) -> dict of every stage tensor, 'O' is the output.
 
     Omega_K: a second random matrix for the key side (Algorithm 1 draws separate projection
-    matrices for Q and K); None = the one shared matrix of Section 3.1 step 7."""
+    matrices for Q and K); None = the one shared matrix of Section 3.1 step 7.
+    gate_given: (logits, s, F) computed outside (the gate pooled over heads), else this head's own."""
     OmK = Omega if Omega_K is None else np.asarray(Omega_K, np.float64)
     Q = np.asarray(Q, np.float64)
     K = np.asarray(K, np.float64)
     V = np.asarray(V, np.float64)
     qbar = Q.mean(axis=0)
-    logits, s, F = gate(qbar, Wg_h, bg_h, omega)
+    logits, s, F = gate(qbar, Wg_h, bg_h, omega) if gate_given is None else gate_given
     QF = haar_filter(Q, F, L)
     KF = haar_filter(K, F, L)
     UQ, PhiQ = feature_map(QF, Omega, sigma, bw_floor, proj_dtype)
@@ -180,7 +183,7 @@ def _haar_filter_vjp(X, F, L, dXF):
 
 
 def backward_slice(Q, K, V, Omega, sigma, Wg_h, bg_h, omega, L, eps, bw_floor, dO,
-                   fwd=None, proj_dtype=None, Omega_K=None):
+                   fwd=None, proj_dtype=None, Omega_K=None, gate_outside=False):
     """Returns dict dQ, dK, dV (n, d), dWg_h (L+1, d), dbg_h, domega (L+1,),
     dsigma (scalar, term-by-term chain rule form), plus intermediates."""
     Q = np.asarray(Q, np.float64)
@@ -220,6 +223,8 @@ def backward_slice(Q, K, V, Omega, sigma, Wg_h, bg_h, omega, L, eps, bw_floor, d
     dQ, dF_q = _haar_filter_vjp(Q, f["F"], L, dQF)
     dK, dF_k = _haar_filter_vjp(K, f["F"], L, dKF)
     dF = dF_q + dF_k
+    if gate_outside:   # the caller owns the gate (pooled over heads): hand back dF, no pooled-query term yet
+        return dict(dQ=dQ, dK=dK, dV=dV, dsigma=dsigma, dS=dS, dz=dz, dD=dD, dF=dF, dQF=dQF, dKF=dKF)
     # F = s * omega ; s = sigmoid(logits) ; logits = Wg qbar + bg ; qbar = mean(Q)
     s = f["s"]
     domega = dF * s
@@ -236,8 +241,19 @@ def backward_slice(Q, K, V, Omega, sigma, Wg_h, bg_h, omega, L, eps, bw_floor, d
 # ----------------------------------------------------------------------------
 # Whole call over (B, H, n, d)
 # ----------------------------------------------------------------------------
+def pooled_gate(Qb, Wg, bg, omega):
+    """Algorithm 1's gate: the per-head pooled queries of one batch element, concatenated over the
+    heads, go through ONE linear map to L+1 logits; every head of that batch element shares the
+    filter.  With the per-head parameter layout Wg (H, L+1, d), bg (H, L+1) the map is
+    logits_i = sum_h (Wg[h, i] . qbar_h + bg[h, i]).  Qb is (H, n, d)."""
+    qbars = np.asarray(Qb, np.float64).mean(axis=1)                  # (H, d)
+    logits = np.einsum("hid,hd->i", np.asarray(Wg, np.float64), qbars) + np.asarray(bg, np.float64).sum(axis=0)
+    s = 1.0 / (1.0 + np.exp(-logits))
+    return qbars, logits, s, s * np.asarray(omega, np.float64)
+
+
 def forward(Q, K, V, Omega, sigma, Wg, bg, omega, L, eps=1e-6, bw_floor=1e-6,
-            slices=None, keep=("O",), proj_dtype=None, Omega_K=None):
+            slices=None, keep=("O",), proj_dtype=None, Omega_K=None, pooled=False):
     """Q, K, V (B, H, n, d); Omega (d, m); Wg (H, L+1, d); bg (H, L+1); omega (L+1,).
 
     Returns dict of stacked stage tensors named in `keep`, each (B, H, ...).
@@ -249,9 +265,13 @@ def forward(Q, K, V, Omega, sigma, Wg, bg, omega, L, eps=1e-6, bw_floor=1e-6,
     out = {}
     todo = slices if slices is not None else [(b, h) for b in range(B) for h in range(H)]
     for (b, h) in todo:
+        given = None
+        if pooled:
+            _, lg, sg, Fg = pooled_gate(Q[b], Wg, bg, omega)
+            given = (lg, sg, Fg)
         f = forward_slice(Q[b, h], K[b, h], V[b, h], Omega, sigma,
                           np.asarray(Wg[h], np.float64), np.asarray(bg[h], np.float64),
-                          np.asarray(omega, np.float64), L, eps, bw_floor, proj_dtype, Omega_K)
+                          np.asarray(omega, np.float64), L, eps, bw_floor, proj_dtype, Omega_K, given)
         for name in keep:
             if name not in out:
                 out[name] = np.zeros((B, H) + np.shape(f[name]), np.float64)
@@ -259,13 +279,49 @@ def forward(Q, K, V, Omega, sigma, Wg, bg, omega, L, eps=1e-6, bw_floor=1e-6,
     return out
 
 
+def backward_pooled(Q, K, V, Omega, sigma, Wg, bg, omega, L, dO, eps=1e-6, bw_floor=1e-6,
+                    proj_dtype=None, Omega_K=None):
+    """Backward with the gate pooled over heads (pooled_gate): dF of the heads of a batch element
+    add up before the sigmoid's derivative; the pooled-query term then goes back to each head."""
+    B, H, n, d = Q.shape
+    Omega = np.asarray(Omega, np.float64)
+    omega = np.asarray(omega, np.float64)
+    Wg = np.asarray(Wg, np.float64)
+    g = dict(dQ=np.zeros((B, H, n, d)), dK=np.zeros((B, H, n, d)), dV=np.zeros((B, H, n, d)),
+             dWg=np.zeros((H, L + 1, d)), dbg=np.zeros((H, L + 1)), domega=np.zeros(L + 1),
+             dsigma=0.0, O=np.zeros((B, H, n, d)), dD_sum=0.0)
+    for b in range(B):
+        qbars, lg, sg, Fg = pooled_gate(Q[b], Wg, bg, omega)
+        dF = np.zeros(L + 1)
+        for h in range(H):
+            args = (Q[b, h], K[b, h], V[b, h], Omega, sigma, Wg[h], np.asarray(bg[h], np.float64), omega, L,
+                    eps, bw_floor)
+            f = forward_slice(*args, proj_dtype, Omega_K, (lg, sg, Fg))
+            r = backward_slice(*args, dO[b, h], fwd=f, Omega_K=Omega_K, gate_outside=True)
+            g["O"][b, h] = f["O"]
+            g["dQ"][b, h], g["dK"][b, h], g["dV"][b, h] = r["dQ"], r["dK"], r["dV"]
+            g["dsigma"] += r["dsigma"]
+            g["dD_sum"] += float(np.sum(r["dD"]))
+            dF += r["dF"]
+        g["domega"] += dF * sg
+        dlogits = dF * omega * sg * (1.0 - sg)
+        for h in range(H):
+            g["dWg"][h] += np.outer(dlogits, qbars[h])
+            g["dbg"][h] += dlogits
+            g["dQ"][b, h] += (Wg[h].T @ dlogits)[None, :] / n
+    return g
+
+
 def backward(Q, K, V, Omega, sigma, Wg, bg, omega, L, dO, eps=1e-6, bw_floor=1e-6,
-             slices=None, proj_dtype=None, Omega_K=None):
+             slices=None, proj_dtype=None, Omega_K=None, pooled=False):
     """Gradients of sum(O * dO) w.r.t. Q, K, V, Wg, bg, omega, sigma.
 
     Parameter gradients are summed over every slice processed (all of them
     unless `slices` restricts the work).
     """
+    if pooled:
+        assert slices is None, "the pooled gate couples the heads of a batch element"
+        return backward_pooled(Q, K, V, Omega, sigma, Wg, bg, omega, L, dO, eps, bw_floor, proj_dtype, Omega_K)
     B, H, n, d = Q.shape
     Omega = np.asarray(Omega, np.float64)
     omega = np.asarray(omega, np.float64)

@@ -500,3 +500,51 @@ def test_separate_key_matrix_explicit_kernel_and_gradients():
             am[idx] -= h
             fd = (loss(**{name: ap}) - loss(**{name: am})) / (2 * h)
             assert abs(fd - g[gname][idx]) < 3e-6 * max(1.0, abs(fd)), (name, idx, fd, g[gname][idx])
+
+
+# ---------------------------------------------------------------- Algorithm 1 variant: gate pooled over heads
+def test_pooled_gate_definition_special_cases_and_gradients():
+    """Algorithm 1's gate: one linear map on the concatenated pooled queries, one filter per batch
+    element.  Pins: the logits equal W_filter . concat(qbar_h) written out by hand; with a single
+    head it is the per-head gate; every head of a batch element gets the same F; all gradients
+    match central differences (the cross-head sum of dF included)."""
+    L, eps = 2, 1e-2
+    p = _rand_problem(71, B=2, H=3, n=32, d=4, m=16, L=L)
+    qbars, lg, sg, Fg = wo.pooled_gate(p["Q"][1], p["Wg"], p["bg"], p["omega"])
+    Wfilter = np.concatenate([p["Wg"][h] for h in range(3)], axis=1)          # (L+1, H*d)
+    qcat = np.concatenate([p["Q"][1, h].mean(axis=0) for h in range(3)])      # (H*d,)
+    np.testing.assert_allclose(lg, Wfilter @ qcat + p["bg"].sum(axis=0), rtol=1e-12)
+    np.testing.assert_allclose(Fg, p["omega"] / (1.0 + np.exp(-lg)), rtol=1e-12)
+    # one head: identical to the per-head gate
+    p1 = _rand_problem(72, B=2, H=1, n=32, d=4, m=16, L=L)
+    a = wo.forward(p1["Q"], p1["K"], p1["V"], p1["Omega"], p1["sigma"], p1["Wg"], p1["bg"], p1["omega"], L, eps=eps)
+    b = wo.forward(p1["Q"], p1["K"], p1["V"], p1["Omega"], p1["sigma"], p1["Wg"], p1["bg"], p1["omega"], L, eps=eps,
+                   pooled=True)
+    np.testing.assert_allclose(a["O"], b["O"], rtol=1e-12)
+    f = wo.forward(p["Q"], p["K"], p["V"], p["Omega"], p["sigma"], p["Wg"], p["bg"], p["omega"], L, eps=eps,
+                   pooled=True, keep=("O", "F"))
+    for bb in range(2):
+        for h in range(1, 3):
+            np.testing.assert_array_equal(f["F"][bb, h], f["F"][bb, 0])
+    g = wo.backward(p["Q"], p["K"], p["V"], p["Omega"], p["sigma"], p["Wg"], p["bg"], p["omega"], L, p["dO"],
+                    eps=eps, pooled=True)
+    np.testing.assert_allclose(g["O"], f["O"], rtol=1e-12)
+    h_ = 1e-6
+    r = np.random.default_rng(7)
+
+    def loss(**over):
+        q = dict(p, **over)
+        O = wo.forward(q["Q"], q["K"], q["V"], q["Omega"], q["sigma"], q["Wg"], q["bg"], q["omega"], L, eps=eps,
+                       pooled=True)["O"]
+        return float(np.sum(O * p["dO"]))
+
+    for name, gname, count in (("Q", "dQ", 10), ("K", "dK", 6), ("V", "dV", 4), ("Wg", "dWg", 10), ("bg", "dbg", 6),
+                               ("omega", "domega", 3)):
+        arr = p[name]
+        for fi in r.choice(arr.size, size=min(count, arr.size), replace=False):
+            idx = np.unravel_index(fi, arr.shape)
+            ap, am = arr.copy(), arr.copy()
+            ap[idx] += h_
+            am[idx] -= h_
+            fd = (loss(**{name: ap}) - loss(**{name: am})) / (2 * h_)
+            assert abs(fd - g[gname][idx]) < 3e-6 * max(1.0, abs(fd)), (name, idx, fd, g[gname][idx])
