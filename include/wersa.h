@@ -66,6 +66,12 @@ typedef enum { WERSA_F32 = 0, WERSA_BF16 = 1 } wersa_dtype;
  * W_K^rand independently; Section 3.1 step 7 uses one): omega_rf then holds two d x m row-major
  * matrices back to back, the query-side one first. */
 #define WERSA_FLAG_SEPARATE_OMEGA 2
+/* Gate pooled over heads (Algorithm 1: the pooled queries of all heads of a batch element are
+ * concatenated and go through one linear map, giving one filter per batch element):
+ * logits_i = sum_h (gate_w[h][i] . qbar_h + gate_b[h][i]), F = sigmoid(logits) * scale_w for every
+ * head of that batch element. Parameter shapes are unchanged (gate_w read as the (L+1) x (H*d)
+ * map in head blocks). Default (Section 3.1 step 4): each head gates itself. */
+#define WERSA_FLAG_POOLED_GATE 4
 
 /*
  * Problem descriptor (host memory, read during the call only).

@@ -1306,7 +1306,7 @@ wersa_status fast_forward_t(const wersa_desc &c, const bf16_t *q, const bf16_t *
               qbar_partial_kernel<DH><<<dim3(p.chunksQ, slices), 256, 0, st>>>(q, tv, c.n, p.rowsQ, w.qpart));
   WERSA_STAGE("gate_fwd_kernel", st,
               gate_fwd_kernel<<<slices, 256, 0, st>>>(w.qpart, p.chunksQ, c.n, c.d, c.L, c.H, gate_w, gate_b,
-                                                     scale_w, qbar, s, F, w.coef));
+                                                     scale_w, qbar, s, F, w.coef, (c.flags & WERSA_FLAG_POOLED_GATE) ? 1 : 0));
   WERSA_STAGE("wersa_haar_stage", st,
               haar_stage_kernel<DH><<<dim3(c.n / 64, slices), 256, 0, st>>>(q, tv, c.n, w.coef, QF));
   WERSA_STAGE("wersa_haar_stage", st,
@@ -1349,7 +1349,7 @@ wersa_status fast_backward_t(const wersa_desc &c, const bf16_t *q, const bf16_t 
     return WERSA_ERR_LAUNCH;
   WERSA_STAGE("gate_bwd_slice_kernel", st,
               gate_bwd_slice_kernel<<<slices, 64, 0, st>>>(w.partQ, w.partK, p.rowsWgsG, c.L, c.d, c.H, s,
-                                                           gate_w, scale_w, w.dF, w.dlogit, w.dqbar));
+                                                           gate_w, scale_w, w.dF, w.dlogit, w.dqbar, (c.flags & WERSA_FLAG_POOLED_GATE) ? 1 : 0));
   WERSA_STAGE("gate_bwd_params_kernel", st,
               gate_bwd_params_kernel<<<gate_bwd_params_blocks(c.H, c.L, c.d), 256, 0, st>>>(w.dF, w.dlogit, s, qbar, w.dDpart, slices * p.chunksC,
                                                         c.B, c.H, c.L, c.d, c.eps, w.scalars, dgate_w,

@@ -458,7 +458,7 @@ wersa_status forward_t(const wersa_desc &c, const T *q, const T *k, const T *v, 
   // step 4: pooled query and gate
   launch_colsum<T>(q, tv, slices, c.n, c.d, nullptr, w.qpart, nullptr, 1.f, st);
   WERSA_STAGE("gate_fwd_kernel", st, gate_fwd_kernel<<<slices, 256, 0, st>>>(w.qpart, colsum_chunks(c.n), c.n, c.d, c.L, c.H, gate_w,
-                                         gate_b, scale_w, qbar, s, F, nullptr));
+                                         gate_b, scale_w, qbar, s, F, nullptr, (c.flags & WERSA_FLAG_POOLED_GATE) ? 1 : 0));
   // steps 3, 5, 6: gated Haar filter of Q and K
   launch_haar<T>(c, q, tv, w.QF, F, st);
   launch_haar<T>(c, k, tv, w.KF, F, st);
@@ -534,7 +534,7 @@ wersa_status backward_t(const wersa_desc &c, const T *q, const T *k, const T *v,
   WERSA_STAGE("band_dots_kernel", st, band_dots_kernel<T><<<tgrid, 256, 0, st>>>(q, tv, w.QF, cv, c.n, c.d, c.L, w.partQ));
   WERSA_STAGE("band_dots_kernel", st, band_dots_kernel<T><<<tgrid, 256, 0, st>>>(k, tv, w.KF, cv, c.n, c.d, c.L, w.partK));
   WERSA_STAGE("gate_bwd_slice_kernel", st, gate_bwd_slice_kernel<<<slices, 64, 0, st>>>(w.partQ, w.partK, tiles, c.L, c.d, c.H, s, gate_w,
-                                               scale_w, w.dF, w.dlogit, w.dqbar));
+                                               scale_w, w.dF, w.dlogit, w.dqbar, (c.flags & WERSA_FLAG_POOLED_GATE) ? 1 : 0));
   WERSA_STAGE("gate_bwd_params_kernel", st, gate_bwd_params_kernel<<<gate_bwd_params_blocks(c.H, c.L, c.d), 256, 0, st>>>(w.dF, w.dlogit, s, qbar, w.dDpart,
                                             slices * colsum_chunks(c.n), c.B, c.H, c.L, c.d, c.eps,
                                             w.scalars, dgate_w, dgate_b, dscale_w, dsigma));

@@ -41,11 +41,11 @@ def gpu_forward_backward(p, cfg, backward=True, eps=1e-6, bw_floor=1e-6, layout=
     return res
 
 
-def oracle_backward(p, cfg, eps=1e-6, bw_floor=1e-6, slices=None, proj_dtype=None):
+def oracle_backward(p, cfg, eps=1e-6, bw_floor=1e-6, slices=None, proj_dtype=None, pooled=False):
     from oracle import wersa_oracle as wo
     return wo.backward(p["Q"], p["K"], p["V"], p["Omega"], float(p["sigma"]), p["Wg"], p["bg"],
                        p["omega"], cfg["L"], p["dO"], eps=eps, bw_floor=bw_floor, slices=slices,
-                       proj_dtype=proj_dtype, Omega_K=p.get("OmegaK"))
+                       proj_dtype=proj_dtype, Omega_K=p.get("OmegaK"), pooled=pooled)
 
 
 def oracle_forward(p, cfg, eps=1e-6, bw_floor=1e-6, slices=None,

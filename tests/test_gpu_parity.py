@@ -260,6 +260,31 @@ def test_separate_query_and_key_random_matrices(path):
         _check_all(res, ref, TOL[dtype], where=f"separate omega {path}")
 
 
+@pytest.mark.parametrize("path", ["generic_f32", "generic_bf16", "mfma"])
+def test_gate_pooled_over_heads(path):
+    """WERSA_FLAG_POOLED_GATE (Algorithm 1's gate: one filter per batch element from the pooled
+    queries of all heads) on both paths against the oracle's pooled form."""
+    dtype = "f32" if path == "generic_f32" else "bf16"
+    cfg = dict(B=2, H=3, n=256, d=64, L=4, m=128, dtype=dtype, flavour="plain", seed_base=3300, q_mean=0.4)
+    p = workloads.make_inputs(**cfg)
+    flags = 4 | (0 if path == "mfma" else 1)
+    res = hp.gpu_forward_backward(p, cfg, flags=flags)
+    ref = hp.oracle_backward(p, cfg, pooled=True)
+    F = res["saved"]["F"].view(cfg["B"], cfg["H"], cfg["L"] + 1)
+    assert float((F - F[:, :1]).abs().max().cpu()) == 0.0          # every head of a batch element shares F
+    per_head = hp.oracle_backward(p, cfg)
+    assert hp.rel_err(res["O"], per_head["O"]) > 1e-2                # and it is not the per-head gate
+    if path == "mfma":
+        _check_all(res, ref, 2e-2, names=("O", "dQ", "dK", "dV"), where="pooled gate mfma")
+        ref16 = hp.oracle_backward(p, cfg, proj_dtype=np.float16, pooled=True)
+        scales = hp.gate_grad_scales(p, cfg)   # per-head magnitudes: the same order for the pooled sums
+        errs = {k: hp.scaled_err(res[k], ref16[k], scales[k]) for k in ("dWg", "dbg", "domega")}
+        print("pooled gate mfma, gate grads vs un-cancelled scale", errs, flush=True)
+        assert all(v < GATE_NOISE_TOL for v in errs.values()), errs
+    else:
+        _check_all(res, ref, TOL[dtype], where=f"pooled gate {path}")
+
+
 # ------------------------------------------------------------------ benchmark configurations
 def test_config1_tiny_fp32():
     cfg, p = workloads.make_config(1, backward=True)
