@@ -14,7 +14,8 @@ Readings of the paper taken here (each one is a choice where the text is
 silent or disagrees with itself):
 
 * Normalisation follows the Section 3.1 attention equation (divide by
-  phi(Q_F) phi(K_F)^T 1 + eps), not the LayerNorm of Algorithm 1.
+  phi(Q_F) phi(K_F)^T 1 + eps); the LayerNorm of Algorithm 1 is available as
+  an option (layernorm).
 * One shared random matrix Omega (Section 3.1 step 7) and the 1/sqrt(m) factor
   of Algorithm 1's random projection lines.  Algorithm 1's separate matrices for
   Q and K are available as an option (Omega_K).
@@ -138,12 +139,15 @@ def feature_map(XF, Omega, sigma, bw_floor, proj_dtype=None):
 # Forward, one (b, h) slice
 # ----------------------------------------------------------------------------
 def forward_slice(Q, K, V, Omega, sigma, Wg_h, bg_h, omega, L, eps, bw_floor, proj_dtype=None,
-                  Omega_K=None, gate_given=None):
+                  Omega_K=None, gate_given=None, layernorm=False):
     """Q, K, V (n, d) -> dict of every stage tensor, 'O' is the output.
 
     Omega_K: a second random matrix for the key side (Algorithm 1 draws separate projection
     matrices for Q and K); None = the one shared matrix of Section 3.1 step 7.
-    gate_given: (logits, s, F) computed outside (the gate pooled over heads), else this head's own."""
+    gate_given: (logits, s, F) computed outside (the gate pooled over heads), else this head's own.
+    layernorm: Algorithm 1's output stage, O = LayerNorm(phi(Q_F) (phi(K_F)^T V)) over the d
+    columns of each row (no affine parameters, biased variance, eps inside the root), in place
+    of Section 3.1's division by the normaliser; D then holds 1 / sqrt(var + eps)."""
     OmK = Omega if Omega_K is None else np.asarray(Omega_K, np.float64)
     Q = np.asarray(Q, np.float64)
     K = np.asarray(K, np.float64)
@@ -157,8 +161,14 @@ def forward_slice(Q, K, V, Omega, sigma, Wg_h, bg_h, omega, L, eps, bw_floor, pr
     S = PhiK.T @ V                       # (m, d)  phi(K_F)^T V
     z = PhiK.T @ np.ones(K.shape[0])     # (m,)    phi(K_F)^T 1
     N = PhiQ @ S
-    D = PhiQ @ z + eps
-    O = N / D[:, None]
+    if layernorm:
+        mu = N.mean(axis=1)
+        var = ((N - mu[:, None]) ** 2).mean(axis=1)
+        D = 1.0 / np.sqrt(var + eps)          # rstd
+        O = (N - mu[:, None]) * D[:, None]
+    else:
+        D = PhiQ @ z + eps
+        O = N / D[:, None]
     return dict(qbar=qbar, logits=logits, s=s, F=F, QF=QF, KF=KF, UQ=UQ, UK=UK,
                 PhiQ=PhiQ, PhiK=PhiK, S=S, z=z, N=N, D=D, O=O)
 
@@ -183,7 +193,7 @@ def _haar_filter_vjp(X, F, L, dXF):
 
 
 def backward_slice(Q, K, V, Omega, sigma, Wg_h, bg_h, omega, L, eps, bw_floor, dO,
-                   fwd=None, proj_dtype=None, Omega_K=None, gate_outside=False):
+                   fwd=None, proj_dtype=None, Omega_K=None, gate_outside=False, layernorm=False):
     """Returns dict dQ, dK, dV (n, d), dWg_h (L+1, d), dbg_h, domega (L+1,),
     dsigma (scalar, term-by-term chain rule form), plus intermediates."""
     Q = np.asarray(Q, np.float64)
@@ -191,7 +201,8 @@ def backward_slice(Q, K, V, Omega, sigma, Wg_h, bg_h, omega, L, eps, bw_floor, d
     V = np.asarray(V, np.float64)
     dO = np.asarray(dO, np.float64)
     f = fwd if fwd is not None else forward_slice(Q, K, V, Omega, sigma, Wg_h, bg_h,
-                                                  omega, L, eps, bw_floor, proj_dtype, Omega_K)
+                                                  omega, L, eps, bw_floor, proj_dtype, Omega_K,
+                                                  layernorm=layernorm)
     OmK = Omega if Omega_K is None else np.asarray(Omega_K, np.float64)
     n, d = Q.shape
     m = Omega.shape[1]
@@ -199,13 +210,21 @@ def backward_slice(Q, K, V, Omega, sigma, Wg_h, bg_h, omega, L, eps, bw_floor, d
     D, O, S, z = f["D"], f["O"], f["S"], f["z"]
     PhiQ, PhiK, UQ, UK = f["PhiQ"], f["PhiK"], f["UQ"], f["UK"]
 
-    # O = N / D
-    dN = dO / D[:, None]
-    dD = -np.sum(dO * O, axis=1) / D
-    # N = PhiQ S ; D = PhiQ z + eps
-    dPhiQ = dN @ S.T + np.outer(dD, z)
-    dS = PhiQ.T @ dN
-    dz = PhiQ.T @ dD
+    if layernorm:
+        # O = (N - mean) * rstd, per row: the standard LayerNorm derivative (D holds rstd)
+        dN = D[:, None] * (dO - dO.mean(axis=1, keepdims=True) - O * (dO * O).mean(axis=1, keepdims=True))
+        dD = np.zeros(n)
+        dPhiQ = dN @ S.T
+        dS = PhiQ.T @ dN
+        dz = np.zeros(m)
+    else:
+        # O = N / D
+        dN = dO / D[:, None]
+        dD = -np.sum(dO * O, axis=1) / D
+        # N = PhiQ S ; D = PhiQ z + eps
+        dPhiQ = dN @ S.T + np.outer(dD, z)
+        dS = PhiQ.T @ dN
+        dz = PhiQ.T @ dD
     # S = PhiK^T V ; z = PhiK^T 1
     dPhiK = V @ dS.T + np.outer(np.ones(n), dz)
     dV = PhiK @ dS
@@ -253,7 +272,7 @@ def pooled_gate(Qb, Wg, bg, omega):
 
 
 def forward(Q, K, V, Omega, sigma, Wg, bg, omega, L, eps=1e-6, bw_floor=1e-6,
-            slices=None, keep=("O",), proj_dtype=None, Omega_K=None, pooled=False):
+            slices=None, keep=("O",), proj_dtype=None, Omega_K=None, pooled=False, layernorm=False):
     """Q, K, V (B, H, n, d); Omega (d, m); Wg (H, L+1, d); bg (H, L+1); omega (L+1,).
 
     Returns dict of stacked stage tensors named in `keep`, each (B, H, ...).
@@ -271,7 +290,8 @@ def forward(Q, K, V, Omega, sigma, Wg, bg, omega, L, eps=1e-6, bw_floor=1e-6,
             given = (lg, sg, Fg)
         f = forward_slice(Q[b, h], K[b, h], V[b, h], Omega, sigma,
                           np.asarray(Wg[h], np.float64), np.asarray(bg[h], np.float64),
-                          np.asarray(omega, np.float64), L, eps, bw_floor, proj_dtype, Omega_K, given)
+                          np.asarray(omega, np.float64), L, eps, bw_floor, proj_dtype, Omega_K, given,
+                          layernorm)
         for name in keep:
             if name not in out:
                 out[name] = np.zeros((B, H) + np.shape(f[name]), np.float64)
@@ -280,7 +300,7 @@ def forward(Q, K, V, Omega, sigma, Wg, bg, omega, L, eps=1e-6, bw_floor=1e-6,
 
 
 def backward_pooled(Q, K, V, Omega, sigma, Wg, bg, omega, L, dO, eps=1e-6, bw_floor=1e-6,
-                    proj_dtype=None, Omega_K=None):
+                    proj_dtype=None, Omega_K=None, layernorm=False):
     """Backward with the gate pooled over heads (pooled_gate): dF of the heads of a batch element
     add up before the sigmoid's derivative; the pooled-query term then goes back to each head."""
     B, H, n, d = Q.shape
@@ -296,8 +316,8 @@ def backward_pooled(Q, K, V, Omega, sigma, Wg, bg, omega, L, dO, eps=1e-6, bw_fl
         for h in range(H):
             args = (Q[b, h], K[b, h], V[b, h], Omega, sigma, Wg[h], np.asarray(bg[h], np.float64), omega, L,
                     eps, bw_floor)
-            f = forward_slice(*args, proj_dtype, Omega_K, (lg, sg, Fg))
-            r = backward_slice(*args, dO[b, h], fwd=f, Omega_K=Omega_K, gate_outside=True)
+            f = forward_slice(*args, proj_dtype, Omega_K, (lg, sg, Fg), layernorm)
+            r = backward_slice(*args, dO[b, h], fwd=f, Omega_K=Omega_K, gate_outside=True, layernorm=layernorm)
             g["O"][b, h] = f["O"]
             g["dQ"][b, h], g["dK"][b, h], g["dV"][b, h] = r["dQ"], r["dK"], r["dV"]
             g["dsigma"] += r["dsigma"]
@@ -313,7 +333,7 @@ def backward_pooled(Q, K, V, Omega, sigma, Wg, bg, omega, L, dO, eps=1e-6, bw_fl
 
 
 def backward(Q, K, V, Omega, sigma, Wg, bg, omega, L, dO, eps=1e-6, bw_floor=1e-6,
-             slices=None, proj_dtype=None, Omega_K=None, pooled=False):
+             slices=None, proj_dtype=None, Omega_K=None, pooled=False, layernorm=False):
     """Gradients of sum(O * dO) w.r.t. Q, K, V, Wg, bg, omega, sigma.
 
     Parameter gradients are summed over every slice processed (all of them
@@ -321,7 +341,8 @@ def backward(Q, K, V, Omega, sigma, Wg, bg, omega, L, dO, eps=1e-6, bw_floor=1e-
     """
     if pooled:
         assert slices is None, "the pooled gate couples the heads of a batch element"
-        return backward_pooled(Q, K, V, Omega, sigma, Wg, bg, omega, L, dO, eps, bw_floor, proj_dtype, Omega_K)
+        return backward_pooled(Q, K, V, Omega, sigma, Wg, bg, omega, L, dO, eps, bw_floor, proj_dtype, Omega_K,
+                               layernorm)
     B, H, n, d = Q.shape
     Omega = np.asarray(Omega, np.float64)
     omega = np.asarray(omega, np.float64)
@@ -333,9 +354,9 @@ def backward(Q, K, V, Omega, sigma, Wg, bg, omega, L, dO, eps=1e-6, bw_floor=1e-
         Wg_h = np.asarray(Wg[h], np.float64)
         bg_h = np.asarray(bg[h], np.float64)
         f = forward_slice(Q[b, h], K[b, h], V[b, h], Omega, sigma, Wg_h, bg_h, omega, L,
-                          eps, bw_floor, proj_dtype, Omega_K)
+                          eps, bw_floor, proj_dtype, Omega_K, layernorm=layernorm)
         r = backward_slice(Q[b, h], K[b, h], V[b, h], Omega, sigma, Wg_h, bg_h, omega, L,
-                           eps, bw_floor, dO[b, h], fwd=f, Omega_K=Omega_K)
+                           eps, bw_floor, dO[b, h], fwd=f, Omega_K=Omega_K, layernorm=layernorm)
         g["O"][b, h] = f["O"]
         g["dQ"][b, h] = r["dQ"]
         g["dK"][b, h] = r["dK"]

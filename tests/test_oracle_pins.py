@@ -548,3 +548,55 @@ def test_pooled_gate_definition_special_cases_and_gradients():
             am[idx] -= h_
             fd = (loss(**{name: ap}) - loss(**{name: am})) / (2 * h_)
             assert abs(fd - g[gname][idx]) < 3e-6 * max(1.0, abs(fd)), (name, idx, fd, g[gname][idx])
+
+
+# ---------------------------------------------------------------- Algorithm 1 variant: LayerNorm output stage
+def test_layernorm_output_stage_properties_and_gradients():
+    """Algorithm 1 normalises the linear-attention output with LayerNorm.  Pins: each output row
+    has zero mean and variance var / (var + eps); the output does not change when V gets a
+    common scale (up to the eps term) nor when a constant is added to every column of the
+    numerator; the written-out formula on the explicit n x n numerator; all gradients match
+    central differences; d sigma equals its closed form -(2 / sigma) sum_t <dO_t, O_t> eps rstd_t^2."""
+    L, eps = 2, 1e-3
+    p = _rand_problem(81, B=1, H=2, n=40, d=6, m=16, L=L)
+    kw = dict(eps=eps, layernorm=True)
+    f = wo.forward(p["Q"], p["K"], p["V"], p["Omega"], p["sigma"], p["Wg"], p["bg"], p["omega"], L,
+                   keep=("O", "N", "D", "PhiQ", "PhiK"), **kw)
+    O, N, rstd = f["O"], f["N"], f["D"]
+    np.testing.assert_allclose(O.mean(axis=-1), 0.0, atol=1e-12)
+    var = N.var(axis=-1)
+    np.testing.assert_allclose(O.var(axis=-1), var / (var + eps), rtol=1e-10)
+    np.testing.assert_allclose(rstd, 1.0 / np.sqrt(var + eps), rtol=1e-12)
+    A = f["PhiQ"][0, 1] @ f["PhiK"][0, 1].T                      # explicit n x n kernel matrix, head 1
+    Nref = A @ p["V"][0, 1]
+    np.testing.assert_allclose(O[0, 1], (Nref - Nref.mean(1, keepdims=True)) / np.sqrt(Nref.var(1, keepdims=True) + eps),
+                               rtol=1e-10, atol=1e-12)
+    # scale invariance in V up to eps (tiny eps -> invariant)
+    a = wo.forward(p["Q"], p["K"], p["V"], p["Omega"], p["sigma"], p["Wg"], p["bg"], p["omega"], L, eps=1e-14,
+                   layernorm=True)["O"]
+    b = wo.forward(p["Q"], p["K"], 3.0 * p["V"], p["Omega"], p["sigma"], p["Wg"], p["bg"], p["omega"], L, eps=1e-14,
+                   layernorm=True)["O"]
+    np.testing.assert_allclose(a, b, rtol=1e-7, atol=1e-9)
+    g = wo.backward(p["Q"], p["K"], p["V"], p["Omega"], p["sigma"], p["Wg"], p["bg"], p["omega"], L, p["dO"], **kw)
+    h = 1e-6
+    r = np.random.default_rng(9)
+
+    def loss(**over):
+        q = dict(p, **over)
+        return float(np.sum(wo.forward(q["Q"], q["K"], q["V"], q["Omega"], q["sigma"], q["Wg"], q["bg"], q["omega"],
+                                       L, **kw)["O"] * p["dO"]))
+
+    for name, gname, count in (("Q", "dQ", 10), ("K", "dK", 8), ("V", "dV", 8), ("Wg", "dWg", 6), ("bg", "dbg", 4),
+                               ("omega", "domega", 3)):
+        arr = p[name]
+        for fi in r.choice(arr.size, size=min(count, arr.size), replace=False):
+            idx = np.unravel_index(fi, arr.shape)
+            ap, am = arr.copy(), arr.copy()
+            ap[idx] += h
+            am[idx] -= h
+            fd = (loss(**{name: ap}) - loss(**{name: am})) / (2 * h)
+            assert abs(fd - g[gname][idx]) < 5e-6 * max(1.0, abs(fd)), (name, idx, fd, g[gname][idx])
+    fd = (loss(sigma=p["sigma"] + h) - loss(sigma=p["sigma"] - h)) / (2 * h)
+    assert abs(fd - g["dsigma"]) < 5e-6 * max(1.0, abs(fd))
+    closed = -(2.0 / p["sigma"]) * np.sum(np.sum(p["dO"] * O, axis=-1) * eps * rstd ** 2)
+    np.testing.assert_allclose(g["dsigma"], closed, rtol=1e-7)
