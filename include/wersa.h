@@ -72,6 +72,10 @@ typedef enum { WERSA_F32 = 0, WERSA_BF16 = 1 } wersa_dtype;
  * head of that batch element. Parameter shapes are unchanged (gate_w read as the (L+1) x (H*d)
  * map in head blocks). Default (Section 3.1 step 4): each head gates itself. */
 #define WERSA_FLAG_POOLED_GATE 4
+/* Output stage of Algorithm 1: O = LayerNorm(phi(Q_F) (phi(K_F)^T V)) over the d columns of each
+ * row (no affine parameters, biased variance, desc.eps inside the square root) in place of
+ * Section 3.1's division by the normaliser. The saved per-row value is then 1 / sqrt(var + eps). */
+#define WERSA_FLAG_LAYERNORM 8
 
 /*
  * Problem descriptor (host memory, read during the call only).

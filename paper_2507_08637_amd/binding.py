@@ -137,6 +137,7 @@ def _same_layout(ref, *others):
 FLAG_GENERIC_PATH = 1
 FLAG_SEPARATE_OMEGA = 2
 FLAG_POOLED_GATE = 4
+FLAG_LAYERNORM = 8
 
 
 def _check_omega(omega_rf, q, flags):

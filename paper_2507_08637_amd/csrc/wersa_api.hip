@@ -16,7 +16,8 @@ wersa_status validate_desc(const wersa_desc *c) {
   if (c->m % 16 != 0 || c->m < 16 || c->m > 4096) return WERSA_ERR_UNSUPPORTED;
   if ((int64_t)c->B * c->H > 1023) return WERSA_ERR_UNSUPPORTED;
   if ((int64_t)c->n > (int64_t)1 << 22) return WERSA_ERR_UNSUPPORTED;
-  if (c->flags & ~(WERSA_FLAG_GENERIC_PATH | WERSA_FLAG_SEPARATE_OMEGA | WERSA_FLAG_POOLED_GATE)) return WERSA_ERR_INVALID_ARG;
+  if (c->flags & ~(WERSA_FLAG_GENERIC_PATH | WERSA_FLAG_SEPARATE_OMEGA | WERSA_FLAG_POOLED_GATE |
+                   WERSA_FLAG_LAYERNORM)) return WERSA_ERR_INVALID_ARG;
   return WERSA_OK;
 }
 

@@ -123,6 +123,21 @@ __device__ __forceinline__ bf16x8 lds_perm8(const bf16_t *row, int base, int h) 
   return r;
 }
 
+// Sum over the 32 lanes of a half-wave, result in every lane: two quad exchanges and two row
+// rotations inside each group of 16 lanes (DPP), then one swap of the two groups (swizzle).
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));
+}
+__device__ __forceinline__ float half_wave_sum(float v) {
+  v += dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]
+  v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]
+  v += dpp_move<0x124>(v);   // row_ror 4
+  v += dpp_move<0x128>(v);   // row_ror 8
+  v += __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F));   // lane ^ 16
+  return v;
+}
+
 // ------------------------------------------------------------------------------------
 // Per-call constants: block 0 writes the scalars; every block transposes its share of Omega
 // into Omega^T in fp16 ([m][d]), the projection's MFMA operand.  (The filter coefficients of
@@ -585,7 +600,7 @@ __global__ __launch_bounds__(256) void reduce_contract_kernel(const float *Spart
 // layout, rows on registers), per-band inner products with X for dF, bf16 stores.
 // ------------------------------------------------------------------------------------
 
-template <int DH, int MODE, int NW, int MC>
+template <int DH, int MODE, int NW, int MC, bool LN>   // LN (MODE 0): LayerNorm over the columns of a row instead of the normaliser
 __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
     const _Float16 *xf,        // X_F fp16 [slices][n][DH]
     const bf16_t *x, View vx,  // X (Q or K), for the band inner products (MODE 1, 2)
@@ -927,7 +942,34 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
     const int prow = lane >> 3, pcol = (lane & 7) * 4;   // this lane's 8-byte piece: rows prow + 8 j
     bf16_t *os = out0 + vo.slice_base(slice) + (int64_t)t0 * vo.sn;
 
-    if (MODE == 0) {   // normaliser D_t = c * sum_r relu(R) z + eps, row scale c / D_t
+    if (MODE == 0 && LN) {
+      // Output stage of Algorithm 1: O_t = (N_t - mean N_t) / sqrt(var N_t + eps), N = c * acc.
+      // A row lives on one register index across the 32 lanes of a half-wave (and the CT column
+      // tiles): mean first, then the centred second moment.  1 / sqrt(var + eps) goes to D.
+      float *dl = s_wave + wave * 64;
+#pragma unroll
+      for (int ti = 0; ti < 2; ++ti)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          float v = 0.f;
+#pragma unroll
+          for (int ct = 0; ct < CT; ++ct) v += acc0[ti][ct][i];
+          const float mu = half_wave_sum(v) * (1.0f / (float)DH);
+          float q = 0.f;
+#pragma unroll
+          for (int ct = 0; ct < CT; ++ct) {
+            const float e = (acc0[ti][ct][i] - mu) * cscale;
+            acc0[ti][ct][i] = e;
+            q = fmaf(e, e, q);
+          }
+          const float rstd = 1.0f / sqrtf(half_wave_sum(q) * (1.0f / (float)DH) + eps);
+#pragma unroll
+          for (int ct = 0; ct < CT; ++ct) acc0[ti][ct][i] *= rstd;
+          if (l32 == 0) dl[32 * ti + acc_row(i, h)] = rstd;
+        }
+      __builtin_amdgcn_wave_barrier();
+      Dout[(int64_t)slice * n + t0 + lane] = dl[lane];
+    } else if (MODE == 0) {   // normaliser D_t = c * sum_r relu(R) z + eps, row scale c / D_t
       float *dl = s_wave + wave * 64;
 #pragma unroll
       for (int ti = 0; ti < 2; ++ti) {
@@ -941,6 +983,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
     // Row scale of the accumulators (rows on registers): c / D_t (MODE 0 from the per-wave LDS
     // array written just above; LDS operations of one wave stay in order; MODE 1 from D), or c.
     __builtin_amdgcn_wave_barrier();
+    if (!(MODE == 0 && LN))
 #pragma unroll
     for (int ti = 0; ti < 2; ++ti) {
       float sc[16];
@@ -1126,6 +1169,59 @@ __global__ __launch_bounds__(256) void add_pooled_kernel(bf16_t *dq, View v, con
   }
 }
 
+// Backward of the LayerNorm output stage (Algorithm 1), row by row:
+//   dN_t = rstd_t (dO_t - mean dO_t - O_t mean(dO_t * O_t))   -> bf16 [slices][n][DH]
+// The gradient kernels then run as without a normaliser: D = 1 and dD = 0 (written here).
+// part[slice][chunk] = sum over the chunk's rows of -<dO_t, O_t> rstd_t^2, the per-row term of
+// d sigma (N scales with 1 / sigma^2 and <dN_t, N_t> = <dO_t, O_t> eps rstd_t^2).
+// DH / 8 lanes share a row, 16 bytes each.
+template <int DH>
+__global__ __launch_bounds__(256) void ln_prep_kernel(const bf16_t *dout, const bf16_t *out, View v,
+                                                     const float *rstd, int n, int rows_per_chunk,
+                                                     bf16_t *dN, float *ones, float *zeros, float *part) {
+  constexpr int CPR = DH / 8, RPB = 256 / CPR;
+  const int slice = blockIdx.y, chunk = blockIdx.x, tid = threadIdx.x;
+  const int t_begin = chunk * rows_per_chunk, t_end = min(n, t_begin + rows_per_chunk);
+  const int r = tid / CPR, cc = tid % CPR;
+  const int64_t base = v.slice_base(slice);
+  float acc = 0.f;
+  for (int t = t_begin + r; t < t_end; t += RPB) {
+    const int64_t off = base + (int64_t)t * v.sn + cc * 8;
+    const u16x8 g8 = *reinterpret_cast<const u16x8 *>(dout + off);
+    const u16x8 o8 = *reinterpret_cast<const u16x8 *>(out + off);
+    float g[8], o[8], sg = 0.f, sgo = 0.f;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      g[q] = bf16_to_f32(g8[q]);
+      o[q] = bf16_to_f32(o8[q]);
+      sg += g[q];
+      sgo = fmaf(g[q], o[q], sgo);
+    }
+#pragma unroll
+    for (int d = 1; d < CPR; d <<= 1) {
+      sg += __shfl_xor(sg, d, 64);
+      sgo += __shfl_xor(sgo, d, 64);
+    }
+    const int64_t row = (int64_t)slice * n + t;
+    const float rs = rstd[row];
+    const float m1 = sg * (1.0f / (float)DH), m2 = sgo * (1.0f / (float)DH);
+    u16x8 d8;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) d8[q] = cvt_bf16(rs * (g[q] - m1 - o[q] * m2));
+    *reinterpret_cast<u16x8 *>(dN + row * DH + cc * 8) = d8;
+    if (cc == 0) {
+      ones[row] = 1.0f;
+      zeros[row] = 0.0f;
+      acc -= sgo * rs * rs;
+    }
+  }
+  acc = wave_sum64(acc);
+  __shared__ float red[4];
+  if ((tid & 63) == 0) red[tid >> 6] = acc;
+  __syncthreads();
+  if (tid == 0) part[(int64_t)slice * gridDim.x + chunk] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
 // ---------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------
@@ -1172,6 +1268,8 @@ struct FastWs {
       *dlogit, *dqbar;
   _Float16 *omT;
   bf16_t *Sx, *ST, *zb, *dSx, *dST, *dzb;
+  bf16_t *dN;    // LayerNorm output stage: gradient with respect to the un-normalised rows
+  float *ones;   // and the stand-in for D in the gradient kernels
   int64_t total;
 };
 
@@ -1207,6 +1305,10 @@ FastWs fast_ws(const wersa_desc &c, const FastPlan &p, int bwd, float *base, flo
     w.dF = b.take(sl * (c.L + 1));
     w.dlogit = b.take(sl * (c.L + 1));
     w.dqbar = b.take(sl * c.d);
+    if (c.flags & WERSA_FLAG_LAYERNORM) {
+      w.dN = reinterpret_cast<bf16_t *>(b.take(sl * c.n * c.d / 2));
+      w.ones = b.take(sl * c.n);
+    }
   }
   w.total = b.off;
   return w;
@@ -1229,7 +1331,8 @@ template <int DH, int MODE>
 hipError_t launch_rows(const wersa_desc &c, const FastPlan &p, const _Float16 *xf, const bf16_t *x,
                        const bf16_t *y, const float *Dsaved, const float *arow, const FastWs &w,
                        const bf16_t *omega, const bf16_t *Mx, const bf16_t *MT, const bf16_t *bb,
-                       bf16_t *out0, float *Dout, float *partF, hipStream_t st) {
+                       bf16_t *out0, float *Dout, float *partF, hipStream_t st,
+                       const View *yview = nullptr) {
   constexpr bool IS_GRAD = (MODE == 1 || MODE == 2);
   constexpr int NW = IS_GRAD ? kWavesGrad : waves_apply(DH);
   // key-side modes take the second random matrix when the descriptor has two
@@ -1247,27 +1350,31 @@ hipError_t launch_rows(const wersa_desc &c, const FastPlan &p, const _Float16 *x
     if (e != hipSuccess) return e;
     WERSA_STAGE(name, st,
                 kern<<<dim3(wgs, c.B * c.H), NW * 64, smem, st>>>(
-                    xf, x, tv, y, tv, Dsaved, arow, omT, omega, Mx, MT, bb, w.coef, w.scalars, c.eps, c.n, c.m,
-                    groups, out0, tv, Dout, partF, c.L));
+                    xf, x, tv, y, yview ? *yview : tv, Dsaved, arow, omT, omega, Mx, MT, bb, w.coef, w.scalars,
+                    c.eps, c.n, c.m, groups, out0, tv, Dout, partF, c.L));
     return hipSuccess;
   };
-  if (p.mc == 256) return go(&rows_kernel<DH, MODE, NW, 256>);
-  return go(&rows_kernel<DH, MODE, NW, 128>);
+  if (MODE == 0 && (c.flags & WERSA_FLAG_LAYERNORM)) {
+    if (p.mc == 256) return go(&rows_kernel<DH, MODE, NW, 256, MODE == 0>);
+    return go(&rows_kernel<DH, MODE, NW, 128, MODE == 0>);
+  }
+  if (p.mc == 256) return go(&rows_kernel<DH, MODE, NW, 256, false>);
+  return go(&rows_kernel<DH, MODE, NW, 128, false>);
 }
 
-// orows != nullptr selects the backward form that derives dD from the rows of O itself.
+// orows != nullptr selects the backward form that derives dD from the rows of O itself;
+// otherwise the row weights of the vector part are `wts` (all ones when nullptr).
 template <int DH>
 void launch_contract(const wersa_desc &c, const FastPlan &p, const _Float16 *xf, const bf16_t *y,
-                     const float *rowdiv, const bf16_t *orows, const FastWs &w, float *S, float *z,
-                     bf16_t *Mx, bf16_t *MT, bf16_t *bb, hipStream_t st) {
-  const View tv{c.stride_b, c.stride_h, c.stride_n, c.H};
+                     const View &yv, const float *rowdiv, const float *wts, const bf16_t *orows,
+                     bool key_side, const FastWs &w, float *S, float *z, bf16_t *Mx, bf16_t *MT,
+                     bf16_t *bb, hipStream_t st) {
   const int slices = c.B * c.H;
   dim3 grid(p.chunksC, c.m / p.MB, slices);
-  // the forward launch contracts over the key side, the backward one (orows given) over the query side
-  const _Float16 *omT = w.omT + (((c.flags & WERSA_FLAG_SEPARATE_OMEGA) && !orows) ? (int64_t)c.d * c.m : 0);
+  const _Float16 *omT = w.omT + (((c.flags & WERSA_FLAG_SEPARATE_OMEGA) && key_side) ? (int64_t)c.d * c.m : 0);
   auto go = [&](auto kern) {
     WERSA_STAGE("wersa_phiT_contract", st,
-                kern<<<grid, 256, 0, st>>>(xf, y, tv, rowdiv, nullptr, orows, w.dD, w.dDpart, omT, c.n, c.m,
+                kern<<<grid, 256, 0, st>>>(xf, y, yv, rowdiv, wts, orows, w.dD, w.dDpart, omT, c.n, c.m,
                                            p.rowsC, w.Spart, w.zpart));
   };
   if (p.FW == 64) {
@@ -1311,7 +1418,7 @@ wersa_status fast_forward_t(const wersa_desc &c, const bf16_t *q, const bf16_t *
               haar_stage_kernel<DH><<<dim3(c.n / 64, slices), 256, 0, st>>>(q, tv, c.n, w.coef, QF));
   WERSA_STAGE("wersa_haar_stage", st,
               haar_stage_kernel<DH><<<dim3(c.n / 64, slices), 256, 0, st>>>(k, tv, c.n, w.coef, KF));
-  launch_contract<DH>(c, p, KF, v, nullptr, nullptr, w, S, z, w.Sx, w.ST, w.zb, st);
+  launch_contract<DH>(c, p, KF, v, tv, nullptr, nullptr, nullptr, true, w, S, z, w.Sx, w.ST, w.zb, st);
   if (launch_rows<DH, 0>(c, p, QF, nullptr, nullptr, nullptr, nullptr, w, omega, nullptr, w.ST, w.zb, out, D,
                          nullptr, st) != hipSuccess)
     return WERSA_ERR_LAUNCH;
@@ -1337,10 +1444,22 @@ wersa_status fast_backward_t(const wersa_desc &c, const bf16_t *q, const bf16_t 
 
   // dS = Phi_Q^T dN, dz = Phi_Q^T dD; the same pass derives dD_t = -<dO_t, O_t> / D_t from the
   // rows of O and leaves it in the workspace for the Q-side gradient kernel.
-  launch_contract<DH>(c, p, QF, dout, D, out, w, w.dS, w.dz, w.dSx, w.dST, w.dzb, st);
-  if (launch_rows<DH, 1>(c, p, QF, q, dout, D, w.dD, w, omega, w.Sx, nullptr, nullptr, dq, nullptr, w.partQ,
-                         st) != hipSuccess)
-    return WERSA_ERR_LAUNCH;
+  if (c.flags & WERSA_FLAG_LAYERNORM) {
+    // LayerNorm output stage: dN first, then the same kernels with D = 1 and dD = 0 (so dz = 0).
+    const View nv{(int64_t)c.H * c.n * DH, (int64_t)c.n * DH, DH, c.H};
+    WERSA_STAGE("wersa_ln_prep", st,
+                ln_prep_kernel<DH><<<dim3(p.chunksC, slices), 256, 0, st>>>(dout, out, tv, D, c.n, p.rowsC, w.dN,
+                                                                           w.ones, w.dD, w.dDpart));
+    launch_contract<DH>(c, p, QF, w.dN, nv, nullptr, w.dD, nullptr, false, w, w.dS, w.dz, w.dSx, w.dST, w.dzb, st);
+    if (launch_rows<DH, 1>(c, p, QF, q, w.dN, w.ones, w.dD, w, omega, w.Sx, nullptr, nullptr, dq, nullptr,
+                           w.partQ, st, &nv) != hipSuccess)
+      return WERSA_ERR_LAUNCH;
+  } else {
+    launch_contract<DH>(c, p, QF, dout, tv, D, nullptr, out, false, w, w.dS, w.dz, w.dSx, w.dST, w.dzb, st);
+    if (launch_rows<DH, 1>(c, p, QF, q, dout, D, w.dD, w, omega, w.Sx, nullptr, nullptr, dq, nullptr,
+                           w.partQ, st) != hipSuccess)
+      return WERSA_ERR_LAUNCH;
+  }
   if (launch_rows<DH, 2>(c, p, KF, k, v, nullptr, nullptr, w, omega, w.dSx, nullptr, nullptr, dk, nullptr,
                          w.partK, st) != hipSuccess)
     return WERSA_ERR_LAUNCH;

@@ -306,6 +306,56 @@ __global__ void prep_dn_kernel(const T *dout, const T *out, View v, const float 
   if (lane == 0) dD[(int64_t)slice * n + t] = -acc / Dt;
 }
 
+// Output stage of Algorithm 1: O_t = (N_t - mean N_t) * rstd_t over the d columns of a row,
+// rstd_t = 1 / sqrt(var N_t + eps) (biased variance), kept in D.   (one wave per row)
+template <typename T>
+__global__ void ln_rows_kernel(const float *N, T *out, View v, int n, int d, float eps, float *D) {
+  const int slice = blockIdx.y;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (t >= n) return;
+  const float *p = N + ((int64_t)slice * n + t) * d;
+  float acc = 0.f;
+  for (int j = lane; j < d; j += 64) acc += p[j];
+  const float mu = wave_sum(acc) / (float)d;
+  acc = 0.f;
+  for (int j = lane; j < d; j += 64) {
+    const float e = p[j] - mu;
+    acc += e * e;
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum(acc) / (float)d + eps);
+  const int64_t base = v.slice_base(slice) + (int64_t)t * v.sn;
+  for (int j = lane; j < d; j += 64) st(out + base + j, (p[j] - mu) * rstd);
+  if (lane == 0) D[(int64_t)slice * n + t] = rstd;
+}
+
+// Backward of that stage: dN_t = rstd_t (dO_t - mean dO_t - O_t mean(dO_t * O_t)); there is no
+// normaliser, so dD = 0; sig_t = -<dO_t, O_t> rstd_t^2 carries the bandwidth gradient
+// (N scales with 1 / sigma^2, and <dN_t, N_t> = <dO_t, O_t> eps rstd_t^2).
+template <typename T>
+__global__ void prep_ln_kernel(const T *dout, const T *out, View v, const float *D, int n, int d,
+                               float *dN, float *dD, float *sig) {
+  const int slice = blockIdx.y;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (t >= n) return;
+  const int64_t base = v.slice_base(slice) + (int64_t)t * v.sn;
+  const float rstd = D[(int64_t)slice * n + t];
+  float sg = 0.f, sgo = 0.f;
+  for (int j = lane; j < d; j += 64) {
+    const float g = ld(dout + base + j);
+    sg += g;
+    sgo += g * ld(out + base + j);
+  }
+  sg = wave_sum(sg);
+  sgo = wave_sum(sgo);
+  const float m1 = sg / (float)d, m2 = sgo / (float)d;
+  for (int j = lane; j < d; j += 64)
+    dN[((int64_t)slice * n + t) * d + j] = rstd * (ld(dout + base + j) - m1 - ld(out + base + j) * m2);
+  if (lane == 0) {
+    dD[(int64_t)slice * n + t] = 0.f;
+    sig[(int64_t)slice * n + t] = -sgo * rstd * rstd;
+  }
+}
+
 // R = (R + a[slice][t] * b[slice][r]) * 1[Phi > 0] * c     (a == nullptr means a = 1)
 __global__ void mask_scale_kernel(float *R, const float *phi, const float *a, const float *b,
                                   const float *c_ptr, int n, int m, int64_t total) {
@@ -339,7 +389,7 @@ int ew_blocks(int64_t total) {
 
 struct GenericWs {
   float *scalars, *qpart, *QF, *KF, *Vf, *Of, *Phi, *R, *Spart, *zpart, *Nbuf;
-  float *dN, *dD, *dS, *dz, *dDpart, *dVf, *partQ, *partK, *dF, *dlogit, *dqbar;
+  float *dN, *dD, *sig, *dS, *dz, *dDpart, *dVf, *partQ, *partK, *dF, *dlogit, *dqbar;
   int64_t total;
 };
 
@@ -363,6 +413,7 @@ GenericWs plan(const wersa_desc &c, int bwd, float *base) {
     w.R = b.take(nm);
     w.dN = w.Nbuf;
     w.dD = b.take(sl * c.n);
+    w.sig = b.take(sl * c.n);
     w.dS = b.take(sl * (int64_t)c.m * c.d);
     w.dz = b.take(sl * c.m);
     w.dDpart = b.take(sl * chunks);
@@ -475,8 +526,12 @@ wersa_status forward_t(const wersa_desc &c, const T *q, const T *k, const T *v, 
   // step 7 on Q, then step 8
   launch_features(c, w.QF, 0, w, st);
   launch_rows_gemm(c, w.Phi, c.m, S, c.d, 1, (int64_t)c.m * c.d, c.d, w.Nbuf, st);
-  WERSA_STAGE("rowdot_kernel", st, rowdot_kernel<<<dim3((c.n + 3) / 4, slices), 256, 0, st>>>(w.Phi, z, c.n, c.m, c.eps, D));
-  WERSA_STAGE("scatter_kernel", st, scatter_kernel<T><<<ew_blocks(nd), 256, 0, st>>>(w.Nbuf, D, out, tv, c.n, c.d, nd));
+  if (c.flags & WERSA_FLAG_LAYERNORM) {
+    WERSA_STAGE("ln_rows_kernel", st, ln_rows_kernel<T><<<dim3((c.n + 3) / 4, slices), 256, 0, st>>>(w.Nbuf, out, tv, c.n, c.d, c.eps, D));
+  } else {
+    WERSA_STAGE("rowdot_kernel", st, rowdot_kernel<<<dim3((c.n + 3) / 4, slices), 256, 0, st>>>(w.Phi, z, c.n, c.m, c.eps, D));
+    WERSA_STAGE("scatter_kernel", st, scatter_kernel<T><<<ew_blocks(nd), 256, 0, st>>>(w.Nbuf, D, out, tv, c.n, c.d, nd));
+  }
   return hipGetLastError() == hipSuccess ? WERSA_OK : WERSA_ERR_LAUNCH;
 }
 
@@ -506,12 +561,17 @@ wersa_status backward_t(const wersa_desc &c, const T *q, const T *k, const T *v,
     WERSA_STAGE("gather_f32_kernel", st, gather_f32_kernel<T><<<ew_blocks(om), 256, 0, st>>>(
         omega_rf, contiguous_view(c.d, c.m), c.d, c.m, om, w.Of));
   }
-  // O = N / D
-  WERSA_STAGE("prep_dn_kernel", st, prep_dn_kernel<T><<<dim3((c.n + 3) / 4, slices), 256, 0, st>>>(dout, out, tv, D, c.n, c.d, w.dN, w.dD));
-  {  // sum of dD over everything, for d sigma
+  const bool ln = (c.flags & WERSA_FLAG_LAYERNORM) != 0;
+  // O = N / D, or O = LayerNorm(N)
+  if (ln) {
+    WERSA_STAGE("prep_ln_kernel", st, prep_ln_kernel<T><<<dim3((c.n + 3) / 4, slices), 256, 0, st>>>(dout, out, tv, D, c.n, c.d, w.dN, w.dD, w.sig));
+  } else {
+    WERSA_STAGE("prep_dn_kernel", st, prep_dn_kernel<T><<<dim3((c.n + 3) / 4, slices), 256, 0, st>>>(dout, out, tv, D, c.n, c.d, w.dN, w.dD));
+  }
+  {  // sum over everything of the per-row term of d sigma: dD, or sig with LayerNorm
     const int chunks = colsum_chunks(c.n), rows = (c.n + chunks - 1) / chunks;
     WERSA_STAGE("colsum_partial_kernel", st, colsum_partial_kernel<float><<<dim3(chunks, slices), 256, 0, st>>>(
-        w.dD, contiguous_view(c.n, 1), c.n, 1, rows, nullptr, w.dDpart));
+        ln ? w.sig : w.dD, contiguous_view(c.n, 1), c.n, 1, rows, nullptr, w.dDpart));
   }
   // Q side: dPhi_Q = dN S^T + dD z^T ; dS = Phi_Q^T dN ; dz = Phi_Q^T dD
   launch_features(c, w.QF, 0, w, st);

@@ -41,18 +41,20 @@ def gpu_forward_backward(p, cfg, backward=True, eps=1e-6, bw_floor=1e-6, layout=
     return res
 
 
-def oracle_backward(p, cfg, eps=1e-6, bw_floor=1e-6, slices=None, proj_dtype=None, pooled=False):
+def oracle_backward(p, cfg, eps=1e-6, bw_floor=1e-6, slices=None, proj_dtype=None, pooled=False,
+                    layernorm=False):
     from oracle import wersa_oracle as wo
     return wo.backward(p["Q"], p["K"], p["V"], p["Omega"], float(p["sigma"]), p["Wg"], p["bg"],
                        p["omega"], cfg["L"], p["dO"], eps=eps, bw_floor=bw_floor, slices=slices,
-                       proj_dtype=proj_dtype, Omega_K=p.get("OmegaK"), pooled=pooled)
+                       proj_dtype=proj_dtype, Omega_K=p.get("OmegaK"), pooled=pooled, layernorm=layernorm)
 
 
 def oracle_forward(p, cfg, eps=1e-6, bw_floor=1e-6, slices=None,
-                   keep=("O", "S", "z", "qbar", "s", "F", "D")):
+                   keep=("O", "S", "z", "qbar", "s", "F", "D"), layernorm=False):
     from oracle import wersa_oracle as wo
     return wo.forward(p["Q"], p["K"], p["V"], p["Omega"], float(p["sigma"]), p["Wg"], p["bg"],
-                      p["omega"], cfg["L"], eps=eps, bw_floor=bw_floor, slices=slices, keep=keep)
+                      p["omega"], cfg["L"], eps=eps, bw_floor=bw_floor, slices=slices, keep=keep,
+                      Omega_K=p.get("OmegaK"), layernorm=layernorm)
 
 
 def rel_err(gpu, ref):
@@ -62,7 +64,7 @@ def rel_err(gpu, ref):
     return float(np.linalg.norm(a - ref) / (den if den > 0 else 1.0))
 
 
-def gate_grad_scales(p, cfg, eps=1e-6, bw_floor=1e-6):
+def gate_grad_scales(p, cfg, eps=1e-6, bw_floor=1e-6, layernorm=False):
     """Un-cancelled magnitudes of the gate-parameter gradients, for conditioning-aware checks.
 
     dF_i of one slice is an inner product <band_i(W dX_F), band_i(W X)> summed over Q and K.  On
@@ -85,8 +87,9 @@ def gate_grad_scales(p, cfg, eps=1e-6, bw_floor=1e-6):
                     np.asarray(p["V"][b, h], np.float64), Om, float(p["sigma"]),
                     np.asarray(p["Wg"][h], np.float64), np.asarray(p["bg"][h], np.float64), omega, L,
                     eps, bw_floor)
-            r = wo.backward_slice(*args, np.asarray(p["dO"][b, h], np.float64), Omega_K=p.get("OmegaK"))
-            f = wo.forward_slice(*args, Omega_K=p.get("OmegaK"))
+            r = wo.backward_slice(*args, np.asarray(p["dO"][b, h], np.float64), Omega_K=p.get("OmegaK"),
+                                  layernorm=layernorm)
+            f = wo.forward_slice(*args, Omega_K=p.get("OmegaK"), layernorm=layernorm)
             s_all[b, h], qbar[b, h] = f["s"], f["qbar"]
             for X, G in ((args[0], r["dQF"]), (args[1], r["dKF"])):
                 cx, _ = wo.haar_dwt(X, L)

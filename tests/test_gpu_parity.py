@@ -285,6 +285,66 @@ def test_gate_pooled_over_heads(path):
         _check_all(res, ref, TOL[dtype], where=f"pooled gate {path}")
 
 
+@pytest.mark.parametrize("path", ["generic_f32", "generic_bf16", "mfma"])
+def test_layernorm_output_stage(path):
+    """WERSA_FLAG_LAYERNORM (Algorithm 1's output stage: LayerNorm over the head dimension in
+    place of the normaliser) on both paths against the oracle's option; eps = 1e-3 so that the
+    eps-order bandwidth gradient is well above rounding."""
+    import torch
+    from paper_2507_08637_amd import binding
+    dtype = "f32" if path == "generic_f32" else "bf16"
+    cfg = dict(B=2, H=2, n=320, d=64, L=4, m=128, dtype=dtype, flavour="plain", seed_base=3500, q_mean=0.4)
+    p = workloads.make_inputs(**cfg)
+    eps = 1e-3
+    flags = 8 | (0 if path == "mfma" else 1)
+    res = hp.gpu_forward_backward(p, cfg, eps=eps, flags=flags)
+    ref = hp.oracle_backward(p, cfg, eps=eps, layernorm=True)
+    plain = hp.oracle_backward(p, cfg, eps=eps)
+    assert hp.rel_err(res["O"], plain["O"]) > 0.1                    # it is not the Section 3.1 normaliser
+    O = res["O"].float()
+    assert float(O.mean(dim=-1).abs().max().cpu()) < (1e-5 if dtype == "f32" else 2e-2)
+    fwd = hp.oracle_forward(p, cfg, eps=eps, keep=("D",), layernorm=True)
+    D = res["saved"]["D"].view(cfg["B"], cfg["H"], cfg["n"])
+    assert hp.rel_err(D, fwd["D"]) < TOL[dtype]
+    if path == "mfma":
+        probe = torch.empty(cfg["B"], cfg["H"], cfg["n"], cfg["d"], dtype=torch.bfloat16, device="cuda")
+        assert binding.wersa_path_name(binding.make_desc(probe, cfg["L"], cfg["m"], eps, 1e-6, flags)) == "mfma"
+        _check_all(res, ref, 2e-2, names=("O", "dQ", "dK", "dV"), where="layernorm mfma")
+        ref16 = hp.oracle_backward(p, cfg, eps=eps, proj_dtype=np.float16, layernorm=True)
+        scales = hp.gate_grad_scales(p, cfg, eps=eps, layernorm=True)
+        errs = {k: hp.scaled_err(res[k], ref16[k], scales[k]) for k in ("dWg", "dbg", "domega")}
+        print("layernorm mfma, gate grads vs un-cancelled scale", errs, flush=True)
+        assert all(v < GATE_NOISE_TOL for v in errs.values()), errs
+        assert abs(float(res["dsigma"].cpu()) - ref["dsigma"]) < 5e-2 * abs(ref["dsigma"])
+    else:
+        _check_all(res, ref, TOL[dtype], where=f"layernorm {path}")
+        assert abs(float(res["dsigma"].cpu()) - ref["dsigma"]) < (1e-3 if dtype == "f32" else 2e-2) * abs(ref["dsigma"])
+
+
+@pytest.mark.parametrize("shape", [dict(B=1, H=2, n=1024, d=64, L=5, m=256),
+                                   dict(B=2, H=1, n=832, d=128, L=6, m=256)])
+def test_layernorm_output_stage_mfma_shapes(shape):
+    """The LayerNorm output stage on the other MFMA kernel variants: 256-feature operand blocks
+    (d = 64) and the head dimension 128."""
+    import torch
+    from paper_2507_08637_amd import binding
+    cfg = dict(shape, dtype="bf16", flavour="plain", seed_base=3600, q_mean=0.3)
+    p = workloads.make_inputs(**cfg)
+    eps = 1e-3
+    probe = torch.empty(cfg["B"], cfg["H"], cfg["n"], cfg["d"], dtype=torch.bfloat16, device="cuda")
+    assert binding.wersa_path_name(binding.make_desc(probe, cfg["L"], cfg["m"], eps, 1e-6, 8)) == "mfma"
+    res = hp.gpu_forward_backward(p, cfg, eps=eps, flags=8)
+    ref = hp.oracle_backward(p, cfg, eps=eps, layernorm=True)
+    _check_all(res, ref, 2e-2, names=("O", "dQ", "dK", "dV"), where=f"layernorm mfma {shape}")
+    fwd = hp.oracle_forward(p, cfg, eps=eps, keep=("D",), layernorm=True)
+    assert hp.rel_err(res["saved"]["D"].view(cfg["B"], cfg["H"], cfg["n"]), fwd["D"]) < 2e-2
+    ref16 = hp.oracle_backward(p, cfg, eps=eps, proj_dtype=np.float16, layernorm=True)
+    scales = hp.gate_grad_scales(p, cfg, eps=eps, layernorm=True)
+    errs = {k: hp.scaled_err(res[k], ref16[k], scales[k]) for k in ("dWg", "dbg", "domega")}
+    assert all(v < GATE_NOISE_TOL for v in errs.values()), errs
+    assert abs(float(res["dsigma"].cpu()) - ref["dsigma"]) < 5e-2 * abs(ref["dsigma"])
+
+
 # ------------------------------------------------------------------ benchmark configurations
 def test_config1_tiny_fp32():
     cfg, p = workloads.make_config(1, backward=True)
