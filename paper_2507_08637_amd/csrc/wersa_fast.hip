@@ -339,6 +339,73 @@ __device__ __forceinline__ bf16x4 lds_read_tr4(const bf16_t *p) {
   return __builtin_bit_cast(bf16x4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)p));
 }
 
+// The same packing as pack_half into an fp16 operand.
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ f16x8 pack_half_f16(const f32x16 &v, int a) {
+  f16x8 p;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    f32x2 f;
+    f[0] = v[8 * a + 2 * j];
+    f[1] = v[8 * a + 2 * j + 1];
+    const f16x2_t c = __builtin_convertvector(f, f16x2_t);
+    p[2 * j] = c[0];
+    p[2 * j + 1] = c[1];
+  }
+  return p;
+}
+
+// In-kernel stage A (head dimension 64): the gated Haar filter of one aligned 64-row block is
+// the product with a 64 x 64 matrix G (from the block-mean coefficients of the slice), so the kernels
+// that consume X_F take the raw rows of Q or K and form X_F^T = X^T G^T on the matrix cores.
+// G[t'][t] depends only on the highest bit in which t' and t differ: g_k = sum of coef_l over
+// l >= k, k = 0 for t' == t, else (position of that bit) + 1.  For the matrix cores G is split
+// into a bf16 high part and a bf16 low part (the gradients are sensitive to a relative error of
+// 2^-9 in the filter), and its B operands (column t', k-slot t = 8 j + q) come out of a small
+// table T[part][t' % 8][(t' / 8) ^ j][q] = part of g at t' ^ t, one 16-byte read each.
+__device__ __forceinline__ void build_filter_table(bf16_t *T, const float *coef8, int tid, int nthreads) {
+  float g[7], acc = 0.f;
+#pragma unroll
+  for (int l = 6; l >= 0; --l) {
+    acc += coef8[l];
+    g[l] = acc;
+  }
+  for (int e = tid; e < 512; e += nthreads) {
+    const int b = e >> 6, xh = (e >> 3) & 7, q = e & 7;
+    const int x = 8 * xh + (b ^ q);
+    const int lvl = x ? 32 - __clz(x) : 0;
+    float v = g[0];
+#pragma unroll
+    for (int k = 1; k < 7; ++k) v = (lvl == k) ? g[k] : v;
+    const __bf16 hi = (__bf16)v;
+    const __bf16 lo = (__bf16)(v - (float)hi);
+    T[e] = __builtin_bit_cast(bf16_t, hi);
+    T[512 + e] = __builtin_bit_cast(bf16_t, lo);
+  }
+}
+__device__ __forceinline__ bf16x8 filter_operand(const bf16_t *T, int part, int trow, int j) {
+  return *reinterpret_cast<const bf16x8 *>(&T[part * 512 + (((trow & 7) << 3) | ((trow >> 3) ^ j)) * 8]);
+}
+// This is the A operand of that product from a row-major bf16 tile [t][stride]: operand row
+// lane % 32 is tile column col0 + lane % 32 (PERM: with bits 2 and 3 of lane % 32 swapped),
+// k-slot (h, q) is tile row 16 ks + 8 h + q.  With PERM, pack_half of the result delivers the
+// columns in natural order (k-slot (h, q) of half a is column 16 a + 8 h + q).
+template <bool PERM>
+__device__ __forceinline__ bf16x8 tile_cols_operand(const bf16_t *tile, int stride, int col0, int ks, int lane) {
+  const int i16 = lane & 15, g16 = lane >> 4;
+  int k = i16 & 3;
+  if (PERM) k = ((k & 1) << 1) | (k >> 1);
+  const bf16_t *p = tile + (16 * ks + 8 * (g16 >> 1) + (i16 >> 2)) * stride + col0 + 16 * (g16 & 1) + 4 * k;
+  const bf16x4 lo = lds_read_tr4(p), hi = lds_read_tr4(p + 4 * stride);
+  bf16x8 r;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    r[q] = lo[q];
+    r[4 + q] = hi[q];
+  }
+  return r;
+}
+
 // ------------------------------------------------------------------------------------
 // phiT_contract: for the rows of one chunk and the features [f0, f0 + 4*FW) of one slice
 //   Spart[r][c] = sum_t ReLU(X_F Omega)[t][r] * (Y[t][c] / rowdiv_t)
@@ -352,11 +419,16 @@ __device__ __forceinline__ bf16x4 lds_read_tr4(const bf16_t *p) {
 // read: w_t = dD_t = -<dO_t, O_t> / D_t from the rows of O (`orows`, laid out like Y).  The
 // feature block 0 also writes dD [slices][n] for the gradient rows kernel and one partial sum
 // of dD per (slice, chunk) for d sigma.
+// Head dimension 64 (FUSE): `xf` is not read; the rows of X (Q or K, bf16, view vx) are staged
+// raw and each step starts with X_F = G X for its tile, one 32 x 32 quarter per wave, written
+// to LDS in fp16 for the projection.
 template <int DH, int FW, bool PREP>
 __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
-    const _Float16 *xf, const bf16_t *y, View vy, const float *rowdiv, const float *w,
+    const _Float16 *xf, const bf16_t *xraw, View vx, const float *coef,
+    const bf16_t *y, View vy, const float *rowdiv, const float *w,
     const bf16_t *orows, float *dDout, float *dDpart,
     const _Float16 *omT, int n, int m, int rows_per_chunk, float *Spart, float *zpart) {
+  constexpr bool FUSE = (DH == 64);
   constexpr int KS = DH / 16;   // k-steps of the projection
   constexpr int RT = FW / 32;   // feature tiles per wave
   constexpr int CT = DH / 32;   // column tiles of Y
@@ -366,7 +438,9 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
                                 // of 256, so the four rows of a transposing read fall into different bank quarters
   constexpr int XS = DH + 8;    // row stride (elements) of the X_F tile
   __shared__ __attribute__((aligned(16))) bf16_t yt[2][64 * YS];
-  __shared__ __attribute__((aligned(16))) _Float16 xt[2][64 * XS];
+  __shared__ __attribute__((aligned(16))) _Float16 xt[2][64 * XS];   // FUSE: raw bf16 rows of X
+  __shared__ __attribute__((aligned(16))) _Float16 xq[FUSE ? 64 * XS : 8];   // FUSE: X_F of the current tile
+  __shared__ __attribute__((aligned(16))) bf16_t gt[FUSE ? 1024 : 8];        // FUSE: filter operand table
   __shared__ __attribute__((aligned(16))) bf16_t wl[2][64];
   const int slice = blockIdx.z, chunk = blockIdx.x, chunks = gridDim.x;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
@@ -390,9 +464,11 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) S[rt][ct] = zero16();
   }
-  const _Float16 *xs = xf + (int64_t)slice * n * DH;
+  const _Float16 *xs = FUSE ? nullptr : xf + (int64_t)slice * n * DH;
+  const bf16_t *xrs = FUSE ? xraw + vx.slice_base(slice) : nullptr;
   const bf16_t *ys = y + vy.slice_base(slice);
   const float *rd = rowdiv ? rowdiv + (int64_t)slice * n : nullptr;
+  if (FUSE) build_filter_table(gt, coef + slice * 8, tid, 256);   // visible after the first barrier below
   const float *ws = w ? w + (int64_t)slice * n : nullptr;
 
   // X_F and Y pieces are taken row-major (coalesced) and stored as they are; the Y operand
@@ -419,7 +495,8 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
       const int e = tid + 256 * i, r = e / CPR, cc = e % CPR;
-      xr[i] = *reinterpret_cast<const u16x8 *>(xs + (int64_t)(t0 + r) * DH + cc * 8);
+      xr[i] = FUSE ? *reinterpret_cast<const u16x8 *>(xrs + (int64_t)(t0 + r) * vx.sn + cc * 8)
+                   : *reinterpret_cast<const u16x8 *>(xs + (int64_t)(t0 + r) * DH + cc * 8);
       yr[i] = *reinterpret_cast<const u16x8 *>(ys + (int64_t)(t0 + r) * vy.sn + cc * 8);
       inv[i] = rd ? rd[t0 + r] : 1.0f;   // divided at the stash, when the load has landed
     }
@@ -470,12 +547,39 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
       t_stash = t_begin + 64 * (s + 1);
       fetch(t_stash);
     }
+    if (FUSE) {
+      // X_F^T quarter: columns 32 (wave % 2) .. + 31 of the tile, rows 32 (wave / 2) .. + 31.
+      const bf16_t *raw = reinterpret_cast<const bf16_t *>(&xt[buf][0]);
+      // rows 32 (wave / 2) + l32 of G (high and low part) are the B operands
+      f32x16 q = zero16(), q2 = zero16();
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const bf16x8 xa = tile_cols_operand<false>(raw, XS, 32 * (wave & 1), ks, lane);
+        q = mfma_bf16(xa, filter_operand(gt, 0, 32 * (wave >> 1) + l32, 2 * ks + h), q);
+        // the low part matters inside the quarter's own 32-row half only (wave-uniform branch)
+        if ((ks >> 1) == (wave >> 1))
+          q2 = mfma_bf16(xa, filter_operand(gt, 1, 32 * (wave >> 1) + l32, 2 * ks + h), q2);
+      }
+#pragma unroll
+      for (int i = 0; i < 16; ++i) q[i] += q2[i];
+      // accumulator register i is column 32 (wave % 2) + acc_row(i, h), lane l32 is row 32 (wave / 2) + l32
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+        f16x4 pk;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pk[e] = (_Float16)q[4 * g + e];
+        *reinterpret_cast<f16x4 *>(&xq[(32 * (wave >> 1) + l32) * XS + 32 * (wave & 1) + 8 * g + 4 * h]) = pk;
+      }
+      __syncthreads();
+    }
+    const _Float16 *xcur = FUSE ? &xq[0] : &xt[buf][0];
 #pragma unroll
     for (int ti = 0; ti < 2; ++ti) {
       f16x8 xa[KS];   // projection A operand: rows 32 ti + l32, k = 8h + q (+16 per k-step)
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks)
-        xa[ks] = *reinterpret_cast<const f16x8 *>(&xt[buf][(32 * ti + l32) * XS + 16 * ks + 8 * h]);
+        xa[ks] = *reinterpret_cast<const f16x8 *>(&xcur[(32 * ti + l32) * XS + 16 * ks + 8 * h]);
       bf16x8 yb[2][CT], wp[2];
 #pragma unroll
       for (int a = 0; a < 2; ++a) {
@@ -602,8 +706,8 @@ __global__ __launch_bounds__(256) void reduce_contract_kernel(const float *Spart
 
 template <int DH, int MODE, int NW, int MC, bool LN>   // LN (MODE 0): LayerNorm over the columns of a row instead of the normaliser
 __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
-    const _Float16 *xf,        // X_F fp16 [slices][n][DH]
-    const bf16_t *x, View vx,  // X (Q or K), for the band inner products (MODE 1, 2)
+    const _Float16 *xf,        // X_F fp16 [slices][n][DH] (head dimension 128; with 64 it is formed here)
+    const bf16_t *x, View vx,  // X (Q or K): band inner products (MODE 1, 2); source of X_F (head dimension 64)
     const bf16_t *y, View vy,  // dO (MODE 1) or V (MODE 2)
     const float *Dsaved,       // D [slices][n] (MODE 1)
     const float *arow,         // dD [slices][n] (MODE 1)
@@ -625,13 +729,16 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
   constexpr int NT = NW * 64;
   constexpr bool IS_GRAD = (MODE == 1 || MODE == 2);
   constexpr bool IS_APPLY = (MODE == 0 || MODE == 3);
-  // The X tiles and D rows of the gradient epilogue are requested before the feature loop when
-  // the register file has room for them (head dimension 64), at the epilogue otherwise.
-  constexpr bool EARLY = (DH == 64);
   // Gradient modes run with the 512-register budget: projection and dPhi results go to VGPRs
   // where the register file has room for all their operands in VGPRs as well (head dimension 64
   // with the whole feature range staged; the other shapes keep the compiler's own allocation).
   constexpr bool VGPR_RG = IS_GRAD && NW == 4 && DH == 64 && MC == 256;
+  // Head dimension 64: stage A runs here.  Each wave keeps the raw rows of its 64-row block in
+  // LDS (one 64 x 32 panel per column tile), forms X_F^T = X^T G^T with 16 MFMAs at the top of
+  // the block and packs the result into the projection's fp16 operands; the gradient modes
+  // read X for the band inner products from the same panels, and every mode sends its output
+  // tiles through a panel once its X values are used up.
+  constexpr bool FUSE = (DH == 64);
   // Head dimension 128, gradient modes: two waves share a row group and each owns one half of
   // the output columns (the projection and dPhi are computed by both), which keeps the
   // accumulators and operands of a wave within the register file.
@@ -651,7 +758,10 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
   float *s_wave = reinterpret_cast<float *>(p); p += (size_t)NW * 64 * 4;              // [waves][64]
   constexpr int TS = 36;                // row stride (elements) of the per-wave 64 x 32 epilogue tile
   constexpr int TT = 68;                // column stride (elements) of the same tile held transposed [32][64]
-  bf16_t *s_tile = reinterpret_cast<bf16_t *>(p);                                      // [waves][64][TS]
+  bf16_t *s_tile = reinterpret_cast<bf16_t *>(p);            // [waves][64][TS]; FUSE: [waves][CT][64][TS]
+  constexpr int PANELS = FUSE ? CT : 1;
+  p += (size_t)NW * PANELS * 64 * TS * 2;
+  bf16_t *s_T = reinterpret_cast<bf16_t *>(p);               // FUSE: filter operand table [2][512]
 
   const int slice = blockIdx.y;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
@@ -731,25 +841,34 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
     for (int l = 0; l < kMaxBands; ++l) cf[l] = coef[slice * 8 + l];
   }
 
-  if (nchunks == 1) {
-    stage(0);
-    __syncthreads();
-  }
+  if (FUSE) build_filter_table(s_T, coef + slice * 8, tid, NT);
+  if (nchunks == 1) stage(0);
+  if (FUSE || nchunks == 1) __syncthreads();
 
   // ---- per-wave row-side operands; the next row group's are fetched right after the feature
   // loop of the current one (their registers are free by then), so that the latency of these
   // loads hides behind the epilogue.
   f16x8 xb[2][KS];      // X_F rows: B operand of the transposed projection
+  bf16x4 xp[FUSE ? CT : 1][8];   // FUSE: raw X rows of the next block, 8-byte row-major pieces (rows lane / 8 + 8 j)
   bf16x8 yb[2][KSX];    // dO or V rows (+ the a_t extension): B operand of the dPhi MFMA
   float dval[2] = {1.f, 1.f};   // D of rows 32 ti + l32 (MODE 1)
   float aval[2] = {1.f, 1.f};   // dD of the same rows (MODE 1)
   auto load_rows = [&](int t0) {
-    const _Float16 *xs = xf + ((int64_t)slice * n + t0) * DH;
+    if (FUSE) {
+      const bf16_t *xsrc = x + vx.slice_base(slice) + (int64_t)t0 * vx.sn;
 #pragma unroll
-    for (int ti = 0; ti < 2; ++ti)
+      for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
-        xb[ti][ks] = *reinterpret_cast<const f16x8 *>(xs + (int64_t)(32 * ti + l32) * DH + 16 * ks + 8 * h);
+        for (int j = 0; j < 8; ++j)
+          xp[ct][j] = *reinterpret_cast<const bf16x4 *>(xsrc + (int64_t)((lane >> 3) + 8 * j) * vx.sn + 32 * ct + (lane & 7) * 4);
+    } else {
+      const _Float16 *xs = xf + ((int64_t)slice * n + t0) * DH;
+#pragma unroll
+      for (int ti = 0; ti < 2; ++ti)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+          xb[ti][ks] = *reinterpret_cast<const f16x8 *>(xs + (int64_t)(32 * ti + l32) * DH + 16 * ks + 8 * h);
+    }
     if (IS_GRAD) {
       // MODE 1 works with the raw dO rows: G' = D_t * G (the extension carries dD_t * D_t), and
       // row t of dX_F is scaled by c / D_t at the end; MODE 2 scales by c.
@@ -778,9 +897,26 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
       }
     }
   };
+  // FUSE: the raw rows go from the registers into the wave's panels as soon as the panels are
+  // free (end of the epilogue), so that they do not occupy registers during the feature loop.
+  bf16_t *panels = s_tile + wave * (PANELS * 64 * TS);
+  auto put_rows = [&]() {
+    if (FUSE) {
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          *reinterpret_cast<bf16x4 *>(&panels[ct * (64 * TS) + ((lane >> 3) + 8 * j) * TS + (lane & 7) * 4]) = xp[ct][j];
+      __builtin_amdgcn_wave_barrier();
+    }
+  };
   {
     const int t_first = (blockIdx.x * NWR + rwave) * 64;
-    if (blockIdx.x < row_groups && t_first < n) load_rows(t_first);
+    if (blockIdx.x < row_groups && t_first < n) {
+      load_rows(t_first);
+      put_rows();
+    }
   }
   // With two waves per SIMD, start the second one about an epilogue later, so that one wave's
   // epilogue (no matrix work) runs under the other's feature loop instead of both idling the pipe.
@@ -792,16 +928,47 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
     const int t0 = (rg * NWR + rwave) * 64;
     const bool active = t0 < n;
 
-    bf16x4 xpiece[EARLY ? CTW : 1][8];   // X tiles of the band inner products (MODE 1, 2), 8-byte row-major pieces
+    bf16x4 xpiece[8];   // X tile of the band inner products (MODE 1, 2, head dimension 128), 8-byte row-major pieces
     auto load_xpiece = [&](int ct, bf16x4 *dst) {
       const bf16_t *xsrc = x + vx.slice_base(slice) + (int64_t)t0 * vx.sn;
 #pragma unroll
       for (int j = 0; j < 8; ++j)
         dst[j] = *reinterpret_cast<const bf16x4 *>(xsrc + (int64_t)((lane >> 3) + 8 * j) * vx.sn + 32 * (cbase + ct) + (lane & 7) * 4);
     };
-    if (IS_GRAD && EARLY && active) {   // issued before the feature loop: their latency hides behind it
+    if (FUSE && active) {
+      // X_F^T = X^T G^T per (column tile, row tile) from the raw rows in the panels (written at
+      // the end of the previous block's epilogue), then the projection's fp16 operands.
+      __builtin_amdgcn_wave_barrier();
+      f32x16 q[CT][2];
 #pragma unroll
-      for (int ct = 0; ct < CTW; ++ct) load_xpiece(ct, xpiece[ct]);
+      for (int ct = 0; ct < CT; ++ct) q[ct][0] = q[ct][1] = zero16();
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        bf16x8 gop[2][2];
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+          gop[tt][0] = filter_operand(s_T, 0, 32 * tt + l32, 2 * ks + h);
+          gop[tt][1] = filter_operand(s_T, 1, 32 * tt + l32, 2 * ks + h);
+        }
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+          const bf16x8 xa = tile_cols_operand<true>(panels + ct * (64 * TS), TS, 0, ks, lane);
+          // The low part matters inside the row tile's own 32-row half only: across the halves
+          // every entry of G is the single coarsest-level coefficient.
+#pragma unroll
+          for (int tt = 0; tt < 2; ++tt) {
+            q[ct][tt] = mfma_bf16(xa, gop[tt][0], q[ct][tt]);
+            if ((ks >> 1) == tt) q[ct][tt] = mfma_bf16(xa, gop[tt][1], q[ct][tt]);
+          }
+        }
+      }
+#pragma unroll
+      for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+          xb[tt][2 * ct] = pack_half_f16(q[ct][tt], 0);
+          xb[tt][2 * ct + 1] = pack_half_f16(q[ct][tt], 1);
+        }
     }
     if (active) finish_rows();
     if (MODE == 1 && active) {   // row scales c / D_t for the epilogue, before the next rows' D replace them
@@ -915,7 +1082,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
       const int t_next = ((rg + gridDim.x) * NWR + rwave) * 64;
       load_rows((rg + gridDim.x < row_groups && t_next < n) ? t_next : t0);
     }
-    bf16_t *tl = s_tile + wave * (64 * TS);
+    bf16_t *tl = panels;   // FUSE, gradient modes: moves to the panel of the column tile in hand
     // Gradient modes: output tiles leave through the wave's LDS tile held transposed ([column][row]): a lane
     // stores its four consecutive accumulator rows as one 8-byte write, and transposing reads
     // hand back 8-byte row-major pieces (read u: rows 16 (u % 4) + lane % 16, columns
@@ -1022,6 +1189,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
         for (int j = 0; j < 8; ++j)
           *reinterpret_cast<bf16x4 *>(os + (int64_t)(prow + 8 * j) * vo.sn + 32 * ct + pcol) = piece[j];
       }
+      put_rows();
       continue;
     }
 
@@ -1033,13 +1201,17 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
     // that global memory sees 8-byte row-major accesses and the column accesses stay in LDS.
 #pragma unroll
     for (int ct = 0; ct < CTW; ++ct) {
-      // ---- X tile -> LDS
-      if (!EARLY) load_xpiece(ct, xpiece[0]);
-      __builtin_amdgcn_wave_barrier();
+      // ---- X tile -> LDS (FUSE: it is there already, in this column tile's panel)
+      if (FUSE) {
+        tl = panels + ct * (64 * TS);
+      } else {
+        load_xpiece(ct, xpiece);
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
-      for (int j = 0; j < 8; ++j)
-        *reinterpret_cast<bf16x4 *>(&tl[(prow + 8 * j) * TS + pcol]) = xpiece[EARLY ? ct : 0][j];
-      __builtin_amdgcn_wave_barrier();
+        for (int j = 0; j < 8; ++j)
+          *reinterpret_cast<bf16x4 *>(&tl[(prow + 8 * j) * TS + pcol]) = xpiece[j];
+        __builtin_amdgcn_wave_barrier();
+      }
       // ---- pass 1: block sums of g and x, band inner products, keep the 32-row sums
       float g5[2], x5[2];
 #pragma unroll
@@ -1116,6 +1288,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
       // ---- LDS -> dX
       tile_store(os, vo.sn, 32 * (cbase + ct));
     }
+    put_rows();
   }
   if (IS_APPLY) return;
 
@@ -1323,7 +1496,8 @@ size_t rows_smem_bytes(int mc) {
   else s += (size_t)DH * BS * 2;
   if (MODE == 0) s += (size_t)mc * 2;
   s += NW * 64 * 4;
-  s += (size_t)NW * 64 * 36 * 2;
+  if (DH == 64) s += (size_t)NW * (DH / 32) * 64 * 36 * 2 + 2 * 512 * 2;   // X panels per wave and the filter table
+  else s += (size_t)NW * 64 * 36 * 2;
   return s;
 }
 
@@ -1365,8 +1539,8 @@ hipError_t launch_rows(const wersa_desc &c, const FastPlan &p, const _Float16 *x
 // orows != nullptr selects the backward form that derives dD from the rows of O itself;
 // otherwise the row weights of the vector part are `wts` (all ones when nullptr).
 template <int DH>
-void launch_contract(const wersa_desc &c, const FastPlan &p, const _Float16 *xf, const bf16_t *y,
-                     const View &yv, const float *rowdiv, const float *wts, const bf16_t *orows,
+void launch_contract(const wersa_desc &c, const FastPlan &p, const _Float16 *xf, const bf16_t *xraw,
+                     const bf16_t *y, const View &yv, const float *rowdiv, const float *wts, const bf16_t *orows,
                      bool key_side, const FastWs &w, float *S, float *z, bf16_t *Mx, bf16_t *MT,
                      bf16_t *bb, hipStream_t st) {
   const int slices = c.B * c.H;
@@ -1374,8 +1548,9 @@ void launch_contract(const wersa_desc &c, const FastPlan &p, const _Float16 *xf,
   const _Float16 *omT = w.omT + (((c.flags & WERSA_FLAG_SEPARATE_OMEGA) && key_side) ? (int64_t)c.d * c.m : 0);
   auto go = [&](auto kern) {
     WERSA_STAGE("wersa_phiT_contract", st,
-                kern<<<grid, 256, 0, st>>>(xf, y, yv, rowdiv, wts, orows, w.dD, w.dDpart, omT, c.n, c.m,
-                                           p.rowsC, w.Spart, w.zpart));
+                kern<<<grid, 256, 0, st>>>(xf, xraw, View{c.stride_b, c.stride_h, c.stride_n, c.H}, w.coef, y, yv,
+                                           rowdiv, wts, orows, w.dD, w.dDpart, omT, c.n, c.m, p.rowsC, w.Spart,
+                                           w.zpart));
   };
   if (p.FW == 64) {
     if (orows) go(&phiT_contract_kernel<DH, 64, true>);
@@ -1402,8 +1577,8 @@ wersa_status fast_forward_t(const wersa_desc &c, const bf16_t *q, const bf16_t *
   const View tv{c.stride_b, c.stride_h, c.stride_n, c.H};
   float *S = saved + sv.S, *z = saved + sv.z, *qbar = saved + sv.qbar, *s = saved + sv.s,
         *F = saved + sv.F, *D = saved + sv.D;
-  _Float16 *QF = reinterpret_cast<_Float16 *>(saved + sv.QF);
-  _Float16 *KF = reinterpret_cast<_Float16 *>(saved + sv.KF);
+  _Float16 *QF = sv.QF >= 0 ? reinterpret_cast<_Float16 *>(saved + sv.QF) : nullptr;
+  _Float16 *KF = sv.KF >= 0 ? reinterpret_cast<_Float16 *>(saved + sv.KF) : nullptr;
 
   const int nmat = (c.flags & WERSA_FLAG_SEPARATE_OMEGA) ? 2 : 1;
   WERSA_STAGE("wersa_setup", st,
@@ -1414,12 +1589,14 @@ wersa_status fast_forward_t(const wersa_desc &c, const bf16_t *q, const bf16_t *
   WERSA_STAGE("gate_fwd_kernel", st,
               gate_fwd_kernel<<<slices, 256, 0, st>>>(w.qpart, p.chunksQ, c.n, c.d, c.L, c.H, gate_w, gate_b,
                                                      scale_w, qbar, s, F, w.coef, (c.flags & WERSA_FLAG_POOLED_GATE) ? 1 : 0));
-  WERSA_STAGE("wersa_haar_stage", st,
-              haar_stage_kernel<DH><<<dim3(c.n / 64, slices), 256, 0, st>>>(q, tv, c.n, w.coef, QF));
-  WERSA_STAGE("wersa_haar_stage", st,
-              haar_stage_kernel<DH><<<dim3(c.n / 64, slices), 256, 0, st>>>(k, tv, c.n, w.coef, KF));
-  launch_contract<DH>(c, p, KF, v, tv, nullptr, nullptr, nullptr, true, w, S, z, w.Sx, w.ST, w.zb, st);
-  if (launch_rows<DH, 0>(c, p, QF, nullptr, nullptr, nullptr, nullptr, w, omega, nullptr, w.ST, w.zb, out, D,
+  if (DH != 64) {   // head dimension 64 runs stage A inside the kernels that consume X_F
+    WERSA_STAGE("wersa_haar_stage", st,
+                haar_stage_kernel<DH><<<dim3(c.n / 64, slices), 256, 0, st>>>(q, tv, c.n, w.coef, QF));
+    WERSA_STAGE("wersa_haar_stage", st,
+                haar_stage_kernel<DH><<<dim3(c.n / 64, slices), 256, 0, st>>>(k, tv, c.n, w.coef, KF));
+  }
+  launch_contract<DH>(c, p, KF, k, v, tv, nullptr, nullptr, nullptr, true, w, S, z, w.Sx, w.ST, w.zb, st);
+  if (launch_rows<DH, 0>(c, p, QF, q, nullptr, nullptr, nullptr, w, omega, nullptr, w.ST, w.zb, out, D,
                          nullptr, st) != hipSuccess)
     return WERSA_ERR_LAUNCH;
   return hipGetLastError() == hipSuccess ? WERSA_OK : WERSA_ERR_LAUNCH;
@@ -1439,8 +1616,8 @@ wersa_status fast_backward_t(const wersa_desc &c, const bf16_t *q, const bf16_t 
   const View tv{c.stride_b, c.stride_h, c.stride_n, c.H};
   const float *z = saved + sv.z, *qbar = saved + sv.qbar, *s = saved + sv.s, *F = saved + sv.F,
               *D = saved + sv.D;
-  const _Float16 *QF = reinterpret_cast<const _Float16 *>(saved + sv.QF);
-  const _Float16 *KF = reinterpret_cast<const _Float16 *>(saved + sv.KF);
+  const _Float16 *QF = sv.QF >= 0 ? reinterpret_cast<const _Float16 *>(saved + sv.QF) : nullptr;
+  const _Float16 *KF = sv.KF >= 0 ? reinterpret_cast<const _Float16 *>(saved + sv.KF) : nullptr;
 
   // dS = Phi_Q^T dN, dz = Phi_Q^T dD; the same pass derives dD_t = -<dO_t, O_t> / D_t from the
   // rows of O and leaves it in the workspace for the Q-side gradient kernel.
@@ -1450,12 +1627,12 @@ wersa_status fast_backward_t(const wersa_desc &c, const bf16_t *q, const bf16_t 
     WERSA_STAGE("wersa_ln_prep", st,
                 ln_prep_kernel<DH><<<dim3(p.chunksC, slices), 256, 0, st>>>(dout, out, tv, D, c.n, p.rowsC, w.dN,
                                                                            w.ones, w.dD, w.dDpart));
-    launch_contract<DH>(c, p, QF, w.dN, nv, nullptr, w.dD, nullptr, false, w, w.dS, w.dz, w.dSx, w.dST, w.dzb, st);
+    launch_contract<DH>(c, p, QF, q, w.dN, nv, nullptr, w.dD, nullptr, false, w, w.dS, w.dz, w.dSx, w.dST, w.dzb, st);
     if (launch_rows<DH, 1>(c, p, QF, q, w.dN, w.ones, w.dD, w, omega, w.Sx, nullptr, nullptr, dq, nullptr,
                            w.partQ, st, &nv) != hipSuccess)
       return WERSA_ERR_LAUNCH;
   } else {
-    launch_contract<DH>(c, p, QF, dout, tv, D, nullptr, out, false, w, w.dS, w.dz, w.dSx, w.dST, w.dzb, st);
+    launch_contract<DH>(c, p, QF, q, dout, tv, D, nullptr, out, false, w, w.dS, w.dz, w.dSx, w.dST, w.dzb, st);
     if (launch_rows<DH, 1>(c, p, QF, q, dout, D, w.dD, w, omega, w.Sx, nullptr, nullptr, dq, nullptr,
                            w.partQ, st) != hipSuccess)
       return WERSA_ERR_LAUNCH;
@@ -1463,7 +1640,7 @@ wersa_status fast_backward_t(const wersa_desc &c, const bf16_t *q, const bf16_t 
   if (launch_rows<DH, 2>(c, p, KF, k, v, nullptr, nullptr, w, omega, w.dSx, nullptr, nullptr, dk, nullptr,
                          w.partK, st) != hipSuccess)
     return WERSA_ERR_LAUNCH;
-  if (launch_rows<DH, 3>(c, p, KF, nullptr, nullptr, nullptr, nullptr, w, omega, nullptr, w.dST, nullptr, dv,
+  if (launch_rows<DH, 3>(c, p, KF, k, nullptr, nullptr, nullptr, w, omega, nullptr, w.dST, nullptr, dv,
                          nullptr, nullptr, st) != hipSuccess)
     return WERSA_ERR_LAUNCH;
   WERSA_STAGE("gate_bwd_slice_kernel", st,

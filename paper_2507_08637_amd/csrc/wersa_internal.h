@@ -64,9 +64,11 @@ inline SavedLayout saved_layout(const wersa_desc &c) {
   o.F = off;    off += up(sl * (c.L + 1));
   o.D = off;    off += up(sl * c.n);
   o.QF = o.KF = o.scalars = o.coef = o.omT = o.Sx = o.ST = o.zb = -1;
-  if (use_fast(c)) {  // filtered Q and K in fp16, kept for the backward
-    o.QF = off; off += up(sl * c.n * c.d / 2);
-    o.KF = off; off += up(sl * c.n * c.d / 2);
+  if (use_fast(c)) {
+    if (c.d != 64) {  // filtered Q and K in fp16, kept for the backward (head dimension 64 re-forms them from Q, K)
+      o.QF = off; off += up(sl * c.n * c.d / 2);
+      o.KF = off; off += up(sl * c.n * c.d / 2);
+    }
     const int64_t md = (int64_t)c.m * c.d, mx = (int64_t)c.m * (c.d + 16);
     o.scalars = off; off += 64;
     o.coef = off;    off += up(sl * 8);
