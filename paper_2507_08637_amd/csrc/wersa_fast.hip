@@ -849,18 +849,19 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
   // loop of the current one (their registers are free by then), so that the latency of these
   // loads hides behind the epilogue.
   f16x8 xb[2][KS];      // X_F rows: B operand of the transposed projection
-  bf16x4 xp[FUSE ? CT : 1][8];   // FUSE: raw X rows of the next block, 8-byte row-major pieces (rows lane / 8 + 8 j)
+  u16x8 xp[8];          // FUSE: raw X rows of the next block, 16-byte row-major pieces (row lane / 8 + 8 j, columns 8 (lane % 8) ..)
   bf16x8 yb[2][KSX];    // dO or V rows (+ the a_t extension): B operand of the dPhi MFMA
   float dval[2] = {1.f, 1.f};   // D of rows 32 ti + l32 (MODE 1)
   float aval[2] = {1.f, 1.f};   // dD of the same rows (MODE 1)
   auto load_rows = [&](int t0) {
     if (FUSE) {
-      const bf16_t *xsrc = x + vx.slice_base(slice) + (int64_t)t0 * vx.sn;
+      // one running pointer (eight separately scaled row offsets would each be kept in registers)
+      const bf16_t *xsrc = x + vx.slice_base(slice) + (int64_t)(t0 + (lane >> 3)) * vx.sn + (lane & 7) * 8;
 #pragma unroll
-      for (int ct = 0; ct < CT; ++ct)
-#pragma unroll
-        for (int j = 0; j < 8; ++j)
-          xp[ct][j] = *reinterpret_cast<const bf16x4 *>(xsrc + (int64_t)((lane >> 3) + 8 * j) * vx.sn + 32 * ct + (lane & 7) * 4);
+      for (int j = 0; j < 8; ++j) {
+        xp[j] = *reinterpret_cast<const u16x8 *>(xsrc);
+        xsrc += 8 * vx.sn;
+      }
     } else {
       const _Float16 *xs = xf + ((int64_t)slice * n + t0) * DH;
 #pragma unroll
@@ -903,11 +904,21 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
   auto put_rows = [&]() {
     if (FUSE) {
       __builtin_amdgcn_wave_barrier();
+      // a 16-byte piece lies inside one panel (columns 8 (lane % 8) .. + 7); two 8-byte writes
+      // because odd panel rows are only 8-byte aligned
+      bf16_t *dstp = panels + ((lane & 7) >> 2) * (64 * TS) + (lane >> 3) * TS + ((lane & 3) << 3);
 #pragma unroll
-      for (int ct = 0; ct < CT; ++ct)
+      for (int j = 0; j < 8; ++j) {
+        typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
+        u16x4 lo4, hi4;
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-          *reinterpret_cast<bf16x4 *>(&panels[ct * (64 * TS) + ((lane >> 3) + 8 * j) * TS + (lane & 7) * 4]) = xp[ct][j];
+        for (int q = 0; q < 4; ++q) {
+          lo4[q] = xp[j][q];
+          hi4[q] = xp[j][4 + q];
+        }
+        *reinterpret_cast<u16x4 *>(dstp + 8 * j * TS) = lo4;
+        *reinterpret_cast<u16x4 *>(dstp + 8 * j * TS + 4) = hi4;
+      }
       __builtin_amdgcn_wave_barrier();
     }
   };
@@ -939,36 +950,42 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
       // X_F^T = X^T G^T per (column tile, row tile) from the raw rows in the panels (written at
       // the end of the previous block's epilogue), then the projection's fp16 operands.
       __builtin_amdgcn_wave_barrier();
-      f32x16 q[CT][2];
+      // (apply modes: one column tile at a time, their 256-register budget has no room for four
+      // accumulators next to the operands being built)
+      constexpr int CG = IS_APPLY ? 1 : CT;   // column tiles per pass
 #pragma unroll
-      for (int ct = 0; ct < CT; ++ct) q[ct][0] = q[ct][1] = zero16();
+      for (int c0 = 0; c0 < CT; c0 += CG) {
+        f32x16 q[CG][2];
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        bf16x8 gop[2][2];
+        for (int cg = 0; cg < CG; ++cg) q[cg][0] = q[cg][1] = zero16();
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-          gop[tt][0] = filter_operand(s_T, 0, 32 * tt + l32, 2 * ks + h);
-          gop[tt][1] = filter_operand(s_T, 1, 32 * tt + l32, 2 * ks + h);
-        }
-#pragma unroll
-        for (int ct = 0; ct < CT; ++ct) {
-          const bf16x8 xa = tile_cols_operand<true>(panels + ct * (64 * TS), TS, 0, ks, lane);
-          // The low part matters inside the row tile's own 32-row half only: across the halves
-          // every entry of G is the single coarsest-level coefficient.
+        for (int ks = 0; ks < 4; ++ks) {
+          bf16x8 gop[2][2];
 #pragma unroll
           for (int tt = 0; tt < 2; ++tt) {
-            q[ct][tt] = mfma_bf16(xa, gop[tt][0], q[ct][tt]);
-            if ((ks >> 1) == tt) q[ct][tt] = mfma_bf16(xa, gop[tt][1], q[ct][tt]);
+            gop[tt][0] = filter_operand(s_T, 0, 32 * tt + l32, 2 * ks + h);
+            gop[tt][1] = filter_operand(s_T, 1, 32 * tt + l32, 2 * ks + h);
+          }
+#pragma unroll
+          for (int cg = 0; cg < CG; ++cg) {
+            const bf16x8 xa = tile_cols_operand<true>(panels + (c0 + cg) * (64 * TS), TS, 0, ks, lane);
+            // The low part matters inside the row tile's own 32-row half only: across the halves
+            // every entry of G is the single coarsest-level coefficient.
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt) {
+              q[cg][tt] = mfma_bf16(xa, gop[tt][0], q[cg][tt]);
+              if ((ks >> 1) == tt) q[cg][tt] = mfma_bf16(xa, gop[tt][1], q[cg][tt]);
+            }
           }
         }
+#pragma unroll
+        for (int cg = 0; cg < CG; ++cg)
+#pragma unroll
+          for (int tt = 0; tt < 2; ++tt) {
+            xb[tt][2 * (c0 + cg)] = pack_half_f16(q[cg][tt], 0);
+            xb[tt][2 * (c0 + cg) + 1] = pack_half_f16(q[cg][tt], 1);
+          }
       }
-#pragma unroll
-      for (int ct = 0; ct < CT; ++ct)
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-          xb[tt][2 * ct] = pack_half_f16(q[ct][tt], 0);
-          xb[tt][2 * ct + 1] = pack_half_f16(q[ct][tt], 1);
-        }
     }
     if (active) finish_rows();
     if (MODE == 1 && active) {   // row scales c / D_t for the epilogue, before the next rows' D replace them
@@ -1185,9 +1202,12 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
 #pragma unroll
         for (int j = 0; j < 8; ++j)
           piece[j] = *reinterpret_cast<const bf16x4 *>(&tl[(prow + 8 * j) * TS + pcol]);
+        bf16_t *orow = os + (int64_t)prow * vo.sn + 32 * ct + pcol;
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-          *reinterpret_cast<bf16x4 *>(os + (int64_t)(prow + 8 * j) * vo.sn + 32 * ct + pcol) = piece[j];
+        for (int j = 0; j < 8; ++j) {
+          *reinterpret_cast<bf16x4 *>(orow) = piece[j];
+          orow += 8 * vo.sn;
+        }
       }
       put_rows();
       continue;
