@@ -26,10 +26,10 @@ PEAK = {"hbm": (8000.0, "GB/s"), "mfma_bf16": (2500.0, "TFLOP/s"), "fp32": (157.
 MIB = 1024.0 * 1024.0
 SURVEY_STEPS = 5   # untimed steps with every launch bracketed, to rank the kernels
 MEASURED_TRAFFIC_CONFIG4 = {
-    "wersa_rows_fwd": (130.4 + 133.2) * MIB, "wersa_rows_bwd_q": (425.1 + 133.4) * MIB,
-    "wersa_rows_bwd_k": (387.3 + 131.4) * MIB, "wersa_rows_bwd_v": (130.4 + 132.4) * MIB,
+    "wersa_rows_fwd": (137.1 + 134.6) * MIB, "wersa_rows_bwd_q": (270.8 + 131.0) * MIB,
+    "wersa_rows_bwd_k": (275.3 + 132.9) * MIB, "wersa_rows_bwd_v": (138.2 + 131.1) * MIB,
     "wersa_phiT_contract": ((256.4 + 32.5) + (388.4 + 36.5)) / 2 * MIB,   # average of the two launches
-    "wersa_haar_stage": (128.0 + 128.0) * MIB, "wersa_qbar": 128.3 * MIB, "wersa_add_pooled": 256.1 * MIB,
+    "wersa_qbar": 128.3 * MIB, "wersa_add_pooled": 256.1 * MIB,
 }
 
 
@@ -52,13 +52,13 @@ def kernel_models(cfg):
         "colsum_partial_kernel": ("hbm", "hbm", nd * e),
         # fused MFMA path
         "wersa_qbar": ("hbm", "hbm", nd * e),
-        "wersa_haar_stage": ("hbm", "hbm", nd * (e + 2)),       # one tensor in (bf16), one out (fp16)
+        "wersa_haar_stage": ("hbm", "hbm", nd * (e + 2)),       # head dimension 128: one tensor in (bf16), one out (fp16)
         "wersa_phiT_contract": ("mfma", "mfma_bf16", 2 * unit),  # projection + Phi^T Y
         "wersa_rows_fwd": ("mfma", "mfma_bf16", 2 * unit),       # projection + Phi S
         "wersa_rows_bwd_q": ("mfma", "mfma_bf16", 3 * unit),     # projection, dPhi, dX_F
         "wersa_rows_bwd_k": ("mfma", "mfma_bf16", 3 * unit),     # projection, dPhi, dX_F
         "wersa_rows_bwd_v": ("mfma", "mfma_bf16", 2 * unit),     # projection, Phi dS
-        "wersa_prep_bwd": ("hbm", "hbm", 2 * nd * e),
+        "wersa_ln_prep": ("hbm", "hbm", 3 * nd * e),
         "wersa_add_pooled": ("hbm", "hbm", 2 * nd * e),
     }
     # attention block (configuration 5): hidden x hidden projections over all tokens.  Average
