@@ -941,10 +941,12 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
 
     bf16x4 xpiece[8];   // X tile of the band inner products (MODE 1, 2, head dimension 128), 8-byte row-major pieces
     auto load_xpiece = [&](int ct, bf16x4 *dst) {
-      const bf16_t *xsrc = x + vx.slice_base(slice) + (int64_t)t0 * vx.sn;
+      const bf16_t *xsrc = x + vx.slice_base(slice) + (int64_t)(t0 + (lane >> 3)) * vx.sn + 32 * (cbase + ct) + (lane & 7) * 4;
 #pragma unroll
-      for (int j = 0; j < 8; ++j)
-        dst[j] = *reinterpret_cast<const bf16x4 *>(xsrc + (int64_t)((lane >> 3) + 8 * j) * vx.sn + 32 * (cbase + ct) + (lane & 7) * 4);
+      for (int j = 0; j < 8; ++j) {   // one running pointer instead of eight scaled row offsets
+        dst[j] = *reinterpret_cast<const bf16x4 *>(xsrc);
+        xsrc += 8 * vx.sn;
+      }
     };
     if (FUSE && active) {
       // X_F^T = X^T G^T per (column tile, row tile) from the raw rows in the panels (written at
@@ -1119,9 +1121,13 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
 #pragma unroll
       for (int u = 0; u < 8; ++u)
         piece[u] = lds_read_tr4(&tl[(16 * (u >> 2) + 4 * g16 + (i16 >> 2)) * TT + 16 * (u & 3) + 4 * (i16 & 3)]);
+      bf16_t *drow = dst + (int64_t)i16 * sn + col0 + 4 * g16;
 #pragma unroll
-      for (int u = 0; u < 8; ++u)
-        *reinterpret_cast<bf16x4 *>(dst + (int64_t)(16 * (u & 3) + i16) * sn + col0 + 16 * (u >> 2) + 4 * g16) = piece[u];
+      for (int u = 0; u < 4; ++u) {   // one running pointer instead of four scaled row offsets
+        *reinterpret_cast<bf16x4 *>(drow) = piece[u];
+        *reinterpret_cast<bf16x4 *>(drow + 16) = piece[u + 4];
+        drow += 16 * sn;
+      }
     };
     const int prow = lane >> 3, pcol = (lane & 7) * 4;   // this lane's 8-byte piece: rows prow + 8 j
     bf16_t *os = out0 + vo.slice_base(slice) + (int64_t)t0 * vo.sn;
