@@ -59,7 +59,7 @@ typedef enum { WERSA_F32 = 0, WERSA_BF16 = 1 } wersa_dtype;
 
 /* desc.flags bits. By default the library picks the MFMA path (bf16 storage, fp16/bf16 matrix
  * cores, float32 accumulation) when the shape allows it: dtype bf16, d in {64, 128},
- * n % 64 == 0, m % 128 == 0, strides multiples of 8 elements; otherwise the generic
+ * n % 64 == 0, m % 128 == 0, L <= 6, strides multiples of 8 elements; otherwise the generic
  * float32-arithmetic path. WERSA_FLAG_GENERIC_PATH forces the generic path. */
 #define WERSA_FLAG_GENERIC_PATH 1
 /* Separate random matrices for the query and the key side (Algorithm 1 draws W_Q^rand and
@@ -79,12 +79,13 @@ typedef enum { WERSA_F32 = 0, WERSA_BF16 = 1 } wersa_dtype;
 
 /*
  * Problem descriptor (host memory, read during the call only).
- * Supported range: B, H, n >= 1; 0 <= L <= 6; d % 16 == 0, 16 <= d <= 256; m % 16 == 0,
+ * Supported range: B, H, n >= 1; 0 <= L <= 20; d % 16 == 0, 16 <= d <= 256; m % 16 == 0,
  * 16 <= m <= 4096. Anything else that is otherwise well formed returns WERSA_ERR_UNSUPPORTED.
  * Any n is accepted: the Haar filter is local to aligned blocks of 2^L rows, so Algorithm 2's
  * zero padding to the next power of two and the trim after the inverse are the same as reading
  * the rows past n of the last block as zeros and not writing them (done in-kernel; the pooled
- * query averages the n real rows).
+ * query averages the n real rows). L > 6 (blocks longer than one 64-row tile) runs on the
+ * generic path: six levels inside the tiles, the rest on the tiles' approximation coefficients.
  */
 typedef struct {
   int32_t B, H, n, d, L, m;
@@ -122,6 +123,7 @@ wersa_status wersa_backward(const wersa_desc *desc, const void *q, const void *k
  * Stage entry point: the gated Haar filter alone, X_F = W^-1(F (.) W X) (Section 3.1 steps
  * 3, 5, 6; Appendix A equations) for one tensor x laid out like q, with per-slice filter
  * coefficients filt [B*H][L+1] (float32, device). Output xf has the same layout and dtype.
+ * It takes no workspace and covers L <= 6; a deeper transform returns WERSA_ERR_UNSUPPORTED here.
  */
 wersa_status wersa_haar_filter(const wersa_desc *desc, const void *x, const float *filt,
                                void *xf, void *hip_stream);

@@ -832,13 +832,13 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
       for (int e = tid; e < MC; e += NT) s_bb[e] = bb[(int64_t)slice * m + m0 + e];
   };
 
-  float u[kMaxBands];   // u_l = sum over blocks of bs_l(g) * bs_l(x), this lane's share
+  float u[kTileBands];   // u_l = sum over blocks of bs_l(g) * bs_l(x), this lane's share
 #pragma unroll
-  for (int l = 0; l < kMaxBands; ++l) u[l] = 0.f;
-  float cf[kMaxBands];
+  for (int l = 0; l < kTileBands; ++l) u[l] = 0.f;
+  float cf[kTileBands];
   if (IS_GRAD) {
 #pragma unroll
-    for (int l = 0; l < kMaxBands; ++l) cf[l] = coef[slice * 8 + l];
+    for (int l = 0; l < kTileBands; ++l) cf[l] = coef[slice * 8 + l];
   }
 
   if (FUSE) build_filter_table(s_T, coef + slice * 8, tid, NT);
@@ -1322,7 +1322,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
   // dF_L = u_L and dF_{l-1} = u_{l-1} - u_l (l = 1..L); one partial per workgroup.
   __syncthreads();   // operand arrays are no longer read; s_wave is free for the reduction
 #pragma unroll
-  for (int l = 0; l < kMaxBands; ++l) {
+  for (int l = 0; l < kTileBands; ++l) {
     const float s = wave_sum64(u[l]) / (float)(1 << l);
     if (lane == 0) s_wave[wave * 8 + l] = s;
   }
@@ -1686,7 +1686,7 @@ wersa_status fast_backward_t(const wersa_desc &c, const bf16_t *q, const bf16_t 
 }  // namespace
 
 bool fast_supported(const wersa_desc &c) {
-  return c.dtype == WERSA_BF16 && (c.d == 64 || c.d == 128) && c.n % 64 == 0 && c.m % 128 == 0 &&
+  return c.dtype == WERSA_BF16 && (c.d == 64 || c.d == 128) && c.n % 64 == 0 && c.m % 128 == 0 && c.L <= kTileL &&
          c.stride_n % 8 == 0 && c.stride_h % 8 == 0 && c.stride_b % 8 == 0;
 }
 

@@ -8,7 +8,7 @@ namespace {
 
 #include "wersa_small_kernels.inc"
 
-constexpr int kTileRows = 64;  // rows of one Haar tile: the largest aligned block, 2^kMaxL
+constexpr int kTileRows = 64;  // rows of one Haar tile: the largest aligned block, 2^kTileL
 constexpr int kTileCols = 64;
 
 View contiguous_view(int64_t rows, int64_t width) {
@@ -95,16 +95,33 @@ __device__ __forceinline__ int band_of_row(int r, int L) {
   return pos == 0 ? L : __builtin_ctz(pos);
 }
 
+// One level of the transform as the tile kernels see it.  Up to six analysis levels run inside a
+// 64-row tile; a deeper transform (L > 6) continues on the tiles' approximation coefficients
+// a_6, a signal of ceil(n / 64) rows that goes through the same kernels again (Algorithm 2's
+// recursion on the approximation, 64 rows = six levels at a time).
+struct HaarLevel {
+  int Lt;       // analysis levels inside the tile at this stage (6 unless it is the last stage)
+  int foff;     // index into F of this stage's finest detail band
+  int fstride;  // L + 1: entries of F per slice
+  int top;      // last stage: the tile's approximation band is a_L, gated by F[L]
+};
+
 // y = W^-1 (F (.) W x) (+ addscale * addvec[slice][j]) on 64-row x 64-column tiles.
+//   approx_out != nullptr: also write the tile's a_6 to approx_out[slice][tile][j] (Lt == 6)
+//   y == nullptr: stop after that (analysis only)
+//   approx_in != nullptr: the tile's a_6 is replaced by approx_in[slice][tile][j] (the filtered
+//   coefficient coming back from the deeper stage) before the synthesis
 template <typename TIn, typename TOut>
 __global__ void haar_filter_kernel(const TIn *x, View vin, TOut *y, View vout, const float *filt,
-                                   const float *addvec, float addscale, int n, int d, int L) {
+                                   const float *addvec, float addscale, int n, int d, HaarLevel lv,
+                                   const float *approx_in, float *approx_out) {
   __shared__ float tile[kTileRows][kTileCols];
-  __shared__ float F[kMaxBands];
-  const int slice = blockIdx.z;
+  __shared__ float F[kTileBands];
+  const int slice = blockIdx.z, L = lv.Lt;
   const int t0 = blockIdx.x * kTileRows, j = blockIdx.y * kTileCols + (threadIdx.x & 63);
   const int c = threadIdx.x & 63, g = threadIdx.x >> 6;
-  if (threadIdx.x <= L) F[threadIdx.x] = filt[slice * (L + 1) + threadIdx.x];
+  if (threadIdx.x <= L)
+    F[threadIdx.x] = (threadIdx.x < L || lv.top) ? filt[slice * lv.fstride + lv.foff + threadIdx.x] : 1.0f;
   const TIn *xs = x + vin.slice_base(slice);
   for (int r = g; r < kTileRows; r += 4) {
     const int t = t0 + r;
@@ -112,7 +129,11 @@ __global__ void haar_filter_kernel(const TIn *x, View vin, TOut *y, View vout, c
   }
   __syncthreads();
   haar_analysis_tile(tile, L, c, g);
+  const int64_t aidx = ((int64_t)slice * gridDim.x + blockIdx.x) * d + j;
+  if (approx_out && g == 0 && j < d) approx_out[aidx] = tile[0][c];
+  if (!y) return;
   for (int r = g; r < kTileRows; r += 4) tile[r][c] *= F[band_of_row(r, L)];
+  if (approx_in && g == 0 && j < d) tile[0][c] = approx_in[aidx];
   __syncthreads();
   haar_synthesis_tile(tile, L, c, g);
   TOut *ys = y + vout.slice_base(slice);
@@ -123,14 +144,19 @@ __global__ void haar_filter_kernel(const TIn *x, View vin, TOut *y, View vout, c
   }
 }
 
-// part[slice][tile][band] = sum over the tile of band_i(W x) * band_i(W g)
+// part[slice][tile][foff + band] (=, or += when accumulate) sum over the tile of
+// band_i(W x) * band_i(W g) for this stage's bands; `tiles0` is the tile count of the first
+// stage (the row stride of part).  The first stage of a deeper transform writes zeros into
+// the bands of the later stages, which then add their sums to the rows of their own tiles.
+// approx_out_x / approx_out_g: the tiles' a_6 of both operands for the next stage.
 template <typename TX>
 __global__ void band_dots_kernel(const TX *x, View vx, const float *gr, View vg, int n, int d,
-                                 int L, float *part) {
+                                 HaarLevel lv, int64_t tiles0, int accumulate, float *part,
+                                 float *approx_out_x, float *approx_out_g) {
   __shared__ float tx[kTileRows][kTileCols];
   __shared__ float tg[kTileRows][kTileCols];
-  __shared__ float red[4][kMaxBands];
-  const int slice = blockIdx.z;
+  __shared__ float red[4][kTileBands];
+  const int slice = blockIdx.z, L = lv.Lt;
   const int t0 = blockIdx.x * kTileRows, j = blockIdx.y * kTileCols + (threadIdx.x & 63);
   const int c = threadIdx.x & 63, g = threadIdx.x >> 6;
   const TX *xs = x + vx.slice_base(slice);
@@ -144,26 +170,36 @@ __global__ void band_dots_kernel(const TX *x, View vx, const float *gr, View vg,
   __syncthreads();
   haar_analysis_tile(tx, L, c, g);
   haar_analysis_tile(tg, L, c, g);
-  float acc[kMaxBands];
+  if (approx_out_x && g == 0 && j < d) {
+    const int64_t aidx = ((int64_t)slice * gridDim.x + blockIdx.x) * d + j;
+    approx_out_x[aidx] = tx[0][c];
+    approx_out_g[aidx] = tg[0][c];
+  }
+  float acc[kTileBands];
 #pragma unroll
-  for (int b = 0; b < kMaxBands; ++b) acc[b] = 0.f;
+  for (int b = 0; b < kTileBands; ++b) acc[b] = 0.f;
   for (int r = g; r < kTileRows; r += 4) {
     const int band = band_of_row(r, L);
     const float pr = tx[r][c] * tg[r][c];
 #pragma unroll
-    for (int b = 0; b < kMaxBands; ++b) acc[b] += (band == b) ? pr : 0.f;
+    for (int b = 0; b < kTileBands; ++b) acc[b] += (band == b) ? pr : 0.f;
   }
 #pragma unroll
-  for (int b = 0; b < kMaxBands; ++b) {
+  for (int b = 0; b < kTileBands; ++b) {
     const float s = wave_sum(acc[b]);
     if (c == 0) red[g][b] = s;
   }
   __syncthreads();
-  if (threadIdx.x <= L) {
-    const int64_t tile_id = (int64_t)blockIdx.x * gridDim.y + blockIdx.y;
-    const int64_t tiles = (int64_t)gridDim.x * gridDim.y;
-    part[((int64_t)slice * tiles + tile_id) * (L + 1) + threadIdx.x] =
-        (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+  const int nb = lv.top ? L + 1 : L;   // the approximation band counts at the last stage only
+  const int64_t tile_id = (int64_t)blockIdx.x * gridDim.y + blockIdx.y;
+  float *row = part + ((int64_t)slice * tiles0 + tile_id) * lv.fstride;
+  if (accumulate) {
+    if ((int)threadIdx.x < nb)
+      row[lv.foff + threadIdx.x] +=
+          (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+  } else {
+    for (int i = threadIdx.x; i < lv.fstride; i += blockDim.x)
+      row[i] = i < nb ? (red[0][i] + red[1][i]) + (red[2][i] + red[3][i]) : 0.f;
   }
 }
 
@@ -387,9 +423,41 @@ int ew_blocks(int64_t total) {
   return (int)(b > 65536 ? 65536 : (b < 1 ? 1 : b));
 }
 
+// Stages of the transform: stage 0 works on the n rows of the tensor, stage k + 1 on the
+// ceil(n_k / 64) tile approximations of stage k; six levels per stage, the rest in the last.
+constexpr int kMaxStages = 4;   // 6 + 6 + 6 + 2 levels cover kMaxL = 20
+struct Stages {
+  int count;
+  int n[kMaxStages];
+  HaarLevel lv[kMaxStages];
+  int64_t off[kMaxStages];   // float offset of stage k's approximation array (k >= 1) in a deep buffer
+  int64_t total;             // floats of one deep buffer
+};
+Stages stages_of(const wersa_desc &c) {
+  Stages s{};
+  const int64_t sl = (int64_t)c.B * c.H;
+  int rem = c.L, rows = c.n, foff = 0, k = 0;
+  int64_t off = 0;
+  for (;; ++k) {
+    s.n[k] = rows;
+    const bool last = rem <= kTileL;
+    s.lv[k] = HaarLevel{last ? rem : kTileL, foff, c.L + 1, last ? 1 : 0};
+    if (last) break;
+    rem -= kTileL;
+    foff += kTileL;
+    rows = (rows + kTileRows - 1) / kTileRows;
+    s.off[k + 1] = off;
+    off += sl * rows * c.d;
+  }
+  s.count = k + 1;
+  s.total = off;
+  return s;
+}
+
 struct GenericWs {
   float *scalars, *qpart, *QF, *KF, *Vf, *Of, *Phi, *R, *Spart, *zpart, *Nbuf;
   float *dN, *dD, *sig, *dS, *dz, *dDpart, *dVf, *partQ, *partK, *dF, *dlogit, *dqbar;
+  float *deepA, *deepB;   // approximation arrays of the transform's stages above the first (L > 6)
   int64_t total;
 };
 
@@ -409,7 +477,10 @@ GenericWs plan(const wersa_desc &c, int bwd, float *base) {
   w.Spart = b.take(sl * splits * (int64_t)c.m * c.d);
   w.zpart = w.qpart;  // same shape family, used after qpart is consumed
   w.Nbuf = b.take(nd);
+  const int64_t deep = stages_of(c).total;
+  w.deepA = b.take(deep);
   if (bwd) {
+    w.deepB = b.take(deep);
     w.R = b.take(nm);
     w.dN = w.Nbuf;
     w.dD = b.take(sl * c.n);
@@ -485,12 +556,72 @@ void launch_rows_gemm(const wersa_desc &c, const float *A, int K, const float *B
   launch_gemm(a, c.B * c.H, st, "gemm_rows");
 }
 
+dim3 tile_grid(int rows, const wersa_desc &c) {
+  return dim3((rows + kTileRows - 1) / kTileRows, (c.d + kTileCols - 1) / kTileCols, c.B * c.H);
+}
+
+// y = G_F x over all stages.  `deep` holds the approximation arrays of the stages above 0
+// (Stages::total floats; unused when L <= 6).
+template <typename TIn, typename TOut>
+void launch_filter(const wersa_desc &c, const TIn *x, View vin, TOut *y, View vout, const float *filt,
+                   const float *addvec, float addscale, float *deep, hipStream_t st) {
+  const Stages sg = stages_of(c);
+  const int K = sg.count;
+  if (K == 1) {
+    WERSA_STAGE("haar_filter_kernel", st, haar_filter_kernel<TIn, TOut><<<tile_grid(c.n, c), 256, 0, st>>>(
+        x, vin, y, vout, filt, addvec, addscale, c.n, c.d, sg.lv[0], nullptr, nullptr));
+    return;
+  }
+  auto arr = [&](int k) { return deep + sg.off[k]; };
+  // analysis upwards: a_6 of every tile becomes the next stage's signal
+  WERSA_STAGE("haar_filter_kernel", st, haar_filter_kernel<TIn, TOut><<<tile_grid(c.n, c), 256, 0, st>>>(
+      x, vin, (TOut *)nullptr, vout, filt, nullptr, 0.f, c.n, c.d, sg.lv[0], nullptr, arr(1)));
+  for (int k = 1; k + 1 < K; ++k) {
+    const View cvk = contiguous_view(sg.n[k], c.d);
+    WERSA_STAGE("haar_filter_kernel", st, haar_filter_kernel<float, float><<<tile_grid(sg.n[k], c), 256, 0, st>>>(
+        arr(k), cvk, (float *)nullptr, cvk, filt, nullptr, 0.f, sg.n[k], c.d, sg.lv[k], nullptr, arr(k + 1)));
+  }
+  {  // last stage: plain filter of its signal, in place
+    const int k = K - 1;
+    const View cvk = contiguous_view(sg.n[k], c.d);
+    WERSA_STAGE("haar_filter_kernel", st, haar_filter_kernel<float, float><<<tile_grid(sg.n[k], c), 256, 0, st>>>(
+        arr(k), cvk, arr(k), cvk, filt, nullptr, 0.f, sg.n[k], c.d, sg.lv[k], nullptr, nullptr));
+  }
+  // synthesis downwards: every tile takes its filtered a_6 from the stage above
+  for (int k = K - 2; k >= 1; --k) {
+    const View cvk = contiguous_view(sg.n[k], c.d);
+    WERSA_STAGE("haar_filter_kernel", st, haar_filter_kernel<float, float><<<tile_grid(sg.n[k], c), 256, 0, st>>>(
+        arr(k), cvk, arr(k), cvk, filt, nullptr, 0.f, sg.n[k], c.d, sg.lv[k], arr(k + 1), nullptr));
+  }
+  WERSA_STAGE("haar_filter_kernel", st, haar_filter_kernel<TIn, TOut><<<tile_grid(c.n, c), 256, 0, st>>>(
+      x, vin, y, vout, filt, addvec, addscale, c.n, c.d, sg.lv[0], arr(1), nullptr));
+}
+
+// part[slice][tile of stage 0][band] over all stages; deep_x / deep_g hold the approximation
+// arrays of the two operands.
 template <typename T>
-void launch_haar(const wersa_desc &c, const T *x, View vin, float *y, const float *filt,
+void launch_band_dots(const wersa_desc &c, const T *x, View vx, const float *g, float *part,
+                      float *deep_x, float *deep_g, hipStream_t st) {
+  const Stages sg = stages_of(c);
+  const dim3 g0 = tile_grid(c.n, c);
+  const int64_t tiles0 = (int64_t)g0.x * g0.y;
+  const bool deepen = sg.count > 1;
+  WERSA_STAGE("band_dots_kernel", st, band_dots_kernel<T><<<g0, 256, 0, st>>>(
+      x, vx, g, contiguous_view(c.n, c.d), c.n, c.d, sg.lv[0], tiles0, 0, part,
+      deepen ? deep_x + sg.off[1] : nullptr, deepen ? deep_g + sg.off[1] : nullptr));
+  for (int k = 1; k < sg.count; ++k) {
+    const View cvk = contiguous_view(sg.n[k], c.d);
+    const bool more = k + 1 < sg.count;
+    WERSA_STAGE("band_dots_kernel", st, band_dots_kernel<float><<<tile_grid(sg.n[k], c), 256, 0, st>>>(
+        deep_x + sg.off[k], cvk, deep_g + sg.off[k], cvk, sg.n[k], c.d, sg.lv[k], tiles0, 1, part,
+        more ? deep_x + sg.off[k + 1] : nullptr, more ? deep_g + sg.off[k + 1] : nullptr));
+  }
+}
+
+template <typename T>
+void launch_haar(const wersa_desc &c, const T *x, View vin, float *y, const float *filt, float *deep,
                  hipStream_t st) {
-  dim3 grid((c.n + kTileRows - 1) / kTileRows, (c.d + kTileCols - 1) / kTileCols, c.B * c.H);
-  WERSA_STAGE("haar_filter_kernel", st, haar_filter_kernel<T, float><<<grid, 256, 0, st>>>(x, vin, y, contiguous_view(c.n, c.d), filt,
-                                                     nullptr, 0.f, c.n, c.d, c.L));
+  launch_filter<T, float>(c, x, vin, y, contiguous_view(c.n, c.d), filt, nullptr, 0.f, deep, st);
 }
 
 template <typename T>
@@ -511,8 +642,8 @@ wersa_status forward_t(const wersa_desc &c, const T *q, const T *k, const T *v, 
   WERSA_STAGE("gate_fwd_kernel", st, gate_fwd_kernel<<<slices, 256, 0, st>>>(w.qpart, colsum_chunks(c.n), c.n, c.d, c.L, c.H, gate_w,
                                          gate_b, scale_w, qbar, s, F, nullptr, (c.flags & WERSA_FLAG_POOLED_GATE) ? 1 : 0));
   // steps 3, 5, 6: gated Haar filter of Q and K
-  launch_haar<T>(c, q, tv, w.QF, F, st);
-  launch_haar<T>(c, k, tv, w.KF, F, st);
+  launch_haar<T>(c, q, tv, w.QF, F, w.deepA, st);
+  launch_haar<T>(c, k, tv, w.KF, F, w.deepA, st);
   WERSA_STAGE("gather_f32_kernel", st, gather_f32_kernel<T><<<ew_blocks(nd), 256, 0, st>>>(v, tv, c.n, c.d, nd, w.Vf));
   {
     const int64_t om = (int64_t)c.d * c.m * ((c.flags & WERSA_FLAG_SEPARATE_OMEGA) ? 2 : 1);
@@ -553,8 +684,8 @@ wersa_status backward_t(const wersa_desc &c, const T *q, const T *k, const T *v,
   const int64_t md = (int64_t)c.m * c.d;
 
   WERSA_STAGE("scalars_kernel", st, scalars_kernel<<<1, 64, 0, st>>>(sigma, c.bw_floor, c.m, w.scalars));
-  launch_haar<T>(c, q, tv, w.QF, F, st);
-  launch_haar<T>(c, k, tv, w.KF, F, st);
+  launch_haar<T>(c, q, tv, w.QF, F, w.deepA, st);
+  launch_haar<T>(c, k, tv, w.KF, F, w.deepA, st);
   WERSA_STAGE("gather_f32_kernel", st, gather_f32_kernel<T><<<ew_blocks(nd), 256, 0, st>>>(v, tv, c.n, c.d, nd, w.Vf));
   {
     const int64_t om = (int64_t)c.d * c.m * ((c.flags & WERSA_FLAG_SEPARATE_OMEGA) ? 2 : 1);
@@ -591,16 +722,15 @@ wersa_status backward_t(const wersa_desc &c, const T *q, const T *k, const T *v,
   // wavelet stage backward: dF from band inner products, then dX = G_F dX_F
   dim3 tgrid((c.n + kTileRows - 1) / kTileRows, (c.d + kTileCols - 1) / kTileCols, slices);
   const int64_t tiles = (int64_t)tgrid.x * tgrid.y;
-  WERSA_STAGE("band_dots_kernel", st, band_dots_kernel<T><<<tgrid, 256, 0, st>>>(q, tv, w.QF, cv, c.n, c.d, c.L, w.partQ));
-  WERSA_STAGE("band_dots_kernel", st, band_dots_kernel<T><<<tgrid, 256, 0, st>>>(k, tv, w.KF, cv, c.n, c.d, c.L, w.partK));
+  launch_band_dots<T>(c, q, tv, w.QF, w.partQ, w.deepA, w.deepB, st);
+  launch_band_dots<T>(c, k, tv, w.KF, w.partK, w.deepA, w.deepB, st);
   WERSA_STAGE("gate_bwd_slice_kernel", st, gate_bwd_slice_kernel<<<slices, 64, 0, st>>>(w.partQ, w.partK, tiles, c.L, c.d, c.H, s, gate_w,
                                                scale_w, w.dF, w.dlogit, w.dqbar, (c.flags & WERSA_FLAG_POOLED_GATE) ? 1 : 0));
   WERSA_STAGE("gate_bwd_params_kernel", st, gate_bwd_params_kernel<<<gate_bwd_params_blocks(c.H, c.L, c.d), 256, 0, st>>>(w.dF, w.dlogit, s, qbar, w.dDpart,
                                             slices * colsum_chunks(c.n), c.B, c.H, c.L, c.d, c.eps,
                                             w.scalars, dgate_w, dgate_b, dscale_w, dsigma));
-  WERSA_STAGE("haar_filter_kernel", st, haar_filter_kernel<float, T><<<tgrid, 256, 0, st>>>(w.QF, cv, dq, tv, F, w.dqbar, 1.0f / (float)c.n,
-                                                      c.n, c.d, c.L));
-  WERSA_STAGE("haar_filter_kernel", st, haar_filter_kernel<float, T><<<tgrid, 256, 0, st>>>(w.KF, cv, dk, tv, F, nullptr, 0.f, c.n, c.d, c.L));
+  launch_filter<float, T>(c, w.QF, cv, dq, tv, F, w.dqbar, 1.0f / (float)c.n, w.deepA, st);
+  launch_filter<float, T>(c, w.KF, cv, dk, tv, F, nullptr, 0.f, w.deepA, st);
   return hipGetLastError() == hipSuccess ? WERSA_OK : WERSA_ERR_LAUNCH;
 }
 
@@ -640,16 +770,15 @@ wersa_status generic_backward(const wersa_desc &c, const void *q, const void *k,
                             (bf16_t *)dk, (bf16_t *)dv, dgate_w, dgate_b, dscale_w, dsigma, ws, st);
 }
 
+// The stage entry point has no workspace argument, so it covers the single-stage range (L <= 6).
 wersa_status generic_haar_filter(const wersa_desc &c, const void *x, const float *filt, void *xf,
                                  hipStream_t st) {
+  if (c.L > kTileL) return WERSA_ERR_UNSUPPORTED;
   const View tv{c.stride_b, c.stride_h, c.stride_n, c.H};
-  dim3 grid((c.n + kTileRows - 1) / kTileRows, (c.d + kTileCols - 1) / kTileCols, c.B * c.H);
   if (c.dtype == WERSA_F32)
-    WERSA_STAGE("haar_filter_kernel", st, haar_filter_kernel<float, float><<<grid, 256, 0, st>>>((const float *)x, tv, (float *)xf, tv, filt,
-                                                           nullptr, 0.f, c.n, c.d, c.L));
+    launch_filter<float, float>(c, (const float *)x, tv, (float *)xf, tv, filt, nullptr, 0.f, nullptr, st);
   else
-    WERSA_STAGE("haar_filter_kernel", st, haar_filter_kernel<bf16_t, bf16_t><<<grid, 256, 0, st>>>((const bf16_t *)x, tv, (bf16_t *)xf, tv,
-                                                             filt, nullptr, 0.f, c.n, c.d, c.L));
+    launch_filter<bf16_t, bf16_t>(c, (const bf16_t *)x, tv, (bf16_t *)xf, tv, filt, nullptr, 0.f, nullptr, st);
   return hipGetLastError() == hipSuccess ? WERSA_OK : WERSA_ERR_LAUNCH;
 }
 

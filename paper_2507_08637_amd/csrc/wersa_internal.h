@@ -8,7 +8,9 @@
 
 namespace wersa {
 
-constexpr int kMaxL = 6;
+constexpr int kTileL = 6;                 // Haar levels inside one 64-row tile
+constexpr int kTileBands = kTileL + 1;
+constexpr int kMaxL = 20;                 // deepest transform (levels above 6 run on tile approximations)
 constexpr int kMaxBands = kMaxL + 1;
 
 // Strided view of a (B, H, n, d) tensor; element (b, h, t, j) at b*sb + h*sh + t*sn + j.

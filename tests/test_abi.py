@@ -51,7 +51,7 @@ def test_sizes_and_status_strings(lib):
 @pytest.mark.parametrize("kw,status", [
     (dict(B=0), 1), (dict(n=0), 1), (dict(L=-1), 1), (dict(dtype=7), 1), (dict(bw_floor=0.0), 1),
     (dict(stride_n=32), 1), (dict(stride_h=0), 1), (dict(flags=1 << 20), 1),
-    (dict(L=7, n=1024), 2), (dict(d=40), 2), (dict(m=72), 2), (dict(d=512, stride_n=512), 2),
+    (dict(L=21, n=1024), 2), (dict(d=40), 2), (dict(m=72), 2), (dict(d=512, stride_n=512), 2),
 ])
 def test_bad_descriptors_are_rejected_before_launch(lib, kw, status):
     assert lib.wersa_saved_bytes(ctypes.byref(_desc(n=100, L=3))) > 0   # any n: padding is done in-kernel

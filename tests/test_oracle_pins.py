@@ -78,7 +78,7 @@ def _block_mean(x, size):
     return np.broadcast_to(mean, (npad // size, size, xp.shape[1])).reshape(npad, -1)[:n]
 
 
-@pytest.mark.parametrize("n,L", [(64, 3), (256, 6), (48, 3), (100, 2), (192, 5)])
+@pytest.mark.parametrize("n,L", [(64, 3), (256, 6), (48, 3), (100, 2), (192, 5), (300, 7), (1000, 9), (700, 12)])
 def test_block_mean_closed_form(n, L):
     """Gated Haar filter == F_0 x + sum_l (F_l - F_{l-1}) * (mean over aligned 2^l blocks).
 
