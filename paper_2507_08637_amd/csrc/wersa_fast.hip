@@ -739,12 +739,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
   // read X for the band inner products from the same panels, and every mode sends its output
   // tiles through a panel once its X values are used up.
   constexpr bool FUSE = (DH == 64);
-  // Head dimension 128, gradient modes: two waves share a row group and each owns one half of
-  // the output columns (the projection and dPhi are computed by both), which keeps the
-  // accumulators and operands of a wave within the register file.
-  constexpr int CS = (IS_GRAD && DH == 128) ? 2 : 1;
-  constexpr int NWR = NW / CS;          // row groups of 64 rows per workgroup step
-  constexpr int CTW = CT / CS;          // column tiles of this wave
+  constexpr int NWR = NW;               // row groups of 64 rows per workgroup step (one per wave)
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   constexpr int mc = MC;
   constexpr int BS = MC + 4;            // stride of [DH][feature] arrays (8-byte permuted reads)
@@ -765,7 +760,6 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
 
   const int slice = blockIdx.y;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
-  const int rwave = wave / CS, cbase = (wave % CS) * CTW;
   const float cscale = scalars[0];
   const int nchunks = m / mc;
 
@@ -923,7 +917,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
     }
   };
   {
-    const int t_first = (blockIdx.x * NWR + rwave) * 64;
+    const int t_first = (blockIdx.x * NWR + wave) * 64;
     if (blockIdx.x < row_groups && t_first < n) {
       load_rows(t_first);
       put_rows();
@@ -936,12 +930,12 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
   }
 
   for (int rg = blockIdx.x; rg < row_groups; rg += gridDim.x) {
-    const int t0 = (rg * NWR + rwave) * 64;
+    const int t0 = (rg * NWR + wave) * 64;
     const bool active = t0 < n;
 
     bf16x4 xpiece[8];   // X tile of the band inner products (MODE 1, 2, head dimension 128), 8-byte row-major pieces
     auto load_xpiece = [&](int ct, bf16x4 *dst) {
-      const bf16_t *xsrc = x + vx.slice_base(slice) + (int64_t)(t0 + (lane >> 3)) * vx.sn + 32 * (cbase + ct) + (lane & 7) * 4;
+      const bf16_t *xsrc = x + vx.slice_base(slice) + (int64_t)(t0 + (lane >> 3)) * vx.sn + 32 * ct + (lane & 7) * 4;
 #pragma unroll
       for (int j = 0; j < 8; ++j) {   // one running pointer instead of eight scaled row offsets
         dst[j] = *reinterpret_cast<const bf16x4 *>(xsrc);
@@ -995,12 +989,12 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
       for (int ti = 0; ti < 2; ++ti)
         if (h == 0) s_wave[wave * 64 + 32 * ti + l32] = cscale * __builtin_amdgcn_rcpf(dval[ti]);
     }
-    f32x16 acc0[2][CTW];   // N, dV (MODE 0, 3) or dX_F (MODE 1, 2): rows on registers, columns on lanes
+    f32x16 acc0[2][CT];   // N, dV (MODE 0, 3) or dX_F (MODE 1, 2): rows on registers, columns on lanes
     float dacc[2] = {0.f, 0.f};   // D partial of this lane's row (MODE 0)
 #pragma unroll
     for (int ti = 0; ti < 2; ++ti)
 #pragma unroll
-      for (int ct = 0; ct < CTW; ++ct) acc0[ti][ct] = zero16();
+      for (int ct = 0; ct < CT; ++ct) acc0[ti][ct] = zero16();
 
     for (int m0 = 0; m0 < m; m0 += mc) {
       if (nchunks > 1) {
@@ -1010,7 +1004,11 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
       }
       if (!active) continue;
 
-      for (int rt = 0; rt < mc / 32; ++rt) {
+      // Head dimension 128, gradient modes: a bound the compiler cannot see keeps the loop rolled
+      // (unrolled, the operands of several feature tiles are fetched ahead and spill).
+      int rt_end = mc / 32;
+      if (IS_GRAD && DH == 128) asm volatile("" : "+s"(rt_end));
+      for (int rt = 0; rt < rt_end; ++rt) {
         f16x8 oa[KS];     // Omega^T rows of this feature tile: A operand of the projection
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
@@ -1045,8 +1043,8 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
             for (int a = 0; a < 2; ++a) {
               const bf16x8 pg = pack_half(Gv[ti], a);
 #pragma unroll
-              for (int ct = 0; ct < CTW; ++ct) {
-                const bf16x8 ob = lds_perm8(&s_om[(32 * (cbase + ct) + l32) * BS], 32 * rt + 16 * a, h);
+              for (int ct = 0; ct < CT; ++ct) {
+                const bf16x8 ob = lds_perm8(&s_om[(32 * ct + l32) * BS], 32 * rt + 16 * a, h);
                 acc0[ti][ct] = mfma_bf16(pg, ob, acc0[ti][ct]);
               }
             }
@@ -1082,8 +1080,8 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
             for (int a = 0; a < 2; ++a) {
               const bf16x8 pg = pack_half(G, a);
 #pragma unroll
-              for (int ct = 0; ct < CTW; ++ct) {
-                const bf16x8 ob = lds_perm8(&s_om[(32 * (cbase + ct) + l32) * BS], 32 * rt + 16 * a, h);
+              for (int ct = 0; ct < CT; ++ct) {
+                const bf16x8 ob = lds_perm8(&s_om[(32 * ct + l32) * BS], 32 * rt + 16 * a, h);
                 acc0[ti][ct] = mfma_bf16(pg, ob, acc0[ti][ct]);
               }
             }
@@ -1098,7 +1096,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
       // Unconditional (the last round re-requests its own rows): a branch around these loads
       // would leave two paths with different numbers of outstanding memory operations, and the
       // waits the compiler then places further down would cover the loads just issued.
-      const int t_next = ((rg + gridDim.x) * NWR + rwave) * 64;
+      const int t_next = ((rg + gridDim.x) * NWR + wave) * 64;
       load_rows((rg + gridDim.x < row_groups && t_next < n) ? t_next : t0);
     }
     bf16_t *tl = panels;   // FUSE, gradient modes: moves to the panel of the column tile in hand
@@ -1189,7 +1187,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
         for (int i = 0; i < 16; ++i) sc[i] = cscale;
       }
 #pragma unroll
-      for (int ct = 0; ct < CTW; ++ct)
+      for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc0[ti][ct][i] *= sc[i];
     }
@@ -1226,7 +1224,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
     // X comes in and dX goes out through a wave-private LDS tile of 64 rows x 32 columns, so
     // that global memory sees 8-byte row-major accesses and the column accesses stay in LDS.
 #pragma unroll
-    for (int ct = 0; ct < CTW; ++ct) {
+    for (int ct = 0; ct < CT; ++ct) {
       // ---- X tile -> LDS (FUSE: it is there already, in this column tile's panel)
       if (FUSE) {
         tl = panels + ct * (64 * TS);
@@ -1312,7 +1310,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
       }
       __builtin_amdgcn_wave_barrier();
       // ---- LDS -> dX
-      tile_store(os, vo.sn, 32 * (cbase + ct));
+      tile_store(os, vo.sn, 32 * ct);
     }
     put_rows();
   }
@@ -1456,8 +1454,7 @@ FastPlan fast_plan(const wersa_desc &c) {
   // 256 workgroups in total, so that no second, mostly empty round follows the first.
   int wgs = 256 / slices < 1 ? 1 : 256 / slices;
   p.rowsWgsA = wgs < p.rowGroupsA ? wgs : p.rowGroupsA;
-  const int nwr = kWavesGrad / (c.d == 128 ? 2 : 1);   // row groups per gradient workgroup step
-  p.rowGroupsG = (blocks + nwr - 1) / nwr;
+  p.rowGroupsG = (blocks + kWavesGrad - 1) / kWavesGrad;
   p.rowsWgsG = wgs < p.rowGroupsG ? wgs : p.rowGroupsG;
   return p;
 }
