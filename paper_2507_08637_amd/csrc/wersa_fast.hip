@@ -540,6 +540,15 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
     stash(0);
   }
   __syncthreads();
+  // FUSE: rows 32 (wave / 2) + l32 of G are this wave's B operands in every step: kept in
+  // registers (high part for the four k-steps, low part for the two of the quarter's own half).
+  bf16x8 ghi[4], glo[2];
+  if (FUSE) {
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) ghi[ks] = filter_operand(gt, 0, 32 * (wave >> 1) + l32, 2 * ks + h);
+#pragma unroll
+    for (int u = 0; u < 2; ++u) glo[u] = filter_operand(gt, 1, 32 * (wave >> 1) + l32, 2 * (2 * (wave >> 1) + u) + h);
+  }
   for (int s = 0; s < steps; ++s) {
     const int buf = s & 1;
     const bool more = s + 1 < steps;
@@ -550,15 +559,13 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
     if (FUSE) {
       // X_F^T quarter: columns 32 (wave % 2) .. + 31 of the tile, rows 32 (wave / 2) .. + 31.
       const bf16_t *raw = reinterpret_cast<const bf16_t *>(&xt[buf][0]);
-      // rows 32 (wave / 2) + l32 of G (high and low part) are the B operands
       f32x16 q = zero16(), q2 = zero16();
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
         const bf16x8 xa = tile_cols_operand<false>(raw, XS, 32 * (wave & 1), ks, lane);
-        q = mfma_bf16(xa, filter_operand(gt, 0, 32 * (wave >> 1) + l32, 2 * ks + h), q);
+        q = mfma_bf16(xa, ghi[ks], q);
         // the low part matters inside the quarter's own 32-row half only (wave-uniform branch)
-        if ((ks >> 1) == (wave >> 1))
-          q2 = mfma_bf16(xa, filter_operand(gt, 1, 32 * (wave >> 1) + l32, 2 * ks + h), q2);
+        if ((ks >> 1) == (wave >> 1)) q2 = mfma_bf16(xa, glo[ks & 1], q2);
       }
 #pragma unroll
       for (int i = 0; i < 16; ++i) q[i] += q2[i];
