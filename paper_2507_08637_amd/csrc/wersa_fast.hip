@@ -422,7 +422,7 @@ __device__ __forceinline__ bf16x8 tile_cols_operand(const bf16_t *tile, int stri
 // Head dimension 64 (FUSE): `xf` is not read; the rows of X (Q or K, bf16, view vx) are staged
 // raw and each step starts with X_F = G X for its tile, one 32 x 32 quarter per wave, written
 // to LDS in fp16 for the projection.
-template <int DH, int FW, bool PREP>
+template <int DH, int FW, bool PREP, bool RAGGED>   // RAGGED: n % 64 != 0, rows past n count as zeros with weight 0
 __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
     const _Float16 *xf, const bf16_t *xraw, View vx, const float *coef,
     const bf16_t *y, View vy, const float *rowdiv, const float *w,
@@ -446,7 +446,7 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
   const int f0 = blockIdx.y * (4 * FW) + wave * FW;
   const int t_begin = chunk * rows_per_chunk, t_end = min(n, t_begin + rows_per_chunk);
-  const int steps = (t_end - t_begin) / 64;
+  const int steps = (t_end - t_begin + 63) / 64;   // the last tile of the sequence may be partial
 
   // Omega^T operands of this wave's features: B operand, column = feature, k = 8h + q.
   f16x8 om[RT][KS];
@@ -482,25 +482,38 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
   float pdiv = 1.0f, dsum = 0.f;
   const int prow = 16 * wave + (lane & 15), pquart = lane >> 4;
   const bf16_t *os = PREP ? orows + vy.slice_base(slice) : nullptr;
+  // RAGGED: rows past n (partial last tile) count as zeros with weight 0: the address is clamped
+  // to the last row and the value replaced.
   auto fetch = [&](int t0) {
+    const int last = RAGGED ? n - t0 - 1 : 63;
     if (PREP) {
+      const bool bad = RAGGED && prow > last;
+      const int pr = t0 + (RAGGED ? min(prow, last) : prow);
 #pragma unroll
       for (int j = 0; j < QP; ++j) {
-        const int64_t off = (int64_t)(t0 + prow) * vy.sn + (pquart * QP + j) * 8;
+        const int64_t off = (int64_t)pr * vy.sn + (pquart * QP + j) * 8;
         po[j] = *reinterpret_cast<const bf16x8 *>(os + off);
         pd[j] = *reinterpret_cast<const bf16x8 *>(ys + off);
+        if (bad) pd[j] = splat_bf16x8(0.f);
       }
-      pdiv = rd[t0 + prow];
+      pdiv = bad ? 1.0f : rd[pr];
     }
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
       const int e = tid + 256 * i, r = e / CPR, cc = e % CPR;
-      xr[i] = FUSE ? *reinterpret_cast<const u16x8 *>(xrs + (int64_t)(t0 + r) * vx.sn + cc * 8)
-                   : *reinterpret_cast<const u16x8 *>(xs + (int64_t)(t0 + r) * DH + cc * 8);
-      yr[i] = *reinterpret_cast<const u16x8 *>(ys + (int64_t)(t0 + r) * vy.sn + cc * 8);
-      inv[i] = rd ? rd[t0 + r] : 1.0f;   // divided at the stash, when the load has landed
+      const bool bad = RAGGED && r > last;
+      const int rc = t0 + (RAGGED ? min(r, last) : r);
+      xr[i] = FUSE ? *reinterpret_cast<const u16x8 *>(xrs + (int64_t)rc * vx.sn + cc * 8)
+                   : *reinterpret_cast<const u16x8 *>(xs + (int64_t)rc * DH + cc * 8);
+      yr[i] = *reinterpret_cast<const u16x8 *>(ys + (int64_t)rc * vy.sn + cc * 8);
+      inv[i] = rd ? rd[rc] : 1.0f;   // divided at the stash, when the load has landed
+      if (bad) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) { xr[i][q] = 0; yr[i][q] = 0; }
+        inv[i] = 1.0f;
+      }
     }
-    if (!PREP && tid < 64) wv = ws ? ws[t0 + tid] : 1.0f;
+    if (!PREP && tid < 64) wv = (RAGGED && tid > last) ? 0.f : (ws ? ws[t0 + tid] : 1.0f);
   };
   int t_stash = t_begin;   // first row of the tile the registers hold
   auto stash = [&](int buf) {
@@ -528,7 +541,7 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
       if (lane < 16) {
         wl[buf][prow] = cvt_bf16(dDt);
         dsum += dDt;
-        if (blockIdx.y == 0) dDout[(int64_t)slice * n + t_stash + prow] = dDt;
+        if (blockIdx.y == 0 && (!RAGGED || t_stash + prow < n)) dDout[(int64_t)slice * n + t_stash + prow] = dDt;
       }
     } else if (tid < 64) {
       wl[buf][tid] = cvt_bf16(wv);
@@ -711,7 +724,10 @@ __global__ __launch_bounds__(256) void reduce_contract_kernel(const float *Spart
 // layout, rows on registers), per-band inner products with X for dF, bf16 stores.
 // ------------------------------------------------------------------------------------
 
-template <int DH, int MODE, int NW, int MC, bool LN>   // LN (MODE 0): LayerNorm over the columns of a row instead of the normaliser
+// LN (MODE 0): LayerNorm over the columns of a row instead of the normaliser.  RAGGED: n is not a
+// multiple of 64; rows past n of the last block read as zeros (clamped address, value replaced)
+// and that block's output goes through a side buffer.  The plain instance has none of that code.
+template <int DH, int MODE, int NW, int MC, bool LN, bool RAGGED>
 __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
     const _Float16 *xf,        // X_F fp16 [slices][n][DH] (head dimension 128; with 64 it is formed here)
     const bf16_t *x, View vx,  // X (Q or K): band inner products (MODE 1, 2); source of X_F (head dimension 64)
@@ -727,7 +743,8 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
     const float *scalars, float eps, int n, int m, int row_groups,
     bf16_t *out0, View vo,     // O (MODE 0) / dQ or dK (MODE 1, 2) / dV (MODE 3)
     float *Dout,               // D (MODE 0)
-    float *partF, int L)       // [slices][gridDim.x][L+1] band partials (MODE 1, 2)
+    float *partF, int L,       // [slices][gridDim.x][L+1] band partials (MODE 1, 2)
+    bf16_t *tail_out, float *tail_D)   // partial last block: its 64 output rows [slices][64][DH] and D [slices][64]
 {
   constexpr int KS = DH / 16, CT = DH / 32;
   constexpr int KSX = KS + 1;           // k-steps of the dPhi MFMA incl. the rank-one extension
@@ -854,37 +871,66 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
   bf16x8 yb[2][KSX];    // dO or V rows (+ the a_t extension): B operand of the dPhi MFMA
   float dval[2] = {1.f, 1.f};   // D of rows 32 ti + l32 (MODE 1)
   float aval[2] = {1.f, 1.f};   // dD of the same rows (MODE 1)
-  auto load_rows = [&](int t0) {
-    if (FUSE) {
-      // one running pointer (eight separately scaled row offsets would each be kept in registers)
-      const bf16_t *xsrc = x + vx.slice_base(slice) + (int64_t)(t0 + (lane >> 3)) * vx.sn + (lane & 7) * 8;
+  auto zero_if = [](bool bad, auto v) {
+    if (bad) {
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        xp[j] = *reinterpret_cast<const u16x8 *>(xsrc);
-        xsrc += 8 * vx.sn;
+      for (int q = 0; q < 8; ++q) v[q] = 0;
+    }
+    return v;
+  };
+  auto load_rows = [&](int t0) {
+    const int last = RAGGED ? n - t0 - 1 : 63;   // last row of this block that exists
+    if (FUSE) {
+      if (!RAGGED) {
+        // one running pointer (eight separately scaled row offsets would each be kept in registers)
+        const bf16_t *xsrc = x + vx.slice_base(slice) + (int64_t)(t0 + (lane >> 3)) * vx.sn + (lane & 7) * 8;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          xp[j] = *reinterpret_cast<const u16x8 *>(xsrc);
+          xsrc += 8 * vx.sn;
+        }
+      } else {
+        const bf16_t *xsrc = x + vx.slice_base(slice) + (int64_t)t0 * vx.sn + (lane & 7) * 8;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int row = (lane >> 3) + 8 * j;
+          xp[j] = zero_if(row > last, *reinterpret_cast<const u16x8 *>(xsrc + (int64_t)min(row, last) * vx.sn));
+        }
       }
     } else {
       const _Float16 *xs = xf + ((int64_t)slice * n + t0) * DH;
 #pragma unroll
-      for (int ti = 0; ti < 2; ++ti)
+      for (int ti = 0; ti < 2; ++ti) {
+        const int row = 32 * ti + l32, rc = RAGGED ? min(row, last) : row;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-          xb[ti][ks] = *reinterpret_cast<const f16x8 *>(xs + (int64_t)(32 * ti + l32) * DH + 16 * ks + 8 * h);
+        for (int ks = 0; ks < KS; ++ks) {
+          const f16x8 v = *reinterpret_cast<const f16x8 *>(xs + (int64_t)rc * DH + 16 * ks + 8 * h);
+          xb[ti][ks] = RAGGED ? zero_if(row > last, v) : v;
+        }
+      }
     }
     if (IS_GRAD) {
       // MODE 1 works with the raw dO rows: G' = D_t * G (the extension carries dD_t * D_t), and
-      // row t of dX_F is scaled by c / D_t at the end; MODE 2 scales by c.
+      // row t of dX_F is scaled by c / D_t at the end; MODE 2 scales by c (extension 1, or 0 for
+      // a row past n, which must not pick up the vector part).
       const bf16_t *ys = y + vy.slice_base(slice);
 #pragma unroll
       for (int ti = 0; ti < 2; ++ti) {
-        const int t = t0 + 32 * ti + l32;
+        const int row = 32 * ti + l32;
+        const bool bad = RAGGED && row > last;
+        const int t = t0 + (RAGGED ? min(row, last) : row);
         if (MODE == 1) {   // only requested here: used at the top of the next round (finish_rows)
           dval[ti] = Dsaved[(int64_t)slice * n + t];
           aval[ti] = arow[(int64_t)slice * n + t];
+          if (bad) { dval[ti] = 1.f; aval[ti] = 0.f; }
+        } else if (RAGGED) {
+          aval[ti] = bad ? 0.f : 1.f;
         }
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-          yb[ti][ks] = *reinterpret_cast<const bf16x8 *>(ys + (int64_t)t * vy.sn + 16 * ks + 8 * h);
+        for (int ks = 0; ks < KS; ++ks) {
+          const bf16x8 v = *reinterpret_cast<const bf16x8 *>(ys + (int64_t)t * vy.sn + 16 * ks + 8 * h);
+          yb[ti][ks] = RAGGED ? zero_if(bad, v) : v;
+        }
       }
     }
   };
@@ -894,7 +940,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
 #pragma unroll
       for (int ti = 0; ti < 2; ++ti) {
         bf16x8 ext = splat_bf16x8(0.f);
-        if (h == 0) ext[0] = (__bf16)(MODE == 1 ? aval[ti] * dval[ti] : 1.0f);
+        if (h == 0) ext[0] = (__bf16)(MODE == 1 ? aval[ti] * dval[ti] : (RAGGED ? aval[ti] : 1.0f));
         yb[ti][KSX - 1] = ext;
       }
     }
@@ -939,14 +985,30 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
   for (int rg = blockIdx.x; rg < row_groups; rg += gridDim.x) {
     const int t0 = (rg * NWR + wave) * 64;
     const bool active = t0 < n;
+    // A partial last block (n not a multiple of 64) writes all its 64 rows to a side buffer, from
+    // which a small kernel copies the rows that exist: the stores themselves stay unguarded
+    // (guards or pointer selects around them cost the gradient kernels 230 bytes of spills per lane).
+    const int valid = RAGGED ? n - t0 : 64;
+    const bool tail = RAGGED && valid < 64;
 
     bf16x4 xpiece[8];   // X tile of the band inner products (MODE 1, 2, head dimension 128), 8-byte row-major pieces
     auto load_xpiece = [&](int ct, bf16x4 *dst) {
-      const bf16_t *xsrc = x + vx.slice_base(slice) + (int64_t)(t0 + (lane >> 3)) * vx.sn + 32 * ct + (lane & 7) * 4;
+      if (!RAGGED) {
+        const bf16_t *xsrc = x + vx.slice_base(slice) + (int64_t)(t0 + (lane >> 3)) * vx.sn + 32 * ct + (lane & 7) * 4;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {   // one running pointer instead of eight scaled row offsets
-        dst[j] = *reinterpret_cast<const bf16x4 *>(xsrc);
-        xsrc += 8 * vx.sn;
+        for (int j = 0; j < 8; ++j) {   // one running pointer instead of eight scaled row offsets
+          dst[j] = *reinterpret_cast<const bf16x4 *>(xsrc);
+          xsrc += 8 * vx.sn;
+        }
+      } else {
+        const bf16_t *xsrc = x + vx.slice_base(slice) + (int64_t)t0 * vx.sn + 32 * ct + (lane & 7) * 4;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {   // rows past n: clamped address, value replaced by zeros
+          const int row = (lane >> 3) + 8 * j;
+          bf16x4 v4 = *reinterpret_cast<const bf16x4 *>(xsrc + (int64_t)min(row, valid - 1) * vx.sn);
+          if (row >= valid) v4 = bf16x4{0, 0, 0, 0};
+          dst[j] = v4;
+        }
       }
     };
     if (FUSE && active) {
@@ -1135,7 +1197,9 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
       }
     };
     const int prow = lane >> 3, pcol = (lane & 7) * 4;   // this lane's 8-byte piece: rows prow + 8 j
-    bf16_t *os = out0 + vo.slice_base(slice) + (int64_t)t0 * vo.sn;
+    bf16_t *os = tail ? tail_out + (int64_t)slice * 64 * DH : out0 + vo.slice_base(slice) + (int64_t)t0 * vo.sn;
+    const int64_t osn = tail ? DH : vo.sn;   // row stride of the output rows
+    float *Dp = tail ? tail_D + slice * 64 : Dout + (int64_t)slice * n + t0;
 
     if (MODE == 0 && LN) {
       // Output stage of Algorithm 1: O_t = (N_t - mean N_t) / sqrt(var N_t + eps), N = c * acc.
@@ -1163,7 +1227,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
           if (l32 == 0) dl[32 * ti + acc_row(i, h)] = rstd;
         }
       __builtin_amdgcn_wave_barrier();
-      Dout[(int64_t)slice * n + t0 + lane] = dl[lane];
+      Dp[lane] = dl[lane];
     } else if (MODE == 0) {   // normaliser D_t = c * sum_r relu(R) z + eps, row scale c / D_t
       float *dl = s_wave + wave * 64;
 #pragma unroll
@@ -1172,7 +1236,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
         const float Dt = fmaf(cscale, dsum, eps);
         // both half-waves hold the same sum and write the same values: no branch around the store
         dl[32 * ti + l32] = cscale * __builtin_amdgcn_rcpf(Dt);
-        Dout[(int64_t)slice * n + t0 + 32 * ti + l32] = Dt;
+        Dp[32 * ti + l32] = Dt;
       }
     }
     // Row scale of the accumulators (rows on registers): c / D_t (MODE 0 from the per-wave LDS
@@ -1213,11 +1277,11 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
 #pragma unroll
         for (int j = 0; j < 8; ++j)
           piece[j] = *reinterpret_cast<const bf16x4 *>(&tl[(prow + 8 * j) * TS + pcol]);
-        bf16_t *orow = os + (int64_t)prow * vo.sn + 32 * ct + pcol;
+        bf16_t *orow = os + (int64_t)prow * osn + 32 * ct + pcol;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           *reinterpret_cast<bf16x4 *>(orow) = piece[j];
-          orow += 8 * vo.sn;
+          orow += 8 * osn;
         }
       }
       put_rows();
@@ -1317,7 +1381,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
       }
       __builtin_amdgcn_wave_barrier();
       // ---- LDS -> dX
-      tile_store(os, vo.sn, 32 * ct);
+      tile_store(os, osn, 32 * ct);
     }
     put_rows();
   }
@@ -1426,6 +1490,21 @@ __global__ __launch_bounds__(256) void ln_prep_kernel(const bf16_t *dout, const 
   if (tid == 0) part[(int64_t)slice * gridDim.x + chunk] = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
+// Partial last block of a sequence: rows [t0, n) of the side buffer [slices][64][DH] (and of
+// D [slices][64] when given) go to their place in the output.
+template <int DH>
+__global__ __launch_bounds__(256) void tail_copy_kernel(const bf16_t *tail_out, const float *tail_D, int n,
+                                                       int t0, bf16_t *out, View v, float *D) {
+  constexpr int CPR = DH / 8;
+  const int slice = blockIdx.x, valid = n - t0;
+  for (int e = threadIdx.x; e < valid * CPR; e += 256) {
+    const int r = e / CPR, cc = e % CPR;
+    *reinterpret_cast<u16x8 *>(out + v.slice_base(slice) + (int64_t)(t0 + r) * v.sn + cc * 8) =
+        *reinterpret_cast<const u16x8 *>(tail_out + ((int64_t)slice * 64 + r) * DH + cc * 8);
+  }
+  if (D && (int)threadIdx.x < valid) D[(int64_t)slice * n + t0 + threadIdx.x] = tail_D[slice * 64 + threadIdx.x];
+}
+
 // ---------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------
@@ -1445,7 +1524,7 @@ FastPlan fast_plan(const wersa_desc &c) {
   p.DH = c.d;
   if (c.m % 256 == 0 && c.d == 64) { p.FW = 64; p.MB = 256; } else { p.FW = 32; p.MB = 128; }
   p.mc = (c.d == 64 && c.m % 256 == 0) ? 256 : 128;
-  const int slices = c.B * c.H, blocks = c.n / 64;
+  const int slices = c.B * c.H, blocks = (c.n + 63) / 64;
   int cq = (c.n + 1023) / 1024;
   p.chunksQ = cq < 1 ? 1 : (cq > 512 ? 512 : cq);
   p.rowsQ = (c.n + p.chunksQ - 1) / p.chunksQ;
@@ -1469,6 +1548,8 @@ FastPlan fast_plan(const wersa_desc &c) {
 struct FastWs {
   float *scalars, *coef, *qpart, *Spart, *zpart, *dD, *dDpart, *dS, *dz, *partQ, *partK, *dF,
       *dlogit, *dqbar;
+  bf16_t *tail_out;   // partial last block of the sequence: its 64 output rows [slices][64][d]
+  float *tail_D;      // and its D values [slices][64]
   _Float16 *omT;
   bf16_t *Sx, *ST, *zb, *dSx, *dST, *dzb;
   bf16_t *dN;    // LayerNorm output stage: gradient with respect to the un-normalised rows
@@ -1491,6 +1572,8 @@ FastWs fast_ws(const wersa_desc &c, const FastPlan &p, int bwd, float *base, flo
     w.ST = reinterpret_cast<bf16_t *>(saved + sv.ST);
     w.zb = reinterpret_cast<bf16_t *>(saved + sv.zb);
   }
+  w.tail_out = reinterpret_cast<bf16_t *>(b.take(sl * 64 * c.d / 2));
+  w.tail_D = b.take(sl * 64);
   w.qpart = b.take(sl * p.chunksQ * c.d);
   w.Spart = b.take(sl * p.chunksC * md);
   w.zpart = b.take(sl * p.chunksC * c.m);
@@ -1555,15 +1638,22 @@ hipError_t launch_rows(const wersa_desc &c, const FastPlan &p, const _Float16 *x
     WERSA_STAGE(name, st,
                 kern<<<dim3(wgs, c.B * c.H), NW * 64, smem, st>>>(
                     xf, x, tv, y, yview ? *yview : tv, Dsaved, arow, omT, omega, Mx, MT, bb, w.coef, w.scalars,
-                    c.eps, c.n, c.m, groups, out0, tv, Dout, partF, c.L));
+                    c.eps, c.n, c.m, groups, out0, tv, Dout, partF, c.L, w.tail_out, w.tail_D));
+    if (c.n % 64 != 0)
+      WERSA_STAGE("wersa_tail_copy", st,
+                  tail_copy_kernel<DH><<<c.B * c.H, 256, 0, st>>>(w.tail_out, MODE == 0 ? w.tail_D : nullptr, c.n,
+                                                                   c.n / 64 * 64, out0, tv, Dout));
     return hipSuccess;
   };
-  if (MODE == 0 && (c.flags & WERSA_FLAG_LAYERNORM)) {
-    if (p.mc == 256) return go(&rows_kernel<DH, MODE, NW, 256, MODE == 0>);
-    return go(&rows_kernel<DH, MODE, NW, 128, MODE == 0>);
+  const bool ln = MODE == 0 && (c.flags & WERSA_FLAG_LAYERNORM), ragged = c.n % 64 != 0;
+  if (ragged) {   // the shapes with a partial last block take the guarded instances
+    if (ln) return p.mc == 256 ? go(&rows_kernel<DH, MODE, NW, 256, MODE == 0, true>)
+                               : go(&rows_kernel<DH, MODE, NW, 128, MODE == 0, true>);
+    return p.mc == 256 ? go(&rows_kernel<DH, MODE, NW, 256, false, true>) : go(&rows_kernel<DH, MODE, NW, 128, false, true>);
   }
-  if (p.mc == 256) return go(&rows_kernel<DH, MODE, NW, 256, false>);
-  return go(&rows_kernel<DH, MODE, NW, 128, false>);
+  if (ln) return p.mc == 256 ? go(&rows_kernel<DH, MODE, NW, 256, MODE == 0, false>)
+                             : go(&rows_kernel<DH, MODE, NW, 128, MODE == 0, false>);
+  return p.mc == 256 ? go(&rows_kernel<DH, MODE, NW, 256, false, false>) : go(&rows_kernel<DH, MODE, NW, 128, false, false>);
 }
 
 // orows != nullptr selects the backward form that derives dD from the rows of O itself;
@@ -1582,12 +1672,13 @@ void launch_contract(const wersa_desc &c, const FastPlan &p, const _Float16 *xf,
                                            rowdiv, wts, orows, w.dD, w.dDpart, omT, c.n, c.m, p.rowsC, w.Spart,
                                            w.zpart));
   };
+  const bool ragged = c.n % 64 != 0;
   if (p.FW == 64) {
-    if (orows) go(&phiT_contract_kernel<DH, 64, true>);
-    else go(&phiT_contract_kernel<DH, 64, false>);
+    if (orows) ragged ? go(&phiT_contract_kernel<DH, 64, true, true>) : go(&phiT_contract_kernel<DH, 64, true, false>);
+    else ragged ? go(&phiT_contract_kernel<DH, 64, false, true>) : go(&phiT_contract_kernel<DH, 64, false, false>);
   } else {
-    if (orows) go(&phiT_contract_kernel<DH, 32, true>);
-    else go(&phiT_contract_kernel<DH, 32, false>);
+    if (orows) ragged ? go(&phiT_contract_kernel<DH, 32, true, true>) : go(&phiT_contract_kernel<DH, 32, true, false>);
+    else ragged ? go(&phiT_contract_kernel<DH, 32, false, true>) : go(&phiT_contract_kernel<DH, 32, false, false>);
   }
   const int64_t W = (int64_t)c.m * DH;
   WERSA_STAGE("wersa_reduce_contract", st,
@@ -1621,9 +1712,9 @@ wersa_status fast_forward_t(const wersa_desc &c, const bf16_t *q, const bf16_t *
                                                      scale_w, qbar, s, F, w.coef, (c.flags & WERSA_FLAG_POOLED_GATE) ? 1 : 0));
   if (DH != 64) {   // head dimension 64 runs stage A inside the kernels that consume X_F
     WERSA_STAGE("wersa_haar_stage", st,
-                haar_stage_kernel<DH><<<dim3(c.n / 64, slices), 256, 0, st>>>(q, tv, c.n, w.coef, QF));
+                haar_stage_kernel<DH><<<dim3((c.n + 63) / 64, slices), 256, 0, st>>>(q, tv, c.n, w.coef, QF));
     WERSA_STAGE("wersa_haar_stage", st,
-                haar_stage_kernel<DH><<<dim3(c.n / 64, slices), 256, 0, st>>>(k, tv, c.n, w.coef, KF));
+                haar_stage_kernel<DH><<<dim3((c.n + 63) / 64, slices), 256, 0, st>>>(k, tv, c.n, w.coef, KF));
   }
   launch_contract<DH>(c, p, KF, k, v, tv, nullptr, nullptr, nullptr, true, w, S, z, w.Sx, w.ST, w.zb, st);
   if (launch_rows<DH, 0>(c, p, QF, q, nullptr, nullptr, nullptr, w, omega, nullptr, w.ST, w.zb, out, D,
@@ -1690,7 +1781,7 @@ wersa_status fast_backward_t(const wersa_desc &c, const bf16_t *q, const bf16_t 
 }  // namespace
 
 bool fast_supported(const wersa_desc &c) {
-  return c.dtype == WERSA_BF16 && (c.d == 64 || c.d == 128) && c.n % 64 == 0 && c.m % 128 == 0 && c.L <= kTileL &&
+  return c.dtype == WERSA_BF16 && (c.d == 64 || c.d == 128) && c.m % 128 == 0 && c.L <= kTileL &&
          c.stride_n % 8 == 0 && c.stride_h % 8 == 0 && c.stride_b % 8 == 0;
 }
 

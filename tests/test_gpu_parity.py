@@ -99,6 +99,11 @@ MFMA_SHAPES = [
     dict(B=1, H=1, n=64, d=128, L=6, m=128),      # head dimension 128: column halves split over waves
     dict(B=2, H=2, n=832, d=128, L=6, m=512),     # 13 blocks, four operand chunks
     dict(B=1, H=2, n=1536, d=128, L=4, m=256),
+    # sequence lengths that are not multiples of the 64-row block: the last block is partial
+    dict(B=2, H=2, n=1000, d=64, L=6, m=256),     # 15 full blocks + 40 rows
+    dict(B=1, H=2, n=100, d=64, L=5, m=128),      # one full block + 36 rows
+    dict(B=1, H=1, n=40, d=64, L=3, m=128),       # less than one block
+    dict(B=1, H=2, n=203, d=128, L=6, m=128),     # head dimension 128, 3 blocks + 11 rows
 ]
 
 
