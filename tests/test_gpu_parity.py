@@ -337,7 +337,8 @@ def test_layernorm_output_stage(path):
 
 
 @pytest.mark.parametrize("shape", [dict(B=1, H=2, n=1024, d=64, L=5, m=256),
-                                   dict(B=2, H=1, n=832, d=128, L=6, m=256)])
+                                   dict(B=2, H=1, n=832, d=128, L=6, m=256),
+                                   dict(B=1, H=2, n=1000, d=64, L=5, m=256)])   # partial last block
 def test_layernorm_output_stage_mfma_shapes(shape):
     """The LayerNorm output stage on the other MFMA kernel variants: 256-feature operand blocks
     (d = 64) and the head dimension 128."""
