@@ -21,6 +21,27 @@ wersa_status validate_desc(const wersa_desc *c) {
   return WERSA_OK;
 }
 
+static bool misaligned(const void *p, size_t a) { return ((uintptr_t)p % a) != 0; }
+
+wersa_status forward_checked(const wersa_desc *desc, const void *q, const void *k, const void *v,
+                                    const void *omega_rf, const float *sigma, const float *gate_w,
+                                    const float *gate_b, const float *scale_w, void *out, void *saved,
+                                    void *workspace, size_t workspace_bytes, void *hip_stream,
+                                    const PooledSums *pooled) {
+  const wersa_status vs = validate_desc(desc);
+  if (vs != WERSA_OK) return vs;
+  if (!q || !k || !v || !omega_rf || !sigma || !gate_w || !gate_b || !scale_w || !out || !saved)
+    return WERSA_ERR_INVALID_ARG;
+  if (!workspace || workspace_bytes < wersa_workspace_bytes(desc, 0) || misaligned(workspace, 256) ||
+      misaligned(saved, 256))
+    return WERSA_ERR_WORKSPACE;
+  if (use_fast(*desc))
+    return fast_forward(*desc, q, k, v, omega_rf, sigma, gate_w, gate_b, scale_w, out, (float *)saved,
+                        (float *)workspace, (hipStream_t)hip_stream, pooled);
+  return generic_forward(*desc, q, k, v, omega_rf, sigma, gate_w, gate_b, scale_w, out, (float *)saved,
+                         (float *)workspace, (hipStream_t)hip_stream);
+}
+
 }  // namespace wersa
 
 using namespace wersa;
@@ -57,24 +78,12 @@ int64_t wersa_saved_offset(const wersa_desc *desc, int which) {
   }
 }
 
-static bool misaligned(const void *p, size_t a) { return ((uintptr_t)p % a) != 0; }
-
 wersa_status wersa_forward(const wersa_desc *desc, const void *q, const void *k, const void *v,
                            const void *omega_rf, const float *sigma, const float *gate_w,
                            const float *gate_b, const float *scale_w, void *out, void *saved,
                            void *workspace, size_t workspace_bytes, void *hip_stream) {
-  const wersa_status vs = validate_desc(desc);
-  if (vs != WERSA_OK) return vs;
-  if (!q || !k || !v || !omega_rf || !sigma || !gate_w || !gate_b || !scale_w || !out || !saved)
-    return WERSA_ERR_INVALID_ARG;
-  if (!workspace || workspace_bytes < wersa_workspace_bytes(desc, 0) || misaligned(workspace, 256) ||
-      misaligned(saved, 256))
-    return WERSA_ERR_WORKSPACE;
-  if (use_fast(*desc))
-    return fast_forward(*desc, q, k, v, omega_rf, sigma, gate_w, gate_b, scale_w, out, (float *)saved,
-                        (float *)workspace, (hipStream_t)hip_stream);
-  return generic_forward(*desc, q, k, v, omega_rf, sigma, gate_w, gate_b, scale_w, out, (float *)saved,
-                         (float *)workspace, (hipStream_t)hip_stream);
+  return wersa::forward_checked(desc, q, k, v, omega_rf, sigma, gate_w, gate_b, scale_w, out, saved, workspace,
+                                workspace_bytes, hip_stream, nullptr);
 }
 
 wersa_status wersa_backward(const wersa_desc *desc, const void *q, const void *k, const void *v,

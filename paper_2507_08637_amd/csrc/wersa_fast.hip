@@ -1690,7 +1690,7 @@ template <int DH>
 wersa_status fast_forward_t(const wersa_desc &c, const bf16_t *q, const bf16_t *k, const bf16_t *v,
                             const bf16_t *omega, const float *sigma, const float *gate_w,
                             const float *gate_b, const float *scale_w, bf16_t *out, float *saved,
-                            float *ws, hipStream_t st) {
+                            float *ws, hipStream_t st, const PooledSums *pooled) {
   const FastPlan p = fast_plan(c);
   const FastWs w = fast_ws(c, p, 0, ws, saved);
   const SavedLayout sv = saved_layout(c);
@@ -1705,11 +1705,21 @@ wersa_status fast_forward_t(const wersa_desc &c, const bf16_t *q, const bf16_t *
   WERSA_STAGE("wersa_setup", st,
               setup_kernel<<<(nmat * c.d * c.m + 255) / 256, 256, 0, st>>>(sigma, c.bw_floor, omega, c.d, c.m, nmat,
                                                                            w.scalars, w.omT));
-  WERSA_STAGE("wersa_qbar", st,
-              qbar_partial_kernel<DH><<<dim3(p.chunksQ, slices), 256, 0, st>>>(q, tv, c.n, p.rowsQ, w.qpart));
-  WERSA_STAGE("gate_fwd_kernel", st,
-              gate_fwd_kernel<<<slices, 256, 0, st>>>(w.qpart, p.chunksQ, c.n, c.d, c.L, c.H, gate_w, gate_b,
-                                                     scale_w, qbar, s, F, w.coef, (c.flags & WERSA_FLAG_POOLED_GATE) ? 1 : 0));
+  if (pooled && c.n % 128 == 0) {
+    // the caller's column sums per 128 token rows: batch b owns row blocks [b n/128, (b+1) n/128)
+    const int chunks = c.n / 128;
+    WERSA_STAGE("gate_fwd_kernel", st,
+                gate_fwd_kernel<<<slices, 256, 0, st>>>(pooled->sums, chunks, c.n, c.d, c.L, c.H, gate_w, gate_b, scale_w,
+                                                       qbar, s, F, w.coef, (c.flags & WERSA_FLAG_POOLED_GATE) ? 1 : 0,
+                                                       PooledLayout{chunks * pooled->hidden, c.d, pooled->hidden}));
+  } else {
+    WERSA_STAGE("wersa_qbar", st,
+                qbar_partial_kernel<DH><<<dim3(p.chunksQ, slices), 256, 0, st>>>(q, tv, c.n, p.rowsQ, w.qpart));
+    WERSA_STAGE("gate_fwd_kernel", st,
+                gate_fwd_kernel<<<slices, 256, 0, st>>>(w.qpart, p.chunksQ, c.n, c.d, c.L, c.H, gate_w, gate_b, scale_w,
+                                                       qbar, s, F, w.coef, (c.flags & WERSA_FLAG_POOLED_GATE) ? 1 : 0,
+                                                       PooledLayout{(int64_t)c.H * p.chunksQ * c.d, (int64_t)p.chunksQ * c.d, c.d}));
+  }
   if (DH != 64) {   // head dimension 64 runs stage A inside the kernels that consume X_F
     WERSA_STAGE("wersa_haar_stage", st,
                 haar_stage_kernel<DH><<<dim3((c.n + 63) / 64, slices), 256, 0, st>>>(q, tv, c.n, w.coef, QF));
@@ -1792,14 +1802,14 @@ size_t fast_workspace_bytes(const wersa_desc &c, int for_backward) {
 wersa_status fast_forward(const wersa_desc &c, const void *q, const void *k, const void *v,
                           const void *omega_rf, const float *sigma, const float *gate_w,
                           const float *gate_b, const float *scale_w, void *out, float *saved,
-                          float *ws, hipStream_t st) {
+                          float *ws, hipStream_t st, const PooledSums *pooled) {
   if (c.d == 64)
     return fast_forward_t<64>(c, (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,
                               (const bf16_t *)omega_rf, sigma, gate_w, gate_b, scale_w, (bf16_t *)out,
-                              saved, ws, st);
+                              saved, ws, st, pooled);
   return fast_forward_t<128>(c, (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,
                              (const bf16_t *)omega_rf, sigma, gate_w, gate_b, scale_w, (bf16_t *)out,
-                             saved, ws, st);
+                             saved, ws, st, pooled);
 }
 
 wersa_status fast_backward(const wersa_desc &c, const void *q, const void *k, const void *v,

@@ -640,7 +640,8 @@ wersa_status forward_t(const wersa_desc &c, const T *q, const T *k, const T *v, 
   // step 4: pooled query and gate
   launch_colsum<T>(q, tv, slices, c.n, c.d, nullptr, w.qpart, nullptr, 1.f, st);
   WERSA_STAGE("gate_fwd_kernel", st, gate_fwd_kernel<<<slices, 256, 0, st>>>(w.qpart, colsum_chunks(c.n), c.n, c.d, c.L, c.H, gate_w,
-                                         gate_b, scale_w, qbar, s, F, nullptr, (c.flags & WERSA_FLAG_POOLED_GATE) ? 1 : 0));
+                                         gate_b, scale_w, qbar, s, F, nullptr, (c.flags & WERSA_FLAG_POOLED_GATE) ? 1 : 0,
+                                         PooledLayout{(int64_t)c.H * colsum_chunks(c.n) * c.d, (int64_t)colsum_chunks(c.n) * c.d, c.d}));
   // steps 3, 5, 6: gated Haar filter of Q and K
   launch_haar<T>(c, q, tv, w.QF, F, w.deepA, st);
   launch_haar<T>(c, k, tv, w.KF, F, w.deepA, st);

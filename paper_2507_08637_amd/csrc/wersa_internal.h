@@ -112,10 +112,23 @@ wersa_status generic_backward(const wersa_desc &c, const void *q, const void *k,
                               float *dgate_w, float *dgate_b, float *dscale_w, float *dsigma,
                               float *ws, hipStream_t st);
 size_t fast_workspace_bytes(const wersa_desc &c, int for_backward);
+// Column sums of Q over 128-row blocks computed by the caller (the attention block's W^Q GEMM
+// leaves them in its epilogue): sums[row block of (B*n)/128][H*d], float32.  When given to the
+// MFMA path's forward, the pass over Q that pools the queries is skipped.  Needs n % 128 == 0.
+struct PooledSums {
+  const float *sums;
+  int64_t hidden;
+};
 wersa_status fast_forward(const wersa_desc &c, const void *q, const void *k, const void *v,
                           const void *omega_rf, const float *sigma, const float *gate_w,
                           const float *gate_b, const float *scale_w, void *out, float *saved,
-                          float *ws, hipStream_t st);
+                          float *ws, hipStream_t st, const PooledSums *pooled = nullptr);
+// wersa_forward after validation of the descriptor and buffers, with the optional pooled sums.
+wersa_status forward_checked(const wersa_desc *desc, const void *q, const void *k, const void *v,
+                             const void *omega_rf, const float *sigma, const float *gate_w,
+                             const float *gate_b, const float *scale_w, void *out, void *saved,
+                             void *workspace, size_t workspace_bytes, void *hip_stream,
+                             const PooledSums *pooled);
 wersa_status fast_backward(const wersa_desc &c, const void *q, const void *k, const void *v,
                            const void *omega_rf, const float *sigma, const float *gate_w,
                            const float *scale_w, const void *out, const void *dout,
