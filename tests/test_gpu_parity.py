@@ -58,6 +58,7 @@ SMALL = [
     dict(B=2, H=2, n=203, d=32, L=3, m=48),     # n not a multiple of 2^L: zero padding of Algorithm 2 in-kernel
     dict(B=1, H=2, n=100, d=64, L=6, m=64),     # n between 2^L and 2^(L+1)
     dict(B=1, H=1, n=5, d=16, L=2, m=16),       # n barely above one block
+    dict(B=2, H=1, n=1, d=16, L=3, m=16),       # a single token: the block is all padding but one row
     # transforms deeper than one 64-row tile: two and three stages, ragged tiles at every stage
     dict(B=1, H=2, n=1000, d=32, L=8, m=32),    # blocks of 256 rows: 16 tiles, then 4 blocks of 4 tile coefficients
     dict(B=2, H=1, n=4177, d=48, L=12, m=32),   # 66 tiles -> 2 tiles at the second stage, one block of 4096 rows + tail
@@ -86,6 +87,15 @@ def test_small_shapes_forward_backward(shape, dtype):
         names = ("O", "dQ", "dK", "dV")
         scale = float(np.linalg.norm(ref["dQ"]) * np.linalg.norm(p["Q"]))
         assert float(res["domega"].abs().max().cpu()) < 1e-3 * scale
+    if shape["n"] == 1:
+        # One token: O = V whatever Q and K are (numerator and normaliser carry the same single
+        # feature product), so every gradient but dV is an eps-order remainder of terms that
+        # cancel.  Require those to be tiny against dV instead of comparing noise with noise.
+        names = ("O", "dV")
+        scale = float(np.linalg.norm(ref["dV"]))
+        for k in ("dQ", "dK", "dWg", "dbg", "domega"):
+            assert float(res[k].float().norm().cpu()) < 1e-3 * scale, k
+            assert float(np.linalg.norm(ref[k])) < 1e-3 * scale, k
     _check_all(res, ref, TOL[dtype], names=names, where=f"{shape} {dtype}")
 
 
@@ -99,6 +109,8 @@ MFMA_SHAPES = [
     dict(B=1, H=1, n=64, d=128, L=6, m=128),      # head dimension 128: column halves split over waves
     dict(B=2, H=2, n=832, d=128, L=6, m=512),     # 13 blocks, four operand chunks
     dict(B=1, H=2, n=1536, d=128, L=4, m=256),
+    dict(B=1, H=1, n=256, d=64, L=4, m=4096),     # maximum feature count: 16 operand chunks per row group
+    dict(B=6, H=8, n=128, d=64, L=5, m=128),      # 48 slices of two blocks: more workgroups than row groups
     # sequence lengths that are not multiples of the 64-row block: the last block is partial
     dict(B=2, H=2, n=1000, d=64, L=6, m=256),     # 15 full blocks + 40 rows
     dict(B=1, H=2, n=100, d=64, L=5, m=128),      # one full block + 36 rows

@@ -600,3 +600,73 @@ def test_layernorm_output_stage_properties_and_gradients():
     assert abs(fd - g["dsigma"]) < 5e-6 * max(1.0, abs(fd))
     closed = -(2.0 / p["sigma"]) * np.sum(np.sum(p["dO"] * O, axis=-1) * eps * rstd ** 2)
     np.testing.assert_allclose(g["dsigma"], closed, rtol=1e-7)
+
+
+def test_planted_mistakes_in_the_variants_are_caught(monkeypatch):
+    """The pins of the Algorithm 1 variants notice plausible mistakes planted into the oracle (on
+    the CPU): a LayerNorm backward without its projection terms, a LayerNorm with the unbiased
+    variance, a pooled gate that averages the heads' logits instead of summing them, and a key
+    side that silently keeps the query-side random matrix."""
+    mod = wo
+
+    def expect_failure(pins):
+        failed = 0
+        for pin in pins:
+            try:
+                pin()
+            except AssertionError:
+                failed += 1
+        assert failed >= 1, "no pin noticed the planted mistake"
+
+    # 1. LayerNorm backward as a plain row scaling (mean and projection terms dropped)
+    real_bwd = mod.backward_slice
+
+    def bwd_ln_scaling_only(*args, **kw):
+        if not kw.get("layernorm"):
+            return real_bwd(*args, **kw)
+        dO = args[11]
+        return real_bwd(*args[:11], dO - 0.0 * dO, **dict(kw, layernorm=False))   # the plain path's gradients
+    monkeypatch.setattr(mod, "backward_slice", bwd_ln_scaling_only)
+    expect_failure([test_layernorm_output_stage_properties_and_gradients])
+    monkeypatch.setattr(mod, "backward_slice", real_bwd)
+
+    # 2. LayerNorm with the unbiased variance (divide by d - 1)
+    real_fwd = mod.forward_slice
+
+    def fwd_ln_unbiased(*args, **kw):
+        f = real_fwd(*args, **kw)
+        if kw.get("layernorm") or (len(args) > 14 and args[14]):
+            f = dict(f)
+            N, eps = f["N"], args[9]
+            d = N.shape[1]
+            var = N.var(axis=1, ddof=1)
+            f["D"] = 1.0 / np.sqrt(var + eps)
+            f["O"] = (N - N.mean(axis=1, keepdims=True)) * f["D"][:, None]
+        return f
+    monkeypatch.setattr(mod, "forward_slice", fwd_ln_unbiased)
+    expect_failure([test_layernorm_output_stage_properties_and_gradients])
+    monkeypatch.setattr(mod, "forward_slice", real_fwd)
+
+    # 3. pooled gate that averages the heads' logits instead of summing them
+    real_pg = mod.pooled_gate
+
+    def pooled_gate_mean(Qb, Wg, bg, omega):
+        qbars, lg, s, F = real_pg(Qb, Wg, bg, omega)
+        lg = lg / Qb.shape[0]
+        s = 1.0 / (1.0 + np.exp(-lg))
+        return qbars, lg, s, s * omega
+    monkeypatch.setattr(mod, "pooled_gate", pooled_gate_mean)
+    expect_failure([test_pooled_gate_definition_special_cases_and_gradients])
+    monkeypatch.setattr(mod, "pooled_gate", real_pg)
+
+    # 4. key side keeps the query-side random matrix
+    def fwd_ignores_key_matrix(*args, **kw):
+        kw = dict(kw)
+        kw["Omega_K"] = None
+        args = list(args)
+        if len(args) > 12:
+            args[12] = None
+        return real_fwd(*args, **kw)
+    monkeypatch.setattr(mod, "forward_slice", fwd_ignores_key_matrix)
+    expect_failure([test_separate_key_matrix_explicit_kernel_and_gradients])
+    monkeypatch.setattr(mod, "forward_slice", real_fwd)
