@@ -59,7 +59,8 @@ typedef enum { WERSA_F32 = 0, WERSA_BF16 = 1 } wersa_dtype;
 
 /* desc.flags bits. By default the library picks the MFMA path (bf16 storage, fp16/bf16 matrix
  * cores, float32 accumulation) when the shape allows it: dtype bf16, d in {64, 128},
- * m % 128 == 0, L <= 6, strides multiples of 8 elements (any n); otherwise the generic
+ * m % 128 == 0, L <= 6 (L <= 20 with d == 64 and n % 64 == 0), strides multiples of 8 elements
+ * (any n); otherwise the generic
  * float32-arithmetic path. WERSA_FLAG_GENERIC_PATH forces the generic path. */
 #define WERSA_FLAG_GENERIC_PATH 1
 /* Separate random matrices for the query and the key side (Algorithm 1 draws W_Q^rand and
@@ -84,8 +85,8 @@ typedef enum { WERSA_F32 = 0, WERSA_BF16 = 1 } wersa_dtype;
  * Any n is accepted: the Haar filter is local to aligned blocks of 2^L rows, so Algorithm 2's
  * zero padding to the next power of two and the trim after the inverse are the same as reading
  * the rows past n of the last block as zeros and not writing them (done in-kernel; the pooled
- * query averages the n real rows). L > 6 (blocks longer than one 64-row tile) runs on the
- * generic path: six levels inside the tiles, the rest on the tiles' approximation coefficients.
+ * query averages the n real rows). L > 6 (blocks longer than one 64-row tile): six levels run
+ * inside the tiles, the rest on per-tile sums.
  */
 typedef struct {
   int32_t B, H, n, d, L, m;

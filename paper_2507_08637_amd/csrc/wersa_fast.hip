@@ -254,7 +254,7 @@ __global__ __launch_bounds__(256) void haar_stage_kernel(const bf16_t *x, View v
   __shared__ float cf[8];
   const int slice = blockIdx.y, t0 = blockIdx.x * 64;
   const int tid = threadIdx.x;
-  if (tid < 8) cf[tid] = coef[slice * 8 + tid];
+  if (tid < 8) cf[tid] = coef[slice * kCoefStride + tid];
   const bf16_t *xs = x + v.slice_base(slice);
   for (int e = tid; e < 64 * CPR; e += 256) {
     const int r = e / CPR, cc = e % CPR;
@@ -422,9 +422,11 @@ __device__ __forceinline__ bf16x8 tile_cols_operand(const bf16_t *tile, int stri
 // Head dimension 64 (FUSE): `xf` is not read; the rows of X (Q or K, bf16, view vx) are staged
 // raw and each step starts with X_F = G X for its tile, one 32 x 32 quarter per wave, written
 // to LDS in fp16 for the projection.
-template <int DH, int FW, bool PREP, bool RAGGED>   // RAGGED: n % 64 != 0, rows past n count as zeros with weight 0
+// RAGGED: n % 64 != 0, rows past n count as zeros with weight 0.  DEEP: L > 6, the filter's levels
+// above 6 enter as the per-tile addend tile_add [slices][n / 64][DH] (the accumulators of X_F start there).
+template <int DH, int FW, bool PREP, bool RAGGED, bool DEEP>
 __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
-    const _Float16 *xf, const bf16_t *xraw, View vx, const float *coef,
+    const _Float16 *xf, const bf16_t *xraw, View vx, const float *coef, const float *tile_add,
     const bf16_t *y, View vy, const float *rowdiv, const float *w,
     const bf16_t *orows, float *dDout, float *dDpart,
     const _Float16 *omT, int n, int m, int rows_per_chunk, float *Spart, float *zpart) {
@@ -468,7 +470,7 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
   const bf16_t *xrs = FUSE ? xraw + vx.slice_base(slice) : nullptr;
   const bf16_t *ys = y + vy.slice_base(slice);
   const float *rd = rowdiv ? rowdiv + (int64_t)slice * n : nullptr;
-  if (FUSE) build_filter_table(gt, coef + slice * 8, tid, 256);   // visible after the first barrier below
+  if (FUSE) build_filter_table(gt, coef + slice * kCoefStride, tid, 256);   // visible after the first barrier below
   const float *ws = w ? w + (int64_t)slice * n : nullptr;
 
   // X_F and Y pieces are taken row-major (coalesced) and stored as they are; the Y operand
@@ -573,6 +575,11 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
       // X_F^T quarter: columns 32 (wave % 2) .. + 31 of the tile, rows 32 (wave / 2) .. + 31.
       const bf16_t *raw = reinterpret_cast<const bf16_t *>(&xt[buf][0]);
       f32x16 q = zero16(), q2 = zero16();
+      if (DEEP) {   // register i is column 32 (wave % 2) + acc_row(i, h) for every row of the quarter
+        const float *ta = tile_add + ((int64_t)slice * (n / 64) + (t_begin / 64 + s)) * DH + 32 * (wave & 1);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) q[i] = ta[acc_row(i, h)];
+      }
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
         const bf16x8 xa = tile_cols_operand<false>(raw, XS, 32 * (wave & 1), ks, lane);
@@ -727,7 +734,10 @@ __global__ __launch_bounds__(256) void reduce_contract_kernel(const float *Spart
 // LN (MODE 0): LayerNorm over the columns of a row instead of the normaliser.  RAGGED: n is not a
 // multiple of 64; rows past n of the last block read as zeros (clamped address, value replaced)
 // and that block's output goes through a side buffer.  The plain instance has none of that code.
-template <int DH, int MODE, int NW, int MC, bool LN, bool RAGGED>
+// DEEP: L > 6 (head dimension 64, whole blocks): X_F starts from the per-tile addend of the levels
+// above 6 (tile_add [slices][n / 64][DH]); the gradient modes also write the 64-row sums of dX_F
+// per column (tile_gsum, same shape) and leave band 6 of their partials as u_6 alone.
+template <int DH, int MODE, int NW, int MC, bool LN, bool RAGGED, bool DEEP>
 __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
     const _Float16 *xf,        // X_F fp16 [slices][n][DH] (head dimension 128; with 64 it is formed here)
     const bf16_t *x, View vx,  // X (Q or K): band inner products (MODE 1, 2); source of X_F (head dimension 64)
@@ -744,7 +754,8 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
     bf16_t *out0, View vo,     // O (MODE 0) / dQ or dK (MODE 1, 2) / dV (MODE 3)
     float *Dout,               // D (MODE 0)
     float *partF, int L,       // [slices][gridDim.x][L+1] band partials (MODE 1, 2)
-    bf16_t *tail_out, float *tail_D)   // partial last block: its 64 output rows [slices][64][DH] and D [slices][64]
+    bf16_t *tail_out, float *tail_D,   // partial last block: its 64 output rows [slices][64][DH] and D [slices][64]
+    const float *tile_add, float *tile_gsum)   // DEEP (see above)
 {
   constexpr int KS = DH / 16, CT = DH / 32;
   constexpr int KSX = KS + 1;           // k-steps of the dPhi MFMA incl. the rank-one extension
@@ -856,10 +867,10 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
   float cf[kTileBands];
   if (IS_GRAD) {
 #pragma unroll
-    for (int l = 0; l < kTileBands; ++l) cf[l] = coef[slice * 8 + l];
+    for (int l = 0; l < kTileBands; ++l) cf[l] = coef[slice * kCoefStride + l];
   }
 
-  if (FUSE) build_filter_table(s_T, coef + slice * 8, tid, NT);
+  if (FUSE) build_filter_table(s_T, coef + slice * kCoefStride, tid, NT);
   if (nchunks == 1) stage(0);
   if (FUSE || nchunks == 1) __syncthreads();
 
@@ -1022,7 +1033,16 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
       for (int c0 = 0; c0 < CT; c0 += CG) {
         f32x16 q[CG][2];
 #pragma unroll
-        for (int cg = 0; cg < CG; ++cg) q[cg][0] = q[cg][1] = zero16();
+        for (int cg = 0; cg < CG; ++cg) {
+          q[cg][0] = zero16();
+          if (DEEP) {
+            // register i stands for column 32 ct + (acc_row(i, h) with bits 2 and 3 swapped), every lane's row alike
+            const float *ta = tile_add + ((int64_t)slice * (n / 64) + t0 / 64) * DH + 32 * (c0 + cg);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) q[cg][0][i] = ta[16 * (i >> 3) + 8 * h + 4 * ((i >> 2) & 1) + (i & 3)];
+          }
+          q[cg][1] = q[cg][0];
+        }
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
           bf16x8 gop[2][2];
@@ -1344,6 +1364,8 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
       }
       const float g6 = g5[0] + g5[1], x6 = x5[0] + x5[1];
       u[6] = fmaf(0.5f * g6, x6, u[6]);
+      // both half-waves hold the same sum and write the same value: no branch around the store
+      if (DEEP) tile_gsum[((int64_t)slice * (n / 64) + t0 / 64) * DH + 32 * ct + l32] = g6;
       const float T6 = cf[6] * g6;
       __builtin_amdgcn_wave_barrier();
       // ---- pass 2: filtered gradient, top-down (block sums of g rebuilt), bf16 into the tile
@@ -1397,28 +1419,34 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
   }
   __syncthreads();
   if (tid <= L) {
+    // DEEP: levels above 6 are not seen here; band 6 keeps u_6 alone (its -u_7, and the bands
+    // above, come from the tile-sum kernel in one extra row of the partials), bands above get 0.
     float ul = 0.f, ul1 = 0.f;
-    for (int wv = 0; wv < NW; ++wv) {
-      ul += s_wave[wv * 8 + tid];
-      if (tid < L) ul1 += s_wave[wv * 8 + tid + 1];
-    }
-    partF[((int64_t)slice * gridDim.x + blockIdx.x) * (L + 1) + tid] = tid < L ? ul - ul1 : ul;
+    if (tid < kTileBands)
+      for (int wv = 0; wv < NW; ++wv) {
+        ul += s_wave[wv * 8 + tid];
+        if (tid < L && tid + 1 < kTileBands) ul1 += s_wave[wv * 8 + tid + 1];
+      }
+    const int rows = DEEP ? gridDim.x + 1 : gridDim.x;
+    partF[((int64_t)slice * rows + blockIdx.x) * (L + 1) + tid] = tid < L ? ul - ul1 : ul;
   }
 }
 
-// dQ[t][:] += dqbar / n  (the pooled-query path), bf16 read-modify-write with 16-byte accesses,
-// four independent pieces per thread.
-template <int DH>
+// dX[t][:] += dqbar / n (the pooled-query path; dqbar may be nullptr) + tile_add[t / 64][:] (the
+// part of the gated filter above level 6; may be nullptr), bf16 read-modify-write with 16-byte
+// accesses, four independent pieces per thread.
+template <int DH, bool TILE>   // TILE: tile_add is given (the plain instance has none of its code)
 __global__ __launch_bounds__(256) void add_pooled_kernel(bf16_t *dq, View v, const float *dqbar, int n,
-                                                        float inv_n) {
+                                                        float inv_n, const float *tile_add) {
   constexpr int CPR = DH / 8;
   const int slice = blockIdx.y;
   const int64_t total = (int64_t)n * CPR;
   const int64_t e0 = (int64_t)blockIdx.x * 1024 + threadIdx.x;
   const int cc = threadIdx.x % CPR;   // 256 and 1024 are multiples of CPR: same columns for all four
+  const int ntiles = (n + 63) / 64;
   float add[8];
 #pragma unroll
-  for (int q = 0; q < 8; ++q) add[q] = dqbar[(int64_t)slice * DH + cc * 8 + q] * inv_n;
+  for (int q = 0; q < 8; ++q) add[q] = (!TILE || dqbar) ? dqbar[(int64_t)slice * DH + cc * 8 + q] * inv_n : 0.f;
   bf16_t *base = dq + v.slice_base(slice) + cc * 8;
   u16x8 val[4];
 #pragma unroll
@@ -1430,10 +1458,117 @@ __global__ __launch_bounds__(256) void add_pooled_kernel(bf16_t *dq, View v, con
   for (int u = 0; u < 4; ++u) {
     const int64_t e = e0 + 256 * u;
     if (e < total) {
+      const int64_t row = e / CPR;
+      const float *ta = TILE ? tile_add + ((int64_t)slice * ntiles + (row >> 6)) * DH + cc * 8 : nullptr;
 #pragma unroll
-      for (int q = 0; q < 8; ++q) val[u][q] = f32_to_bf16(bf16_to_f32(val[u][q]) + add[q]);
-      *reinterpret_cast<u16x8 *>(base + (e / CPR) * v.sn) = val[u];
+      for (int q = 0; q < 8; ++q)
+        val[u][q] = f32_to_bf16(bf16_to_f32(val[u][q]) + add[q] + (TILE ? ta[q] : 0.f));
+      *reinterpret_cast<u16x8 *>(base + row * v.sn) = val[u];
     }
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// Transforms deeper than one 64-row block (L > 6, head dimension 64).  In block-mean form the
+// levels above 6 add, to every row of a tile, coef_l times the sum of X over the 2^l-row block
+// that holds the tile: a per-(tile, column) addend built from the tile sums.
+// Pyramid of one signal: level j (1 .. J) holds the sums over 2^j consecutive tiles,
+// [ceil(ntiles / 2^j)][64], levels packed one after the other in P (< ntiles + J rows).
+// One workgroup of 1024 threads; thread (column c = tid % 64, group g = tid / 64 of kCoarseGroups);
+// the loops over tiles carry no dependency and are unrolled so that several loads are in flight.
+// ------------------------------------------------------------------------------------
+constexpr int kCoarseGroups = 16;
+__device__ __forceinline__ void build_tile_pyramid(const float *T, int ntiles, int J, float *P, int c, int g) {
+  const float *prev = T;
+  int nprev = ntiles;
+  float *cur = P;
+  for (int j = 1; j <= J; ++j) {
+    const int nb = (nprev + 1) / 2;
+#pragma unroll 4
+    for (int b = g; b < nb; b += kCoarseGroups)
+      cur[b * 64 + c] = prev[2 * b * 64 + c] + (2 * b + 1 < nprev ? prev[(2 * b + 1) * 64 + c] : 0.f);
+    __threadfence_block();
+    __syncthreads();
+    prev = cur;
+    nprev = nb;
+    cur += nb * 64;
+  }
+}
+// addend[tile][c] = sum over j of coef[6 + j] * P_j[tile >> j][c]
+__device__ __forceinline__ void tile_addend(const float *P, const float *coef, int ntiles, int J, float *A, int c, int g) {
+#pragma unroll 4
+  for (int tile = g; tile < ntiles; tile += kCoarseGroups) {
+    float acc = 0.f;
+    const float *lvl = P;
+    int nprev = ntiles;
+    for (int j = 1; j <= J; ++j) {
+      const int nb = (nprev + 1) / 2;
+      acc = fmaf(coef[6 + j], lvl[(tile >> j) * 64 + c], acc);
+      lvl += nb * 64;
+      nprev = nb;
+    }
+    A[tile * 64 + c] = acc;
+  }
+}
+constexpr int64_t pyramid_floats(int ntiles) { return ((int64_t)ntiles + 32) * 64; }
+
+// Forward: blockIdx.y = 0 for Q, 1 for K.  T*: tile sums [S][ntiles][64]; A*: addends, same shape;
+// pyr: 2 * S pyramids of pyramid_floats(ntiles).
+__global__ __launch_bounds__(64 * kCoarseGroups) void coarse_addend_kernel(const float *Tq, const float *Tk, const float *coef,
+                                                           int ntiles, int L, float *pyr, float *Aq, float *Ak) {
+  const int slice = blockIdx.x, side = blockIdx.y, c = threadIdx.x & 63, g = threadIdx.x >> 6;
+  const int64_t base = (int64_t)slice * ntiles * 64;
+  float *P = pyr + ((int64_t)slice * 2 + side) * pyramid_floats(ntiles);
+  build_tile_pyramid((side ? Tk : Tq) + base, ntiles, L - 6, P, c, g);
+  tile_addend(P, coef + slice * kCoefStride, ntiles, L - 6, (side ? Ak : Aq) + base, c, g);
+}
+
+// Backward, after both gradient kernels: Tg* = tile sums of dX_F (written by their epilogues),
+// Tx* = tile sums of X.  Writes the addends of dX (the filter is symmetric) and, into the extra
+// row `row` of the band partials part*[S][row + 1][L + 1], the contribution of the levels above
+// 6: with u_l = 2^-l * sum over 2^l-row blocks and columns of blocksum(dX_F) * blocksum(X),
+// band 6 gets -u_7, band l (7 .. L-1) gets u_l - u_{l+1}, band L gets u_L (the gradient kernels
+// leave u_6 alone in band 6 and zeros above).
+__global__ __launch_bounds__(64 * kCoarseGroups) void coarse_bwd_kernel(const float *TgQ, const float *TgK, const float *TxQ,
+                                                        const float *TxK, const float *coef, int ntiles, int L,
+                                                        float *pyr, float *AQ, float *AK, float *partQ,
+                                                        float *partK, int row) {
+  const int slice = blockIdx.x, side = blockIdx.y, c = threadIdx.x & 63, g = threadIdx.x >> 6, J = L - 6;
+  const int64_t base = (int64_t)slice * ntiles * 64;
+  float *Pg = pyr + (((int64_t)slice * 2 + side) * 2) * pyramid_floats(ntiles);
+  float *Px = Pg + pyramid_floats(ntiles);
+  build_tile_pyramid((side ? TgK : TgQ) + base, ntiles, J, Pg, c, g);
+  build_tile_pyramid((side ? TxK : TxQ) + base, ntiles, J, Px, c, g);
+  tile_addend(Pg, coef + slice * kCoefStride, ntiles, J, (side ? AK : AQ) + base, c, g);
+  __shared__ float red[kCoarseGroups];
+  __shared__ float u[kMaxBands + 1];
+  const float *lg = Pg, *lx = Px;
+  int nprev = ntiles;
+  for (int j = 1; j <= J; ++j) {
+    const int nb = (nprev + 1) / 2;
+    float acc = 0.f;
+#pragma unroll 4
+    for (int b = g; b < nb; b += kCoarseGroups) acc = fmaf(lg[b * 64 + c], lx[b * 64 + c], acc);
+    acc = wave_sum64(acc);
+    if (c == 0) red[g] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      float tot = 0.f;
+      for (int i = 0; i < kCoarseGroups; ++i) tot += red[i];
+      u[6 + j] = tot / (float)(1 << (6 + j));
+    }
+    __syncthreads();
+    lg += nb * 64;
+    lx += nb * 64;
+    nprev = nb;
+  }
+  if ((int)threadIdx.x <= L) {
+    const int i = threadIdx.x;
+    float val = 0.f;
+    if (i == 6) val = -u[7];
+    else if (i > 6) val = i < L ? u[i] - u[i + 1] : u[i];
+    float *part = side ? partK : partQ;
+    part[((int64_t)slice * (row + 1) + row) * (L + 1) + i] = val;
   }
 }
 
@@ -1529,6 +1664,10 @@ FastPlan fast_plan(const wersa_desc &c) {
   p.chunksQ = cq < 1 ? 1 : (cq > 512 ? 512 : cq);
   p.rowsQ = (c.n + p.chunksQ - 1) / p.chunksQ;
   p.chunksQ = (c.n + p.rowsQ - 1) / p.rowsQ;
+  if (c.L > kTileL) {   // the pooled-query partial sums double as the 64-row tile sums
+    p.rowsQ = 64;
+    p.chunksQ = blocks;
+  }
   int want = 512 / (slices * (c.m / p.MB));   // two resident workgroups per compute unit, one round
   if (want < 1) want = 1;
   if (want > blocks) want = blocks;
@@ -1554,6 +1693,9 @@ struct FastWs {
   bf16_t *Sx, *ST, *zb, *dSx, *dST, *dzb;
   bf16_t *dN;    // LayerNorm output stage: gradient with respect to the un-normalised rows
   float *ones;   // and the stand-in for D in the gradient kernels
+  // L > 6: tile sums of Q and K and the addends of the levels above 6 (saved buffer); tile sums
+  // of dQ_F and dK_F, the addends of dQ and dK, and the pyramids (workspace)
+  float *tileQ, *tileK, *addQ, *addK, *gsumQ, *gsumK, *gaddQ, *gaddK, *pyr;
   int64_t total;
 };
 
@@ -1571,7 +1713,15 @@ FastWs fast_ws(const wersa_desc &c, const FastPlan &p, int bwd, float *base, flo
     w.Sx = reinterpret_cast<bf16_t *>(saved + sv.Sx);
     w.ST = reinterpret_cast<bf16_t *>(saved + sv.ST);
     w.zb = reinterpret_cast<bf16_t *>(saved + sv.zb);
+    if (sv.tileQ >= 0) {
+      w.tileQ = saved + sv.tileQ;
+      w.tileK = saved + sv.tileK;
+      w.addQ = saved + sv.addQ;
+      w.addK = saved + sv.addK;
+    }
   }
+  const bool deep = c.L > kTileL;
+  const int ntiles = (c.n + 63) / 64;
   w.tail_out = reinterpret_cast<bf16_t *>(b.take(sl * 64 * c.d / 2));
   w.tail_D = b.take(sl * 64);
   w.qpart = b.take(sl * p.chunksQ * c.d);
@@ -1586,8 +1736,15 @@ FastWs fast_ws(const wersa_desc &c, const FastPlan &p, int bwd, float *base, flo
     w.dSx = reinterpret_cast<bf16_t *>(b.take(sl * mx / 2));
     w.dST = reinterpret_cast<bf16_t *>(b.take(sl * md / 2));
     w.dzb = reinterpret_cast<bf16_t *>(b.take(sl * c.m / 2));
-    w.partQ = b.take(sl * p.rowsWgsG * (c.L + 1));
-    w.partK = b.take(sl * p.rowsWgsG * (c.L + 1));
+    w.partQ = b.take(sl * (p.rowsWgsG + 1) * (c.L + 1));   // (+ one row: the levels above 6)
+    w.partK = b.take(sl * (p.rowsWgsG + 1) * (c.L + 1));
+    if (deep) {
+      const int64_t tiles = sl * ntiles * c.d;
+      w.gsumQ = b.take(tiles);
+      w.gsumK = b.take(tiles);
+      w.gaddQ = b.take(tiles);
+      w.gaddK = b.take(tiles);
+    }
     w.dF = b.take(sl * (c.L + 1));
     w.dlogit = b.take(sl * (c.L + 1));
     w.dqbar = b.take(sl * c.d);
@@ -1596,6 +1753,7 @@ FastWs fast_ws(const wersa_desc &c, const FastPlan &p, int bwd, float *base, flo
       w.ones = b.take(sl * c.n);
     }
   }
+  if (deep) w.pyr = b.take(sl * 4 * pyramid_floats(ntiles));
   w.total = b.off;
   return w;
 }
@@ -1638,7 +1796,8 @@ hipError_t launch_rows(const wersa_desc &c, const FastPlan &p, const _Float16 *x
     WERSA_STAGE(name, st,
                 kern<<<dim3(wgs, c.B * c.H), NW * 64, smem, st>>>(
                     xf, x, tv, y, yview ? *yview : tv, Dsaved, arow, omT, omega, Mx, MT, bb, w.coef, w.scalars,
-                    c.eps, c.n, c.m, groups, out0, tv, Dout, partF, c.L, w.tail_out, w.tail_D));
+                    c.eps, c.n, c.m, groups, out0, tv, Dout, partF, c.L, w.tail_out, w.tail_D,
+                    MODE >= 2 ? w.addK : w.addQ, MODE == 1 ? w.gsumQ : w.gsumK));
     if (c.n % 64 != 0)
       WERSA_STAGE("wersa_tail_copy", st,
                   tail_copy_kernel<DH><<<c.B * c.H, 256, 0, st>>>(w.tail_out, MODE == 0 ? w.tail_D : nullptr, c.n,
@@ -1646,14 +1805,22 @@ hipError_t launch_rows(const wersa_desc &c, const FastPlan &p, const _Float16 *x
     return hipSuccess;
   };
   const bool ln = MODE == 0 && (c.flags & WERSA_FLAG_LAYERNORM), ragged = c.n % 64 != 0;
-  if (ragged) {   // the shapes with a partial last block take the guarded instances
-    if (ln) return p.mc == 256 ? go(&rows_kernel<DH, MODE, NW, 256, MODE == 0, true>)
-                               : go(&rows_kernel<DH, MODE, NW, 128, MODE == 0, true>);
-    return p.mc == 256 ? go(&rows_kernel<DH, MODE, NW, 256, false, true>) : go(&rows_kernel<DH, MODE, NW, 128, false, true>);
+  if (DH == 64 && c.L > kTileL) {   // deeper than one block (whole blocks only, see fast_supported)
+    if (ln) return p.mc == 256 ? go(&rows_kernel<DH, MODE, NW, 256, MODE == 0, false, DH == 64>)
+                               : go(&rows_kernel<DH, MODE, NW, 128, MODE == 0, false, DH == 64>);
+    return p.mc == 256 ? go(&rows_kernel<DH, MODE, NW, 256, false, false, DH == 64>)
+                       : go(&rows_kernel<DH, MODE, NW, 128, false, false, DH == 64>);
   }
-  if (ln) return p.mc == 256 ? go(&rows_kernel<DH, MODE, NW, 256, MODE == 0, false>)
-                             : go(&rows_kernel<DH, MODE, NW, 128, MODE == 0, false>);
-  return p.mc == 256 ? go(&rows_kernel<DH, MODE, NW, 256, false, false>) : go(&rows_kernel<DH, MODE, NW, 128, false, false>);
+  if (ragged) {   // the shapes with a partial last block take the guarded instances
+    if (ln) return p.mc == 256 ? go(&rows_kernel<DH, MODE, NW, 256, MODE == 0, true, false>)
+                               : go(&rows_kernel<DH, MODE, NW, 128, MODE == 0, true, false>);
+    return p.mc == 256 ? go(&rows_kernel<DH, MODE, NW, 256, false, true, false>)
+                       : go(&rows_kernel<DH, MODE, NW, 128, false, true, false>);
+  }
+  if (ln) return p.mc == 256 ? go(&rows_kernel<DH, MODE, NW, 256, MODE == 0, false, false>)
+                             : go(&rows_kernel<DH, MODE, NW, 128, MODE == 0, false, false>);
+  return p.mc == 256 ? go(&rows_kernel<DH, MODE, NW, 256, false, false, false>)
+                     : go(&rows_kernel<DH, MODE, NW, 128, false, false, false>);
 }
 
 // orows != nullptr selects the backward form that derives dD from the rows of O itself;
@@ -1668,17 +1835,23 @@ void launch_contract(const wersa_desc &c, const FastPlan &p, const _Float16 *xf,
   const _Float16 *omT = w.omT + (((c.flags & WERSA_FLAG_SEPARATE_OMEGA) && key_side) ? (int64_t)c.d * c.m : 0);
   auto go = [&](auto kern) {
     WERSA_STAGE("wersa_phiT_contract", st,
-                kern<<<grid, 256, 0, st>>>(xf, xraw, View{c.stride_b, c.stride_h, c.stride_n, c.H}, w.coef, y, yv,
+                kern<<<grid, 256, 0, st>>>(xf, xraw, View{c.stride_b, c.stride_h, c.stride_n, c.H}, w.coef,
+                                           key_side ? w.addK : w.addQ, y, yv,
                                            rowdiv, wts, orows, w.dD, w.dDpart, omT, c.n, c.m, p.rowsC, w.Spart,
                                            w.zpart));
   };
-  const bool ragged = c.n % 64 != 0;
-  if (p.FW == 64) {
-    if (orows) ragged ? go(&phiT_contract_kernel<DH, 64, true, true>) : go(&phiT_contract_kernel<DH, 64, true, false>);
-    else ragged ? go(&phiT_contract_kernel<DH, 64, false, true>) : go(&phiT_contract_kernel<DH, 64, false, false>);
+  const bool ragged = c.n % 64 != 0, deep = DH == 64 && c.L > kTileL;
+  if (deep) {
+    if (p.FW == 64) orows ? go(&phiT_contract_kernel<DH, 64, true, false, DH == 64>)
+                          : go(&phiT_contract_kernel<DH, 64, false, false, DH == 64>);
+    else orows ? go(&phiT_contract_kernel<DH, 32, true, false, DH == 64>)
+               : go(&phiT_contract_kernel<DH, 32, false, false, DH == 64>);
+  } else if (p.FW == 64) {
+    if (orows) ragged ? go(&phiT_contract_kernel<DH, 64, true, true, false>) : go(&phiT_contract_kernel<DH, 64, true, false, false>);
+    else ragged ? go(&phiT_contract_kernel<DH, 64, false, true, false>) : go(&phiT_contract_kernel<DH, 64, false, false, false>);
   } else {
-    if (orows) ragged ? go(&phiT_contract_kernel<DH, 32, true, true>) : go(&phiT_contract_kernel<DH, 32, true, false>);
-    else ragged ? go(&phiT_contract_kernel<DH, 32, false, true>) : go(&phiT_contract_kernel<DH, 32, false, false>);
+    if (orows) ragged ? go(&phiT_contract_kernel<DH, 32, true, true, false>) : go(&phiT_contract_kernel<DH, 32, true, false, false>);
+    else ragged ? go(&phiT_contract_kernel<DH, 32, false, true, false>) : go(&phiT_contract_kernel<DH, 32, false, false, false>);
   }
   const int64_t W = (int64_t)c.m * DH;
   WERSA_STAGE("wersa_reduce_contract", st,
@@ -1705,7 +1878,8 @@ wersa_status fast_forward_t(const wersa_desc &c, const bf16_t *q, const bf16_t *
   WERSA_STAGE("wersa_setup", st,
               setup_kernel<<<(nmat * c.d * c.m + 255) / 256, 256, 0, st>>>(sigma, c.bw_floor, omega, c.d, c.m, nmat,
                                                                            w.scalars, w.omT));
-  if (pooled && c.n % 128 == 0) {
+  const bool deep = c.L > kTileL;   // (head dimension 64, whole blocks: see fast_supported)
+  if (pooled && c.n % 128 == 0 && !deep) {
     // the caller's column sums per 128 token rows: batch b owns row blocks [b n/128, (b+1) n/128)
     const int chunks = c.n / 128;
     WERSA_STAGE("gate_fwd_kernel", st,
@@ -1713,12 +1887,21 @@ wersa_status fast_forward_t(const wersa_desc &c, const bf16_t *q, const bf16_t *
                                                        qbar, s, F, w.coef, (c.flags & WERSA_FLAG_POOLED_GATE) ? 1 : 0,
                                                        PooledLayout{chunks * pooled->hidden, c.d, pooled->hidden}));
   } else {
+    // deep: one partial per 64-row tile, kept (with those of K) as the tile sums of the levels above 6
+    float *qpart = deep ? w.tileQ : w.qpart;
     WERSA_STAGE("wersa_qbar", st,
-                qbar_partial_kernel<DH><<<dim3(p.chunksQ, slices), 256, 0, st>>>(q, tv, c.n, p.rowsQ, w.qpart));
+                qbar_partial_kernel<DH><<<dim3(p.chunksQ, slices), 256, 0, st>>>(q, tv, c.n, p.rowsQ, qpart));
     WERSA_STAGE("gate_fwd_kernel", st,
-                gate_fwd_kernel<<<slices, 256, 0, st>>>(w.qpart, p.chunksQ, c.n, c.d, c.L, c.H, gate_w, gate_b, scale_w,
+                gate_fwd_kernel<<<slices, 256, 0, st>>>(qpart, p.chunksQ, c.n, c.d, c.L, c.H, gate_w, gate_b, scale_w,
                                                        qbar, s, F, w.coef, (c.flags & WERSA_FLAG_POOLED_GATE) ? 1 : 0,
                                                        PooledLayout{(int64_t)c.H * p.chunksQ * c.d, (int64_t)p.chunksQ * c.d, c.d}));
+  }
+  if (deep) {
+    WERSA_STAGE("wersa_qbar", st,
+                qbar_partial_kernel<DH><<<dim3(p.chunksQ, slices), 256, 0, st>>>(k, tv, c.n, p.rowsQ, w.tileK));
+    WERSA_STAGE("wersa_coarse_addend", st,
+                coarse_addend_kernel<<<dim3(slices, 2), 64 * kCoarseGroups, 0, st>>>(w.tileQ, w.tileK, w.coef, p.chunksQ, c.L, w.pyr,
+                                                                      w.addQ, w.addK));
   }
   if (DH != 64) {   // head dimension 64 runs stage A inside the kernels that consume X_F
     WERSA_STAGE("wersa_haar_stage", st,
@@ -1774,24 +1957,40 @@ wersa_status fast_backward_t(const wersa_desc &c, const bf16_t *q, const bf16_t 
   if (launch_rows<DH, 3>(c, p, KF, k, nullptr, nullptr, nullptr, w, omega, nullptr, w.dST, nullptr, dv,
                          nullptr, nullptr, st) != hipSuccess)
     return WERSA_ERR_LAUNCH;
+  const bool deep = c.L > kTileL;
+  if (deep)   // levels above 6: addends of dQ and dK and the bands' extra row, from the tile sums
+    WERSA_STAGE("wersa_coarse_bwd", st,
+                coarse_bwd_kernel<<<dim3(slices, 2), 64 * kCoarseGroups, 0, st>>>(w.gsumQ, w.gsumK, w.tileQ, w.tileK, w.coef,
+                                                                   (c.n + 63) / 64, c.L, w.pyr, w.gaddQ, w.gaddK,
+                                                                   w.partQ, w.partK, p.rowsWgsG));
   WERSA_STAGE("gate_bwd_slice_kernel", st,
-              gate_bwd_slice_kernel<<<slices, 64, 0, st>>>(w.partQ, w.partK, p.rowsWgsG, c.L, c.d, c.H, s,
-                                                           gate_w, scale_w, w.dF, w.dlogit, w.dqbar, (c.flags & WERSA_FLAG_POOLED_GATE) ? 1 : 0));
+              gate_bwd_slice_kernel<<<slices, 64, 0, st>>>(w.partQ, w.partK, deep ? p.rowsWgsG + 1 : p.rowsWgsG, c.L,
+                                                           c.d, c.H, s, gate_w, scale_w, w.dF, w.dlogit, w.dqbar,
+                                                           (c.flags & WERSA_FLAG_POOLED_GATE) ? 1 : 0));
   WERSA_STAGE("gate_bwd_params_kernel", st,
               gate_bwd_params_kernel<<<gate_bwd_params_blocks(c.H, c.L, c.d), 256, 0, st>>>(w.dF, w.dlogit, s, qbar, w.dDpart, slices * p.chunksC,
                                                         c.B, c.H, c.L, c.d, c.eps, w.scalars, dgate_w,
                                                         dgate_b, dscale_w, dsigma));
   const int64_t chunks = (int64_t)c.n * (DH / 8);
-  WERSA_STAGE("wersa_add_pooled", st,
-              add_pooled_kernel<DH><<<dim3((unsigned)((chunks + 1023) / 1024), slices), 256, 0, st>>>(
-                  dq, tv, w.dqbar, c.n, 1.0f / (float)c.n));
+  const dim3 agrid((unsigned)((chunks + 1023) / 1024), slices);
+  if (deep) {
+    WERSA_STAGE("wersa_add_pooled", st,
+                (add_pooled_kernel<DH, true><<<agrid, 256, 0, st>>>(dq, tv, w.dqbar, c.n, 1.0f / (float)c.n, w.gaddQ)));
+    WERSA_STAGE("wersa_add_pooled", st,
+                (add_pooled_kernel<DH, true><<<agrid, 256, 0, st>>>(dk, tv, nullptr, c.n, 0.f, w.gaddK)));
+  } else {
+    WERSA_STAGE("wersa_add_pooled", st,
+                (add_pooled_kernel<DH, false><<<agrid, 256, 0, st>>>(dq, tv, w.dqbar, c.n, 1.0f / (float)c.n, nullptr)));
+  }
   return hipGetLastError() == hipSuccess ? WERSA_OK : WERSA_ERR_LAUNCH;
 }
 
 }  // namespace
 
 bool fast_supported(const wersa_desc &c) {
-  return c.dtype == WERSA_BF16 && (c.d == 64 || c.d == 128) && c.m % 128 == 0 && c.L <= kTileL &&
+  // transforms deeper than one 64-row block: head dimension 64 and whole blocks only
+  const bool levels_ok = c.L <= kTileL || (c.d == 64 && c.n % 64 == 0);
+  return c.dtype == WERSA_BF16 && (c.d == 64 || c.d == 128) && c.m % 128 == 0 && levels_ok &&
          c.stride_n % 8 == 0 && c.stride_h % 8 == 0 && c.stride_b % 8 == 0;
 }
 

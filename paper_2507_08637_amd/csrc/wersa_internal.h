@@ -12,6 +12,7 @@ constexpr int kTileL = 6;                 // Haar levels inside one 64-row tile
 constexpr int kTileBands = kTileL + 1;
 constexpr int kMaxL = 20;                 // deepest transform (levels above 6 run on tile approximations)
 constexpr int kMaxBands = kMaxL + 1;
+constexpr int kCoefStride = 24;           // block-mean coefficients per slice (levels 0 .. kMaxL, padded)
 
 // Strided view of a (B, H, n, d) tensor; element (b, h, t, j) at b*sb + h*sh + t*sn + j.
 struct View {
@@ -53,6 +54,9 @@ struct SavedLayout {
   // MFMA path only: per-call constants and bf16 operand copies written by the forward and
   // read again by the backward (scalars, filter coefficients, Omega^T fp16, (S|z), S^T, z).
   int64_t scalars, coef, omT, Sx, ST, zb;
+  // MFMA path with L > 6: sums of Q and K over 64-row tiles [S][n/64][d] and the per-tile
+  // addends of the levels above 6 (same shape), kept for the backward.
+  int64_t tileQ, tileK, addQ, addK;
 };
 inline SavedLayout saved_layout(const wersa_desc &c) {
   SavedLayout o;
@@ -66,6 +70,7 @@ inline SavedLayout saved_layout(const wersa_desc &c) {
   o.F = off;    off += up(sl * (c.L + 1));
   o.D = off;    off += up(sl * c.n);
   o.QF = o.KF = o.scalars = o.coef = o.omT = o.Sx = o.ST = o.zb = -1;
+  o.tileQ = o.tileK = o.addQ = o.addK = -1;
   if (use_fast(c)) {
     if (c.d != 64) {  // filtered Q and K in fp16, kept for the backward (head dimension 64 re-forms them from Q, K)
       o.QF = off; off += up(sl * c.n * c.d / 2);
@@ -73,11 +78,18 @@ inline SavedLayout saved_layout(const wersa_desc &c) {
     }
     const int64_t md = (int64_t)c.m * c.d, mx = (int64_t)c.m * (c.d + 16);
     o.scalars = off; off += 64;
-    o.coef = off;    off += up(sl * 8);
+    o.coef = off;    off += up(sl * kCoefStride);
     o.omT = off;     off += up(md / 2 * ((c.flags & WERSA_FLAG_SEPARATE_OMEGA) ? 2 : 1));
     o.Sx = off;      off += up(sl * mx / 2);
     o.ST = off;      off += up(sl * md / 2);
     o.zb = off;      off += up(sl * c.m / 2);
+    if (c.L > kTileL) {
+      const int64_t tiles = sl * ((c.n + 63) / 64) * c.d;
+      o.tileQ = off; off += up(tiles);
+      o.tileK = off; off += up(tiles);
+      o.addQ = off;  off += up(tiles);
+      o.addK = off;  off += up(tiles);
+    }
   }
   o.total = off;
   return o;

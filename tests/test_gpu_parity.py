@@ -350,7 +350,8 @@ def test_layernorm_output_stage(path):
 
 @pytest.mark.parametrize("shape", [dict(B=1, H=2, n=1024, d=64, L=5, m=256),
                                    dict(B=2, H=1, n=832, d=128, L=6, m=256),
-                                   dict(B=1, H=2, n=1000, d=64, L=5, m=256)])   # partial last block
+                                   dict(B=1, H=2, n=1000, d=64, L=5, m=256),    # partial last block
+                                   dict(B=1, H=2, n=1024, d=64, L=8, m=256)])   # transform deeper than one block
 def test_layernorm_output_stage_mfma_shapes(shape):
     """The LayerNorm output stage on the other MFMA kernel variants: 256-feature operand blocks
     (d = 64) and the head dimension 128."""
@@ -373,12 +374,37 @@ def test_layernorm_output_stage_mfma_shapes(shape):
     assert abs(float(res["dsigma"].cpu()) - ref["dsigma"]) < 5e-2 * abs(ref["dsigma"])
 
 
-def test_deep_transform_on_an_mfma_shape_takes_the_generic_path():
-    """L > 6 on a shape the MFMA path would otherwise take: the default selection falls back to
-    the generic path (the MFMA kernels hold one 64-row block per wave) and meets the bf16 bar."""
+@pytest.mark.parametrize("shape", [dict(B=1, H=2, n=1024, d=64, L=8, m=256),      # 16 tiles, blocks of 4 tiles
+                                   dict(B=2, H=1, n=4160, d=64, L=12, m=128),     # 65 tiles: one 4096-row block + one tile
+                                   dict(B=1, H=1, n=8192, d=64, L=13, m=256),     # one block of 128 tiles
+                                   dict(B=1, H=2, n=640, d=64, L=7, m=128)])      # 10 tiles, pairs
+def test_deep_transform_on_the_mfma_path(shape):
+    """L > 6 with head dimension 64 and whole 64-row blocks stays on the MFMA path: levels up to
+    6 inside the kernels, the levels above as per-tile addends built from the tile sums (and,
+    backwards, from the tile sums of dX_F, with their share of the band inner products)."""
     import torch
     from paper_2507_08637_amd import binding
-    cfg = dict(B=1, H=2, n=2048, d=64, L=9, m=128, dtype="bf16", flavour="plain", seed_base=3700, q_mean=0.3)
+    cfg = dict(shape, dtype="bf16", flavour="plain", seed_base=3800, q_mean=0.3)
+    probe = torch.empty(cfg["B"], cfg["H"], cfg["n"], cfg["d"], dtype=torch.bfloat16, device="cuda")
+    assert binding.wersa_path_name(binding.make_desc(probe, cfg["L"], cfg["m"])) == "mfma"
+    p = workloads.make_inputs(**cfg)
+    res = hp.gpu_forward_backward(p, cfg)
+    ref = hp.oracle_backward(p, cfg)
+    _check_mfma(res, ref, p, cfg, where=f"deep mfma {shape}")
+    fwd = hp.oracle_forward(p, cfg)
+    sl = cfg["B"] * cfg["H"]
+    for name in ("qbar", "s", "F", "S", "z", "D"):
+        r = fwd[name].reshape((sl,) + fwd[name].shape[2:])
+        assert hp.rel_err(res["saved"][name], r) < 2e-2, name
+
+
+def test_deep_transform_on_an_mfma_shape_takes_the_generic_path():
+    """L > 6 on a shape of the MFMA path with head dimension 128: the default selection falls back
+    to the generic path (deep transforms on the MFMA path need head dimension 64 and whole blocks)
+    and meets the bf16 bar."""
+    import torch
+    from paper_2507_08637_amd import binding
+    cfg = dict(B=1, H=2, n=1024, d=128, L=9, m=128, dtype="bf16", flavour="plain", seed_base=3700, q_mean=0.3)
     probe = torch.empty(cfg["B"], cfg["H"], cfg["n"], cfg["d"], dtype=torch.bfloat16, device="cuda")
     assert binding.wersa_path_name(binding.make_desc(probe, cfg["L"], cfg["m"])) == "generic"
     assert binding.wersa_path_name(binding.make_desc(probe, 6, cfg["m"])) == "mfma"
