@@ -1427,7 +1427,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
         ul += s_wave[wv * 8 + tid];
         if (tid < L && tid + 1 < kTileBands) ul1 += s_wave[wv * 8 + tid + 1];
       }
-    const int rows = DEEP ? gridDim.x + 1 : gridDim.x;
+    const int rows = DEEP ? gridDim.x + 4 : gridDim.x;   // (four extra rows: the tile-sum kernel's column quarters)
     partF[((int64_t)slice * rows + blockIdx.x) * (L + 1) + tid] = tid < L ? ul - ul1 : ul;
   }
 }
@@ -1459,10 +1459,18 @@ __global__ __launch_bounds__(256) void add_pooled_kernel(bf16_t *dq, View v, con
     const int64_t e = e0 + 256 * u;
     if (e < total) {
       const int64_t row = e / CPR;
-      const float *ta = TILE ? tile_add + ((int64_t)slice * ntiles + (row >> 6)) * DH + cc * 8 : nullptr;
+      float tadd[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      if (TILE) {   // two 16-byte loads of the tile's addend (32-byte aligned: DH and 8 cc are multiples of 8)
+        const f32x4 *ta = reinterpret_cast<const f32x4 *>(tile_add + ((int64_t)slice * ntiles + (row >> 6)) * DH + cc * 8);
+        const f32x4 t0 = ta[0], t1 = ta[1];
 #pragma unroll
-      for (int q = 0; q < 8; ++q)
-        val[u][q] = f32_to_bf16(bf16_to_f32(val[u][q]) + add[q] + (TILE ? ta[q] : 0.f));
+        for (int q = 0; q < 4; ++q) {
+          tadd[q] = t0[q];
+          tadd[4 + q] = t1[q];
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < 8; ++q) val[u][q] = f32_to_bf16(bf16_to_f32(val[u][q]) + add[q] + tadd[q]);
       *reinterpret_cast<u16x8 *>(base + row * v.sn) = val[u];
     }
   }
@@ -1474,10 +1482,12 @@ __global__ __launch_bounds__(256) void add_pooled_kernel(bf16_t *dq, View v, con
 // that holds the tile: a per-(tile, column) addend built from the tile sums.
 // Pyramid of one signal: level j (1 .. J) holds the sums over 2^j consecutive tiles,
 // [ceil(ntiles / 2^j)][64], levels packed one after the other in P (< ntiles + J rows).
-// One workgroup of 1024 threads; thread (column c = tid % 64, group g = tid / 64 of kCoarseGroups);
-// the loops over tiles carry no dependency and are unrolled so that several loads are in flight.
+// Four workgroups of 1024 threads per signal, one per 16 columns; thread (column c = tid % 16 of
+// the quarter, group g = tid / 16 of kCoarseGroups); the loops over tiles carry no dependency and
+// are unrolled so that several loads are in flight.
 // ------------------------------------------------------------------------------------
-constexpr int kCoarseGroups = 16;
+constexpr int kCoarseGroups = 64, kCoarseCols = 16, kCoarseSplit = 64 / kCoarseCols;
+static_assert(kCoarseSplit == 4, "the gradient rows kernel leaves four extra rows in its band partials");
 __device__ __forceinline__ void build_tile_pyramid(const float *T, int ntiles, int J, float *P, int c, int g) {
   const float *prev = T;
   int nprev = ntiles;
@@ -1512,11 +1522,12 @@ __device__ __forceinline__ void tile_addend(const float *P, const float *coef, i
 }
 constexpr int64_t pyramid_floats(int ntiles) { return ((int64_t)ntiles + 32) * 64; }
 
-// Forward: blockIdx.y = 0 for Q, 1 for K.  T*: tile sums [S][ntiles][64]; A*: addends, same shape;
-// pyr: 2 * S pyramids of pyramid_floats(ntiles).
-__global__ __launch_bounds__(64 * kCoarseGroups) void coarse_addend_kernel(const float *Tq, const float *Tk, const float *coef,
-                                                           int ntiles, int L, float *pyr, float *Aq, float *Ak) {
-  const int slice = blockIdx.x, side = blockIdx.y, c = threadIdx.x & 63, g = threadIdx.x >> 6;
+// Forward: blockIdx.y = 0 for Q, 1 for K; blockIdx.z = column quarter.  T*: tile sums
+// [S][ntiles][64]; A*: addends, same shape; pyr: 2 * S pyramids of pyramid_floats(ntiles).
+__global__ __launch_bounds__(1024) void coarse_addend_kernel(const float *Tq, const float *Tk, const float *coef,
+                                                            int ntiles, int L, float *pyr, float *Aq, float *Ak) {
+  const int slice = blockIdx.x, side = blockIdx.y;
+  const int c = kCoarseCols * blockIdx.z + (threadIdx.x & (kCoarseCols - 1)), g = threadIdx.x / kCoarseCols;
   const int64_t base = (int64_t)slice * ntiles * 64;
   float *P = pyr + ((int64_t)slice * 2 + side) * pyramid_floats(ntiles);
   build_tile_pyramid((side ? Tk : Tq) + base, ntiles, L - 6, P, c, g);
@@ -1525,22 +1536,24 @@ __global__ __launch_bounds__(64 * kCoarseGroups) void coarse_addend_kernel(const
 
 // Backward, after both gradient kernels: Tg* = tile sums of dX_F (written by their epilogues),
 // Tx* = tile sums of X.  Writes the addends of dX (the filter is symmetric) and, into the extra
-// row `row` of the band partials part*[S][row + 1][L + 1], the contribution of the levels above
-// 6: with u_l = 2^-l * sum over 2^l-row blocks and columns of blocksum(dX_F) * blocksum(X),
-// band 6 gets -u_7, band l (7 .. L-1) gets u_l - u_{l+1}, band L gets u_L (the gradient kernels
-// leave u_6 alone in band 6 and zeros above).
-__global__ __launch_bounds__(64 * kCoarseGroups) void coarse_bwd_kernel(const float *TgQ, const float *TgK, const float *TxQ,
-                                                        const float *TxK, const float *coef, int ntiles, int L,
-                                                        float *pyr, float *AQ, float *AK, float *partQ,
-                                                        float *partK, int row) {
-  const int slice = blockIdx.x, side = blockIdx.y, c = threadIdx.x & 63, g = threadIdx.x >> 6, J = L - 6;
+// rows row .. row + 3 (one per column quarter) of the band partials part*[S][row + 4][L + 1], the
+// contribution of the levels above 6: with u_l = 2^-l * sum over 2^l-row blocks and columns of
+// blocksum(dX_F) * blocksum(X), band 6 gets -u_7, band l (7 .. L-1) gets u_l - u_{l+1}, band L
+// gets u_L (the gradient kernels leave u_6 alone in band 6 and zeros above).
+__global__ __launch_bounds__(1024) void coarse_bwd_kernel(const float *TgQ, const float *TgK, const float *TxQ,
+                                                         const float *TxK, const float *coef, int ntiles, int L,
+                                                         float *pyr, float *AQ, float *AK, float *partQ,
+                                                         float *partK, int row) {
+  const int slice = blockIdx.x, side = blockIdx.y, J = L - 6;
+  const int c = kCoarseCols * blockIdx.z + (threadIdx.x & (kCoarseCols - 1)), g = threadIdx.x / kCoarseCols;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int64_t base = (int64_t)slice * ntiles * 64;
   float *Pg = pyr + (((int64_t)slice * 2 + side) * 2) * pyramid_floats(ntiles);
   float *Px = Pg + pyramid_floats(ntiles);
   build_tile_pyramid((side ? TgK : TgQ) + base, ntiles, J, Pg, c, g);
   build_tile_pyramid((side ? TxK : TxQ) + base, ntiles, J, Px, c, g);
   tile_addend(Pg, coef + slice * kCoefStride, ntiles, J, (side ? AK : AQ) + base, c, g);
-  __shared__ float red[kCoarseGroups];
+  __shared__ float red[16];
   __shared__ float u[kMaxBands + 1];
   const float *lg = Pg, *lx = Px;
   int nprev = ntiles;
@@ -1550,11 +1563,11 @@ __global__ __launch_bounds__(64 * kCoarseGroups) void coarse_bwd_kernel(const fl
 #pragma unroll 4
     for (int b = g; b < nb; b += kCoarseGroups) acc = fmaf(lg[b * 64 + c], lx[b * 64 + c], acc);
     acc = wave_sum64(acc);
-    if (c == 0) red[g] = acc;
+    if (lane == 0) red[wave] = acc;
     __syncthreads();
     if (threadIdx.x == 0) {
       float tot = 0.f;
-      for (int i = 0; i < kCoarseGroups; ++i) tot += red[i];
+      for (int i = 0; i < 16; ++i) tot += red[i];
       u[6 + j] = tot / (float)(1 << (6 + j));
     }
     __syncthreads();
@@ -1568,7 +1581,7 @@ __global__ __launch_bounds__(64 * kCoarseGroups) void coarse_bwd_kernel(const fl
     if (i == 6) val = -u[7];
     else if (i > 6) val = i < L ? u[i] - u[i + 1] : u[i];
     float *part = side ? partK : partQ;
-    part[((int64_t)slice * (row + 1) + row) * (L + 1) + i] = val;
+    part[((int64_t)slice * (row + kCoarseSplit) + row + blockIdx.z) * (L + 1) + i] = val;
   }
 }
 
@@ -1736,8 +1749,8 @@ FastWs fast_ws(const wersa_desc &c, const FastPlan &p, int bwd, float *base, flo
     w.dSx = reinterpret_cast<bf16_t *>(b.take(sl * mx / 2));
     w.dST = reinterpret_cast<bf16_t *>(b.take(sl * md / 2));
     w.dzb = reinterpret_cast<bf16_t *>(b.take(sl * c.m / 2));
-    w.partQ = b.take(sl * (p.rowsWgsG + 1) * (c.L + 1));   // (+ one row: the levels above 6)
-    w.partK = b.take(sl * (p.rowsWgsG + 1) * (c.L + 1));
+    w.partQ = b.take(sl * (p.rowsWgsG + kCoarseSplit) * (c.L + 1));   // (+ the rows of the levels above 6)
+    w.partK = b.take(sl * (p.rowsWgsG + kCoarseSplit) * (c.L + 1));
     if (deep) {
       const int64_t tiles = sl * ntiles * c.d;
       w.gsumQ = b.take(tiles);
@@ -1900,7 +1913,7 @@ wersa_status fast_forward_t(const wersa_desc &c, const bf16_t *q, const bf16_t *
     WERSA_STAGE("wersa_qbar", st,
                 qbar_partial_kernel<DH><<<dim3(p.chunksQ, slices), 256, 0, st>>>(k, tv, c.n, p.rowsQ, w.tileK));
     WERSA_STAGE("wersa_coarse_addend", st,
-                coarse_addend_kernel<<<dim3(slices, 2), 64 * kCoarseGroups, 0, st>>>(w.tileQ, w.tileK, w.coef, p.chunksQ, c.L, w.pyr,
+                coarse_addend_kernel<<<dim3(slices, 2, kCoarseSplit), 1024, 0, st>>>(w.tileQ, w.tileK, w.coef, p.chunksQ, c.L, w.pyr,
                                                                       w.addQ, w.addK));
   }
   if (DH != 64) {   // head dimension 64 runs stage A inside the kernels that consume X_F
@@ -1960,11 +1973,11 @@ wersa_status fast_backward_t(const wersa_desc &c, const bf16_t *q, const bf16_t 
   const bool deep = c.L > kTileL;
   if (deep)   // levels above 6: addends of dQ and dK and the bands' extra row, from the tile sums
     WERSA_STAGE("wersa_coarse_bwd", st,
-                coarse_bwd_kernel<<<dim3(slices, 2), 64 * kCoarseGroups, 0, st>>>(w.gsumQ, w.gsumK, w.tileQ, w.tileK, w.coef,
+                coarse_bwd_kernel<<<dim3(slices, 2, kCoarseSplit), 1024, 0, st>>>(w.gsumQ, w.gsumK, w.tileQ, w.tileK, w.coef,
                                                                    (c.n + 63) / 64, c.L, w.pyr, w.gaddQ, w.gaddK,
                                                                    w.partQ, w.partK, p.rowsWgsG));
   WERSA_STAGE("gate_bwd_slice_kernel", st,
-              gate_bwd_slice_kernel<<<slices, 64, 0, st>>>(w.partQ, w.partK, deep ? p.rowsWgsG + 1 : p.rowsWgsG, c.L,
+              gate_bwd_slice_kernel<<<slices, 64, 0, st>>>(w.partQ, w.partK, deep ? p.rowsWgsG + kCoarseSplit : p.rowsWgsG, c.L,
                                                            c.d, c.H, s, gate_w, scale_w, w.dF, w.dlogit, w.dqbar,
                                                            (c.flags & WERSA_FLAG_POOLED_GATE) ? 1 : 0));
   WERSA_STAGE("gate_bwd_params_kernel", st,
