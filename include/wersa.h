@@ -59,7 +59,7 @@ typedef enum { WERSA_F32 = 0, WERSA_BF16 = 1 } wersa_dtype;
 
 /* desc.flags bits. By default the library picks the MFMA path (bf16 storage, fp16/bf16 matrix
  * cores, float32 accumulation) when the shape allows it: dtype bf16, d in {64, 128},
- * m % 128 == 0, L <= 6 (L <= 20 with d == 64 and n % 64 == 0), strides multiples of 8 elements
+ * m % 128 == 0, L <= 6 (L <= 20 with d == 64), strides multiples of 8 elements
  * (any n); otherwise the generic
  * float32-arithmetic path. WERSA_FLAG_GENERIC_PATH forces the generic path. */
 #define WERSA_FLAG_GENERIC_PATH 1

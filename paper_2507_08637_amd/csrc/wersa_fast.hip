@@ -423,7 +423,7 @@ __device__ __forceinline__ bf16x8 tile_cols_operand(const bf16_t *tile, int stri
 // raw and each step starts with X_F = G X for its tile, one 32 x 32 quarter per wave, written
 // to LDS in fp16 for the projection.
 // RAGGED: n % 64 != 0, rows past n count as zeros with weight 0.  DEEP: L > 6, the filter's levels
-// above 6 enter as the per-tile addend tile_add [slices][n / 64][DH] (the accumulators of X_F start there).
+// above 6 enter as the per-tile addend tile_add [slices][ceil(n / 64)][DH] (the accumulators of X_F start there).
 template <int DH, int FW, bool PREP, bool RAGGED, bool DEEP>
 __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
     const _Float16 *xf, const bf16_t *xraw, View vx, const float *coef, const float *tile_add,
@@ -576,7 +576,7 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
       const bf16_t *raw = reinterpret_cast<const bf16_t *>(&xt[buf][0]);
       f32x16 q = zero16(), q2 = zero16();
       if (DEEP) {   // register i is column 32 (wave % 2) + acc_row(i, h) for every row of the quarter
-        const float *ta = tile_add + ((int64_t)slice * (n / 64) + (t_begin / 64 + s)) * DH + 32 * (wave & 1);
+        const float *ta = tile_add + ((int64_t)slice * ((n + 63) / 64) + (t_begin / 64 + s)) * DH + 32 * (wave & 1);
 #pragma unroll
         for (int i = 0; i < 16; ++i) q[i] = ta[acc_row(i, h)];
       }
@@ -735,7 +735,7 @@ __global__ __launch_bounds__(256) void reduce_contract_kernel(const float *Spart
 // multiple of 64; rows past n of the last block read as zeros (clamped address, value replaced)
 // and that block's output goes through a side buffer.  The plain instance has none of that code.
 // DEEP: L > 6 (head dimension 64, whole blocks): X_F starts from the per-tile addend of the levels
-// above 6 (tile_add [slices][n / 64][DH]); the gradient modes also write the 64-row sums of dX_F
+// above 6 (tile_add [slices][ceil(n / 64)][DH]); the gradient modes also write the 64-row sums of dX_F
 // per column (tile_gsum, same shape) and leave band 6 of their partials as u_6 alone.
 template <int DH, int MODE, int NW, int MC, bool LN, bool RAGGED, bool DEEP>
 __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
@@ -1037,7 +1037,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
           q[cg][0] = zero16();
           if (DEEP) {
             // register i stands for column 32 ct + (acc_row(i, h) with bits 2 and 3 swapped), every lane's row alike
-            const float *ta = tile_add + ((int64_t)slice * (n / 64) + t0 / 64) * DH + 32 * (c0 + cg);
+            const float *ta = tile_add + ((int64_t)slice * ((n + 63) / 64) + t0 / 64) * DH + 32 * (c0 + cg);
 #pragma unroll
             for (int i = 0; i < 16; ++i) q[cg][0][i] = ta[16 * (i >> 3) + 8 * h + 4 * ((i >> 2) & 1) + (i & 3)];
           }
@@ -1365,7 +1365,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
       const float g6 = g5[0] + g5[1], x6 = x5[0] + x5[1];
       u[6] = fmaf(0.5f * g6, x6, u[6]);
       // both half-waves hold the same sum and write the same value: no branch around the store
-      if (DEEP) tile_gsum[((int64_t)slice * (n / 64) + t0 / 64) * DH + 32 * ct + l32] = g6;
+      if (DEEP) tile_gsum[((int64_t)slice * ((n + 63) / 64) + t0 / 64) * DH + 32 * ct + l32] = g6;
       const float T6 = cf[6] * g6;
       __builtin_amdgcn_wave_barrier();
       // ---- pass 2: filtered gradient, top-down (block sums of g rebuilt), bf16 into the tile
@@ -1818,7 +1818,13 @@ hipError_t launch_rows(const wersa_desc &c, const FastPlan &p, const _Float16 *x
     return hipSuccess;
   };
   const bool ln = MODE == 0 && (c.flags & WERSA_FLAG_LAYERNORM), ragged = c.n % 64 != 0;
-  if (DH == 64 && c.L > kTileL) {   // deeper than one block (whole blocks only, see fast_supported)
+  if (DH == 64 && c.L > kTileL) {   // deeper than one block (head dimension 64, see fast_supported)
+    if (ragged) {
+      if (ln) return p.mc == 256 ? go(&rows_kernel<DH, MODE, NW, 256, MODE == 0, DH == 64, DH == 64>)
+                                 : go(&rows_kernel<DH, MODE, NW, 128, MODE == 0, DH == 64, DH == 64>);
+      return p.mc == 256 ? go(&rows_kernel<DH, MODE, NW, 256, false, DH == 64, DH == 64>)
+                         : go(&rows_kernel<DH, MODE, NW, 128, false, DH == 64, DH == 64>);
+    }
     if (ln) return p.mc == 256 ? go(&rows_kernel<DH, MODE, NW, 256, MODE == 0, false, DH == 64>)
                                : go(&rows_kernel<DH, MODE, NW, 128, MODE == 0, false, DH == 64>);
     return p.mc == 256 ? go(&rows_kernel<DH, MODE, NW, 256, false, false, DH == 64>)
@@ -1854,7 +1860,12 @@ void launch_contract(const wersa_desc &c, const FastPlan &p, const _Float16 *xf,
                                            w.zpart));
   };
   const bool ragged = c.n % 64 != 0, deep = DH == 64 && c.L > kTileL;
-  if (deep) {
+  if (deep && ragged) {
+    if (p.FW == 64) orows ? go(&phiT_contract_kernel<DH, 64, true, DH == 64, DH == 64>)
+                          : go(&phiT_contract_kernel<DH, 64, false, DH == 64, DH == 64>);
+    else orows ? go(&phiT_contract_kernel<DH, 32, true, DH == 64, DH == 64>)
+               : go(&phiT_contract_kernel<DH, 32, false, DH == 64, DH == 64>);
+  } else if (deep) {
     if (p.FW == 64) orows ? go(&phiT_contract_kernel<DH, 64, true, false, DH == 64>)
                           : go(&phiT_contract_kernel<DH, 64, false, false, DH == 64>);
     else orows ? go(&phiT_contract_kernel<DH, 32, true, false, DH == 64>)
@@ -1891,7 +1902,7 @@ wersa_status fast_forward_t(const wersa_desc &c, const bf16_t *q, const bf16_t *
   WERSA_STAGE("wersa_setup", st,
               setup_kernel<<<(nmat * c.d * c.m + 255) / 256, 256, 0, st>>>(sigma, c.bw_floor, omega, c.d, c.m, nmat,
                                                                            w.scalars, w.omT));
-  const bool deep = c.L > kTileL;   // (head dimension 64, whole blocks: see fast_supported)
+  const bool deep = c.L > kTileL;   // (head dimension 64: see fast_supported)
   if (pooled && c.n % 128 == 0 && !deep) {
     // the caller's column sums per 128 token rows: batch b owns row blocks [b n/128, (b+1) n/128)
     const int chunks = c.n / 128;
@@ -2001,8 +2012,8 @@ wersa_status fast_backward_t(const wersa_desc &c, const bf16_t *q, const bf16_t 
 }  // namespace
 
 bool fast_supported(const wersa_desc &c) {
-  // transforms deeper than one 64-row block: head dimension 64 and whole blocks only
-  const bool levels_ok = c.L <= kTileL || (c.d == 64 && c.n % 64 == 0);
+  // transforms deeper than one 64-row block: head dimension 64 only
+  const bool levels_ok = c.L <= kTileL || c.d == 64;
   return c.dtype == WERSA_BF16 && (c.d == 64 || c.d == 128) && c.m % 128 == 0 && levels_ok &&
          c.stride_n % 8 == 0 && c.stride_h % 8 == 0 && c.stride_b % 8 == 0;
 }

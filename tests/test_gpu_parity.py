@@ -377,9 +377,11 @@ def test_layernorm_output_stage_mfma_shapes(shape):
 @pytest.mark.parametrize("shape", [dict(B=1, H=2, n=1024, d=64, L=8, m=256),      # 16 tiles, blocks of 4 tiles
                                    dict(B=2, H=1, n=4160, d=64, L=12, m=128),     # 65 tiles: one 4096-row block + one tile
                                    dict(B=1, H=1, n=8192, d=64, L=13, m=256),     # one block of 128 tiles
-                                   dict(B=1, H=2, n=640, d=64, L=7, m=128)])      # 10 tiles, pairs
+                                   dict(B=1, H=2, n=640, d=64, L=7, m=128),       # 10 tiles, pairs
+                                   dict(B=1, H=2, n=1000, d=64, L=9, m=256),      # partial last tile: 15 tiles + 40 rows
+                                   dict(B=1, H=1, n=100, d=64, L=7, m=128)])      # two tiles, the second partial
 def test_deep_transform_on_the_mfma_path(shape):
-    """L > 6 with head dimension 64 and whole 64-row blocks stays on the MFMA path: levels up to
+    """L > 6 with head dimension 64 stays on the MFMA path: levels up to
     6 inside the kernels, the levels above as per-tile addends built from the tile sums (and,
     backwards, from the tile sums of dX_F, with their share of the band inner products)."""
     import torch
