@@ -59,8 +59,7 @@ typedef enum { WERSA_F32 = 0, WERSA_BF16 = 1 } wersa_dtype;
 
 /* desc.flags bits. By default the library picks the MFMA path (bf16 storage, fp16/bf16 matrix
  * cores, float32 accumulation) when the shape allows it: dtype bf16, d in {64, 128},
- * m % 128 == 0, L <= 6 (L <= 20 with d == 64), strides multiples of 8 elements
- * (any n); otherwise the generic
+ * m % 128 == 0, strides multiples of 8 elements (any n, any L <= 20); otherwise the generic
  * float32-arithmetic path. WERSA_FLAG_GENERIC_PATH forces the generic path. */
 #define WERSA_FLAG_GENERIC_PATH 1
 /* Separate random matrices for the query and the key side (Algorithm 1 draws W_Q^rand and

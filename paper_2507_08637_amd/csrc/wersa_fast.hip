@@ -243,9 +243,10 @@ __device__ __forceinline__ float segment_sum(const float (&v)[RS]) {
 // Steps: coalesced 16-byte loads into LDS; one thread per (column, row segment) computes the
 // nested block sums (in registers up to the segment, through LDS above it) and the filtered
 // values; fp16 results go back to LDS and leave with coalesced 16-byte stores.
+// tile_add (L > 6, else nullptr): [slices][ceil(n / 64)][DH], the per-tile addend of the levels above 6.
 template <int DH>
 __global__ __launch_bounds__(256) void haar_stage_kernel(const bf16_t *x, View v, int n,
-                                                        const float *coef, _Float16 *xf) {
+                                                        const float *coef, const float *tile_add, _Float16 *xf) {
   constexpr int SEGS = 256 / DH;   // row segments per column: 4 (DH=64) or 2 (DH=128)
   constexpr int RS = 64 / SEGS;    // rows per segment: 16 or 32
   constexpr int CPR = DH / 8;
@@ -280,6 +281,7 @@ __global__ __launch_bounds__(256) void haar_stage_kernel(const bf16_t *x, View v
   } else {
     upper = cf[6] * (segsum[0][c] + segsum[1][c]);
   }
+  if (tile_add) upper += tile_add[((int64_t)slice * gridDim.x + blockIdx.x) * DH + c];
   filter_segment<RS>(vals, cf, upper);
   _Float16 *tile16 = reinterpret_cast<_Float16 *>(tile);
 #pragma unroll
@@ -734,9 +736,10 @@ __global__ __launch_bounds__(256) void reduce_contract_kernel(const float *Spart
 // LN (MODE 0): LayerNorm over the columns of a row instead of the normaliser.  RAGGED: n is not a
 // multiple of 64; rows past n of the last block read as zeros (clamped address, value replaced)
 // and that block's output goes through a side buffer.  The plain instance has none of that code.
-// DEEP: L > 6 (head dimension 64, whole blocks): X_F starts from the per-tile addend of the levels
-// above 6 (tile_add [slices][ceil(n / 64)][DH]); the gradient modes also write the 64-row sums of dX_F
-// per column (tile_gsum, same shape) and leave band 6 of their partials as u_6 alone.
+// DEEP: L > 6: X_F starts from the per-tile addend of the levels above 6 (tile_add
+// [slices][ceil(n / 64)][DH]; head dimension 128 finds them in xf already); the gradient modes also
+// write the 64-row sums of dX_F per column (tile_gsum, same shape) and leave band 6 of their
+// partials as u_6 alone.
 template <int DH, int MODE, int NW, int MC, bool LN, bool RAGGED, bool DEEP>
 __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
     const _Float16 *xf,        // X_F fp16 [slices][n][DH] (head dimension 128; with 64 it is formed here)
@@ -1427,7 +1430,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
         ul += s_wave[wv * 8 + tid];
         if (tid < L && tid + 1 < kTileBands) ul1 += s_wave[wv * 8 + tid + 1];
       }
-    const int rows = DEEP ? gridDim.x + 4 : gridDim.x;   // (four extra rows: the tile-sum kernel's column quarters)
+    const int rows = DEEP ? gridDim.x + DH / 16 : gridDim.x;   // (extra rows: one per workgroup of the tile-sum kernel)
     partF[((int64_t)slice * rows + blockIdx.x) * (L + 1) + tid] = tid < L ? ul - ul1 : ul;
   }
 }
@@ -1477,18 +1480,17 @@ __global__ __launch_bounds__(256) void add_pooled_kernel(bf16_t *dq, View v, con
 }
 
 // ------------------------------------------------------------------------------------
-// Transforms deeper than one 64-row block (L > 6, head dimension 64).  In block-mean form the
+// Transforms deeper than one 64-row block (L > 6).  In block-mean form the
 // levels above 6 add, to every row of a tile, coef_l times the sum of X over the 2^l-row block
 // that holds the tile: a per-(tile, column) addend built from the tile sums.
 // Pyramid of one signal: level j (1 .. J) holds the sums over 2^j consecutive tiles,
-// [ceil(ntiles / 2^j)][64], levels packed one after the other in P (< ntiles + J rows).
-// Four workgroups of 1024 threads per signal, one per 16 columns; thread (column c = tid % 16 of
-// the quarter, group g = tid / 16 of kCoarseGroups); the loops over tiles carry no dependency and
+// [ceil(ntiles / 2^j)][d], levels packed one after the other in P (< ntiles + J rows).
+// d / 16 workgroups of 1024 threads per signal, one per 16 columns; thread (column c = tid % 16 of
+// its 16, group g = tid / 16 of kCoarseGroups); the loops over tiles carry no dependency and
 // are unrolled so that several loads are in flight.
 // ------------------------------------------------------------------------------------
-constexpr int kCoarseGroups = 64, kCoarseCols = 16, kCoarseSplit = 64 / kCoarseCols;
-static_assert(kCoarseSplit == 4, "the gradient rows kernel leaves four extra rows in its band partials");
-__device__ __forceinline__ void build_tile_pyramid(const float *T, int ntiles, int J, float *P, int c, int g) {
+constexpr int kCoarseGroups = 64, kCoarseCols = 16;   // (the gradient rows kernel leaves d / 16 extra rows in its band partials)
+__device__ __forceinline__ void build_tile_pyramid(const float *T, int ntiles, int d, int J, float *P, int c, int g) {
   const float *prev = T;
   int nprev = ntiles;
   float *cur = P;
@@ -1496,16 +1498,16 @@ __device__ __forceinline__ void build_tile_pyramid(const float *T, int ntiles, i
     const int nb = (nprev + 1) / 2;
 #pragma unroll 4
     for (int b = g; b < nb; b += kCoarseGroups)
-      cur[b * 64 + c] = prev[2 * b * 64 + c] + (2 * b + 1 < nprev ? prev[(2 * b + 1) * 64 + c] : 0.f);
+      cur[b * d + c] = prev[2 * b * d + c] + (2 * b + 1 < nprev ? prev[(2 * b + 1) * d + c] : 0.f);
     __threadfence_block();
     __syncthreads();
     prev = cur;
     nprev = nb;
-    cur += nb * 64;
+    cur += nb * d;
   }
 }
 // addend[tile][c] = sum over j of coef[6 + j] * P_j[tile >> j][c]
-__device__ __forceinline__ void tile_addend(const float *P, const float *coef, int ntiles, int J, float *A, int c, int g) {
+__device__ __forceinline__ void tile_addend(const float *P, const float *coef, int ntiles, int d, int J, float *A, int c, int g) {
 #pragma unroll 4
   for (int tile = g; tile < ntiles; tile += kCoarseGroups) {
     float acc = 0.f;
@@ -1513,46 +1515,46 @@ __device__ __forceinline__ void tile_addend(const float *P, const float *coef, i
     int nprev = ntiles;
     for (int j = 1; j <= J; ++j) {
       const int nb = (nprev + 1) / 2;
-      acc = fmaf(coef[6 + j], lvl[(tile >> j) * 64 + c], acc);
-      lvl += nb * 64;
+      acc = fmaf(coef[6 + j], lvl[(tile >> j) * d + c], acc);
+      lvl += nb * d;
       nprev = nb;
     }
-    A[tile * 64 + c] = acc;
+    A[tile * d + c] = acc;
   }
 }
-constexpr int64_t pyramid_floats(int ntiles) { return ((int64_t)ntiles + 32) * 64; }
+constexpr int64_t pyramid_floats(int ntiles, int d) { return ((int64_t)ntiles + 32) * d; }
 
-// Forward: blockIdx.y = 0 for Q, 1 for K; blockIdx.z = column quarter.  T*: tile sums
-// [S][ntiles][64]; A*: addends, same shape; pyr: 2 * S pyramids of pyramid_floats(ntiles).
+// Forward: blockIdx.y = 0 for Q, 1 for K; blockIdx.z = group of 16 columns.  T*: tile sums
+// [S][ntiles][d]; A*: addends, same shape; pyr: 2 * S pyramids of pyramid_floats(ntiles, d).
 __global__ __launch_bounds__(1024) void coarse_addend_kernel(const float *Tq, const float *Tk, const float *coef,
-                                                            int ntiles, int L, float *pyr, float *Aq, float *Ak) {
+                                                            int ntiles, int d, int L, float *pyr, float *Aq, float *Ak) {
   const int slice = blockIdx.x, side = blockIdx.y;
   const int c = kCoarseCols * blockIdx.z + (threadIdx.x & (kCoarseCols - 1)), g = threadIdx.x / kCoarseCols;
-  const int64_t base = (int64_t)slice * ntiles * 64;
-  float *P = pyr + ((int64_t)slice * 2 + side) * pyramid_floats(ntiles);
-  build_tile_pyramid((side ? Tk : Tq) + base, ntiles, L - 6, P, c, g);
-  tile_addend(P, coef + slice * kCoefStride, ntiles, L - 6, (side ? Ak : Aq) + base, c, g);
+  const int64_t base = (int64_t)slice * ntiles * d;
+  float *P = pyr + ((int64_t)slice * 2 + side) * pyramid_floats(ntiles, d);
+  build_tile_pyramid((side ? Tk : Tq) + base, ntiles, d, L - 6, P, c, g);
+  tile_addend(P, coef + slice * kCoefStride, ntiles, d, L - 6, (side ? Ak : Aq) + base, c, g);
 }
 
 // Backward, after both gradient kernels: Tg* = tile sums of dX_F (written by their epilogues),
 // Tx* = tile sums of X.  Writes the addends of dX (the filter is symmetric) and, into the extra
-// rows row .. row + 3 (one per column quarter) of the band partials part*[S][row + 4][L + 1], the
+// rows row .. row + d / 16 - 1 (one per workgroup) of the band partials part*[S][row + d / 16][L + 1], the
 // contribution of the levels above 6: with u_l = 2^-l * sum over 2^l-row blocks and columns of
 // blocksum(dX_F) * blocksum(X), band 6 gets -u_7, band l (7 .. L-1) gets u_l - u_{l+1}, band L
 // gets u_L (the gradient kernels leave u_6 alone in band 6 and zeros above).
 __global__ __launch_bounds__(1024) void coarse_bwd_kernel(const float *TgQ, const float *TgK, const float *TxQ,
-                                                         const float *TxK, const float *coef, int ntiles, int L,
+                                                         const float *TxK, const float *coef, int ntiles, int d, int L,
                                                          float *pyr, float *AQ, float *AK, float *partQ,
                                                          float *partK, int row) {
   const int slice = blockIdx.x, side = blockIdx.y, J = L - 6;
   const int c = kCoarseCols * blockIdx.z + (threadIdx.x & (kCoarseCols - 1)), g = threadIdx.x / kCoarseCols;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int64_t base = (int64_t)slice * ntiles * 64;
-  float *Pg = pyr + (((int64_t)slice * 2 + side) * 2) * pyramid_floats(ntiles);
-  float *Px = Pg + pyramid_floats(ntiles);
-  build_tile_pyramid((side ? TgK : TgQ) + base, ntiles, J, Pg, c, g);
-  build_tile_pyramid((side ? TxK : TxQ) + base, ntiles, J, Px, c, g);
-  tile_addend(Pg, coef + slice * kCoefStride, ntiles, J, (side ? AK : AQ) + base, c, g);
+  const int64_t base = (int64_t)slice * ntiles * d;
+  float *Pg = pyr + (((int64_t)slice * 2 + side) * 2) * pyramid_floats(ntiles, d);
+  float *Px = Pg + pyramid_floats(ntiles, d);
+  build_tile_pyramid((side ? TgK : TgQ) + base, ntiles, d, J, Pg, c, g);
+  build_tile_pyramid((side ? TxK : TxQ) + base, ntiles, d, J, Px, c, g);
+  tile_addend(Pg, coef + slice * kCoefStride, ntiles, d, J, (side ? AK : AQ) + base, c, g);
   __shared__ float red[16];
   __shared__ float u[kMaxBands + 1];
   const float *lg = Pg, *lx = Px;
@@ -1561,7 +1563,7 @@ __global__ __launch_bounds__(1024) void coarse_bwd_kernel(const float *TgQ, cons
     const int nb = (nprev + 1) / 2;
     float acc = 0.f;
 #pragma unroll 4
-    for (int b = g; b < nb; b += kCoarseGroups) acc = fmaf(lg[b * 64 + c], lx[b * 64 + c], acc);
+    for (int b = g; b < nb; b += kCoarseGroups) acc = fmaf(lg[b * d + c], lx[b * d + c], acc);
     acc = wave_sum64(acc);
     if (lane == 0) red[wave] = acc;
     __syncthreads();
@@ -1571,8 +1573,8 @@ __global__ __launch_bounds__(1024) void coarse_bwd_kernel(const float *TgQ, cons
       u[6 + j] = tot / (float)(1 << (6 + j));
     }
     __syncthreads();
-    lg += nb * 64;
-    lx += nb * 64;
+    lg += nb * d;
+    lx += nb * d;
     nprev = nb;
   }
   if ((int)threadIdx.x <= L) {
@@ -1581,7 +1583,7 @@ __global__ __launch_bounds__(1024) void coarse_bwd_kernel(const float *TgQ, cons
     if (i == 6) val = -u[7];
     else if (i > 6) val = i < L ? u[i] - u[i + 1] : u[i];
     float *part = side ? partK : partQ;
-    part[((int64_t)slice * (row + kCoarseSplit) + row + blockIdx.z) * (L + 1) + i] = val;
+    part[((int64_t)slice * (row + gridDim.z) + row + blockIdx.z) * (L + 1) + i] = val;
   }
 }
 
@@ -1749,8 +1751,8 @@ FastWs fast_ws(const wersa_desc &c, const FastPlan &p, int bwd, float *base, flo
     w.dSx = reinterpret_cast<bf16_t *>(b.take(sl * mx / 2));
     w.dST = reinterpret_cast<bf16_t *>(b.take(sl * md / 2));
     w.dzb = reinterpret_cast<bf16_t *>(b.take(sl * c.m / 2));
-    w.partQ = b.take(sl * (p.rowsWgsG + kCoarseSplit) * (c.L + 1));   // (+ the rows of the levels above 6)
-    w.partK = b.take(sl * (p.rowsWgsG + kCoarseSplit) * (c.L + 1));
+    w.partQ = b.take(sl * (p.rowsWgsG + c.d / kCoarseCols) * (c.L + 1));   // (+ the rows of the levels above 6)
+    w.partK = b.take(sl * (p.rowsWgsG + c.d / kCoarseCols) * (c.L + 1));
     if (deep) {
       const int64_t tiles = sl * ntiles * c.d;
       w.gsumQ = b.take(tiles);
@@ -1766,7 +1768,7 @@ FastWs fast_ws(const wersa_desc &c, const FastPlan &p, int bwd, float *base, flo
       w.ones = b.take(sl * c.n);
     }
   }
-  if (deep) w.pyr = b.take(sl * 4 * pyramid_floats(ntiles));
+  if (deep) w.pyr = b.take(sl * 4 * pyramid_floats(ntiles, c.d));
   w.total = b.off;
   return w;
 }
@@ -1818,7 +1820,13 @@ hipError_t launch_rows(const wersa_desc &c, const FastPlan &p, const _Float16 *x
     return hipSuccess;
   };
   const bool ln = MODE == 0 && (c.flags & WERSA_FLAG_LAYERNORM), ragged = c.n % 64 != 0;
-  if (DH == 64 && c.L > kTileL) {   // deeper than one block (head dimension 64, see fast_supported)
+  if (DH == 128 && IS_GRAD && c.L > kTileL) {
+    // deeper than one block, head dimension 128: X_F arrives with the levels above 6 in it; the
+    // gradient modes still write the tile sums of dX_F and the extra rows of the band partials
+    if (ragged) return go(&rows_kernel<DH, MODE, NW, 128, false, DH == 128 && IS_GRAD, DH == 128 && IS_GRAD>);
+    return go(&rows_kernel<DH, MODE, NW, 128, false, false, DH == 128 && IS_GRAD>);
+  }
+  if (DH == 64 && c.L > kTileL) {   // deeper than one block, head dimension 64
     if (ragged) {
       if (ln) return p.mc == 256 ? go(&rows_kernel<DH, MODE, NW, 256, MODE == 0, DH == 64, DH == 64>)
                                  : go(&rows_kernel<DH, MODE, NW, 128, MODE == 0, DH == 64, DH == 64>);
@@ -1902,7 +1910,7 @@ wersa_status fast_forward_t(const wersa_desc &c, const bf16_t *q, const bf16_t *
   WERSA_STAGE("wersa_setup", st,
               setup_kernel<<<(nmat * c.d * c.m + 255) / 256, 256, 0, st>>>(sigma, c.bw_floor, omega, c.d, c.m, nmat,
                                                                            w.scalars, w.omT));
-  const bool deep = c.L > kTileL;   // (head dimension 64: see fast_supported)
+  const bool deep = c.L > kTileL;
   if (pooled && c.n % 128 == 0 && !deep) {
     // the caller's column sums per 128 token rows: batch b owns row blocks [b n/128, (b+1) n/128)
     const int chunks = c.n / 128;
@@ -1924,14 +1932,14 @@ wersa_status fast_forward_t(const wersa_desc &c, const bf16_t *q, const bf16_t *
     WERSA_STAGE("wersa_qbar", st,
                 qbar_partial_kernel<DH><<<dim3(p.chunksQ, slices), 256, 0, st>>>(k, tv, c.n, p.rowsQ, w.tileK));
     WERSA_STAGE("wersa_coarse_addend", st,
-                coarse_addend_kernel<<<dim3(slices, 2, kCoarseSplit), 1024, 0, st>>>(w.tileQ, w.tileK, w.coef, p.chunksQ, c.L, w.pyr,
+                coarse_addend_kernel<<<dim3(slices, 2, DH / kCoarseCols), 1024, 0, st>>>(w.tileQ, w.tileK, w.coef, p.chunksQ, DH, c.L, w.pyr,
                                                                       w.addQ, w.addK));
   }
   if (DH != 64) {   // head dimension 64 runs stage A inside the kernels that consume X_F
     WERSA_STAGE("wersa_haar_stage", st,
-                haar_stage_kernel<DH><<<dim3((c.n + 63) / 64, slices), 256, 0, st>>>(q, tv, c.n, w.coef, QF));
+                haar_stage_kernel<DH><<<dim3((c.n + 63) / 64, slices), 256, 0, st>>>(q, tv, c.n, w.coef, deep ? w.addQ : nullptr, QF));
     WERSA_STAGE("wersa_haar_stage", st,
-                haar_stage_kernel<DH><<<dim3((c.n + 63) / 64, slices), 256, 0, st>>>(k, tv, c.n, w.coef, KF));
+                haar_stage_kernel<DH><<<dim3((c.n + 63) / 64, slices), 256, 0, st>>>(k, tv, c.n, w.coef, deep ? w.addK : nullptr, KF));
   }
   launch_contract<DH>(c, p, KF, k, v, tv, nullptr, nullptr, nullptr, true, w, S, z, w.Sx, w.ST, w.zb, st);
   if (launch_rows<DH, 0>(c, p, QF, q, nullptr, nullptr, nullptr, w, omega, nullptr, w.ST, w.zb, out, D,
@@ -1984,11 +1992,11 @@ wersa_status fast_backward_t(const wersa_desc &c, const bf16_t *q, const bf16_t 
   const bool deep = c.L > kTileL;
   if (deep)   // levels above 6: addends of dQ and dK and the bands' extra row, from the tile sums
     WERSA_STAGE("wersa_coarse_bwd", st,
-                coarse_bwd_kernel<<<dim3(slices, 2, kCoarseSplit), 1024, 0, st>>>(w.gsumQ, w.gsumK, w.tileQ, w.tileK, w.coef,
-                                                                   (c.n + 63) / 64, c.L, w.pyr, w.gaddQ, w.gaddK,
+                coarse_bwd_kernel<<<dim3(slices, 2, DH / kCoarseCols), 1024, 0, st>>>(w.gsumQ, w.gsumK, w.tileQ, w.tileK, w.coef,
+                                                                   (c.n + 63) / 64, DH, c.L, w.pyr, w.gaddQ, w.gaddK,
                                                                    w.partQ, w.partK, p.rowsWgsG));
   WERSA_STAGE("gate_bwd_slice_kernel", st,
-              gate_bwd_slice_kernel<<<slices, 64, 0, st>>>(w.partQ, w.partK, deep ? p.rowsWgsG + kCoarseSplit : p.rowsWgsG, c.L,
+              gate_bwd_slice_kernel<<<slices, 64, 0, st>>>(w.partQ, w.partK, deep ? p.rowsWgsG + DH / kCoarseCols : p.rowsWgsG, c.L,
                                                            c.d, c.H, s, gate_w, scale_w, w.dF, w.dlogit, w.dqbar,
                                                            (c.flags & WERSA_FLAG_POOLED_GATE) ? 1 : 0));
   WERSA_STAGE("gate_bwd_params_kernel", st,
@@ -2012,9 +2020,7 @@ wersa_status fast_backward_t(const wersa_desc &c, const bf16_t *q, const bf16_t 
 }  // namespace
 
 bool fast_supported(const wersa_desc &c) {
-  // transforms deeper than one 64-row block: head dimension 64 only
-  const bool levels_ok = c.L <= kTileL || c.d == 64;
-  return c.dtype == WERSA_BF16 && (c.d == 64 || c.d == 128) && c.m % 128 == 0 && levels_ok &&
+  return c.dtype == WERSA_BF16 && (c.d == 64 || c.d == 128) && c.m % 128 == 0 &&
          c.stride_n % 8 == 0 && c.stride_h % 8 == 0 && c.stride_b % 8 == 0;
 }
 

@@ -43,7 +43,7 @@ template <> __device__ __forceinline__ void st<float>(float *p, float v) { *p = 
 template <> __device__ __forceinline__ void st<bf16_t>(bf16_t *p, float v) { *p = f32_to_bf16(v); }
 
 // ---- saved-buffer layout (floats) -------------------------------------------------------
-// MFMA path (bf16 storage, d in {64, 128}, m % 128 == 0, L <= 6, 16-byte aligned rows).
+// MFMA path (bf16 storage, d in {64, 128}, m % 128 == 0, 16-byte aligned rows).
 bool fast_supported(const wersa_desc &c);
 inline bool use_fast(const wersa_desc &c) {
   return !(c.flags & WERSA_FLAG_GENERIC_PATH) && fast_supported(c);

@@ -379,9 +379,12 @@ def test_layernorm_output_stage_mfma_shapes(shape):
                                    dict(B=1, H=1, n=8192, d=64, L=13, m=256),     # one block of 128 tiles
                                    dict(B=1, H=2, n=640, d=64, L=7, m=128),       # 10 tiles, pairs
                                    dict(B=1, H=2, n=1000, d=64, L=9, m=256),      # partial last tile: 15 tiles + 40 rows
-                                   dict(B=1, H=1, n=100, d=64, L=7, m=128)])      # two tiles, the second partial
+                                   dict(B=1, H=1, n=100, d=64, L=7, m=128),       # two tiles, the second partial
+                                   dict(B=1, H=2, n=1024, d=128, L=9, m=128),     # head dimension 128: stage A kernel takes the addends
+                                   dict(B=2, H=1, n=4160, d=128, L=12, m=256),
+                                   dict(B=1, H=1, n=1000, d=128, L=8, m=128)])    # ... with a partial last tile
 def test_deep_transform_on_the_mfma_path(shape):
-    """L > 6 with head dimension 64 stays on the MFMA path: levels up to
+    """L > 6 stays on the MFMA path: levels up to
     6 inside the kernels, the levels above as per-tile addends built from the tile sums (and,
     backwards, from the tile sums of dX_F, with their share of the band inner products)."""
     import torch
@@ -400,16 +403,15 @@ def test_deep_transform_on_the_mfma_path(shape):
         assert hp.rel_err(res["saved"][name], r) < 2e-2, name
 
 
-def test_deep_transform_on_an_mfma_shape_takes_the_generic_path():
-    """L > 6 on a shape of the MFMA path with head dimension 128: the default selection falls back
-    to the generic path (deep transforms on the MFMA path need head dimension 64 and whole blocks)
-    and meets the bf16 bar."""
+def test_deep_transform_outside_the_mfma_shapes_takes_the_generic_path():
+    """L > 6 with a feature count the MFMA path does not take (m % 128 != 0): the default
+    selection is the generic path, which meets the bf16 bar."""
     import torch
     from paper_2507_08637_amd import binding
-    cfg = dict(B=1, H=2, n=1024, d=128, L=9, m=128, dtype="bf16", flavour="plain", seed_base=3700, q_mean=0.3)
+    cfg = dict(B=1, H=2, n=1024, d=128, L=9, m=192, dtype="bf16", flavour="plain", seed_base=3700, q_mean=0.3)
     probe = torch.empty(cfg["B"], cfg["H"], cfg["n"], cfg["d"], dtype=torch.bfloat16, device="cuda")
     assert binding.wersa_path_name(binding.make_desc(probe, cfg["L"], cfg["m"])) == "generic"
-    assert binding.wersa_path_name(binding.make_desc(probe, 6, cfg["m"])) == "mfma"
+    assert binding.wersa_path_name(binding.make_desc(probe, cfg["L"], 128)) == "mfma"
     p = workloads.make_inputs(**cfg)
     res = hp.gpu_forward_backward(p, cfg)
     ref = hp.oracle_backward(p, cfg)
