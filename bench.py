@@ -56,7 +56,9 @@ def kernel_models(cfg):
         "wersa_phiT_contract": ("mfma", "mfma_bf16", 2 * unit),  # projection + Phi^T Y
         "wersa_rows_fwd": ("mfma", "mfma_bf16", 2 * unit),       # projection + Phi S
         "wersa_rows_bwd_q": ("mfma", "mfma_bf16", 3 * unit),     # projection, dPhi, dX_F
-        "wersa_rows_bwd_k": ("mfma", "mfma_bf16", 3 * unit),     # projection, dPhi, dX_F
+        # projection, dPhi, dX_F; with head dimension 64, 256 features per pass and whole 64-row
+        # blocks the kernel also forms dV = Phi dS (a fourth contraction) and no rows_bwd_v launch follows
+        "wersa_rows_bwd_k": ("mfma", "mfma_bf16", (4 if (d == 64 and m % 256 == 0 and n % 64 == 0) else 3) * unit),
         "wersa_rows_bwd_v": ("mfma", "mfma_bf16", 2 * unit),     # projection, Phi dS
         "wersa_ln_prep": ("hbm", "hbm", 3 * nd * e),
         "wersa_add_pooled": ("hbm", "hbm", 2 * nd * e),

@@ -740,7 +740,10 @@ __global__ __launch_bounds__(256) void reduce_contract_kernel(const float *Spart
 // [slices][ceil(n / 64)][DH]; head dimension 128 finds them in xf already); the gradient modes also
 // write the 64-row sums of dX_F per column (tile_gsum, same shape) and leave band 6 of their
 // partials as u_6 alone.
-template <int DH, int MODE, int NW, int MC, bool LN, bool RAGGED, bool DEEP>
+// DV (MODE 2, head dimension 64): the kernel also forms dV = c relu(R) dS of MODE 3 from the
+// projection it has in hand (B operand: the rows of (dS | dz) in LDS through transposing reads)
+// and writes it to out1; the separate MODE 3 launch, its pass over K and its projection go away.
+template <int DH, int MODE, int NW, int MC, bool LN, bool RAGGED, bool DEEP, bool DV = false>
 __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
     const _Float16 *xf,        // X_F fp16 [slices][n][DH] (head dimension 128; with 64 it is formed here)
     const bf16_t *x, View vx,  // X (Q or K): band inner products (MODE 1, 2); source of X_F (head dimension 64)
@@ -758,8 +761,10 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
     float *Dout,               // D (MODE 0)
     float *partF, int L,       // [slices][gridDim.x][L+1] band partials (MODE 1, 2)
     bf16_t *tail_out, float *tail_D,   // partial last block: its 64 output rows [slices][64][DH] and D [slices][64]
-    const float *tile_add, float *tile_gsum)   // DEEP (see above)
+    const float *tile_add, float *tile_gsum,   // DEEP (see above)
+    bf16_t *out1)                              // DV: dV, laid out like out0
 {
+  static_assert(!DV || (MODE == 2 && DH == 64 && NW == 4 && MC == 256), "dV rides along with the K-side gradient only");
   constexpr int KS = DH / 16, CT = DH / 32;
   constexpr int KSX = KS + 1;           // k-steps of the dPhi MFMA incl. the rank-one extension
   constexpr int AS = DH + 8;            // stride of the [feature][DH] fp16 array (16-byte reads)
@@ -1082,11 +1087,15 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
         if (h == 0) s_wave[wave * 64 + 32 * ti + l32] = cscale * __builtin_amdgcn_rcpf(dval[ti]);
     }
     f32x16 acc0[2][CT];   // N, dV (MODE 0, 3) or dX_F (MODE 1, 2): rows on registers, columns on lanes
+    f32x16 acc1[DV ? 2 : 1][DV ? CT : 1];   // DV: dV
     float dacc[2] = {0.f, 0.f};   // D partial of this lane's row (MODE 0)
 #pragma unroll
     for (int ti = 0; ti < 2; ++ti)
 #pragma unroll
-      for (int ct = 0; ct < CT; ++ct) acc0[ti][ct] = zero16();
+      for (int ct = 0; ct < CT; ++ct) {
+        acc0[ti][ct] = zero16();
+        if (DV) acc1[ti][ct] = zero16();
+      }
 
     for (int m0 = 0; m0 < m; m0 += mc) {
       if (nchunks > 1) {
@@ -1138,6 +1147,25 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
               for (int ct = 0; ct < CT; ++ct) {
                 const bf16x8 ob = lds_perm8(&s_om[(32 * ct + l32) * BS], 32 * rt + 16 * a, h);
                 acc0[ti][ct] = mfma_bf16(pg, ob, acc0[ti][ct]);
+              }
+              if (DV) {
+                // k-slot (h, q) stands for feature 32 rt + 16 a + 8 (q / 4) + 4 h + (q % 4): two
+                // transposing reads of four consecutive rows of (dS | dz) each, at column 32 ct + l32.
+                const bf16x8 pa = relu_bf16x8(pack_half(Rv[ti], a));
+                const int i16 = lane & 15, c16 = 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
+                const int frow = 32 * rt + 16 * a + 4 * h + (i16 >> 2);
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct) {
+                  const bf16x4 lo = lds_read_tr4(&s_Mx[frow * AM + 32 * ct + c16]);
+                  const bf16x4 hi = lds_read_tr4(&s_Mx[(frow + 8) * AM + 32 * ct + c16]);
+                  bf16x8 sb;
+#pragma unroll
+                  for (int q = 0; q < 4; ++q) {
+                    sb[q] = lo[q];
+                    sb[4 + q] = hi[q];
+                  }
+                  acc1[ti][ct] = mfma_bf16(pa, sb, acc1[ti][ct]);
+                }
               }
             }
           }
@@ -1223,6 +1251,10 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
     bf16_t *os = tail ? tail_out + (int64_t)slice * 64 * DH : out0 + vo.slice_base(slice) + (int64_t)t0 * vo.sn;
     const int64_t osn = tail ? DH : vo.sn;   // row stride of the output rows
     float *Dp = tail ? tail_D + slice * 64 : Dout + (int64_t)slice * n + t0;
+    // DV: the second output's rows (side buffer: behind the first output's, [2][slices][64][DH])
+    bf16_t *os1 = !DV ? nullptr
+                      : (tail ? tail_out + ((int64_t)gridDim.y + slice) * 64 * DH
+                              : out1 + vo.slice_base(slice) + (int64_t)t0 * vo.sn);
 
     if (MODE == 0 && LN) {
       // Output stage of Algorithm 1: O_t = (N_t - mean N_t) / sqrt(var N_t + eps), N = c * acc.
@@ -1407,6 +1439,18 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
       __builtin_amdgcn_wave_barrier();
       // ---- LDS -> dX
       tile_store(os, osn, 32 * ct);
+      if (DV) {   // dV tile through the same panel (its X values are used up)
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int ti = 0; ti < 2; ++ti) {
+          float o16[16];
+#pragma unroll
+          for (int i = 0; i < 16; ++i) o16[i] = cscale * acc1[ti][ct][i];
+          tile_put(ti, o16);
+        }
+        __builtin_amdgcn_wave_barrier();
+        tile_store(os1, osn, 32 * ct);
+      }
     }
     put_rows();
   }
@@ -1737,7 +1781,7 @@ FastWs fast_ws(const wersa_desc &c, const FastPlan &p, int bwd, float *base, flo
   }
   const bool deep = c.L > kTileL;
   const int ntiles = (c.n + 63) / 64;
-  w.tail_out = reinterpret_cast<bf16_t *>(b.take(sl * 64 * c.d / 2));
+  w.tail_out = reinterpret_cast<bf16_t *>(b.take(2 * sl * 64 * c.d / 2));   // (two outputs when dV rides along with dK)
   w.tail_D = b.take(sl * 64);
   w.qpart = b.take(sl * p.chunksQ * c.d);
   w.Spart = b.take(sl * p.chunksC * md);
@@ -1787,12 +1831,19 @@ size_t rows_smem_bytes(int mc) {
   return s;
 }
 
+// dV formed by the K-side gradient kernel instead of a launch of its own: head dimension 64 with
+// 256 features staged per pass, whole 64-row blocks (with a partial last block the merged kernel
+// would spill ~100 bytes per lane; those shapes keep the two launches).
+inline bool dv_rides_along(const wersa_desc &c, const FastPlan &p) {
+  return c.d == 64 && p.mc == 256 && c.n % 64 == 0;
+}
+
 template <int DH, int MODE>
 hipError_t launch_rows(const wersa_desc &c, const FastPlan &p, const _Float16 *xf, const bf16_t *x,
                        const bf16_t *y, const float *Dsaved, const float *arow, const FastWs &w,
                        const bf16_t *omega, const bf16_t *Mx, const bf16_t *MT, const bf16_t *bb,
                        bf16_t *out0, float *Dout, float *partF, hipStream_t st,
-                       const View *yview = nullptr) {
+                       const View *yview = nullptr, bf16_t *out1 = nullptr) {
   constexpr bool IS_GRAD = (MODE == 1 || MODE == 2);
   constexpr int NW = IS_GRAD ? kWavesGrad : waves_apply(DH);
   // key-side modes take the second random matrix when the descriptor has two
@@ -1812,13 +1863,24 @@ hipError_t launch_rows(const wersa_desc &c, const FastPlan &p, const _Float16 *x
                 kern<<<dim3(wgs, c.B * c.H), NW * 64, smem, st>>>(
                     xf, x, tv, y, yview ? *yview : tv, Dsaved, arow, omT, omega, Mx, MT, bb, w.coef, w.scalars,
                     c.eps, c.n, c.m, groups, out0, tv, Dout, partF, c.L, w.tail_out, w.tail_D,
-                    MODE >= 2 ? w.addK : w.addQ, MODE == 1 ? w.gsumQ : w.gsumK));
-    if (c.n % 64 != 0)
+                    MODE >= 2 ? w.addK : w.addQ, MODE == 1 ? w.gsumQ : w.gsumK, out1));
+    if (c.n % 64 != 0) {
       WERSA_STAGE("wersa_tail_copy", st,
                   tail_copy_kernel<DH><<<c.B * c.H, 256, 0, st>>>(w.tail_out, MODE == 0 ? w.tail_D : nullptr, c.n,
                                                                    c.n / 64 * 64, out0, tv, Dout));
+      if (out1)
+        WERSA_STAGE("wersa_tail_copy", st,
+                    tail_copy_kernel<DH><<<c.B * c.H, 256, 0, st>>>(w.tail_out + (int64_t)c.B * c.H * 64 * DH, nullptr, c.n,
+                                                                     c.n / 64 * 64, out1, tv, nullptr));
+    }
     return hipSuccess;
   };
+  if (out1) {   // dV rides along with the K-side gradient (see dv_rides_along)
+    constexpr bool OK = MODE == 2 && DH == 64;
+    constexpr int MCV = OK ? 256 : 128;
+    if (c.L > kTileL) return go(&rows_kernel<DH, MODE, NW, MCV, false, false, OK, OK>);
+    return go(&rows_kernel<DH, MODE, NW, MCV, false, false, false, OK>);
+  }
   const bool ln = MODE == 0 && (c.flags & WERSA_FLAG_LAYERNORM), ragged = c.n % 64 != 0;
   if (DH == 128 && IS_GRAD && c.L > kTileL) {
     // deeper than one block, head dimension 128: X_F arrives with the levels above 6 in it; the
@@ -1983,11 +2045,12 @@ wersa_status fast_backward_t(const wersa_desc &c, const bf16_t *q, const bf16_t 
                            w.partQ, st) != hipSuccess)
       return WERSA_ERR_LAUNCH;
   }
+  const bool dv_too = dv_rides_along(c, p);
   if (launch_rows<DH, 2>(c, p, KF, k, v, nullptr, nullptr, w, omega, w.dSx, nullptr, nullptr, dk, nullptr,
-                         w.partK, st) != hipSuccess)
+                         w.partK, st, nullptr, dv_too ? dv : nullptr) != hipSuccess)
     return WERSA_ERR_LAUNCH;
-  if (launch_rows<DH, 3>(c, p, KF, k, nullptr, nullptr, nullptr, w, omega, nullptr, w.dST, nullptr, dv,
-                         nullptr, nullptr, st) != hipSuccess)
+  if (!dv_too && launch_rows<DH, 3>(c, p, KF, k, nullptr, nullptr, nullptr, w, omega, nullptr, w.dST, nullptr, dv,
+                                    nullptr, nullptr, st) != hipSuccess)
     return WERSA_ERR_LAUNCH;
   const bool deep = c.L > kTileL;
   if (deep)   // levels above 6: addends of dQ and dK and the bands' extra row, from the tile sums
