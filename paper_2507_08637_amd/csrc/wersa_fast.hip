@@ -88,6 +88,12 @@ __device__ __forceinline__ f32x16 zero16() {
   for (int i = 0; i < 16; ++i) z[i] = 0.f;
   return z;
 }
+// x[lane] + x[lane ^ 32] in every lane: one swap of the upper half of a register with the lower
+// half of its copy (a VALU instruction of gfx950) and an add, instead of an exchange through LDS.
+__device__ __forceinline__ float xor32_sum(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
 __device__ __forceinline__ float wave_sum64(float v) {
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
   return v;
@@ -540,7 +546,7 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
 #pragma unroll
       for (int j = 0; j < QP; ++j) dot = dot8_bf16(po[j], pd[j], dot);
       dot += __shfl_xor(dot, 16, 64);
-      dot += __shfl_xor(dot, 32, 64);
+      dot = xor32_sum(dot);
       const float dDt = -dot / pdiv;
       if (lane < 16) {
         wl[buf][prow] = cvt_bf16(dDt);
@@ -653,7 +659,7 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
 #pragma unroll
       for (int i = 0; i < 16; ++i)
         sp[(int64_t)(f0 + 32 * rt + acc_row(i, h)) * DH + 32 * ct + l32] = S[rt][ct][i];
-    const float zt = zacc[rt] + __shfl_xor(zacc[rt], 32, 64);
+    const float zt = xor32_sum(zacc[rt]);
     if (h == 0) zpart[((int64_t)slice * chunks + chunk) * m + f0 + 32 * rt + l32] = zt;
   }
   if (PREP && blockIdx.y == 0) {   // sum of dD over this chunk's rows, fixed order
@@ -1105,38 +1111,26 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
       }
       if (!active) continue;
 
-      // Head dimension 128, gradient modes: a bound the compiler cannot see keeps the loop rolled
-      // (unrolled, the operands of several feature tiles are fetched ahead and spill).
-      int rt_end = mc / 32;
-      if (IS_GRAD && DH == 128) asm volatile("" : "+s"(rt_end));
-      for (int rt = 0; rt < rt_end; ++rt) {
-        f16x8 oa[KS];     // Omega^T rows of this feature tile: A operand of the projection
+      if (VGPR_RG) {
+        // Both row tiles' projection and dPhi chains are issued first (interleaved G R G R ...,
+        // results in VGPRs), so that the mask/pack VALU work of tile 0 runs while the matrix
+        // pipe works through tile 1's chain, and tile 1's VALU work behind tile 0's dX_F MFMAs.
+        // The feature-side A operands of the next feature tile are read from LDS while the
+        // current one is worked on (two register sets, the loop advances two tiles per round).
+        auto load_ops = [&](int rt, f16x8 *oa, bf16x8 *ma) {
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-          oa[ks] = *reinterpret_cast<const f16x8 *>(&s_omT[(32 * rt + l32) * AS + 16 * ks + 8 * h]);
-        bf16x8 ma[KSX];   // (M | b) rows of this feature tile: A operand of the dPhi MFMA
-        if (IS_GRAD) {
+          for (int ks = 0; ks < KS; ++ks)
+            oa[ks] = *reinterpret_cast<const f16x8 *>(&s_omT[(32 * rt + l32) * AS + 16 * ks + 8 * h]);
 #pragma unroll
           for (int ks = 0; ks < KSX; ++ks)
             ma[ks] = *reinterpret_cast<const bf16x8 *>(&s_Mx[(32 * rt + l32) * AM + 16 * ks + 8 * h]);
-        }
-        if (VGPR_RG) {
-          // Both row tiles' projection and dPhi chains are issued first (interleaved G R G R ...,
-          // results in VGPRs), so that the mask/pack VALU work of tile 0 runs while the matrix
-          // pipe works through tile 1's chain, and tile 1's VALU work behind tile 0's dX_F MFMAs.
-          // (Head dimension 128 has no registers to spare for that: one tile at a time.)
-          constexpr bool JOINT = (DH == 64);
+        };
+        auto body = [&](int rt, const f16x8 *oa, const bf16x8 *ma) {
           f32x16 Rv[2], Gv[2];
-          if (JOINT) {
-            chain_first(Rv[0], Gv[0], oa, xb[0], ma, yb[0]);
-            chain_first(Rv[1], Gv[1], oa, xb[1], ma, yb[1]);
-          }
+          chain_first(Rv[0], Gv[0], oa, xb[0], ma, yb[0]);
+          chain_first(Rv[1], Gv[1], oa, xb[1], ma, yb[1]);
 #pragma unroll
           for (int ti = 0; ti < 2; ++ti) {
-            if (!JOINT) {
-              chain_first(Rv[ti], Gv[ti], oa, xb[ti], ma, yb[ti]);
-              if (DH == 128) chain_more(Rv[ti], Gv[ti], oa + 4, xb[ti] + 4, ma + 5, yb[ti] + 5);
-            }
 #pragma unroll
             for (int i = 0; i < 16; ++i)
               Gv[ti][i] *= __builtin_amdgcn_fmed3f(Rv[ti][i] * 0x1p+100f, 0.f, 1.f);
@@ -1169,7 +1163,33 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
               }
             }
           }
-          continue;
+        };
+        constexpr int TILES = MC / 32;
+        f16x8 oaA[KS], oaB[KS];
+        bf16x8 maA[KSX], maB[KSX];
+        load_ops(0, oaA, maA);
+        for (int rt = 0; rt < TILES; rt += 2) {
+          load_ops(rt + 1, oaB, maB);
+          body(rt, oaA, maA);
+          load_ops((rt + 2) & (TILES - 1), oaA, maA);   // (the last round re-reads tile 0: in bounds, unused)
+          body(rt + 1, oaB, maB);
+        }
+        continue;
+      }
+      // Head dimension 128, gradient modes: a bound the compiler cannot see keeps the loop rolled
+      // (unrolled, the operands of several feature tiles are fetched ahead and spill).
+      int rt_end = mc / 32;
+      if (IS_GRAD && DH == 128) asm volatile("" : "+s"(rt_end));
+      for (int rt = 0; rt < rt_end; ++rt) {
+        f16x8 oa[KS];     // Omega^T rows of this feature tile: A operand of the projection
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+          oa[ks] = *reinterpret_cast<const f16x8 *>(&s_omT[(32 * rt + l32) * AS + 16 * ks + 8 * h]);
+        bf16x8 ma[KSX];   // (M | b) rows of this feature tile: A operand of the dPhi MFMA
+        if (IS_GRAD) {
+#pragma unroll
+          for (int ks = 0; ks < KSX; ++ks)
+            ma[ks] = *reinterpret_cast<const bf16x8 *>(&s_Mx[(32 * rt + l32) * AM + 16 * ks + 8 * h]);
         }
 #pragma unroll
         for (int ti = 0; ti < 2; ++ti) {
@@ -1287,7 +1307,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
       float *dl = s_wave + wave * 64;
 #pragma unroll
       for (int ti = 0; ti < 2; ++ti) {
-        const float dsum = dacc[ti] + __shfl_xor(dacc[ti], 32, 64);
+        const float dsum = xor32_sum(dacc[ti]);
         const float Dt = fmaf(cscale, dsum, eps);
         // both half-waves hold the same sum and write the same values: no branch around the store
         dl[32 * ti + l32] = cscale * __builtin_amdgcn_rcpf(Dt);
@@ -1386,8 +1406,8 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
         for (int k = 0; k < 4; ++k) {
           const float g2 = g1[2 * k] + g1[2 * k + 1], x2 = x1[2 * k] + x1[2 * k + 1];
           u[2] = fmaf(g2, x2, u[2]);
-          g3[k] = g2 + __shfl_xor(g2, 32, 64);   // 8-row blocks: both half-waves hold the same sums
-          x3[k] = x2 + __shfl_xor(x2, 32, 64);
+          g3[k] = xor32_sum(g2);   // 8-row blocks: both half-waves hold the same sums
+          x3[k] = xor32_sum(x2);
           u[3] = fmaf(0.5f * g3[k], x3[k], u[3]);
         }
         const float g4a = g3[0] + g3[1], g4b = g3[2] + g3[3];
@@ -1413,7 +1433,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
           g2[k] = g1[2 * k] + g1[2 * k + 1];
-          g3[k] = g2[k] + __shfl_xor(g2[k], 32, 64);
+          g3[k] = xor32_sum(g2[k]);
         }
 #pragma unroll
         for (int k2 = 0; k2 < 2; ++k2) {
