@@ -66,6 +66,137 @@ __device__ __forceinline__ void chain_first(f32x16 &R, f32x16 &G, const f16x8 *o
         "v"(ma[0]), "v"(ma[1]), "v"(ma[2]), "v"(ma[3]), "v"(ma[4]), "v"(yb[0]), "v"(yb[1]), "v"(yb[2]),
         "v"(yb[3]), "v"(yb[4]));
 }
+// The same chains with their results in fixed registers (tile 0 of a 64-row block: R, G in
+// v[192:207], v[208:223]; tile 1: v[224:239], v[240:255]), so that a chain's statement can also
+// carry the mask multiplies of the OTHER tile's finished chain, G_i *= clamp(R_i * 2^100, 0, 1),
+// written on those registers between its MFMAs: the VALU work runs while the matrix pipe works
+// through the chain instead of after it.  Hazards: the masked registers were written by the
+// previous chain statement, which ends with the wait states its last MFMA needs; no MFMA here
+// reads a register the multiplies write.
+__device__ __forceinline__ void chain0_first(f32x16 &R0, f32x16 &G0, const f16x8 *oa, const f16x8 *xb,
+                                             const bf16x8 *ma, const bf16x8 *yb) {
+  asm volatile(
+      "v_mfma_f32_32x32x16_bf16 %1, %10, %15, 0\n\t"
+      "v_mfma_f32_32x32x16_f16 %0, %2, %6, 0\n\t"
+      "v_mfma_f32_32x32x16_bf16 %1, %11, %16, %1\n\t"
+      "v_mfma_f32_32x32x16_f16 %0, %3, %7, %0\n\t"
+      "v_mfma_f32_32x32x16_bf16 %1, %12, %17, %1\n\t"
+      "v_mfma_f32_32x32x16_f16 %0, %4, %8, %0\n\t"
+      "v_mfma_f32_32x32x16_bf16 %1, %13, %18, %1\n\t"
+      "v_mfma_f32_32x32x16_f16 %0, %5, %9, %0\n\t"
+      "v_mfma_f32_32x32x16_bf16 %1, %14, %19, %1\n\t"
+      "s_nop 11"
+      : "=&{v[192:207]}"(R0), "=&{v[208:223]}"(G0)
+      : "v"(oa[0]), "v"(oa[1]), "v"(oa[2]), "v"(oa[3]), "v"(xb[0]), "v"(xb[1]), "v"(xb[2]), "v"(xb[3]),
+        "v"(ma[0]), "v"(ma[1]), "v"(ma[2]), "v"(ma[3]), "v"(ma[4]), "v"(yb[0]), "v"(yb[1]), "v"(yb[2]),
+        "v"(yb[3]), "v"(yb[4]));
+}
+// chain of tile 1 (R1, G1) with the mask of tile 0 (G0 *= 1[R0 > 0])
+__device__ __forceinline__ void chain1_mask0(f32x16 &R1, f32x16 &G1, f32x16 &G0, const f32x16 &R0,
+                                             const f16x8 *oa, const f16x8 *xb, const bf16x8 *ma,
+                                             const bf16x8 *yb, float big) {
+  float tmp;
+  asm volatile(
+      "v_mfma_f32_32x32x16_bf16 %1, %12, %17, 0\n\t"
+      "v_mul_f32_e64 %3, v192, %23 clamp\n\t"
+      "v_mul_f32_e32 v208, v208, %3\n\t"
+      "v_mul_f32_e64 %3, v193, %23 clamp\n\t"
+      "v_mul_f32_e32 v209, v209, %3\n\t"
+      "v_mfma_f32_32x32x16_f16 %0, %4, %8, 0\n\t"
+      "v_mul_f32_e64 %3, v194, %23 clamp\n\t"
+      "v_mul_f32_e32 v210, v210, %3\n\t"
+      "v_mul_f32_e64 %3, v195, %23 clamp\n\t"
+      "v_mul_f32_e32 v211, v211, %3\n\t"
+      "v_mfma_f32_32x32x16_bf16 %1, %13, %18, %1\n\t"
+      "v_mul_f32_e64 %3, v196, %23 clamp\n\t"
+      "v_mul_f32_e32 v212, v212, %3\n\t"
+      "v_mul_f32_e64 %3, v197, %23 clamp\n\t"
+      "v_mul_f32_e32 v213, v213, %3\n\t"
+      "v_mfma_f32_32x32x16_f16 %0, %5, %9, %0\n\t"
+      "v_mul_f32_e64 %3, v198, %23 clamp\n\t"
+      "v_mul_f32_e32 v214, v214, %3\n\t"
+      "v_mul_f32_e64 %3, v199, %23 clamp\n\t"
+      "v_mul_f32_e32 v215, v215, %3\n\t"
+      "v_mfma_f32_32x32x16_bf16 %1, %14, %19, %1\n\t"
+      "v_mul_f32_e64 %3, v200, %23 clamp\n\t"
+      "v_mul_f32_e32 v216, v216, %3\n\t"
+      "v_mul_f32_e64 %3, v201, %23 clamp\n\t"
+      "v_mul_f32_e32 v217, v217, %3\n\t"
+      "v_mfma_f32_32x32x16_f16 %0, %6, %10, %0\n\t"
+      "v_mul_f32_e64 %3, v202, %23 clamp\n\t"
+      "v_mul_f32_e32 v218, v218, %3\n\t"
+      "v_mul_f32_e64 %3, v203, %23 clamp\n\t"
+      "v_mul_f32_e32 v219, v219, %3\n\t"
+      "v_mfma_f32_32x32x16_bf16 %1, %15, %20, %1\n\t"
+      "v_mul_f32_e64 %3, v204, %23 clamp\n\t"
+      "v_mul_f32_e32 v220, v220, %3\n\t"
+      "v_mul_f32_e64 %3, v205, %23 clamp\n\t"
+      "v_mul_f32_e32 v221, v221, %3\n\t"
+      "v_mfma_f32_32x32x16_f16 %0, %7, %11, %0\n\t"
+      "v_mul_f32_e64 %3, v206, %23 clamp\n\t"
+      "v_mul_f32_e32 v222, v222, %3\n\t"
+      "v_mul_f32_e64 %3, v207, %23 clamp\n\t"
+      "v_mul_f32_e32 v223, v223, %3\n\t"
+      "v_mfma_f32_32x32x16_bf16 %1, %16, %21, %1\n\t"
+      "s_nop 11"
+      : "=&{v[224:239]}"(R1), "=&{v[240:255]}"(G1), "+{v[208:223]}"(G0), "=&v"(tmp)
+      : "v"(oa[0]), "v"(oa[1]), "v"(oa[2]), "v"(oa[3]), "v"(xb[0]), "v"(xb[1]), "v"(xb[2]), "v"(xb[3]),
+        "v"(ma[0]), "v"(ma[1]), "v"(ma[2]), "v"(ma[3]), "v"(ma[4]), "v"(yb[0]), "v"(yb[1]), "v"(yb[2]),
+        "v"(yb[3]), "v"(yb[4]), "{v[192:207]}"(R0), "s"(big));
+}
+// chain of tile 0 (R0, G0) of the next feature tile with the mask of tile 1 (G1 *= 1[R1 > 0])
+__device__ __forceinline__ void chain0_mask1(f32x16 &R0, f32x16 &G0, f32x16 &G1, const f32x16 &R1,
+                                             const f16x8 *oa, const f16x8 *xb, const bf16x8 *ma,
+                                             const bf16x8 *yb, float big) {
+  float tmp;
+  asm volatile(
+      "v_mfma_f32_32x32x16_bf16 %1, %12, %17, 0\n\t"
+      "v_mul_f32_e64 %3, v224, %23 clamp\n\t"
+      "v_mul_f32_e32 v240, v240, %3\n\t"
+      "v_mul_f32_e64 %3, v225, %23 clamp\n\t"
+      "v_mul_f32_e32 v241, v241, %3\n\t"
+      "v_mfma_f32_32x32x16_f16 %0, %4, %8, 0\n\t"
+      "v_mul_f32_e64 %3, v226, %23 clamp\n\t"
+      "v_mul_f32_e32 v242, v242, %3\n\t"
+      "v_mul_f32_e64 %3, v227, %23 clamp\n\t"
+      "v_mul_f32_e32 v243, v243, %3\n\t"
+      "v_mfma_f32_32x32x16_bf16 %1, %13, %18, %1\n\t"
+      "v_mul_f32_e64 %3, v228, %23 clamp\n\t"
+      "v_mul_f32_e32 v244, v244, %3\n\t"
+      "v_mul_f32_e64 %3, v229, %23 clamp\n\t"
+      "v_mul_f32_e32 v245, v245, %3\n\t"
+      "v_mfma_f32_32x32x16_f16 %0, %5, %9, %0\n\t"
+      "v_mul_f32_e64 %3, v230, %23 clamp\n\t"
+      "v_mul_f32_e32 v246, v246, %3\n\t"
+      "v_mul_f32_e64 %3, v231, %23 clamp\n\t"
+      "v_mul_f32_e32 v247, v247, %3\n\t"
+      "v_mfma_f32_32x32x16_bf16 %1, %14, %19, %1\n\t"
+      "v_mul_f32_e64 %3, v232, %23 clamp\n\t"
+      "v_mul_f32_e32 v248, v248, %3\n\t"
+      "v_mul_f32_e64 %3, v233, %23 clamp\n\t"
+      "v_mul_f32_e32 v249, v249, %3\n\t"
+      "v_mfma_f32_32x32x16_f16 %0, %6, %10, %0\n\t"
+      "v_mul_f32_e64 %3, v234, %23 clamp\n\t"
+      "v_mul_f32_e32 v250, v250, %3\n\t"
+      "v_mul_f32_e64 %3, v235, %23 clamp\n\t"
+      "v_mul_f32_e32 v251, v251, %3\n\t"
+      "v_mfma_f32_32x32x16_bf16 %1, %15, %20, %1\n\t"
+      "v_mul_f32_e64 %3, v236, %23 clamp\n\t"
+      "v_mul_f32_e32 v252, v252, %3\n\t"
+      "v_mul_f32_e64 %3, v237, %23 clamp\n\t"
+      "v_mul_f32_e32 v253, v253, %3\n\t"
+      "v_mfma_f32_32x32x16_f16 %0, %7, %11, %0\n\t"
+      "v_mul_f32_e64 %3, v238, %23 clamp\n\t"
+      "v_mul_f32_e32 v254, v254, %3\n\t"
+      "v_mul_f32_e64 %3, v239, %23 clamp\n\t"
+      "v_mul_f32_e32 v255, v255, %3\n\t"
+      "v_mfma_f32_32x32x16_bf16 %1, %16, %21, %1\n\t"
+      "s_nop 11"
+      : "=&{v[192:207]}"(R0), "=&{v[208:223]}"(G0), "+{v[240:255]}"(G1), "=&v"(tmp)
+      : "v"(oa[0]), "v"(oa[1]), "v"(oa[2]), "v"(oa[3]), "v"(xb[0]), "v"(xb[1]), "v"(xb[2]), "v"(xb[3]),
+        "v"(ma[0]), "v"(ma[1]), "v"(ma[2]), "v"(ma[3]), "v"(ma[4]), "v"(yb[0]), "v"(yb[1]), "v"(yb[2]),
+        "v"(yb[3]), "v"(yb[4]), "{v[224:239]}"(R1), "s"(big));
+}
 __device__ __forceinline__ void chain_more(f32x16 &R, f32x16 &G, const f16x8 *oa, const f16x8 *xb,
                                            const bf16x8 *ma, const bf16x8 *yb) {
   asm volatile(
@@ -1112,11 +1243,8 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
       if (!active) continue;
 
       if (VGPR_RG) {
-        // Both row tiles' projection and dPhi chains are issued first (interleaved G R G R ...,
-        // results in VGPRs), so that the mask/pack VALU work of tile 0 runs while the matrix
-        // pipe works through tile 1's chain, and tile 1's VALU work behind tile 0's dX_F MFMAs.
-        // The feature-side A operands of the next feature tile are read from LDS while the
-        // current one is worked on (two register sets, the loop advances two tiles per round).
+        // The feature-side A operands of the next feature tile are read from LDS as soon as the
+        // current tile's second chain has taken them.
         auto load_ops = [&](int rt, f16x8 *oa, bf16x8 *ma) {
 #pragma unroll
           for (int ks = 0; ks < KS; ++ks)
@@ -1125,54 +1253,106 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
           for (int ks = 0; ks < KSX; ++ks)
             ma[ks] = *reinterpret_cast<const bf16x8 *>(&s_Mx[(32 * rt + l32) * AM + 16 * ks + 8 * h]);
         };
-        auto body = [&](int rt, const f16x8 *oa, const bf16x8 *ma) {
-          f32x16 Rv[2], Gv[2];
-          chain_first(Rv[0], Gv[0], oa, xb[0], ma, yb[0]);
-          chain_first(Rv[1], Gv[1], oa, xb[1], ma, yb[1]);
+        // The B operands of what follows a chain are read from LDS BEFORE the chain's statement
+        // (the compiler moves no LDS read across it): Omega[c][f] for dX_F, and for dV the rows of
+        // (dS | dz) through transposing reads (k-slot (h, q) stands for feature
+        // 32 rt + 16 a + 8 (q / 4) + 4 h + (q % 4): two reads of four consecutive rows each, at
+        // column 32 ct + l32).  Both row tiles of a feature tile use the same operands.
+        auto read_ob = [&](int rt, bf16x8 (*ob)[CT]) {
 #pragma unroll
-          for (int ti = 0; ti < 2; ++ti) {
+          for (int a = 0; a < 2; ++a)
 #pragma unroll
-            for (int i = 0; i < 16; ++i)
-              Gv[ti][i] *= __builtin_amdgcn_fmed3f(Rv[ti][i] * 0x1p+100f, 0.f, 1.f);
+            for (int ct = 0; ct < CT; ++ct)
+              ob[a][ct] = lds_perm8(&s_om[(32 * ct + l32) * BS], 32 * rt + 16 * a, h);
+        };
+        auto read_sb = [&](int rt, bf16x8 (*sb)[CT]) {
+          const int i16 = lane & 15, c16 = 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
 #pragma unroll
-            for (int a = 0; a < 2; ++a) {
-              const bf16x8 pg = pack_half(Gv[ti], a);
+          for (int a = 0; a < 2; ++a) {
+            const int frow = 32 * rt + 16 * a + 4 * h + (i16 >> 2);
 #pragma unroll
-              for (int ct = 0; ct < CT; ++ct) {
-                const bf16x8 ob = lds_perm8(&s_om[(32 * ct + l32) * BS], 32 * rt + 16 * a, h);
-                acc0[ti][ct] = mfma_bf16(pg, ob, acc0[ti][ct]);
-              }
-              if (DV) {
-                // k-slot (h, q) stands for feature 32 rt + 16 a + 8 (q / 4) + 4 h + (q % 4): two
-                // transposing reads of four consecutive rows of (dS | dz) each, at column 32 ct + l32.
-                const bf16x8 pa = relu_bf16x8(pack_half(Rv[ti], a));
-                const int i16 = lane & 15, c16 = 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
-                const int frow = 32 * rt + 16 * a + 4 * h + (i16 >> 2);
+            for (int ct = 0; ct < CT; ++ct) {
+              const bf16x4 lo = lds_read_tr4(&s_Mx[frow * AM + 32 * ct + c16]);
+              const bf16x4 hi = lds_read_tr4(&s_Mx[(frow + 8) * AM + 32 * ct + c16]);
 #pragma unroll
-                for (int ct = 0; ct < CT; ++ct) {
-                  const bf16x4 lo = lds_read_tr4(&s_Mx[frow * AM + 32 * ct + c16]);
-                  const bf16x4 hi = lds_read_tr4(&s_Mx[(frow + 8) * AM + 32 * ct + c16]);
-                  bf16x8 sb;
-#pragma unroll
-                  for (int q = 0; q < 4; ++q) {
-                    sb[q] = lo[q];
-                    sb[4 + q] = hi[q];
-                  }
-                  acc1[ti][ct] = mfma_bf16(pa, sb, acc1[ti][ct]);
-                }
+              for (int q = 0; q < 4; ++q) {
+                sb[a][ct][q] = lo[q];
+                sb[a][ct][4 + q] = hi[q];
               }
             }
           }
         };
-        constexpr int TILES = MC / 32;
-        f16x8 oaA[KS], oaB[KS];
-        bf16x8 maA[KSX], maB[KSX];
-        load_ops(0, oaA, maA);
-        for (int rt = 0; rt < TILES; rt += 2) {
-          load_ops(rt + 1, oaB, maB);
-          body(rt, oaA, maA);
-          load_ops((rt + 2) & (TILES - 1), oaA, maA);   // (the last round re-reads tile 0: in bounds, unused)
-          body(rt + 1, oaB, maB);
+        // What follows a masked chain: pack to bf16, dX_F += dR Omega^T (and dV += relu(R) dS).
+        auto consume = [&](int ti, const f32x16 &Rt, const f32x16 &Gt, const bf16x8 (*ob)[CT],
+                           const bf16x8 (*sb)[CT]) {
+#pragma unroll
+          for (int a = 0; a < 2; ++a) {
+            const bf16x8 pg = pack_half(Gt, a);
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) acc0[ti][ct] = mfma_bf16(pg, ob[a][ct], acc0[ti][ct]);
+            if (DV) {
+              const bf16x8 pa = relu_bf16x8(pack_half(Rt, a));
+#pragma unroll
+              for (int ct = 0; ct < CT; ++ct) acc1[ti][ct] = mfma_bf16(pa, sb[a][ct], acc1[ti][ct]);
+            }
+          }
+        };
+        // The pipelined form keeps two more chain results alive than the plain one: it is used where
+        // the registers allow it without spills (not next to the dV accumulators, not with the
+        // partial-block code).
+        constexpr bool PIPE = !DV && !RAGGED;
+        if (PIPE) {
+          // Software pipeline over the feature tiles: while the matrix pipe works through the
+          // chain of one row tile, the VALU masks the other row tile's finished chain (inside the
+          // chain statements above); pack and dX_F MFMAs of a masked tile follow.  Per feature tile:
+          //   chain of row tile 1 | mask of row tile 0, consume row tile 0,
+          //   chain of row tile 0 of the NEXT feature tile | mask of row tile 1, consume row tile 1.
+          constexpr int TILES = MC / 32;
+          constexpr float kBig = 0x1p+100f;   // clamp(R * 2^100, 0, 1) = 1[R > 0] for every R > 2^-100
+          f16x8 oa[KS];     // Omega^T rows of a feature tile: A operand of the projection
+          bf16x8 ma[KSX];   // (M | b) rows of the same tile: A operand of the dPhi MFMA
+          bf16x8 ob[2][CT];
+          f32x16 R0, G0, R1, G1;
+          load_ops(0, oa, ma);
+          chain0_first(R0, G0, oa, xb[0], ma, yb[0]);
+          for (int rt = 0; rt < TILES - 1; ++rt) {
+            read_ob(rt, ob);
+            chain1_mask0(R1, G1, G0, R0, oa, xb[1], ma, yb[1], kBig);
+            load_ops(rt + 1, oa, ma);   // (lands while row tile 0 is consumed)
+            consume(0, R0, G0, ob, nullptr);
+            chain0_mask1(R0, G0, G1, R1, oa, xb[0], ma, yb[0], kBig);
+            consume(1, R1, G1, ob, nullptr);
+          }
+          {   // the last feature tile: no chain follows it
+            read_ob(TILES - 1, ob);
+            chain1_mask0(R1, G1, G0, R0, oa, xb[1], ma, yb[1], kBig);
+            consume(0, R0, G0, ob, nullptr);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) G1[i] *= __builtin_amdgcn_fmed3f(R1[i] * kBig, 0.f, 1.f);
+            consume(1, R1, G1, ob, nullptr);
+          }
+        } else {
+          // Both row tiles' chains first, then mask, pack and the MFMAs that follow, tile by tile.
+          constexpr int TILES = MC / 32;
+          f16x8 oa[KS];
+          bf16x8 ma[KSX];
+          load_ops(0, oa, ma);
+          for (int rt = 0; rt < TILES; ++rt) {
+            bf16x8 ob[2][CT], sb[DV ? 2 : 1][CT];
+            read_ob(rt, ob);
+            if (DV) read_sb(rt, sb);
+            f32x16 Rv[2], Gv[2];
+            chain_first(Rv[0], Gv[0], oa, xb[0], ma, yb[0]);
+            chain_first(Rv[1], Gv[1], oa, xb[1], ma, yb[1]);
+            load_ops((rt + 1) & (TILES - 1), oa, ma);   // (the last round re-reads tile 0: in bounds, unused)
+#pragma unroll
+            for (int ti = 0; ti < 2; ++ti) {
+#pragma unroll
+              for (int i = 0; i < 16; ++i)
+                Gv[ti][i] *= __builtin_amdgcn_fmed3f(Rv[ti][i] * 0x1p+100f, 0.f, 1.f);
+              consume(ti, Rv[ti], Gv[ti], ob, sb);
+            }
+          }
         }
         continue;
       }
