@@ -696,12 +696,17 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
   __syncthreads();
   // FUSE: rows 32 (wave / 2) + l32 of G are this wave's B operands in every step: kept in
   // registers (high part for the four k-steps, low part for the two of the quarter's own half).
+  // The k-steps are taken own half first (ks_own, ks_own + 1: high and low part), then the other
+  // half (high part only), so that the step loop has no branch and its LDS reads go out together.
   bf16x8 ghi[4], glo[2];
+  const int ks_own = 2 * (wave >> 1), ks_oth = ks_own ^ 2;
   if (FUSE) {
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) ghi[ks] = filter_operand(gt, 0, 32 * (wave >> 1) + l32, 2 * ks + h);
-#pragma unroll
-    for (int u = 0; u < 2; ++u) glo[u] = filter_operand(gt, 1, 32 * (wave >> 1) + l32, 2 * (2 * (wave >> 1) + u) + h);
+    for (int u = 0; u < 2; ++u) {
+      ghi[u] = filter_operand(gt, 0, 32 * (wave >> 1) + l32, 2 * (ks_own + u) + h);
+      ghi[2 + u] = filter_operand(gt, 0, 32 * (wave >> 1) + l32, 2 * (ks_oth + u) + h);
+      glo[u] = filter_operand(gt, 1, 32 * (wave >> 1) + l32, 2 * (ks_own + u) + h);
+    }
   }
   for (int s = 0; s < steps; ++s) {
     const int buf = s & 1;
@@ -719,13 +724,19 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
 #pragma unroll
         for (int i = 0; i < 16; ++i) q[i] = ta[acc_row(i, h)];
       }
+      bf16x8 xa[4];
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        const bf16x8 xa = tile_cols_operand<false>(raw, XS, 32 * (wave & 1), ks, lane);
-        q = mfma_bf16(xa, ghi[ks], q);
-        // the low part matters inside the quarter's own 32-row half only (wave-uniform branch)
-        if ((ks >> 1) == (wave >> 1)) q2 = mfma_bf16(xa, glo[ks & 1], q2);
+      for (int u = 0; u < 2; ++u) {
+        xa[u] = tile_cols_operand<false>(raw, XS, 32 * (wave & 1), ks_own + u, lane);
+        xa[2 + u] = tile_cols_operand<false>(raw, XS, 32 * (wave & 1), ks_oth + u, lane);
       }
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {   // the low part matters inside the quarter's own 32-row half only
+        q = mfma_bf16(xa[u], ghi[u], q);
+        q2 = mfma_bf16(xa[u], glo[u], q2);
+      }
+#pragma unroll
+      for (int u = 0; u < 2; ++u) q = mfma_bf16(xa[2 + u], ghi[2 + u], q);
 #pragma unroll
       for (int i = 0; i < 16; ++i) q[i] += q2[i];
       // accumulator register i is column 32 (wave % 2) + acc_row(i, h), lane l32 is row 32 (wave / 2) + l32
@@ -2130,19 +2141,18 @@ void launch_contract(const wersa_desc &c, const FastPlan &p, const _Float16 *xf,
                                            w.zpart));
   };
   const bool ragged = c.n % 64 != 0, deep = DH == 64 && c.L > kTileL;
+  constexpr int FWB = DH == 64 ? 64 : 32;   // 64 features per wave exist for head dimension 64 only (see fast_plan)
+  constexpr bool D64 = DH == 64;
+  const bool wide = p.FW == 64;
   if (deep && ragged) {
-    if (p.FW == 64) orows ? go(&phiT_contract_kernel<DH, 64, true, DH == 64, DH == 64>)
-                          : go(&phiT_contract_kernel<DH, 64, false, DH == 64, DH == 64>);
-    else orows ? go(&phiT_contract_kernel<DH, 32, true, DH == 64, DH == 64>)
-               : go(&phiT_contract_kernel<DH, 32, false, DH == 64, DH == 64>);
+    if (wide) orows ? go(&phiT_contract_kernel<DH, FWB, true, D64, D64>) : go(&phiT_contract_kernel<DH, FWB, false, D64, D64>);
+    else orows ? go(&phiT_contract_kernel<DH, 32, true, D64, D64>) : go(&phiT_contract_kernel<DH, 32, false, D64, D64>);
   } else if (deep) {
-    if (p.FW == 64) orows ? go(&phiT_contract_kernel<DH, 64, true, false, DH == 64>)
-                          : go(&phiT_contract_kernel<DH, 64, false, false, DH == 64>);
-    else orows ? go(&phiT_contract_kernel<DH, 32, true, false, DH == 64>)
-               : go(&phiT_contract_kernel<DH, 32, false, false, DH == 64>);
-  } else if (p.FW == 64) {
-    if (orows) ragged ? go(&phiT_contract_kernel<DH, 64, true, true, false>) : go(&phiT_contract_kernel<DH, 64, true, false, false>);
-    else ragged ? go(&phiT_contract_kernel<DH, 64, false, true, false>) : go(&phiT_contract_kernel<DH, 64, false, false, false>);
+    if (wide) orows ? go(&phiT_contract_kernel<DH, FWB, true, false, D64>) : go(&phiT_contract_kernel<DH, FWB, false, false, D64>);
+    else orows ? go(&phiT_contract_kernel<DH, 32, true, false, D64>) : go(&phiT_contract_kernel<DH, 32, false, false, D64>);
+  } else if (wide) {
+    if (orows) ragged ? go(&phiT_contract_kernel<DH, FWB, true, true, false>) : go(&phiT_contract_kernel<DH, FWB, true, false, false>);
+    else ragged ? go(&phiT_contract_kernel<DH, FWB, false, true, false>) : go(&phiT_contract_kernel<DH, FWB, false, false, false>);
   } else {
     if (orows) ragged ? go(&phiT_contract_kernel<DH, 32, true, true, false>) : go(&phiT_contract_kernel<DH, 32, true, false, false>);
     else ragged ? go(&phiT_contract_kernel<DH, 32, false, true, false>) : go(&phiT_contract_kernel<DH, 32, false, false, false>);
@@ -2229,22 +2239,19 @@ wersa_status fast_backward_t(const wersa_desc &c, const bf16_t *q, const bf16_t 
 
   // dS = Phi_Q^T dN, dz = Phi_Q^T dD; the same pass derives dD_t = -<dO_t, O_t> / D_t from the
   // rows of O and leaves it in the workspace for the Q-side gradient kernel.
-  if (c.flags & WERSA_FLAG_LAYERNORM) {
-    // LayerNorm output stage: dN first, then the same kernels with D = 1 and dD = 0 (so dz = 0).
-    const View nv{(int64_t)c.H * c.n * DH, (int64_t)c.n * DH, DH, c.H};
+  const bool ln = (c.flags & WERSA_FLAG_LAYERNORM) != 0;
+  // LayerNorm output stage: dN first, then the same kernels with D = 1 and dD = 0 (so dz = 0).
+  const View nv{(int64_t)c.H * c.n * DH, (int64_t)c.n * DH, DH, c.H};
+  if (ln) {
     WERSA_STAGE("wersa_ln_prep", st,
                 ln_prep_kernel<DH><<<dim3(p.chunksC, slices), 256, 0, st>>>(dout, out, tv, D, c.n, p.rowsC, w.dN,
                                                                            w.ones, w.dD, w.dDpart));
     launch_contract<DH>(c, p, QF, q, w.dN, nv, nullptr, w.dD, nullptr, false, w, w.dS, w.dz, w.dSx, w.dST, w.dzb, st);
-    if (launch_rows<DH, 1>(c, p, QF, q, w.dN, w.ones, w.dD, w, omega, w.Sx, nullptr, nullptr, dq, nullptr,
-                           w.partQ, st, &nv) != hipSuccess)
-      return WERSA_ERR_LAUNCH;
   } else {
     launch_contract<DH>(c, p, QF, q, dout, tv, D, nullptr, out, false, w, w.dS, w.dz, w.dSx, w.dST, w.dzb, st);
-    if (launch_rows<DH, 1>(c, p, QF, q, dout, D, w.dD, w, omega, w.Sx, nullptr, nullptr, dq, nullptr,
-                           w.partQ, st) != hipSuccess)
-      return WERSA_ERR_LAUNCH;
   }
+  // K side first: the Q-side kernel then is the last writer of a large tensor before the pass
+  // that adds the pooled-query term to dQ, which finds part of dQ still in the last-level cache.
   const bool dv_too = dv_rides_along(c, p);
   if (launch_rows<DH, 2>(c, p, KF, k, v, nullptr, nullptr, w, omega, w.dSx, nullptr, nullptr, dk, nullptr,
                          w.partK, st, nullptr, dv_too ? dv : nullptr) != hipSuccess)
@@ -2252,6 +2259,15 @@ wersa_status fast_backward_t(const wersa_desc &c, const bf16_t *q, const bf16_t 
   if (!dv_too && launch_rows<DH, 3>(c, p, KF, k, nullptr, nullptr, nullptr, w, omega, nullptr, w.dST, nullptr, dv,
                                     nullptr, nullptr, st) != hipSuccess)
     return WERSA_ERR_LAUNCH;
+  if (ln) {
+    if (launch_rows<DH, 1>(c, p, QF, q, w.dN, w.ones, w.dD, w, omega, w.Sx, nullptr, nullptr, dq, nullptr,
+                           w.partQ, st, &nv) != hipSuccess)
+      return WERSA_ERR_LAUNCH;
+  } else {
+    if (launch_rows<DH, 1>(c, p, QF, q, dout, D, w.dD, w, omega, w.Sx, nullptr, nullptr, dq, nullptr,
+                           w.partQ, st) != hipSuccess)
+      return WERSA_ERR_LAUNCH;
+  }
   const bool deep = c.L > kTileL;
   if (deep)   // levels above 6: addends of dQ and dK and the bands' extra row, from the tile sums
     WERSA_STAGE("wersa_coarse_bwd", st,
