@@ -2275,7 +2275,7 @@ wersa_status fast_backward_t(const wersa_desc &c, const bf16_t *q, const bf16_t 
                                                                    (c.n + 63) / 64, DH, c.L, w.pyr, w.gaddQ, w.gaddK,
                                                                    w.partQ, w.partK, p.rowsWgsG));
   WERSA_STAGE("gate_bwd_slice_kernel", st,
-              gate_bwd_slice_kernel<<<slices, 64, 0, st>>>(w.partQ, w.partK, deep ? p.rowsWgsG + DH / kCoarseCols : p.rowsWgsG, c.L,
+              gate_bwd_slice_kernel<<<slices, kGateBwdThreads, 0, st>>>(w.partQ, w.partK, deep ? p.rowsWgsG + DH / kCoarseCols : p.rowsWgsG, c.L,
                                                            c.d, c.H, s, gate_w, scale_w, w.dF, w.dlogit, w.dqbar,
                                                            (c.flags & WERSA_FLAG_POOLED_GATE) ? 1 : 0));
   WERSA_STAGE("gate_bwd_params_kernel", st,

@@ -725,7 +725,7 @@ wersa_status backward_t(const wersa_desc &c, const T *q, const T *k, const T *v,
   const int64_t tiles = (int64_t)tgrid.x * tgrid.y;
   launch_band_dots<T>(c, q, tv, w.QF, w.partQ, w.deepA, w.deepB, st);
   launch_band_dots<T>(c, k, tv, w.KF, w.partK, w.deepA, w.deepB, st);
-  WERSA_STAGE("gate_bwd_slice_kernel", st, gate_bwd_slice_kernel<<<slices, 64, 0, st>>>(w.partQ, w.partK, tiles, c.L, c.d, c.H, s, gate_w,
+  WERSA_STAGE("gate_bwd_slice_kernel", st, gate_bwd_slice_kernel<<<slices, kGateBwdThreads, 0, st>>>(w.partQ, w.partK, tiles, c.L, c.d, c.H, s, gate_w,
                                                scale_w, w.dF, w.dlogit, w.dqbar, (c.flags & WERSA_FLAG_POOLED_GATE) ? 1 : 0));
   WERSA_STAGE("gate_bwd_params_kernel", st, gate_bwd_params_kernel<<<gate_bwd_params_blocks(c.H, c.L, c.d), 256, 0, st>>>(w.dF, w.dlogit, s, qbar, w.dDpart,
                                             slices * colsum_chunks(c.n), c.B, c.H, c.L, c.d, c.eps,
