@@ -26,8 +26,8 @@ PEAK = {"hbm": (8000.0, "GB/s"), "mfma_bf16": (2500.0, "TFLOP/s"), "fp32": (157.
 MIB = 1024.0 * 1024.0
 SURVEY_STEPS = 5   # untimed steps with every launch bracketed, to rank the kernels
 MEASURED_TRAFFIC_CONFIG4 = {
-    "wersa_rows_fwd": (137.7 + 134.9) * MIB, "wersa_rows_bwd_q": (270.6 + 131.8) * MIB,
-    "wersa_rows_bwd_k": (275.1 + 261.2) * MIB,   # with dV
+    "wersa_rows_fwd": (137.8 + 135.0) * MIB, "wersa_rows_bwd_q": (272.0 + 128.9) * MIB,
+    "wersa_rows_bwd_k": (267.8 + 258.4) * MIB,   # with dV
     "wersa_phiT_contract": ((256.4 + 32.5) + (388.4 + 36.5)) / 2 * MIB,   # average of the two launches
     "wersa_qbar": 128.3 * MIB, "wersa_add_pooled": 256.1 * MIB,
 }
