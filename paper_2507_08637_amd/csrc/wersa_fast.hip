@@ -616,29 +616,15 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
   // (t along k) comes out of its tile through transposing LDS reads.
   u16x8 yr[LPT], xr[LPT];
   float inv[LPT], wv = 1.0f;
-  // PREP: the wave owns rows 16 wave .. 16 wave + 15 of the tile for the row dot products; lane
-  // (r, quarter) takes a quarter of row r, the four quarters meet by two lane exchanges.
-  constexpr int QP = CPR / 4;   // 16-byte pieces per quarter row
-  bf16x8 po[PREP ? QP : 1], pd[PREP ? QP : 1];
-  float pdiv = 1.0f, dsum = 0.f;
-  const int prow = 16 * wave + (lane & 15), pquart = lane >> 4;
+  // PREP: the rows of O come in like those of Y (the thread that holds piece cc of row r of dO
+  // holds the same piece of O); the CPR partial dot products of a row sit in neighbouring lanes.
+  u16x8 orw[PREP ? LPT : 1];
+  float dsum = 0.f;
   const bf16_t *os = PREP ? orows + vy.slice_base(slice) : nullptr;
   // RAGGED: rows past n (partial last tile) count as zeros with weight 0: the address is clamped
   // to the last row and the value replaced.
   auto fetch = [&](int t0) {
     const int last = RAGGED ? n - t0 - 1 : 63;
-    if (PREP) {
-      const bool bad = RAGGED && prow > last;
-      const int pr = t0 + (RAGGED ? min(prow, last) : prow);
-#pragma unroll
-      for (int j = 0; j < QP; ++j) {
-        const int64_t off = (int64_t)pr * vy.sn + (pquart * QP + j) * 8;
-        po[j] = *reinterpret_cast<const bf16x8 *>(os + off);
-        pd[j] = *reinterpret_cast<const bf16x8 *>(ys + off);
-        if (bad) pd[j] = splat_bf16x8(0.f);
-      }
-      pdiv = bad ? 1.0f : rd[pr];
-    }
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
       const int e = tid + 256 * i, r = e / CPR, cc = e % CPR;
@@ -647,6 +633,7 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
       xr[i] = FUSE ? *reinterpret_cast<const u16x8 *>(xrs + (int64_t)rc * vx.sn + cc * 8)
                    : *reinterpret_cast<const u16x8 *>(xs + (int64_t)rc * DH + cc * 8);
       yr[i] = *reinterpret_cast<const u16x8 *>(ys + (int64_t)rc * vy.sn + cc * 8);
+      if (PREP) orw[i] = *reinterpret_cast<const u16x8 *>(os + (int64_t)rc * vy.sn + cc * 8);
       inv[i] = rd ? rd[rc] : 1.0f;   // divided at the stash, when the load has landed
       if (bad) {
 #pragma unroll
@@ -673,16 +660,22 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
       }
     }
     if (PREP) {
-      float dot = 0.f;
+      static_assert(!PREP || CPR == 8 || CPR == 16, "row pieces sit in 8 or 16 neighbouring lanes");
 #pragma unroll
-      for (int j = 0; j < QP; ++j) dot = dot8_bf16(po[j], pd[j], dot);
-      dot += __shfl_xor(dot, 16, 64);
-      dot = xor32_sum(dot);
-      const float dDt = -dot / pdiv;
-      if (lane < 16) {
-        wl[buf][prow] = cvt_bf16(dDt);
-        dsum += dDt;
-        if (blockIdx.y == 0 && (!RAGGED || t_stash + prow < n)) dDout[(int64_t)slice * n + t_stash + prow] = dDt;
+      for (int i = 0; i < LPT; ++i) {
+        const int e = tid + 256 * i, r = e / CPR, cc = e % CPR;
+        // (rows past n hold zeros in yr and 1 in inv: their dD is 0)
+        float dot = dot8_bf16(__builtin_bit_cast(bf16x8, orw[i]), __builtin_bit_cast(bf16x8, yr[i]), 0.f);
+        dot += dpp_move<0xB1>(dot);    // lane ^ 1
+        dot += dpp_move<0x4E>(dot);    // lane ^ 2
+        dot += dpp_move<0x141>(dot);   // mirror inside each group of 8 lanes: the other quad's sum
+        if (CPR == 16) dot += dpp_move<0x140>(dot);   // mirror inside the row of 16 lanes: the other half's sum
+        const float dDt = -dot / inv[i];
+        if (cc == 0) {
+          wl[buf][r] = cvt_bf16(dDt);
+          dsum += dDt;
+          if (blockIdx.y == 0 && (!RAGGED || t_stash + r < n)) dDout[(int64_t)slice * n + t_stash + r] = dDt;
+        }
       }
     } else if (tid < 64) {
       wl[buf][tid] = cvt_bf16(wv);
