@@ -623,7 +623,34 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
   const bf16_t *os = PREP ? orows + vy.slice_base(slice) : nullptr;
   // RAGGED: rows past n (partial last tile) count as zeros with weight 0: the address is clamped
   // to the last row and the value replaced.
+  // Whole tiles (the plain instances): one running pointer per tensor, advanced by a tile per
+  // call (the tiles are requested in order); piece i sits i * (256 / CPR) rows further on.
+  constexpr int RPP = 256 / CPR;   // rows between a thread's pieces
+  const int r0 = tid / CPR, c0 = (tid % CPR) * 8;
+  const int64_t xsn = FUSE ? vx.sn : DH;
+  const u16x8 *px = reinterpret_cast<const u16x8 *>((FUSE ? xrs : reinterpret_cast<const bf16_t *>(xs)) +
+                                                    (int64_t)(t_begin + r0) * xsn + c0);
+  const u16x8 *py = reinterpret_cast<const u16x8 *>(ys + (int64_t)(t_begin + r0) * vy.sn + c0);
+  const u16x8 *po = PREP ? reinterpret_cast<const u16x8 *>(os + (int64_t)(t_begin + r0) * vy.sn + c0) : nullptr;
+  const float *prd = rd ? rd + t_begin + r0 : nullptr;
+  const float *pws = ws ? ws + t_begin + tid : nullptr;
   auto fetch = [&](int t0) {
+    if (!RAGGED) {
+#pragma unroll
+      for (int i = 0; i < LPT; ++i) {
+        xr[i] = *reinterpret_cast<const u16x8 *>(reinterpret_cast<const bf16_t *>(px) + i * RPP * xsn);
+        yr[i] = *reinterpret_cast<const u16x8 *>(reinterpret_cast<const bf16_t *>(py) + i * RPP * vy.sn);
+        if (PREP) orw[i] = *reinterpret_cast<const u16x8 *>(reinterpret_cast<const bf16_t *>(po) + i * RPP * vy.sn);
+        inv[i] = prd ? prd[i * RPP] : 1.0f;   // divided at the stash, when the load has landed
+      }
+      if (!PREP && tid < 64) wv = pws ? *pws : 1.0f;
+      px = reinterpret_cast<const u16x8 *>(reinterpret_cast<const bf16_t *>(px) + 64 * xsn);
+      py = reinterpret_cast<const u16x8 *>(reinterpret_cast<const bf16_t *>(py) + 64 * vy.sn);
+      if (PREP) po = reinterpret_cast<const u16x8 *>(reinterpret_cast<const bf16_t *>(po) + 64 * vy.sn);
+      if (prd) prd += 64;
+      if (pws) pws += 64;
+      return;
+    }
     const int last = RAGGED ? n - t0 - 1 : 63;
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
