@@ -380,6 +380,7 @@ def test_layernorm_output_stage_mfma_shapes(shape):
                                    dict(B=1, H=2, n=640, d=64, L=7, m=128),       # 10 tiles, pairs
                                    dict(B=1, H=2, n=1000, d=64, L=9, m=256),      # partial last tile: 15 tiles + 40 rows
                                    dict(B=1, H=1, n=100, d=64, L=7, m=128),       # two tiles, the second partial
+                                   dict(B=1, H=1, n=2048, d=64, L=8, m=512),      # two passes of 256 features (dV inside the K-side kernel)
                                    dict(B=1, H=2, n=1024, d=128, L=9, m=128),     # head dimension 128: stage A kernel takes the addends
                                    dict(B=2, H=1, n=4160, d=128, L=12, m=256),
                                    dict(B=1, H=1, n=1000, d=128, L=8, m=128)])    # ... with a partial last tile
