@@ -1937,7 +1937,7 @@ constexpr int kWavesGrad = 4;
 constexpr int waves_apply(int d) { return d == 64 ? 8 : 4; }   // head dimension 128: 512 registers per lane
 
 struct FastPlan {
-  int DH, FW, MB, mc;
+  int DH, FW, MB, mc, mcA;   // features staged in LDS per pass by the rows kernels (mcA: the dV kernel)
   int chunksQ, rowsQ;   // pooled-query partial sums
   int chunksC, rowsC;   // split of n in phiT_contract
   int rowGroupsA, rowsWgsA;   // apply-type rows kernel (4 waves): row groups / workgroups per slice
@@ -1949,6 +1949,9 @@ FastPlan fast_plan(const wersa_desc &c) {
   p.DH = c.d;
   if (c.m % 256 == 0 && c.d == 64) { p.FW = 64; p.MB = 256; } else { p.FW = 32; p.MB = 128; }
   p.mc = (c.d == 64 && c.m % 256 == 0) ? 256 : 128;
+  // the dV kernel stages no (M | b) array: 256 features fit for head dimension 128 too (the forward
+  // kernel, which could do the same, measured 3 % slower with 256 than with 128)
+  p.mcA = c.m % 256 == 0 ? 256 : 128;
   const int slices = c.B * c.H, blocks = (c.n + 63) / 64;
   int cq = (c.n + 1023) / 1024;
   p.chunksQ = cq < 1 ? 1 : (cq > 512 ? 512 : cq);
@@ -2082,7 +2085,8 @@ hipError_t launch_rows(const wersa_desc &c, const FastPlan &p, const _Float16 *x
   const _Float16 *omT = w.omT + side;
   omega += side;
   const View tv{c.stride_b, c.stride_h, c.stride_n, c.H};
-  const size_t smem = rows_smem_bytes<DH, MODE, NW>(p.mc);
+  const int mcs = MODE == 3 ? p.mcA : p.mc;
+  const size_t smem = rows_smem_bytes<DH, MODE, NW>(mcs);
   const char *name = MODE == 0 ? "wersa_rows_fwd"
                                : (MODE == 1 ? "wersa_rows_bwd_q" : (MODE == 2 ? "wersa_rows_bwd_k" : "wersa_rows_bwd_v"));
   const int wgs = IS_GRAD ? p.rowsWgsG : p.rowsWgsA, groups = IS_GRAD ? p.rowGroupsG : p.rowGroupsA;
@@ -2121,25 +2125,25 @@ hipError_t launch_rows(const wersa_desc &c, const FastPlan &p, const _Float16 *x
   }
   if (DH == 64 && c.L > kTileL) {   // deeper than one block, head dimension 64
     if (ragged) {
-      if (ln) return p.mc == 256 ? go(&rows_kernel<DH, MODE, NW, 256, MODE == 0, DH == 64, DH == 64>)
+      if (ln) return mcs == 256 ? go(&rows_kernel<DH, MODE, NW, 256, MODE == 0, DH == 64, DH == 64>)
                                  : go(&rows_kernel<DH, MODE, NW, 128, MODE == 0, DH == 64, DH == 64>);
-      return p.mc == 256 ? go(&rows_kernel<DH, MODE, NW, 256, false, DH == 64, DH == 64>)
+      return mcs == 256 ? go(&rows_kernel<DH, MODE, NW, 256, false, DH == 64, DH == 64>)
                          : go(&rows_kernel<DH, MODE, NW, 128, false, DH == 64, DH == 64>);
     }
-    if (ln) return p.mc == 256 ? go(&rows_kernel<DH, MODE, NW, 256, MODE == 0, false, DH == 64>)
+    if (ln) return mcs == 256 ? go(&rows_kernel<DH, MODE, NW, 256, MODE == 0, false, DH == 64>)
                                : go(&rows_kernel<DH, MODE, NW, 128, MODE == 0, false, DH == 64>);
-    return p.mc == 256 ? go(&rows_kernel<DH, MODE, NW, 256, false, false, DH == 64>)
+    return mcs == 256 ? go(&rows_kernel<DH, MODE, NW, 256, false, false, DH == 64>)
                        : go(&rows_kernel<DH, MODE, NW, 128, false, false, DH == 64>);
   }
   if (ragged) {   // the shapes with a partial last block take the guarded instances
-    if (ln) return p.mc == 256 ? go(&rows_kernel<DH, MODE, NW, 256, MODE == 0, true, false>)
+    if (ln) return mcs == 256 ? go(&rows_kernel<DH, MODE, NW, 256, MODE == 0, true, false>)
                                : go(&rows_kernel<DH, MODE, NW, 128, MODE == 0, true, false>);
-    return p.mc == 256 ? go(&rows_kernel<DH, MODE, NW, 256, false, true, false>)
+    return mcs == 256 ? go(&rows_kernel<DH, MODE, NW, 256, false, true, false>)
                        : go(&rows_kernel<DH, MODE, NW, 128, false, true, false>);
   }
-  if (ln) return p.mc == 256 ? go(&rows_kernel<DH, MODE, NW, 256, MODE == 0, false, false>)
+  if (ln) return mcs == 256 ? go(&rows_kernel<DH, MODE, NW, 256, MODE == 0, false, false>)
                              : go(&rows_kernel<DH, MODE, NW, 128, MODE == 0, false, false>);
-  return p.mc == 256 ? go(&rows_kernel<DH, MODE, NW, 256, false, false, false>)
+  return mcs == 256 ? go(&rows_kernel<DH, MODE, NW, 256, false, false, false>)
                      : go(&rows_kernel<DH, MODE, NW, 128, false, false, false>);
 }
 
