@@ -2086,6 +2086,8 @@ hipError_t launch_rows(const wersa_desc &c, const FastPlan &p, const _Float16 *x
   omega += side;
   const View tv{c.stride_b, c.stride_h, c.stride_n, c.H};
   const int mcs = MODE == 3 ? p.mcA : p.mc;
+  // (the gradient kernels of head dimension 128 exist with 128 staged features only)
+  constexpr int MCH = (DH == 128 && IS_GRAD) ? 128 : 256;
   const size_t smem = rows_smem_bytes<DH, MODE, NW>(mcs);
   const char *name = MODE == 0 ? "wersa_rows_fwd"
                                : (MODE == 1 ? "wersa_rows_bwd_q" : (MODE == 2 ? "wersa_rows_bwd_k" : "wersa_rows_bwd_v"));
@@ -2125,25 +2127,25 @@ hipError_t launch_rows(const wersa_desc &c, const FastPlan &p, const _Float16 *x
   }
   if (DH == 64 && c.L > kTileL) {   // deeper than one block, head dimension 64
     if (ragged) {
-      if (ln) return mcs == 256 ? go(&rows_kernel<DH, MODE, NW, 256, MODE == 0, DH == 64, DH == 64>)
+      if (ln) return mcs == 256 ? go(&rows_kernel<DH, MODE, NW, MCH, MODE == 0, DH == 64, DH == 64>)
                                  : go(&rows_kernel<DH, MODE, NW, 128, MODE == 0, DH == 64, DH == 64>);
-      return mcs == 256 ? go(&rows_kernel<DH, MODE, NW, 256, false, DH == 64, DH == 64>)
+      return mcs == 256 ? go(&rows_kernel<DH, MODE, NW, MCH, false, DH == 64, DH == 64>)
                          : go(&rows_kernel<DH, MODE, NW, 128, false, DH == 64, DH == 64>);
     }
-    if (ln) return mcs == 256 ? go(&rows_kernel<DH, MODE, NW, 256, MODE == 0, false, DH == 64>)
+    if (ln) return mcs == 256 ? go(&rows_kernel<DH, MODE, NW, MCH, MODE == 0, false, DH == 64>)
                                : go(&rows_kernel<DH, MODE, NW, 128, MODE == 0, false, DH == 64>);
-    return mcs == 256 ? go(&rows_kernel<DH, MODE, NW, 256, false, false, DH == 64>)
+    return mcs == 256 ? go(&rows_kernel<DH, MODE, NW, MCH, false, false, DH == 64>)
                        : go(&rows_kernel<DH, MODE, NW, 128, false, false, DH == 64>);
   }
   if (ragged) {   // the shapes with a partial last block take the guarded instances
-    if (ln) return mcs == 256 ? go(&rows_kernel<DH, MODE, NW, 256, MODE == 0, true, false>)
+    if (ln) return mcs == 256 ? go(&rows_kernel<DH, MODE, NW, MCH, MODE == 0, true, false>)
                                : go(&rows_kernel<DH, MODE, NW, 128, MODE == 0, true, false>);
-    return mcs == 256 ? go(&rows_kernel<DH, MODE, NW, 256, false, true, false>)
+    return mcs == 256 ? go(&rows_kernel<DH, MODE, NW, MCH, false, true, false>)
                        : go(&rows_kernel<DH, MODE, NW, 128, false, true, false>);
   }
-  if (ln) return mcs == 256 ? go(&rows_kernel<DH, MODE, NW, 256, MODE == 0, false, false>)
+  if (ln) return mcs == 256 ? go(&rows_kernel<DH, MODE, NW, MCH, MODE == 0, false, false>)
                              : go(&rows_kernel<DH, MODE, NW, 128, MODE == 0, false, false>);
-  return mcs == 256 ? go(&rows_kernel<DH, MODE, NW, 256, false, false, false>)
+  return mcs == 256 ? go(&rows_kernel<DH, MODE, NW, MCH, false, false, false>)
                      : go(&rows_kernel<DH, MODE, NW, 128, false, false, false>);
 }
 
