@@ -47,7 +47,7 @@ __device__ __forceinline__ f32x16 mfma_bf16(bf16x8 a, bf16x8 b, f32x16 c) {
 // statement is hazard-safe on its own: dependent MFMAs are never adjacent (the two chains
 // alternate), and the statement ends with the wait states an 8-pass MFMA needs before anything
 // (VALU, a copy, a spill) may read its result.
-//   chain_first: G = sum_{k<5} ma_k yb_k, R = sum_{k<4} oa_k xb_k;  chain_more: four more steps of each.
+//   chain_first: G = sum_{k<5} ma_k yb_k, R = sum_{k<4} oa_k xb_k.
 __device__ __forceinline__ void chain_first(f32x16 &R, f32x16 &G, const f16x8 *oa, const f16x8 *xb,
                                             const bf16x8 *ma, const bf16x8 *yb) {
   asm volatile(
@@ -196,22 +196,6 @@ __device__ __forceinline__ void chain0_mask1(f32x16 &R0, f32x16 &G0, f32x16 &G1,
       : "v"(oa[0]), "v"(oa[1]), "v"(oa[2]), "v"(oa[3]), "v"(xb[0]), "v"(xb[1]), "v"(xb[2]), "v"(xb[3]),
         "v"(ma[0]), "v"(ma[1]), "v"(ma[2]), "v"(ma[3]), "v"(ma[4]), "v"(yb[0]), "v"(yb[1]), "v"(yb[2]),
         "v"(yb[3]), "v"(yb[4]), "{v[224:239]}"(R1), "s"(big));
-}
-__device__ __forceinline__ void chain_more(f32x16 &R, f32x16 &G, const f16x8 *oa, const f16x8 *xb,
-                                           const bf16x8 *ma, const bf16x8 *yb) {
-  asm volatile(
-      "v_mfma_f32_32x32x16_bf16 %1, %10, %14, %1\n\t"
-      "v_mfma_f32_32x32x16_f16 %0, %2, %6, %0\n\t"
-      "v_mfma_f32_32x32x16_bf16 %1, %11, %15, %1\n\t"
-      "v_mfma_f32_32x32x16_f16 %0, %3, %7, %0\n\t"
-      "v_mfma_f32_32x32x16_bf16 %1, %12, %16, %1\n\t"
-      "v_mfma_f32_32x32x16_f16 %0, %4, %8, %0\n\t"
-      "v_mfma_f32_32x32x16_bf16 %1, %13, %17, %1\n\t"
-      "v_mfma_f32_32x32x16_f16 %0, %5, %9, %0\n\t"
-      "s_nop 11"
-      : "+v"(R), "+v"(G)
-      : "v"(oa[0]), "v"(oa[1]), "v"(oa[2]), "v"(oa[3]), "v"(xb[0]), "v"(xb[1]), "v"(xb[2]), "v"(xb[3]),
-        "v"(ma[0]), "v"(ma[1]), "v"(ma[2]), "v"(ma[3]), "v"(yb[0]), "v"(yb[1]), "v"(yb[2]), "v"(yb[3]));
 }
 __device__ __forceinline__ f32x16 zero16() {
   f32x16 z;
@@ -1158,7 +1142,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
   };
   {
     const int t_first = (blockIdx.x * NWR + wave) * 64;
-    if (blockIdx.x < row_groups && t_first < n) {
+    if ((int)blockIdx.x < row_groups && t_first < n) {
       load_rows(t_first);
       put_rows();
     }
@@ -1448,7 +1432,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
       // would leave two paths with different numbers of outstanding memory operations, and the
       // waits the compiler then places further down would cover the loads just issued.
       const int t_next = ((rg + gridDim.x) * NWR + wave) * 64;
-      load_rows((rg + gridDim.x < row_groups && t_next < n) ? t_next : t0);
+      load_rows((rg + (int)gridDim.x < row_groups && t_next < n) ? t_next : t0);
     }
     bf16_t *tl = panels;   // FUSE, gradient modes: moves to the panel of the column tile in hand
     // Gradient modes: output tiles leave through the wave's LDS tile held transposed ([column][row]): a lane
@@ -2258,8 +2242,7 @@ wersa_status fast_backward_t(const wersa_desc &c, const bf16_t *q, const bf16_t 
   const SavedLayout sv = saved_layout(c);
   const int slices = c.B * c.H;
   const View tv{c.stride_b, c.stride_h, c.stride_n, c.H};
-  const float *z = saved + sv.z, *qbar = saved + sv.qbar, *s = saved + sv.s, *F = saved + sv.F,
-              *D = saved + sv.D;
+  const float *qbar = saved + sv.qbar, *s = saved + sv.s, *D = saved + sv.D;
   const _Float16 *QF = sv.QF >= 0 ? reinterpret_cast<const _Float16 *>(saved + sv.QF) : nullptr;
   const _Float16 *KF = sv.KF >= 0 ? reinterpret_cast<const _Float16 *>(saved + sv.KF) : nullptr;
 

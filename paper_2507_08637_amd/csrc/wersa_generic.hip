@@ -120,8 +120,8 @@ __global__ void haar_filter_kernel(const TIn *x, View vin, TOut *y, View vout, c
   const int slice = blockIdx.z, L = lv.Lt;
   const int t0 = blockIdx.x * kTileRows, j = blockIdx.y * kTileCols + (threadIdx.x & 63);
   const int c = threadIdx.x & 63, g = threadIdx.x >> 6;
-  if (threadIdx.x <= L)
-    F[threadIdx.x] = (threadIdx.x < L || lv.top) ? filt[slice * lv.fstride + lv.foff + threadIdx.x] : 1.0f;
+  if ((int)threadIdx.x <= L)
+    F[threadIdx.x] = ((int)threadIdx.x < L || lv.top) ? filt[slice * lv.fstride + lv.foff + threadIdx.x] : 1.0f;
   const TIn *xs = x + vin.slice_base(slice);
   for (int r = g; r < kTileRows; r += 4) {
     const int t = t0 + r;
