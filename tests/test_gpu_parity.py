@@ -419,6 +419,24 @@ def test_deep_transform_outside_the_mfma_shapes_takes_the_generic_path():
     _check_all(res, ref, TOL["bf16"], where="deep transform, default path")
 
 
+@pytest.mark.parametrize("shape", [dict(B=2, H=2, n=4096, d=64, L=6, m=256, dtype="bf16"),     # dV inside the K-side kernel
+                                   dict(B=1, H=2, n=1000, d=64, L=9, m=256, dtype="bf16"),     # partial last block, deep
+                                   dict(B=1, H=2, n=2048, d=128, L=5, m=256, dtype="bf16"),
+                                   dict(B=1, H=2, n=1500, d=48, L=4, m=80, dtype="f32")])      # generic path
+def test_results_are_bitwise_reproducible(shape):
+    """Every reduction runs in a fixed order (no atomics): two runs on the same inputs give the
+    same bits in every output, forward and backward."""
+    import torch
+    cfg = dict(shape, flavour="plain", seed_base=4100, q_mean=0.2)
+    p = workloads.make_inputs(**cfg)
+    a = hp.gpu_forward_backward(p, cfg)
+    b = hp.gpu_forward_backward(p, cfg)
+    for name in ("O", "dQ", "dK", "dV", "dWg", "dbg", "domega", "dsigma"):
+        assert torch.equal(a[name], b[name]), name
+    for name in ("S", "z", "D", "F"):
+        assert torch.equal(a["saved"][name], b["saved"][name]), name
+
+
 # ------------------------------------------------------------------ benchmark configurations
 def test_config1_tiny_fp32():
     cfg, p = workloads.make_config(1, backward=True)
