@@ -80,6 +80,18 @@ def test_block_forward_backward(shape):
     assert all(v < 5e-2 for v in gerr.values()), gerr
 
 
+def test_block_results_are_bitwise_reproducible():
+    """The split-k partials of the weight gradients are summed in a fixed order and the core has
+    no atomics: two runs of the block on the same inputs give the same bits."""
+    import torch
+    cfg = dict(B=2, H=4, n=384, d=128, L=6, m=256)
+    p = workloads.make_block_inputs(**cfg, seed_base=9300, x_mean=0.1)
+    a = _gpu_block(p, cfg)
+    b = _gpu_block(p, cfg)
+    for name in ("Y", "A", "dX", "dWQ", "dWK", "dWV", "dWO", "dWg", "dbg", "domega", "dsigma"):
+        assert torch.equal(a[name], b[name]), name
+
+
 def test_block_gradient_of_query_weights_with_shifted_input():
     """With a non-zero token mean of X the weight gradient dW^Q = X^T dQ' picks up the rank-one
     term (sum_t X_t) (dqbar / n)^T: the pooled-query gradient, a cancelling sum whose error is
