@@ -264,33 +264,50 @@ __device__ __forceinline__ float half_wave_sum(float v) {
 // into Omega^T in fp16 ([m][d]), the projection's MFMA operand.  (The filter coefficients of
 // the block-mean form come from the gate kernel.)
 // ------------------------------------------------------------------------------------
-__global__ void setup_kernel(const float *sigma, float bw_floor, const bf16_t *omega, int d, int m,
-                             int matrices, float *scalars, _Float16 *omT) {
-  if (blockIdx.x == 0 && threadIdx.x == 0) {
-    const float s = *sigma;
-    const float se = fmaxf(s, bw_floor);
-    scalars[0] = 1.0f / (se * sqrtf((float)m));
-    scalars[1] = se;
-    scalars[2] = s > bw_floor ? 1.0f : 0.0f;
-    scalars[3] = 1.0f;
+struct SetupArgs {
+  const float *sigma;
+  float bw_floor;
+  const bf16_t *omega;
+  int d, m, matrices;
+  float *scalars;
+  _Float16 *omT;
+  int blocks;   // workgroups of 256 threads that cover matrices * d * m elements (0: nothing to do)
+};
+inline int setup_blocks(int d, int m, int matrices) { return (matrices * d * m + 255) / 256; }
+__device__ __forceinline__ void setup_body(const SetupArgs &a, int block) {
+  if (block == 0 && threadIdx.x == 0) {
+    const float s = *a.sigma;
+    const float se = fmaxf(s, a.bw_floor);
+    a.scalars[0] = 1.0f / (se * sqrtf((float)a.m));
+    a.scalars[1] = se;
+    a.scalars[2] = s > a.bw_floor ? 1.0f : 0.0f;
+    a.scalars[3] = 1.0f;
   }
-  const int e = blockIdx.x * blockDim.x + threadIdx.x;
-  if (e < matrices * d * m) {   // one or two d x m matrices, each transposed on its own
-    const int mat = e / (d * m), w = e % (d * m);
-    const int r = w / d, j = w % d;
-    omT[e] = (_Float16)bf16_to_f32(omega[(int64_t)mat * d * m + (int64_t)j * m + r]);
+  const int e = block * 256 + threadIdx.x;
+  if (e < a.matrices * a.d * a.m) {   // one or two d x m matrices, each transposed on its own
+    const int mat = e / (a.d * a.m), w = e % (a.d * a.m);
+    const int r = w / a.d, j = w % a.d;
+    a.omT[e] = (_Float16)bf16_to_f32(a.omega[(int64_t)mat * a.d * a.m + (int64_t)j * a.m + r]);
   }
 }
+__global__ __launch_bounds__(256) void setup_kernel(SetupArgs a) { setup_body(a, blockIdx.x); }
 
 // ------------------------------------------------------------------------------------
 // Column sums of Q for the pooled query: 16-byte loads, one partial per (slice, chunk).
+// Grid (chunks + su.blocks, slices): the workgroups past `chunks` of slice 0 carry the per-call
+// constants (one launch fewer at the head of the forward pass); those of the other slices exit.
 // ------------------------------------------------------------------------------------
 template <int DH>
 __global__ __launch_bounds__(256) void qbar_partial_kernel(const bf16_t *q, View v, int n,
-                                                          int rows_per_chunk, float *part) {
+                                                          int rows_per_chunk, float *part, int chunks,
+                                                          SetupArgs su) {
   constexpr int CPR = DH / 8;        // 16-byte chunks per row
   constexpr int RPI = 256 / CPR;     // rows per iteration
-  const int slice = blockIdx.y, chunk = blockIdx.x, chunks = gridDim.x;
+  if ((int)blockIdx.x >= chunks) {
+    if (blockIdx.y == 0) setup_body(su, blockIdx.x - chunks);
+    return;
+  }
+  const int slice = blockIdx.y, chunk = blockIdx.x;
   const int t0 = chunk * rows_per_chunk, t1 = min(n, t0 + rows_per_chunk);
   const int cc = threadIdx.x % CPR, rr = threadIdx.x / CPR;
   const bf16_t *qs = q + v.slice_base(slice) + cc * 8;
@@ -2189,11 +2206,11 @@ wersa_status fast_forward_t(const wersa_desc &c, const bf16_t *q, const bf16_t *
   _Float16 *KF = sv.KF >= 0 ? reinterpret_cast<_Float16 *>(saved + sv.KF) : nullptr;
 
   const int nmat = (c.flags & WERSA_FLAG_SEPARATE_OMEGA) ? 2 : 1;
-  WERSA_STAGE("wersa_setup", st,
-              setup_kernel<<<(nmat * c.d * c.m + 255) / 256, 256, 0, st>>>(sigma, c.bw_floor, omega, c.d, c.m, nmat,
-                                                                           w.scalars, w.omT));
+  SetupArgs su{sigma, c.bw_floor, omega, c.d, c.m, nmat, w.scalars, w.omT, setup_blocks(c.d, c.m, nmat)};
+  const SetupArgs none{};
   const bool deep = c.L > kTileL;
   if (pooled && c.n % 128 == 0 && !deep) {
+    WERSA_STAGE("wersa_setup", st, setup_kernel<<<su.blocks, 256, 0, st>>>(su));
     // the caller's column sums per 128 token rows: batch b owns row blocks [b n/128, (b+1) n/128)
     const int chunks = c.n / 128;
     WERSA_STAGE("gate_fwd_kernel", st,
@@ -2204,7 +2221,8 @@ wersa_status fast_forward_t(const wersa_desc &c, const bf16_t *q, const bf16_t *
     // deep: one partial per 64-row tile, kept (with those of K) as the tile sums of the levels above 6
     float *qpart = deep ? w.tileQ : w.qpart;
     WERSA_STAGE("wersa_qbar", st,
-                qbar_partial_kernel<DH><<<dim3(p.chunksQ, slices), 256, 0, st>>>(q, tv, c.n, p.rowsQ, qpart));
+                qbar_partial_kernel<DH><<<dim3(p.chunksQ + su.blocks, slices), 256, 0, st>>>(q, tv, c.n, p.rowsQ, qpart,
+                                                                                             p.chunksQ, su));
     WERSA_STAGE("gate_fwd_kernel", st,
                 gate_fwd_kernel<<<slices, 256, 0, st>>>(qpart, p.chunksQ, c.n, c.d, c.L, c.H, gate_w, gate_b, scale_w,
                                                        qbar, s, F, w.coef, (c.flags & WERSA_FLAG_POOLED_GATE) ? 1 : 0,
@@ -2212,7 +2230,8 @@ wersa_status fast_forward_t(const wersa_desc &c, const bf16_t *q, const bf16_t *
   }
   if (deep) {
     WERSA_STAGE("wersa_qbar", st,
-                qbar_partial_kernel<DH><<<dim3(p.chunksQ, slices), 256, 0, st>>>(k, tv, c.n, p.rowsQ, w.tileK));
+                qbar_partial_kernel<DH><<<dim3(p.chunksQ, slices), 256, 0, st>>>(k, tv, c.n, p.rowsQ, w.tileK,
+                                                                                 p.chunksQ, none));
     WERSA_STAGE("wersa_coarse_addend", st,
                 coarse_addend_kernel<<<dim3(slices, 2, DH / kCoarseCols), 1024, 0, st>>>(w.tileQ, w.tileK, w.coef, p.chunksQ, DH, c.L, w.pyr,
                                                                       w.addQ, w.addK));
