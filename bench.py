@@ -24,7 +24,7 @@ PEAK = {"hbm": (8000.0, "GB/s"), "mfma_bf16": (2500.0, "TFLOP/s"), "fp32": (157.
 # runs summarised in profiles/mfma_path_config4_hbm_traffic.md (FETCH_SIZE scaled by the factor 2.0 that
 # a plain 1 GiB copy shows for this counter, WRITE_SIZE by 1.0).
 MIB = 1024.0 * 1024.0
-SURVEY_STEPS = 5   # untimed steps with every launch bracketed, to rank the kernels
+RANKING_STEPS = 5   # untimed steps with every launch bracketed, to rank the kernels
 MEASURED_TRAFFIC_CONFIG4 = {
     "wersa_rows_fwd": (137.8 + 135.0) * MIB, "wersa_rows_bwd_q": (272.0 + 128.9) * MIB,
     "wersa_rows_bwd_k": (267.8 + 258.4) * MIB,   # with dV
@@ -232,7 +232,7 @@ def main():
     survey, dominant = {}, None
     if not args.no_events:
         binding.wersa_profile_enable(True)
-        for _ in range(SURVEY_STEPS):
+        for _ in range(RANKING_STEPS):
             step()
         torch.cuda.synchronize()
         survey = binding.wersa_profile_collect()
@@ -249,8 +249,8 @@ def main():
             graph.replay()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-        prof = {dominant: (survey[dominant][0] * args.steps / SURVEY_STEPS,
-                           survey[dominant][1] * args.steps // SURVEY_STEPS)} if dominant else {}
+        prof = {dominant: (survey[dominant][0] * args.steps / RANKING_STEPS,
+                           survey[dominant][1] * args.steps // RANKING_STEPS)} if dominant else {}
     else:
         binding.wersa_profile_enable(dominant is not None, only=dominant)
         torch.cuda.synchronize()
@@ -289,7 +289,7 @@ def main():
                     "frac": achieved / peak, "traffic": traffic, "kernel": name,
                     "avg_launch_ms": avg_ms, "launches_per_step": launches / args.steps}
         # every kernel, from the untimed survey steps (all launches bracketed)
-        rec["kernels_ms_per_step"] = {k: round(v[0] / SURVEY_STEPS, 4) for k, v in
+        rec["kernels_ms_per_step"] = {k: round(v[0] / RANKING_STEPS, 4) for k, v in
                                       sorted(survey.items(), key=lambda kv: -kv[1][0])}
     rec["roofline"] = roof
     if not args.no_cpu_baseline:
