@@ -437,6 +437,48 @@ def test_results_are_bitwise_reproducible(shape):
         assert torch.equal(a["saved"][name], b["saved"][name]), name
 
 
+@pytest.mark.parametrize("kind", ["mfma", "generic"])
+def test_maximum_sequence_length_keeps_convexity_and_periodicity(kind):
+    """n = 2^22 (the largest the library takes) on either path, no oracle pass at this size.
+    Forward: with V = 1 every output row is (D - eps) / D, a convex combination of ones, so all
+    4 M rows must come out as 1, and S must repeat z in every column.  Backward: Q, K and dO repeat
+    a block of 4096 random rows; every per-row result (O, dQ, dK, dV) depends on its 64-row block
+    and on slice-wide sums only, so it must repeat with the same period, bit for bit.  Row-index
+    arithmetic that wraps or skips anywhere in the 4 M rows breaks one of the two."""
+    import torch
+    from paper_2507_08637_amd import binding
+    n, L, P = 1 << 22, 6, 4096
+    d, m, dt = (64, 256, torch.bfloat16) if kind == "mfma" else (16, 32, torch.float32)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(4200)
+    rnd = lambda *sh: torch.randn(*sh, device="cuda", generator=g, dtype=torch.float32)
+    tile = lambda base: base.to(dt).repeat(n // P, 1).view(1, 1, n, d).contiguous()
+    Q, K, dO = tile(rnd(P, d)), tile(rnd(P, d)), tile(rnd(P, d))
+    V = torch.ones(1, 1, n, d, device="cuda", dtype=dt)
+    Om = rnd(d, m).to(dt)
+    sigma = torch.ones(1, device="cuda")
+    Wg, bg, om = 0.1 * rnd(1, L + 1, d), 0.1 * rnd(1, L + 1), torch.ones(L + 1, device="cuda")
+    desc = binding.make_desc(Q, L, m)
+    assert binding.wersa_path_name(desc) == kind
+    out, saved = binding.wersa_forward(Q, K, V, Om, sigma, Wg, bg, om, L)
+    sv = binding.saved_views(desc, saved)
+    o = out.float()
+    assert torch.isfinite(o).all()
+    assert (o - 1.0).abs().max().item() < (1e-2 if kind == "mfma" else 1e-4)   # rounding of (D - eps) / D
+    assert (sv["D"] > 0).all()
+    S, z = sv["S"].reshape(m, d), sv["z"].reshape(m)
+    assert torch.allclose(S, z[:, None].expand(m, d), rtol=1e-4, atol=0.0)
+    gr = binding.wersa_backward(Q, K, V, Om, sigma, Wg, bg, om, out, dO, saved, L)
+    torch.cuda.synchronize()
+    for name in ("dq", "dk", "dv", "dgate_w", "dgate_b", "dscale_w", "dsigma"):
+        assert torch.isfinite(gr[name].float()).all(), name
+    periodic = lambda x: bool((x.view(n // P, P, d) == x.view(n // P, P, d)[0]).all())
+    assert periodic(sv["D"].reshape(n, 1).expand(n, d)), "D"
+    for name, x in (("O", out), ("dQ", gr["dq"]), ("dK", gr["dk"]), ("dV", gr["dv"])):
+        assert periodic(x), name
+    assert gr["dv"].float().abs().max().item() > 0
+
+
 # ------------------------------------------------------------------ benchmark configurations
 def test_config1_tiny_fp32():
     cfg, p = workloads.make_config(1, backward=True)
