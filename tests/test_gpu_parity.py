@@ -111,6 +111,7 @@ MFMA_SHAPES = [
     dict(B=1, H=2, n=1536, d=128, L=4, m=256),
     dict(B=1, H=1, n=256, d=64, L=4, m=4096),     # maximum feature count: 16 operand chunks per row group
     dict(B=6, H=8, n=128, d=64, L=5, m=128),      # 48 slices of two blocks: more workgroups than row groups
+    dict(B=33, H=31, n=64, d=64, L=4, m=128),     # 1023 slices, the most the library takes
     # sequence lengths that are not multiples of the 64-row block: the last block is partial
     dict(B=2, H=2, n=1000, d=64, L=6, m=256),     # 15 full blocks + 40 rows
     dict(B=1, H=2, n=100, d=64, L=5, m=128),      # one full block + 36 rows
