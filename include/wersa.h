@@ -123,10 +123,24 @@ wersa_status wersa_backward(const wersa_desc *desc, const void *q, const void *k
  * Stage entry point: the gated Haar filter alone, X_F = W^-1(F (.) W X) (Section 3.1 steps
  * 3, 5, 6; Appendix A equations) for one tensor x laid out like q, with per-slice filter
  * coefficients filt [B*H][L+1] (float32, device). Output xf has the same layout and dtype.
- * It takes no workspace and covers L <= 6; a deeper transform returns WERSA_ERR_UNSUPPORTED here.
+ * It takes no workspace and covers L <= 6; a deeper transform returns WERSA_ERR_UNSUPPORTED here
+ * (wersa_haar_filter_ws takes it).
  */
 wersa_status wersa_haar_filter(const wersa_desc *desc, const void *x, const float *filt,
                                void *xf, void *hip_stream);
+
+/*
+ * The same stage for every L the library takes (Appendix A: L = O(log n)). Levels above 6 run
+ * on the approximation coefficients of the 64-row tiles, which live in `workspace` (device
+ * memory owned by the caller, 256-byte aligned, at least wersa_haar_filter_workspace_bytes(desc)
+ * bytes; 0 bytes and a NULL pointer are fine for L <= 6). Contents of the workspace are scratch.
+ * Errors as for wersa_forward; a workspace that is too small or misaligned returns
+ * WERSA_ERR_WORKSPACE before anything is enqueued.
+ */
+size_t wersa_haar_filter_workspace_bytes(const wersa_desc *desc);
+wersa_status wersa_haar_filter_ws(const wersa_desc *desc, const void *x, const float *filt,
+                                  void *xf, void *workspace, size_t workspace_bytes,
+                                  void *hip_stream);
 
 /*
  * Attention block around the core (Section 3.1 steps 1-2: Q' = X W^Q, K' = X W^K, V' = X W^V,

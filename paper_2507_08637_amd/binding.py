@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libwersa.so")
 WERSA_F32, WERSA_BF16 = 0, 1
 WERSA_FLAG_GENERIC_PATH = 1
 EXPORTS = ["wersa_workspace_bytes", "wersa_saved_bytes", "wersa_forward", "wersa_backward",
-           "wersa_haar_filter", "wersa_saved_offset", "wersa_selected_path", "wersa_status_string", "wersa_version",
+           "wersa_haar_filter", "wersa_haar_filter_ws", "wersa_haar_filter_workspace_bytes", "wersa_saved_offset", "wersa_selected_path", "wersa_status_string", "wersa_version",
            "wersa_profile_enable", "wersa_profile_only", "wersa_profile_reset", "wersa_profile_collect", "wersa_profile_get",
            "wersa_block_workspace_bytes", "wersa_block_saved_bytes", "wersa_block_saved_offset",
            "wersa_block_workspace_offset",
@@ -65,6 +65,10 @@ def load_library():
         [vp, ctypes.c_size_t, vp]
     lib.wersa_haar_filter.restype = ctypes.c_int
     lib.wersa_haar_filter.argtypes = [dp, vp, fp, vp, vp]
+    lib.wersa_haar_filter_workspace_bytes.restype = ctypes.c_size_t
+    lib.wersa_haar_filter_workspace_bytes.argtypes = [dp]
+    lib.wersa_haar_filter_ws.restype = ctypes.c_int
+    lib.wersa_haar_filter_ws.argtypes = [dp, vp, fp, vp, vp, ctypes.c_size_t, vp]
     lib.wersa_block_workspace_bytes.restype = ctypes.c_size_t
     lib.wersa_block_workspace_bytes.argtypes = [dp, ctypes.c_int]
     lib.wersa_block_saved_bytes.restype = ctypes.c_size_t
@@ -263,7 +267,13 @@ def wersa_haar_filter(x, filt, L, out=None, stream=None):
     assert filt.dtype == torch.float32 and filt.is_contiguous() and filt.numel() == x.shape[0] * x.shape[1] * (L + 1)
     if out is None:
         out = torch.empty_strided(x.shape, x.stride(), dtype=x.dtype, device=x.device)
-    _check(lib.wersa_haar_filter(ctypes.byref(desc), _ptr(x), _ptr(filt), _ptr(out), _stream(stream)))
+    wb = lib.wersa_haar_filter_workspace_bytes(ctypes.byref(desc))
+    if wb == 0:
+        _check(lib.wersa_haar_filter(ctypes.byref(desc), _ptr(x), _ptr(filt), _ptr(out), _stream(stream)))
+    else:   # levels above 6: the tiles' approximation coefficients go through a workspace
+        ws = torch.empty(wb // 4, dtype=torch.float32, device=x.device)
+        _check(lib.wersa_haar_filter_ws(ctypes.byref(desc), _ptr(x), _ptr(filt), _ptr(out), _ptr(ws), wb,
+                                        _stream(stream)))
     return out
 
 

@@ -114,7 +114,22 @@ wersa_status wersa_haar_filter(const wersa_desc *desc, const void *x, const floa
   const wersa_status vs = validate_desc(desc);
   if (vs != WERSA_OK) return vs;
   if (!x || !filt || !xf) return WERSA_ERR_INVALID_ARG;
-  return generic_haar_filter(*desc, x, filt, xf, (hipStream_t)hip_stream);
+  return generic_haar_filter(*desc, x, filt, xf, nullptr, (hipStream_t)hip_stream);
+}
+
+size_t wersa_haar_filter_workspace_bytes(const wersa_desc *desc) {
+  if (validate_desc(desc) != WERSA_OK) return 0;
+  return generic_haar_filter_floats(*desc) * sizeof(float);
+}
+
+wersa_status wersa_haar_filter_ws(const wersa_desc *desc, const void *x, const float *filt, void *xf,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream) {
+  const wersa_status vs = validate_desc(desc);
+  if (vs != WERSA_OK) return vs;
+  if (!x || !filt || !xf) return WERSA_ERR_INVALID_ARG;
+  const size_t need = generic_haar_filter_floats(*desc) * sizeof(float);
+  if (need && (!workspace || workspace_bytes < need || misaligned(workspace, 256))) return WERSA_ERR_WORKSPACE;
+  return generic_haar_filter(*desc, x, filt, xf, need ? (float *)workspace : nullptr, (hipStream_t)hip_stream);
 }
 
 const char *wersa_status_string(wersa_status status) {

@@ -771,15 +771,16 @@ wersa_status generic_backward(const wersa_desc &c, const void *q, const void *k,
                             (bf16_t *)dk, (bf16_t *)dv, dgate_w, dgate_b, dscale_w, dsigma, ws, st);
 }
 
-// The stage entry point has no workspace argument, so it covers the single-stage range (L <= 6).
+// The stage alone.  Without the approximation arrays it covers the single-stage range (L <= 6).
+size_t generic_haar_filter_floats(const wersa_desc &c) { return (size_t)stages_of(c).total; }
 wersa_status generic_haar_filter(const wersa_desc &c, const void *x, const float *filt, void *xf,
-                                 hipStream_t st) {
-  if (c.L > kTileL) return WERSA_ERR_UNSUPPORTED;
+                                 float *deep, hipStream_t st) {
+  if (c.L > kTileL && !deep) return WERSA_ERR_UNSUPPORTED;
   const View tv{c.stride_b, c.stride_h, c.stride_n, c.H};
   if (c.dtype == WERSA_F32)
-    launch_filter<float, float>(c, (const float *)x, tv, (float *)xf, tv, filt, nullptr, 0.f, nullptr, st);
+    launch_filter<float, float>(c, (const float *)x, tv, (float *)xf, tv, filt, nullptr, 0.f, deep, st);
   else
-    launch_filter<bf16_t, bf16_t>(c, (const bf16_t *)x, tv, (bf16_t *)xf, tv, filt, nullptr, 0.f, nullptr, st);
+    launch_filter<bf16_t, bf16_t>(c, (const bf16_t *)x, tv, (bf16_t *)xf, tv, filt, nullptr, 0.f, deep, st);
   return hipGetLastError() == hipSuccess ? WERSA_OK : WERSA_ERR_LAUNCH;
 }
 

@@ -147,7 +147,10 @@ wersa_status fast_backward(const wersa_desc &c, const void *q, const void *k, co
                            const float *saved, void *dq, void *dk, void *dv, float *dgate_w,
                            float *dgate_b, float *dscale_w, float *dsigma, float *ws,
                            hipStream_t st);
+// deep: approximation arrays of the stages above the first (generic_haar_filter_floats(c) floats;
+// nullptr for L <= 6).
+size_t generic_haar_filter_floats(const wersa_desc &c);
 wersa_status generic_haar_filter(const wersa_desc &c, const void *x, const float *filt, void *xf,
-                                 hipStream_t st);
+                                 float *deep, hipStream_t st);
 
 }  // namespace wersa

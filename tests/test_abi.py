@@ -75,3 +75,13 @@ def test_null_pointers_and_small_workspace(lib):
     assert lib.wersa_backward(ctypes.byref(d), *([one] * 4 + [one] * 4 + [one, None, one] + [one] * 3 + [None] * 4),
                               one, 1 << 40, None) == 1
     assert lib.wersa_haar_filter(ctypes.byref(d), None, one, one, None) == 1
+    # the stage entry point: no workspace needed up to six levels, a deeper transform needs one
+    assert lib.wersa_haar_filter_workspace_bytes(ctypes.byref(d)) == 0
+    assert lib.wersa_haar_filter_ws(ctypes.byref(d), None, one, one, None, 0, None) == 1
+    deep = _desc(n=8192, L=9, stride_b=2 * 8192 * 64, stride_h=8192 * 64)
+    need = lib.wersa_haar_filter_workspace_bytes(ctypes.byref(deep))
+    assert need == 2 * 128 * 64 * 4          # one approximation row per 64-row tile, per slice and column
+    assert lib.wersa_haar_filter(ctypes.byref(deep), one, one, one, None) == 2             # unsupported without
+    assert lib.wersa_haar_filter_ws(ctypes.byref(deep), one, one, one, None, 0, None) == 3
+    assert lib.wersa_haar_filter_ws(ctypes.byref(deep), one, one, one, one, need - 4, None) == 3
+    assert lib.wersa_haar_filter_ws(ctypes.byref(deep), one, one, one, ctypes.c_void_p(264), need, None) == 3

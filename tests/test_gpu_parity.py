@@ -245,6 +245,27 @@ def test_haar_filter_stage(dtype):
     assert hp.rel_err(y1, x.astype(np.float64)) < tol
 
 
+@pytest.mark.parametrize("shape", [dict(n=4160, L=12), dict(n=1000, L=9), dict(n=5000, L=7)])
+def test_haar_filter_stage_deeper_than_one_tile(shape):
+    """The stage entry point with a workspace: levels above 6 run on the approximation
+    coefficients of the tiles (sequence lengths with a partial last tile and a partial last
+    block included)."""
+    import torch
+    from oracle import wersa_oracle as wo
+    from paper_2507_08637_amd import binding
+    B, H, d = 1, 2, 48
+    n, L = shape["n"], shape["L"]
+    rng = np.random.default_rng(7)
+    x = (rng.standard_normal((B, H, n, d)) + 0.3).astype(np.float32)
+    filt = rng.uniform(0.0, 1.5, (B * H, L + 1)).astype(np.float32)
+    xt = torch.from_numpy(x).cuda()
+    y = binding.wersa_haar_filter(xt, torch.from_numpy(filt).cuda(), L)
+    torch.cuda.synchronize()
+    ref = np.stack([wo.haar_filter(x[b, h].astype(np.float64), filt[b * H + h].astype(np.float64), L)
+                    for b in range(B) for h in range(H)]).reshape(B, H, n, d)
+    assert hp.rel_err(y, ref) < 2e-6
+
+
 def test_rerun_is_bit_identical():
     """Fixed-order reductions: two runs give identical bits (doubles as a race check)."""
     import torch
