@@ -104,6 +104,7 @@ MFMA_SHAPES = [
     dict(B=2, H=2, n=320, d=64, L=6, m=256),      # 5 blocks: last workgroup partly idle
     dict(B=1, H=3, n=1024, d=64, L=3, m=384),     # three feature blocks of 128
     dict(B=1, H=2, n=704, d=64, L=0, m=128),      # no wavelet levels
+    dict(B=1, H=2, n=640, d=64, L=0, m=256),      # no wavelet levels, 256 features per pass
     dict(B=2, H=1, n=4096, d=64, L=5, m=512),     # two operand chunks in the rows kernel
     dict(B=1, H=2, n=2560, d=64, L=1, m=256),
     dict(B=1, H=1, n=64, d=128, L=6, m=128),      # head dimension 128: column halves split over waves
