@@ -290,12 +290,15 @@ def test_unsupported_shape_raises_without_launch():
     assert e.value.status == 2
 
 
-@pytest.mark.parametrize("path", ["generic_f32", "generic_bf16", "mfma"])
+@pytest.mark.parametrize("path", ["generic_f32", "generic_bf16", "mfma", "mfma256"])
 def test_separate_query_and_key_random_matrices(path):
     """WERSA_FLAG_SEPARATE_OMEGA (Algorithm 1's independent W_Q^rand, W_K^rand): omega_rf carries
     two matrices; both paths against the oracle given the same pair."""
     dtype = "f32" if path == "generic_f32" else "bf16"
     cfg = dict(B=2, H=2, n=256, d=64, L=4, m=128, dtype=dtype, flavour="plain", seed_base=3100, q_mean=0.4)
+    if path == "mfma256":   # 256 features per pass: the gradient kernels' other loop forms, dV inside the K-side kernel
+        cfg.update(m=256)
+        path = "mfma"
     p = workloads.make_inputs(**cfg)
     omk = np.random.default_rng(3199).standard_normal(p["Omega"].shape, dtype=np.float32)
     p["OmegaK"] = workloads.round_to_bf16(omk) if dtype == "bf16" else omk
@@ -310,12 +313,15 @@ def test_separate_query_and_key_random_matrices(path):
         _check_all(res, ref, TOL[dtype], where=f"separate omega {path}")
 
 
-@pytest.mark.parametrize("path", ["generic_f32", "generic_bf16", "mfma"])
+@pytest.mark.parametrize("path", ["generic_f32", "generic_bf16", "mfma", "mfma256"])
 def test_gate_pooled_over_heads(path):
     """WERSA_FLAG_POOLED_GATE (Algorithm 1's gate: one filter per batch element from the pooled
     queries of all heads) on both paths against the oracle's pooled form."""
     dtype = "f32" if path == "generic_f32" else "bf16"
     cfg = dict(B=2, H=3, n=256, d=64, L=4, m=128, dtype=dtype, flavour="plain", seed_base=3300, q_mean=0.4)
+    if path == "mfma256":
+        cfg.update(m=256)
+        path = "mfma"
     p = workloads.make_inputs(**cfg)
     flags = 4 | (0 if path == "mfma" else 1)
     res = hp.gpu_forward_backward(p, cfg, flags=flags)
