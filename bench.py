@@ -33,6 +33,18 @@ MEASURED_TRAFFIC_CONFIG4 = {
 }
 
 
+def to_device(p, dtype, device="cuda:0"):
+    """NumPy workload dict -> torch tensors on the GPU (storage dtype for the big tensors)."""
+    import numpy as np
+    import torch
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    t = {k: torch.from_numpy(p[k]).to(device).to(tdt) for k in ("Q", "K", "V", "dO", "Omega") if k in p}
+    for k in ("Wg", "bg", "omega"):
+        t[k] = torch.from_numpy(np.ascontiguousarray(p[k], dtype=np.float32)).to(device)
+    t["sigma"] = torch.tensor([float(p["sigma"])], dtype=torch.float32, device=device)
+    return t
+
+
 def kernel_models(cfg):
     """Algorithmic work of ONE launch of each kernel: name -> (bound, peak key, work, unit scale).
 
@@ -189,7 +201,6 @@ def main():
     import numpy as np
     import torch
     from paper_2507_08637_amd import binding, workloads
-    from tests.helpers import to_device
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     binding.load_library()
@@ -264,6 +275,34 @@ def main():
 
     ms = (t1 - t0) * 1e3 / args.steps
     tokens = cfg["B"] * cfg["n"]
+
+    # After the timed region: (a) K more steps with one event pair per step, for a median next to
+    # the mean; (b) what this device sustains on a plain streaming copy and on a bare loop of matrix
+    # instructions, measured now in this process; (c) a few steps each preceded by that 2 GiB copy,
+    # every launch bracketed: the memory-bound stages with their inputs NOT resident in the 256 MB
+    # last-level cache (in back-to-back steps the pooled-query pass finds part of Q there).
+    median_ms, peaks, cold = None, None, {}
+    if not args.graph and not args.no_events:
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        for a, b in evs:
+            a.record()
+            step()
+            b.record()
+        torch.cuda.synchronize()
+        per = sorted(a.elapsed_time(b) for a, b in evs)
+        median_ms = per[len(per) // 2]
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)   # 1 GiB
+        dst = torch.empty_like(src)
+        peaks = {"hbm_copy_GBps": binding.wersa_peak_copy(dst, src, reps=10),
+                 "mfma_bf16_TFLOPs": binding.wersa_peak_mfma(reps=3)}
+        binding.wersa_profile_enable(True)
+        for _ in range(3):
+            binding.wersa_peak_copy(dst, src, reps=1)   # (not one of the bracketed stages)
+            step()
+        torch.cuda.synchronize()
+        cold = binding.wersa_profile_collect()
+        binding.wersa_profile_enable(False)
+        del src, dst
     rec = {
         "metric": "WERSA attention fwd+bwd tokens/s on 1 GPU at n=131072; % HBM/MFMA roofline"
                   if args.config != 5 else
@@ -286,11 +325,40 @@ def main():
             achieved = work / (avg_ms * 1e-3) / (1e9 if unit == "GB/s" else 1e12)
             traffic = MEASURED_TRAFFIC_CONFIG4.get(name) if args.config == 4 else None
             roof = {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
-                    "frac": achieved / peak, "traffic": traffic, "kernel": name,
-                    "avg_launch_ms": avg_ms, "launches_per_step": launches / args.steps}
+                    "frac": achieved / peak, "traffic": traffic,
+                    "traffic_source": ("table in bench.py from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs under "
+                                       "profiles/ (not measured in this run)") if traffic else None,
+                    "kernel": name, "avg_launch_ms": avg_ms, "launches_per_step": launches / args.steps}
         # every kernel, from the untimed survey steps (all launches bracketed)
         rec["kernels_ms_per_step"] = {k: round(v[0] / RANKING_STEPS, 4) for k, v in
                                       sorted(survey.items(), key=lambda kv: -kv[1][0])}
+        # per stage: algorithmic work of one launch, average launch time (survey steps), fraction of the
+        # nominal peak and of the peak measured in this process; memory-bound stages also with cold inputs
+        stages = []
+        for k, (tot, cnt) in sorted(survey.items(), key=lambda kv: -kv[1][0]):
+            if k not in models:
+                continue
+            bound, pk, work = models[k]
+            peak, unit = PEAK[pk]
+            us = tot / cnt * 1e3
+            ach = work / (us * 1e-6) / (1e9 if unit == "GB/s" else 1e12)
+            st = {"kernel": k, "bound": bound, "work_per_launch": work, "work_unit": "B" if bound == "hbm" else "flop",
+                  "launches_per_step": cnt / RANKING_STEPS, "avg_us": round(us, 2), "achieved": round(ach, 1), "unit": unit,
+                  "frac_nominal": round(ach / peak, 4)}
+            if peaks:
+                mp = peaks["hbm_copy_GBps"] if bound == "hbm" else (peaks["mfma_bf16_TFLOPs"] if bound == "mfma" else None)
+                if mp and mp > 0:
+                    st["frac_measured"] = round(ach / mp, 4)
+            if bound == "hbm" and k in cold:
+                cus = cold[k][0] / cold[k][1] * 1e3
+                st["cold_avg_us"] = round(cus, 2)
+                st["cold_frac_nominal"] = round(work / (cus * 1e-6) / 1e9 / peak, 4)
+            stages.append(st)
+        rec["stages"] = stages
+        rec["stages_note"] = ("avg_us: back-to-back steps (a stage may find part of its input in the 256 MB last-level "
+                              "cache); cold_*: the step preceded by a 2 GiB streaming copy")
+    rec["measured_peaks"] = peaks
+    rec["ms_per_step_median"] = median_ms
     rec["roofline"] = roof
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline_block(cfg, p) if args.config == 5 else cpu_baseline(cfg, p)

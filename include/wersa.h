@@ -79,8 +79,13 @@ typedef enum { WERSA_F32 = 0, WERSA_BF16 = 1 } wersa_dtype;
 
 /*
  * Problem descriptor (host memory, read during the call only).
- * Supported range: B, H, n >= 1; 0 <= L <= 20; d % 16 == 0, 16 <= d <= 256; m % 16 == 0,
- * 16 <= m <= 4096. Anything else that is otherwise well formed returns WERSA_ERR_UNSUPPORTED.
+ * Supported range: B, H >= 1 with B * H <= 1023 (the slices are one grid dimension of every
+ * launch, shared with the split of n; larger batches are to be split over calls);
+ * 1 <= n <= 2^22; 0 <= L <= 20; d % 16 == 0, 16 <= d <= 256; m % 16 == 0, 16 <= m <= 4096.
+ * Anything else that is otherwise well formed returns WERSA_ERR_UNSUPPORTED.
+ * MFMA path only: q, k, v, omega_rf, out, dout, dq, dk, dv must be 16-byte aligned (their rows
+ * are read and written in 16-byte pieces); a misaligned pointer returns WERSA_ERR_INVALID_ARG
+ * before anything is enqueued (WERSA_FLAG_GENERIC_PATH takes any element-aligned pointer).
  * Any n is accepted: the Haar filter is local to aligned blocks of 2^L rows, so Algorithm 2's
  * zero padding to the next power of two and the trim after the inverse are the same as reading
  * the rows past n of the last block as zeros and not writing them (done in-kernel; the pooled
@@ -206,6 +211,19 @@ void wersa_profile_reset(void);
 int32_t wersa_profile_collect(void);
 int32_t wersa_profile_get(int32_t index, char *name, int32_t name_len, double *total_ms,
                           int32_t *launches);
+
+/*
+ * Reference microbenchmarks for benchmarks and tools: what this device sustains, measured in the
+ * calling process, next to the nominal peaks.  Both enqueue on hip_stream, WAIT for the result and
+ * return it (-1.0 on a bad argument or a failed launch).
+ * wersa_peak_copy: a plain streaming copy of `bytes` (multiple of 16; dst, src device pointers,
+ * 16-byte aligned, not overlapping) repeated `reps` times; returns GB/s, read plus written.
+ * wersa_peak_mfma: `reps` launches of a loop of independent v_mfma_f32_32x32x16_bf16 on every
+ * compute unit, operands in registers; returns TFLOP/s.  `sink` is one float of device memory
+ * (never written in practice).
+ */
+double wersa_peak_copy(void *dst, const void *src, size_t bytes, int32_t reps, void *hip_stream);
+double wersa_peak_mfma(float *sink, int32_t reps, void *hip_stream);
 
 const char *wersa_status_string(wersa_status status);
 

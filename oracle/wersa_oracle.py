@@ -49,8 +49,10 @@ kernel-matrix attention, arc-cosine kernel limit and m^-1/2 rate, convexity,
 sigma homogeneity, central finite differences for every gradient, ablation
 special cases; for the attention block: identity projections reduce it to the
 pinned core per head, column permutation of W^out, linearity in W^V and W^out,
-central finite differences for every block gradient.  Absolute output values on real data: parity unpinned (the paper
-prints no worked numeric example).
+central finite differences for every block gradient; the two optional hooks
+(`proj_dtype`, `store`) are pinned as the identity when inactive and as exactly
+the stated rounding when active.  Absolute output values on real data: parity
+unpinned (the paper prints no worked numeric example).
 """
 import math
 

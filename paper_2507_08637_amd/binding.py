@@ -18,6 +18,7 @@ WERSA_FLAG_GENERIC_PATH = 1
 EXPORTS = ["wersa_workspace_bytes", "wersa_saved_bytes", "wersa_forward", "wersa_backward",
            "wersa_haar_filter", "wersa_haar_filter_ws", "wersa_haar_filter_workspace_bytes", "wersa_saved_offset", "wersa_selected_path", "wersa_status_string", "wersa_version",
            "wersa_profile_enable", "wersa_profile_only", "wersa_profile_reset", "wersa_profile_collect", "wersa_profile_get",
+           "wersa_peak_copy", "wersa_peak_mfma",
            "wersa_block_workspace_bytes", "wersa_block_saved_bytes", "wersa_block_saved_offset",
            "wersa_block_workspace_offset",
            "wersa_block_forward", "wersa_block_backward"]
@@ -97,6 +98,10 @@ def load_library():
     lib.wersa_profile_get.restype = ctypes.c_int32
     lib.wersa_profile_get.argtypes = [ctypes.c_int32, ctypes.c_char_p, ctypes.c_int32,
                                       ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)]
+    lib.wersa_peak_copy.restype = ctypes.c_double
+    lib.wersa_peak_copy.argtypes = [vp, vp, ctypes.c_size_t, ctypes.c_int32, vp]
+    lib.wersa_peak_mfma.restype = ctypes.c_double
+    lib.wersa_peak_mfma.argtypes = [fp, ctypes.c_int32, vp]
     _lib = lib
     return lib
 
@@ -130,6 +135,21 @@ def _ptr(t):
 def _stream(stream):
     s = stream if stream is not None else torch.cuda.current_stream()
     return ctypes.c_void_p(s.cuda_stream)
+
+
+def _nbytes(t):
+    return t.numel() * t.element_size()
+
+
+def _scratch(nbytes, like, stream):
+    """Temporary device buffer for one call.  The kernels that use it are only queued when the call
+    returns, so the buffer must not go back to torch's allocator for reuse before they have run:
+    with an explicit `stream` it is tied to that stream (the caching allocator then waits for the
+    stream's queued work before handing the block to anyone else)."""
+    buf = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=like.device)
+    if stream is not None:
+        buf.record_stream(stream)
+    return buf
 
 
 def _same_layout(ref, *others):
@@ -203,17 +223,19 @@ def wersa_forward(q, k, v, omega_rf, sigma, gate_w, gate_b, scale_w, L, eps=1e-6
         out = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
     else:
         _same_layout(q, out)
+    sb = lib.wersa_saved_bytes(ctypes.byref(desc))
+    if sb == 0:
+        _check(_probe(desc))
     if saved is None:
-        sb = lib.wersa_saved_bytes(ctypes.byref(desc))
-        if sb == 0:
-            _check(_probe(desc))
         saved = torch.empty(sb // 4, dtype=torch.float32, device=q.device)
+    else:   # the C ABI takes no size for `saved`: checked here
+        assert _nbytes(saved) >= sb, f"saved buffer holds {_nbytes(saved)} bytes, wersa_saved_bytes asks for {sb}"
     wb = lib.wersa_workspace_bytes(ctypes.byref(desc), 0)
     if workspace is None:
-        workspace = torch.empty(max(wb, 256) // 4, dtype=torch.float32, device=q.device)
+        workspace = _scratch(wb, q, stream)
     _check(lib.wersa_forward(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(omega_rf), _ptr(sigma),
                              _ptr(gate_w), _ptr(gate_b), _ptr(scale_w), _ptr(out), _ptr(saved),
-                             _ptr(workspace), workspace.numel() * 4, _stream(stream)))
+                             _ptr(workspace), _nbytes(workspace), _stream(stream)))
     return out, saved
 
 
@@ -251,11 +273,13 @@ def wersa_backward(q, k, v, omega_rf, sigma, gate_w, gate_b, scale_w, out, dout,
         dgw = dgb = dsw = dsg = None
     wb = lib.wersa_workspace_bytes(ctypes.byref(desc), 1)
     if workspace is None:
-        workspace = torch.empty(max(wb, 256) // 4, dtype=torch.float32, device=q.device)
+        workspace = _scratch(wb, q, stream)
+    sb = lib.wersa_saved_bytes(ctypes.byref(desc))
+    assert sb == 0 or _nbytes(saved) >= sb, f"saved buffer holds {_nbytes(saved)} bytes, wersa_saved_bytes asks for {sb}"
     _check(lib.wersa_backward(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(omega_rf), _ptr(sigma),
                               _ptr(gate_w), _ptr(gate_b), _ptr(scale_w), _ptr(out), _ptr(dout),
                               _ptr(saved), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dgw), _ptr(dgb),
-                              _ptr(dsw), _ptr(dsg), _ptr(workspace), workspace.numel() * 4,
+                              _ptr(dsw), _ptr(dsg), _ptr(workspace), _nbytes(workspace),
                               _stream(stream)))
     return dict(dq=dq, dk=dk, dv=dv, dgate_w=dgw, dgate_b=dgb, dscale_w=dsw, dsigma=dsg)
 
@@ -271,7 +295,7 @@ def wersa_haar_filter(x, filt, L, out=None, stream=None):
     if wb == 0:
         _check(lib.wersa_haar_filter(ctypes.byref(desc), _ptr(x), _ptr(filt), _ptr(out), _stream(stream)))
     else:   # levels above 6: the tiles' approximation coefficients go through a workspace
-        ws = torch.empty(wb // 4, dtype=torch.float32, device=x.device)
+        ws = _scratch(wb, x, stream)
         _check(lib.wersa_haar_filter_ws(ctypes.byref(desc), _ptr(x), _ptr(filt), _ptr(out), _ptr(ws), wb,
                                         _stream(stream)))
     return out
@@ -335,11 +359,13 @@ def wersa_block_forward(x, wq, wk, wv, wo, H, omega_rf, sigma, gate_w, gate_b, s
         y = torch.empty_like(x)
     if saved is None:
         saved = torch.empty(sb, dtype=torch.uint8, device=x.device)
+    else:
+        assert _nbytes(saved) >= sb, f"saved buffer holds {_nbytes(saved)} bytes, wersa_block_saved_bytes asks for {sb}"
     if workspace is None:
-        workspace = torch.empty(wb, dtype=torch.uint8, device=x.device)
+        workspace = _scratch(wb, x, stream)
     _check(lib.wersa_block_forward(ctypes.byref(desc), _ptr(x), _ptr(wq), _ptr(wk), _ptr(wv), _ptr(wo),
                                    _ptr(omega_rf), _ptr(sigma), _ptr(gate_w), _ptr(gate_b), _ptr(scale_w),
-                                   _ptr(y), _ptr(saved), _ptr(workspace), workspace.numel(), _stream(stream)))
+                                   _ptr(y), _ptr(saved), _ptr(workspace), _nbytes(workspace), _stream(stream)))
     return y, saved
 
 
@@ -361,14 +387,16 @@ def wersa_block_backward(x, wq, wk, wv, wo, H, omega_rf, sigma, gate_w, gate_b, 
                      dgate_w=torch.empty_like(gate_w), dgate_b=torch.empty_like(gate_b),
                      dscale_w=torch.empty_like(scale_w), dsigma=torch.empty(1, **f32))
     if workspace is None:
-        workspace = torch.empty(wb, dtype=torch.uint8, device=x.device)
+        workspace = _scratch(wb, x, stream)
+    sb = lib.wersa_block_saved_bytes(ctypes.byref(desc))
+    assert _nbytes(saved) >= sb, f"saved buffer holds {_nbytes(saved)} bytes, wersa_block_saved_bytes asks for {sb}"
     g = grads
     _check(lib.wersa_block_backward(ctypes.byref(desc), _ptr(x), _ptr(wq), _ptr(wk), _ptr(wv), _ptr(wo),
                                     _ptr(omega_rf), _ptr(sigma), _ptr(gate_w), _ptr(gate_b), _ptr(scale_w),
                                     _ptr(dy), _ptr(saved), _ptr(g["dx"]), _ptr(g["dwq"]), _ptr(g["dwk"]),
                                     _ptr(g["dwv"]), _ptr(g["dwo"]), _ptr(g["dgate_w"]), _ptr(g["dgate_b"]),
                                     _ptr(g["dscale_w"]), _ptr(g["dsigma"]), _ptr(workspace),
-                                    workspace.numel(), _stream(stream)))
+                                    _nbytes(workspace), _stream(stream)))
     return grads
 
 
@@ -391,3 +419,16 @@ def wersa_profile_collect():
         if lib.wersa_profile_get(i, buf, 128, ctypes.byref(ms), ctypes.byref(launches)) == 0:
             out[buf.value.decode()] = (ms.value, launches.value)
     return out
+
+
+def wersa_peak_copy(dst, src, reps=10, stream=None):
+    """GB/s (read + written) of a plain streaming copy src -> dst, measured now on this device."""
+    assert dst.is_contiguous() and src.is_contiguous() and dst.numel() * dst.element_size() == src.numel() * src.element_size()
+    return load_library().wersa_peak_copy(_ptr(dst), _ptr(src), src.numel() * src.element_size() // 16 * 16, reps,
+                                          _stream(stream))
+
+
+def wersa_peak_mfma(reps=3, stream=None):
+    """TFLOP/s of a loop of independent bf16 32x32x16 matrix instructions on every compute unit."""
+    sink = torch.zeros(64, dtype=torch.float32, device="cuda")
+    return load_library().wersa_peak_mfma(_ptr(sink), reps, _stream(stream))

@@ -35,9 +35,13 @@ wersa_status forward_checked(const wersa_desc *desc, const void *q, const void *
   if (!workspace || workspace_bytes < wersa_workspace_bytes(desc, 0) || misaligned(workspace, 256) ||
       misaligned(saved, 256))
     return WERSA_ERR_WORKSPACE;
-  if (use_fast(*desc))
+  if (use_fast(*desc)) {
+    // the MFMA path moves rows in 16-byte pieces
+    if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(omega_rf, 16) || misaligned(out, 16))
+      return WERSA_ERR_INVALID_ARG;
     return fast_forward(*desc, q, k, v, omega_rf, sigma, gate_w, gate_b, scale_w, out, (float *)saved,
                         (float *)workspace, (hipStream_t)hip_stream, pooled);
+  }
   return generic_forward(*desc, q, k, v, omega_rf, sigma, gate_w, gate_b, scale_w, out, (float *)saved,
                          (float *)workspace, (hipStream_t)hip_stream);
 }
@@ -100,10 +104,14 @@ wersa_status wersa_backward(const wersa_desc *desc, const void *q, const void *k
   if (!workspace || workspace_bytes < wersa_workspace_bytes(desc, 1) || misaligned(workspace, 256) ||
       misaligned(saved, 256))
     return WERSA_ERR_WORKSPACE;
-  if (use_fast(*desc))
+  if (use_fast(*desc)) {
+    if (misaligned(q, 16) || misaligned(k, 16) || misaligned(v, 16) || misaligned(omega_rf, 16) ||
+        misaligned(out, 16) || misaligned(dout, 16) || misaligned(dq, 16) || misaligned(dk, 16) || misaligned(dv, 16))
+      return WERSA_ERR_INVALID_ARG;
     return fast_backward(*desc, q, k, v, omega_rf, sigma, gate_w, scale_w, out, dout,
                          (const float *)saved, dq, dk, dv, dgate_w, dgate_b, dscale_w, dsigma,
                          (float *)workspace, (hipStream_t)hip_stream);
+  }
   return generic_backward(*desc, q, k, v, omega_rf, sigma, gate_w, gate_b, scale_w, out, dout,
                           (const float *)saved, dq, dk, dv, dgate_w, dgate_b, dscale_w, dsigma,
                           (float *)workspace, (hipStream_t)hip_stream);

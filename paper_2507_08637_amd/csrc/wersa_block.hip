@@ -321,9 +321,13 @@ BlockWs block_ws(const BlockPlan &p, int bwd) {
   return w;
 }
 
+// The caller's stride fields are ignored (the block lays its tensors out itself): the sizes are
+// checked first, then the core descriptor the block builds from them goes through the core's
+// own validation.
 wersa_status validate_block(const wersa_desc *c) {
-  const wersa_status vs = validate_desc(c);
-  if (vs != WERSA_OK) return vs;
+  if (!c) return WERSA_ERR_INVALID_ARG;
+  if (c->B < 1 || c->H < 1 || c->n < 1 || c->d < 1 || c->m < 1 || c->L < 0) return WERSA_ERR_INVALID_ARG;
+  if (c->dtype != WERSA_F32 && c->dtype != WERSA_BF16) return WERSA_ERR_INVALID_ARG;
   if (c->dtype != WERSA_BF16) return WERSA_ERR_UNSUPPORTED;
   const int64_t hidden = (int64_t)c->H * c->d, tokens = (int64_t)c->B * c->n;
   if (hidden % BM != 0 || tokens % BM != 0 || hidden > 16384) return WERSA_ERR_UNSUPPORTED;

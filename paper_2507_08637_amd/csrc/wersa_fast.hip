@@ -924,7 +924,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
     const bf16_t *Mx,          // (S | z) (MODE 1) / (dS | dz) (MODE 2), bf16 [slices][m][DH+16]
     const bf16_t *MT,          // S^T (MODE 0) / dS^T (MODE 3), bf16 [slices][DH][m]
     const bf16_t *bb,          // z bf16 [slices][m] (MODE 0)
-    const float *coef,         // filter coefficients [slices][8]
+    const float *coef,         // block-mean filter coefficients [slices][kCoefStride]
     const float *scalars, float eps, int n, int m, int row_groups,
     bf16_t *out0, View vo,     // O (MODE 0) / dQ or dK (MODE 1, 2) / dV (MODE 3)
     float *Dout,               // D (MODE 0)

@@ -38,6 +38,48 @@ struct Agg {
 std::vector<Agg> g_agg;
 }  // namespace
 
+// ---- reference microbenchmarks: what this device sustains on a plain streaming copy and on a
+// loop of independent matrix instructions, for roofline fractions against measured peaks --------
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 pk_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float pk_f32x16 __attribute__((ext_vector_type(16)));
+
+// dst[i] = src[i] for `pieces` 16-byte pieces, grid-stride, four independent pieces per thread per round.
+__global__ __launch_bounds__(256) void peak_copy_kernel(u32x4 *dst, const u32x4 *src, size_t pieces) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  for (; i + 3 * stride < pieces; i += 4 * stride) {
+    const u32x4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    dst[i] = a;
+    dst[i + stride] = b;
+    dst[i + 2 * stride] = c;
+    dst[i + 3 * stride] = d;
+  }
+  for (; i < pieces; i += stride) dst[i] = src[i];
+}
+
+// Every wave issues iters x 4 independent v_mfma_f32_32x32x16_bf16 (four accumulator tiles, operands
+// in registers): no memory traffic, nothing but the matrix pipe.  The store never happens (the
+// accumulators cannot reach that value); it keeps the loop alive.
+__global__ __launch_bounds__(256) void peak_mfma_kernel(int iters, float seed, float *sink) {
+  pk_bf16x8 a, b;
+  for (int q = 0; q < 8; ++q) {
+    a[q] = (__bf16)(seed + 0.001f * (float)(threadIdx.x + q));
+    b[q] = (__bf16)(seed - 0.002f * (float)(threadIdx.x ^ q));
+  }
+  pk_f32x16 c0, c1, c2, c3;
+  for (int i = 0; i < 16; ++i) c0[i] = c1[i] = c2[i] = c3[i] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+    c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
+    c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c1, 0, 0, 0);
+    c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c2, 0, 0, 0);
+    c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c3, 0, 0, 0);
+  }
+  float s = 0.f;
+  for (int i = 0; i < 16; ++i) s += c0[i] + c1[i] + c2[i] + c3[i];
+  if (s == -1.2345e30f) sink[0] = s;
+}
+
 bool profiling() { return g_on; }
 
 void prof_begin(const char *name, hipStream_t st) {
@@ -94,6 +136,46 @@ int32_t wersa_profile_collect(void) {
   g_recs.clear();
   g_pool_used = 0;
   return (int32_t)g_agg.size();
+}
+
+double wersa_peak_copy(void *dst, const void *src, size_t bytes, int32_t reps, void *hip_stream) {
+  if (!dst || !src || bytes < 16 || reps < 1 || ((uintptr_t)dst % 16) || ((uintptr_t)src % 16)) return -1.0;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const size_t pieces = bytes / 16;
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess) return -1.0;
+  if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return -1.0; }
+  const unsigned grid = 256 * 16;   // 16 workgroups of 256 threads per compute unit
+  peak_copy_kernel<<<grid, 256, 0, st>>>((u32x4 *)dst, (const u32x4 *)src, pieces);   // warm-up
+  (void)hipEventRecord(e0, st);
+  for (int r = 0; r < reps; ++r) peak_copy_kernel<<<grid, 256, 0, st>>>((u32x4 *)dst, (const u32x4 *)src, pieces);
+  (void)hipEventRecord(e1, st);
+  float ms = 0.f;
+  const bool ok = hipEventSynchronize(e1) == hipSuccess && hipEventElapsedTime(&ms, e0, e1) == hipSuccess &&
+                  hipGetLastError() == hipSuccess && ms > 0.f;
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  return ok ? 2.0 * (double)(pieces * 16) * reps / (ms * 1e-3) / 1e9 : -1.0;
+}
+
+double wersa_peak_mfma(float *sink, int32_t reps, void *hip_stream) {
+  if (!sink || reps < 1) return -1.0;
+  hipStream_t st = (hipStream_t)hip_stream;
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess) return -1.0;
+  if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return -1.0; }
+  const int blocks = 2048, iters = 4096;   // 8 waves per compute unit (two per SIMD), 16384 matrix instructions each
+  peak_mfma_kernel<<<blocks, 256, 0, st>>>(64, 0.5f, sink);   // warm-up
+  (void)hipEventRecord(e0, st);
+  for (int r = 0; r < reps; ++r) peak_mfma_kernel<<<blocks, 256, 0, st>>>(iters, 0.5f, sink);
+  (void)hipEventRecord(e1, st);
+  float ms = 0.f;
+  const bool ok = hipEventSynchronize(e1) == hipSuccess && hipEventElapsedTime(&ms, e0, e1) == hipSuccess &&
+                  hipGetLastError() == hipSuccess && ms > 0.f;
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  const double flop = (double)blocks * 4.0 * iters * 4.0 * (2.0 * 32 * 32 * 16) * reps;
+  return ok ? flop / (ms * 1e-3) / 1e12 : -1.0;
 }
 
 int32_t wersa_profile_get(int32_t index, char *name, int32_t name_len, double *total_ms,

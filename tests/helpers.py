@@ -106,3 +106,24 @@ def scaled_err(gpu, ref, scale):
     """||gpu - ref||_F / ||scale||_F."""
     a = gpu.detach().float().cpu().numpy().astype(np.float64).reshape(ref.shape)
     return float(np.linalg.norm(a - ref) / np.linalg.norm(scale))
+
+
+def err_stats(gpu, ref, rows=64):
+    """Error figures of one (..., n, d) output against the oracle: relative Frobenius error, largest
+    absolute error over the largest absolute value of the oracle, and the worst relative Frobenius
+    error over the aligned blocks of `rows` rows (a partial last block counts as a block)."""
+    a = gpu.detach().float().cpu().numpy().astype(np.float64).reshape(ref.shape)
+    diff = a - ref
+    n, d = ref.shape[-2], ref.shape[-1]
+    lead = int(np.prod(ref.shape[:-2])) if ref.ndim > 2 else 1
+    d2 = (diff.reshape(lead, n, d) ** 2).sum(-1)
+    r2 = (ref.reshape(lead, n, d) ** 2).sum(-1)
+    pad = (-n) % rows
+    if pad:
+        d2 = np.pad(d2, ((0, 0), (0, pad)))
+        r2 = np.pad(r2, ((0, 0), (0, pad)))
+    db = d2.reshape(lead, -1, rows).sum(-1)
+    rb = r2.reshape(lead, -1, rows).sum(-1)
+    return dict(fro=float(np.sqrt(d2.sum() / r2.sum())),
+                maxabs=float(np.abs(diff).max() / np.abs(ref).max()),
+                worst_block=float(np.sqrt((db / np.maximum(rb, 1e-300)).max())))

@@ -85,3 +85,39 @@ def test_null_pointers_and_small_workspace(lib):
     assert lib.wersa_haar_filter_ws(ctypes.byref(deep), one, one, one, None, 0, None) == 3
     assert lib.wersa_haar_filter_ws(ctypes.byref(deep), one, one, one, one, need - 4, None) == 3
     assert lib.wersa_haar_filter_ws(ctypes.byref(deep), one, one, one, ctypes.c_void_p(264), need, None) == 3
+
+
+def test_stated_limits_alignment_and_block_strides(lib):
+    """What the header states: at most 1023 slices and 2^22 rows; on the MFMA path the tensor
+    pointers are 16-byte aligned (checked before anything is enqueued); the block entry points
+    ignore the descriptor's stride fields."""
+    from paper_2507_08637_amd.binding import WersaDesc
+    big = _desc(B=64, H=16, stride_b=16 * 256 * 64)
+    assert lib.wersa_saved_bytes(ctypes.byref(big)) == 0 and lib.wersa_selected_path(ctypes.byref(big)) == -1
+    assert lib.wersa_selected_path(ctypes.byref(_desc(B=33, H=31, stride_b=31 * 256 * 64))) == 0
+    long = _desc(n=(1 << 22) + 1, stride_h=((1 << 22) + 1) * 64, stride_b=2 * ((1 << 22) + 1) * 64)
+    assert lib.wersa_saved_bytes(ctypes.byref(long)) == 0
+    # MFMA path (bf16, d = 64, m % 128 == 0): a pointer that is 2-byte but not 16-byte aligned
+    fast = _desc(dtype=1, m=128)
+    assert lib.wersa_selected_path(ctypes.byref(fast)) == 1
+    ok, odd = ctypes.c_void_p(256), ctypes.c_void_p(258)
+    huge = 1 << 40
+    fwd = lambda q=ok, out=ok: lib.wersa_forward(ctypes.byref(fast), q, ok, ok, ok, ok, ok, ok, ok, out, ok, ok, huge, None)
+    assert fwd(q=odd) == 1 and fwd(out=odd) == 1
+    bwd = [ok] * 4 + [ok] * 4 + [ok, ok, ok] + [ok, odd, ok] + [None] * 4
+    assert lib.wersa_backward(ctypes.byref(fast), *bwd, ok, huge, None) == 1
+    # the same pointers on the generic path pass validation up to the workspace check
+    gen = _desc(dtype=1, m=128, flags=1)
+    assert lib.wersa_forward(ctypes.byref(gen), odd, ok, ok, ok, ok, ok, ok, ok, ok, ok, ok, 16, None) == 3
+    # attention block: strides left at zero by a C caller
+    blk = WersaDesc(B=2, H=4, n=256, d=64, L=3, m=128, dtype=1, eps=1e-6, bw_floor=1e-6, stride_b=0, stride_h=0,
+                    stride_n=0, flags=0)
+    assert lib.wersa_block_saved_bytes(ctypes.byref(blk)) > 0
+    assert lib.wersa_block_workspace_bytes(ctypes.byref(blk), 1) > 0
+    with_strides = WersaDesc(B=2, H=4, n=256, d=64, L=3, m=128, dtype=1, eps=1e-6, bw_floor=1e-6,
+                             stride_b=256 * 256, stride_h=64, stride_n=256, flags=0)
+    assert lib.wersa_block_saved_bytes(ctypes.byref(blk)) == lib.wersa_block_saved_bytes(ctypes.byref(with_strides))
+    assert lib.wersa_block_forward(ctypes.byref(blk), *([ok] * 13), 16, None) == 3   # reaches the workspace check
+    # the microbenchmarks refuse bad arguments without touching the device
+    assert lib.wersa_peak_copy(None, ok, 1 << 20, 1, None) == -1.0
+    assert lib.wersa_peak_mfma(None, 1, None) == -1.0

@@ -74,6 +74,10 @@ def test_block_forward_backward(shape):
     core_p = dict(Q=wo.split_heads(ref["Qp"], H), K=wo.split_heads(ref["Kp"], H), V=wo.split_heads(ref["Vp"], H),
                   dO=wo.split_heads(ref["dA"], H), Omega=p["Omega"], Wg=p["Wg"], bg=p["bg"], omega=p["omega"],
                   sigma=p["sigma"])
+    plain = {k: hp.rel_err(res[k], ref[k]) for k in ("dWg", "dbg", "domega")}
+    print(shape, "gate grads, plain relative", {k: f"{v:.2e}" for k, v in plain.items()}, flush=True)
+    if all(v < 2e-2 for v in plain.values()):
+        return
     scales = hp.gate_grad_scales(core_p, dict(cfg, d=cfg["d"]))
     gerr = {k: hp.scaled_err(res[k], ref16[k], scales[k]) for k in ("dWg", "dbg", "domega")}
     print(shape, "gate grads vs un-cancelled scale", {k: f"{v:.2e}" for k, v in gerr.items()}, flush=True)
@@ -118,15 +122,14 @@ def test_block_gradient_of_query_weights_with_shifted_input():
 
 def test_config5_block_full_size():
     """Configuration 5 at full size (B=2, H=16, n=65536, d=128, hidden 2048) through the block
-    entry points.  The oracle recomputes head h of both batches from the inputs alone (its own
-    projections, core forward and backward), which pins: the projections, A, dA, dQ', dK', dV' on
-    those slices and the column (row) blocks of the four weight gradients that belong to head h
-    (they sum over both batches).  Y and dX mix all heads of a token; they are checked as the
-    stated product of the kernel's own stage inputs on sampled tokens (a property of the stage
-    that holds at any size), the stage inputs themselves being pinned per slice as above."""
+    entry points against the oracle's block on the whole problem: every projection, every head's
+    A, dA, dQ', dK', dV', the outputs Y and dX on every token, the four weight gradients and the
+    gate-parameter gradients (which sum over all 32 slices), plus per-block and per-element bounds
+    on the per-head tensors (see BLOCK_BOUNDS in the core's parity tests)."""
+    import time
     import torch
-    from oracle import wersa_oracle as wo
     from paper_2507_08637_amd import binding
+    from tests.test_gpu_parity import BLOCK_BOUNDS
     cfg = dict(workloads.CONFIGS[5])
     B, H, n, d, L, m = (cfg[k] for k in ("B", "H", "n", "d", "L", "m"))
     hidden = H * d
@@ -148,56 +151,52 @@ def test_config5_block_full_size():
     sv = binding.block_saved_views(desc, saved)
     wv = binding.block_workspace_views(desc, wsb)
     print("config5 block: GPU forward and backward done", flush=True)
+    # the oracle, one batch element at a time (they are independent; gradients of parameters and
+    # weights sum over them), so that each call finishes in about a minute and prints when it has
+    t0 = time.time()
+    ref = None
+    per_token = ("Y", "A", "Qp", "Kp", "Vp", "dA", "dQp", "dKp", "dVp", "dX")
+    for b in range(B):
+        rb = _oracle_block(dict(p, X=p["X"][b:b + 1], dY=p["dY"][b:b + 1]), cfg)
+        print(f"config5 block: oracle, batch element {b} done after {time.time() - t0:.0f} s", flush=True)
+        if ref is None:
+            ref = rb
+        else:
+            for k in rb:
+                ref[k] = np.concatenate([ref[k], rb[k]], axis=0) if k in per_token else ref[k] + rb[k]
+        del rb
 
-    h = 11
-    cols = slice(h * d, (h + 1) * d)
-    rb = lambda a: workloads.round_to_bf16(a).astype(np.float64)
-    f64 = lambda a: np.asarray(a, np.float64)
-    WQ, WK, WV, WO = (f64(p[k]) for k in ("WQ", "WK", "WV", "WO"))
-    Om, Wg_h, bg_h, om = f64(p["Omega"]), f64(p["Wg"][h]), f64(p["bg"][h]), f64(p["omega"])
-    sigma = float(p["sigma"])
-    dW = {k: np.zeros((hidden, d)) for k in ("dWQ", "dWK", "dWV")}
-    dWO_rows = np.zeros((d, hidden))
-
-    def gpu_np(tensor):
-        return tensor.double().cpu().numpy()
-
-    def check(name, gpu, ref, tol=2e-2):
-        e = float(np.linalg.norm(gpu - ref) / np.linalg.norm(ref))
+    def check(name, gpu, r, tol=2e-2):
+        e = hp.rel_err(gpu, r)
         print(f"config5 block {name}: {e:.2e}", flush=True)
         assert e < tol, (name, e)
 
-    for b in range(B):
-        Xb, dYb = f64(p["X"][b]), f64(p["dY"][b])
-        Qs, Ks, Vs = rb(Xb @ WQ[:, cols]), rb(Xb @ WK[:, cols]), rb(Xb @ WV[:, cols])
-        for name, ref in (("Qp", Qs), ("Kp", Ks), ("Vp", Vs)):
-            check(f"b{b} h{h} {name}", gpu_np(sv[name][b][:, cols]), ref, tol=2e-3)
-        fw = wo.forward_slice(Qs, Ks, Vs, Om, sigma, Wg_h, bg_h, om, L, 1e-6, 1e-6)
-        As = rb(fw["O"])
-        check(f"b{b} h{h} A", gpu_np(sv["A"][b][:, cols]), As)
-        dAs = rb(dYb @ WO[cols, :].T)
-        check(f"b{b} h{h} dA", gpu_np(wv["dA"][b][:, cols]), dAs, tol=2e-3)
-        bw = wo.backward_slice(Qs, Ks, Vs, Om, sigma, Wg_h, bg_h, om, L, 1e-6, 1e-6, dAs, fwd=fw)
-        for name, key in (("dQp", "dQ"), ("dKp", "dK"), ("dVp", "dV")):
-            ref = rb(bw[key])
-            check(f"b{b} h{h} {name}", gpu_np(wv[name][b][:, cols]), ref)
-            dW["dW" + name[1].upper()] += Xb.T @ ref
-        dWO_rows += As.T @ dYb
-        del Xb, dYb, fw, bw
-    for name, key in (("dWQ", "dwq"), ("dWK", "dwk"), ("dWV", "dwv")):
-        check(f"{name}[:, head {h}]", gpu_np(g[key][:, cols]), dW[name])
-    check(f"dWO[head {h}, :]", gpu_np(g["dwo"][cols, :]), dWO_rows)
-
-    # Y = A W^out and dX = dQ' W^Q^T + dK' W^K^T + dV' W^V^T on sampled tokens, from the kernel's
-    # own stage inputs.
-    r = np.random.default_rng(55)
-    toks = [(int(r.integers(B)), int(r.integers(n))) for _ in range(48)] + [(0, 0), (B - 1, n - 1)]
-    bi = torch.tensor([b for b, _ in toks], device=dev)
-    ti = torch.tensor([tt for _, tt in toks], device=dev)
-    rows = lambda tensor: gpu_np(tensor[bi, ti])
-    check("Y on sampled tokens", rows(y), rows(sv["A"]) @ WO, tol=5e-3)
-    check("dX on sampled tokens", rows(g["dx"]),
-          rows(wv["dQp"]) @ WQ.T + rows(wv["dKp"]) @ WK.T + rows(wv["dVp"]) @ WV.T, tol=5e-3)
+    for name in ("Qp", "Kp", "Vp"):
+        check(name, sv[name], ref[name], tol=2e-3)
+    check("dA", wv["dA"], ref["dA"], tol=2e-3)
+    check("A", sv["A"], ref["A"])
+    for name in ("dQp", "dKp", "dVp"):
+        check(name, wv[name], ref[name])
+    check("Y", y, ref["Y"])
+    check("dX", g["dx"], ref["dX"])
+    for name, key in (("dWQ", "dwq"), ("dWK", "dwk"), ("dWV", "dwv"), ("dWO", "dwo")):
+        check(name, g[key], ref[name])
+    for name, key in (("dWg", "dgate_w"), ("dbg", "dgate_b"), ("domega", "dscale_w")):
+        check(name, g[key], ref[name])
+    # per head: Frobenius error of every (batch, head) slice, worst 64-row block, largest element error
+    from oracle import wersa_oracle as wo
+    for name, gpu, bound in (("A", sv["A"], "O"), ("dQp", wv["dQp"], "dQ"), ("dKp", wv["dKp"], "dK"),
+                             ("dVp", wv["dVp"], "dV")):
+        gh = gpu.view(B, n, H, d).permute(0, 2, 1, 3)
+        rh = wo.split_heads(ref[name], H)
+        st = hp.err_stats(gh, rh)
+        print(f"config5 block {name} per-head figures", {k: f"{v:.2e}" for k, v in st.items()}, flush=True)
+        for k, limit in BLOCK_BOUNDS[bound].items():
+            assert st[k] < limit, (name, k, st[k])
+        for b in range(B):
+            for h in range(H):
+                e = hp.rel_err(gh[b, h], rh[b, h])
+                assert e < 2e-2, (name, b, h, e)
 
 
 def test_block_rejects_unsupported_shapes():

@@ -26,22 +26,31 @@ def _check_all(res, ref, tol, names=("O", "dQ", "dK", "dV", "dWg", "dbg", "domeg
     return errs
 
 
-def _check_mfma(res, ref, p, cfg, where=""):
-    """MFMA path: O, dQ, dK, dV within 2e-2 relative Frobenius error of the float64 oracle.
-    The gate-parameter gradients are inner products of dX_F (a tensor that itself carries the
-    2e-2 tolerance) with the wavelet bands of X; on random inputs they cancel down to the noise
-    floor, so their error is bounded against the un-cancelled magnitude (helpers.gate_grad_scales)
-    with the same 2e-2, and the plain relative error against the float64 oracle is printed for
-    the record."""
+def _check_mfma(res, ref, p, cfg, where="", noise_limited=False, eps=1e-6, pooled=False, layernorm=False):
+    """MFMA path against the plain float64 oracle.  O, dQ, dK, dV: 2e-2 relative Frobenius error,
+    always.  Gate-parameter gradients (dW_g, db_g, d omega): the same plain 2e-2, unless the case
+    is listed as noise-limited: these gradients are inner products of dX_F (a tensor that itself
+    carries the 2e-2 tolerance) with the wavelet bands of X, and on small seeded random inputs they
+    cancel down to their statistical noise floor, where a relative error says nothing.  For those
+    listed cases the error is bounded against the un-cancelled magnitude of the sum
+    (helpers.gate_grad_scales), both sides taking the ReLU decision at the kernel's precision
+    (X_F rounded to fp16 before the projection); the plain relative error is printed.  Every kernel
+    variant that has such a case also has a signal-carrying case held to the plain 2e-2
+    (test_mfma_gate_gradients_with_signal).  noise_limited=None accepts either criterion."""
     _check_all(res, ref, 2e-2, names=("O", "dQ", "dK", "dV"), where=where)
-    scales = hp.gate_grad_scales(p, cfg)
-    # The ReLU derivative is a float-decided binary decision; for the cancelling sums both sides
-    # take it at the kernel's precision (X_F rounded to fp16 before the projection).
-    ref16 = hp.oracle_backward(p, cfg, proj_dtype=np.float16)
-    errs = {k: hp.scaled_err(res[k], ref16[k], scales[k]) for k in ("dWg", "dbg", "domega")}
     plain = {k: hp.rel_err(res[k], ref[k]) for k in ("dWg", "dbg", "domega")}
-    print(where, "gate grads vs un-cancelled scale", {k: f"{v:.2e}" for k, v in errs.items()},
-          "plain relative", {k: f"{v:.2e}" for k, v in plain.items()}, flush=True)
+    strict_ok = all(v < 2e-2 for v in plain.values())
+    print(where, "gate grads, plain relative", {k: f"{v:.2e}" for k, v in plain.items()},
+          "STRICT-OK" if strict_ok else "ABOVE-2e-2", flush=True)
+    if noise_limited is False:
+        assert strict_ok, (where, plain)
+        return
+    if noise_limited is None and strict_ok:
+        return
+    scales = hp.gate_grad_scales(p, cfg, eps=eps, layernorm=layernorm)
+    ref16 = hp.oracle_backward(p, cfg, eps=eps, proj_dtype=np.float16, pooled=pooled, layernorm=layernorm)
+    errs = {k: hp.scaled_err(res[k], ref16[k], scales[k]) for k in ("dWg", "dbg", "domega")}
+    print(where, "gate grads vs un-cancelled scale", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
     bad = {k: v for k, v in errs.items() if not v < GATE_NOISE_TOL}
     assert not bad, (where, bad)
 
@@ -99,25 +108,27 @@ def test_small_shapes_forward_backward(shape, dtype):
     _check_all(res, ref, TOL[dtype], names=names, where=f"{shape} {dtype}")
 
 
+# noise=True: seeded random inputs on which the gate-parameter gradients sit at their noise floor
+# (measured plain relative errors of dW_g / d omega in the comment; see _check_mfma)
 MFMA_SHAPES = [
-    dict(B=1, H=1, n=64, d=64, L=6, m=128),       # one Haar block, one wave active
+    dict(B=1, H=1, n=64, d=64, L=6, m=128, noise=True),       # one Haar block, one wave active  (1.4e-2 / 3.0e-2)
     dict(B=2, H=2, n=320, d=64, L=6, m=256),      # 5 blocks: last workgroup partly idle
     dict(B=1, H=3, n=1024, d=64, L=3, m=384),     # three feature blocks of 128
-    dict(B=1, H=2, n=704, d=64, L=0, m=128),      # no wavelet levels
-    dict(B=1, H=2, n=640, d=64, L=0, m=256),      # no wavelet levels, 256 features per pass
-    dict(B=2, H=1, n=4096, d=64, L=5, m=512),     # two operand chunks in the rows kernel
-    dict(B=1, H=2, n=2560, d=64, L=1, m=256),
-    dict(B=1, H=1, n=64, d=128, L=6, m=128),      # head dimension 128: column halves split over waves
+    dict(B=1, H=2, n=704, d=64, L=0, m=128, noise=True),      # no wavelet levels (dF_0 is an eps-order remainder)
+    dict(B=1, H=2, n=640, d=64, L=0, m=256, noise=True),      # no wavelet levels, 256 features per pass
+    dict(B=2, H=1, n=4096, d=64, L=5, m=512, noise=True),     # two operand chunks in the rows kernel  (9.8e-3 / 6.0e-2)
+    dict(B=1, H=2, n=2560, d=64, L=1, m=256, noise=True),     # (1.3e-2 / 2.3e-2)
+    dict(B=1, H=1, n=64, d=128, L=6, m=128, noise=True),      # head dimension 128  (3.3e-3 / 2.6e-2)
     dict(B=2, H=2, n=832, d=128, L=6, m=512),     # 13 blocks, four operand chunks
     dict(B=1, H=2, n=1536, d=128, L=4, m=256),
-    dict(B=1, H=1, n=256, d=64, L=4, m=4096),     # maximum feature count: 16 operand chunks per row group
+    dict(B=1, H=1, n=256, d=64, L=4, m=4096, noise=True),     # maximum feature count: 16 operand chunks per row group  (7.0e-2 / 1.2e-1)
     dict(B=6, H=8, n=128, d=64, L=5, m=128),      # 48 slices of two blocks: more workgroups than row groups
-    dict(B=33, H=31, n=64, d=64, L=4, m=128),     # 1023 slices, the most the library takes
+    dict(B=33, H=31, n=64, d=64, L=4, m=128, noise=None),     # 1023 slices, the most the library takes
     # sequence lengths that are not multiples of the 64-row block: the last block is partial
     dict(B=2, H=2, n=1000, d=64, L=6, m=256),     # 15 full blocks + 40 rows
     dict(B=1, H=2, n=100, d=64, L=5, m=128),      # one full block + 36 rows
-    dict(B=1, H=1, n=40, d=64, L=3, m=128),       # less than one block
-    dict(B=1, H=2, n=203, d=128, L=6, m=128),     # head dimension 128, 3 blocks + 11 rows
+    dict(B=1, H=1, n=40, d=64, L=3, m=128, noise=True),       # less than one block  (2.2e-1 / 6.0e-1)
+    dict(B=1, H=2, n=203, d=128, L=6, m=128, noise=True),     # head dimension 128, 3 blocks + 11 rows  (1.2e-2 / 4.6e-2)
 ]
 
 
@@ -126,13 +137,15 @@ def test_mfma_path_shapes(shape):
     """bf16 shapes that run on the MFMA path (checked through wersa_selected_path)."""
     import torch
     from paper_2507_08637_amd import binding
+    shape = dict(shape)
+    noise = shape.pop("noise", False)
     cfg = dict(shape, dtype="bf16", flavour="plain", seed_base=555, q_mean=0.5)
     probe = torch.empty(cfg["B"], cfg["H"], cfg["n"], cfg["d"], dtype=torch.bfloat16, device="cuda")
     assert binding.wersa_path_name(binding.make_desc(probe, cfg["L"], cfg["m"])) == "mfma"
     p = workloads.make_inputs(**cfg)
     res = hp.gpu_forward_backward(p, cfg)
     ref = hp.oracle_backward(p, cfg)
-    _check_mfma(res, ref, p, cfg, where=f"mfma {shape}")
+    _check_mfma(res, ref, p, cfg, where=f"mfma {shape}", noise_limited=noise)
     fwd = hp.oracle_forward(p, cfg)
     sl = cfg["B"] * cfg["H"]
     for name in ("qbar", "s", "F", "S", "z", "D"):
@@ -141,21 +154,83 @@ def test_mfma_path_shapes(shape):
         assert e < 2e-2, (name, e)
 
 
-def test_mfma_gate_gradients_with_signal():
-    """Gate-parameter gradients at the strict tolerance when they are well above the noise floor:
-    Q, K, V share a low-frequency component and the loss is 0.5 ||O - T||^2 with a phase-shifted
-    target T, so dF is a coherent sum (|dF_i| is 6 to 80 times its un-cancelled statistical scale)."""
-    cfg = dict(B=1, H=2, n=2048, d=64, L=4, m=256, dtype="bf16", flavour="smooth", seed_base=777)
+def _signal_problem(cfg, eps=1e-6, pooled=False, layernorm=False, separate_omega=False):
+    """A workload on which the gate-parameter gradients are coherent sums: Q, K, V share a
+    low-frequency component and the loss is 0.5 ||O - T||^2 with a phase-shifted target T, so that
+    dO = O - T (O from the oracle's forward)."""
     p = workloads.make_inputs(**cfg)
-    O = hp.oracle_forward(p, cfg, keep=("O",))["O"]
+    if separate_omega:
+        omk = np.random.default_rng(3199).standard_normal(p["Omega"].shape, dtype=np.float32)
+        p["OmegaK"] = workloads.round_to_bf16(omk)
+    if pooled:
+        from oracle import wersa_oracle as wo
+        O = wo.forward(p["Q"], p["K"], p["V"], p["Omega"], float(p["sigma"]), p["Wg"], p["bg"], p["omega"],
+                       cfg["L"], eps=eps, pooled=True, keep=("O",))["O"]
+    else:
+        O = hp.oracle_forward(p, cfg, eps=eps, keep=("O",), layernorm=layernorm)["O"]
     t = np.arange(cfg["n"])
     p["dO"] = workloads.round_to_bf16((O - np.cos(2 * np.pi * t / 256.0)[None, None, :, None]).astype(np.float32))
-    res = hp.gpu_forward_backward(p, cfg)
-    ref = hp.oracle_backward(p, cfg)
-    scales = hp.gate_grad_scales(p, cfg)
+    return p
+
+
+SIGNAL_CASES = {
+    # one per kernel variant of the MFMA path (all at the plain 2e-2 on every output)
+    "d64_m256_dv_inside": (dict(B=1, H=2, n=2048, d=64, L=4, m=256), {}),
+    "d64_m128": (dict(B=1, H=2, n=2048, d=64, L=5, m=128), {}),
+    "d64_m512_two_chunks": (dict(B=1, H=2, n=2048, d=64, L=5, m=512), {}),
+    "d64_one_level": (dict(B=1, H=2, n=2560, d=64, L=1, m=256), {}),
+    "d128": (dict(B=1, H=2, n=2048, d=128, L=5, m=256), {}),
+    "d128_m512": (dict(B=1, H=2, n=2048, d=128, L=6, m=512), {}),
+    "ragged": (dict(B=1, H=2, n=2000, d=64, L=6, m=256), {}),
+    "ragged_d128": (dict(B=1, H=2, n=1992, d=128, L=6, m=128), {}),
+    "deep": (dict(B=1, H=2, n=4096, d=64, L=9, m=256), {}),
+    "deep_d128": (dict(B=1, H=2, n=4096, d=128, L=8, m=128), {}),
+    "deep_ragged": (dict(B=1, H=2, n=4000, d=64, L=8, m=256), {}),
+    "layernorm": (dict(B=1, H=2, n=2048, d=64, L=4, m=256, flavour="smooth_cols"), dict(flags=8, eps=1e-3, layernorm=True)),
+    "pooled_gate": (dict(B=2, H=3, n=2048, d=64, L=4, m=256), dict(flags=4, pooled=True)),
+    "separate_omega": (dict(B=1, H=2, n=2048, d=64, L=4, m=256), dict(flags=2, separate_omega=True)),
+}
+
+
+@pytest.mark.parametrize("case", sorted(SIGNAL_CASES))
+def test_mfma_gate_gradients_with_signal(case):
+    """Gate-parameter gradients at the plain tolerance on every kernel variant of the MFMA path,
+    on workloads where they are well above the noise floor (see _signal_problem)."""
+    shape, kw = SIGNAL_CASES[case]
+    flags, eps = kw.get("flags", 0), kw.get("eps", 1e-6)
+    pooled, layernorm = kw.get("pooled", False), kw.get("layernorm", False)
+    cfg = dict(dict(flavour="smooth"), **shape, dtype="bf16", seed_base=777)
+    p = _signal_problem(cfg, eps=eps, pooled=pooled, layernorm=layernorm, separate_omega=kw.get("separate_omega", False))
+    res = hp.gpu_forward_backward(p, cfg, flags=flags, eps=eps)
+    ref = hp.oracle_backward(p, cfg, eps=eps, pooled=pooled, layernorm=layernorm)
+    scales = hp.gate_grad_scales(p, cfg, eps=eps, layernorm=layernorm)   # (per-head gates: the same order when pooled)
     signal = float(np.linalg.norm(ref["domega"]) / np.linalg.norm(scales["domega"]))
-    assert signal > 5.0, signal     # the premise of this test
-    _check_all(res, ref, 2e-2, where=f"mfma, gate gradients with signal (x{signal:.0f} the noise scale)")
+    assert signal > 3.0, signal     # the premise of this test: |dF| well above its un-cancelled statistical scale
+    _check_all(res, ref, 2e-2, where=f"mfma, gate gradients with signal: {case} (x{signal:.0f} the noise scale)")
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_mfma_dsigma_against_the_oracle(d):
+    """d sigma of the default normaliser on the MFMA path (Section 3.1 step 7's bandwidth reaches
+    the output only through eps, so eps = 1e-2 makes the gradient measurable): the kernels' closed
+    form (2 eps / sigma) sum_t dD_t against the oracle's term-by-term chain rule, on a workload
+    where the sum is coherent; and zero below the bandwidth floor."""
+    eps = 1e-2
+    cfg = dict(B=1, H=2, n=2048, d=d, L=4, m=256, dtype="bf16", flavour="smooth", seed_base=777)
+    p = _signal_problem(cfg, eps=eps)
+    p["sigma"] = np.float32(1.5)
+    p = dict(p)
+    res = hp.gpu_forward_backward(p, cfg, eps=eps)
+    ref = hp.oracle_backward(p, cfg, eps=eps)
+    _check_all(res, ref, 2e-2, where=f"mfma d sigma, d={d}")
+    got = float(res["dsigma"].cpu()[0])
+    print(f"d sigma d={d}: gpu {got:.6e} oracle {ref['dsigma']:.6e}", flush=True)
+    assert abs(ref["dsigma"]) > 1e-3                                    # the premise: measurable
+    assert abs(got - ref["dsigma"]) < 2e-2 * abs(ref["dsigma"]), (got, ref["dsigma"])
+    res2 = hp.gpu_forward_backward(p, cfg, eps=eps, bw_floor=2.0)
+    ref2 = hp.oracle_backward(p, cfg, eps=eps, bw_floor=2.0)
+    assert float(res2["dsigma"].cpu()[0]) == 0.0 and ref2["dsigma"] == 0.0
+    _check_all(res2, ref2, 2e-2, names=("O", "dQ", "dK", "dV"), where="mfma, sigma below the floor")
 
 
 def test_mfma_and_generic_paths_agree():
@@ -168,7 +243,7 @@ def test_mfma_and_generic_paths_agree():
     res = hp.gpu_forward_backward(p, cfg, flags=binding.WERSA_FLAG_GENERIC_PATH)
     _check_all(res, ref, 2e-2, where="generic path")
     res = hp.gpu_forward_backward(p, cfg, flags=0)
-    _check_mfma(res, ref, p, cfg, where="mfma path")
+    _check_mfma(res, ref, p, cfg, where="mfma path", noise_limited=None)
 
 
 def test_mfma_strided_layout():
@@ -176,7 +251,7 @@ def test_mfma_strided_layout():
     p = workloads.make_inputs(**cfg)
     res = hp.gpu_forward_backward(p, cfg, layout="bnhd")
     ref = hp.oracle_backward(p, cfg)
-    _check_mfma(res, ref, p, cfg, where="mfma strided")
+    _check_mfma(res, ref, p, cfg, where="mfma strided", noise_limited=None)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -308,7 +383,7 @@ def test_separate_query_and_key_random_matrices(path):
     shared = hp.oracle_backward({k: v for k, v in p.items() if k != "OmegaK"}, cfg)
     assert hp.rel_err(res["O"], shared["O"]) > 0.1   # the key-side matrix is really the second one
     if path == "mfma":
-        _check_mfma(res, ref, p, cfg, where="separate omega mfma")
+        _check_mfma(res, ref, p, cfg, where="separate omega mfma", noise_limited=None)
     else:
         _check_all(res, ref, TOL[dtype], where=f"separate omega {path}")
 
@@ -331,12 +406,8 @@ def test_gate_pooled_over_heads(path):
     per_head = hp.oracle_backward(p, cfg)
     assert hp.rel_err(res["O"], per_head["O"]) > 1e-2                # and it is not the per-head gate
     if path == "mfma":
-        _check_all(res, ref, 2e-2, names=("O", "dQ", "dK", "dV"), where="pooled gate mfma")
-        ref16 = hp.oracle_backward(p, cfg, proj_dtype=np.float16, pooled=True)
-        scales = hp.gate_grad_scales(p, cfg)   # per-head magnitudes: the same order for the pooled sums
-        errs = {k: hp.scaled_err(res[k], ref16[k], scales[k]) for k in ("dWg", "dbg", "domega")}
-        print("pooled gate mfma, gate grads vs un-cancelled scale", errs, flush=True)
-        assert all(v < GATE_NOISE_TOL for v in errs.values()), errs
+        # (un-cancelled scales are the per-head magnitudes: the same order for the pooled sums)
+        _check_mfma(res, ref, p, cfg, where="pooled gate mfma", noise_limited=None, pooled=True)
     else:
         _check_all(res, ref, TOL[dtype], where=f"pooled gate {path}")
 
@@ -365,12 +436,7 @@ def test_layernorm_output_stage(path):
     if path == "mfma":
         probe = torch.empty(cfg["B"], cfg["H"], cfg["n"], cfg["d"], dtype=torch.bfloat16, device="cuda")
         assert binding.wersa_path_name(binding.make_desc(probe, cfg["L"], cfg["m"], eps, 1e-6, flags)) == "mfma"
-        _check_all(res, ref, 2e-2, names=("O", "dQ", "dK", "dV"), where="layernorm mfma")
-        ref16 = hp.oracle_backward(p, cfg, eps=eps, proj_dtype=np.float16, layernorm=True)
-        scales = hp.gate_grad_scales(p, cfg, eps=eps, layernorm=True)
-        errs = {k: hp.scaled_err(res[k], ref16[k], scales[k]) for k in ("dWg", "dbg", "domega")}
-        print("layernorm mfma, gate grads vs un-cancelled scale", errs, flush=True)
-        assert all(v < GATE_NOISE_TOL for v in errs.values()), errs
+        _check_mfma(res, ref, p, cfg, where="layernorm mfma", noise_limited=None, eps=eps, layernorm=True)
         assert abs(float(res["dsigma"].cpu()) - ref["dsigma"]) < 5e-2 * abs(ref["dsigma"])
     else:
         _check_all(res, ref, TOL[dtype], where=f"layernorm {path}")
@@ -393,13 +459,9 @@ def test_layernorm_output_stage_mfma_shapes(shape):
     assert binding.wersa_path_name(binding.make_desc(probe, cfg["L"], cfg["m"], eps, 1e-6, 8)) == "mfma"
     res = hp.gpu_forward_backward(p, cfg, eps=eps, flags=8)
     ref = hp.oracle_backward(p, cfg, eps=eps, layernorm=True)
-    _check_all(res, ref, 2e-2, names=("O", "dQ", "dK", "dV"), where=f"layernorm mfma {shape}")
+    _check_mfma(res, ref, p, cfg, where=f"layernorm mfma {shape}", noise_limited=None, eps=eps, layernorm=True)
     fwd = hp.oracle_forward(p, cfg, eps=eps, keep=("D",), layernorm=True)
     assert hp.rel_err(res["saved"]["D"].view(cfg["B"], cfg["H"], cfg["n"]), fwd["D"]) < 2e-2
-    ref16 = hp.oracle_backward(p, cfg, eps=eps, proj_dtype=np.float16, layernorm=True)
-    scales = hp.gate_grad_scales(p, cfg, eps=eps, layernorm=True)
-    errs = {k: hp.scaled_err(res[k], ref16[k], scales[k]) for k in ("dWg", "dbg", "domega")}
-    assert all(v < GATE_NOISE_TOL for v in errs.values()), errs
     assert abs(float(res["dsigma"].cpu()) - ref["dsigma"]) < 5e-2 * abs(ref["dsigma"])
 
 
@@ -425,7 +487,7 @@ def test_deep_transform_on_the_mfma_path(shape):
     p = workloads.make_inputs(**cfg)
     res = hp.gpu_forward_backward(p, cfg)
     ref = hp.oracle_backward(p, cfg)
-    _check_mfma(res, ref, p, cfg, where=f"deep mfma {shape}")
+    _check_mfma(res, ref, p, cfg, where=f"deep mfma {shape}", noise_limited=None)
     fwd = hp.oracle_forward(p, cfg)
     sl = cfg["B"] * cfg["H"]
     for name in ("qbar", "s", "F", "S", "z", "D"):
@@ -523,28 +585,46 @@ def test_config2_bf16_forward():
     assert hp.rel_err(res["O"], ref["O"]) < 2e-2
 
 
-def _sampled_slices_check(idx, slices, reduced):
-    """Full-size GPU run; the oracle recomputes a sample of (b, h) slices in full (slices are
-    independent for O, dQ, dK, dV).  Parameter gradients, which sum over slices, are checked on
-    a run restricted to `reduced` batch/heads with the same n, d, m, L."""
+# Bounds on the per-block and per-element error figures at full size (helpers.err_stats), next to the
+# 2e-2 Frobenius bar.  O and dV are smooth functions of the inputs: every 64-row block and every
+# element must sit near the bf16 output rounding (2^-9).  dQ and dK contain the ReLU derivative, a
+# binary decision: where a pre-activation is within fp16 rounding of zero the kernel and float64
+# decide differently and that row's gradient moves by one feature's whole contribution, so single
+# rows and the blocks that hold them carry errors well above the tensor's average (measured: worst
+# block 4e-2 .. 6e-2, largest element error 4e-2 .. 1.1e-1 of the largest element); the bounds
+# below leave a factor of two over that and still reject a wholly wrong block (relative error 1)
+# or a wrong element of the size of the largest.
+BLOCK_BOUNDS = dict(O=dict(worst_block=1e-2, maxabs=1e-2), dV=dict(worst_block=1e-2, maxabs=1e-2),
+                    dQ=dict(worst_block=0.15, maxabs=0.25), dK=dict(worst_block=0.15, maxabs=0.25))
+
+
+def _check_blocks(res, ref, where):
+    for name, bounds in BLOCK_BOUNDS.items():
+        st = hp.err_stats(res[name], ref[name])
+        print(where, name, {k: f"{v:.2e}" for k, v in st.items()}, flush=True)
+        for k, limit in bounds.items():
+            assert st[k] < limit, (where, name, k, st[k])
+
+
+def _full_size_check(idx):
+    """Full-size GPU run against the oracle on EVERY (batch, head) slice: the plain 2e-2 on O, dQ,
+    dK, dV and on the gate-parameter gradients, which sum over all slices, plus the per-block and
+    per-element bounds above."""
     cfg, p = workloads.make_config(idx)
     res = hp.gpu_forward_backward(p, cfg)
-    ref = hp.oracle_backward(p, cfg, slices=slices)
-    for (b, h) in slices:
-        for name in ("O", "dQ", "dK", "dV"):
-            e = hp.rel_err(res[name][b, h], ref[name][b, h])
-            print(f"config{idx} slice {(b, h)} {name} {e:.2e}", flush=True)
-            assert e < 2e-2, (name, b, h, e)
-    del res, ref, p
-    cfg2, p2 = workloads.make_config(idx, **reduced)
-    res2 = hp.gpu_forward_backward(p2, cfg2)
-    ref2 = hp.oracle_backward(p2, cfg2)
-    _check_mfma(res2, ref2, p2, cfg2, where=f"config{idx} reduced {reduced}")
+    ref = hp.oracle_backward(p, cfg)
+    _check_all(res, ref, 2e-2, where=f"config{idx}")
+    _check_blocks(res, ref, f"config{idx}")
+    for b in range(cfg["B"]):
+        for h in range(cfg["H"]):
+            for name in ("O", "dQ", "dK", "dV"):
+                e = hp.rel_err(res[name][b, h], ref[name][b, h])
+                assert e < 2e-2, (name, b, h, e)
 
 
 def test_config3_spikes_forward_backward():
-    _sampled_slices_check(3, [(0, 0), (3, 11)], dict(B=1, H=3))
+    _full_size_check(3)
 
 
 def test_config4_long_sequence_forward_backward():
-    _sampled_slices_check(4, [(0, 5)], dict(B=1, H=2))
+    _full_size_check(4)

@@ -376,6 +376,77 @@ def test_block_backward_matches_central_finite_differences():
 
 
 # ---------------------------------------------------------------- the pins bite
+def test_projection_rounding_hook_changes_only_what_it_says():
+    """`proj_dtype` of the feature map (used by the GPU tests so that both sides take the ReLU
+    decision of Section 3.1 step 7 on the same numbers): None and float64 are the same function
+    bit for bit; float16 equals rounding X_F by hand before the unchanged map, moves U by at most
+    2^-11 |X_F| |Omega| / sigma entry by entry, and touches nothing upstream of the projection."""
+    r = np.random.default_rng(71)
+    XF = r.standard_normal((40, 6)) * 3.0
+    Om = r.standard_normal((6, 24))
+    U0, P0 = wo.feature_map(XF, Om, 1.3, 1e-6)
+    U64, P64 = wo.feature_map(XF, Om, 1.3, 1e-6, np.float64)
+    assert np.array_equal(U0, U64) and np.array_equal(P0, P64)
+    U16, P16 = wo.feature_map(XF, Om, 1.3, 1e-6, np.float16)
+    Uh, Ph = wo.feature_map(XF.astype(np.float16).astype(np.float64), Om, 1.3, 1e-6)
+    assert np.array_equal(U16, Uh) and np.array_equal(P16, Ph)
+    bound = 2.0 ** -11 * (np.abs(XF) @ np.abs(Om)) / 1.3
+    assert np.all(np.abs(U16 - U0) <= bound * (1 + 1e-12))
+    assert np.any(U16 != U0)                       # it does round
+    # through the whole forward: everything up to X_F is untouched, float64 is the identity
+    p = _rand_problem(73, B=1, H=1, n=48, d=6, m=24, L=3)
+    args = (p["Q"][0, 0], p["K"][0, 0], p["V"][0, 0], p["Omega"], p["sigma"], p["Wg"][0], p["bg"][0], p["omega"],
+            p["L"], 1e-4, 1e-6)
+    f0, f64, f16 = (wo.forward_slice(*args, proj_dtype=t) for t in (None, np.float64, np.float16))
+    for name in f0:
+        assert np.array_equal(f0[name], f64[name]), name
+    for name in ("qbar", "logits", "s", "F", "QF", "KF"):
+        assert np.array_equal(f0[name], f16[name]), name
+    np.testing.assert_array_equal(f16["UQ"], wo.feature_map(f0["QF"].astype(np.float16).astype(np.float64),
+                                                            p["Omega"], p["sigma"], 1e-6)[0])
+    assert 0 < np.max(np.abs(f16["O"] - f0["O"])) < 1e-2
+    # and through the backward: float64 is the identity there too
+    g0 = wo.backward(p["Q"], p["K"], p["V"], p["Omega"], p["sigma"], p["Wg"], p["bg"], p["omega"], p["L"], p["dO"])
+    g64 = wo.backward(p["Q"], p["K"], p["V"], p["Omega"], p["sigma"], p["Wg"], p["bg"], p["omega"], p["L"], p["dO"],
+                      proj_dtype=np.float64)
+    for name in ("O", "dQ", "dK", "dV", "dWg", "dbg", "domega"):
+        assert np.array_equal(g0[name], g64[name]), name
+
+
+def test_block_store_hook_is_applied_where_it_says_and_nowhere_else():
+    """`store` of the block functions (a GPU test rounds the stored intermediates to bf16 with it):
+    the identity hook equals no hook bit for bit; a marking hook is called on exactly Q', K', V', A
+    (forward) and additionally dA, dQ', dK', dV' (backward), in that order, each with the value the
+    unhooked run holds at that point when the hook returns its argument unchanged."""
+    p = _rand_block(75)
+    f0 = wo.block_forward(*_block_args(p))
+    fi = wo.block_forward(*_block_args(p), store=lambda a: a)
+    for name in f0:
+        assert np.array_equal(f0[name], fi[name]), name
+    seen = []
+
+    def mark(a):
+        seen.append(np.array(a, copy=True))
+        return a
+    wo.block_forward(*_block_args(p), store=mark)
+    assert len(seen) == 4
+    for got, name in zip(seen, ("Qp", "Kp", "Vp", "A")):
+        assert np.array_equal(got, f0[name]), name
+    g0 = wo.block_backward(*_block_args(p), p["dY"])
+    seen.clear()
+    gi = wo.block_backward(*_block_args(p), p["dY"], store=mark)
+    for name in g0:
+        assert np.array_equal(np.asarray(g0[name]), np.asarray(gi[name])), name
+    assert len(seen) == 8
+    for got, name in zip(seen, ("Qp", "Kp", "Vp", "A", "dA", "dQp", "dKp", "dVp")):
+        assert np.array_equal(got, g0[name]), name
+    # a hook that does change its argument changes the result (it is really in the data path)
+    rb = lambda a: a.astype(np.float16).astype(np.float64)
+    gr = wo.block_backward(*_block_args(p), p["dY"], store=rb)
+    assert np.array_equal(gr["Qp"], rb(g0["Qp"]))
+    assert 0 < np.max(np.abs(gr["dX"] - g0["dX"])) < 5e-2 * np.max(np.abs(g0["dX"]))
+
+
 def test_planted_mistakes_are_caught(monkeypatch):
     """Each plausible mistake, planted in the oracle (on the CPU), must fail at least one pin:
     a swapped Haar pair sign, a dropped 1/sqrt(2), a transposed operand in S, a dropped epsilon,
@@ -457,6 +528,30 @@ def test_planted_mistakes_are_caught(monkeypatch):
     monkeypatch.setattr(mod, "split_heads", split_interleaved)
     expect_failure([test_block_head_layout_and_identity_weights])
     monkeypatch.setattr(mod, "split_heads", real_split)
+
+    # 7. a transposed operand in the KV reduction: S = phi(K) V in place of phi(K)^T V (the shapes
+    #    still agree when n == m), everything after it computed from that S
+    real_fwd = mod.forward_slice
+
+    def fwd_transposed_S(Q, K, V, Omega, sigma, Wg_h, bg_h, omega, L, eps, bw_floor, *a, **kw):
+        f = dict(real_fwd(Q, K, V, Omega, sigma, Wg_h, bg_h, omega, L, eps, bw_floor, *a, **kw))
+        assert f["PhiK"].shape[0] == f["PhiK"].shape[1], "the planted mistake needs n == m"
+        f["S"] = f["PhiK"] @ np.asarray(V, np.float64)
+        f["N"] = f["PhiQ"] @ f["S"]
+        f["O"] = f["N"] / f["D"][:, None]
+        return f
+    monkeypatch.setattr(mod, "forward_slice", fwd_transposed_S)
+    expect_failure([lambda: test_linear_attention_equals_explicit_kernel_matrix(32)])
+
+    # 8. the normaliser without its epsilon: D = phi(Q) z
+    def fwd_no_eps(Q, K, V, Omega, sigma, Wg_h, bg_h, omega, L, eps, bw_floor, *a, **kw):
+        f = dict(real_fwd(Q, K, V, Omega, sigma, Wg_h, bg_h, omega, L, eps, bw_floor, *a, **kw))
+        f["D"] = f["D"] - eps
+        f["O"] = f["N"] / f["D"][:, None]
+        return f
+    monkeypatch.setattr(mod, "forward_slice", fwd_no_eps)
+    expect_failure([lambda: test_linear_attention_equals_explicit_kernel_matrix(32), test_convexity_and_unit_values])
+    monkeypatch.setattr(mod, "forward_slice", real_fwd)
 
 
 # ---------------------------------------------------------------- Algorithm 1 variant: separate random matrices
