@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 
 BLOCK_SHAPES = [
     dict(B=1, H=4, n=256, d=64, L=4, m=128),     # hidden 256: one tile in each direction
-    dict(B=2, H=4, n=384, d=128, L=6, m=256),    # hidden 512, 768 tokens: 3 x 2 tiles, head dim 128
+    dict(B=2, H=4, n=384, d=128, L=6, m=256, noise=True),    # hidden 512, 768 tokens: 3 x 2 tiles, head dim 128 (plain d omega 2.1e-2)
     dict(B=3, H=8, n=256, d=64, L=3, m=128),     # hidden 512, weight-gradient split over tokens
 ]
 
@@ -54,6 +54,7 @@ def _oracle_block(p, cfg, proj_dtype=None):
 def test_block_forward_backward(shape):
     from oracle import wersa_oracle as wo
     cfg = dict(shape)
+    noise = cfg.pop("noise", False)
     p = workloads.make_block_inputs(**cfg, seed_base=9100, x_mean=0.0)
     res = _gpu_block(p, cfg)
     ref = _oracle_block(p, cfg)
@@ -76,7 +77,8 @@ def test_block_forward_backward(shape):
                   sigma=p["sigma"])
     plain = {k: hp.rel_err(res[k], ref[k]) for k in ("dWg", "dbg", "domega")}
     print(shape, "gate grads, plain relative", {k: f"{v:.2e}" for k, v in plain.items()}, flush=True)
-    if all(v < 2e-2 for v in plain.values()):
+    if not noise:   # the plain bar, except where the sums sit at their noise floor on these small random inputs
+        assert all(v < 2e-2 for v in plain.values()), plain
         return
     scales = hp.gate_grad_scales(core_p, dict(cfg, d=cfg["d"]))
     gerr = {k: hp.scaled_err(res[k], ref16[k], scales[k]) for k in ("dWg", "dbg", "domega")}

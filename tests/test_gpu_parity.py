@@ -36,16 +36,14 @@ def _check_mfma(res, ref, p, cfg, where="", noise_limited=False, eps=1e-6, poole
     (helpers.gate_grad_scales), both sides taking the ReLU decision at the kernel's precision
     (X_F rounded to fp16 before the projection); the plain relative error is printed.  Every kernel
     variant that has such a case also has a signal-carrying case held to the plain 2e-2
-    (test_mfma_gate_gradients_with_signal).  noise_limited=None accepts either criterion."""
+    (test_mfma_gate_gradients_with_signal)."""
     _check_all(res, ref, 2e-2, names=("O", "dQ", "dK", "dV"), where=where)
     plain = {k: hp.rel_err(res[k], ref[k]) for k in ("dWg", "dbg", "domega")}
     strict_ok = all(v < 2e-2 for v in plain.values())
     print(where, "gate grads, plain relative", {k: f"{v:.2e}" for k, v in plain.items()},
           "STRICT-OK" if strict_ok else "ABOVE-2e-2", flush=True)
-    if noise_limited is False:
+    if not noise_limited:
         assert strict_ok, (where, plain)
-        return
-    if noise_limited is None and strict_ok:
         return
     scales = hp.gate_grad_scales(p, cfg, eps=eps, layernorm=layernorm)
     ref16 = hp.oracle_backward(p, cfg, eps=eps, proj_dtype=np.float16, pooled=pooled, layernorm=layernorm)
@@ -123,7 +121,7 @@ MFMA_SHAPES = [
     dict(B=1, H=2, n=1536, d=128, L=4, m=256),
     dict(B=1, H=1, n=256, d=64, L=4, m=4096, noise=True),     # maximum feature count: 16 operand chunks per row group  (7.0e-2 / 1.2e-1)
     dict(B=6, H=8, n=128, d=64, L=5, m=128),      # 48 slices of two blocks: more workgroups than row groups
-    dict(B=33, H=31, n=64, d=64, L=4, m=128, noise=None),     # 1023 slices, the most the library takes
+    dict(B=33, H=31, n=64, d=64, L=4, m=128),     # 1023 slices, the most the library takes
     # sequence lengths that are not multiples of the 64-row block: the last block is partial
     dict(B=2, H=2, n=1000, d=64, L=6, m=256),     # 15 full blocks + 40 rows
     dict(B=1, H=2, n=100, d=64, L=5, m=128),      # one full block + 36 rows
@@ -157,7 +155,9 @@ def test_mfma_path_shapes(shape):
 def _signal_problem(cfg, eps=1e-6, pooled=False, layernorm=False, separate_omega=False):
     """A workload on which the gate-parameter gradients are coherent sums: Q, K, V share a
     low-frequency component and the loss is 0.5 ||O - T||^2 with a phase-shifted target T, so that
-    dO = O - T (O from the oracle's forward)."""
+    dO = O - T (O from the oracle's forward).  With the LayerNorm output stage the target also
+    varies over the columns: a target that is constant along a row is orthogonal to every
+    normalised row, and the loss would have no gradient but rounding noise."""
     p = workloads.make_inputs(**cfg)
     if separate_omega:
         omk = np.random.default_rng(3199).standard_normal(p["Omega"].shape, dtype=np.float32)
@@ -169,7 +169,10 @@ def _signal_problem(cfg, eps=1e-6, pooled=False, layernorm=False, separate_omega
     else:
         O = hp.oracle_forward(p, cfg, eps=eps, keep=("O",), layernorm=layernorm)["O"]
     t = np.arange(cfg["n"])
-    p["dO"] = workloads.round_to_bf16((O - np.cos(2 * np.pi * t / 256.0)[None, None, :, None]).astype(np.float32))
+    T = np.cos(2 * np.pi * t / 256.0)[None, None, :, None]
+    if layernorm:
+        T = 1.5 * T * np.sin(2 * np.pi * np.arange(cfg["d"]) / cfg["d"] + 0.7)[None, None, None, :]
+    p["dO"] = workloads.round_to_bf16((O - T).astype(np.float32))
     return p
 
 
@@ -186,9 +189,12 @@ SIGNAL_CASES = {
     "deep": (dict(B=1, H=2, n=4096, d=64, L=9, m=256), {}),
     "deep_d128": (dict(B=1, H=2, n=4096, d=128, L=8, m=128), {}),
     "deep_ragged": (dict(B=1, H=2, n=4000, d=64, L=8, m=256), {}),
-    "layernorm": (dict(B=1, H=2, n=2048, d=64, L=4, m=256, flavour="smooth_cols"), dict(flags=8, eps=1e-3, layernorm=True)),
+    # (min_signal: with the LayerNorm output stage, and with unrelated feature maps for Q and K, the
+    # shared component gives a smaller coherent part: about 2 x and 0.5 x the un-cancelled scale)
+    "layernorm": (dict(B=1, H=2, n=2048, d=64, L=4, m=256, flavour="smooth_cols"),
+                  dict(flags=8, eps=1e-3, layernorm=True, min_signal=1.0)),
     "pooled_gate": (dict(B=2, H=3, n=2048, d=64, L=4, m=256), dict(flags=4, pooled=True)),
-    "separate_omega": (dict(B=1, H=2, n=2048, d=64, L=4, m=256), dict(flags=2, separate_omega=True)),
+    "separate_omega": (dict(B=1, H=2, n=2048, d=64, L=4, m=256), dict(flags=2, separate_omega=True, min_signal=0.3)),
 }
 
 
@@ -205,7 +211,8 @@ def test_mfma_gate_gradients_with_signal(case):
     ref = hp.oracle_backward(p, cfg, eps=eps, pooled=pooled, layernorm=layernorm)
     scales = hp.gate_grad_scales(p, cfg, eps=eps, layernorm=layernorm)   # (per-head gates: the same order when pooled)
     signal = float(np.linalg.norm(ref["domega"]) / np.linalg.norm(scales["domega"]))
-    assert signal > 3.0, signal     # the premise of this test: |dF| well above its un-cancelled statistical scale
+    # the premise of this test: |dF| well above the error a 2e-2 tensor can leave in a cancelling sum
+    assert signal > kw.get("min_signal", 3.0), signal
     _check_all(res, ref, 2e-2, where=f"mfma, gate gradients with signal: {case} (x{signal:.0f} the noise scale)")
 
 
@@ -243,7 +250,7 @@ def test_mfma_and_generic_paths_agree():
     res = hp.gpu_forward_backward(p, cfg, flags=binding.WERSA_FLAG_GENERIC_PATH)
     _check_all(res, ref, 2e-2, where="generic path")
     res = hp.gpu_forward_backward(p, cfg, flags=0)
-    _check_mfma(res, ref, p, cfg, where="mfma path", noise_limited=None)
+    _check_mfma(res, ref, p, cfg, where="mfma path")
 
 
 def test_mfma_strided_layout():
@@ -251,7 +258,7 @@ def test_mfma_strided_layout():
     p = workloads.make_inputs(**cfg)
     res = hp.gpu_forward_backward(p, cfg, layout="bnhd")
     ref = hp.oracle_backward(p, cfg)
-    _check_mfma(res, ref, p, cfg, where="mfma strided", noise_limited=None)
+    _check_mfma(res, ref, p, cfg, where="mfma strided", noise_limited=True)   # n = 256, random: plain 2.0e-2 on db_g
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -383,7 +390,8 @@ def test_separate_query_and_key_random_matrices(path):
     shared = hp.oracle_backward({k: v for k, v in p.items() if k != "OmegaK"}, cfg)
     assert hp.rel_err(res["O"], shared["O"]) > 0.1   # the key-side matrix is really the second one
     if path == "mfma":
-        _check_mfma(res, ref, p, cfg, where="separate omega mfma", noise_limited=None)
+        # n = 256, random inputs: plain 1.1e-2 .. 1.6e-2 on dW_g, 2.1e-2 .. 3.2e-2 on d omega
+        _check_mfma(res, ref, p, cfg, where="separate omega mfma", noise_limited=True)
     else:
         _check_all(res, ref, TOL[dtype], where=f"separate omega {path}")
 
@@ -407,7 +415,8 @@ def test_gate_pooled_over_heads(path):
     assert hp.rel_err(res["O"], per_head["O"]) > 1e-2                # and it is not the per-head gate
     if path == "mfma":
         # (un-cancelled scales are the per-head magnitudes: the same order for the pooled sums)
-        _check_mfma(res, ref, p, cfg, where="pooled gate mfma", noise_limited=None, pooled=True)
+        # (128 features: plain 2.1e-2 on dW_g; 256 features: 7.7e-3)
+        _check_mfma(res, ref, p, cfg, where="pooled gate mfma", noise_limited=cfg["m"] == 128, pooled=True)
     else:
         _check_all(res, ref, TOL[dtype], where=f"pooled gate {path}")
 
@@ -436,22 +445,24 @@ def test_layernorm_output_stage(path):
     if path == "mfma":
         probe = torch.empty(cfg["B"], cfg["H"], cfg["n"], cfg["d"], dtype=torch.bfloat16, device="cuda")
         assert binding.wersa_path_name(binding.make_desc(probe, cfg["L"], cfg["m"], eps, 1e-6, flags)) == "mfma"
-        _check_mfma(res, ref, p, cfg, where="layernorm mfma", noise_limited=None, eps=eps, layernorm=True)
+        _check_mfma(res, ref, p, cfg, where="layernorm mfma", eps=eps, layernorm=True)
         assert abs(float(res["dsigma"].cpu()) - ref["dsigma"]) < 5e-2 * abs(ref["dsigma"])
     else:
         _check_all(res, ref, TOL[dtype], where=f"layernorm {path}")
         assert abs(float(res["dsigma"].cpu()) - ref["dsigma"]) < (1e-3 if dtype == "f32" else 2e-2) * abs(ref["dsigma"])
 
 
-@pytest.mark.parametrize("shape", [dict(B=1, H=2, n=1024, d=64, L=5, m=256),
+@pytest.mark.parametrize("shape", [dict(B=1, H=2, n=1024, d=64, L=5, m=256, noise=True),    # (plain d omega 2.8e-2)
                                    dict(B=2, H=1, n=832, d=128, L=6, m=256),
-                                   dict(B=1, H=2, n=1000, d=64, L=5, m=256),    # partial last block
+                                   dict(B=1, H=2, n=1000, d=64, L=5, m=256, noise=True),    # partial last block (2.2e-2)
                                    dict(B=1, H=2, n=1024, d=64, L=8, m=256)])   # transform deeper than one block
 def test_layernorm_output_stage_mfma_shapes(shape):
     """The LayerNorm output stage on the other MFMA kernel variants: 256-feature operand blocks
     (d = 64) and the head dimension 128."""
     import torch
     from paper_2507_08637_amd import binding
+    shape = dict(shape)
+    noise = shape.pop("noise", False)
     cfg = dict(shape, dtype="bf16", flavour="plain", seed_base=3600, q_mean=0.3)
     p = workloads.make_inputs(**cfg)
     eps = 1e-3
@@ -459,7 +470,7 @@ def test_layernorm_output_stage_mfma_shapes(shape):
     assert binding.wersa_path_name(binding.make_desc(probe, cfg["L"], cfg["m"], eps, 1e-6, 8)) == "mfma"
     res = hp.gpu_forward_backward(p, cfg, eps=eps, flags=8)
     ref = hp.oracle_backward(p, cfg, eps=eps, layernorm=True)
-    _check_mfma(res, ref, p, cfg, where=f"layernorm mfma {shape}", noise_limited=None, eps=eps, layernorm=True)
+    _check_mfma(res, ref, p, cfg, where=f"layernorm mfma {shape}", noise_limited=noise, eps=eps, layernorm=True)
     fwd = hp.oracle_forward(p, cfg, eps=eps, keep=("D",), layernorm=True)
     assert hp.rel_err(res["saved"]["D"].view(cfg["B"], cfg["H"], cfg["n"]), fwd["D"]) < 2e-2
     assert abs(float(res["dsigma"].cpu()) - ref["dsigma"]) < 5e-2 * abs(ref["dsigma"])
@@ -467,11 +478,11 @@ def test_layernorm_output_stage_mfma_shapes(shape):
 
 @pytest.mark.parametrize("shape", [dict(B=1, H=2, n=1024, d=64, L=8, m=256),      # 16 tiles, blocks of 4 tiles
                                    dict(B=2, H=1, n=4160, d=64, L=12, m=128),     # 65 tiles: one 4096-row block + one tile
-                                   dict(B=1, H=1, n=8192, d=64, L=13, m=256),     # one block of 128 tiles
+                                   dict(B=1, H=1, n=8192, d=64, L=13, m=256, noise=True),     # one block of 128 tiles (one slice, random: plain d omega 3.2e-2)
                                    dict(B=1, H=2, n=640, d=64, L=7, m=128),       # 10 tiles, pairs
                                    dict(B=1, H=2, n=1000, d=64, L=9, m=256),      # partial last tile: 15 tiles + 40 rows
-                                   dict(B=1, H=1, n=100, d=64, L=7, m=128),       # two tiles, the second partial
-                                   dict(B=1, H=1, n=2048, d=64, L=8, m=512),      # two passes of 256 features (dV inside the K-side kernel)
+                                   dict(B=1, H=1, n=100, d=64, L=7, m=128, noise=True),       # two tiles, the second partial (6.4e-2)
+                                   dict(B=1, H=1, n=2048, d=64, L=8, m=512, noise=True),      # two passes of 256 features (dV inside the K-side kernel) (2.7e-2)
                                    dict(B=1, H=2, n=1024, d=128, L=9, m=128),     # head dimension 128: stage A kernel takes the addends
                                    dict(B=2, H=1, n=4160, d=128, L=12, m=256),
                                    dict(B=1, H=1, n=1000, d=128, L=8, m=128)])    # ... with a partial last tile
@@ -481,13 +492,15 @@ def test_deep_transform_on_the_mfma_path(shape):
     backwards, from the tile sums of dX_F, with their share of the band inner products)."""
     import torch
     from paper_2507_08637_amd import binding
+    shape = dict(shape)
+    noise = shape.pop("noise", False)
     cfg = dict(shape, dtype="bf16", flavour="plain", seed_base=3800, q_mean=0.3)
     probe = torch.empty(cfg["B"], cfg["H"], cfg["n"], cfg["d"], dtype=torch.bfloat16, device="cuda")
     assert binding.wersa_path_name(binding.make_desc(probe, cfg["L"], cfg["m"])) == "mfma"
     p = workloads.make_inputs(**cfg)
     res = hp.gpu_forward_backward(p, cfg)
     ref = hp.oracle_backward(p, cfg)
-    _check_mfma(res, ref, p, cfg, where=f"deep mfma {shape}", noise_limited=None)
+    _check_mfma(res, ref, p, cfg, where=f"deep mfma {shape}", noise_limited=noise)
     fwd = hp.oracle_forward(p, cfg)
     sl = cfg["B"] * cfg["H"]
     for name in ("qbar", "s", "F", "S", "z", "D"):
