@@ -47,9 +47,10 @@ def make_inputs(B, H, n, d, L, m, dtype="f32", flavour="plain", seed_base=0, q_m
              "sinusoid" as plain, then K[t, :] += sin(2 pi t / 4096)
              "smooth"   Q, K = 0.5 N(0,1) + 1.5 sin(2 pi t / 256), V = 0.3 N(0,1) + sin(2 pi t / 256):
                         a shared low-frequency component, so that the wavelet scales carry signal
-             "smooth_cols" as smooth, with the wave of V scaled by cos(2 pi j / d) in column j, so
-                        that the rows of the un-normalised output vary over the columns (a
-                        LayerNorm over nearly constant rows would amplify rounding noise)
+             "smooth_cols" as smooth, but V = 0.3 N(0,1) + sin(2 pi t / 256) cos(x_j) + cos(2 pi t / 128) sin(x_j)
+                        + 0.7 sin(2 pi t / 512) cos(2 x_j), x_j = 2 pi j / d: three column profiles with their own
+                        time courses, so that the un-normalised output rows move in several directions
+                        (a LayerNorm of rows that all share one profile has a vanishing Jacobian)
     q_mean shifts Q so that the pooled-query path carries signal.
     """
     def rng(name):
@@ -71,7 +72,11 @@ def make_inputs(B, H, n, d, L, m, dtype="f32", flavour="plain", seed_base=0, q_m
             t = np.arange(n, dtype=np.float64)
             wave = np.sin(2.0 * np.pi * t / 256.0).astype(np.float32)[None, None, :, None]
             if flavour == "smooth_cols" and name == "V":
-                wave = wave * np.cos(2.0 * np.pi * np.arange(d) / d).astype(np.float32)[None, None, None, :]
+                xj = 2.0 * np.pi * np.arange(d) / d
+                wave = (np.sin(2.0 * np.pi * t / 256.0)[:, None] * np.cos(xj)[None, :]
+                        + np.cos(2.0 * np.pi * t / 128.0)[:, None] * np.sin(xj)[None, :]
+                        + 0.7 * np.sin(2.0 * np.pi * t / 512.0)[:, None] * np.cos(2.0 * xj)[None, :]
+                        ).astype(np.float32)[None, None, :, :]
             x = (np.float32(0.3) * x + wave) if name == "V" else (np.float32(0.5) * x + np.float32(1.5) * wave)
         if name == "Q" and q_mean != 0.0:
             x = x + np.float32(q_mean)

@@ -155,9 +155,11 @@ def test_mfma_path_shapes(shape):
 def _signal_problem(cfg, eps=1e-6, pooled=False, layernorm=False, separate_omega=False):
     """A workload on which the gate-parameter gradients are coherent sums: Q, K, V share a
     low-frequency component and the loss is 0.5 ||O - T||^2 with a phase-shifted target T, so that
-    dO = O - T (O from the oracle's forward).  With the LayerNorm output stage the target also
-    varies over the columns: a target that is constant along a row is orthogonal to every
-    normalised row, and the loss would have no gradient but rounding noise."""
+    dO = O - T (O from the oracle's forward).  With the LayerNorm output stage the loss is the
+    linear one <O, T> with a target that also varies over the columns, dO = T: a normalised row
+    has a fixed norm and is orthogonal to anything constant along the row, so the quadratic loss
+    would leave a gradient that is the small difference of nearly equal terms, dominated by the
+    rounding of O."""
     p = workloads.make_inputs(**cfg)
     if separate_omega:
         omk = np.random.default_rng(3199).standard_normal(p["Omega"].shape, dtype=np.float32)
@@ -171,8 +173,12 @@ def _signal_problem(cfg, eps=1e-6, pooled=False, layernorm=False, separate_omega
     t = np.arange(cfg["n"])
     T = np.cos(2 * np.pi * t / 256.0)[None, None, :, None]
     if layernorm:
-        T = 1.5 * T * np.sin(2 * np.pi * np.arange(cfg["d"]) / cfg["d"] + 0.7)[None, None, None, :]
-    p["dO"] = workloads.round_to_bf16((O - T).astype(np.float32))
+        xj = 2 * np.pi * np.arange(cfg["d"]) / cfg["d"]
+        T = (np.sin(2 * np.pi * t / 256.0)[:, None] * np.sin(xj + 0.7)[None, :]
+             + 0.5 * np.cos(2 * np.pi * t / 128.0)[:, None] * np.cos(2 * xj + 0.3)[None, :])[None, None]
+        p["dO"] = workloads.round_to_bf16(np.broadcast_to(T, O.shape).astype(np.float32))
+    else:
+        p["dO"] = workloads.round_to_bf16((O - T).astype(np.float32))
     return p
 
 
