@@ -115,6 +115,25 @@ wersa_status wersa_forward(const wersa_desc *desc, const void *q, const void *k,
                            const float *gate_b, const float *scale_w, void *out, void *saved,
                            void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * wersa_forward for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the same computation with the workspace
+ * taken from a scratch array built into the library (device memory, wersa_static_scratch_bytes()
+ * = 40 MiB per GPU, held from the first use until the process ends).  The caller still passes
+ * inputs, `out` and `saved`; the call allocates nothing and never synchronises.  A problem whose
+ * wersa_workspace_bytes(desc, 0) exceeds the scratch returns WERSA_ERR_WORKSPACE before anything is
+ * enqueued (the MFMA-path forward needs 17-35 MiB at the benchmark shapes, so those fit; deeper
+ * transforms than six levels at long n and large generic-path problems do not).  Every call on a
+ * GPU shares that GPU's array, whose contents are scratch (nothing in it needs to start at zero):
+ * calls that overlap in time on one GPU, on any streams, race; calls on different GPUs do not.
+ * The device that is current at the call must be the one that holds the tensors.
+ */
+size_t wersa_static_scratch_bytes(void);
+wersa_status wersa_forward_static(const wersa_desc *desc, const void *q, const void *k, const void *v,
+                                  const void *omega_rf, const float *sigma, const float *gate_w,
+                                  const float *gate_b, const float *scale_w, void *out, void *saved,
+                                  void *hip_stream);
+
 /* Backward pass: derivative of wersa_forward. `out` and `saved` are those of the matching
  * forward call on the same inputs. */
 wersa_status wersa_backward(const wersa_desc *desc, const void *q, const void *k, const void *v,

@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libwersa.so")
 WERSA_F32, WERSA_BF16 = 0, 1
 WERSA_FLAG_GENERIC_PATH = 1
 EXPORTS = ["wersa_workspace_bytes", "wersa_saved_bytes", "wersa_forward", "wersa_backward",
+           "wersa_forward_static", "wersa_static_scratch_bytes",
            "wersa_haar_filter", "wersa_haar_filter_ws", "wersa_haar_filter_workspace_bytes", "wersa_saved_offset", "wersa_selected_path", "wersa_status_string", "wersa_version",
            "wersa_profile_enable", "wersa_profile_only", "wersa_profile_reset", "wersa_profile_collect", "wersa_profile_get",
            "wersa_peak_copy", "wersa_peak_mfma",
@@ -61,6 +62,10 @@ def load_library():
     lib.wersa_saved_offset.argtypes = [dp, ctypes.c_int]
     lib.wersa_forward.restype = ctypes.c_int
     lib.wersa_forward.argtypes = [dp, vp, vp, vp, vp, fp, fp, fp, fp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.wersa_forward_static.restype = ctypes.c_int
+    lib.wersa_forward_static.argtypes = [dp, vp, vp, vp, vp, fp, fp, fp, fp, vp, vp, vp]
+    lib.wersa_static_scratch_bytes.restype = ctypes.c_size_t
+    lib.wersa_static_scratch_bytes.argtypes = []
     lib.wersa_backward.restype = ctypes.c_int
     lib.wersa_backward.argtypes = [dp] + [vp] * 4 + [fp] * 4 + [vp] * 3 + [vp] * 3 + [fp] * 4 + \
         [vp, ctypes.c_size_t, vp]
@@ -236,6 +241,22 @@ def wersa_forward(q, k, v, omega_rf, sigma, gate_w, gate_b, scale_w, L, eps=1e-6
     _check(lib.wersa_forward(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(omega_rf), _ptr(sigma),
                              _ptr(gate_w), _ptr(gate_b), _ptr(scale_w), _ptr(out), _ptr(saved),
                              _ptr(workspace), _nbytes(workspace), _stream(stream)))
+    return out, saved
+
+
+def wersa_forward_static(q, k, v, omega_rf, sigma, gate_w, gate_b, scale_w, L, out, saved, eps=1e-6,
+                         bw_floor=1e-6, stream=None, flags=0):
+    """wersa_forward with the library's built-in scratch as the workspace: `out` and `saved` come
+    from the caller and nothing is allocated here or in the library.  Returns (out, saved)."""
+    lib = load_library()
+    _same_layout(q, k, v, out)
+    desc = make_desc(q, L, omega_rf.shape[-1], eps, bw_floor, flags)
+    _check_omega(omega_rf, q, flags)
+    sb = lib.wersa_saved_bytes(ctypes.byref(desc))
+    assert sb == 0 or _nbytes(saved) >= sb, f"saved buffer holds {_nbytes(saved)} bytes, wersa_saved_bytes asks for {sb}"
+    _check(lib.wersa_forward_static(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(omega_rf), _ptr(sigma),
+                                    _ptr(gate_w), _ptr(gate_b), _ptr(scale_w), _ptr(out), _ptr(saved),
+                                    _stream(stream)))
     return out, saved
 
 

@@ -1,6 +1,8 @@
 // C ABI entry points: argument validation and dispatch. See include/wersa.h for the contract.
 #include "wersa_internal.h"
 
+#include <mutex>
+
 namespace wersa {
 
 wersa_status validate_desc(const wersa_desc *c) {
@@ -22,6 +24,30 @@ wersa_status validate_desc(const wersa_desc *c) {
 }
 
 static bool misaligned(const void *p, size_t a) { return ((uintptr_t)p % a) != 0; }
+
+// Scratch of wersa_forward_static: the forward's workspace for callers that cannot allocate.
+// One copy of the array lives on every device the library's code object is loaded on, at that
+// device's own address; the name below is only a host-side handle for hipGetSymbolAddress and is
+// never passed to a kernel.
+constexpr size_t kStaticScratchBytes = (size_t)40 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices] = {};
+static std::mutex g_scratch_mutex;
+
+// Address of the current device's copy of the scratch array (looked up once per device).
+static wersa_status static_scratch(void **out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return WERSA_ERR_LAUNCH;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return WERSA_ERR_LAUNCH;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return WERSA_OK;
+}
 
 wersa_status forward_checked(const wersa_desc *desc, const void *q, const void *k, const void *v,
                                     const void *omega_rf, const float *sigma, const float *gate_w,
@@ -88,6 +114,23 @@ wersa_status wersa_forward(const wersa_desc *desc, const void *q, const void *k,
                            void *workspace, size_t workspace_bytes, void *hip_stream) {
   return wersa::forward_checked(desc, q, k, v, omega_rf, sigma, gate_w, gate_b, scale_w, out, saved, workspace,
                                 workspace_bytes, hip_stream, nullptr);
+}
+
+size_t wersa_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+wersa_status wersa_forward_static(const wersa_desc *desc, const void *q, const void *k, const void *v,
+                                  const void *omega_rf, const float *sigma, const float *gate_w,
+                                  const float *gate_b, const float *scale_w, void *out, void *saved,
+                                  void *hip_stream) {
+  const wersa_status vs = validate_desc(desc);
+  if (vs != WERSA_OK) return vs;
+  const size_t need = wersa_workspace_bytes(desc, 0);
+  if (need == 0 || need > kStaticScratchBytes) return WERSA_ERR_WORKSPACE;   // beyond the built-in scratch
+  void *ws = nullptr;
+  const wersa_status ss = static_scratch(&ws);
+  if (ss != WERSA_OK) return ss;
+  return wersa::forward_checked(desc, q, k, v, omega_rf, sigma, gate_w, gate_b, scale_w, out, saved, ws,
+                                kStaticScratchBytes, hip_stream, nullptr);
 }
 
 wersa_status wersa_backward(const wersa_desc *desc, const void *q, const void *k, const void *v,
