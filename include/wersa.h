@@ -83,6 +83,13 @@ typedef enum { WERSA_F32 = 0, WERSA_BF16 = 1 } wersa_dtype;
  * launch, shared with the split of n; larger batches are to be split over calls);
  * 1 <= n <= 2^22; 0 <= L <= 20; d % 16 == 0, 16 <= d <= 256; m % 16 == 0, 16 <= m <= 4096.
  * Anything else that is otherwise well formed returns WERSA_ERR_UNSUPPORTED.
+ * MFMA path only: the filtered Q and K enter the random projection (step 7) rounded to fp16, after
+ * a power-of-two scale chosen per (batch, head) slice from max|Q| and the filter of that slice
+ * (ReLU is positively homogeneous, so the scale drops out exactly); inputs, bandwidth and per-scale
+ * weights of any magnitude are fine as long as the filtered K of a slice stays below about 2^11
+ * times the bound on its filtered Q (beyond that the fp16 operands overflow: take
+ * WERSA_FLAG_GENERIC_PATH).  The block entry points pool the queries in their own GEMM and use no
+ * such scale: there |X_F| must stay below 65504.
  * MFMA path only: q, k, v, omega_rf, out, dout, dq, dk, dv must be 16-byte aligned (their rows
  * are read and written in 16-byte pieces); a misaligned pointer returns WERSA_ERR_INVALID_ARG
  * before anything is enqueued (WERSA_FLAG_GENERIC_PATH takes any element-aligned pointer).

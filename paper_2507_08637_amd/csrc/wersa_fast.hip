@@ -300,7 +300,7 @@ __global__ __launch_bounds__(256) void setup_kernel(SetupArgs a) { setup_body(a,
 template <int DH>
 __global__ __launch_bounds__(256) void qbar_partial_kernel(const bf16_t *q, View v, int n,
                                                           int rows_per_chunk, float *part, int chunks,
-                                                          SetupArgs su) {
+                                                          SetupArgs su, float *amax_part) {
   constexpr int CPR = DH / 8;        // 16-byte chunks per row
   constexpr int RPI = 256 / CPR;     // rows per iteration
   if ((int)blockIdx.x >= chunks) {
@@ -314,30 +314,48 @@ __global__ __launch_bounds__(256) void qbar_partial_kernel(const bf16_t *q, View
   float acc[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+  // largest magnitude seen: integer maximum of the values with their sign bits cleared (packed 16-bit)
+  u16x8 mx = {0, 0, 0, 0, 0, 0, 0, 0};
+  const u16x8 magn = {0x7fff, 0x7fff, 0x7fff, 0x7fff, 0x7fff, 0x7fff, 0x7fff, 0x7fff};
+  auto track = [&](const u16x8 &x) { mx = __builtin_elementwise_max(mx, x & magn); };
   int t = t0 + rr;
   for (; t + 7 * RPI < t1; t += 8 * RPI) {   // eight independent loads in flight
     u16x8 x[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) x[u] = *reinterpret_cast<const u16x8 *>(qs + (int64_t)(t + u * RPI) * v.sn);
 #pragma unroll
-    for (int u = 0; u < 8; ++u)
+    for (int u = 0; u < 8; ++u) {
+      track(x[u]);
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc[e] += bf16_to_f32(x[u][e]);
+    }
   }
   for (; t < t1; t += RPI) {
     const u16x8 x = *reinterpret_cast<const u16x8 *>(qs + (int64_t)t * v.sn);
+    track(x);
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] += bf16_to_f32(x[e]);
   }
   __shared__ float red[RPI][DH + 1];
+  __shared__ float amax_w[4];
 #pragma unroll
   for (int e = 0; e < 8; ++e) red[rr][cc * 8 + e] = acc[e];
+  if (amax_part) {   // (NaN and infinity compare as the largest magnitudes and are passed on as such)
+    unsigned short m16 = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) m16 = mx[e] > m16 ? mx[e] : m16;
+    float m = bf16_to_f32(m16);
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+    if ((threadIdx.x & 63) == 0) amax_w[threadIdx.x >> 6] = m;
+  }
   __syncthreads();
   if (threadIdx.x < DH) {
     float s = 0.f;
     for (int r = 0; r < RPI; ++r) s += red[r][threadIdx.x];
     part[((int64_t)slice * chunks + chunk) * DH + threadIdx.x] = s;
   }
+  if (amax_part && threadIdx.x == 0)
+    amax_part[(int64_t)slice * chunks + chunk] = fmaxf(fmaxf(amax_w[0], amax_w[1]), fmaxf(amax_w[2], amax_w[3]));
 }
 
 // ------------------------------------------------------------------------------------
@@ -834,7 +852,8 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
   }
 }
 
-// M[slice][e] = scale * sum_chunk part[slice][chunk][e]  (e over m*DH) and the vector part
+// M[slice][e] = scale[slice] * sum_chunk part[slice][chunk][e]  (e over m*DH; scale_ptr points at the
+// slice rows' c * 2^-k entries, kCoefStride apart) and the vector part
 // b likewise; plus the bf16 MFMA operand copies:
 //   Mx  [m][DH+16]: row r = (M[r][0..DH), b[r], 0 x 15)   (A operand of dPhi = Y M^T + a b^T)
 //   MT  [DH][m]   : M transposed                           (B operand of Phi M)
@@ -869,7 +888,7 @@ __global__ __launch_bounds__(256) void reduce_contract_kernel(const float *Spart
   part[grp][lane] = acc;
   __syncthreads();
   if (grp != 0) return;
-  acc = ((part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane])) * (*scale_ptr);
+  acc = ((part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane])) * scale_ptr[slice * kCoefStride];
   const bf16_t b = f32_to_bf16(acc);
   if (!is_z) {
     S[(int64_t)slice * W + e] = acc;
@@ -972,7 +991,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
 
   const int slice = blockIdx.y;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
-  const float cscale = scalars[0];
+  const float cscale = coef[slice * kCoefStride + kCoefCscale];   // c * 2^-k of this slice (X_F carries 2^k)
   const int nchunks = m / mc;
 
   // Feature-side operands of features [m0, m0 + MC) into LDS: every piece count is a compile-time
@@ -1979,6 +1998,7 @@ FastPlan fast_plan(const wersa_desc &c) {
 }
 
 struct FastWs {
+  float *qamax;   // largest |Q| per (slice, chunk) of the pooling pass
   float *scalars, *coef, *qpart, *Spart, *zpart, *dD, *dDpart, *dS, *dz, *partQ, *partK, *dF,
       *dlogit, *dqbar;
   bf16_t *tail_out;   // partial last block of the sequence: its 64 output rows [slices][64][d]
@@ -2019,6 +2039,7 @@ FastWs fast_ws(const wersa_desc &c, const FastPlan &p, int bwd, float *base, flo
   w.tail_out = reinterpret_cast<bf16_t *>(b.take(2 * sl * 64 * c.d / 2));   // (two outputs when dV rides along with dK)
   w.tail_D = b.take(sl * 64);
   w.qpart = b.take(sl * p.chunksQ * c.d);
+  w.qamax = b.take(sl * p.chunksQ);
   w.Spart = b.take(sl * p.chunksC * md);
   w.zpart = b.take(sl * p.chunksC * c.m);
   const int64_t mx = (int64_t)c.m * (c.d + 16);
@@ -2187,7 +2208,7 @@ void launch_contract(const wersa_desc &c, const FastPlan &p, const _Float16 *xf,
   const int64_t W = (int64_t)c.m * DH;
   WERSA_STAGE("wersa_reduce_contract", st,
               reduce_contract_kernel<DH><<<dim3((unsigned)(W / 64 + c.m / 64), slices), 256, 0, st>>>(
-                  w.Spart, w.zpart, p.chunksC, c.m, w.scalars, S, z, Mx, MT, bb));
+                  w.Spart, w.zpart, p.chunksC, c.m, w.coef + kCoefCscale, S, z, Mx, MT, bb));
 }
 
 template <int DH>
@@ -2216,22 +2237,24 @@ wersa_status fast_forward_t(const wersa_desc &c, const bf16_t *q, const bf16_t *
     WERSA_STAGE("gate_fwd_kernel", st,
                 gate_fwd_kernel<<<slices, 256, 0, st>>>(pooled->sums, chunks, c.n, c.d, c.L, c.H, gate_w, gate_b, scale_w,
                                                        qbar, s, F, w.coef, (c.flags & WERSA_FLAG_POOLED_GATE) ? 1 : 0,
-                                                       PooledLayout{chunks * pooled->hidden, c.d, pooled->hidden}));
+                                                       PooledLayout{chunks * pooled->hidden, c.d, pooled->hidden},
+                                                       nullptr, 0, w.scalars));
   } else {
     // deep: one partial per 64-row tile, kept (with those of K) as the tile sums of the levels above 6
     float *qpart = deep ? w.tileQ : w.qpart;
     WERSA_STAGE("wersa_qbar", st,
                 qbar_partial_kernel<DH><<<dim3(p.chunksQ + su.blocks, slices), 256, 0, st>>>(q, tv, c.n, p.rowsQ, qpart,
-                                                                                             p.chunksQ, su));
+                                                                                             p.chunksQ, su, w.qamax));
     WERSA_STAGE("gate_fwd_kernel", st,
                 gate_fwd_kernel<<<slices, 256, 0, st>>>(qpart, p.chunksQ, c.n, c.d, c.L, c.H, gate_w, gate_b, scale_w,
                                                        qbar, s, F, w.coef, (c.flags & WERSA_FLAG_POOLED_GATE) ? 1 : 0,
-                                                       PooledLayout{(int64_t)c.H * p.chunksQ * c.d, (int64_t)p.chunksQ * c.d, c.d}));
+                                                       PooledLayout{(int64_t)c.H * p.chunksQ * c.d, (int64_t)p.chunksQ * c.d, c.d},
+                                                       w.qamax, p.chunksQ, w.scalars));
   }
   if (deep) {
     WERSA_STAGE("wersa_qbar", st,
                 qbar_partial_kernel<DH><<<dim3(p.chunksQ, slices), 256, 0, st>>>(k, tv, c.n, p.rowsQ, w.tileK,
-                                                                                 p.chunksQ, none));
+                                                                                 p.chunksQ, none, nullptr));
     WERSA_STAGE("wersa_coarse_addend", st,
                 coarse_addend_kernel<<<dim3(slices, 2, DH / kCoarseCols), 1024, 0, st>>>(w.tileQ, w.tileK, w.coef, p.chunksQ, DH, c.L, w.pyr,
                                                                       w.addQ, w.addK));
@@ -2305,7 +2328,7 @@ wersa_status fast_backward_t(const wersa_desc &c, const bf16_t *q, const bf16_t 
   WERSA_STAGE("gate_bwd_slice_kernel", st,
               gate_bwd_slice_kernel<<<slices, kGateBwdThreads, 0, st>>>(w.partQ, w.partK, deep ? p.rowsWgsG + DH / kCoarseCols : p.rowsWgsG, c.L,
                                                            c.d, c.H, s, gate_w, scale_w, w.dF, w.dlogit, w.dqbar,
-                                                           (c.flags & WERSA_FLAG_POOLED_GATE) ? 1 : 0));
+                                                           (c.flags & WERSA_FLAG_POOLED_GATE) ? 1 : 0, w.coef));
   WERSA_STAGE("gate_bwd_params_kernel", st,
               gate_bwd_params_kernel<<<gate_bwd_params_blocks(c.H, c.L, c.d), 256, 0, st>>>(w.dF, w.dlogit, s, qbar, w.dDpart, slices * p.chunksC,
                                                         c.B, c.H, c.L, c.d, c.eps, w.scalars, dgate_w,

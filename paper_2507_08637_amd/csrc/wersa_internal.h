@@ -13,6 +13,8 @@ constexpr int kTileBands = kTileL + 1;
 constexpr int kMaxL = 20;                 // deepest transform (levels above 6 run on tile approximations)
 constexpr int kMaxBands = kMaxL + 1;
 constexpr int kCoefStride = 24;           // block-mean coefficients per slice (levels 0 .. kMaxL, padded)
+constexpr int kCoefScale = 22;            // MFMA path: slot of the slice's operand scale 2^k in its coefficient row
+constexpr int kCoefCscale = 23;           // ... and of c * 2^-k, c = 1 / (sigma_eff sqrt(m))
 
 // Strided view of a (B, H, n, d) tensor; element (b, h, t, j) at b*sb + h*sh + t*sn + j.
 struct View {

@@ -246,6 +246,42 @@ def test_mfma_dsigma_against_the_oracle(d):
     _check_all(res2, ref2, 2e-2, names=("O", "dQ", "dK", "dV"), where="mfma, sigma below the floor")
 
 
+@pytest.mark.parametrize("case", ["large", "tiny", "large_scale_weights", "mixed"])
+def test_mfma_path_input_range(case):
+    """The MFMA path rounds X_F to fp16 before the projection (Section 3.1 step 7).  ReLU is
+    positively homogeneous, so a power of two chosen per slice from max|Q| and the filter keeps
+    those operands in range: inputs (and the bandwidth with them) of the order 2^13 or 2^-20, and
+    per-scale weights of the order 2^10, must meet the same bar as inputs of order one.  (Without
+    the scale, 2^13 inputs overflow fp16 to infinity and 2^-20 inputs vanish below its subnormals.)
+    'mixed': K sixteen times larger than Q."""
+    import torch
+    from paper_2507_08637_amd import binding
+    cfg = dict(B=1, H=2, n=1024, d=64, L=5, m=256, dtype="bf16", flavour="plain", seed_base=8800, q_mean=0.3)
+    p = workloads.make_inputs(**cfg)
+    f = {"large": 2.0 ** 13, "tiny": 2.0 ** -20, "large_scale_weights": 1.0, "mixed": 1.0}[case]
+    for k in ("Q", "K"):
+        p[k] = (p[k] * np.float32(f)).astype(np.float32)     # exact: a power of two
+    p["sigma"] = np.float32(f)
+    p["Wg"] = (p["Wg"] / np.float32(f)).astype(np.float32)   # the gate's logits stay of order one
+    if case == "large_scale_weights":
+        p["omega"] = (p["omega"] * np.float32(1024.0)).astype(np.float32)
+    if case == "mixed":
+        p["K"] = (p["K"] * np.float32(16.0)).astype(np.float32)
+    probe = torch.empty(cfg["B"], cfg["H"], cfg["n"], cfg["d"], dtype=torch.bfloat16, device="cuda")
+    assert binding.wersa_path_name(binding.make_desc(probe, cfg["L"], cfg["m"])) == "mfma"
+    res = hp.gpu_forward_backward(p, cfg)
+    for k in ("O", "dQ", "dK", "dV", "dWg", "dbg", "domega"):
+        assert bool(torch.isfinite(res[k].float()).all()), k
+    ref = hp.oracle_backward(p, cfg)
+    _check_all(res, ref, 2e-2, names=("O", "dQ", "dK", "dV"), where=f"mfma input range: {case}")
+    fwd = hp.oracle_forward(p, cfg)
+    sl = cfg["B"] * cfg["H"]
+    for name in ("S", "z", "D"):
+        r = fwd[name].reshape((sl,) + fwd[name].shape[2:])
+        assert hp.rel_err(res["saved"][name], r) < 2e-2, name
+    _check_mfma(res, ref, p, cfg, where=f"mfma input range: {case}")   # plain 1.3e-2 .. 1.5e-2, as at order one
+
+
 def test_mfma_and_generic_paths_agree():
     """Same bf16 problem through both paths (descriptor flag): both within tolerance of the
     oracle, hence of each other."""
