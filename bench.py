@@ -297,7 +297,7 @@ def main():
                  "mfma_bf16_TFLOPs": binding.wersa_peak_mfma(reps=3)}
         binding.wersa_profile_enable(True)
         for _ in range(3):
-            binding.wersa_peak_copy(dst, src, reps=1)   # (not one of the bracketed stages)
+            dst.copy_(src)   # flushes the cache; asynchronous, so the step follows without a host wait
             step()
         torch.cuda.synchronize()
         cold = binding.wersa_profile_collect()

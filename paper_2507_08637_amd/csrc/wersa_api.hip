@@ -165,6 +165,8 @@ wersa_status wersa_haar_filter(const wersa_desc *desc, const void *x, const floa
   const wersa_status vs = validate_desc(desc);
   if (vs != WERSA_OK) return vs;
   if (!x || !filt || !xf) return WERSA_ERR_INVALID_ARG;
+  if (!(desc->flags & WERSA_FLAG_GENERIC_PATH) && fast_haar_filter_supported(*desc, x, xf))
+    return fast_haar_filter(*desc, x, filt, xf, (hipStream_t)hip_stream);
   return generic_haar_filter(*desc, x, filt, xf, nullptr, (hipStream_t)hip_stream);
 }
 
@@ -180,6 +182,8 @@ wersa_status wersa_haar_filter_ws(const wersa_desc *desc, const void *x, const f
   if (!x || !filt || !xf) return WERSA_ERR_INVALID_ARG;
   const size_t need = generic_haar_filter_floats(*desc) * sizeof(float);
   if (need && (!workspace || workspace_bytes < need || misaligned(workspace, 256))) return WERSA_ERR_WORKSPACE;
+  if (!(desc->flags & WERSA_FLAG_GENERIC_PATH) && fast_haar_filter_supported(*desc, x, xf))
+    return fast_haar_filter(*desc, x, filt, xf, (hipStream_t)hip_stream);
   return generic_haar_filter(*desc, x, filt, xf, need ? (float *)workspace : nullptr, (hipStream_t)hip_stream);
 }
 

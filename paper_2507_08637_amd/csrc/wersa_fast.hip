@@ -452,6 +452,67 @@ __global__ __launch_bounds__(256) void haar_stage_kernel(const bf16_t *x, View v
   }
 }
 
+// float32 -> bf16 storage with the hardware conversion (round to nearest even)
+__device__ __forceinline__ bf16_t cvt_bf16(float f) {
+  return __builtin_bit_cast(bf16_t, (__bf16)f);
+}
+
+// The gated Haar filter as a stage of its own on bf16 tensors (steps 3, 5, 6 of Section 3.1; the
+// stage entry point): X -> X_F in the same layout and dtype, up to six levels, one tile of 64 rows x
+// 64 columns per workgroup.  Rows move in 16-byte pieces both ways; the filter is evaluated in
+// block-mean form, one thread per (column, 16-row segment), the 32- and 64-row sums through LDS;
+// no float copy of the tile exists anywhere.  filt: [slices][L + 1] (band order of Algorithm 2).
+__global__ __launch_bounds__(256) void haar_filter_bf16_kernel(const bf16_t *x, bf16_t *y, View v, int n, int d,
+                                                              const float *filt, int L) {
+  constexpr int TC = 64, RS = 16, CPR = TC / 8;
+  __shared__ __attribute__((aligned(16))) bf16_t tile[64 * TC];
+  __shared__ float segsum[4][TC];
+  __shared__ float cf[8];
+  const int slice = blockIdx.z, t0 = blockIdx.x * 64, c0 = blockIdx.y * TC;
+  const int tid = threadIdx.x;
+  if (tid < 8) {   // block-mean coefficients: coef_0 = F_0, coef_l = (F_l - F_{l-1}) / 2^l, 0 above L
+    const float *F = filt + (int64_t)slice * (L + 1);
+    cf[tid] = tid == 0 ? F[0] : (tid <= L ? (F[tid] - F[tid - 1]) / (float)(1 << tid) : 0.f);
+  }
+  const int64_t base = v.slice_base(slice);
+  u16x8 piece[2];
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int e = tid + 256 * u, r = e / CPR, cc = e % CPR;
+    const bool ok = t0 + r < n && c0 + cc * 8 < d;
+    // (rows past n and columns past d read as zeros: Algorithm 2's padding)
+    piece[u] = *reinterpret_cast<const u16x8 *>(x + base + (int64_t)(ok ? t0 + r : 0) * v.sn + (ok ? c0 + cc * 8 : 0));
+    if (!ok)
+#pragma unroll
+      for (int q = 0; q < 8; ++q) piece[u][q] = 0;
+  }
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int e = tid + 256 * u;
+    *reinterpret_cast<u16x8 *>(&tile[(e / CPR) * TC + (e % CPR) * 8]) = piece[u];
+  }
+  __syncthreads();
+  const int c = tid % TC, seg = tid / TC;
+  float vals[RS];
+#pragma unroll
+  for (int i = 0; i < RS; ++i) vals[i] = bf16_to_f32(tile[(seg * RS + i) * TC + c]);
+  segsum[seg][c] = segment_sum<RS>(vals);
+  __syncthreads();
+  const float s5 = segsum[seg & ~1][c] + segsum[seg | 1][c];
+  const float s6 = (segsum[0][c] + segsum[1][c]) + (segsum[2][c] + segsum[3][c]);
+  filter_segment<RS>(vals, cf, fmaf(cf[5], s5, cf[6] * s6));
+#pragma unroll
+  for (int i = 0; i < RS; ++i) tile[(seg * RS + i) * TC + c] = cvt_bf16(vals[i]);
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int e = tid + 256 * u, r = e / CPR, cc = e % CPR;
+    if (t0 + r < n && c0 + cc * 8 < d)
+      *reinterpret_cast<u16x8 *>(y + base + (int64_t)(t0 + r) * v.sn + c0 + cc * 8) =
+          *reinterpret_cast<const u16x8 *>(&tile[r * TC + cc * 8]);
+  }
+}
+
 // ------------------------------------------------------------------------------------
 // Small helpers for the chained MFMAs.
 // ------------------------------------------------------------------------------------
@@ -475,10 +536,6 @@ __device__ __forceinline__ float dot8_bf16(bf16x8 p, bf16x8 w, float acc) {
     acc = __builtin_amdgcn_fdot2_f32_bf16(a, b, acc, false);
   }
   return acc;
-}
-// float32 -> bf16 storage with the hardware conversion (round to nearest even)
-__device__ __forceinline__ bf16_t cvt_bf16(float f) {
-  return __builtin_bit_cast(bf16_t, (__bf16)f);
 }
 __device__ __forceinline__ bf16x8 splat_bf16x8(float v) {
   bf16x8 r;
@@ -2348,6 +2405,19 @@ wersa_status fast_backward_t(const wersa_desc &c, const bf16_t *q, const bf16_t 
 }
 
 }  // namespace
+
+bool fast_haar_filter_supported(const wersa_desc &c, const void *x, const void *xf) {
+  return c.dtype == WERSA_BF16 && c.L <= kTileL && c.d % 8 == 0 && c.stride_n % 8 == 0 && c.stride_h % 8 == 0 &&
+         c.stride_b % 8 == 0 && ((uintptr_t)x % 16) == 0 && ((uintptr_t)xf % 16) == 0;
+}
+
+wersa_status fast_haar_filter(const wersa_desc &c, const void *x, const float *filt, void *xf, hipStream_t st) {
+  const View tv{c.stride_b, c.stride_h, c.stride_n, c.H};
+  const dim3 grid((unsigned)((c.n + 63) / 64), (unsigned)((c.d + 63) / 64), (unsigned)(c.B * c.H));
+  WERSA_STAGE("wersa_haar_filter_bf16", st,
+              haar_filter_bf16_kernel<<<grid, 256, 0, st>>>((const bf16_t *)x, (bf16_t *)xf, tv, c.n, c.d, filt, c.L));
+  return hipGetLastError() == hipSuccess ? WERSA_OK : WERSA_ERR_LAUNCH;
+}
 
 bool fast_supported(const wersa_desc &c) {
   return c.dtype == WERSA_BF16 && (c.d == 64 || c.d == 128) && c.m % 128 == 0 &&

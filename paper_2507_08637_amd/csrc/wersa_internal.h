@@ -151,6 +151,10 @@ wersa_status fast_backward(const wersa_desc &c, const void *q, const void *k, co
                            hipStream_t st);
 // deep: approximation arrays of the stages above the first (generic_haar_filter_floats(c) floats;
 // nullptr for L <= 6).
+// bf16 tensors with 16-byte aligned rows, up to six levels: the stage as one streaming kernel with
+// 16-byte row accesses (everything else takes generic_haar_filter)
+bool fast_haar_filter_supported(const wersa_desc &c, const void *x, const void *xf);
+wersa_status fast_haar_filter(const wersa_desc &c, const void *x, const float *filt, void *xf, hipStream_t st);
 size_t generic_haar_filter_floats(const wersa_desc &c);
 wersa_status generic_haar_filter(const wersa_desc &c, const void *x, const float *filt, void *xf,
                                  float *deep, hipStream_t st);

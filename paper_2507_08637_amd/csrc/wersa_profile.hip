@@ -44,18 +44,21 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 pk_bf16x8 __attribute__((ext_vector_type(8)));
 typedef float pk_f32x16 __attribute__((ext_vector_type(16)));
 
-// dst[i] = src[i] for `pieces` 16-byte pieces, grid-stride, four independent pieces per thread per round.
+// dst[i] = src[i] for `pieces` 16-byte pieces: each workgroup streams contiguous runs of 8 x 4 KiB,
+// eight independent 16-byte loads per thread in flight before the first store.
 __global__ __launch_bounds__(256) void peak_copy_kernel(u32x4 *dst, const u32x4 *src, size_t pieces) {
-  const size_t stride = (size_t)gridDim.x * 256;
-  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  for (; i + 3 * stride < pieces; i += 4 * stride) {
-    const u32x4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-    dst[i] = a;
-    dst[i + stride] = b;
-    dst[i + 2 * stride] = c;
-    dst[i + 3 * stride] = d;
+  constexpr size_t RUN = 8 * 256;   // pieces per workgroup per round
+  const size_t rounds = pieces / RUN;
+  for (size_t r = blockIdx.x; r < rounds; r += gridDim.x) {
+    const size_t i0 = r * RUN + threadIdx.x;
+    u32x4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(src + i0 + 256 * u);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) __builtin_nontemporal_store(v[u], dst + i0 + 256 * u);
   }
-  for (; i < pieces; i += stride) dst[i] = src[i];
+  if (blockIdx.x == 0)
+    for (size_t i = rounds * RUN + threadIdx.x; i < pieces; i += 256) dst[i] = src[i];
 }
 
 // Every wave issues iters x 4 independent v_mfma_f32_32x32x16_bf16 (four accumulator tiles, operands
@@ -145,7 +148,7 @@ double wersa_peak_copy(void *dst, const void *src, size_t bytes, int32_t reps, v
   hipEvent_t e0, e1;
   if (hipEventCreate(&e0) != hipSuccess) return -1.0;
   if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return -1.0; }
-  const unsigned grid = 256 * 16;   // 16 workgroups of 256 threads per compute unit
+  const unsigned grid = 256 * 8;   // eight workgroups of 256 threads per compute unit, each walking many rounds
   peak_copy_kernel<<<grid, 256, 0, st>>>((u32x4 *)dst, (const u32x4 *)src, pieces);   // warm-up
   (void)hipEventRecord(e0, st);
   for (int r = 0; r < reps; ++r) peak_copy_kernel<<<grid, 256, 0, st>>>((u32x4 *)dst, (const u32x4 *)src, pieces);

@@ -370,6 +370,33 @@ def test_haar_filter_stage(dtype):
     assert hp.rel_err(y1, x.astype(np.float64)) < tol
 
 
+@pytest.mark.parametrize("shape", [dict(B=1, H=2, n=203, d=48, L=3),      # partial last tile, partial column tile
+                                   dict(B=2, H=2, n=1000, d=128, L=6),    # two column tiles
+                                   dict(B=1, H=3, n=64, d=16, L=0),       # no levels: a plain scale by F_0
+                                   dict(B=2, H=2, n=640, d=64, L=5, layout="bnhd")])   # heads addressed by stride
+def test_haar_filter_stage_bf16_streaming_kernel(shape):
+    """The stage entry point on bf16 tensors (one streaming kernel in block-mean form, 16-byte row
+    pieces) against the oracle's lifting recursion, edge shapes; the float32-arithmetic kernel
+    behind WERSA_FLAG_GENERIC_PATH must agree with it to the output rounding."""
+    import torch
+    from oracle import wersa_oracle as wo
+    from paper_2507_08637_amd import binding
+    B, H, n, d, L = (shape[k] for k in ("B", "H", "n", "d", "L"))
+    rng = np.random.default_rng(9)
+    x = workloads.round_to_bf16((rng.standard_normal((B, H, n, d)) + 0.2).astype(np.float32))
+    filt = rng.uniform(-0.5, 1.5, (B * H, L + 1)).astype(np.float32)
+    xt = torch.from_numpy(x).cuda().to(torch.bfloat16)
+    if shape.get("layout") == "bnhd":
+        xt = xt.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    y = torch.full_like(xt, float("nan"))
+    binding.wersa_haar_filter(xt, torch.from_numpy(filt).cuda(), L, out=y)
+    torch.cuda.synchronize()
+    ref = np.stack([wo.haar_filter(x[b, h].astype(np.float64), filt[b * H + h].astype(np.float64), L)
+                    for b in range(B) for h in range(H)]).reshape(B, H, n, d)
+    assert bool(torch.isfinite(y.float()).all())
+    assert hp.rel_err(y, ref) < 4e-3   # bf16 output rounding: 2^-9 per element
+
+
 @pytest.mark.parametrize("shape", [dict(n=4160, L=12), dict(n=1000, L=9), dict(n=5000, L=7)])
 def test_haar_filter_stage_deeper_than_one_tile(shape):
     """The stage entry point with a workspace: levels above 6 run on the approximation
