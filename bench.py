@@ -24,12 +24,12 @@ PEAK = {"hbm": (8000.0, "GB/s"), "mfma_bf16": (2500.0, "TFLOP/s"), "fp32": (157.
 # runs summarised in profiles/mfma_path_config4_hbm_traffic.md (FETCH_SIZE scaled by the factor 2.0 that
 # a plain 1 GiB copy shows for this counter, WRITE_SIZE by 1.0).
 MIB = 1024.0 * 1024.0
-RANKING_STEPS = 5   # untimed steps with every launch bracketed, to rank the kernels
+RANKING_STEPS = 20   # untimed steps with every launch bracketed, to rank the kernels
 MEASURED_TRAFFIC_CONFIG4 = {
-    "wersa_rows_fwd": (137.8 + 135.0) * MIB, "wersa_rows_bwd_q": (272.0 + 128.9) * MIB,
-    "wersa_rows_bwd_k": (267.8 + 258.4) * MIB,   # with dV
+    "wersa_rows_fwd": (137.7 + 134.8) * MIB, "wersa_rows_bwd_q": (272.0 + 130.1) * MIB,
+    "wersa_rows_bwd_k": (275.2 + 260.4) * MIB,   # with dV
     "wersa_phiT_contract": ((256.4 + 32.5) + (388.4 + 36.5)) / 2 * MIB,   # average of the two launches
-    "wersa_qbar": 128.3 * MIB, "wersa_add_pooled": 256.1 * MIB,
+    "wersa_qbar": 128.6 * MIB, "wersa_add_pooled": 256.1 * MIB,
 }
 
 
@@ -181,8 +181,8 @@ def run_block(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", type=int, default=4, help="workload configuration (1-4: the core; 5: the attention block)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not bracket kernels with HIP events")
@@ -281,7 +281,7 @@ def main():
     # instructions, measured now in this process; (c) a few steps each preceded by that 2 GiB copy,
     # every launch bracketed: the memory-bound stages with their inputs NOT resident in the 256 MB
     # last-level cache (in back-to-back steps the pooled-query pass finds part of Q there).
-    median_ms, peaks, cold = None, None, {}
+    median_ms, peaks, cold, haar_stage = None, None, {}, None
     if not args.graph and not args.no_events:
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
         for a, b in evs:
@@ -301,6 +301,25 @@ def main():
             step()
         torch.cuda.synchronize()
         cold = binding.wersa_profile_collect()
+        # (d) the gated Haar filter as a stage of its own (steps 3, 5, 6 through the stage entry point), which
+        # the fused step never launches at head dimension 64: on a 1 GiB bf16 tensor of the workload's
+        # slice count, row length and depth (8 slices x 2^20 rows x 64 columns; larger than the cache)
+        if cfg["dtype"] == "bf16" and args.config != 5 and cfg["L"] <= 6:
+            sl, dcol = cfg["B"] * cfg["H"], cfg["d"]
+            rows = (1 << 29) // (sl * dcol)
+            if rows <= (1 << 22) and sl * rows * dcol == (1 << 29):
+                xs = src.view(torch.bfloat16).view(1, sl, rows, dcol)
+                ys = dst.view(torch.bfloat16).view(1, sl, rows, dcol)
+                filt = torch.rand(sl, cfg["L"] + 1, device="cuda")
+                for _ in range(4):
+                    binding.wersa_haar_filter(xs, filt, cfg["L"], out=ys)
+                torch.cuda.synchronize()
+                hs = binding.wersa_profile_collect().get("wersa_haar_filter_bf16")
+                if hs:
+                    haar_stage = {"kernel": "wersa_haar_filter_bf16", "bound": "hbm", "work_per_launch": float(2 << 30),
+                                  "work_unit": "B", "avg_us": round(hs[0] / hs[1] * 1e3, 2),
+                                  "input": f"1 GiB bf16 tensor ({sl} slices x {rows} rows x {dcol} columns, L={cfg['L']}), "
+                                           "read once and written once; not a launch of the step"}
         binding.wersa_profile_enable(False)
         del src, dst
     rec = {
@@ -354,6 +373,11 @@ def main():
                 st["cold_avg_us"] = round(cus, 2)
                 st["cold_frac_nominal"] = round(work / (cus * 1e-6) / 1e9 / peak, 4)
             stages.append(st)
+        if haar_stage:
+            ach = haar_stage["work_per_launch"] / (haar_stage["avg_us"] * 1e-6) / 1e9
+            haar_stage.update({"achieved": round(ach, 1), "unit": "GB/s", "frac_nominal": round(ach / PEAK["hbm"][0], 4),
+                               "frac_measured": round(ach / peaks["hbm_copy_GBps"], 4)})
+            stages.append(haar_stage)
         rec["stages"] = stages
         rec["stages_note"] = ("avg_us: back-to-back steps (a stage may find part of its input in the 256 MB last-level "
                               "cache); cold_*: the step preceded by a 2 GiB streaming copy")
