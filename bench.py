@@ -58,10 +58,10 @@ def kernel_models(cfg):
     nd = float(n) * d * sl
     models = {
         # generic (float32 arithmetic) path
-        "gemm_features": ("alu", "fp32", unit), "gemm_phiT": ("alu", "fp32", unit),
-        "gemm_rows": ("alu", "fp32", unit),
+        # (float32 MFMA: v_mfma_f32_32x32x2_f32, dense float32 matrix peak)
+        "gemm_features": ("mfma", "fp32", unit), "gemm_phiT": ("mfma", "fp32", unit),
+        "gemm_rows": ("mfma", "fp32", unit),
         "haar_filter_kernel": ("hbm", "hbm", nd * (e + 4)),
-        "colsum_partial_kernel": ("hbm", "hbm", nd * e),
         # fused MFMA path
         "wersa_qbar": ("hbm", "hbm", nd * e),
         "wersa_haar_stage": ("hbm", "hbm", nd * (e + 2)),       # head dimension 128: one tensor in (bf16), one out (fp16)
@@ -184,6 +184,8 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", type=int, default=4, help="workload configuration (1-4: the core; 5: the attention block)")
+    ap.add_argument("--generic", action="store_true",
+                    help="force the float32-arithmetic path (WERSA_FLAG_GENERIC_PATH) on configurations 1-4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not bracket kernels with HIP events")
     ap.add_argument("--graph", action="store_true",
@@ -210,7 +212,8 @@ def main():
         cfg, p = workloads.make_config(args.config, backward=True)
         t = to_device(p, cfg["dtype"])
         L = cfg["L"]
-        desc = binding.make_desc(t["Q"], L, cfg["m"])
+        flags = binding.WERSA_FLAG_GENERIC_PATH if args.generic else 0
+        desc = binding.make_desc(t["Q"], L, cfg["m"], flags=flags)
         saved, ws_f = binding.alloc_like(desc, t["Q"], 0)
         _, ws_b = binding.alloc_like(desc, t["Q"], 1)
         out = torch.empty_like(t["Q"])
@@ -223,9 +226,10 @@ def main():
         def step():
             nonlocal grads
             binding.wersa_forward(t["Q"], t["K"], t["V"], t["Omega"], t["sigma"], t["Wg"], t["bg"], t["omega"], L,
-                                  out=out, saved=saved, workspace=ws_f)
+                                  out=out, saved=saved, workspace=ws_f, flags=flags)
             grads = binding.wersa_backward(t["Q"], t["K"], t["V"], t["Omega"], t["sigma"], t["Wg"], t["bg"],
-                                           t["omega"], out, t["dO"], saved, L, workspace=ws_b, grads=grads)
+                                           t["omega"], out, t["dO"], saved, L, workspace=ws_b, grads=grads,
+                                           flags=flags)
 
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)   # 1 GiB
@@ -304,7 +308,7 @@ def main():
         # (d) the gated Haar filter as a stage of its own (steps 3, 5, 6 through the stage entry point), which
         # the fused step never launches at head dimension 64: on a 1 GiB bf16 tensor of the workload's
         # slice count, row length and depth (8 slices x 2^20 rows x 64 columns; larger than the cache)
-        if cfg["dtype"] == "bf16" and args.config != 5 and cfg["L"] <= 6:
+        if cfg["dtype"] == "bf16" and args.config != 5 and cfg["L"] <= 6 and not args.generic:
             sl, dcol = cfg["B"] * cfg["H"], cfg["d"]
             rows = (1 << 29) // (sl * dcol)
             if rows <= (1 << 22) and sl * rows * dcol == (1 << 29):
@@ -365,7 +369,7 @@ def main():
                   "launches_per_step": cnt / RANKING_STEPS, "avg_us": round(us, 2), "achieved": round(ach, 1), "unit": unit,
                   "frac_nominal": round(ach / peak, 4)}
             if peaks:
-                mp = peaks["hbm_copy_GBps"] if bound == "hbm" else (peaks["mfma_bf16_TFLOPs"] if bound == "mfma" else None)
+                mp = peaks["hbm_copy_GBps"] if bound == "hbm" else (peaks["mfma_bf16_TFLOPs"] if pk == "mfma_bf16" else None)
                 if mp and mp > 0:
                     st["frac_measured"] = round(ach / mp, 4)
             if bound == "hbm" and k in cold:

@@ -247,8 +247,13 @@ struct GemmArgs {
   int relu;               // apply max(.,0) before alpha
 };
 
+// 64 x 64 output tile per workgroup, 16 k per LDS stage; the four waves each own a 32 x 32 quadrant
+// and accumulate it on the matrix cores in float32 (v_mfma_f32_32x32x2_f32: lane (l32, h) supplies
+// A(row l32, k = h) and B(k = h, column l32) of a k-pair; accumulator register i is row
+// 8 (i / 4) + 4 h + (i % 4), column l32 of the quadrant).
 __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
   constexpr int BM = 64, BN = 64, BK = 16;
+  typedef float f32x16 __attribute__((ext_vector_type(16)));
   __shared__ float As[BK][BM + 4];
   __shared__ float Bs[BK][BN + 4];
   const int bz = blockIdx.z / a.splits, sp = blockIdx.z % a.splits;
@@ -259,51 +264,60 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs a) {
   int kc = (a.K + a.splits - 1) / a.splits;
   kc = (kc + BK - 1) / BK * BK;
   const int kbeg = sp * kc, kend = min(a.K, kbeg + kc);
-  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
-  float acc[4][4];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
+  const int wm = wave >> 1, wn = wave & 1;
+  f32x16 acc;
 #pragma unroll
-  for (int u = 0; u < 4; ++u)
-#pragma unroll
-    for (int w = 0; w < 4; ++w) acc[u][w] = 0.f;
+  for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+  // Each thread moves four elements of A and four of B per stage, always the same positions of the
+  // tile (lanes run along whichever index is contiguous in memory): one running pointer per element,
+  // advanced by a stage, and the next stage's values are requested before the current one is used.
   const bool a_k_fast = (a.sAk == 1), b_j_fast = (a.sBj == 1);
+  const float *pa[4], *pb[4];
+  int ka[4], ia[4], kb[4], jb[4];
+  bool oka[4], okb[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int e = tid + 256 * q;
+    if (a_k_fast) { ka[q] = e & 15; ia[q] = e >> 4; } else { ia[q] = e & 63; ka[q] = e >> 6; }
+    if (b_j_fast) { jb[q] = e & 63; kb[q] = e >> 6; } else { kb[q] = e & 15; jb[q] = e >> 4; }
+    oka[q] = i0 + ia[q] < a.M;
+    okb[q] = j0 + jb[q] < a.N;
+    pa[q] = A + (int64_t)(i0 + ia[q]) * a.sAi + (int64_t)(kbeg + ka[q]) * a.sAk;
+    pb[q] = B + (int64_t)(kbeg + kb[q]) * a.sBk + (int64_t)(j0 + jb[q]) * a.sBj;
+  }
+  float ra[4], rb[4];
+  auto fetch = [&](int k0) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      ra[q] = (oka[q] && k0 + ka[q] < kend) ? *pa[q] : 0.f;
+      rb[q] = (okb[q] && k0 + kb[q] < kend) ? *pb[q] : 0.f;
+      pa[q] += (int64_t)BK * a.sAk;
+      pb[q] += (int64_t)BK * a.sBk;
+    }
+  };
+  if (kbeg < kend) fetch(kbeg);
   for (int k0 = kbeg; k0 < kend; k0 += BK) {
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      const int e = tid + 256 * q;
-      int ii, kk;
-      if (a_k_fast) { kk = e & 15; ii = e >> 4; } else { ii = e & 63; kk = e >> 6; }
-      const int gi = i0 + ii, gk = k0 + kk;
-      As[kk][ii] = (gi < a.M && gk < kend) ? A[(int64_t)gi * a.sAi + (int64_t)gk * a.sAk] : 0.f;
-      int jj, kb;
-      if (b_j_fast) { jj = e & 63; kb = e >> 6; } else { kb = e & 15; jj = e >> 4; }
-      const int gj = j0 + jj, gkb = k0 + kb;
-      Bs[kb][jj] = (gj < a.N && gkb < kend) ? B[(int64_t)gkb * a.sBk + (int64_t)gj * a.sBj] : 0.f;
+      As[ka[q]][ia[q]] = ra[q];
+      Bs[kb[q]][jb[q]] = rb[q];
     }
     __syncthreads();
+    if (k0 + BK < kend) fetch(k0 + BK);
 #pragma unroll
-    for (int kk = 0; kk < BK; ++kk) {
-      float av[4], bv[4];
-#pragma unroll
-      for (int u = 0; u < 4; ++u) av[u] = As[kk][ty * 4 + u];
-#pragma unroll
-      for (int w = 0; w < 4; ++w) bv[w] = Bs[kk][tx * 4 + w];
-#pragma unroll
-      for (int u = 0; u < 4; ++u)
-#pragma unroll
-        for (int w = 0; w < 4; ++w) acc[u][w] = fmaf(av[u], bv[w], acc[u][w]);
-    }
+    for (int kk = 0; kk < BK; kk += 2)
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(As[kk + h][32 * wm + l32], Bs[kk + h][32 * wn + l32], acc, 0, 0, 0);
     __syncthreads();
   }
   const float alpha = a.alpha ? *a.alpha : 1.0f;
+  const int gj = j0 + 32 * wn + l32;
+  if (gj < a.N) {
 #pragma unroll
-  for (int u = 0; u < 4; ++u) {
-    const int gi = i0 + ty * 4 + u;
-    if (gi >= a.M) continue;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const int gj = j0 + tx * 4 + w;
-      if (gj >= a.N) continue;
-      float val = acc[u][w];
+    for (int i = 0; i < 16; ++i) {
+      const int gi = i0 + 32 * wm + 8 * (i >> 2) + 4 * h + (i & 3);
+      if (gi >= a.M) continue;
+      float val = acc[i];
       if (a.relu) val = fmaxf(val, 0.f);
       C[(int64_t)gi * a.ldc + gj] = val * alpha;
     }
