@@ -206,6 +206,7 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     binding.load_library()
+    halves = None
     if args.config == 5:
         cfg, p, step, path, workload = run_block(args)
     else:
@@ -223,13 +224,20 @@ def main():
                     f"L={cfg['L']} m={cfg['m']} {cfg['dtype']} storage, {cfg['flavour']} inputs, "
                     "forward+backward")
 
-        def step():
-            nonlocal grads
+        def fwd():
             binding.wersa_forward(t["Q"], t["K"], t["V"], t["Omega"], t["sigma"], t["Wg"], t["bg"], t["omega"], L,
                                   out=out, saved=saved, workspace=ws_f, flags=flags)
+
+        def bwd():
+            nonlocal grads
             grads = binding.wersa_backward(t["Q"], t["K"], t["V"], t["Omega"], t["sigma"], t["Wg"], t["bg"],
                                            t["omega"], out, t["dO"], saved, L, workspace=ws_b, grads=grads,
                                            flags=flags)
+
+        def step():
+            fwd()
+            bwd()
+        halves = (fwd, bwd)
 
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)   # 1 GiB
@@ -285,7 +293,7 @@ def main():
     # instructions, measured now in this process; (c) a few steps each preceded by that 2 GiB copy,
     # every launch bracketed: the memory-bound stages with their inputs NOT resident in the 256 MB
     # last-level cache (in back-to-back steps the pooled-query pass finds part of Q there).
-    median_ms, peaks, cold, haar_stage = None, None, {}, None
+    median_ms, peaks, cold, haar_stage, split_ms = None, None, {}, None, None
     if not args.graph and not args.no_events:
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
         for a, b in evs:
@@ -295,6 +303,18 @@ def main():
         torch.cuda.synchronize()
         per = sorted(a.elapsed_time(b) for a, b in evs)
         median_ms = per[len(per) // 2]
+        if halves:   # forward and backward on their own: three events per step
+            ev3 = [tuple(torch.cuda.Event(enable_timing=True) for _ in range(3)) for _ in range(args.steps)]
+            for a, b, c in ev3:
+                a.record()
+                halves[0]()
+                b.record()
+                halves[1]()
+                c.record()
+            torch.cuda.synchronize()
+            fw = sorted(a.elapsed_time(b) for a, b, c in ev3)
+            bw = sorted(b.elapsed_time(c) for a, b, c in ev3)
+            split_ms = {"forward_ms_median": fw[len(fw) // 2], "backward_ms_median": bw[len(bw) // 2]}
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)   # 1 GiB
         dst = torch.empty_like(src)
         peaks = {"hbm_copy_GBps": binding.wersa_peak_copy(dst, src, reps=10),
@@ -387,6 +407,8 @@ def main():
                               "cache); cold_*: the step preceded by a 2 GiB streaming copy")
     rec["measured_peaks"] = peaks
     rec["ms_per_step_median"] = median_ms
+    if split_ms:
+        rec.update(split_ms)
     rec["roofline"] = roof
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline_block(cfg, p) if args.config == 5 else cpu_baseline(cfg, p)
