@@ -88,8 +88,8 @@ typedef enum { WERSA_F32 = 0, WERSA_BF16 = 1 } wersa_dtype;
  * (ReLU is positively homogeneous, so the scale drops out exactly); inputs, bandwidth and per-scale
  * weights of any magnitude are fine as long as the filtered K of a slice stays below about 2^11
  * times the bound on its filtered Q (beyond that the fp16 operands overflow: take
- * WERSA_FLAG_GENERIC_PATH).  The block entry points pool the queries in their own GEMM and use no
- * such scale: there |X_F| must stay below 65504.
+ * WERSA_FLAG_GENERIC_PATH).  The block entry points take the same maxima from the epilogue of their
+ * W^Q product (when n % 128 != 0 or L > 6 the core pools, and scales, by itself).
  * MFMA path only: q, k, v, omega_rf, out, dout, dq, dk, dv must be 16-byte aligned (their rows
  * are read and written in 16-byte pieces); a misaligned pointer returns WERSA_ERR_INVALID_ARG
  * before anything is enqueued (WERSA_FLAG_GENERIC_PATH takes any element-aligned pointer).

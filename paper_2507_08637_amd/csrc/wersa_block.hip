@@ -64,9 +64,11 @@ template <bool TRANS, bool OUT_F32, int NW>
 // colsum (bf16 output form, may be nullptr): float32 [M / 128][N], the column sums of each wave's
 // 128 output rows from the float32 accumulators; the block uses them as the pooled-query partial
 // sums of Q' = X W^Q (Section 3.1 step 4) instead of a separate pass over Q'.
+// colmax (with colsum): float32 [M / 128][N / 64], the largest |accumulator| of each wave's 128 rows x
+// 64 columns; the core derives the fp16 operand scale of a (batch, head) slice from them.
 __global__ __launch_bounds__(64 * NW, 1) void gemm_bf16_kernel(GemmSrc src, int lda, int ldb, void *Cout,
                                                               int ldc, int M, int N, int K, int k_chunk,
-                                                              int splits, float *colsum) {
+                                                              int splits, float *colsum, float *colmax) {
   constexpr int NT = 64 * NW;
   constexpr int WN = NW / 2;            // waves along n
   constexpr int TN = 8 / WN;            // 32-column tiles per wave: 4 or 2
@@ -192,6 +194,19 @@ __global__ __launch_bounds__(64 * NW, 1) void gemm_bf16_kernel(GemmSrc src, int 
         v += __shfl_xor(v, 32, 64);   // the two half-waves hold the two halves of every 8-row group
         if (h == 0) colsum[(int64_t)((m0 + wm) >> 7) * N + n0 + wn + 32 * j + l32] = v;
       }
+      if (colmax) {
+        static_assert(NW != 8 || 32 * TN == kPooledMaxCols, "one maximum per wave tile of 64 columns");
+        float mx = 0.f;
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, fabsf(acc[i][j][r]));
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+        if (lane == 0) colmax[(int64_t)((m0 + wm) >> 7) * (N / (32 * TN)) + (n0 + wn) / (32 * TN)] = mx;
+      }
     }
     bf16_t *tl = reinterpret_cast<bf16_t *>(smem_raw) + wave * (32 * ES);
 #pragma unroll
@@ -245,7 +260,8 @@ static_assert(BM * LS == BK * LT && BN == BM, "both tile forms share one LDS bud
 
 template <bool TRANS, bool OUT_F32>
 hipError_t launch_gemm(const char *name, const GemmSrc &src, int lda, int ldb, void *C, int ldc, int M, int N,
-                       int K, int k_chunk, int splits, hipStream_t st, float *colsum = nullptr) {
+                       int K, int k_chunk, int splits, hipStream_t st, float *colsum = nullptr,
+                       float *colmax = nullptr) {
   constexpr int kGemmWaves = 8;   // two waves per SIMD
   auto kern = &gemm_bf16_kernel<TRANS, OUT_F32, kGemmWaves>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -254,7 +270,7 @@ hipError_t launch_gemm(const char *name, const GemmSrc &src, int lda, int ldb, v
   const int total = (M / BM) * (N / BN) * splits;
   const int grid = ((total + 7) / 8) * 8;
   WERSA_STAGE(name, st,
-              kern<<<grid, 64 * kGemmWaves, kGemmSmem, st>>>(src, lda, ldb, C, ldc, M, N, K, k_chunk, splits, colsum));
+              kern<<<grid, 64 * kGemmWaves, kGemmSmem, st>>>(src, lda, ldb, C, ldc, M, N, K, k_chunk, splits, colsum, colmax));
   return hipSuccess;
 }
 
@@ -286,7 +302,7 @@ BlockPlan block_plan(const wersa_desc &c) {
 
 // Byte layouts. saved: Q' | K' | V' | A (bf16, (B, n, hidden)) | the core's saved buffer.
 struct BlockSaved { size_t qp, kp, vp, a, core, total; };
-struct BlockWs { size_t wT[4], qsums, dA, dQp, dKp, dVp, part, core, total; };
+struct BlockWs { size_t wT[4], qsums, qmax, dA, dQp, dKp, dVp, part, core, total; };
 size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 
 BlockSaved block_saved(const BlockPlan &p) {
@@ -308,6 +324,7 @@ BlockWs block_ws(const BlockPlan &p, int bwd) {
   if (!bwd) {
     for (int i = 0; i < 4; ++i) { w.wT[i] = off; off += up256((size_t)p.hidden * p.hidden * 2); }
     w.qsums = off; off += up256((size_t)(p.tokens / 128) * p.hidden * 4);   // column sums of Q' per 128 rows
+    w.qmax = off;  off += up256((size_t)(p.tokens / 128) * (p.hidden / kPooledMaxCols) * 4);   // and the largest |Q'| per 64 columns
   } else {
     const size_t act = up256((size_t)p.act * 2);
     w.dA = off;  off += act;
@@ -410,12 +427,13 @@ wersa_status wersa_block_forward(const wersa_desc *desc, const void *x, const vo
     src.b[0] = wT[i];
     src.count = 1;
     if (launch_gemm<false, false>("wersa_gemm_nt", src, hid, hid, proj[i], hid, M, hid, hid, hid, 1, st,
-                                  i == 0 ? (float *)(ws + w.qsums) : nullptr) != hipSuccess)
+                                  i == 0 ? (float *)(ws + w.qsums) : nullptr,
+                                  i == 0 ? (float *)(ws + w.qmax) : nullptr) != hipSuccess)
       return WERSA_ERR_LAUNCH;
   }
   bf16_t *A = (bf16_t *)(sb + sv.a);
   // The pooled query comes out of the W^Q GEMM's epilogue (the core takes it when it can).
-  const PooledSums pooled{(const float *)(ws + w.qsums), p.hidden};
+  const PooledSums pooled{(const float *)(ws + w.qsums), p.hidden, (const float *)(ws + w.qmax)};
   const wersa_status cs = forward_checked(&p.core, proj[0], proj[1], proj[2], omega_rf, sigma, gate_w, gate_b,
                                           scale_w, A, sb + sv.core, ws + w.core,
                                           wersa_workspace_bytes(&p.core, 0), hip_stream, &pooled);

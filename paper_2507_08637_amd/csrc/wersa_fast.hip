@@ -2295,7 +2295,9 @@ wersa_status fast_forward_t(const wersa_desc &c, const bf16_t *q, const bf16_t *
                 gate_fwd_kernel<<<slices, 256, 0, st>>>(pooled->sums, chunks, c.n, c.d, c.L, c.H, gate_w, gate_b, scale_w,
                                                        qbar, s, F, w.coef, (c.flags & WERSA_FLAG_POOLED_GATE) ? 1 : 0,
                                                        PooledLayout{chunks * pooled->hidden, c.d, pooled->hidden},
-                                                       nullptr, 0, w.scalars));
+                                                       pooled->amax, chunks * (c.d / kPooledMaxCols), w.scalars,
+                                                       AmaxLayout{chunks * (pooled->hidden / kPooledMaxCols), c.d / kPooledMaxCols,
+                                                                  pooled->hidden / kPooledMaxCols, c.d / kPooledMaxCols}));
   } else {
     // deep: one partial per 64-row tile, kept (with those of K) as the tile sums of the levels above 6
     float *qpart = deep ? w.tileQ : w.qpart;
@@ -2306,7 +2308,8 @@ wersa_status fast_forward_t(const wersa_desc &c, const bf16_t *q, const bf16_t *
                 gate_fwd_kernel<<<slices, 256, 0, st>>>(qpart, p.chunksQ, c.n, c.d, c.L, c.H, gate_w, gate_b, scale_w,
                                                        qbar, s, F, w.coef, (c.flags & WERSA_FLAG_POOLED_GATE) ? 1 : 0,
                                                        PooledLayout{(int64_t)c.H * p.chunksQ * c.d, (int64_t)p.chunksQ * c.d, c.d},
-                                                       w.qamax, p.chunksQ, w.scalars));
+                                                       w.qamax, p.chunksQ, w.scalars,
+                                                       AmaxLayout{(int64_t)c.H * p.chunksQ, p.chunksQ, 0, p.chunksQ}));
   }
   if (deep) {
     WERSA_STAGE("wersa_qbar", st,

@@ -130,9 +130,11 @@ size_t fast_workspace_bytes(const wersa_desc &c, int for_backward);
 // leaves them in its epilogue): sums[row block of (B*n)/128][H*d], float32.  When given to the
 // MFMA path's forward, the pass over Q that pools the queries is skipped.  Needs n % 128 == 0.
 struct PooledSums {
-  const float *sums;
+  const float *sums;    // [token rows / 128][hidden]: column sums of Q' per 128 rows
   int64_t hidden;
+  const float *amax;    // [token rows / 128][hidden / kPooledMaxCols]: largest |Q'| per 128 rows and column group
 };
+constexpr int kPooledMaxCols = 64;
 wersa_status fast_forward(const wersa_desc &c, const void *q, const void *k, const void *v,
                           const void *omega_rf, const float *sigma, const float *gate_w,
                           const float *gate_b, const float *scale_w, void *out, float *saved,

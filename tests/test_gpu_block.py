@@ -86,6 +86,38 @@ def test_block_forward_backward(shape):
     assert all(v < 5e-2 for v in gerr.values()), gerr
 
 
+@pytest.mark.parametrize("case", ["large", "tiny"])
+def test_block_input_range(case):
+    """The block hands the core the largest |Q'| per 128 rows and 64 columns from the epilogue of
+    its W^Q product, so the fp16 operands of the projection (Section 3.1 step 7) carry the same
+    per-slice power-of-two scale as in the core's own entry points: token features of the order
+    2^13 (the filtered rows would overflow fp16 without the scale) or 2^-16 (they would sit among
+    its subnormals; the bandwidth stays above the descriptor's floor), with the bandwidth scaled alike, must meet the bar of order-one inputs.
+    The factor is a power of two f, so the whole computation is homogeneous: against the run on the
+    unscaled inputs, Y and the weight gradients carry f, dX carries 1, d b_g and d omega carry f and
+    d W_g (logits kept where they were by W_g / f) carries f^2 - to the last bits, which also holds
+    the gate-parameter gradients (noise-limited against the oracle at this size) to account."""
+    import torch
+    cfg = dict(B=1, H=4, n=256, d=64, L=4, m=128)
+    p0 = workloads.make_block_inputs(**cfg, seed_base=9400, x_mean=0.0)
+    f = 2.0 ** 13 if case == "large" else 2.0 ** -16
+    p = dict(p0)
+    p["X"] = workloads.round_to_bf16(p0["X"] * np.float32(f))     # a power of two: still exact bf16 values
+    p["sigma"] = np.float32(float(p0["sigma"]) * f)
+    p["Wg"] = (p0["Wg"] / np.float32(f)).astype(np.float32)        # keeps the gate logits where they were
+    res = _gpu_block(p, cfg)
+    ref = _oracle_block(p, cfg)
+    errs = {k: hp.rel_err(res[k], ref[k]) for k in ("A", "Y", "dX", "dWQ", "dWK", "dWV", "dWO")}
+    print("block input range", case, {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+    assert all(bool(torch.isfinite(res[k].float()).all()) for k in ("Y", "dX", "dWQ", "dWg"))
+    assert all(v < 2e-2 for v in errs.values()), errs
+    base = _gpu_block(p0, cfg)
+    power = dict(Y=1, A=1, dX=0, dWQ=1, dWK=1, dWV=1, dWO=1, dWg=2, dbg=1, domega=1)
+    hom = {k: hp.rel_err(res[k].double() / f ** e, base[k].double().cpu().numpy()) for k, e in power.items()}
+    print("block input range", case, "against the unscaled run", {k: f"{v:.1e}" for k, v in hom.items()}, flush=True)
+    assert all(v < 1e-6 for v in hom.values()), hom
+
+
 def test_block_results_are_bitwise_reproducible():
     """The split-k partials of the weight gradients are summed in a fixed order and the core has
     no atomics: two runs of the block on the same inputs give the same bits."""
