@@ -280,6 +280,12 @@ def test_mfma_path_input_range(case):
         r = fwd[name].reshape((sl,) + fwd[name].shape[2:])
         assert hp.rel_err(res["saved"][name], r) < 2e-2, name
     _check_mfma(res, ref, p, cfg, where=f"mfma input range: {case}")   # plain 1.3e-2 .. 1.5e-2, as at order one
+    if case == "large":
+        # The factor is a power of two, so against the run on the unscaled inputs the outputs must carry
+        # exact powers of it: O, dV, d b_g, d omega none, dQ and dK 1/f, d W_g f (W_g was divided by f).
+        base = hp.gpu_forward_backward(workloads.make_inputs(**cfg), cfg)
+        for k, e in dict(O=0, dV=0, dQ=-1, dK=-1, dWg=1, dbg=0, domega=0).items():
+            assert torch.equal(res[k].double() / f ** e, base[k].double()), k
 
 
 def test_mfma_and_generic_paths_agree():
