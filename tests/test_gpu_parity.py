@@ -616,6 +616,33 @@ def test_results_are_bitwise_reproducible(shape):
         assert torch.equal(a["saved"][name], b["saved"][name]), name
 
 
+@pytest.mark.parametrize("zero", ["K", "V", "Q"])
+@pytest.mark.parametrize("shape", [dict(B=1, H=2, n=320, d=64, L=4, m=256, dtype="bf16"),     # MFMA path, dV inside the K-side kernel
+                                   dict(B=1, H=2, n=200, d=128, L=5, m=128, dtype="bf16"),    # head dimension 128, partial last block
+                                   dict(B=1, H=2, n=200, d=32, L=3, m=48, dtype="f32")])      # generic path
+def test_degenerate_all_zero_operand(shape, zero):
+    """The degenerate cases of the method.  K = 0: every key feature is ReLU(0) = 0, so S = 0, z = 0,
+    D = eps, O = 0 and every gradient is 0 (the ReLU derivative at exactly 0 is 0).  V = 0: O = 0 and
+    dQ = dK = 0, dV is not.  Q = 0: the pooled query and every query feature are 0, so O = 0 and
+    dK = dV = 0, while dQ = 0 too (derivative at 0).  Everything must come out finite and, where the
+    oracle says zero, exactly zero; the rest at the usual tolerance."""
+    import torch
+    cfg = dict(shape, flavour="plain", seed_base=4300, q_mean=0.2)
+    p = workloads.make_inputs(**cfg)
+    p[zero] = np.zeros_like(p[zero])
+    res = hp.gpu_forward_backward(p, cfg)
+    ref = hp.oracle_backward(p, cfg)
+    tol = TOL[cfg["dtype"]]
+    for name in ("O", "dQ", "dK", "dV", "dWg", "dbg", "domega"):
+        got = res[name].float()
+        assert bool(torch.isfinite(got).all()), name
+        if not np.any(ref[name]):
+            assert not bool(got.abs().max() > 0), (name, float(got.abs().max()))
+        else:
+            assert hp.rel_err(res[name], ref[name]) < tol, (name, hp.rel_err(res[name], ref[name]))
+    assert not np.any(ref["O"])      # the premise: the output vanishes in all three cases
+
+
 @pytest.mark.parametrize("kind", ["mfma", "generic"])
 def test_maximum_sequence_length_keeps_convexity_and_periodicity(kind):
     """n = 2^22 (the largest the library takes) on either path, no oracle pass at this size.
