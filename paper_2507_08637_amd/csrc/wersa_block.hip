@@ -145,6 +145,9 @@ __global__ __launch_bounds__(64 * NW, 1) void gemm_bf16_kernel(GemmSrc src, int 
     if (more) fetch(s + 1);
     const bf16_t *as = At + buf * BM * LS + (TRANS ? wm : wm * LS);
     const bf16_t *bs = Bt + buf * BN * LS + (TRANS ? wn : wn * LS);
+    // Two waves per SIMD: the one in its matrix phase goes ahead of the other's tile traffic (the
+    // requests above, the LDS writes below): NT -2 %, TN -3 %.
+    __builtin_amdgcn_s_setprio(3);
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
       bf16x8 a[4], b[TN];
@@ -162,6 +165,7 @@ __global__ __launch_bounds__(64 * NW, 1) void gemm_bf16_kernel(GemmSrc src, int 
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
+    __builtin_amdgcn_s_setprio(0);
     if (more) stash(buf ^ 1);
     __syncthreads();
   }

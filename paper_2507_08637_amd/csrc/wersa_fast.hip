@@ -847,6 +847,7 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
       __syncthreads();
     }
     const _Float16 *xcur = FUSE ? &xq[0] : &xt[buf][0];
+    __builtin_amdgcn_s_setprio(3);   // the matrix phase goes ahead of the other workgroup's tile traffic (-1 %)
 #pragma unroll
     for (int ti = 0; ti < 2; ++ti) {
       f16x8 xa[KS];   // projection A operand: rows 32 ti + l32, k = 8h + q (+16 per k-step)
@@ -886,6 +887,7 @@ __global__ __launch_bounds__(256, 2) void phiT_contract_kernel(
         }
       }
     }
+    __builtin_amdgcn_s_setprio(0);
     if (more) stash(buf ^ 1);
     __syncthreads();
   }
@@ -1468,6 +1470,9 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
       // (unrolled, the operands of several feature tiles are fetched ahead and spill).
       int rt_end = mc / 32;
       if (IS_GRAD && DH == 128) asm volatile("" : "+s"(rt_end));
+      // Two waves per SIMD: the wave in its feature loop goes first, so that the other wave's epilogue
+      // (no matrix work) fills the gaps instead of competing for issue slots (forward kernel -3 %).
+      if (NW == 8) __builtin_amdgcn_s_setprio(3);
       for (int rt = 0; rt < rt_end; ++rt) {
         f16x8 oa[KS];     // Omega^T rows of this feature tile: A operand of the projection
 #pragma unroll
@@ -1517,6 +1522,7 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
         }
       }
     }
+    if (NW == 8) __builtin_amdgcn_s_setprio(0);
     if (!active) continue;
 
     // ---- epilogues -----------------------------------------------------------------
