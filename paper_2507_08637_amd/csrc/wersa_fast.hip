@@ -1242,11 +1242,9 @@ __global__ __launch_bounds__(NW * 64, NW == 8 ? 2 : 1) void rows_kernel(
       put_rows();
     }
   }
-  // With two waves per SIMD, start the second one about an epilogue later, so that one wave's
-  // epilogue (no matrix work) runs under the other's feature loop instead of both idling the pipe.
-  if (NW == 8 && wave >= 4) {
-    __builtin_amdgcn_s_sleep(100);
-  }
+  // (Two waves per SIMD: the wave priorities set around the feature loop below are what lets one
+  // wave's epilogue run under the other's matrix work; an explicit start delay for the second wave
+  // group, used before the priorities were there, no longer gains anything.)
 
   for (int rg = blockIdx.x; rg < row_groups; rg += gridDim.x) {
     const int t0 = (rg * NWR + wave) * 64;
